@@ -1,0 +1,267 @@
+"""ctypes access to the CPU oracle (oracle/oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
+benchmark's cpu_baseline leg.  Nothing in the product package imports this.
+The functions here only marshal numpy arrays; all arithmetic is in oracle.c.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile oracle.c with gcc (no fused multiply-add contraction)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O2", "-std=c99", "-ffp-contract=off", "-fPIC", "-shared", "-Wall",
+             "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        L = C.CDLL(_LIB)
+        L.orc_shuffle_key.restype = C.c_uint64
+        L.orc_shuffle_key.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32]
+        L.orc_slot_word.restype = C.c_uint32
+        L.orc_slot_word.argtypes = [C.c_uint64] + [C.c_uint32] * 5
+        L.orc_exp_clock_q24.restype = C.c_uint32
+        L.orc_exp_clock_q24.argtypes = [C.c_uint32]
+        L.orc_slot_key.restype = C.c_uint64
+        L.orc_slot_key.argtypes = [C.c_uint32, C.c_int, C.c_uint32]
+        L.orc_build_batches.restype = C.c_int
+        L.orc_build_batches.argtypes = [C.c_int, C.c_int32, C.c_uint64, C.c_uint32, C.c_void_p,
+                                        C.c_int64, C.c_void_p, C.c_int32, C.c_void_p]
+        L.orc_sample_hop.restype = C.c_int64
+        L.orc_sample_hop.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+                                     C.c_int32, C.c_uint32, C.c_int, C.c_uint64, C.c_uint32,
+                                     C.c_uint32, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                     C.c_void_p, C.c_void_p, C.c_void_p]
+        L.orc_transpose_block.restype = None
+        L.orc_transpose_block.argtypes = [C.c_int32, C.c_int32] + [C.c_void_p] * 4
+        L.orc_round_bf16.restype = None
+        L.orc_round_bf16.argtypes = [C.c_void_p, C.c_int64, C.c_void_p]
+        L.orc_gather_mean.restype = None
+        L.orc_gather_mean.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                      C.c_int, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p]
+        L.orc_gather_mean_bwd.restype = None
+        L.orc_gather_mean_bwd.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                          C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
+        L.orc_sage_linear_fwd.restype = None
+        L.orc_sage_linear_fwd.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                          C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p]
+        L.orc_sage_linear_bwd.restype = None
+        L.orc_sage_linear_bwd.argtypes = [C.c_int32, C.c_int32, C.c_int32] + [C.c_void_p] * 5 + \
+                                         [C.c_int, C.c_int] + [C.c_void_p] * 4
+        L.orc_sgd_step.restype = None
+        L.orc_sgd_step.argtypes = [C.c_int64, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p,
+                                   C.c_void_p, C.c_double, C.c_double]
+        L.orc_softmax_xent.restype = C.c_double
+        L.orc_softmax_xent.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p,
+                                       C.c_void_p]
+        _lib = L
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _arr(a, dtype):
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a
+
+
+# ---------------------------------------------------------------- random stream
+def philox4x32_10(ctr, key):
+    c = (C.c_uint32 * 4)(*[int(x) & 0xFFFFFFFF for x in ctr])
+    k = (C.c_uint32 * 2)(*[int(x) & 0xFFFFFFFF for x in key])
+    o = (C.c_uint32 * 4)()
+    lib().orc_philox4x32_10(c, k, o)
+    return [int(x) for x in o]
+
+
+def shuffle_key(seed, epoch, domain, ident):
+    return int(lib().orc_shuffle_key(seed, epoch, domain, ident))
+
+
+def slot_word(seed, epoch, batch, layer, node, slot):
+    return int(lib().orc_slot_word(seed, epoch, batch, layer, node, slot))
+
+
+def exp_clock_q24(r):
+    return int(lib().orc_exp_clock_q24(int(r)))
+
+
+def slot_key(r, intra, q_in):
+    return int(lib().orc_slot_key(int(r), int(bool(intra)), int(q_in)))
+
+
+def q_intra(p: float) -> int:
+    """Fixed-point intra-community weight handed to both implementations."""
+    return int(round(p * 65536.0))
+
+
+# ---------------------------------------------------------------- step 1
+NORAND, COMM_RAND, RAND = 0, 1, 2
+
+
+def build_batches(policy, mix, seed, epoch, train_ids, comm, n_comm):
+    train_ids = _arr(train_ids, np.int32)
+    comm = _arr(comm, np.int32)
+    perm = np.empty(train_ids.shape[0], dtype=np.int32)
+    rc = lib().orc_build_batches(policy, mix, seed, epoch, _p(train_ids), train_ids.shape[0],
+                                 _p(comm), n_comm, _p(perm))
+    if rc != 0:
+        raise ValueError("orc_build_batches rejected its arguments")
+    return perm
+
+
+# ---------------------------------------------------------------- step 2
+class Block:
+    """One sampled bipartite block (numpy, host)."""
+
+    def __init__(self, n_dst, src_ids, indptr, indices, slots):
+        self.n_dst = int(n_dst)
+        self.src_ids = src_ids
+        self.n_src = int(src_ids.shape[0])
+        self.indptr = indptr
+        self.indices = indices
+        self.nnz = int(indices.shape[0])
+        self.slots = slots
+        self.t_indptr = None
+        self.t_indices = None
+
+
+def sample_hop(graph, dst_ids, fanout, p, strict, seed, epoch, batch, layer, pos_map=None):
+    indptr, indices, comm = graph
+    dst_ids = _arr(dst_ids, np.int32)
+    n_dst = dst_ids.shape[0]
+    if pos_map is None:
+        pos_map = np.full(indptr.shape[0] - 1, -1, dtype=np.int32)
+    o_indptr = np.empty(n_dst + 1, dtype=np.int32)
+    o_indices = np.empty(max(1, n_dst * fanout), dtype=np.int32)
+    o_slots = np.empty(max(1, n_dst * fanout), dtype=np.int32)
+    o_src = np.empty(max(1, n_dst * (1 + fanout)), dtype=np.int32)
+    n_src = C.c_int32(0)
+    nnz = lib().orc_sample_hop(_p(indptr), _p(indices), _p(comm), _p(dst_ids), n_dst, fanout,
+                               q_intra(p), int(strict), seed, epoch, batch, layer, _p(pos_map),
+                               _p(o_indptr), _p(o_indices), _p(o_src), C.byref(n_src), _p(o_slots))
+    if nnz < 0:
+        raise ValueError("orc_sample_hop rejected its arguments")
+    return Block(n_dst, o_src[:n_src.value].copy(), o_indptr, o_indices[:nnz].copy(),
+                 o_slots[:nnz].copy())
+
+
+def transpose_block(blk: Block):
+    t_indptr = np.empty(blk.n_src + 1, dtype=np.int32)
+    t_indices = np.empty(max(1, blk.nnz), dtype=np.int32)
+    lib().orc_transpose_block(blk.n_dst, blk.n_src, _p(blk.indptr), _p(blk.indices),
+                              _p(t_indptr), _p(t_indices))
+    blk.t_indptr, blk.t_indices = t_indptr, t_indices[:blk.nnz]
+    return blk
+
+
+def sample_blocks(graph, roots, fanouts, p, strict, seed, epoch, batch, pos_map=None,
+                  transpose=True):
+    """Blocks indexed by GNN layer (0 = input side).  Roots are expanded first,
+    with fanouts[L-1]; the frontier of layer l is the destination list of l-1."""
+    L = len(fanouts)
+    blocks = [None] * L
+    dst = _arr(roots, np.int32)
+    if pos_map is None:
+        pos_map = np.full(graph[0].shape[0] - 1, -1, dtype=np.int32)
+    for l in range(L - 1, -1, -1):
+        blk = sample_hop(graph, dst, fanouts[l], p, strict, seed, epoch, batch, l, pos_map)
+        if transpose and l >= 1:
+            transpose_block(blk)
+        blocks[l] = blk
+        dst = blk.src_ids
+    return blocks
+
+
+# ---------------------------------------------------------------- dense math
+def round_bf16(x):
+    x = _arr(x, np.float64)
+    out = np.empty_like(x)
+    lib().orc_round_bf16(_p(x), x.size, _p(out))
+    return out
+
+
+def gather_mean(blk: Block, table, indirect: bool, F=None, want_self=False):
+    """table: float32 [rows, ld] or uint16 (raw bf16) [rows, ld]."""
+    assert table.dtype in (np.float32, np.uint16) and table.flags.c_contiguous
+    F = table.shape[1] if F is None else F
+    agg = np.empty((blk.n_dst, F), dtype=np.float64)
+    self_rows = np.empty((blk.n_dst, F), dtype=np.float64) if want_self else None
+    lib().orc_gather_mean(blk.n_dst, _p(blk.indptr), _p(blk.indices),
+                          _p(blk.src_ids) if indirect else None, _p(table),
+                          0 if table.dtype == np.float32 else 1, table.shape[1], F,
+                          _p(agg), _p(self_rows))
+    return (agg, self_rows) if want_self else agg
+
+
+def gather_mean_bwd(blk: Block, d_agg, d_self=None):
+    d_agg = _arr(d_agg, np.float64)
+    F = d_agg.shape[1]
+    if d_self is not None:
+        d_self = _arr(d_self, np.float64)
+    d_src = np.empty((blk.n_src, F), dtype=np.float64)
+    lib().orc_gather_mean_bwd(blk.n_dst, blk.n_src, _p(blk.indptr), _p(blk.indices), _p(d_agg),
+                              _p(d_self), F, _p(d_src))
+    return d_src
+
+
+def sage_linear_fwd(h_self, agg, W, bias, relu, round_operands):
+    h_self, agg, W, bias = (_arr(a, np.float64) for a in (h_self, agg, W, bias))
+    M, F_in = h_self.shape
+    F_out = W.shape[1]
+    assert W.shape[0] == 2 * F_in and agg.shape == h_self.shape
+    out = np.empty((M, F_out), dtype=np.float64)
+    lib().orc_sage_linear_fwd(M, F_in, F_out, _p(h_self), _p(agg), _p(W), _p(bias), int(relu),
+                              int(round_operands), _p(out))
+    return out
+
+
+def sage_linear_bwd(h_self, agg, W, out, d_out, relu, round_operands, need_dx=True):
+    h_self, agg, W, out, d_out = (_arr(a, np.float64) for a in (h_self, agg, W, out, d_out))
+    M, F_in = h_self.shape
+    F_out = W.shape[1]
+    dW = np.empty((2 * F_in, F_out), dtype=np.float64)
+    db = np.empty(F_out, dtype=np.float64)
+    d_self = np.empty((M, F_in), dtype=np.float64) if need_dx else None
+    d_agg = np.empty((M, F_in), dtype=np.float64) if need_dx else None
+    lib().orc_sage_linear_bwd(M, F_in, F_out, _p(h_self), _p(agg), _p(W), _p(out), _p(d_out),
+                              int(relu), int(round_operands), _p(dW), _p(db), _p(d_self),
+                              _p(d_agg))
+    return dW, db, d_self, d_agg
+
+
+def sgd_step(W, dW, b, db, lr, wd):
+    W = _arr(W, np.float64).copy()
+    b = _arr(b, np.float64).copy()
+    dW = _arr(dW, np.float64)
+    db = _arr(db, np.float64)
+    lib().orc_sgd_step(W.size, _p(W), _p(dW), b.size, _p(b), _p(db), lr, wd)
+    return W, b
+
+
+def softmax_xent(logits, labels, n_classes=None):
+    logits = _arr(logits, np.float64)
+    labels = _arr(labels, np.int32)
+    n, ld = logits.shape
+    Cn = ld if n_classes is None else n_classes
+    d = np.zeros_like(logits)
+    loss = lib().orc_softmax_xent(n, Cn, _p(logits), ld, _p(labels), _p(d))
+    return float(loss), d
