@@ -1,0 +1,257 @@
+/*
+ * commrand.h -- C ABI of libcommrand.so: the single-GPU hot path of COMM-RAND
+ * mini-batch GNN training (community-structure-aware randomized mini-batching)
+ * as hand-written HIP kernels for gfx950 (MI355X).
+ *
+ * The calls follow Algorithm 1 of the paper (mini-batch training of an L-layer
+ * GNN): Step-1 root node partitioning (cr_build_batches), Step-2 sub-graph
+ * construction (cr_sample_blocks), then training on the sub-graph
+ * (cr_gather_aggregate_*, cr_sage_linear_*, cr_softmax_xent).
+ *
+ * Conventions
+ *  - Every function returns a cr_status; cr_last_error() gives the text of the
+ *    calling thread's last failure.  No exception crosses this boundary.
+ *  - "device" pointers are HIP device memory on the current device; "host"
+ *    pointers are ordinary memory.  The library never allocates or frees device
+ *    memory: graph, table, outputs and workspaces are caller-owned and only
+ *    borrowed for the duration of the enqueued work.
+ *  - All work is enqueued on the given hipStream_t (passed as void*, NULL = the
+ *    default stream) and the call returns without synchronising, except where
+ *    stated.  Arguments are validated on the host before anything is launched;
+ *    with cr_set_dry_run(1) calls stop after validation (no GPU needed).
+ *  - Device pointers must be 16-byte aligned.  Row strides (ld*) are in
+ *    elements and must make every row 16-byte aligned.
+ *  - Sizes that depend on the sampled data (rows, edges, frontier length of a
+ *    block) live in a small device-resident header per block; kernels read them
+ *    there, so no host round trip is needed between the calls of one batch.
+ *  - bf16 values are raw uint16_t bit patterns (upper half of an IEEE float32).
+ */
+#ifndef COMMRAND_H
+#define COMMRAND_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t cr_status;
+enum {
+    CR_OK = 0,
+    CR_ERR_INVALID_ARG = 1, /* null / misaligned pointer, knob out of range, shape mismatch */
+    CR_ERR_CAPACITY = 2,    /* a caller-provided buffer or workspace is too small */
+    CR_ERR_UNSUPPORTED = 3, /* valid request outside what the kernels were built for */
+    CR_ERR_HIP = 4          /* the HIP runtime reported an error */
+};
+
+#define CR_MAX_LAYERS 8
+#define CR_MAX_FANOUT 64
+#define CR_HDR_WORDS 8 /* int32 words per block header */
+/* header word indices */
+#define CR_HDR_N_DST 0
+#define CR_HDR_N_SRC 1
+#define CR_HDR_NNZ 2
+#define CR_HDR_STATUS 3 /* 0 = valid; non-zero = the block overflowed its hash table (never with bound-sized capacities) */
+
+const char *cr_last_error(void);
+const char *cr_version(void);
+/* on != 0: every later call on any thread validates its arguments, then returns without touching the GPU. */
+void cr_set_dry_run(int on);
+
+/* ------------------------------------------------------------------------- */
+/* Step-1: root node partitioning (Algorithm 1 Step-1; Section 4.1; Table 1). */
+/* ------------------------------------------------------------------------- */
+enum {
+    CR_ROOTS_NORAND = 0,    /* NORAND-ROOTS: training set as given, static across epochs */
+    CR_ROOTS_COMM_RAND = 1, /* COMM-RAND-MIX: communities shuffled as blocks, mix_count of them merged
+                               into a super-block, contents of each super-block shuffled */
+    CR_ROOTS_RAND = 2       /* RAND-ROOTS: uniform shuffle of the whole training set */
+};
+
+typedef struct {
+    int32_t policy;     /* CR_ROOTS_* */
+    int32_t mix_count;  /* communities per super-block, >= 1 (1 = COMM-RAND-MIX-0%); ignored unless COMM_RAND */
+    int32_t batch_size; /* > 0 */
+    uint32_t epoch;     /* < 2^24 */
+    uint64_t seed;
+} cr_batch_cfg;
+
+/* Number of communities per super-block for COMM-RAND-MIX-k%: k percent of the communities present
+ * in the training set (Section 5, "Evaluated schemes"), rounded to nearest, at least 1. */
+int32_t cr_mix_count_from_percent(double k_percent, int32_t n_comm_in_train);
+
+cr_status cr_build_batches_workspace_bytes(int64_t n_train, int32_t n_comm, size_t *bytes /*host*/);
+
+/* Writes the epoch's permutation of the training set; mini-batch b is
+ * out_perm[b*batch_size .. min((b+1)*batch_size, n_train)) (the last batch may be short and is kept).
+ *   train_ids : device int32[n_train], ascending and distinct (not checked on the device)
+ *   comm      : device int32[n_nodes], community of every node, values in [0, n_comm)
+ *   ws        : device workspace of at least cr_build_batches_workspace_bytes() bytes
+ *   out_perm  : device int32[n_train]
+ *   out_n_batches : host, may be NULL
+ * Shuffles are "sort by a Philox4x32-10 key of (seed, epoch, id)", ties to the smaller id, so the
+ * result is a pure function of the arguments.  n_train < 2^31. */
+cr_status cr_build_batches(const cr_batch_cfg *cfg, const int32_t *train_ids, int64_t n_train,
+                           const int32_t *comm, int32_t n_comm, void *ws, size_t ws_bytes,
+                           int32_t *out_perm, int64_t *out_n_batches, void *stream);
+
+/* ------------------------------------------------------------------------- */
+/* Step-2: sub-graph construction (Algorithm 1 Step-2; Section 4.2).          */
+/* ------------------------------------------------------------------------- */
+typedef struct {
+    int64_t n_nodes;
+    int64_t n_entries;      /* = indptr[n_nodes] */
+    const int64_t *indptr;  /* device int64[n_nodes+1] */
+    const int32_t *indices; /* device int32[n_entries]; row v = neighbours of v (symmetrised graph) */
+    const int32_t *comm;    /* device int32[n_nodes] */
+    int32_t n_comm;
+} cr_graph;
+
+/* The sampled blocks of ONE GNN layer for a group of n_batches mini-batches that are sampled
+ * together.  Every array is laid out [n_batches][capacity]; batch g of the group owns slice g.
+ * For batch g: rows 0..n_dst-1 are destination nodes; src_ids[0..n_src) are the global ids of the
+ * frontier, whose first n_dst entries are the destination nodes themselves and whose remaining
+ * entries are the newly reached neighbours in order of first appearance (rows ascending, adjacency
+ * slot ascending); indptr/indices are a CSR over local source positions.  t_indptr/t_indices hold
+ * the transposed block (for every source position the destination rows that use it, ascending);
+ * they may be NULL for a layer whose input needs no gradient (layer 0). */
+typedef struct {
+    int32_t n_batches;
+    int32_t fanout;
+    int32_t cap_dst;    /* rows per batch */
+    int32_t cap_src;    /* frontier entries per batch */
+    int32_t cap_nnz;    /* edges per batch = cap_dst * fanout */
+    int32_t reserved;
+    int32_t *hdr;       /* device int32[n_batches][CR_HDR_WORDS] */
+    int32_t *src_ids;   /* device int32[n_batches][cap_src] */
+    int32_t *indptr;    /* device int32[n_batches][cap_dst+1] */
+    int32_t *indices;   /* device int32[n_batches][cap_nnz] */
+    int32_t *t_indptr;  /* device int32[n_batches][cap_src+1] or NULL */
+    int32_t *t_indices; /* device int32[n_batches][cap_nnz] or NULL */
+} cr_block_set;
+
+#define CR_SAMPLE_STRICT_INTRA 1u /* at p = 1 never take an inter-community neighbour (rows may be short) */
+
+typedef struct {
+    int32_t n_layers;              /* 1..CR_MAX_LAYERS */
+    int32_t fanout[CR_MAX_LAYERS]; /* by GNN layer, 0 = input side; the roots are expanded with fanout[n_layers-1] */
+    double p_intra;                /* [0.5, 1.0]: unnormalised weight of an intra-community edge; inter = 1 - p */
+    uint64_t seed;
+    uint32_t epoch;                /* < 2^24 */
+    uint32_t first_batch;          /* index (within the epoch) of the group's first mini-batch */
+    uint32_t flags;                /* CR_SAMPLE_* */
+    uint32_t reserved;
+} cr_sample_cfg;
+
+/* Capacities that can never overflow for batches of at most batch_size roots:
+ * cap_dst[L-1] = batch_size, cap_src[l] = min(n_nodes, cap_dst[l]*(1+fanout[l])), cap_dst[l-1] = cap_src[l]. */
+cr_status cr_block_capacities(const cr_sample_cfg *cfg, int64_t n_nodes, int32_t batch_size,
+                              int32_t *cap_dst /*host[n_layers]*/, int32_t *cap_src /*host[n_layers]*/,
+                              int32_t *cap_nnz /*host[n_layers]*/);
+
+cr_status cr_sample_blocks_workspace_bytes(const cr_sample_cfg *cfg, int64_t n_nodes, int32_t batch_size,
+                                           int32_t n_batches, size_t *bytes /*host*/);
+
+/* Samples the blocks of n_batches consecutive mini-batches in one set of launches.
+ *   roots : device int32[n_roots_total]: the slice of the epoch's permutation that starts at
+ *           mini-batch cfg->first_batch; batch g of the group is roots[g*batch_size ..
+ *           min((g+1)*batch_size, n_roots_total)); only the last may be short
+ *   layers: host array [n_layers] of block sets with n_batches == n_batches, fanout == cfg->fanout[l]
+ *           and capacities >= cr_block_capacities()
+ * For every destination row v with d neighbours, adjacency slot j gets the word
+ * Philox4x32-10(seed; slot>>2, v, batch, epoch<<8|2<<4|layer)[slot&3] and an integer key that orders
+ * the slots like independent exponential clocks of rate p (intra) or 1-p (inter); the
+ * min(fanout, d) smallest (key, slot) pairs are kept.  The output is a pure function of the
+ * arguments (bit-reproducible). */
+cr_status cr_sample_blocks(const cr_graph *graph, const cr_sample_cfg *cfg, const int32_t *roots,
+                           int64_t n_roots_total, int32_t batch_size, int32_t n_batches, void *ws,
+                           size_t ws_bytes, cr_block_set *layers, void *stream);
+
+/* ------------------------------------------------------------------------- */
+/* Training on the sub-graph: message passing of Eq. 1 in GraphSAGE-mean form */
+/*   Agg[v] = mean_{u in N_s(v)} H[u]   (0 for an empty row)                  */
+/*   Z[v]   = H[v] W_self + Agg[v] W_neigh + b ; ReLU on hidden layers        */
+/* ------------------------------------------------------------------------- */
+enum { CR_F32 = 0, CR_BF16 = 1 };
+
+/* Feature-row gather with mean aggregation for batch g of a block set (the input-feature fetch the
+ * paper identifies as the cost that tracks the batch's footprint, Section 6.1.1).
+ *   H_src    : device; indirect != 0: the resident feature table [n_nodes][ld_src], row of local
+ *              source position s is src_ids[s]; indirect == 0: dense [n_src][ld_src]
+ *   dtype    : CR_F32 or CR_BF16 element type of H_src;  F <= 1024 columns
+ *   agg      : device float [cap_dst][F] or NULL
+ *   agg_bf16 : device bf16 [cap_dst][ld_bf16] or NULL; columns F..ld_bf16-1 are written as zero
+ *   self_bf16: device bf16 [cap_dst][ld_bf16] or NULL; row v = H_src row of destination v (same padding)
+ *   ld_bf16  : multiple of 32, >= F, <= F rounded up to 64
+ * Rows >= n_dst (read from the block header on the device) are not touched. */
+cr_status cr_gather_aggregate_fwd(const cr_block_set *blocks, int32_t g, const void *H_src,
+                                  int32_t dtype, int64_t ld_src, int32_t F, int32_t indirect,
+                                  float *agg, uint16_t *agg_bf16, uint16_t *self_bf16,
+                                  int64_t ld_bf16, void *stream);
+
+/* Backward of the aggregation w.r.t. the source rows, atomic-free over the transposed block:
+ *   d_src[u] = sum_{v : u in N_s(v)} d_agg[v] / |N_s(v)|   (+ d_self[u] for u < n_dst)
+ *   d_agg, d_self : device float [cap_dst][ld_in] (d_self may be NULL)
+ *   d_src         : device float [cap_src][F] or NULL, rows 0..n_src-1 fully overwritten
+ *   relu_out      : device float [cap_src][ld_relu] or NULL: forward output of the layer below; where it
+ *                   is <= 0 the gradient is zeroed (ReLU backward)
+ *   d_src_bf16    : device bf16 [cap_src][ld_bf16] or NULL (same masking, zero padded columns) */
+cr_status cr_gather_aggregate_bwd(const cr_block_set *blocks, int32_t g, const float *d_agg,
+                                  const float *d_self, int64_t ld_in, int32_t F, const float *relu_out,
+                                  int64_t ld_relu, float *d_src, uint16_t *d_src_bf16, int64_t ld_bf16,
+                                  void *stream);
+
+/* One GraphSAGE layer's parameters.  F_pad = F_in rounded up to 32, N_pad = F_out rounded up to 64. */
+typedef struct {
+    int32_t F_in, F_out;
+    float *W;          /* device float [2*F_in][F_out]: rows 0..F_in-1 = W_self, F_in..2F_in-1 = W_neigh (master) */
+    float *bias;       /* device float [N_pad] (entries >= F_out stay 0) */
+    uint16_t *W_bf16;  /* device bf16 [2*F_pad][N_pad], zero padded shadow of W (row F_pad+k = W_neigh row k) */
+    uint16_t *Wt_bf16; /* device bf16 [N_pad][2*F_pad], its transpose */
+} cr_sage_layer;
+
+cr_status cr_sage_padded_dims(int32_t F_in, int32_t F_out, int32_t *F_pad, int32_t *N_pad);
+/* Rebuilds both bf16 shadows from the float master (call once after initialising W). */
+cr_status cr_sage_refresh_shadows(const cr_sage_layer *layer, void *stream);
+
+/* out[v] = h_self[v] W_self + agg[v] W_neigh + bias (ReLU if relu != 0), bf16 operands on the matrix
+ * cores with float accumulation.
+ *   hdr     : device block header; rows = hdr[CR_HDR_N_DST]; max_rows bounds the launch
+ *   h_self, agg : device bf16 [max_rows][ld_in], ld_in >= F_pad, padded columns zero
+ *   out     : device float [max_rows][N_pad] or NULL;  out_bf16 : device bf16 [max_rows][N_pad] or NULL */
+cr_status cr_sage_linear_fwd(const cr_sage_layer *layer, const int32_t *hdr, int32_t max_rows,
+                             const uint16_t *h_self, const uint16_t *agg, int64_t ld_in, int relu,
+                             float *out, uint16_t *out_bf16, void *stream);
+
+cr_status cr_sage_linear_bwd_workspace_bytes(int32_t F_in, int32_t F_out, int32_t max_rows, size_t *bytes);
+
+/* Backward of cr_sage_linear_fwd followed by one SGD step W <- W - lr*(dW + weight_decay*W),
+ * b <- b - lr*db on the master weights; both bf16 shadows are refreshed.
+ *   dz_bf16 : device bf16 [max_rows][N_pad]: dL/dZ with the ReLU mask already applied, padded columns zero
+ *   d_self, d_agg : device float [max_rows][F_pad] or both NULL (layer 0: the features need no gradient);
+ *                   they are computed with the weights from before the step
+ *   dW_out  : device float [2*F_in][F_out] or NULL, db_out: device float [F_out] or NULL: the gradients
+ *   ws      : device workspace of cr_sage_linear_bwd_workspace_bytes() bytes */
+cr_status cr_sage_linear_bwd(const cr_sage_layer *layer, const int32_t *hdr, int32_t max_rows,
+                             const uint16_t *h_self, const uint16_t *agg, int64_t ld_in,
+                             const uint16_t *dz_bf16, float lr, float weight_decay, float *d_self,
+                             float *d_agg, float *dW_out, float *db_out, void *ws, size_t ws_bytes,
+                             void *stream);
+
+/* Mean softmax cross-entropy over the root rows (labels exist for roots only) and its gradient.
+ *   hdr      : device block header of the root block; n = hdr[CR_HDR_N_DST] <= max_rows
+ *   logits   : device float [max_rows][ld], only columns 0..n_classes-1 take part
+ *   labels   : device int32[n_nodes] indexed by global node id;  root_ids : device int32[>= n]
+ *   loss     : device float[1];  row_loss : device float [max_rows] scratch
+ *   d_logits : device float [max_rows][ld] or NULL;  d_logits_bf16 : device bf16 [max_rows][ld] or NULL
+ *              (columns >= n_classes written as zero) */
+cr_status cr_softmax_xent(const int32_t *hdr, int32_t max_rows, const float *logits, int64_t ld,
+                          int32_t n_classes, const int32_t *labels, const int32_t *root_ids,
+                          float *loss, float *row_loss, float *d_logits, uint16_t *d_logits_bf16,
+                          void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* COMMRAND_H */

@@ -1,0 +1,307 @@
+"""ctypes binding of libcommrand.so: same names as the C ABI, argument marshalling only.
+
+torch is used for device memory and streams (plumbing); no arithmetic of the method happens here.
+The library must have been built (``python -m paper_2504_18082_amd.build``); loading fails loudly
+otherwise -- there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libcommrand.so")
+
+CR_MAX_LAYERS = 8
+CR_MAX_FANOUT = 64
+CR_HDR_WORDS = 8
+CR_OK, CR_ERR_INVALID_ARG, CR_ERR_CAPACITY, CR_ERR_UNSUPPORTED, CR_ERR_HIP = range(5)
+CR_ROOTS_NORAND, CR_ROOTS_COMM_RAND, CR_ROOTS_RAND = 0, 1, 2
+CR_F32, CR_BF16 = 0, 1
+CR_SAMPLE_STRICT_INTRA = 1
+
+EXPORTS = [
+    "cr_last_error", "cr_version", "cr_set_dry_run", "cr_mix_count_from_percent",
+    "cr_build_batches_workspace_bytes", "cr_build_batches",
+    "cr_block_capacities", "cr_sample_blocks_workspace_bytes", "cr_sample_blocks",
+    "cr_gather_aggregate_fwd", "cr_gather_aggregate_bwd",
+    "cr_sage_padded_dims", "cr_sage_refresh_shadows", "cr_sage_linear_fwd",
+    "cr_sage_linear_bwd_workspace_bytes", "cr_sage_linear_bwd", "cr_softmax_xent",
+]
+
+
+class CrError(RuntimeError):
+    def __init__(self, status, text):
+        super().__init__(f"cr_status {status}: {text}")
+        self.status = status
+
+
+class cr_batch_cfg(C.Structure):
+    _fields_ = [("policy", C.c_int32), ("mix_count", C.c_int32), ("batch_size", C.c_int32),
+                ("epoch", C.c_uint32), ("seed", C.c_uint64)]
+
+
+class cr_graph(C.Structure):
+    _fields_ = [("n_nodes", C.c_int64), ("n_entries", C.c_int64), ("indptr", C.c_void_p),
+                ("indices", C.c_void_p), ("comm", C.c_void_p), ("n_comm", C.c_int32)]
+
+
+class cr_block_set(C.Structure):
+    _fields_ = [("n_batches", C.c_int32), ("fanout", C.c_int32), ("cap_dst", C.c_int32),
+                ("cap_src", C.c_int32), ("cap_nnz", C.c_int32), ("reserved", C.c_int32),
+                ("hdr", C.c_void_p), ("src_ids", C.c_void_p), ("indptr", C.c_void_p),
+                ("indices", C.c_void_p), ("t_indptr", C.c_void_p), ("t_indices", C.c_void_p)]
+
+
+class cr_sample_cfg(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("fanout", C.c_int32 * CR_MAX_LAYERS),
+                ("p_intra", C.c_double), ("seed", C.c_uint64), ("epoch", C.c_uint32),
+                ("first_batch", C.c_uint32), ("flags", C.c_uint32), ("reserved", C.c_uint32)]
+
+
+class cr_sage_layer(C.Structure):
+    _fields_ = [("F_in", C.c_int32), ("F_out", C.c_int32), ("W", C.c_void_p), ("bias", C.c_void_p),
+                ("W_bf16", C.c_void_p), ("Wt_bf16", C.c_void_p)]
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library; raises if it was not built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2504_18082_amd.build`")
+        L = C.CDLL(LIB_PATH)
+        vp, i32, i64, u64 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64
+        L.cr_last_error.restype = C.c_char_p
+        L.cr_version.restype = C.c_char_p
+        L.cr_set_dry_run.argtypes = [C.c_int]
+        L.cr_set_dry_run.restype = None
+        L.cr_mix_count_from_percent.argtypes = [C.c_double, i32]
+        L.cr_mix_count_from_percent.restype = i32
+        L.cr_build_batches_workspace_bytes.argtypes = [i64, i32, C.POINTER(C.c_size_t)]
+        L.cr_build_batches.argtypes = [C.POINTER(cr_batch_cfg), vp, i64, vp, i32, vp, C.c_size_t, vp,
+                                       C.POINTER(i64), vp]
+        L.cr_block_capacities.argtypes = [C.POINTER(cr_sample_cfg), i64, i32, C.POINTER(i32),
+                                          C.POINTER(i32), C.POINTER(i32)]
+        L.cr_sample_blocks_workspace_bytes.argtypes = [C.POINTER(cr_sample_cfg), i64, i32, i32,
+                                                       C.POINTER(C.c_size_t)]
+        L.cr_sample_blocks.argtypes = [C.POINTER(cr_graph), C.POINTER(cr_sample_cfg), vp, i64, i32, i32,
+                                       vp, C.c_size_t, C.POINTER(cr_block_set), vp]
+        L.cr_gather_aggregate_fwd.argtypes = [C.POINTER(cr_block_set), i32, vp, i32, i64, i32, i32, vp, vp,
+                                              vp, i64, vp]
+        L.cr_gather_aggregate_bwd.argtypes = [C.POINTER(cr_block_set), i32, vp, vp, i64, i32, vp, i64, vp,
+                                              vp, i64, vp]
+        L.cr_sage_padded_dims.argtypes = [i32, i32, C.POINTER(i32), C.POINTER(i32)]
+        L.cr_sage_refresh_shadows.argtypes = [C.POINTER(cr_sage_layer), vp]
+        L.cr_sage_linear_fwd.argtypes = [C.POINTER(cr_sage_layer), vp, i32, vp, vp, i64, C.c_int, vp, vp, vp]
+        L.cr_sage_linear_bwd_workspace_bytes.argtypes = [i32, i32, i32, C.POINTER(C.c_size_t)]
+        L.cr_sage_linear_bwd.argtypes = [C.POINTER(cr_sage_layer), vp, i32, vp, vp, i64, vp, C.c_float,
+                                         C.c_float, vp, vp, vp, vp, vp, C.c_size_t, vp]
+        L.cr_softmax_xent.argtypes = [vp, i32, vp, i64, i32, vp, vp, vp, vp, vp, vp, vp]
+        for name in EXPORTS:
+            fn = getattr(L, name)
+            if name not in ("cr_last_error", "cr_version", "cr_set_dry_run", "cr_mix_count_from_percent"):
+                fn.restype = i32
+        _lib = L
+    return _lib
+
+
+def _check(status):
+    if status != CR_OK:
+        raise CrError(status, lib().cr_last_error().decode())
+
+
+def _ptr(t):
+    """Device (or host) address of a torch tensor / None."""
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(stream=None):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+# --------------------------------------------------------------------------- small host helpers
+def cr_version() -> str:
+    return lib().cr_version().decode()
+
+
+def cr_set_dry_run(on: bool):
+    lib().cr_set_dry_run(int(on))
+
+
+def cr_mix_count_from_percent(k_percent: float, n_comm_in_train: int) -> int:
+    return int(lib().cr_mix_count_from_percent(k_percent, n_comm_in_train))
+
+
+def make_sample_cfg(fanouts: Sequence[int], p_intra: float, seed: int, epoch: int, first_batch: int = 0,
+                    flags: int = 0) -> cr_sample_cfg:
+    cfg = cr_sample_cfg()
+    cfg.n_layers = len(fanouts)
+    for i, f in enumerate(fanouts[:CR_MAX_LAYERS]):
+        cfg.fanout[i] = int(f)
+    cfg.p_intra, cfg.seed, cfg.epoch, cfg.first_batch, cfg.flags = p_intra, seed, epoch, first_batch, flags
+    return cfg
+
+
+def cr_block_capacities(cfg: cr_sample_cfg, n_nodes: int, batch_size: int):
+    L = max(1, min(cfg.n_layers, CR_MAX_LAYERS))
+    a, b, c = (C.c_int32 * L)(), (C.c_int32 * L)(), (C.c_int32 * L)()
+    _check(lib().cr_block_capacities(C.byref(cfg), n_nodes, batch_size, a, b, c))
+    return list(a), list(b), list(c)
+
+
+class BlockSet:
+    """Device storage of one layer's blocks for a group of batches (torch int32 tensors)."""
+
+    def __init__(self, n_batches, fanout, cap_dst, cap_src, cap_nnz, transposed, device="cuda"):
+        import torch
+        z = lambda *shape: torch.zeros(shape, dtype=torch.int32, device=device)
+        self.n_batches, self.fanout = n_batches, fanout
+        self.cap_dst, self.cap_src, self.cap_nnz = cap_dst, cap_src, cap_nnz
+        self.hdr = z(n_batches, CR_HDR_WORDS)
+        self.src_ids = z(n_batches, cap_src)
+        self.indptr = z(n_batches, cap_dst + 1)
+        self.indices = z(n_batches, cap_nnz)
+        self.t_indptr = z(n_batches, cap_src + 1) if transposed else None
+        self.t_indices = z(n_batches, cap_nnz) if transposed else None
+        self.c = cr_block_set(n_batches, fanout, cap_dst, cap_src, cap_nnz, 0, _ptr(self.hdr),
+                              _ptr(self.src_ids), _ptr(self.indptr), _ptr(self.indices),
+                              _ptr(self.t_indptr), _ptr(self.t_indices))
+
+    def hdr_ptr(self, g):
+        return C.c_void_p(self.hdr.data_ptr() + g * CR_HDR_WORDS * 4)
+
+    def src_ids_ptr(self, g):
+        return C.c_void_p(self.src_ids.data_ptr() + g * self.cap_src * 4)
+
+    @classmethod
+    def from_host(cls, blk, fanout, device="cuda"):
+        """Upload one oracle/numpy block (n_dst, src_ids, indptr, indices[, t_indptr, t_indices])."""
+        import numpy as np
+        import torch
+        tr = getattr(blk, "t_indptr", None) is not None
+        cap_dst, cap_src, cap_nnz = max(1, blk.n_dst), max(1, blk.n_src, blk.n_dst), max(1, blk.nnz)
+        bs = cls(1, fanout, cap_dst, cap_src, cap_nnz, tr, device)
+        up = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(device)
+        bs.hdr[0, :3] = up([blk.n_dst, blk.n_src, blk.nnz])
+        bs.src_ids[0, :blk.n_src] = up(blk.src_ids)
+        bs.indptr[0, :blk.n_dst + 1] = up(blk.indptr[:blk.n_dst + 1])
+        bs.indices[0, :blk.nnz] = up(blk.indices)
+        if tr:
+            bs.t_indptr[0, :blk.n_src + 1] = up(blk.t_indptr)
+            bs.t_indices[0, :blk.nnz] = up(blk.t_indices)
+        return bs
+
+
+def alloc_block_sets(cfg: cr_sample_cfg, n_nodes: int, batch_size: int, n_batches: int,
+                     device="cuda") -> List[BlockSet]:
+    cap_dst, cap_src, cap_nnz = cr_block_capacities(cfg, n_nodes, batch_size)
+    return [BlockSet(n_batches, cfg.fanout[l], cap_dst[l], cap_src[l], cap_nnz[l], l >= 1, device)
+            for l in range(cfg.n_layers)]
+
+
+# --------------------------------------------------------------------------- step 1
+def cr_build_batches_workspace_bytes(n_train: int, n_comm: int) -> int:
+    n = C.c_size_t(0)
+    _check(lib().cr_build_batches_workspace_bytes(n_train, n_comm, C.byref(n)))
+    return n.value
+
+
+def cr_build_batches(policy, mix_count, batch_size, seed, epoch, train_ids, comm, n_comm, ws, out_perm,
+                     stream=None) -> int:
+    cfg = cr_batch_cfg(policy, mix_count, batch_size, epoch, seed)
+    nb = C.c_int64(0)
+    _check(lib().cr_build_batches(C.byref(cfg), _ptr(train_ids), train_ids.numel(), _ptr(comm), n_comm,
+                                  _ptr(ws), ws.numel() * ws.element_size(), _ptr(out_perm), C.byref(nb),
+                                  _stream(stream)))
+    return nb.value
+
+
+# --------------------------------------------------------------------------- step 2
+def make_graph(indptr, indices, comm, n_comm) -> cr_graph:
+    return cr_graph(indptr.numel() - 1, indices.numel(), _ptr(indptr), _ptr(indices), _ptr(comm), n_comm)
+
+
+def cr_sample_blocks_workspace_bytes(cfg, n_nodes, batch_size, n_batches) -> int:
+    n = C.c_size_t(0)
+    _check(lib().cr_sample_blocks_workspace_bytes(C.byref(cfg), n_nodes, batch_size, n_batches, C.byref(n)))
+    return n.value
+
+
+def cr_sample_blocks(graph: cr_graph, cfg: cr_sample_cfg, roots, n_roots_total, batch_size, n_batches, ws,
+                     layers: List[BlockSet], stream=None):
+    arr = (cr_block_set * len(layers))(*[b.c for b in layers])
+    _check(lib().cr_sample_blocks(C.byref(graph), C.byref(cfg), _ptr(roots), n_roots_total, batch_size,
+                                  n_batches, _ptr(ws), ws.numel() * ws.element_size(), arr, _stream(stream)))
+
+
+# --------------------------------------------------------------------------- training on the sub-graph
+def cr_gather_aggregate_fwd(blocks: BlockSet, g, H_src, dtype, ld_src, F, indirect, agg=None, agg_bf16=None,
+                            self_bf16=None, ld_bf16=0, stream=None):
+    _check(lib().cr_gather_aggregate_fwd(C.byref(blocks.c), g, _ptr(H_src), dtype, ld_src, F, int(indirect),
+                                         _ptr(agg), _ptr(agg_bf16), _ptr(self_bf16), ld_bf16, _stream(stream)))
+
+
+def cr_gather_aggregate_bwd(blocks: BlockSet, g, d_agg, d_self, ld_in, F, relu_out=None, ld_relu=0, d_src=None,
+                            d_src_bf16=None, ld_bf16=0, stream=None):
+    _check(lib().cr_gather_aggregate_bwd(C.byref(blocks.c), g, _ptr(d_agg), _ptr(d_self), ld_in, F,
+                                         _ptr(relu_out), ld_relu, _ptr(d_src), _ptr(d_src_bf16), ld_bf16,
+                                         _stream(stream)))
+
+
+def cr_sage_padded_dims(F_in, F_out):
+    a, b = C.c_int32(0), C.c_int32(0)
+    _check(lib().cr_sage_padded_dims(F_in, F_out, C.byref(a), C.byref(b)))
+    return a.value, b.value
+
+
+class SageLayer:
+    """Device storage of one layer's parameters: float master + two bf16 shadows."""
+
+    def __init__(self, W_host, b_host, device="cuda"):
+        import torch
+        F2, F_out = W_host.shape
+        self.F_in, self.F_out = F2 // 2, F_out
+        self.F_pad, self.N_pad = cr_sage_padded_dims(self.F_in, F_out)
+        self.W = torch.from_numpy(W_host).to(device=device, dtype=torch.float32).contiguous()
+        self.bias = torch.zeros(self.N_pad, dtype=torch.float32, device=device)
+        self.bias[:F_out] = torch.from_numpy(b_host).to(device)
+        self.W_bf16 = torch.zeros((2 * self.F_pad, self.N_pad), dtype=torch.int16, device=device)
+        self.Wt_bf16 = torch.zeros((self.N_pad, 2 * self.F_pad), dtype=torch.int16, device=device)
+        self.c = cr_sage_layer(self.F_in, self.F_out, _ptr(self.W), _ptr(self.bias), _ptr(self.W_bf16),
+                               _ptr(self.Wt_bf16))
+
+    def refresh(self, stream=None):
+        _check(lib().cr_sage_refresh_shadows(C.byref(self.c), _stream(stream)))
+
+
+def cr_sage_linear_fwd(layer: SageLayer, hdr_ptr, max_rows, h_self, agg, ld_in, relu, out=None, out_bf16=None,
+                       stream=None):
+    _check(lib().cr_sage_linear_fwd(C.byref(layer.c), hdr_ptr, max_rows, _ptr(h_self), _ptr(agg), ld_in,
+                                    int(relu), _ptr(out), _ptr(out_bf16), _stream(stream)))
+
+
+def cr_sage_linear_bwd_workspace_bytes(F_in, F_out, max_rows) -> int:
+    n = C.c_size_t(0)
+    _check(lib().cr_sage_linear_bwd_workspace_bytes(F_in, F_out, max_rows, C.byref(n)))
+    return n.value
+
+
+def cr_sage_linear_bwd(layer: SageLayer, hdr_ptr, max_rows, h_self, agg, ld_in, dz_bf16, lr, weight_decay,
+                       d_self, d_agg, ws, dW_out=None, db_out=None, stream=None):
+    _check(lib().cr_sage_linear_bwd(C.byref(layer.c), hdr_ptr, max_rows, _ptr(h_self), _ptr(agg), ld_in,
+                                    _ptr(dz_bf16), lr, weight_decay, _ptr(d_self), _ptr(d_agg), _ptr(dW_out),
+                                    _ptr(db_out), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)))
+
+
+def cr_softmax_xent(hdr_ptr, max_rows, logits, ld, n_classes, labels, root_ids_ptr, loss, row_loss,
+                    d_logits=None, d_logits_bf16=None, stream=None):
+    _check(lib().cr_softmax_xent(hdr_ptr, max_rows, _ptr(logits), ld, n_classes, _ptr(labels), root_ids_ptr,
+                                 _ptr(loss), _ptr(row_loss), _ptr(d_logits), _ptr(d_logits_bf16),
+                                 _stream(stream)))

@@ -1,0 +1,116 @@
+// Shared host/device helpers of libcommrand.so (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+
+#include "../../include/commrand.h"
+
+namespace cr {
+
+// ---- host side: error text, dry-run flag, argument checks ------------------------------------
+void set_error(const char *fmt, ...);
+bool dry_run();
+
+#define CR_REQUIRE(cond, code, ...)                  \
+    do {                                             \
+        if (!(cond)) {                               \
+            ::cr::set_error(__VA_ARGS__);            \
+            return (code);                           \
+        }                                            \
+    } while (0)
+
+#define CR_HIP_CHECK(expr)                                                              \
+    do {                                                                                \
+        hipError_t e_ = (expr);                                                         \
+        if (e_ != hipSuccess) {                                                         \
+            ::cr::set_error("%s failed: %s", #expr, hipGetErrorString(e_));             \
+            return CR_ERR_HIP;                                                          \
+        }                                                                               \
+    } while (0)
+
+#define CR_LAUNCH_CHECK()                                                               \
+    do {                                                                                \
+        hipError_t e_ = hipGetLastError();                                              \
+        if (e_ != hipSuccess) {                                                         \
+            ::cr::set_error("kernel launch failed: %s", hipGetErrorString(e_));         \
+            return CR_ERR_HIP;                                                          \
+        }                                                                               \
+    } while (0)
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+inline int64_t ceil_div(int64_t x, int64_t m) { return (x + m - 1) / m; }
+
+// carve an aligned slice out of a workspace
+struct Carver {
+    char *base;
+    size_t off = 0;
+    explicit Carver(void *p) : base(static_cast<char *>(p)) {}
+    template <typename T>
+    T *take(size_t n)
+    {
+        off = (off + 255) & ~size_t(255);
+        T *p = base ? reinterpret_cast<T *>(base + off) : nullptr;
+        off += n * sizeof(T);
+        return p;
+    }
+    size_t bytes() const { return (off + 255) & ~size_t(255); }
+};
+
+// ---- device side ------------------------------------------------------------------------------
+constexpr int WAVE = 64;
+
+// Philox4x32-10 (Salmon et al., SC'11): counter (c0..c3), key (k0,k1) -> four words.
+struct u32x4 { uint32_t x, y, z, w; };
+
+__device__ __forceinline__ u32x4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                               uint32_t k0, uint32_t k1)
+{
+#pragma unroll
+    for (int i = 0; i < 10; ++i) {
+        const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        c0 = hi1 ^ c1 ^ k0;
+        c1 = lo1;
+        c2 = hi0 ^ c3 ^ k1;
+        c3 = lo0;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    return {c0, c1, c2, c3};
+}
+
+// stream domains (bits 4..7 of counter word 3)
+constexpr uint32_t DOMAIN_COMMUNITY = 0, DOMAIN_NODE = 1, DOMAIN_NEIGHBOUR = 2;
+
+__device__ __forceinline__ uint64_t shuffle_key(uint64_t seed, uint32_t epoch, uint32_t domain, uint32_t id)
+{
+    const u32x4 w = philox4x32_10(0u, id, 0u, (epoch << 8) | (domain << 4), (uint32_t)seed, (uint32_t)(seed >> 32));
+    return ((uint64_t)w.x << 32) | w.y;
+}
+
+__device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & (WAVE - 1)); }
+
+// bf16 <-> float on raw bit patterns, round to nearest even
+__device__ __forceinline__ uint16_t f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7F800000u) == 0x7F800000u) return (uint16_t)(u >> 16);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+
+// Block ids are dealt round-robin to the 8 XCDs, each with its own L2.  Give every XCD one
+// contiguous range of logical tiles so that neighbouring tiles share a cache.
+__device__ __forceinline__ uint32_t xcd_remap(uint32_t bid, uint32_t nblocks)
+{
+    constexpr uint32_t XCDS = 8;
+    const uint32_t per = nblocks / XCDS;       // full rounds
+    const uint32_t body = per * XCDS;
+    if (bid >= body) return bid;               // ragged tail keeps its place
+    return (bid % XCDS) * per + bid / XCDS;
+}
+
+}  // namespace cr

@@ -1,0 +1,354 @@
+// Feature-row gather with GraphSAGE-mean aggregation (forward) and its atomic-free backward over
+// the transposed block.  HBM-bound: every lane moves 16 bytes per load, a sub-wave group of LPR
+// lanes owns one output row and keeps several independent row loads in flight.
+#include "cr_common.h"
+
+namespace cr {
+
+template <typename T> struct Vec16;
+template <> struct Vec16<float> {
+    static constexpr int N = 4;
+    __device__ static __forceinline__ void load(const float *p, float (&v)[4])
+    {
+        const float4 x = *reinterpret_cast<const float4 *>(p);
+        v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
+    }
+};
+template <> struct Vec16<uint16_t> {
+    static constexpr int N = 8;
+    __device__ static __forceinline__ void load(const uint16_t *p, float (&v)[8])
+    {
+        const uint4 x = *reinterpret_cast<const uint4 *>(p);
+        v[0] = __uint_as_float(x.x << 16); v[1] = __uint_as_float(x.x & 0xFFFF0000u);
+        v[2] = __uint_as_float(x.y << 16); v[3] = __uint_as_float(x.y & 0xFFFF0000u);
+        v[4] = __uint_as_float(x.z << 16); v[5] = __uint_as_float(x.z & 0xFFFF0000u);
+        v[6] = __uint_as_float(x.w << 16); v[7] = __uint_as_float(x.w & 0xFFFF0000u);
+    }
+};
+
+template <int N>
+__device__ __forceinline__ void store_bf16_row(uint16_t *dst, const float (&v)[N], int col, int F)
+{
+    // dst points at column `col` of a zero-padded bf16 row; columns >= F are written as zero
+    uint32_t packed[N / 2];
+#pragma unroll
+    for (int i = 0; i < N; i += 2) {
+        const uint16_t lo = (col + i < F) ? f32_to_bf16(v[i]) : (uint16_t)0;
+        const uint16_t hi = (col + i + 1 < F) ? f32_to_bf16(v[i + 1]) : (uint16_t)0;
+        packed[i / 2] = (uint32_t)lo | ((uint32_t)hi << 16);
+    }
+    if constexpr (N == 4) {
+        *reinterpret_cast<uint2 *>(dst) = make_uint2(packed[0], packed[1]);
+    } else {
+        *reinterpret_cast<uint4 *>(dst) = make_uint4(packed[0], packed[1], packed[2], packed[3]);
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// forward
+// ------------------------------------------------------------------------------------------------
+template <typename T, int LPR, int NCHUNK>
+__global__ __launch_bounds__(256) void gather_mean_fwd_kernel(
+    const int32_t *__restrict__ hdr, const int32_t *__restrict__ indptr,
+    const int32_t *__restrict__ indices, const int32_t *__restrict__ row_map,
+    const T *__restrict__ table, int64_t ld, int F, float *__restrict__ agg,
+    uint16_t *__restrict__ agg_bf16, uint16_t *__restrict__ self_bf16, int64_t ld_bf16)
+{
+    constexpr int VEC = Vec16<T>::N;
+    constexpr int U = NCHUNK == 1 ? 8 : (NCHUNK <= 3 ? 4 : 2);   // independent row loads in flight per lane
+    constexpr int ROWS_PER_BLOCK = 256 / LPR;
+    const int n_dst = hdr[CR_HDR_N_DST];
+    const uint32_t lb = xcd_remap(blockIdx.x, gridDim.x);
+    const int row = (int)(lb * ROWS_PER_BLOCK + threadIdx.x / LPR);
+    if (row >= n_dst) return;
+    const int gl = (int)(threadIdx.x % LPR);
+
+    const int start = indptr[row], end = indptr[row + 1];
+    float acc[NCHUNK][VEC];
+#pragma unroll
+    for (int c = 0; c < NCHUNK; ++c)
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) acc[c][i] = 0.f;
+
+    for (int base = start; base < end; base += LPR) {
+        const int e = base + gl;
+        int rid = 0;
+        if (e < end) {
+            const int s = indices[e];
+            rid = row_map ? row_map[s] : s;
+        }
+        const int cnt = min(LPR, end - base);
+        for (int t = 0; t < cnt; t += U) {
+            float v[U][NCHUNK][VEC];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int r = __shfl(rid, t + u, LPR);
+                const T *p = table + (int64_t)r * ld;
+#pragma unroll
+                for (int c = 0; c < NCHUNK; ++c) {
+                    const int col = (c * LPR + gl) * VEC;
+                    if (col < F && t + u < cnt) Vec16<T>::load(p + col, v[u][c]);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int c = 0; c < NCHUNK; ++c) {
+                    const int col = (c * LPR + gl) * VEC;
+                    if (col < F && t + u < cnt) {
+#pragma unroll
+                        for (int i = 0; i < VEC; ++i) acc[c][i] += v[u][c][i];
+                    }
+                }
+        }
+    }
+
+    const int deg = end - start;
+    const float fdeg = (float)(deg > 0 ? deg : 1);
+#pragma unroll
+    for (int c = 0; c < NCHUNK; ++c) {
+        const int col = (c * LPR + gl) * VEC;
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) acc[c][i] = acc[c][i] / fdeg;
+        if (agg && col < F) {
+            float *o = agg + (int64_t)row * F + col;
+            if ((F & 3) == 0) {
+#pragma unroll
+                for (int i = 0; i < VEC; i += 4)
+                    *reinterpret_cast<float4 *>(o + i) = make_float4(acc[c][i], acc[c][i + 1], acc[c][i + 2], acc[c][i + 3]);
+            } else {
+#pragma unroll
+                for (int i = 0; i < VEC; ++i)
+                    if (col + i < F) o[i] = acc[c][i];
+            }
+        }
+        if (agg_bf16 && col < ld_bf16) store_bf16_row<VEC>(agg_bf16 + (int64_t)row * ld_bf16 + col, acc[c], col, F);
+    }
+
+    if (self_bf16) {
+        const int r = row_map ? row_map[row] : row;
+        const T *p = table + (int64_t)r * ld;
+#pragma unroll
+        for (int c = 0; c < NCHUNK; ++c) {
+            const int col = (c * LPR + gl) * VEC;
+            if (col < ld_bf16) {
+                float v[VEC];
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) v[i] = 0.f;
+                if (col < F) Vec16<T>::load(p + col, v);
+                store_bf16_row<VEC>(self_bf16 + (int64_t)row * ld_bf16 + col, v, col, F);
+            }
+        }
+    }
+}
+
+template <typename T, int LPR, int NCHUNK>
+static void launch_fwd(int cap_dst, const int32_t *hdr, const int32_t *indptr, const int32_t *indices,
+                       const int32_t *row_map, const void *table, int64_t ld, int F, float *agg,
+                       uint16_t *agg_bf16, uint16_t *self_bf16, int64_t ld_bf16, hipStream_t st)
+{
+    const int rows_per_block = 256 / LPR;
+    const unsigned grid = (unsigned)ceil_div(cap_dst, rows_per_block);
+    hipLaunchKernelGGL((gather_mean_fwd_kernel<T, LPR, NCHUNK>), dim3(grid), dim3(256), 0, st, hdr, indptr,
+                       indices, row_map, static_cast<const T *>(table), ld, F, agg, agg_bf16, self_bf16, ld_bf16);
+}
+
+// ------------------------------------------------------------------------------------------------
+// backward: one sub-wave group per source row pulls from the destination rows that used it
+// ------------------------------------------------------------------------------------------------
+template <int LPR, int NCHUNK>
+__global__ __launch_bounds__(256) void gather_mean_bwd_kernel(
+    const int32_t *__restrict__ hdr, const int32_t *__restrict__ indptr,
+    const int32_t *__restrict__ t_indptr, const int32_t *__restrict__ t_indices,
+    const float *__restrict__ d_agg, const float *__restrict__ d_self, int64_t ld_in, int F,
+    const float *__restrict__ relu_out, int64_t ld_relu, float *__restrict__ d_src,
+    uint16_t *__restrict__ d_src_bf16, int64_t ld_bf16)
+{
+    constexpr int VEC = 4;
+    constexpr int U = NCHUNK == 1 ? 8 : (NCHUNK <= 3 ? 4 : 2);
+    constexpr int ROWS_PER_BLOCK = 256 / LPR;
+    const int n_dst = hdr[CR_HDR_N_DST], n_src = hdr[CR_HDR_N_SRC];
+    const uint32_t lb = xcd_remap(blockIdx.x, gridDim.x);
+    const int s = (int)(lb * ROWS_PER_BLOCK + threadIdx.x / LPR);
+    if (s >= n_src) return;
+    const int gl = (int)(threadIdx.x % LPR);
+
+    float acc[NCHUNK][VEC];
+#pragma unroll
+    for (int c = 0; c < NCHUNK; ++c)
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) acc[c][i] = 0.f;
+
+    const int start = t_indptr[s], end = t_indptr[s + 1];
+    for (int base = start; base < end; base += LPR) {
+        const int e = base + gl;
+        int v = 0;
+        float w = 0.f;
+        if (e < end) {
+            v = t_indices[e];
+            w = 1.0f / (float)(indptr[v + 1] - indptr[v]);
+        }
+        const int cnt = min(LPR, end - base);
+        for (int t = 0; t < cnt; t += U) {
+            float4 x[U][NCHUNK];
+            float ww[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int vv = __shfl(v, t + u, LPR);
+                ww[u] = __shfl(w, t + u, LPR);
+                const float *p = d_agg + (int64_t)vv * ld_in;
+#pragma unroll
+                for (int c = 0; c < NCHUNK; ++c) {
+                    const int col = (c * LPR + gl) * VEC;
+                    if (col < F && t + u < cnt) x[u][c] = *reinterpret_cast<const float4 *>(p + col);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int c = 0; c < NCHUNK; ++c) {
+                    const int col = (c * LPR + gl) * VEC;
+                    if (col < F && t + u < cnt) {
+                        acc[c][0] += x[u][c].x * ww[u]; acc[c][1] += x[u][c].y * ww[u];
+                        acc[c][2] += x[u][c].z * ww[u]; acc[c][3] += x[u][c].w * ww[u];
+                    }
+                }
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < NCHUNK; ++c) {
+        const int col = (c * LPR + gl) * VEC;
+        if (col < F) {
+            if (d_self && s < n_dst) {
+                const float4 x = *reinterpret_cast<const float4 *>(d_self + (int64_t)s * ld_in + col);
+                acc[c][0] += x.x; acc[c][1] += x.y; acc[c][2] += x.z; acc[c][3] += x.w;
+            }
+            if (relu_out) {
+                const float4 y = *reinterpret_cast<const float4 *>(relu_out + (int64_t)s * ld_relu + col);
+                if (!(y.x > 0.f)) acc[c][0] = 0.f;
+                if (!(y.y > 0.f)) acc[c][1] = 0.f;
+                if (!(y.z > 0.f)) acc[c][2] = 0.f;
+                if (!(y.w > 0.f)) acc[c][3] = 0.f;
+            }
+            if (d_src) {
+                float *o = d_src + (int64_t)s * F + col;
+                if ((F & 3) == 0) {
+                    *reinterpret_cast<float4 *>(o) = make_float4(acc[c][0], acc[c][1], acc[c][2], acc[c][3]);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i)
+                        if (col + i < F) o[i] = acc[c][i];
+                }
+            }
+        }
+        if (d_src_bf16 && col < ld_bf16) store_bf16_row<VEC>(d_src_bf16 + (int64_t)s * ld_bf16 + col, acc[c], col, F);
+    }
+}
+
+template <int LPR, int NCHUNK>
+static void launch_bwd(int cap_src, const int32_t *hdr, const int32_t *indptr, const int32_t *t_indptr,
+                       const int32_t *t_indices, const float *d_agg, const float *d_self, int64_t ld_in, int F,
+                       const float *relu_out, int64_t ld_relu, float *d_src, uint16_t *d_src_bf16,
+                       int64_t ld_bf16, hipStream_t st)
+{
+    const unsigned grid = (unsigned)ceil_div(cap_src, 256 / LPR);
+    hipLaunchKernelGGL((gather_mean_bwd_kernel<LPR, NCHUNK>), dim3(grid), dim3(256), 0, st, hdr, indptr, t_indptr,
+                       t_indices, d_agg, d_self, ld_in, F, relu_out, ld_relu, d_src, d_src_bf16, ld_bf16);
+}
+
+}  // namespace cr
+
+using namespace cr;
+
+static cr_status check_block_set(const cr_block_set *b, int32_t g, bool need_t)
+{
+    CR_REQUIRE(b != nullptr, CR_ERR_INVALID_ARG, "blocks is NULL");
+    CR_REQUIRE(b->n_batches > 0 && g >= 0 && g < b->n_batches, CR_ERR_INVALID_ARG,
+               "batch index %d outside the block set's %d batches", g, b->n_batches);
+    CR_REQUIRE(b->cap_dst > 0 && b->cap_src >= b->cap_dst && b->cap_nnz > 0, CR_ERR_INVALID_ARG,
+               "block set capacities must be positive with cap_src >= cap_dst");
+    CR_REQUIRE(b->hdr && b->src_ids && b->indptr && b->indices, CR_ERR_INVALID_ARG, "block set has a NULL array");
+    if (need_t) CR_REQUIRE(b->t_indptr && b->t_indices, CR_ERR_INVALID_ARG, "block set carries no transposed block");
+    return CR_OK;
+}
+
+extern "C" cr_status cr_gather_aggregate_fwd(const cr_block_set *blocks, int32_t g, const void *H_src,
+                                             int32_t dtype, int64_t ld_src, int32_t F, int32_t indirect,
+                                             float *agg, uint16_t *agg_bf16, uint16_t *self_bf16,
+                                             int64_t ld_bf16, void *stream)
+{
+    cr_status st = check_block_set(blocks, g, false);
+    if (st != CR_OK) return st;
+    CR_REQUIRE(H_src != nullptr && aligned16(H_src), CR_ERR_INVALID_ARG, "H_src must be a 16-byte aligned device pointer");
+    CR_REQUIRE(dtype == CR_F32 || dtype == CR_BF16, CR_ERR_INVALID_ARG, "dtype must be CR_F32 or CR_BF16");
+    const int vec = dtype == CR_F32 ? 4 : 8;
+    CR_REQUIRE(F >= 1 && F <= 1024, CR_ERR_UNSUPPORTED, "F = %d outside 1..1024", F);
+    CR_REQUIRE(ld_src >= round_up(F, vec) && ld_src % vec == 0, CR_ERR_INVALID_ARG,
+               "ld_src = %lld must be a multiple of %d and cover F rounded up to it", (long long)ld_src, vec);
+    CR_REQUIRE(agg || agg_bf16 || self_bf16, CR_ERR_INVALID_ARG, "no output requested");
+    CR_REQUIRE(aligned16(agg) && aligned16(agg_bf16) && aligned16(self_bf16), CR_ERR_INVALID_ARG, "outputs must be 16-byte aligned");
+    if (agg_bf16 || self_bf16)
+        CR_REQUIRE(ld_bf16 % 32 == 0 && ld_bf16 >= F && ld_bf16 <= round_up(F, 64), CR_ERR_INVALID_ARG,
+                   "ld_bf16 = %lld must be a multiple of 32 in [F, F rounded up to 64]", (long long)ld_bf16);
+    if (dry_run()) return CR_OK;
+
+    const int32_t *hdr = blocks->hdr + (int64_t)g * CR_HDR_WORDS;
+    const int32_t *indptr = blocks->indptr + (int64_t)g * (blocks->cap_dst + 1);
+    const int32_t *indices = blocks->indices + (int64_t)g * blocks->cap_nnz;
+    const int32_t *row_map = indirect ? blocks->src_ids + (int64_t)g * blocks->cap_src : nullptr;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int cap = blocks->cap_dst;
+#define CR_FWD(T, LPR, NC) launch_fwd<T, LPR, NC>(cap, hdr, indptr, indices, row_map, H_src, ld_src, F, agg, agg_bf16, self_bf16, ld_bf16, s)
+    if (dtype == CR_F32) {
+        if (F <= 64) CR_FWD(float, 16, 1);
+        else if (F <= 128) CR_FWD(float, 32, 1);
+        else if (F <= 256) CR_FWD(float, 64, 1);
+        else if (F <= 512) CR_FWD(float, 64, 2);
+        else if (F <= 768) CR_FWD(float, 64, 3);
+        else CR_FWD(float, 64, 4);
+    } else {
+        if (F <= 128) CR_FWD(uint16_t, 16, 1);
+        else if (F <= 256) CR_FWD(uint16_t, 32, 1);
+        else if (F <= 512) CR_FWD(uint16_t, 64, 1);
+        else CR_FWD(uint16_t, 64, 2);
+    }
+#undef CR_FWD
+    CR_LAUNCH_CHECK();
+    return CR_OK;
+}
+
+extern "C" cr_status cr_gather_aggregate_bwd(const cr_block_set *blocks, int32_t g, const float *d_agg,
+                                             const float *d_self, int64_t ld_in, int32_t F,
+                                             const float *relu_out, int64_t ld_relu, float *d_src,
+                                             uint16_t *d_src_bf16, int64_t ld_bf16, void *stream)
+{
+    cr_status st = check_block_set(blocks, g, true);
+    if (st != CR_OK) return st;
+    CR_REQUIRE(d_agg != nullptr && aligned16(d_agg) && aligned16(d_self), CR_ERR_INVALID_ARG, "d_agg / d_self must be 16-byte aligned device pointers");
+    CR_REQUIRE(F >= 1 && F <= 1024, CR_ERR_UNSUPPORTED, "F = %d outside 1..1024", F);
+    CR_REQUIRE(ld_in >= round_up(F, 4) && ld_in % 4 == 0, CR_ERR_INVALID_ARG, "ld_in must be a multiple of 4 covering F");
+    if (relu_out) CR_REQUIRE(aligned16(relu_out) && ld_relu >= round_up(F, 4) && ld_relu % 4 == 0, CR_ERR_INVALID_ARG, "relu_out must be aligned with ld_relu a multiple of 4 covering F");
+    CR_REQUIRE(d_src || d_src_bf16, CR_ERR_INVALID_ARG, "no output requested");
+    CR_REQUIRE(aligned16(d_src) && aligned16(d_src_bf16), CR_ERR_INVALID_ARG, "outputs must be 16-byte aligned");
+    if (d_src_bf16)
+        CR_REQUIRE(ld_bf16 % 32 == 0 && ld_bf16 >= F && ld_bf16 <= round_up(F, 64), CR_ERR_INVALID_ARG,
+                   "ld_bf16 = %lld must be a multiple of 32 in [F, F rounded up to 64]", (long long)ld_bf16);
+    if (dry_run()) return CR_OK;
+
+    const int32_t *hdr = blocks->hdr + (int64_t)g * CR_HDR_WORDS;
+    const int32_t *indptr = blocks->indptr + (int64_t)g * (blocks->cap_dst + 1);
+    const int32_t *t_indptr = blocks->t_indptr + (int64_t)g * (blocks->cap_src + 1);
+    const int32_t *t_indices = blocks->t_indices + (int64_t)g * blocks->cap_nnz;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int cap = blocks->cap_src;
+#define CR_BWD(LPR, NC) launch_bwd<LPR, NC>(cap, hdr, indptr, t_indptr, t_indices, d_agg, d_self, ld_in, F, relu_out, ld_relu, d_src, d_src_bf16, ld_bf16, s)
+    if (F <= 64) CR_BWD(16, 1);
+    else if (F <= 128) CR_BWD(32, 1);
+    else if (F <= 256) CR_BWD(64, 1);
+    else if (F <= 512) CR_BWD(64, 2);
+    else if (F <= 768) CR_BWD(64, 3);
+    else CR_BWD(64, 4);
+#undef CR_BWD
+    CR_LAUNCH_CHECK();
+    return CR_OK;
+}
