@@ -115,7 +115,8 @@ typedef struct {
  * entries are the newly reached neighbours in order of first appearance (rows ascending, adjacency
  * slot ascending); indptr/indices are a CSR over local source positions.  t_indptr/t_indices hold
  * the transposed block (for every source position the destination rows that use it, ascending);
- * they may be NULL for a layer whose input needs no gradient (layer 0). */
+ * they may be NULL when the layer's input needs no gradient, and must be NULL for layer 0 (the
+ * feature table takes no gradient). */
 typedef struct {
     int32_t n_batches;
     int32_t fanout;

@@ -1,0 +1,622 @@
+// Sub-graph construction (Algorithm 1 Step-2 with the intra-community probability knob of
+// Section 4.2): per-layer fanout sampling, frontier de-duplication in first-appearance order,
+// CSR blocks with local column ids and their transposes.  Integer arithmetic only; a whole group of
+// mini-batches is sampled by one set of launches (blockIdx.y = batch within the group).
+#include "cr_common.h"
+
+namespace cr {
+
+constexpr uint64_t KEY_MAX = ~0ull;
+constexpr uint64_t EMPTY = ~0ull;
+
+// ---------------------------------------------------------------------------------------------
+// integer exponential clock: E(r) = -log2((2r+1)/2^33) in Q24, one result bit per squaring
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t exp_clock_q24(uint32_t r)
+{
+    const uint64_t x = 2ull * r + 1ull;
+    const int t = 63 - __clzll((long long)x);
+    uint32_t y = (uint32_t)((x << (63 - t)) >> 32);
+    uint32_t frac = 0;
+#pragma unroll
+    for (int i = 0; i < 24; ++i) {
+        const uint32_t hi = __umulhi(y, y), lo = y * y;
+        const bool top = (hi >> 31) != 0;
+        y = top ? hi : ((hi << 1) | (lo >> 31));
+        frac = (frac << 1) | (top ? 1u : 0u);
+    }
+    return ((uint32_t)(33 - t) << 24) - frac;
+}
+
+__device__ __forceinline__ bool less2(uint64_t ka, uint32_t sa, uint64_t kb, uint32_t sb)
+{
+    return ka < kb || (ka == kb && sa < sb);
+}
+
+struct SelectArgs {
+    const int64_t *g_indptr;
+    const int32_t *g_indices;
+    const int32_t *comm;
+    const int32_t *dst_ids;   // roots, or the frontier of the layer above
+    int64_t dst_stride;
+    const int32_t *prev_hdr;  // header array of the layer above, NULL for the root layer
+    int64_t n_roots_total;
+    int32_t batch_size;
+    int32_t fanout;
+    uint32_t q_in, q_out;
+    uint32_t strict_p1;       // drop inter-community picks (only meaningful when q_out == 0)
+    uint32_t seed_lo, seed_hi, ctr3, first_batch;
+    int32_t *sel;             // [G][cap_dst*fanout] chosen global neighbour ids, rows in slot order
+    int64_t sel_stride;
+    int32_t *cnt;             // [G][cap_dst]
+    int64_t cnt_stride;
+};
+
+__device__ __forceinline__ int group_n_dst(const int32_t *prev_hdr, int g, int64_t n_roots_total, int batch_size)
+{
+    if (prev_hdr) return prev_hdr[(int64_t)g * CR_HDR_WORDS + CR_HDR_N_SRC];
+    const int64_t left = n_roots_total - (int64_t)g * batch_size;
+    return (int)(left < 0 ? 0 : (left > batch_size ? batch_size : left));
+}
+
+// One wave per destination row.  Lane c < fanout holds one candidate (key, slot); the row is
+// streamed in chunks of 64 slots and a slot replaces the current worst candidate when its
+// (key, slot) pair is smaller.  Every pair is distinct, so the surviving set is unique.
+__global__ __launch_bounds__(256) void select_kernel(SelectArgs a)
+{
+    const int g = blockIdx.y;
+    const int n_dst = group_n_dst(a.prev_hdr, g, a.n_roots_total, a.batch_size);
+    const int row = (int)(blockIdx.x * 4 + threadIdx.x / WAVE);
+    if (row >= n_dst) return;
+    const int lane = lane_id();
+    const int f = a.fanout;
+    const int32_t v = a.dst_ids[(int64_t)g * a.dst_stride + row];
+    const int64_t base = a.g_indptr[v];
+    const int64_t deg64 = a.g_indptr[v + 1] - base;
+    const int deg = (int)(deg64 > 0x7FFFFFFF ? 0x7FFFFFFF : deg64);
+    const int k = deg < f ? deg : f;
+    const bool need_class = a.q_in != a.q_out;
+    const int32_t cv = need_class ? a.comm[v] : 0;
+    const uint32_t batch = a.first_batch + (uint32_t)g;
+
+    auto key_of = [&](int j, int32_t &u_out) -> uint64_t {
+        const int32_t u = a.g_indices[base + j];
+        u_out = u;
+        const u32x4 w = philox4x32_10((uint32_t)j >> 2, (uint32_t)v, batch, a.ctr3, a.seed_lo, a.seed_hi);
+        const uint32_t sel = (uint32_t)j & 3u;
+        const uint32_t r = sel == 0 ? w.x : (sel == 1 ? w.y : (sel == 2 ? w.z : w.w));
+        if (!need_class) return (uint64_t)r;
+        const bool intra = a.comm[u] == cv;
+        if (a.q_out == 0) return (intra ? 0ull : (1ull << 62)) + (uint64_t)r;
+        return (uint64_t)exp_clock_q24(r) * (uint64_t)(intra ? a.q_out : a.q_in);
+    };
+
+    uint64_t ckey = 0;       // lanes >= k stay at the minimum so they never become the worst candidate
+    uint32_t cslot = 0;
+    int32_t cu = 0;          // global id of the candidate's neighbour
+    if (lane < k) {
+        ckey = key_of(lane, cu);
+        cslot = (uint32_t)lane;
+    }
+
+    if (deg > f) {
+        uint64_t tkey;
+        uint32_t tslot;
+        int tlane;
+        auto worst = [&]() {
+            uint64_t mk = ckey;
+            uint32_t ms = cslot;
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) {
+                const uint64_t ok = __shfl_xor(mk, off);
+                const uint32_t os = __shfl_xor(ms, off);
+                if (less2(mk, ms, ok, os)) { mk = ok; ms = os; }
+            }
+            tkey = mk;
+            tslot = ms;
+            const uint64_t hit = __ballot(lane < k && ckey == mk && cslot == ms);
+            tlane = __ffsll((long long)hit) - 1;
+        };
+        worst();
+        for (int j0 = k; j0 < deg; j0 += WAVE) {
+            const int j = j0 + lane;
+            uint64_t key = KEY_MAX;
+            int32_t u = 0;
+            if (j < deg) key = key_of(j, u);
+            uint64_t pass = __ballot(j < deg && less2(key, (uint32_t)j, tkey, tslot));
+            while (pass) {
+                const int src = __ffsll((long long)pass) - 1;
+                pass &= pass - 1;
+                const uint64_t nk = __shfl(key, src);
+                const uint32_t ns = (uint32_t)(j0 + src);
+                if (less2(nk, ns, tkey, tslot)) {
+                    const int32_t nu = __shfl(u, src);
+                    if (lane == tlane) { ckey = nk; cslot = ns; cu = nu; }
+                    worst();
+                }
+            }
+        }
+    }
+
+    const bool valid = lane < k && !(a.strict_p1 && ckey >= (1ull << 62));
+    int rank = 0;
+    for (int i = 0; i < k; ++i) {
+        const uint32_t si = __shfl(cslot, i);
+        const int vi = __shfl((int)valid, i);
+        rank += (vi && si < cslot) ? 1 : 0;
+    }
+    const uint64_t vmask = __ballot(valid);
+    if (valid) a.sel[(int64_t)g * a.sel_stride + (int64_t)row * f + rank] = cu;
+    if (lane == 0) a.cnt[(int64_t)g * a.cnt_stride + row] = __popcll(vmask);
+}
+
+// ---------------------------------------------------------------------------------------------
+// exclusive scan of n ints by one workgroup of 1024 threads (one workgroup per batch)
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ int block_exclusive_scan_1024(int x, int *lds /*[17]*/, int &total)
+{
+    const int lane = lane_id(), wave = threadIdx.x / WAVE;
+    int incl = x;
+#pragma unroll
+    for (int off = 1; off < WAVE; off <<= 1) {
+        const int y = __shfl_up(incl, off);
+        if (lane >= off) incl += y;
+    }
+    if (lane == WAVE - 1) lds[wave] = incl;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int run = 0;
+        for (int w = 0; w < 16; ++w) { const int t = lds[w]; lds[w] = run; run += t; }
+        lds[16] = run;
+    }
+    __syncthreads();
+    total = lds[16];
+    return lds[wave] + incl - x;
+}
+
+// out[0..n] = exclusive prefix sums of in[0..n) (out[n] = total).  Each thread owns one contiguous chunk.
+__device__ __forceinline__ int scan_chunked(const int32_t *in, int32_t *out, int32_t *out_copy, int n, int *lds)
+{
+    const int chunk = (n + 1023) / 1024;
+    const int start = threadIdx.x * chunk;
+    const int stop = min(n, start + chunk);
+    int sum = 0;
+    for (int i = start; i < stop; ++i) sum += in[i];
+    int total;
+    int run = block_exclusive_scan_1024(sum, lds, total);
+    for (int i = start; i < stop; ++i) {
+        const int x = in[i];
+        out[i] = run;
+        if (out_copy) out_copy[i] = run;
+        run += x;
+    }
+    if (threadIdx.x == 0) out[n] = total;
+    return total;
+}
+
+struct ScanArgs {
+    const int32_t *prev_hdr;
+    int64_t n_roots_total;
+    int32_t batch_size;
+    int32_t mode;          // 0: row counts -> indptr ; 1: new-node counts -> offsets ; 2: source counts -> t_indptr
+    const int32_t *in;
+    int64_t in_stride;
+    int32_t *out;
+    int64_t out_stride;
+    int32_t *out_copy;     // mode 2: fill cursors
+    int64_t copy_stride;
+    int32_t *hdr;
+};
+
+__global__ __launch_bounds__(1024) void scan_kernel(ScanArgs a)
+{
+    __shared__ int lds[17];
+    const int g = blockIdx.x;
+    int32_t *hdr = a.hdr + (int64_t)g * CR_HDR_WORDS;
+    const int n_dst = group_n_dst(a.prev_hdr, g, a.n_roots_total, a.batch_size);
+    const int n = a.mode == 2 ? hdr[CR_HDR_N_SRC] : n_dst;
+    const int total = scan_chunked(a.in + (int64_t)g * a.in_stride, a.out + (int64_t)g * a.out_stride,
+                                   a.out_copy ? a.out_copy + (int64_t)g * a.copy_stride : nullptr, n, lds);
+    if (threadIdx.x == 0) {
+        if (a.mode == 0) {
+            hdr[CR_HDR_N_DST] = n_dst;
+            hdr[CR_HDR_NNZ] = total;
+            hdr[CR_HDR_STATUS] = 0;
+            hdr[4] = hdr[5] = hdr[6] = hdr[7] = 0;
+        } else if (a.mode == 1) {
+            hdr[CR_HDR_N_SRC] = n_dst + total;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// frontier de-duplication: open-addressing table of (id << 32 | position), min position wins
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t hash_slot(uint32_t id, int bits) { return (id * 0x9E3779B1u) >> (32 - bits); }
+
+__device__ __forceinline__ bool table_insert(unsigned long long *table, int bits, uint32_t id, uint32_t pos)
+{
+    const uint32_t mask = (1u << bits) - 1u;
+    const unsigned long long mine = ((unsigned long long)id << 32) | pos;
+    uint32_t h = hash_slot(id, bits);
+    for (uint32_t probe = 0; probe <= mask; ++probe) {
+        const unsigned long long old = atomicCAS(&table[h], EMPTY, mine);
+        if (old == EMPTY) return true;
+        if ((uint32_t)(old >> 32) == id) {
+            atomicMin(&table[h], mine);
+            return true;
+        }
+        h = (h + 1) & mask;
+    }
+    return false;
+}
+
+// returns the table slot of id (which must be present), or -1
+__device__ __forceinline__ int table_find(const unsigned long long *table, int bits, uint32_t id, uint32_t &value)
+{
+    const uint32_t mask = (1u << bits) - 1u;
+    uint32_t h = hash_slot(id, bits);
+    for (uint32_t probe = 0; probe <= mask; ++probe) {
+        const unsigned long long e = table[h];
+        if ((uint32_t)(e >> 32) == id) { value = (uint32_t)e; return (int)h; }
+        if (e == EMPTY) break;
+        h = (h + 1) & mask;
+    }
+    value = 0;
+    return -1;
+}
+
+// clears the first n (even) entries of every batch's table slice
+__global__ __launch_bounds__(256) void fill_u64_kernel(unsigned long long *base, int64_t slice_stride, int64_t n, unsigned long long v)
+{
+    unsigned long long *p = base + (int64_t)blockIdx.y * slice_stride;
+    int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 2;
+    const int64_t stride = (int64_t)gridDim.x * 256 * 2;
+    for (; i + 1 < n; i += stride) *reinterpret_cast<ulonglong2 *>(p + i) = make_ulonglong2(v, v);
+    if (i < n) p[i] = v;
+}
+
+struct DedupArgs {
+    const int32_t *prev_hdr;
+    int64_t n_roots_total;
+    int32_t batch_size;
+    int32_t fanout;
+    int32_t gw;               // lanes per row: power of two >= fanout
+    const int32_t *dst_ids;
+    int64_t dst_stride;
+    const int32_t *sel;
+    int64_t sel_stride;
+    unsigned long long *table;
+    int64_t table_stride;
+    int32_t table_bits;
+    int32_t *hdr;
+    int32_t *src_ids;
+    int64_t src_stride;
+    int32_t *indptr;
+    int64_t indptr_stride;
+    int32_t *indices;
+    int64_t indices_stride;
+    int32_t *newcnt;          // [G][cap_dst]
+    int32_t *newoff;          // [G][cap_dst+1]
+    unsigned long long *newmask;
+    int64_t row_stride;       // stride of newcnt / newmask
+    int64_t off_stride;
+    int32_t *tcount;          // [G][cap_src] or NULL
+    int32_t *tfill;           // [G][cap_src+1]
+    int64_t t_stride;
+    int32_t *t_indptr;
+    int64_t t_indptr_stride;
+    int32_t *t_indices;
+    int32_t *t_tmp;           // [G][cap_nnz] destination rows in arrival order
+    int32_t *t_pos;           // [G][cap_nnz] where each edge landed in t_tmp
+    int64_t tt_stride;        // stride of t_tmp / t_pos
+};
+
+// maps a thread to (row, j): gw lanes per row
+#define CR_ROW_LANE()                                                                 \
+    const int g = blockIdx.y;                                                         \
+    const int n_dst = group_n_dst(a.prev_hdr, g, a.n_roots_total, a.batch_size);      \
+    const int64_t gt = (int64_t)blockIdx.x * 256 + threadIdx.x;                       \
+    const int row = (int)(gt / a.gw);                                                 \
+    const int j = (int)(gt % a.gw);                                                   \
+    const int32_t *indptr = a.indptr + (int64_t)g * a.indptr_stride;                  \
+    const bool in_row = row < n_dst;                                                  \
+    const int rstart = in_row ? indptr[row] : 0;                                      \
+    const int k = in_row ? indptr[row + 1] - rstart : 0;                              \
+    const bool active = in_row && j < k;                                              \
+    const int64_t ell = (int64_t)row * a.fanout + j;                                  \
+    unsigned long long *table = a.table + (int64_t)g * a.table_stride;                \
+    int32_t *hdr = a.hdr + (int64_t)g * CR_HDR_WORDS;                                 \
+    (void)hdr; (void)table; (void)ell; (void)rstart
+
+__global__ __launch_bounds__(256) void insert_kernel(DedupArgs a)
+{
+    CR_ROW_LANE();
+    bool ok = true;
+    if (in_row && j == 0) {
+        const int32_t v = a.dst_ids[(int64_t)g * a.dst_stride + row];
+        a.src_ids[(int64_t)g * a.src_stride + row] = v;
+        ok = table_insert(table, a.table_bits, (uint32_t)v, (uint32_t)row);
+    }
+    if (active) {
+        const int32_t u = a.sel[(int64_t)g * a.sel_stride + ell];
+        ok = table_insert(table, a.table_bits, (uint32_t)u, (uint32_t)(n_dst + ell)) && ok;
+    }
+    if (!ok) atomicOr(&hdr[CR_HDR_STATUS], 1);
+}
+
+// which chosen neighbours are seen here for the first time (and are not destination nodes)
+__global__ __launch_bounds__(256) void mark_new_kernel(DedupArgs a)
+{
+    CR_ROW_LANE();
+    bool isnew = false;
+    if (active) {
+        const int32_t u = a.sel[(int64_t)g * a.sel_stride + ell];
+        uint32_t pos;
+        const int h = table_find(table, a.table_bits, (uint32_t)u, pos);
+        isnew = h >= 0 && pos == (uint32_t)(n_dst + ell);
+    }
+    const uint64_t m = __ballot(isnew);
+    if (in_row && j == 0) {
+        const int sub = lane_id() / a.gw;
+        const uint64_t rowmask = a.gw == 64 ? m : ((m >> (sub * a.gw)) & ((1ull << a.gw) - 1ull));
+        a.newcnt[(int64_t)g * a.row_stride + row] = __popcll(rowmask);
+        a.newmask[(int64_t)g * a.row_stride + row] = rowmask;
+    }
+}
+
+// new nodes get consecutive frontier positions after the destination nodes; the table entry of a
+// node now holds its position in the frontier
+__global__ __launch_bounds__(256) void assign_kernel(DedupArgs a)
+{
+    CR_ROW_LANE();
+    if (a.tcount) {   // clear the per-source counters of the transposed block
+        const int n_src = hdr[CR_HDR_N_SRC];
+        int32_t *tc = a.tcount + (int64_t)g * a.t_stride;
+        for (int64_t i = gt; i < n_src; i += (int64_t)gridDim.x * 256) tc[i] = 0;
+    }
+    if (!active) return;
+    const uint64_t rowmask = a.newmask[(int64_t)g * a.row_stride + row];
+    if (!((rowmask >> j) & 1ull)) return;
+    const int32_t u = a.sel[(int64_t)g * a.sel_stride + ell];
+    const int local = n_dst + a.newoff[(int64_t)g * a.off_stride + row] + __popcll(rowmask & ((1ull << j) - 1ull));
+    a.src_ids[(int64_t)g * a.src_stride + local] = u;
+    uint32_t pos;
+    const int h = table_find(table, a.table_bits, (uint32_t)u, pos);
+    if (h >= 0) table[h] = ((unsigned long long)(uint32_t)u << 32) | (uint32_t)local;
+}
+
+__global__ __launch_bounds__(256) void relabel_kernel(DedupArgs a)
+{
+    CR_ROW_LANE();
+    if (!active) return;
+    const int32_t u = a.sel[(int64_t)g * a.sel_stride + ell];
+    uint32_t local;
+    table_find(table, a.table_bits, (uint32_t)u, local);
+    a.indices[(int64_t)g * a.indices_stride + rstart + j] = (int32_t)local;
+    if (a.tcount) atomicAdd(&a.tcount[(int64_t)g * a.t_stride + local], 1);
+}
+
+// transposed block: scatter the destination row of every edge into its source's segment in arrival
+// order, then rank inside the segment so that the stored order is ascending (hence reproducible)
+__global__ __launch_bounds__(256) void t_fill_kernel(DedupArgs a)
+{
+    CR_ROW_LANE();
+    if (!active) return;
+    const int64_t e = (int64_t)g * a.indices_stride + rstart + j;
+    const int local = a.indices[e];
+    const int p = atomicAdd(&a.tfill[(int64_t)g * a.t_stride + local], 1);
+    a.t_tmp[(int64_t)g * a.tt_stride + p] = row;
+    a.t_pos[(int64_t)g * a.tt_stride + rstart + j] = p;
+}
+
+__global__ __launch_bounds__(256) void t_rank_kernel(DedupArgs a)
+{
+    CR_ROW_LANE();
+    if (!active) return;
+    const int64_t e = (int64_t)g * a.indices_stride + rstart + j;
+    const int local = a.indices[e];
+    const int32_t *tp = a.t_indptr + (int64_t)g * a.t_indptr_stride;
+    const int s0 = tp[local], s1 = tp[local + 1];
+    const int32_t *tmp = a.t_tmp + (int64_t)g * a.tt_stride;
+    const int mine = a.t_pos[(int64_t)g * a.tt_stride + rstart + j];
+    int rank = 0;
+    for (int q = s0; q < s1; ++q) {
+        const int r = tmp[q];
+        rank += (r < row || (r == row && q < mine)) ? 1 : 0;
+    }
+    a.t_indices[(int64_t)g * a.indices_stride + s0 + rank] = row;
+}
+
+// ---------------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------------
+struct SamplePlan {
+    int L;
+    int32_t cap_dst[CR_MAX_LAYERS], cap_src[CR_MAX_LAYERS], cap_nnz[CR_MAX_LAYERS];
+    int table_bits[CR_MAX_LAYERS];
+    int64_t max_dst = 0, max_src_t = 0, max_nnz = 0, max_nnz_t = 0, max_table = 0;
+    // workspace slices
+    int32_t *sel, *cnt, *newoff, *tcount, *tfill, *t_tmp, *t_pos;
+    unsigned long long *newmask, *table;
+    size_t bytes;
+};
+
+static cr_status make_plan(const cr_sample_cfg *cfg, int64_t n_nodes, int32_t batch_size, int32_t n_batches,
+                           void *ws, SamplePlan &p)
+{
+    CR_REQUIRE(cfg != nullptr, CR_ERR_INVALID_ARG, "cfg is NULL");
+    CR_REQUIRE(cfg->n_layers >= 1 && cfg->n_layers <= CR_MAX_LAYERS, CR_ERR_INVALID_ARG,
+               "n_layers = %d outside 1..%d", cfg->n_layers, CR_MAX_LAYERS);
+    CR_REQUIRE(n_nodes >= 1 && n_nodes <= 0x7FFFFFFF, CR_ERR_INVALID_ARG, "n_nodes must be in 1..2^31-1");
+    CR_REQUIRE(batch_size >= 1, CR_ERR_INVALID_ARG, "batch_size must be positive");
+    CR_REQUIRE(n_batches >= 1 && n_batches <= 65535, CR_ERR_INVALID_ARG, "n_batches must be in 1..65535");
+    CR_REQUIRE(cfg->p_intra >= 0.5 && cfg->p_intra <= 1.0, CR_ERR_INVALID_ARG, "p_intra = %g outside [0.5, 1]", cfg->p_intra);
+    CR_REQUIRE(cfg->epoch < (1u << 24), CR_ERR_INVALID_ARG, "epoch must be below 2^24");
+    p.L = cfg->n_layers;
+    int64_t dst = batch_size;
+    for (int l = p.L - 1; l >= 0; --l) {
+        const int f = cfg->fanout[l];
+        CR_REQUIRE(f >= 1 && f <= CR_MAX_FANOUT, CR_ERR_INVALID_ARG, "fanout[%d] = %d outside 1..%d", l, f, CR_MAX_FANOUT);
+        const int64_t nnz = dst * f;
+        int64_t src = dst * (1 + f);
+        if (src > n_nodes) src = n_nodes;
+        if (src < dst) src = dst;
+        CR_REQUIRE(nnz <= 0x7FFFFFFF / 2, CR_ERR_UNSUPPORTED, "layer %d would hold %lld edges per batch", l, (long long)nnz);
+        p.cap_dst[l] = (int32_t)dst;
+        p.cap_src[l] = (int32_t)src;
+        p.cap_nnz[l] = (int32_t)nnz;
+        int bits = 4;
+        while ((1ll << bits) < 2 * src) ++bits;
+        CR_REQUIRE(bits <= 31, CR_ERR_UNSUPPORTED, "layer %d frontier too large for the de-duplication table", l);
+        p.table_bits[l] = bits;
+        p.max_dst = dst > p.max_dst ? dst : p.max_dst;
+        p.max_nnz = nnz > p.max_nnz ? nnz : p.max_nnz;
+        p.max_table = (1ll << bits) > p.max_table ? (1ll << bits) : p.max_table;
+        if (l >= 1) {
+            p.max_src_t = src > p.max_src_t ? src : p.max_src_t;
+            p.max_nnz_t = nnz > p.max_nnz_t ? nnz : p.max_nnz_t;
+        }
+        dst = src;
+    }
+    const size_t G = (size_t)n_batches;
+    Carver c(ws);
+    p.sel = c.take<int32_t>(G * p.max_nnz);
+    p.cnt = c.take<int32_t>(G * p.max_dst);
+    p.newoff = c.take<int32_t>(G * (p.max_dst + 1));
+    p.newmask = c.take<unsigned long long>(G * p.max_dst);
+    p.table = c.take<unsigned long long>(G * p.max_table);
+    p.tcount = c.take<int32_t>(G * (p.max_src_t + 1));
+    p.tfill = c.take<int32_t>(G * (p.max_src_t + 1));
+    p.t_tmp = c.take<int32_t>(G * (p.max_nnz_t + 1));
+    p.t_pos = c.take<int32_t>(G * (p.max_nnz_t + 1));
+    p.bytes = c.bytes();
+    return CR_OK;
+}
+
+}  // namespace cr
+
+using namespace cr;
+
+extern "C" cr_status cr_block_capacities(const cr_sample_cfg *cfg, int64_t n_nodes, int32_t batch_size,
+                                         int32_t *cap_dst, int32_t *cap_src, int32_t *cap_nnz)
+{
+    SamplePlan p;
+    cr_status st = make_plan(cfg, n_nodes, batch_size, 1, nullptr, p);
+    if (st != CR_OK) return st;
+    CR_REQUIRE(cap_dst && cap_src && cap_nnz, CR_ERR_INVALID_ARG, "output arrays must not be NULL");
+    for (int l = 0; l < p.L; ++l) {
+        cap_dst[l] = p.cap_dst[l];
+        cap_src[l] = p.cap_src[l];
+        cap_nnz[l] = p.cap_nnz[l];
+    }
+    return CR_OK;
+}
+
+extern "C" cr_status cr_sample_blocks_workspace_bytes(const cr_sample_cfg *cfg, int64_t n_nodes, int32_t batch_size,
+                                                      int32_t n_batches, size_t *bytes)
+{
+    SamplePlan p;
+    cr_status st = make_plan(cfg, n_nodes, batch_size, n_batches, nullptr, p);
+    if (st != CR_OK) return st;
+    CR_REQUIRE(bytes != nullptr, CR_ERR_INVALID_ARG, "bytes is NULL");
+    *bytes = p.bytes;
+    return CR_OK;
+}
+
+extern "C" cr_status cr_sample_blocks(const cr_graph *graph, const cr_sample_cfg *cfg, const int32_t *roots,
+                                      int64_t n_roots_total, int32_t batch_size, int32_t n_batches, void *ws,
+                                      size_t ws_bytes, cr_block_set *layers, void *stream)
+{
+    CR_REQUIRE(graph != nullptr, CR_ERR_INVALID_ARG, "graph is NULL");
+    CR_REQUIRE(graph->indptr && graph->indices && graph->comm, CR_ERR_INVALID_ARG, "graph has a NULL array");
+    CR_REQUIRE(graph->n_comm >= 1, CR_ERR_INVALID_ARG, "n_comm must be positive");
+    SamplePlan p;
+    cr_status st = make_plan(cfg, graph->n_nodes, batch_size, n_batches, ws, p);
+    if (st != CR_OK) return st;
+    CR_REQUIRE(roots != nullptr && layers != nullptr, CR_ERR_INVALID_ARG, "roots / layers must not be NULL");
+    CR_REQUIRE(n_roots_total > (int64_t)(n_batches - 1) * batch_size && n_roots_total <= (int64_t)n_batches * batch_size,
+               CR_ERR_INVALID_ARG, "n_roots_total = %lld does not fill %d batches of %d (only the last may be short)",
+               (long long)n_roots_total, n_batches, batch_size);
+    CR_REQUIRE((uint64_t)cfg->first_batch + (uint64_t)n_batches <= 0xFFFFFFFFull, CR_ERR_INVALID_ARG, "batch index overflows 32 bits");
+    CR_REQUIRE(ws != nullptr && aligned16(ws), CR_ERR_INVALID_ARG, "workspace must be a 16-byte aligned device pointer");
+    CR_REQUIRE(ws_bytes >= p.bytes, CR_ERR_CAPACITY, "workspace of %zu bytes, %zu needed", ws_bytes, p.bytes);
+    for (int l = 0; l < p.L; ++l) {
+        const cr_block_set &b = layers[l];
+        CR_REQUIRE(b.n_batches == n_batches && b.fanout == cfg->fanout[l], CR_ERR_INVALID_ARG,
+                   "layers[%d]: n_batches / fanout do not match the request", l);
+        CR_REQUIRE(b.cap_dst >= p.cap_dst[l] && b.cap_src >= p.cap_src[l] && b.cap_nnz >= p.cap_nnz[l], CR_ERR_CAPACITY,
+                   "layers[%d]: capacities (%d, %d, %d) below the bound (%d, %d, %d)", l, b.cap_dst, b.cap_src, b.cap_nnz,
+                   p.cap_dst[l], p.cap_src[l], p.cap_nnz[l]);
+        CR_REQUIRE(b.hdr && b.src_ids && b.indptr && b.indices, CR_ERR_INVALID_ARG, "layers[%d] has a NULL array", l);
+        CR_REQUIRE((b.t_indptr == nullptr) == (b.t_indices == nullptr), CR_ERR_INVALID_ARG,
+                   "layers[%d]: t_indptr and t_indices must be given together", l);
+        CR_REQUIRE(l >= 1 || b.t_indptr == nullptr, CR_ERR_UNSUPPORTED, "layer 0 takes no transposed block (its input needs no gradient)");
+    }
+    if (dry_run()) return CR_OK;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const uint32_t q_in = (uint32_t)llround(cfg->p_intra * 65536.0);
+    const uint32_t q_out = 65536u - q_in;
+    const dim3 blk(256);
+    for (int l = p.L - 1; l >= 0; --l) {
+        const cr_block_set &b = layers[l];
+        const int f = cfg->fanout[l];
+        const bool root = l == p.L - 1;
+        const int32_t *prev_hdr = root ? nullptr : layers[l + 1].hdr;
+        const int32_t *dst_ids = root ? roots : layers[l + 1].src_ids;
+        const int64_t dst_stride = root ? batch_size : layers[l + 1].cap_src;
+        const int cap_dst = p.cap_dst[l];
+
+        SelectArgs sa;
+        sa.g_indptr = graph->indptr; sa.g_indices = graph->indices; sa.comm = graph->comm;
+        sa.dst_ids = dst_ids; sa.dst_stride = dst_stride; sa.prev_hdr = prev_hdr;
+        sa.n_roots_total = n_roots_total; sa.batch_size = batch_size; sa.fanout = f;
+        sa.q_in = q_in; sa.q_out = q_out;
+        sa.strict_p1 = (q_out == 0 && (cfg->flags & CR_SAMPLE_STRICT_INTRA)) ? 1u : 0u;
+        sa.seed_lo = (uint32_t)cfg->seed; sa.seed_hi = (uint32_t)(cfg->seed >> 32);
+        sa.ctr3 = (cfg->epoch << 8) | (DOMAIN_NEIGHBOUR << 4) | (uint32_t)l;
+        sa.first_batch = cfg->first_batch;
+        sa.sel = p.sel; sa.sel_stride = p.max_nnz; sa.cnt = p.cnt; sa.cnt_stride = p.max_dst;
+        hipLaunchKernelGGL(select_kernel, dim3((unsigned)ceil_div(cap_dst, 4), n_batches), blk, 0, s, sa);
+
+        ScanArgs sc;
+        sc.prev_hdr = prev_hdr; sc.n_roots_total = n_roots_total; sc.batch_size = batch_size;
+        sc.mode = 0; sc.in = p.cnt; sc.in_stride = p.max_dst; sc.out = b.indptr; sc.out_stride = b.cap_dst + 1;
+        sc.out_copy = nullptr; sc.copy_stride = 0; sc.hdr = b.hdr;
+        hipLaunchKernelGGL(scan_kernel, dim3(n_batches), dim3(1024), 0, s, sc);
+
+        const int64_t table_size = 1ll << p.table_bits[l];
+        hipLaunchKernelGGL(fill_u64_kernel, dim3((unsigned)(ceil_div(table_size, 512) < 4096 ? ceil_div(table_size, 512) : 4096), n_batches), blk, 0, s,
+                           p.table, p.max_table, table_size, EMPTY);
+
+        DedupArgs da;
+        da.prev_hdr = prev_hdr; da.n_roots_total = n_roots_total; da.batch_size = batch_size; da.fanout = f;
+        da.gw = f <= 16 ? 16 : (f <= 32 ? 32 : 64);
+        da.dst_ids = dst_ids; da.dst_stride = dst_stride; da.sel = p.sel; da.sel_stride = p.max_nnz;
+        da.table = p.table; da.table_stride = p.max_table; da.table_bits = p.table_bits[l];
+        da.hdr = b.hdr; da.src_ids = b.src_ids; da.src_stride = b.cap_src;
+        da.indptr = b.indptr; da.indptr_stride = b.cap_dst + 1; da.indices = b.indices; da.indices_stride = b.cap_nnz;
+        da.newcnt = p.cnt; da.newoff = p.newoff; da.newmask = p.newmask; da.row_stride = p.max_dst; da.off_stride = p.max_dst + 1;
+        const bool tr = b.t_indptr != nullptr;
+        da.tcount = tr ? p.tcount : nullptr; da.tfill = p.tfill; da.t_stride = p.max_src_t + 1;
+        da.t_indptr = b.t_indptr; da.t_indptr_stride = b.cap_src + 1; da.t_indices = b.t_indices;
+        da.t_tmp = p.t_tmp; da.t_pos = p.t_pos; da.tt_stride = p.max_nnz_t + 1;
+        const dim3 grid((unsigned)ceil_div((int64_t)cap_dst * da.gw, 256), n_batches);
+        hipLaunchKernelGGL(insert_kernel, grid, blk, 0, s, da);
+        hipLaunchKernelGGL(mark_new_kernel, grid, blk, 0, s, da);
+        sc.mode = 1; sc.in = p.cnt; sc.in_stride = p.max_dst; sc.out = p.newoff; sc.out_stride = p.max_dst + 1;
+        hipLaunchKernelGGL(scan_kernel, dim3(n_batches), dim3(1024), 0, s, sc);
+        hipLaunchKernelGGL(assign_kernel, grid, blk, 0, s, da);
+        hipLaunchKernelGGL(relabel_kernel, grid, blk, 0, s, da);
+        if (tr) {
+            sc.mode = 2; sc.in = p.tcount; sc.in_stride = p.max_src_t + 1; sc.out = b.t_indptr; sc.out_stride = b.cap_src + 1;
+            sc.out_copy = p.tfill; sc.copy_stride = p.max_src_t + 1;
+            hipLaunchKernelGGL(scan_kernel, dim3(n_batches), dim3(1024), 0, s, sc);
+            hipLaunchKernelGGL(t_fill_kernel, grid, blk, 0, s, da);
+            hipLaunchKernelGGL(t_rank_kernel, grid, blk, 0, s, da);
+        }
+    }
+    CR_LAUNCH_CHECK();
+    return CR_OK;
+}

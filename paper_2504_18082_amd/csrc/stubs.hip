@@ -3,9 +3,6 @@
 #define STUB { cr::set_error("not implemented yet"); return CR_ERR_UNSUPPORTED; }
 extern "C" cr_status cr_build_batches_workspace_bytes(int64_t, int32_t, size_t *) STUB
 extern "C" cr_status cr_build_batches(const cr_batch_cfg *, const int32_t *, int64_t, const int32_t *, int32_t, void *, size_t, int32_t *, int64_t *, void *) STUB
-extern "C" cr_status cr_block_capacities(const cr_sample_cfg *, int64_t, int32_t, int32_t *, int32_t *, int32_t *) STUB
-extern "C" cr_status cr_sample_blocks_workspace_bytes(const cr_sample_cfg *, int64_t, int32_t, int32_t, size_t *) STUB
-extern "C" cr_status cr_sample_blocks(const cr_graph *, const cr_sample_cfg *, const int32_t *, int64_t, int32_t, int32_t, void *, size_t, cr_block_set *, void *) STUB
 extern "C" cr_status cr_sage_padded_dims(int32_t, int32_t, int32_t *, int32_t *) STUB
 extern "C" cr_status cr_sage_refresh_shadows(const cr_sage_layer *, void *) STUB
 extern "C" cr_status cr_sage_linear_fwd(const cr_sage_layer *, const int32_t *, int32_t, const uint16_t *, const uint16_t *, int64_t, int, float *, uint16_t *, void *) STUB
