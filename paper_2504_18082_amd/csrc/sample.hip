@@ -150,50 +150,6 @@ __global__ __launch_bounds__(256) void select_kernel(SelectArgs a)
     if (lane == 0) a.cnt[(int64_t)g * a.cnt_stride + row] = __popcll(vmask);
 }
 
-// ---------------------------------------------------------------------------------------------
-// exclusive scan of n ints by one workgroup of 1024 threads (one workgroup per batch)
-// ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ int block_exclusive_scan_1024(int x, int *lds /*[17]*/, int &total)
-{
-    const int lane = lane_id(), wave = threadIdx.x / WAVE;
-    int incl = x;
-#pragma unroll
-    for (int off = 1; off < WAVE; off <<= 1) {
-        const int y = __shfl_up(incl, off);
-        if (lane >= off) incl += y;
-    }
-    if (lane == WAVE - 1) lds[wave] = incl;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        int run = 0;
-        for (int w = 0; w < 16; ++w) { const int t = lds[w]; lds[w] = run; run += t; }
-        lds[16] = run;
-    }
-    __syncthreads();
-    total = lds[16];
-    return lds[wave] + incl - x;
-}
-
-// out[0..n] = exclusive prefix sums of in[0..n) (out[n] = total).  Each thread owns one contiguous chunk.
-__device__ __forceinline__ int scan_chunked(const int32_t *in, int32_t *out, int32_t *out_copy, int n, int *lds)
-{
-    const int chunk = (n + 1023) / 1024;
-    const int start = threadIdx.x * chunk;
-    const int stop = min(n, start + chunk);
-    int sum = 0;
-    for (int i = start; i < stop; ++i) sum += in[i];
-    int total;
-    int run = block_exclusive_scan_1024(sum, lds, total);
-    for (int i = start; i < stop; ++i) {
-        const int x = in[i];
-        out[i] = run;
-        if (out_copy) out_copy[i] = run;
-        run += x;
-    }
-    if (threadIdx.x == 0) out[n] = total;
-    return total;
-}
-
 struct ScanArgs {
     const int32_t *prev_hdr;
     int64_t n_roots_total;

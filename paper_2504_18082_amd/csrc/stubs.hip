@@ -1,8 +1,6 @@
 // Entry points not yet implemented (removed one by one as the kernels land).
 #include "cr_common.h"
 #define STUB { cr::set_error("not implemented yet"); return CR_ERR_UNSUPPORTED; }
-extern "C" cr_status cr_build_batches_workspace_bytes(int64_t, int32_t, size_t *) STUB
-extern "C" cr_status cr_build_batches(const cr_batch_cfg *, const int32_t *, int64_t, const int32_t *, int32_t, void *, size_t, int32_t *, int64_t *, void *) STUB
 extern "C" cr_status cr_sage_padded_dims(int32_t, int32_t, int32_t *, int32_t *) STUB
 extern "C" cr_status cr_sage_refresh_shadows(const cr_sage_layer *, void *) STUB
 extern "C" cr_status cr_sage_linear_fwd(const cr_sage_layer *, const int32_t *, int32_t, const uint16_t *, const uint16_t *, int64_t, int, float *, uint16_t *, void *) STUB
