@@ -1,0 +1,158 @@
+"""GPU parity: cr_sage_linear_fwd / _bwd (+SGD) and cr_softmax_xent against the oracle.
+
+The GPU feeds bf16 operands to the matrix cores and accumulates in float; the oracle is asked for the
+same operand rounding and accumulates in double.  Tolerance 2e-2 relative (bf16 path)."""
+import ctypes as C
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2504_18082_amd import synth
+from gpu_util import assert_close, bf16_tensor_to_float
+
+pytestmark = pytest.mark.gpu
+RTOL_BF16 = 2e-2
+RTOL_F32 = 1e-5
+
+
+@pytest.fixture(scope="module")
+def torch_mod():
+    import torch
+    assert torch.cuda.is_available()
+    return torch
+
+
+def to_bf16_dev(torch, x, ld):
+    """float array [M, F] -> device int16 [M, ld] of bf16 bits, zero padded."""
+    M, F = x.shape
+    buf = np.zeros((M, ld), dtype=np.uint16)
+    buf[:, :F] = synth.float_to_bf16_bits(x.astype(np.float32))
+    return torch.from_numpy(buf.view(np.int16)).cuda()
+
+
+def hdr_for(torch, n_rows):
+    h = torch.zeros(8, dtype=torch.int32, device="cuda")
+    h[0] = n_rows
+    return h
+
+
+@pytest.mark.parametrize("M,F_in,F_out,relu", [(300, 64, 64, True), (1000, 100, 256, True), (517, 256, 40, False),
+                                               (130, 602, 256, True), (64, 32, 10, False), (1, 64, 64, True)])
+def test_linear_fwd(torch_mod, M, F_in, F_out, relu):
+    torch = torch_mod
+    from paper_2504_18082_amd import binding as B
+    rng = np.random.default_rng(M + F_in)
+    print(f"case fwd M={M} F_in={F_in} F_out={F_out}", flush=True)
+    hs = rng.standard_normal((M, F_in)).astype(np.float32)
+    ag = rng.standard_normal((M, F_in)).astype(np.float32) * 0.5
+    W = (rng.standard_normal((2 * F_in, F_out)) / np.sqrt(2 * F_in)).astype(np.float32)
+    b = rng.standard_normal(F_out).astype(np.float32) * 0.1
+    want = oracle.sage_linear_fwd(hs, ag, W, b, relu, True)
+
+    layer = B.SageLayer(W, b)
+    layer.refresh()
+    cap = M + 37                                     # capacity above the live row count
+    ld_in = layer.F_pad
+    d_hs, d_ag = to_bf16_dev(torch, np.pad(hs, ((0, 37), (0, 0))), ld_in), to_bf16_dev(torch, np.pad(ag, ((0, 37), (0, 0))), ld_in)
+    out = torch.full((cap, layer.N_pad), np.nan, dtype=torch.float32, device="cuda")
+    out_b = torch.full((cap, layer.N_pad), 0x7FC0, dtype=torch.int16, device="cuda")
+    hdr = hdr_for(torch, M)
+    B.cr_sage_linear_fwd(layer, C.c_void_p(hdr.data_ptr()), cap, d_hs, d_ag, ld_in, relu, out, out_b)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert_close(got[:M, :F_out], want, RTOL_BF16, "out")
+    # far tighter in practice: only the accumulation differs
+    assert_close(got[:M, :F_out], want, 1e-4, "out (accumulation only)")
+    assert np.all(got[:M, F_out:] == 0) or not relu
+    assert np.all(np.isnan(got[M:]))                  # rows past the header's count untouched
+    gb = bf16_tensor_to_float(out_b)
+    assert_close(gb[:M, :F_out], want, RTOL_BF16, "out_bf16")
+
+
+@pytest.mark.parametrize("M,F_in,F_out,need_dx", [(300, 64, 64, True), (2500, 100, 256, False), (777, 256, 40, True),
+                                                  (200, 602, 256, False), (33, 32, 10, True)])
+def test_linear_bwd_and_sgd(torch_mod, M, F_in, F_out, need_dx):
+    torch = torch_mod
+    from paper_2504_18082_amd import binding as B
+    rng = np.random.default_rng(M * 3 + F_out)
+    print(f"case bwd M={M} F_in={F_in} F_out={F_out} need_dx={need_dx}", flush=True)
+    hs = rng.standard_normal((M, F_in)).astype(np.float32)
+    ag = rng.standard_normal((M, F_in)).astype(np.float32) * 0.5
+    W = (rng.standard_normal((2 * F_in, F_out)) / np.sqrt(2 * F_in)).astype(np.float32)
+    b = rng.standard_normal(F_out).astype(np.float32) * 0.1
+    dz = (rng.standard_normal((M, F_out)) / M).astype(np.float32)
+    dz[rng.random((M, F_out)) < 0.4] = 0.0            # as after a ReLU mask
+    # oracle: relu flag off, the mask is already in dz; `out` unused then
+    dW, db, d_self, d_agg = oracle.sage_linear_bwd(hs, ag, W, np.ones((M, F_out)), dz, False, True, need_dx=need_dx)
+    # db sums the bf16-rounded dz on the GPU (it reads the same operand as the matrix cores)
+    db = oracle.round_bf16(dz).sum(axis=0)
+    lr, wd = 0.05, 5e-4
+    W_new, b_new = oracle.sgd_step(W, dW, b, db, lr, wd)
+
+    layer = B.SageLayer(W, b)
+    layer.refresh()
+    cap = M + 100
+    ld_in = layer.F_pad
+    pad = lambda x: np.pad(x, ((0, 100), (0, 0)), constant_values=3.0)     # junk rows past the live count
+    d_hs, d_ag = to_bf16_dev(torch, pad(hs), ld_in), to_bf16_dev(torch, pad(ag), ld_in)
+    d_dz = to_bf16_dev(torch, pad(dz), layer.N_pad)
+    ws = torch.empty(B.cr_sage_linear_bwd_workspace_bytes(F_in, F_out, cap), dtype=torch.uint8, device="cuda")
+    g_self = torch.full((cap, layer.F_pad), np.nan, dtype=torch.float32, device="cuda") if need_dx else None
+    g_agg = torch.full((cap, layer.F_pad), np.nan, dtype=torch.float32, device="cuda") if need_dx else None
+    dW_out = torch.zeros((2 * F_in, F_out), dtype=torch.float32, device="cuda")
+    db_out = torch.zeros(F_out, dtype=torch.float32, device="cuda")
+    hdr = hdr_for(torch, M)
+    B.cr_sage_linear_bwd(layer, C.c_void_p(hdr.data_ptr()), cap, d_hs, d_ag, ld_in, d_dz, lr, wd, g_self, g_agg, ws, dW_out, db_out)
+    torch.cuda.synchronize()
+    assert_close(dW_out.cpu().numpy(), dW, RTOL_BF16, "dW")
+    assert_close(dW_out.cpu().numpy(), dW, 1e-4, "dW (accumulation only)")
+    assert_close(db_out.cpu().numpy(), db, 1e-4, "db")
+    assert_close(layer.W.cpu().numpy(), W_new, RTOL_F32, "W after SGD")
+    assert_close(layer.bias.cpu().numpy()[:F_out], b_new, RTOL_F32, "bias after SGD")
+    # shadows follow the master
+    wb = bf16_tensor_to_float(layer.W_bf16)
+    wt = bf16_tensor_to_float(layer.Wt_bf16)
+    Wn = layer.W.cpu().numpy()
+    Fp = layer.F_pad
+    for part in (0, 1):
+        blockW = wb[part * Fp:part * Fp + F_in, :F_out]
+        np.testing.assert_array_equal(blockW.astype(np.float64), oracle.round_bf16(Wn[part * F_in:(part + 1) * F_in]))
+        assert np.all(wb[part * Fp + F_in:(part + 1) * Fp] == 0)
+    assert np.all(wb[:, F_out:] == 0)
+    np.testing.assert_array_equal(wt, wb.T)
+    if need_dx:
+        assert_close(g_self.cpu().numpy()[:M, :F_in], d_self, RTOL_BF16, "d_self")
+        assert_close(g_agg.cpu().numpy()[:M, :F_in], d_agg, RTOL_BF16, "d_agg")
+        assert_close(g_self.cpu().numpy()[:M, :F_in], d_self, 1e-4, "d_self (accumulation only)")
+        assert np.all(g_self.cpu().numpy()[:M, F_in:] == 0)
+
+
+@pytest.mark.parametrize("n,Cn", [(256, 10), (1024, 40), (1000, 172), (1, 7)])
+def test_softmax_xent(torch_mod, n, Cn):
+    torch = torch_mod
+    from paper_2504_18082_amd import binding as B
+    rng = np.random.default_rng(n + Cn)
+    ld = (Cn + 63) // 64 * 64
+    logits = np.zeros((n + 5, ld), dtype=np.float32)
+    logits[:, :Cn] = rng.standard_normal((n + 5, Cn)).astype(np.float32) * 4
+    logits[:, Cn:] = 99.0                               # padded columns must be ignored
+    n_nodes = 5000
+    labels_all = rng.integers(0, Cn, size=n_nodes).astype(np.int32)
+    roots = rng.choice(n_nodes, size=n + 5, replace=False).astype(np.int32)
+    want_loss, want_d = oracle.softmax_xent(logits[:n].astype(np.float64), labels_all[roots[:n]], n_classes=Cn)
+    up = lambda a: torch.from_numpy(a).cuda()
+    d_roots = up(roots)
+    loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+    row_loss = torch.zeros(n + 5, dtype=torch.float32, device="cuda")
+    d = torch.full((n + 5, ld), np.nan, dtype=torch.float32, device="cuda")
+    db = torch.full((n + 5, ld), 0x7FC0, dtype=torch.int16, device="cuda")
+    hdr = hdr_for(torch, n)
+    B.cr_softmax_xent(C.c_void_p(hdr.data_ptr()), n + 5, up(logits), ld, Cn, up(labels_all), C.c_void_p(d_roots.data_ptr()),
+                      loss, row_loss, d, db)
+    torch.cuda.synchronize()
+    assert abs(float(loss.cpu()[0]) - want_loss) <= RTOL_F32 * max(1.0, abs(want_loss))
+    got = d.cpu().numpy()
+    assert_close(got[:n], want_d, RTOL_F32, "d_logits")
+    assert np.all(got[:n, Cn:] == 0) and np.all(np.isnan(got[n:]))
+    assert_close(bf16_tensor_to_float(db)[:n], want_d, 2.0 ** -8, "d_logits bf16")
