@@ -1,0 +1,166 @@
+"""Epoch driver: sequences the C-ABI calls of Algorithm 1 (root partitioning, grouped sub-graph
+sampling, then forward / loss / backward / SGD per mini-batch).  Call sequencing and buffer
+ownership only -- every arithmetic step runs inside libcommrand.so.
+"""
+from __future__ import annotations
+
+import ctypes as C
+from typing import List, Optional
+
+import numpy as np
+
+from . import binding as B
+from . import synth
+
+
+class Trainer:
+    def __init__(self, workload: synth.Workload, group_size: int = 16, lr: float = 0.01,
+                 weight_decay: float = 5e-4, seed: int = 0, device: str = "cuda", weights=None):
+        import torch
+        self.torch = torch
+        self.w = workload
+        cfg = workload.cfg
+        self.cfg = cfg
+        self.L = len(cfg.fanouts)
+        self.B = cfg.batch_size
+        self.G = group_size
+        self.lr, self.wd, self.seed = lr, weight_decay, seed
+        up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(device)
+        self.indptr = up(workload.indptr.astype(np.int64))
+        self.indices = up(workload.indices.astype(np.int32))
+        self.comm = up(workload.comm.astype(np.int32))
+        self.labels = up(workload.labels.astype(np.int32))
+        self.train_ids = up(workload.train_ids.astype(np.int32))
+        feats = workload.features
+        self.feat_dtype = B.CR_BF16 if feats.dtype == np.uint16 else B.CR_F32
+        self.table = up(feats.view(np.int16) if feats.dtype == np.uint16 else feats)
+        self.ld_table = feats.shape[1]
+        self.graph = B.make_graph(self.indptr, self.indices, self.comm, cfg.n_comm)
+        self.n_nodes = cfg.n_nodes
+        self.n_train = int(self.train_ids.numel())
+        self.n_batches = -(-self.n_train // self.B)
+
+        # parameters
+        weights = weights if weights is not None else synth.init_weights(cfg, seed)
+        self.layers: List[B.SageLayer] = [B.SageLayer(W, b, device) for (W, b) in weights]
+        for layer in self.layers:
+            layer.refresh()
+
+        # step 1
+        self.perm = torch.zeros(max(1, self.n_train), dtype=torch.int32, device=device)
+        self.ws_batches = torch.empty(B.cr_build_batches_workspace_bytes(self.n_train, cfg.n_comm), dtype=torch.uint8, device=device)
+
+        # step 2: block storage for one group of batches
+        scfg = B.make_sample_cfg(cfg.fanouts, 0.5, seed, 0)
+        self.blocks = B.alloc_block_sets(scfg, self.n_nodes, self.B, self.G, device)
+        self.ws_sample = torch.empty(B.cr_sample_blocks_workspace_bytes(scfg, self.n_nodes, self.B, self.G), dtype=torch.uint8, device=device)
+
+        # activations / gradients, sized by the per-batch capacities
+        f32 = lambda r, c: torch.zeros((r, c), dtype=torch.float32, device=device)
+        b16 = lambda r, c: torch.zeros((r, c), dtype=torch.int16, device=device)
+        self.self0 = b16(self.blocks[0].cap_dst, self.layers[0].F_pad)
+        self.agg = [b16(self.blocks[l].cap_dst, self.layers[l].F_pad if l == 0 else self.layers[l - 1].N_pad) for l in range(self.L)]
+        self.out = [f32(self.blocks[l].cap_dst, self.layers[l].N_pad) for l in range(self.L)]
+        self.out_b = [b16(self.blocks[l].cap_dst, self.layers[l].N_pad) if l < self.L - 1 else None for l in range(self.L)]
+        self.dz = [b16(self.blocks[l].cap_dst, self.layers[l].N_pad) for l in range(self.L)]
+        self.d_self = [f32(self.blocks[l].cap_dst, self.layers[l].F_pad) if l >= 1 else None for l in range(self.L)]
+        self.d_agg = [f32(self.blocks[l].cap_dst, self.layers[l].F_pad) if l >= 1 else None for l in range(self.L)]
+        self.ws_bwd = [torch.empty(B.cr_sage_linear_bwd_workspace_bytes(self.layers[l].F_in, self.layers[l].F_out, self.blocks[l].cap_dst),
+                                   dtype=torch.uint8, device=device) for l in range(self.L)]
+        self.loss = torch.zeros(1, dtype=torch.float32, device=device)
+        self.row_loss = torch.zeros(self.B, dtype=torch.float32, device=device)
+        self.gather0_events = []          # (start, stop) pairs around the layer-0 gather when timing is on
+        self.time_gather0 = False
+
+    # ------------------------------------------------------------------ step 1
+    def build_batches(self, policy: int, mix_count: int, epoch: int) -> int:
+        return B.cr_build_batches(policy, mix_count, self.B, self.seed, epoch, self.train_ids, self.comm, self.cfg.n_comm,
+                                  self.ws_batches, self.perm)
+
+    # ------------------------------------------------------------------ step 2
+    def sample_group(self, first_batch: int, n_batches: int, p_intra: float, epoch: int, flags: int = 0):
+        """Samples mini-batches first_batch .. first_batch+n_batches-1 of the current permutation."""
+        assert 1 <= n_batches <= self.G
+        scfg = B.make_sample_cfg(self.cfg.fanouts, p_intra, self.seed, epoch, first_batch, flags)
+        start = first_batch * self.B
+        n_roots = min(self.n_train, start + n_batches * self.B) - start
+        roots = C.c_void_p(self.perm.data_ptr() + 4 * start)
+        layers = self.blocks
+        if n_batches != self.G:           # a short last group: same storage, fewer batches
+            layers = [_view_block_set(b, n_batches) for b in self.blocks]
+        arr = (B.cr_block_set * self.L)(*[b.c for b in layers])
+        B._check(B.lib().cr_sample_blocks(C.byref(self.graph), C.byref(scfg), roots, n_roots, self.B, n_batches,
+                                          B._ptr(self.ws_sample), self.ws_sample.numel(), arr, B._stream()))
+
+    # ------------------------------------------------------------------ training on one sub-graph
+    def train_batch(self, g: int, dW_out=None, db_out=None):
+        L, blocks, layers = self.L, self.blocks, self.layers
+        # forward
+        for l in range(L):
+            blk, lay = blocks[l], layers[l]
+            if l == 0:
+                if self.time_gather0:
+                    ev0, ev1 = self.torch.cuda.Event(enable_timing=True), self.torch.cuda.Event(enable_timing=True)
+                    ev0.record()
+                B.cr_gather_aggregate_fwd(blk, g, self.table, self.feat_dtype, self.ld_table, self.cfg.n_feat, True,
+                                          None, self.agg[0], self.self0, lay.F_pad)
+                if self.time_gather0:
+                    ev1.record()
+                    self.gather0_events.append((ev0, ev1))
+                h_self, ld_in = self.self0, lay.F_pad
+            else:
+                prev = layers[l - 1]
+                B.cr_gather_aggregate_fwd(blk, g, self.out[l - 1], B.CR_F32, prev.N_pad, prev.F_out, False,
+                                          None, self.agg[l], None, prev.N_pad)
+                h_self, ld_in = self.out_b[l - 1], prev.N_pad
+            B.cr_sage_linear_fwd(lay, blk.hdr_ptr(g), blk.cap_dst, h_self, self.agg[l], ld_in, l < L - 1,
+                                 self.out[l], self.out_b[l])
+        # loss on the roots
+        top = blocks[L - 1]
+        B.cr_softmax_xent(top.hdr_ptr(g), top.cap_dst, self.out[L - 1], layers[L - 1].N_pad, self.cfg.n_classes,
+                          self.labels, top.src_ids_ptr(g), self.loss, self.row_loss, None, self.dz[L - 1])
+        # backward + SGD
+        for l in range(L - 1, -1, -1):
+            blk, lay = blocks[l], layers[l]
+            if l == 0:
+                h_self, ld_in = self.self0, lay.F_pad
+            else:
+                h_self, ld_in = self.out_b[l - 1], layers[l - 1].N_pad
+            B.cr_sage_linear_bwd(lay, blk.hdr_ptr(g), blk.cap_dst, h_self, self.agg[l], ld_in, self.dz[l], self.lr, self.wd,
+                                 self.d_self[l], self.d_agg[l], self.ws_bwd[l],
+                                 None if dW_out is None else dW_out[l], None if db_out is None else db_out[l])
+            if l >= 1:
+                prev = layers[l - 1]
+                B.cr_gather_aggregate_bwd(blk, g, self.d_agg[l], self.d_self[l], lay.F_pad, lay.F_in, self.out[l - 1],
+                                          prev.N_pad, None, self.dz[l - 1], prev.N_pad)
+
+    # ------------------------------------------------------------------ one epoch
+    def run_epoch(self, policy: int, mix_count: int, p_intra: float, epoch: int, max_batches: Optional[int] = None):
+        nb = self.build_batches(policy, mix_count, epoch)
+        if max_batches is not None:
+            nb = min(nb, max_batches)
+        done = 0
+        while done < nb:
+            n = min(self.G, nb - done)
+            self.sample_group(done, n, p_intra, epoch)
+            for g in range(n):
+                self.train_batch(g)
+            done += n
+        return nb
+
+    def headers(self):
+        """Host copy of the current group's block headers: [layer][batch] -> (n_dst, n_src, nnz, status)."""
+        return [b.hdr.cpu().numpy()[:, :4].copy() for b in self.blocks]
+
+
+class _BlockSetView:
+    """A block set restricted to its first n batches (same device storage)."""
+
+    def __init__(self, c):
+        self.c = c
+
+
+def _view_block_set(b: B.BlockSet, n_batches: int) -> _BlockSetView:
+    c = B.cr_block_set(n_batches, b.fanout, b.cap_dst, b.cap_src, b.cap_nnz, 0, B._ptr(b.hdr), B._ptr(b.src_ids),
+                       B._ptr(b.indptr), B._ptr(b.indices), B._ptr(b.t_indptr), B._ptr(b.t_indices))
+    return _BlockSetView(c)

@@ -1,0 +1,37 @@
+"""One training step of the L-layer GraphSAGE-mean model written with the oracle's pieces only
+(test infrastructure; mirrors the precision points of the GPU path: bf16 operands into every
+contraction, float hidden activations into the next aggregation)."""
+import numpy as np
+
+import oracle
+
+
+def oracle_train_step(graph, table, n_feat, labels, roots, fanouts, p, seed, epoch, batch, params, lr, wd,
+                      pos_map=None, strict=False):
+    """params: list of (W float64 [2F_in, F_out], b float64 [F_out]); returns dict with loss, logits,
+    grads and the updated params (inputs are not modified)."""
+    L = len(fanouts)
+    blocks = oracle.sample_blocks(graph, roots, fanouts, p, strict, seed, epoch, batch, pos_map)
+    h_self, aggs, outs = [None] * L, [None] * L, [None] * L
+    for l in range(L):
+        blk = blocks[l]
+        W, b = params[l]
+        if l == 0:
+            aggs[0], h_self[0] = oracle.gather_mean(blk, table, indirect=True, F=n_feat, want_self=True)
+        else:
+            prev = np.ascontiguousarray(outs[l - 1].astype(np.float32))       # the GPU aggregates float activations
+            aggs[l] = oracle.gather_mean(blk, prev, indirect=False)
+            h_self[l] = outs[l - 1][:blk.n_dst]
+        outs[l] = oracle.sage_linear_fwd(h_self[l], aggs[l], W, b, l < L - 1, True)
+    loss, dz = oracle.softmax_xent(outs[L - 1], labels[np.asarray(roots)])
+    grads, new_params = [None] * L, [None] * L
+    for l in range(L - 1, -1, -1):
+        W, b = params[l]
+        dW, db, d_self, d_agg = oracle.sage_linear_bwd(h_self[l], aggs[l], W, outs[l], dz, False, True, need_dx=l > 0)
+        db = oracle.round_bf16(dz).sum(axis=0)          # the GPU sums the operand it feeds the matrix cores
+        grads[l] = (dW, db)
+        new_params[l] = oracle.sgd_step(W, dW, b, db, lr, wd)
+        if l > 0:
+            d_src = oracle.gather_mean_bwd(blocks[l], d_agg, d_self)
+            dz = d_src * (outs[l - 1] > 0)
+    return dict(blocks=blocks, loss=loss, logits=outs[L - 1], outs=outs, grads=grads, params=new_params)

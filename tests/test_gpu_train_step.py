@@ -1,0 +1,98 @@
+"""GPU parity of the whole hot path: batches -> grouped sampling -> forward -> loss -> backward -> SGD,
+three consecutive mini-batches, against the same steps taken with the oracle."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2504_18082_amd import synth
+from gpu_util import assert_close
+from oracle_step import oracle_train_step
+
+pytestmark = pytest.mark.gpu
+RTOL_BF16 = 2e-2
+
+
+def run_case(w, policy, mix, p, n_steps, group, lr=0.05, wd=5e-4, seed=0, epoch=3):
+    import torch
+    from paper_2504_18082_amd.trainer import Trainer
+    cfg = w.cfg
+    weights = synth.init_weights(cfg, seed)
+    tr = Trainer(w, group_size=group, lr=lr, weight_decay=wd, seed=seed, weights=weights)
+    nb = tr.build_batches(policy, mix, epoch)
+    perm = tr.perm.cpu().numpy()
+    want_perm = oracle.build_batches(policy, mix, seed, epoch, w.train_ids, w.comm, cfg.n_comm)
+    assert np.array_equal(perm, want_perm)
+    params = [(W.astype(np.float64), b.astype(np.float64)) for W, b in weights]
+    pos = np.full(cfg.n_nodes, -1, dtype=np.int32)
+    dW_out = [torch.zeros_like(l.W) for l in tr.layers]
+    db_out = [torch.zeros(l.F_out, dtype=torch.float32, device="cuda") for l in tr.layers]
+    done = 0
+    while done < n_steps:
+        n = min(group, n_steps - done)
+        tr.sample_group(done, n, p, epoch)
+        for g in range(n):
+            b = done + g
+            print(f"step batch={b} policy={policy} p={p}", flush=True)
+            tr.train_batch(g, dW_out, db_out)
+            torch.cuda.synchronize()
+            roots = want_perm[b * cfg.batch_size:(b + 1) * cfg.batch_size]
+            ref = oracle_train_step(w.graph, w.features, cfg.n_feat, w.labels, roots, cfg.fanouts, p, seed, epoch, b,
+                                    params, lr, wd, pos)
+            hdrs = tr.headers()
+            for l in range(tr.L):
+                assert hdrs[l][g].tolist() == [ref["blocks"][l].n_dst, ref["blocks"][l].n_src, ref["blocks"][l].nnz, 0]
+            assert abs(float(tr.loss.cpu()[0]) - ref["loss"]) <= RTOL_BF16 * abs(ref["loss"])
+            assert abs(float(tr.loss.cpu()[0]) - ref["loss"]) <= 1e-3 * abs(ref["loss"])       # in practice far tighter
+            n_roots = len(roots)
+            logits = tr.out[tr.L - 1].cpu().numpy()[:n_roots, :cfg.n_classes]
+            assert_close(logits, ref["logits"], RTOL_BF16, f"logits batch {b}")
+            for l in range(tr.L):
+                assert_close(dW_out[l].cpu().numpy(), ref["grads"][l][0], RTOL_BF16, f"dW layer {l} batch {b}")
+                assert_close(db_out[l].cpu().numpy(), ref["grads"][l][1], RTOL_BF16, f"db layer {l} batch {b}")
+                assert_close(tr.layers[l].W.cpu().numpy(), ref["params"][l][0], RTOL_BF16, f"W layer {l} batch {b}")
+            # keep the two trajectories on the same weights: continue the oracle from the GPU's master copy
+            params = [(l.W.cpu().numpy().astype(np.float64), l.bias.cpu().numpy()[:l.F_out].astype(np.float64)) for l in tr.layers]
+        done += n
+    return tr
+
+
+def test_tiny_three_steps_mid_knobs(tiny_workload):
+    run_case(tiny_workload, oracle.COMM_RAND, 6, 0.9, n_steps=3, group=2)
+
+
+def test_tiny_fully_random_and_fully_community(tiny_workload):
+    run_case(tiny_workload, oracle.RAND, 1, 0.5, n_steps=1, group=1)
+    run_case(tiny_workload, oracle.NORAND, 1, 1.0, n_steps=2, group=4)
+
+
+def test_last_short_batch(tiny_workload):
+    # the tiny training set leaves a short last batch; train on it alone
+    import torch
+    from paper_2504_18082_amd.trainer import Trainer
+    w = tiny_workload
+    cfg = w.cfg
+    weights = synth.init_weights(cfg, 0)
+    tr = Trainer(w, group_size=3, lr=0.05, seed=0, weights=weights)
+    nb = tr.build_batches(oracle.COMM_RAND, 1, 0)
+    last = nb - 1
+    n_last = len(w.train_ids) - last * cfg.batch_size
+    assert 0 < n_last < cfg.batch_size
+    tr.sample_group(last - 1, 2, 0.9, 0)          # group = {full batch, short batch}
+    tr.train_batch(1)
+    torch.cuda.synchronize()
+    perm = tr.perm.cpu().numpy()
+    params = [(W.astype(np.float64), b.astype(np.float64)) for W, b in weights]
+    ref = oracle_train_step(w.graph, w.features, cfg.n_feat, w.labels, perm[last * cfg.batch_size:], cfg.fanouts, 0.9, 0, 0, last,
+                            params, 0.05, 5e-4)
+    assert tr.headers()[tr.L - 1][1][0] == n_last
+    assert abs(float(tr.loss.cpu()[0]) - ref["loss"]) <= 1e-3 * abs(ref["loss"])
+    for l in range(tr.L):
+        assert_close(tr.layers[l].W.cpu().numpy(), ref["params"][l][0], RTOL_BF16, f"W layer {l}")
+
+
+def test_arxiv_one_step_three_layers(arxiv_workload):
+    # 3 layers, hidden 256, batch 1024: ~60K rows at layer 0 (oracle: a few seconds)
+    import copy
+    w = copy.copy(arxiv_workload)
+    tr = run_case(w, oracle.COMM_RAND, 62, 1.0, n_steps=1, group=2, lr=0.01)
+    assert tr.L == 3
