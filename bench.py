@@ -1,0 +1,208 @@
+#!/usr/bin/env python3
+"""Benchmark of the COMM-RAND hot path on one MI355X.
+
+A step is one mini-batch through the whole path: (root partitioning once per epoch,) grouped
+sub-graph sampling, feature gather + mean aggregation, SAGE projections on the matrix cores, loss,
+backward and SGD.  Inputs (graph, feature table, labels, weights) are resident in HBM before the
+timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload arxiv|tiny|reddit|products]
+                    [--group G] [--no-sweep] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+METRIC = "epoch time + gathered-feature GB/s (% HBM peak) vs randomness knob, 1 MI355X"
+
+
+def gather0_bytes(hdr0, n_feat, elem_bytes, f_pad):
+    """Algorithmic bytes of one layer-0 gather/aggregate launch: every gathered row (neighbours and
+    the destination's own row) once, 8 bytes of index per edge (local index + frontier id), the row
+    pointers, and the two bf16 outputs (self rows, aggregated rows)."""
+    n_dst, n_src, nnz = int(hdr0[0]), int(hdr0[1]), int(hdr0[2])
+    reads = (nnz + n_dst) * n_feat * elem_bytes + 8 * nnz + 4 * n_dst + 4 * (n_dst + 1)
+    writes = 2 * n_dst * f_pad * 2
+    return reads + writes, (nnz + n_dst) * n_feat * elem_bytes
+
+
+def run_setting(tr, policy, mix, p, steps, warmup, epoch0):
+    """Times `steps` steps (after `warmup` untimed ones) of one knob setting."""
+    import torch
+    from paper_2504_18082_amd import binding as B
+    G = tr.G
+    stats = dict(gather_bytes=0, feat_bytes=0, n_src0=0, rows0=0, launches=0)
+
+    def run(n_steps, epoch, timed):
+        # one "epoch" = build the permutation, then walk the batches group by group
+        done = 0
+        tr.build_batches(policy, mix, epoch)
+        while done < n_steps:
+            b = done % tr.n_batches
+            if b == 0 and done > 0:
+                epoch += 1
+                tr.build_batches(policy, mix, epoch)
+            n = min(G, n_steps - done, tr.n_batches - b)
+            tr.sample_group(b, n, p, epoch)
+            for g in range(n):
+                tr.train_batch(g)
+            if timed:
+                hdrs.append((n, tr.blocks[0].hdr.clone()))
+            done += n
+        return epoch
+
+    hdrs = []
+    tr.time_gather0 = False
+    run(warmup, epoch0, False)
+    torch.cuda.synchronize()
+    tr.time_gather0 = True
+    tr.gather0_events = []
+    t0 = time.perf_counter()
+    run(steps, epoch0 + 1000, True)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    tr.time_gather0 = False
+    gather_ms = sum(a.elapsed_time(b) for a, b in tr.gather0_events)
+    elem = 2 if tr.feat_dtype == B.CR_BF16 else 4
+    for n, h in hdrs:
+        h = h.cpu().numpy()
+        for g in range(n):
+            tot, feat = gather0_bytes(h[g], tr.cfg.n_feat, elem, tr.layers[0].F_pad)
+            stats["gather_bytes"] += tot
+            stats["feat_bytes"] += feat
+            stats["n_src0"] += int(h[g][1])
+            stats["rows0"] += int(h[g][2]) + int(h[g][0])
+            stats["launches"] += 1
+    return dict(ms_per_step=dt * 1e3 / steps, total_s=dt, gather_ms_per_launch=gather_ms / max(1, stats["launches"]),
+                gather_bytes_per_launch=stats["gather_bytes"] / max(1, stats["launches"]),
+                feat_bytes_per_step=stats["feat_bytes"] / max(1, stats["launches"]),
+                unique_row_ratio=stats["n_src0"] / max(1, stats["rows0"]),
+                mean_input_nodes=stats["n_src0"] / max(1, stats["launches"]))
+
+
+def cpu_baseline(w, n_batches_sample, seed):
+    """The oracle, as it stands, single thread, on the first batches of a fully random epoch."""
+    import oracle
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from oracle_step import oracle_train_step
+    from paper_2504_18082_amd import synth
+    cfg = w.cfg
+    params = [(W.astype(np.float64), b.astype(np.float64)) for W, b in synth.init_weights(cfg, seed)]
+    pos = np.full(cfg.n_nodes, -1, dtype=np.int32)
+    elem = 2 if w.features.dtype == np.uint16 else 4
+    t0 = time.perf_counter()
+    perm = oracle.build_batches(oracle.RAND, 1, seed, 0, w.train_ids, w.comm, cfg.n_comm)
+    feat_bytes = 0
+    for b in range(n_batches_sample):
+        roots = perm[b * cfg.batch_size:(b + 1) * cfg.batch_size]
+        ref = oracle_train_step(w.graph, w.features, cfg.n_feat, w.labels, roots, cfg.fanouts, 0.5, seed, 0, b, params, 0.01, 5e-4, pos)
+        params = ref["params"]
+        feat_bytes += (ref["blocks"][0].nnz + ref["blocks"][0].n_dst) * cfg.n_feat * elem
+    dt = time.perf_counter() - t0
+    return dict(value=feat_bytes / dt / 1e9, unit="GB/s", cores=1, kind="oracle",
+                sample=f"{n_batches_sample} mini-batch(es) of the same workload, whole path (RAND roots, p=0.5), "
+                       f"{dt:.1f} s; {dt * 1e3 / n_batches_sample:.0f} ms per step",
+                ms_per_step=dt * 1e3 / n_batches_sample)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--workload", default="arxiv")
+    ap.add_argument("--group", type=int, default=16)
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-sweep", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-batches", type=int, default=1)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (the whole graph and feature table are resident in one "
+              "MI355X's HBM; no collectives are part of it). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2504_18082_amd import binding as B
+    from paper_2504_18082_amd import synth
+    from paper_2504_18082_amd.trainer import Trainer
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    B.lib()                                   # fail loudly if the HIP library was not built
+
+    w = synth.make_workload(args.workload, seed=args.seed)
+    cfg = w.cfg
+    tr = Trainer(w, group_size=args.group, lr=0.01, weight_decay=5e-4, seed=args.seed)
+    steps = args.steps if args.steps is not None else tr.n_batches          # default: one epoch
+    c_train = int(len(np.unique(w.comm[w.train_ids])))
+    mix_mid = B.cr_mix_count_from_percent(12.5, c_train)
+
+    # headline: the fully random setting (RAND-ROOTS, p = 0.5), the paper's baseline
+    main_res = run_setting(tr, B.CR_ROOTS_RAND, 1, 0.5, steps, args.warmup, 0)
+    sweep = []
+    if not args.no_sweep:
+        for name, policy, mix, p in (("mid: COMM-RAND-MIX-12.5% p=1.0", B.CR_ROOTS_COMM_RAND, mix_mid, 1.0),
+                                     ("fully community: NORAND-ROOTS p=1.0", B.CR_ROOTS_NORAND, 1, 1.0)):
+            r = run_setting(tr, policy, mix, p, steps, min(args.warmup, 4), 50)
+            sweep.append(dict(setting=name, ms_per_step=round(r["ms_per_step"], 4),
+                              epoch_ms=round(r["ms_per_step"] * tr.n_batches, 3),
+                              speedup_vs_random=round(main_res["ms_per_step"] / r["ms_per_step"], 3),
+                              gather_GBps=round(r["gather_bytes_per_launch"] / r["gather_ms_per_launch"] / 1e6, 1),
+                              gather_us=round(r["gather_ms_per_launch"] * 1e3, 2),
+                              mean_input_nodes=round(r["mean_input_nodes"], 1),
+                              unique_row_ratio=round(r["unique_row_ratio"], 4)))
+
+    achieved = main_res["gather_bytes_per_launch"] / main_res["gather_ms_per_launch"] / 1e6      # GB/s
+    value = main_res["feat_bytes_per_step"] / main_res["ms_per_step"] / 1e6                        # GB/s over the whole step
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"gather_fwd_{args.workload}_hbm_traffic.txt")
+    if os.path.exists(tpath):
+        for line in open(tpath):
+            if line.startswith("traffic_bytes_per_launch"):
+                traffic = float(line.split("=")[1])
+    out = {
+        "metric": METRIC,
+        "value": round(value, 3),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(main_res["ms_per_step"], 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16" if cfg.feat_dtype == "bf16" else "f32 gather / bf16 MFMA",
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {cfg.n_nodes} nodes, {len(w.indices)} CSR entries, {cfg.n_feat}-d {cfg.feat_dtype} "
+                               f"features, {len(cfg.fanouts)}-layer GraphSAGE-mean hidden {cfg.hidden}, fanout {cfg.fanouts}, "
+                               f"batch {cfg.batch_size}, {tr.n_batches} batches/epoch",
+                   "setting": "fully random: RAND-ROOTS p=0.5", "group_size": args.group,
+                   "value_definition": "layer-0 gathered feature bytes per second of whole-step time"},
+        "epoch_ms": round(main_res["ms_per_step"] * tr.n_batches, 3),
+        "mean_input_nodes": round(main_res["mean_input_nodes"], 1),
+        "unique_row_ratio": round(main_res["unique_row_ratio"], 4),
+        "roofline": {"bound": "hbm", "kernel": "gather_mean_fwd_kernel (layer 0)", "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                     "traffic": traffic, "bytes_per_launch": round(main_res["gather_bytes_per_launch"]),
+                     "us_per_launch": round(main_res["gather_ms_per_launch"] * 1e3, 2)},
+        "sweep": sweep,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, args.cpu_batches, args.seed)
+        out["cpu_baseline"]["value"] = round(out["cpu_baseline"]["value"], 5)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
