@@ -126,6 +126,8 @@ def main():
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-batches", type=int, default=1)
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy (for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (the whole graph and feature table are resident in one "
@@ -147,6 +149,14 @@ def main():
     steps = args.steps if args.steps is not None else tr.n_batches          # default: one epoch
     c_train = int(len(np.unique(w.comm[w.train_ids])))
     mix_mid = B.cr_mix_count_from_percent(12.5, c_train)
+
+    if args.calibration_copy:
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")       # 256 MiB read + 256 MiB written
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # headline: the fully random setting (RAND-ROOTS, p = 0.5), the paper's baseline
     main_res = run_setting(tr, B.CR_ROOTS_RAND, 1, 0.5, steps, args.warmup, 0)
