@@ -127,35 +127,52 @@ __device__ __forceinline__ int block_exclusive_scan_1024(int x, int *lds /*[17]*
     }
     if (lane == WAVE - 1) lds[wave] = incl;
     __syncthreads();
-    if (threadIdx.x == 0) {
-        int run = 0;
-        for (int w = 0; w < 16; ++w) { const int t = lds[w]; lds[w] = run; run += t; }
-        lds[16] = run;
+    if (wave == 0) {
+        const int t = lane < 16 ? lds[lane] : 0;
+        int inc = t;
+#pragma unroll
+        for (int off = 1; off < 16; off <<= 1) {
+            const int y = __shfl_up(inc, off);
+            if (lane >= off) inc += y;
+        }
+        if (lane < 16) lds[lane] = inc - t;
+        if (lane == 15) lds[16] = inc;
     }
     __syncthreads();
     total = lds[16];
     return lds[wave] + incl - x;
 }
 
-// out[0..n] = exclusive prefix sums of in[0..n) (out[n] = total).  Each thread owns one contiguous chunk.
+// out[0..n] = exclusive prefix sums of in[0..n) (out[n] = total), by one workgroup of 1024 threads.
+// The input is walked in super-tiles of 1024 x 16 elements; a thread owns 16 consecutive elements of
+// a super-tile and issues all of its loads before the first add.
 __device__ __forceinline__ int scan_chunked(const int32_t *in, int32_t *out, int32_t *out_copy, int n, int *lds)
 {
-    const int chunk = (n + 1023) / 1024;
-    const int start = threadIdx.x * chunk;
-    const int stop = min(n, start + chunk);
-    int sum = 0;
-    for (int i = start; i < stop; ++i) sum += in[i];
-    int total;
-    int run = block_exclusive_scan_1024(sum, lds, total);
-    for (int i = start; i < stop; ++i) {
-        const int x = in[i];
-        out[i] = run;
-        if (out_copy) out_copy[i] = run;
-        run += x;
+    constexpr int ITEMS = 16;
+    int carry = 0;
+    for (int tile0 = 0; tile0 < n; tile0 += 1024 * ITEMS) {
+        const int start = tile0 + threadIdx.x * ITEMS;
+        int x[ITEMS];
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) x[i] = start + i < n ? in[start + i] : 0;
+        int sum = 0;
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) sum += x[i];
+        int total;
+        int run = carry + block_exclusive_scan_1024(sum, lds, total);
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            if (start + i < n) {
+                out[start + i] = run;
+                if (out_copy) out_copy[start + i] = run;
+            }
+            run += x[i];
+        }
+        carry += total;
+        __syncthreads();      // lds is reused by the next super-tile
     }
-    if (threadIdx.x == 0) out[n] = total;
-    return total;
+    if (threadIdx.x == 0) out[n] = carry;
+    return carry;
 }
-
 
 }  // namespace cr

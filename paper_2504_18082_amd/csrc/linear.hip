@@ -226,8 +226,15 @@ __global__ __launch_bounds__(256) void sgd_reduce_kernel(SgdArgs a)
     const int k2 = (int)(idx / a.N_pad), n = (int)(idx % a.N_pad);
     const int kin = k2 % a.F_pad, part = k2 / a.F_pad;
     if (kin < a.F_in && n < a.F_out) {
-        float g = 0.f;
-        for (int s = 0; s < active; ++s) g += a.partial[((int64_t)s * K2 + k2) * a.N_pad + n];
+        float g4[4] = {0.f, 0.f, 0.f, 0.f};     // fixed association: split s goes to accumulator s % 4
+        const float *pp = a.partial + (int64_t)k2 * a.N_pad + n;
+        const int64_t ps = (int64_t)K2 * a.N_pad;
+        for (int s = 0; s < active; s += 4) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (s + i < active) g4[i] += pp[(int64_t)(s + i) * ps];
+        }
+        const float g = (g4[0] + g4[1]) + (g4[2] + g4[3]);
         const int64_t wi = (int64_t)(part * a.F_in + kin) * a.F_out + n;
         float w = a.W[wi];
         if (a.dW_out) a.dW_out[wi] = g;

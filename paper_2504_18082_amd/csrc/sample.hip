@@ -28,11 +28,6 @@ __device__ __forceinline__ uint32_t exp_clock_q24(uint32_t r)
     return ((uint32_t)(33 - t) << 24) - frac;
 }
 
-__device__ __forceinline__ bool less2(uint64_t ka, uint32_t sa, uint64_t kb, uint32_t sb)
-{
-    return ka < kb || (ka == kb && sa < sb);
-}
-
 struct SelectArgs {
     const int64_t *g_indptr;
     const int32_t *g_indices;
@@ -59,9 +54,23 @@ __device__ __forceinline__ int group_n_dst(const int32_t *prev_hdr, int g, int64
     return (int)(left < 0 ? 0 : (left > batch_size ? batch_size : left));
 }
 
-// One wave per destination row.  Lane c < fanout holds one candidate (key, slot); the row is
-// streamed in chunks of 64 slots and a slot replaces the current worst candidate when its
-// (key, slot) pair is smaller.  Every pair is distinct, so the surviving set is unique.
+__device__ __forceinline__ uint32_t rl32(uint32_t v, int lane) { return (uint32_t)__builtin_amdgcn_readlane((int)v, lane); }
+__device__ __forceinline__ uint64_t rl64(uint64_t v, int lane)
+{
+    return ((uint64_t)rl32((uint32_t)(v >> 32), lane) << 32) | rl32((uint32_t)v, lane);
+}
+__device__ __forceinline__ uint32_t push32(uint32_t v, int dst_lane) { return (uint32_t)__builtin_amdgcn_ds_permute(dst_lane << 2, (int)v); }
+__device__ __forceinline__ uint64_t push64(uint64_t v, int dst_lane)
+{
+    return ((uint64_t)push32((uint32_t)(v >> 32), dst_lane) << 32) | push32((uint32_t)v, dst_lane);
+}
+
+// One wave per destination row.  A slot's ordering value is the pair (key, slot); with WIDE == false
+// (p = 0.5, 32-bit keys) the pair is packed into one 64-bit word.  Lanes 0..k-1 hold the k smallest
+// pairs seen so far in ascending order: the first 64 slots are ranked by counting and permuted into
+// place, later chunks of 64 slots are tested against the k-th pair and inserted by shifting.  Every
+// pair is distinct, so the surviving set is unique.
+template <bool WIDE>
 __global__ __launch_bounds__(256) void select_kernel(SelectArgs a)
 {
     const int g = blockIdx.y;
@@ -74,79 +83,108 @@ __global__ __launch_bounds__(256) void select_kernel(SelectArgs a)
     const int64_t base = a.g_indptr[v];
     const int64_t deg64 = a.g_indptr[v + 1] - base;
     const int deg = (int)(deg64 > 0x7FFFFFFF ? 0x7FFFFFFF : deg64);
-    const int k = deg < f ? deg : f;
-    const bool need_class = a.q_in != a.q_out;
-    const int32_t cv = need_class ? a.comm[v] : 0;
-    const uint32_t batch = a.first_batch + (uint32_t)g;
+    const int32_t cv = WIDE ? a.comm[v] : 0;
+    int32_t *sel_row = a.sel + (int64_t)g * a.sel_stride + (int64_t)row * f;
+    const uint64_t lt_mask = (1ull << lane) - 1ull;
 
-    auto key_of = [&](int j, int32_t &u_out) -> uint64_t {
+    if (deg <= f) {   // every neighbour is taken (minus inter-community ones in strict mode): no keys needed
+        int32_t u = 0;
+        bool valid = lane < deg;
+        if (valid) {
+            u = a.g_indices[base + lane];
+            if (WIDE && a.strict_p1) valid = a.comm[u] == cv;
+        }
+        const uint64_t vmask = __ballot(valid);
+        if (valid) sel_row[__popcll(vmask & lt_mask)] = u;
+        if (lane == 0) a.cnt[(int64_t)g * a.cnt_stride + row] = __popcll(vmask);
+        return;
+    }
+
+    const int k = f;
+    const uint32_t batch = a.first_batch + (uint32_t)g;
+    // ordering pair of slot j: (ck, cs); narrow mode packs (word << 32 | slot) into ck
+    auto key_of = [&](int j, int32_t &u_out, uint64_t &ck, uint32_t &cs) {
         const int32_t u = a.g_indices[base + j];
         u_out = u;
         const u32x4 w = philox4x32_10((uint32_t)j >> 2, (uint32_t)v, batch, a.ctr3, a.seed_lo, a.seed_hi);
-        const uint32_t sel = (uint32_t)j & 3u;
-        const uint32_t r = sel == 0 ? w.x : (sel == 1 ? w.y : (sel == 2 ? w.z : w.w));
-        if (!need_class) return (uint64_t)r;
-        const bool intra = a.comm[u] == cv;
-        if (a.q_out == 0) return (intra ? 0ull : (1ull << 62)) + (uint64_t)r;
-        return (uint64_t)exp_clock_q24(r) * (uint64_t)(intra ? a.q_out : a.q_in);
+        const uint32_t pick = (uint32_t)j & 3u;
+        const uint32_t r = pick == 0 ? w.x : (pick == 1 ? w.y : (pick == 2 ? w.z : w.w));
+        if (!WIDE) {
+            ck = ((uint64_t)r << 32) | (uint32_t)j;
+            cs = 0;
+        } else {
+            const bool intra = a.comm[u] == cv;
+            if (a.q_out == 0) ck = (intra ? 0ull : (1ull << 62)) + (uint64_t)r;
+            else ck = (uint64_t)exp_clock_q24(r) * (uint64_t)(intra ? a.q_out : a.q_in);
+            cs = (uint32_t)j;
+        }
+    };
+    auto less = [&](uint64_t ka, uint32_t sa, uint64_t kb, uint32_t sb) -> bool {
+        if (!WIDE) return ka < kb;
+        return ka < kb || (ka == kb && sa < sb);
     };
 
-    uint64_t ckey = 0;       // lanes >= k stay at the minimum so they never become the worst candidate
-    uint32_t cslot = 0;
-    int32_t cu = 0;          // global id of the candidate's neighbour
-    if (lane < k) {
-        ckey = key_of(lane, cu);
-        cslot = (uint32_t)lane;
+    // first chunk: rank the first min(deg, 64) slots by counting, then move rank r to lane r
+    uint64_t ck = KEY_MAX;
+    uint32_t cs = 0xFFFFFFFFu;
+    int32_t cu = 0;
+    const int n0 = deg < WAVE ? deg : WAVE;
+    if (lane < n0) key_of(lane, cu, ck, cs);
+    {
+        int rank = 0;
+        for (int j = 0; j < n0; ++j) {
+            const uint64_t kj = rl64(ck, j);
+            const uint32_t sj = WIDE ? rl32(cs, j) : 0u;
+            rank += less(kj, sj, ck, cs) ? 1 : 0;
+        }
+        if (lane >= n0) rank = lane;
+        ck = push64(ck, rank);
+        if (WIDE) cs = push32(cs, rank);
+        cu = (int32_t)push32((uint32_t)cu, rank);
     }
 
-    if (deg > f) {
-        uint64_t tkey;
-        uint32_t tslot;
-        int tlane;
-        auto worst = [&]() {
-            uint64_t mk = ckey;
-            uint32_t ms = cslot;
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) {
-                const uint64_t ok = __shfl_xor(mk, off);
-                const uint32_t os = __shfl_xor(ms, off);
-                if (less2(mk, ms, ok, os)) { mk = ok; ms = os; }
-            }
-            tkey = mk;
-            tslot = ms;
-            const uint64_t hit = __ballot(lane < k && ckey == mk && cslot == ms);
-            tlane = __ffsll((long long)hit) - 1;
-        };
-        worst();
-        for (int j0 = k; j0 < deg; j0 += WAVE) {
+    // later chunks
+    if (deg > WAVE) {
+        uint64_t tk = rl64(ck, k - 1);
+        uint32_t ts = WIDE ? rl32(cs, k - 1) : 0u;
+        for (int j0 = WAVE; j0 < deg; j0 += WAVE) {
             const int j = j0 + lane;
-            uint64_t key = KEY_MAX;
-            int32_t u = 0;
-            if (j < deg) key = key_of(j, u);
-            uint64_t pass = __ballot(j < deg && less2(key, (uint32_t)j, tkey, tslot));
+            uint64_t nk = KEY_MAX;
+            uint32_t ns = 0xFFFFFFFFu;
+            int32_t nu = 0;
+            if (j < deg) key_of(j, nu, nk, ns);
+            uint64_t pass = __ballot(j < deg && less(nk, ns, tk, ts));
             while (pass) {
                 const int src = __ffsll((long long)pass) - 1;
                 pass &= pass - 1;
-                const uint64_t nk = __shfl(key, src);
-                const uint32_t ns = (uint32_t)(j0 + src);
-                if (less2(nk, ns, tkey, tslot)) {
-                    const int32_t nu = __shfl(u, src);
-                    if (lane == tlane) { ckey = nk; cslot = ns; cu = nu; }
-                    worst();
+                const uint64_t xk = rl64(nk, src);
+                const uint32_t xs = WIDE ? rl32(ns, src) : 0u;
+                if (less(xk, xs, tk, ts)) {
+                    const int32_t xu = (int32_t)rl32((uint32_t)nu, src);
+                    const int pos = __popcll(__ballot(lane < k && less(ck, cs, xk, xs)));
+                    const uint64_t upk = __shfl_up(ck, 1);
+                    const uint32_t ups = WIDE ? __shfl_up(cs, 1) : 0u;
+                    const int32_t upu = __shfl_up(cu, 1);
+                    if (lane > pos) { ck = upk; cs = ups; cu = upu; }
+                    if (lane == pos) { ck = xk; cs = xs; cu = xu; }
+                    tk = rl64(ck, k - 1);
+                    ts = WIDE ? rl32(cs, k - 1) : 0u;
                 }
             }
         }
     }
 
-    const bool valid = lane < k && !(a.strict_p1 && ckey >= (1ull << 62));
+    // emit in ascending slot order
+    const uint32_t slot = WIDE ? cs : (uint32_t)ck;
+    const bool valid = lane < k && !(WIDE && a.strict_p1 && ck >= (1ull << 62));
     int rank = 0;
     for (int i = 0; i < k; ++i) {
-        const uint32_t si = __shfl(cslot, i);
-        const int vi = __shfl((int)valid, i);
-        rank += (vi && si < cslot) ? 1 : 0;
+        const uint32_t si = rl32(slot, i);
+        const uint32_t vi = rl32(valid ? 1u : 0u, i);
+        rank += (vi && si < slot) ? 1 : 0;
     }
     const uint64_t vmask = __ballot(valid);
-    if (valid) a.sel[(int64_t)g * a.sel_stride + (int64_t)row * f + rank] = cu;
+    if (valid) sel_row[rank] = cu;
     if (lane == 0) a.cnt[(int64_t)g * a.cnt_stride + row] = __popcll(vmask);
 }
 
@@ -232,7 +270,13 @@ __global__ __launch_bounds__(256) void fill_u64_kernel(unsigned long long *base,
     if (i < n) p[i] = v;
 }
 
+// Direct-address variant for graphs whose node count is within a small factor of the frontier
+// capacity: one int32 per node holding the smallest position seen (INT_MAX = absent).  Insertion is a
+// single no-return atomic, look-ups are single loads; touched entries are reset after the hop.
+constexpr int32_t ABSENT = 0x7FFFFFFF;
+
 struct DedupArgs {
+    int32_t direct;           // 1: table is int32[n_nodes] per batch, 0: open-addressing table
     const int32_t *prev_hdr;
     int64_t n_roots_total;
     int32_t batch_size;
@@ -289,14 +333,17 @@ __global__ __launch_bounds__(256) void insert_kernel(DedupArgs a)
 {
     CR_ROW_LANE();
     bool ok = true;
+    int32_t *dtab = reinterpret_cast<int32_t *>(table);
     if (in_row && j == 0) {
         const int32_t v = a.dst_ids[(int64_t)g * a.dst_stride + row];
         a.src_ids[(int64_t)g * a.src_stride + row] = v;
-        ok = table_insert(table, a.table_bits, (uint32_t)v, (uint32_t)row);
+        if (a.direct) atomicMin(&dtab[v], row);
+        else ok = table_insert(table, a.table_bits, (uint32_t)v, (uint32_t)row);
     }
     if (active) {
         const int32_t u = a.sel[(int64_t)g * a.sel_stride + ell];
-        ok = table_insert(table, a.table_bits, (uint32_t)u, (uint32_t)(n_dst + ell)) && ok;
+        if (a.direct) atomicMin(&dtab[u], (int32_t)(n_dst + ell));
+        else ok = table_insert(table, a.table_bits, (uint32_t)u, (uint32_t)(n_dst + ell)) && ok;
     }
     if (!ok) atomicOr(&hdr[CR_HDR_STATUS], 1);
 }
@@ -308,9 +355,13 @@ __global__ __launch_bounds__(256) void mark_new_kernel(DedupArgs a)
     bool isnew = false;
     if (active) {
         const int32_t u = a.sel[(int64_t)g * a.sel_stride + ell];
-        uint32_t pos;
-        const int h = table_find(table, a.table_bits, (uint32_t)u, pos);
-        isnew = h >= 0 && pos == (uint32_t)(n_dst + ell);
+        if (a.direct) {
+            isnew = reinterpret_cast<const int32_t *>(table)[u] == (int32_t)(n_dst + ell);
+        } else {
+            uint32_t pos;
+            const int h = table_find(table, a.table_bits, (uint32_t)u, pos);
+            isnew = h >= 0 && pos == (uint32_t)(n_dst + ell);
+        }
     }
     const uint64_t m = __ballot(isnew);
     if (in_row && j == 0) {
@@ -337,9 +388,13 @@ __global__ __launch_bounds__(256) void assign_kernel(DedupArgs a)
     const int32_t u = a.sel[(int64_t)g * a.sel_stride + ell];
     const int local = n_dst + a.newoff[(int64_t)g * a.off_stride + row] + __popcll(rowmask & ((1ull << j) - 1ull));
     a.src_ids[(int64_t)g * a.src_stride + local] = u;
-    uint32_t pos;
-    const int h = table_find(table, a.table_bits, (uint32_t)u, pos);
-    if (h >= 0) table[h] = ((unsigned long long)(uint32_t)u << 32) | (uint32_t)local;
+    if (a.direct) {
+        reinterpret_cast<int32_t *>(table)[u] = local;
+    } else {
+        uint32_t pos;
+        const int h = table_find(table, a.table_bits, (uint32_t)u, pos);
+        if (h >= 0) table[h] = ((unsigned long long)(uint32_t)u << 32) | (uint32_t)local;
+    }
 }
 
 __global__ __launch_bounds__(256) void relabel_kernel(DedupArgs a)
@@ -348,9 +403,20 @@ __global__ __launch_bounds__(256) void relabel_kernel(DedupArgs a)
     if (!active) return;
     const int32_t u = a.sel[(int64_t)g * a.sel_stride + ell];
     uint32_t local;
-    table_find(table, a.table_bits, (uint32_t)u, local);
+    if (a.direct) local = (uint32_t)reinterpret_cast<const int32_t *>(table)[u];
+    else table_find(table, a.table_bits, (uint32_t)u, local);
     a.indices[(int64_t)g * a.indices_stride + rstart + j] = (int32_t)local;
     if (a.tcount) atomicAdd(&a.tcount[(int64_t)g * a.t_stride + local], 1);
+}
+
+// direct-address table: put the entries this hop touched back to "absent"
+__global__ __launch_bounds__(256) void reset_kernel(DedupArgs a)
+{
+    const int g = blockIdx.y;
+    const int n_src = a.hdr[(int64_t)g * CR_HDR_WORDS + CR_HDR_N_SRC];
+    int32_t *dtab = reinterpret_cast<int32_t *>(a.table + (int64_t)g * a.table_stride);
+    const int32_t *src = a.src_ids + (int64_t)g * a.src_stride;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n_src; i += (int64_t)gridDim.x * 256) dtab[src[i]] = ABSENT;
 }
 
 // transposed block: scatter the destination row of every edge into its source's segment in arrival
@@ -392,6 +458,8 @@ struct SamplePlan {
     int32_t cap_dst[CR_MAX_LAYERS], cap_src[CR_MAX_LAYERS], cap_nnz[CR_MAX_LAYERS];
     int table_bits[CR_MAX_LAYERS];
     int64_t max_dst = 0, max_src_t = 0, max_nnz = 0, max_nnz_t = 0, max_table = 0;
+    bool direct = false;      // direct-address de-duplication table (one int32 per node) instead of hashing
+    int64_t table_stride = 0; // per batch, in 8-byte units
     // workspace slices
     int32_t *sel, *cnt, *newoff, *tcount, *tfill, *t_tmp, *t_pos;
     unsigned long long *newmask, *table;
@@ -441,7 +509,9 @@ static cr_status make_plan(const cr_sample_cfg *cfg, int64_t n_nodes, int32_t ba
     p.cnt = c.take<int32_t>(G * p.max_dst);
     p.newoff = c.take<int32_t>(G * (p.max_dst + 1));
     p.newmask = c.take<unsigned long long>(G * p.max_dst);
-    p.table = c.take<unsigned long long>(G * p.max_table);
+    p.direct = n_nodes <= 4 * p.max_table;
+    p.table_stride = p.direct ? round_up(ceil_div(n_nodes, 2), 2) : p.max_table;
+    p.table = c.take<unsigned long long>(G * (size_t)p.table_stride);
     p.tcount = c.take<int32_t>(G * (p.max_src_t + 1));
     p.tfill = c.take<int32_t>(G * (p.max_src_t + 1));
     p.t_tmp = c.take<int32_t>(G * (p.max_nnz_t + 1));
@@ -534,7 +604,8 @@ extern "C" cr_status cr_sample_blocks(const cr_graph *graph, const cr_sample_cfg
         sa.ctr3 = (cfg->epoch << 8) | (DOMAIN_NEIGHBOUR << 4) | (uint32_t)l;
         sa.first_batch = cfg->first_batch;
         sa.sel = p.sel; sa.sel_stride = p.max_nnz; sa.cnt = p.cnt; sa.cnt_stride = p.max_dst;
-        hipLaunchKernelGGL(select_kernel, dim3((unsigned)ceil_div(cap_dst, 4), n_batches), blk, 0, s, sa);
+        if (q_in == q_out) hipLaunchKernelGGL(select_kernel<false>, dim3((unsigned)ceil_div(cap_dst, 4), n_batches), blk, 0, s, sa);
+        else hipLaunchKernelGGL(select_kernel<true>, dim3((unsigned)ceil_div(cap_dst, 4), n_batches), blk, 0, s, sa);
 
         ScanArgs sc;
         sc.prev_hdr = prev_hdr; sc.n_roots_total = n_roots_total; sc.batch_size = batch_size;
@@ -542,15 +613,21 @@ extern "C" cr_status cr_sample_blocks(const cr_graph *graph, const cr_sample_cfg
         sc.out_copy = nullptr; sc.copy_stride = 0; sc.hdr = b.hdr;
         hipLaunchKernelGGL(scan_kernel, dim3(n_batches), dim3(1024), 0, s, sc);
 
-        const int64_t table_size = 1ll << p.table_bits[l];
-        hipLaunchKernelGGL(fill_u64_kernel, dim3((unsigned)(ceil_div(table_size, 512) < 4096 ? ceil_div(table_size, 512) : 4096), n_batches), blk, 0, s,
-                           p.table, p.max_table, table_size, EMPTY);
+        if (!p.direct) {
+            const int64_t table_size = 1ll << p.table_bits[l];
+            hipLaunchKernelGGL(fill_u64_kernel, dim3((unsigned)(ceil_div(table_size, 512) < 4096 ? ceil_div(table_size, 512) : 4096), n_batches), blk, 0, s,
+                               p.table, p.table_stride, table_size, EMPTY);
+        } else if (root) {   // once per call; every hop puts the entries it touched back
+            hipLaunchKernelGGL(fill_u64_kernel, dim3((unsigned)(ceil_div(p.table_stride, 512) < 4096 ? ceil_div(p.table_stride, 512) : 4096), n_batches), blk, 0, s,
+                               p.table, p.table_stride, p.table_stride, 0x7FFFFFFF7FFFFFFFull);
+        }
 
         DedupArgs da;
         da.prev_hdr = prev_hdr; da.n_roots_total = n_roots_total; da.batch_size = batch_size; da.fanout = f;
         da.gw = f <= 16 ? 16 : (f <= 32 ? 32 : 64);
         da.dst_ids = dst_ids; da.dst_stride = dst_stride; da.sel = p.sel; da.sel_stride = p.max_nnz;
-        da.table = p.table; da.table_stride = p.max_table; da.table_bits = p.table_bits[l];
+        da.direct = p.direct ? 1 : 0;
+        da.table = p.table; da.table_stride = p.table_stride; da.table_bits = p.table_bits[l];
         da.hdr = b.hdr; da.src_ids = b.src_ids; da.src_stride = b.cap_src;
         da.indptr = b.indptr; da.indptr_stride = b.cap_dst + 1; da.indices = b.indices; da.indices_stride = b.cap_nnz;
         da.newcnt = p.cnt; da.newoff = p.newoff; da.newmask = p.newmask; da.row_stride = p.max_dst; da.off_stride = p.max_dst + 1;
@@ -565,6 +642,8 @@ extern "C" cr_status cr_sample_blocks(const cr_graph *graph, const cr_sample_cfg
         hipLaunchKernelGGL(scan_kernel, dim3(n_batches), dim3(1024), 0, s, sc);
         hipLaunchKernelGGL(assign_kernel, grid, blk, 0, s, da);
         hipLaunchKernelGGL(relabel_kernel, grid, blk, 0, s, da);
+        if (p.direct)
+            hipLaunchKernelGGL(reset_kernel, dim3((unsigned)ceil_div(p.cap_src[l], 1024), n_batches), blk, 0, s, da);
         if (tr) {
             sc.mode = 2; sc.in = p.tcount; sc.in_stride = p.max_src_t + 1; sc.out = b.t_indptr; sc.out_stride = b.cap_src + 1;
             sc.out_copy = p.tfill; sc.copy_stride = p.max_src_t + 1;
