@@ -28,10 +28,10 @@ METRIC = "epoch time + gathered-feature GB/s (% HBM peak) vs randomness knob, 1 
 
 def gather0_bytes(hdr0, n_feat, elem_bytes, f_pad):
     """Algorithmic bytes of one layer-0 gather/aggregate launch: every gathered row (neighbours and
-    the destination's own row) once, 8 bytes of index per edge (local index + frontier id), the row
-    pointers, and the two bf16 outputs (self rows, aggregated rows)."""
+    the destination's own row) once, 4 bytes of index per edge (its global id), 4 bytes per
+    destination for its own id, the row pointers, and the two bf16 outputs (self rows, aggregated rows)."""
     n_dst, n_src, nnz = int(hdr0[0]), int(hdr0[1]), int(hdr0[2])
-    reads = (nnz + n_dst) * n_feat * elem_bytes + 8 * nnz + 4 * n_dst + 4 * (n_dst + 1)
+    reads = (nnz + n_dst) * n_feat * elem_bytes + 4 * nnz + 4 * n_dst + 4 * (n_dst + 1)
     writes = 2 * n_dst * f_pad * 2
     return reads + writes, (nnz + n_dst) * n_feat * elem_bytes
 

@@ -116,7 +116,7 @@ typedef struct {
  * slot ascending); indptr/indices are a CSR over local source positions.  t_indptr/t_indices hold
  * the transposed block (for every source position the destination rows that use it, ascending);
  * they may be NULL when the layer's input needs no gradient, and must be NULL for layer 0 (the
- * feature table takes no gradient). */
+ * feature table takes no gradient).  gather_ids is optional for every layer. */
 typedef struct {
     int32_t n_batches;
     int32_t fanout;
@@ -130,6 +130,9 @@ typedef struct {
     int32_t *indices;   /* device int32[n_batches][cap_nnz] */
     int32_t *t_indptr;  /* device int32[n_batches][cap_src+1] or NULL */
     int32_t *t_indices; /* device int32[n_batches][cap_nnz] or NULL */
+    int32_t *gather_ids;/* device int32[n_batches][cap_nnz] or NULL: global id of every edge's source,
+                           gather_ids[e] == src_ids[indices[e]]; lets the layer-0 feature gather skip one
+                           level of indirection */
 } cr_block_set;
 
 #define CR_SAMPLE_STRICT_INTRA 1u /* at p = 1 never take an inter-community neighbour (rows may be short) */
@@ -179,7 +182,8 @@ enum { CR_F32 = 0, CR_BF16 = 1 };
 /* Feature-row gather with mean aggregation for batch g of a block set (the input-feature fetch the
  * paper identifies as the cost that tracks the batch's footprint, Section 6.1.1).
  *   H_src    : device; indirect != 0: the resident feature table [n_nodes][ld_src], row of local
- *              source position s is src_ids[s]; indirect == 0: dense [n_src][ld_src]
+ *              source position s is src_ids[s] (read through blocks->gather_ids when that is given);
+ *              indirect == 0: dense [n_src][ld_src]
  *   dtype    : CR_F32 or CR_BF16 element type of H_src;  F <= 1024 columns
  *   agg      : device float [cap_dst][F] or NULL
  *   agg_bf16 : device bf16 [cap_dst][ld_bf16] or NULL; columns F..ld_bf16-1 are written as zero

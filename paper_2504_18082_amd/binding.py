@@ -51,7 +51,8 @@ class cr_block_set(C.Structure):
     _fields_ = [("n_batches", C.c_int32), ("fanout", C.c_int32), ("cap_dst", C.c_int32),
                 ("cap_src", C.c_int32), ("cap_nnz", C.c_int32), ("reserved", C.c_int32),
                 ("hdr", C.c_void_p), ("src_ids", C.c_void_p), ("indptr", C.c_void_p),
-                ("indices", C.c_void_p), ("t_indptr", C.c_void_p), ("t_indices", C.c_void_p)]
+                ("indices", C.c_void_p), ("t_indptr", C.c_void_p), ("t_indices", C.c_void_p),
+                ("gather_ids", C.c_void_p)]
 
 
 class cr_sample_cfg(C.Structure):
@@ -159,7 +160,7 @@ def cr_block_capacities(cfg: cr_sample_cfg, n_nodes: int, batch_size: int):
 class BlockSet:
     """Device storage of one layer's blocks for a group of batches (torch int32 tensors)."""
 
-    def __init__(self, n_batches, fanout, cap_dst, cap_src, cap_nnz, transposed, device="cuda"):
+    def __init__(self, n_batches, fanout, cap_dst, cap_src, cap_nnz, transposed, device="cuda", gather_ids=False):
         import torch
         z = lambda *shape: torch.zeros(shape, dtype=torch.int32, device=device)
         self.n_batches, self.fanout = n_batches, fanout
@@ -170,9 +171,10 @@ class BlockSet:
         self.indices = z(n_batches, cap_nnz)
         self.t_indptr = z(n_batches, cap_src + 1) if transposed else None
         self.t_indices = z(n_batches, cap_nnz) if transposed else None
+        self.gather_ids = z(n_batches, cap_nnz) if gather_ids else None
         self.c = cr_block_set(n_batches, fanout, cap_dst, cap_src, cap_nnz, 0, _ptr(self.hdr),
                               _ptr(self.src_ids), _ptr(self.indptr), _ptr(self.indices),
-                              _ptr(self.t_indptr), _ptr(self.t_indices))
+                              _ptr(self.t_indptr), _ptr(self.t_indices), _ptr(self.gather_ids))
 
     def hdr_ptr(self, g):
         return C.c_void_p(self.hdr.data_ptr() + g * CR_HDR_WORDS * 4)
@@ -181,18 +183,21 @@ class BlockSet:
         return C.c_void_p(self.src_ids.data_ptr() + g * self.cap_src * 4)
 
     @classmethod
-    def from_host(cls, blk, fanout, device="cuda"):
-        """Upload one oracle/numpy block (n_dst, src_ids, indptr, indices[, t_indptr, t_indices])."""
+    def from_host(cls, blk, fanout, device="cuda", gather_ids=False):
+        """Upload one oracle/numpy block (n_dst, src_ids, indptr, indices[, t_indptr, t_indices]);
+        gather_ids=True also uploads the per-edge global ids src_ids[indices]."""
         import numpy as np
         import torch
         tr = getattr(blk, "t_indptr", None) is not None
         cap_dst, cap_src, cap_nnz = max(1, blk.n_dst), max(1, blk.n_src, blk.n_dst), max(1, blk.nnz)
-        bs = cls(1, fanout, cap_dst, cap_src, cap_nnz, tr, device)
+        bs = cls(1, fanout, cap_dst, cap_src, cap_nnz, tr, device, gather_ids)
         up = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(device)
         bs.hdr[0, :3] = up([blk.n_dst, blk.n_src, blk.nnz])
         bs.src_ids[0, :blk.n_src] = up(blk.src_ids)
         bs.indptr[0, :blk.n_dst + 1] = up(blk.indptr[:blk.n_dst + 1])
         bs.indices[0, :blk.nnz] = up(blk.indices)
+        if gather_ids:
+            bs.gather_ids[0, :blk.nnz] = up(blk.src_ids[blk.indices])
         if tr:
             bs.t_indptr[0, :blk.n_src + 1] = up(blk.t_indptr)
             bs.t_indices[0, :blk.nnz] = up(blk.t_indices)
@@ -202,7 +207,7 @@ class BlockSet:
 def alloc_block_sets(cfg: cr_sample_cfg, n_nodes: int, batch_size: int, n_batches: int,
                      device="cuda") -> List[BlockSet]:
     cap_dst, cap_src, cap_nnz = cr_block_capacities(cfg, n_nodes, batch_size)
-    return [BlockSet(n_batches, cfg.fanout[l], cap_dst[l], cap_src[l], cap_nnz[l], l >= 1, device)
+    return [BlockSet(n_batches, cfg.fanout[l], cap_dst[l], cap_src[l], cap_nnz[l], l >= 1, device, gather_ids=(l == 0))
             for l in range(cfg.n_layers)]
 
 

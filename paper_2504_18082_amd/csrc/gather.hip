@@ -46,111 +46,147 @@ __device__ __forceinline__ void store_bf16_row(uint16_t *dst, const float (&v)[N
 
 // ------------------------------------------------------------------------------------------------
 // forward
+//   ids[e]      : per-edge source row (through edge_map when it is given)
+//   self_map[v] : table row of destination v (identity when NULL)
+// A workgroup owns a contiguous range of destination rows (XCD-aware), its sub-wave groups walk the
+// range interleaved.  The walk is software pipelined: while the feature rows of the current
+// destination are in flight, the neighbour ids of the next destination and the row pointers of the
+// one after are already being fetched, so a destination costs one memory round trip instead of a
+// chain of four.  Look-ahead loads are unconditional (clamped to valid addresses).
 // ------------------------------------------------------------------------------------------------
 template <typename T, int LPR, int NCHUNK>
 __global__ __launch_bounds__(256) void gather_mean_fwd_kernel(
     const int32_t *__restrict__ hdr, const int32_t *__restrict__ indptr,
-    const int32_t *__restrict__ indices, const int32_t *__restrict__ row_map,
-    const T *__restrict__ table, int64_t ld, int F, float *__restrict__ agg,
-    uint16_t *__restrict__ agg_bf16, uint16_t *__restrict__ self_bf16, int64_t ld_bf16)
+    const int32_t *__restrict__ ids, const int32_t *__restrict__ edge_map,
+    const int32_t *__restrict__ self_map, const T *__restrict__ table, int64_t ld, int F,
+    float *__restrict__ agg, uint16_t *__restrict__ agg_bf16, uint16_t *__restrict__ self_bf16, int64_t ld_bf16)
 {
     constexpr int VEC = Vec16<T>::N;
     constexpr int U = NCHUNK == 1 ? 8 : (NCHUNK <= 3 ? 4 : 2);   // independent row loads in flight per lane
-    constexpr int ROWS_PER_BLOCK = 256 / LPR;
+    constexpr int GPB = 256 / LPR;                                // groups (rows in progress) per workgroup
     const int n_dst = hdr[CR_HDR_N_DST];
+    if (n_dst <= 0) return;
     const uint32_t lb = xcd_remap(blockIdx.x, gridDim.x);
-    const int row = (int)(lb * ROWS_PER_BLOCK + threadIdx.x / LPR);
-    if (row >= n_dst) return;
+    const int rows_per_block = (int)(((int64_t)n_dst + gridDim.x - 1) / gridDim.x + GPB - 1) / GPB * GPB;
+    const int block_first = (int)lb * rows_per_block;
+    const int block_end = min(n_dst, block_first + rows_per_block);
     const int gl = (int)(threadIdx.x % LPR);
+    int row = block_first + (int)(threadIdx.x / LPR);
+    if (row >= block_end) return;
 
-    const int start = indptr[row], end = indptr[row + 1];
-    float acc[NCHUNK][VEC];
-#pragma unroll
-    for (int c = 0; c < NCHUNK; ++c)
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) acc[c][i] = 0.f;
+    auto load_ptrs = [&](int r, int &s, int &e, int &self_row) {
+        const int rc = min(r, n_dst - 1);
+        const int a = indptr[rc], b = indptr[rc + 1];
+        const int sr = self_map ? self_map[rc] : rc;
+        s = r < block_end ? a : 0;
+        e = r < block_end ? b : 0;
+        self_row = sr;
+    };
+    auto load_ids = [&](int first, int e) -> int {
+        const int idx = max(min(first + gl, e - 1), 0);
+        int x = ids[idx];
+        if (edge_map) x = edge_map[x];
+        return x;
+    };
 
-    for (int base = start; base < end; base += LPR) {
-        const int e = base + gl;
-        int rid = 0;
-        if (e < end) {
-            const int s = indices[e];
-            rid = row_map ? row_map[s] : s;
-        }
-        const int cnt = min(LPR, end - base);
-        for (int t = 0; t < cnt; t += U) {
-            float v[U][NCHUNK][VEC];
+    int s0, e0, self0, s1, e1, self1;
+    load_ptrs(row, s0, e0, self0);
+    int rid0 = load_ids(s0, e0);
+    load_ptrs(row + GPB, s1, e1, self1);
+
+    for (; row < block_end; row += GPB) {
+        // look ahead: ids of the next destination, pointers of the one after
+        const int rid1 = load_ids(s1, e1);
+        int s2, e2, self2;
+        load_ptrs(row + 2 * GPB, s2, e2, self2);
+
+        float acc[NCHUNK][VEC];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int r = __shfl(rid, t + u, LPR);
-                const T *p = table + (int64_t)r * ld;
+        for (int c = 0; c < NCHUNK; ++c)
 #pragma unroll
-                for (int c = 0; c < NCHUNK; ++c) {
-                    const int col = (c * LPR + gl) * VEC;
-                    if (col < F && t + u < cnt) Vec16<T>::load(p + col, v[u][c]);
-                }
-            }
+            for (int i = 0; i < VEC; ++i) acc[c][i] = 0.f;
+
+        int rid = rid0;
+        for (int base = s0; base < e0; base += LPR) {
+            if (base > s0) rid = load_ids(base, e0);            // rows longer than the group width
+            const int cnt = min(LPR, e0 - base);
+            for (int t = 0; t < cnt; t += U) {
+                float v[U][NCHUNK][VEC];
 #pragma unroll
-            for (int u = 0; u < U; ++u)
+                for (int u = 0; u < U; ++u) {
+                    const int r = __shfl(rid, t + u, LPR);
+                    const T *p = table + (int64_t)r * ld;
 #pragma unroll
-                for (int c = 0; c < NCHUNK; ++c) {
-                    const int col = (c * LPR + gl) * VEC;
-                    if (col < F && t + u < cnt) {
-#pragma unroll
-                        for (int i = 0; i < VEC; ++i) acc[c][i] += v[u][c][i];
+                    for (int c = 0; c < NCHUNK; ++c) {
+                        const int col = (c * LPR + gl) * VEC;
+                        if (col < F && t + u < cnt) Vec16<T>::load(p + col, v[u][c]);
                     }
                 }
-        }
-    }
-
-    const int deg = end - start;
-    const float fdeg = (float)(deg > 0 ? deg : 1);
 #pragma unroll
-    for (int c = 0; c < NCHUNK; ++c) {
-        const int col = (c * LPR + gl) * VEC;
+                for (int u = 0; u < U; ++u)
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) acc[c][i] = acc[c][i] / fdeg;
-        if (agg && col < F) {
-            float *o = agg + (int64_t)row * F + col;
-            if ((F & 3) == 0) {
+                    for (int c = 0; c < NCHUNK; ++c) {
+                        const int col = (c * LPR + gl) * VEC;
+                        if (col < F && t + u < cnt) {
 #pragma unroll
-                for (int i = 0; i < VEC; i += 4)
-                    *reinterpret_cast<float4 *>(o + i) = make_float4(acc[c][i], acc[c][i + 1], acc[c][i + 2], acc[c][i + 3]);
-            } else {
-#pragma unroll
-                for (int i = 0; i < VEC; ++i)
-                    if (col + i < F) o[i] = acc[c][i];
+                            for (int i = 0; i < VEC; ++i) acc[c][i] += v[u][c][i];
+                        }
+                    }
             }
         }
-        if (agg_bf16 && col < ld_bf16) store_bf16_row<VEC>(agg_bf16 + (int64_t)row * ld_bf16 + col, acc[c], col, F);
-    }
 
-    if (self_bf16) {
-        const int r = row_map ? row_map[row] : row;
-        const T *p = table + (int64_t)r * ld;
+        const int deg = e0 - s0;
+        const float fdeg = (float)(deg > 0 ? deg : 1);
 #pragma unroll
         for (int c = 0; c < NCHUNK; ++c) {
             const int col = (c * LPR + gl) * VEC;
-            if (col < ld_bf16) {
-                float v[VEC];
 #pragma unroll
-                for (int i = 0; i < VEC; ++i) v[i] = 0.f;
-                if (col < F) Vec16<T>::load(p + col, v);
-                store_bf16_row<VEC>(self_bf16 + (int64_t)row * ld_bf16 + col, v, col, F);
+            for (int i = 0; i < VEC; ++i) acc[c][i] = acc[c][i] / fdeg;
+            if (agg && col < F) {
+                float *o = agg + (int64_t)row * F + col;
+                if ((F & 3) == 0) {
+#pragma unroll
+                    for (int i = 0; i < VEC; i += 4)
+                        *reinterpret_cast<float4 *>(o + i) = make_float4(acc[c][i], acc[c][i + 1], acc[c][i + 2], acc[c][i + 3]);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i)
+                        if (col + i < F) o[i] = acc[c][i];
+                }
+            }
+            if (agg_bf16 && col < ld_bf16) store_bf16_row<VEC>(agg_bf16 + (int64_t)row * ld_bf16 + col, acc[c], col, F);
+        }
+
+        if (self_bf16) {
+            const T *p = table + (int64_t)self0 * ld;
+#pragma unroll
+            for (int c = 0; c < NCHUNK; ++c) {
+                const int col = (c * LPR + gl) * VEC;
+                if (col < ld_bf16) {
+                    float v[VEC];
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) v[i] = 0.f;
+                    if (col < F) Vec16<T>::load(p + col, v);
+                    store_bf16_row<VEC>(self_bf16 + (int64_t)row * ld_bf16 + col, v, col, F);
+                }
             }
         }
+
+        s0 = s1; e0 = e1; self0 = self1; rid0 = rid1;
+        s1 = s2; e1 = e2; self1 = self2;
     }
 }
 
 template <typename T, int LPR, int NCHUNK>
-static void launch_fwd(int cap_dst, const int32_t *hdr, const int32_t *indptr, const int32_t *indices,
-                       const int32_t *row_map, const void *table, int64_t ld, int F, float *agg,
-                       uint16_t *agg_bf16, uint16_t *self_bf16, int64_t ld_bf16, hipStream_t st)
+static void launch_fwd(int cap_dst, const int32_t *hdr, const int32_t *indptr, const int32_t *ids,
+                       const int32_t *edge_map, const int32_t *self_map, const void *table, int64_t ld, int F,
+                       float *agg, uint16_t *agg_bf16, uint16_t *self_bf16, int64_t ld_bf16, hipStream_t st)
 {
-    const int rows_per_block = 256 / LPR;
-    const unsigned grid = (unsigned)ceil_div(cap_dst, rows_per_block);
-    hipLaunchKernelGGL((gather_mean_fwd_kernel<T, LPR, NCHUNK>), dim3(grid), dim3(256), 0, st, hdr, indptr,
-                       indices, row_map, static_cast<const T *>(table), ld, F, agg, agg_bf16, self_bf16, ld_bf16);
+    constexpr int GPB = 256 / LPR;
+    int64_t grid = ceil_div(cap_dst, GPB);
+    if (grid > 1024) grid = 1024;          // 4 workgroups per CU; each group then walks several rows
+    hipLaunchKernelGGL((gather_mean_fwd_kernel<T, LPR, NCHUNK>), dim3((unsigned)grid), dim3(256), 0, st, hdr, indptr,
+                       ids, edge_map, self_map, static_cast<const T *>(table), ld, F, agg, agg_bf16, self_bf16, ld_bf16);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -294,11 +330,17 @@ extern "C" cr_status cr_gather_aggregate_fwd(const cr_block_set *blocks, int32_t
 
     const int32_t *hdr = blocks->hdr + (int64_t)g * CR_HDR_WORDS;
     const int32_t *indptr = blocks->indptr + (int64_t)g * (blocks->cap_dst + 1);
-    const int32_t *indices = blocks->indices + (int64_t)g * blocks->cap_nnz;
-    const int32_t *row_map = indirect ? blocks->src_ids + (int64_t)g * blocks->cap_src : nullptr;
+    const int32_t *src_ids = blocks->src_ids + (int64_t)g * blocks->cap_src;
+    const int32_t *ids = blocks->indices + (int64_t)g * blocks->cap_nnz;
+    const int32_t *edge_map = nullptr, *self_map = nullptr;
+    if (indirect) {
+        self_map = src_ids;
+        if (blocks->gather_ids) ids = blocks->gather_ids + (int64_t)g * blocks->cap_nnz;   // per-edge table rows, one level less
+        else edge_map = src_ids;
+    }
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int cap = blocks->cap_dst;
-#define CR_FWD(T, LPR, NC) launch_fwd<T, LPR, NC>(cap, hdr, indptr, indices, row_map, H_src, ld_src, F, agg, agg_bf16, self_bf16, ld_bf16, s)
+#define CR_FWD(T, LPR, NC) launch_fwd<T, LPR, NC>(cap, hdr, indptr, ids, edge_map, self_map, H_src, ld_src, F, agg, agg_bf16, self_bf16, ld_bf16, s)
     if (dtype == CR_F32) {
         if (F <= 64) CR_FWD(float, 16, 1);
         else if (F <= 128) CR_FWD(float, 32, 1);

@@ -8,6 +8,7 @@ namespace cr {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4v __attribute__((ext_vector_type(4)));
 
 constexpr int LDS_ROW = 40;   // 32 bf16 of payload + 8 of padding per staged row (80 bytes)
 
@@ -121,9 +122,12 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(NtArgs a)
 }
 
 // ------------------------------------------------------------------------------------------------
-// P[s][k][n] = sum_{m in split s} A[m][k] * Z[m][n]      (both operands strided along m: the tiles are
-// transposed on their way into LDS).  Also the column sums of Z per split (bias gradient).
-// Workgroup tile 64 (k) x 64 (n), four waves of 32 x 32; 32 rows of m per step.
+// P[s][k][n] = sum_{m in split s} A[m][k] * Z[m][n]      (both operands strided along m).  Also the
+// column sums of Z per split (bias gradient).
+// Workgroup tile 128 (k) x 128 (n), four waves of 64 x 64; 32 rows of m per step.  Half of the
+// threads stage A, half stage Z: a thread fetches one 8-column chunk of four consecutive rows and
+// writes it transposed as eight 64-bit LDS stores (four m of one column each), so the MFMA operands
+// are again 16-byte reads along m.  Global loads run three steps ahead in a register ring.
 // ------------------------------------------------------------------------------------------------
 struct TnArgs {
     const int32_t *hdr;
@@ -140,67 +144,125 @@ struct TnArgs {
 
 __global__ __launch_bounds__(256) void gemm_tn_kernel(TnArgs a)
 {
-    __shared__ __attribute__((aligned(16))) uint16_t At[64][LDS_ROW];
-    __shared__ __attribute__((aligned(16))) uint16_t Zt[64][LDS_ROW];
+    __shared__ __attribute__((aligned(16))) uint16_t T[2][2][128][LDS_ROW];   // [buffer][operand: 0 = A, 1 = Z][column][m]
     const int M = min(a.hdr[CR_HDR_N_DST], a.max_rows);
     const int split = blockIdx.y;
     const int m_begin = split * a.rows_per_split;
     if (m_begin >= M) return;                      // inactive split: the reduction skips it too
     const int m_end = min(M, m_begin + a.rows_per_split);
-    const int n_tiles = a.N / 64;
-    const int k0 = (blockIdx.x / n_tiles) * 64, n0 = (blockIdx.x % n_tiles) * 64;
+    const int n_tiles = (a.N + 127) / 128;
+    const int k_tiles_part = (a.K0 + 127) / 128;   // k-tiles per operand part (self | agg): a tile never straddles the two
+    const int kt = blockIdx.x / n_tiles;
+    const int part = kt / k_tiles_part;
+    const int kp0 = (kt % k_tiles_part) * 128;     // first column of the tile inside its part
+    const int k0 = part * a.K0 + kp0;              // first row of the output tile
+    const int k_valid = min(128, a.K0 - kp0);
+    const int n0 = (blockIdx.x % n_tiles) * 128;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int half = lane >> 5, lr = lane & 31;
     const int wk = wave >> 1, wn = wave & 1;
 
-    // staging: 32 rows of m x 8 chunks of 8 columns, one chunk of each operand per thread
-    const int sm = tid >> 3, sc = (tid & 7) * 8;
-    const int kcol = k0 + sc;
-    const uint16_t *srcA = kcol < a.K0 ? a.A0 + kcol : a.A1 + (kcol - a.K0);
-    const uint16_t *srcZ = a.Z + n0 + sc;
+    // staging role: waves 0,1 stage A, waves 2,3 stage Z.  Buffer loads return zero past the end of the
+    // split's rows (and for columns outside the tile), so no load sits under a branch and the loads of
+    // three steps stay in flight together.
+    const int op = tid >> 7;                       // 0: A, 1: Z (uniform per wave)
+    const int st = tid & 127, mg = st >> 4, sc = (st & 15) * 8;
+    const uint16_t *base = op == 0 ? (part == 0 ? a.A0 : a.A1) : a.Z;
+    const uint32_t ld_bytes = (uint32_t)((op == 0 ? a.lda : (int64_t)a.N) * 2);
+    const bool col_ok = op == 0 ? sc < k_valid : n0 + sc < a.N;
+    const uint32_t col_bytes = (uint32_t)((op == 0 ? kp0 + sc : n0 + sc) * 2);
+    const __amdgpu_buffer_rsrc_t rsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(base), 0, (int)((uint32_t)m_end * ld_bytes), 0x00020000);
 
-    f32x16 acc;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-    float colsum = 0.f;
-
-    for (int mb = m_begin; mb < m_end; mb += 32) {
-        const int gm = mb + sm;
-        uint4 ra = make_uint4(0, 0, 0, 0), rz = make_uint4(0, 0, 0, 0);
-        if (gm < m_end) {
-            ra = *reinterpret_cast<const uint4 *>(srcA + (int64_t)gm * a.lda);
-            rz = *reinterpret_cast<const uint4 *>(srcZ + (int64_t)gm * a.N);
-        }
-        __syncthreads();                           // previous step's reads are done
-        const uint32_t wa[4] = {ra.x, ra.y, ra.z, ra.w}, wz[4] = {rz.x, rz.y, rz.z, rz.w};
+    uint4 ring[3][4];
+    auto fetch = [&](uint4 (&r)[4], int step) {
+        const uint32_t mrow = (uint32_t)(m_begin + step * 32 + mg * 4);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            At[sc + 2 * i][sm] = (uint16_t)(wa[i] & 0xFFFFu);
-            At[sc + 2 * i + 1][sm] = (uint16_t)(wa[i] >> 16);
-            Zt[sc + 2 * i][sm] = (uint16_t)(wz[i] & 0xFFFFu);
-            Zt[sc + 2 * i + 1][sm] = (uint16_t)(wz[i] >> 16);
+            const uint32_t off = col_ok ? (mrow + i) * ld_bytes + col_bytes : 0xFFFFFFF0u;
+            const u32x4v v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)off, 0, 0);
+            r[i] = make_uint4(v[0], v[1], v[2], v[3]);
         }
-        __syncthreads();
+    };
+    auto stage = [&](const uint4 (&r)[4], int buf) {
+        const uint32_t w[4][4] = {{r[0].x, r[0].y, r[0].z, r[0].w}, {r[1].x, r[1].y, r[1].z, r[1].w},
+                                  {r[2].x, r[2].y, r[2].z, r[2].w}, {r[3].x, r[3].y, r[3].z, r[3].w}};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {              // word q holds columns 2q (low half) and 2q+1 (high half)
+            const uint32_t e_lo = (w[0][q] & 0xFFFFu) | (w[1][q] << 16);
+            const uint32_t e_hi = (w[2][q] & 0xFFFFu) | (w[3][q] << 16);
+            const uint32_t o_lo = (w[0][q] >> 16) | (w[1][q] & 0xFFFF0000u);
+            const uint32_t o_hi = (w[2][q] >> 16) | (w[3][q] & 0xFFFF0000u);
+            *reinterpret_cast<uint2 *>(&T[buf][op][sc + 2 * q][mg * 4]) = make_uint2(e_lo, e_hi);
+            *reinterpret_cast<uint2 *>(&T[buf][op][sc + 2 * q + 1][mg * 4]) = make_uint2(o_lo, o_hi);
+        }
+    };
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    float colsum = 0.f;
+    const bool do_colsum = kt == 0 && tid < 128 && n0 + tid < a.N;
+
+    const int nsteps = (m_end - m_begin + 31) / 32;
+    fetch(ring[0], 0);
+    fetch(ring[1], 1);
+    fetch(ring[2], 2);
+    stage(ring[0], 0);
+    __syncthreads();
+
+    auto body = [&](int t, uint4 (&slot_next_fetch)[4], const uint4 (&slot_next_stage)[4]) {
+        const int buf = t & 1;
+        fetch(slot_next_fetch, t + 3);             // the slot that held step t (already staged)
 #pragma unroll
         for (int kk = 0; kk < 2; ++kk) {
-            const int mo = kk * 16 + 8 * (lane >> 5);
-            const bf16x8 x = lds_read8(&At[wk * 32 + (lane & 31)][mo]);
-            const bf16x8 z = lds_read8(&Zt[wn * 32 + (lane & 31)][mo]);
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, z, acc, 0, 0, 0);
+            const int mo = kk * 16 + 8 * half;
+            bf16x8 x[2], z[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                x[i] = lds_read8(&T[buf][0][wk * 64 + i * 32 + lr][mo]);
+                z[i] = lds_read8(&T[buf][1][wn * 64 + i * 32 + lr][mo]);
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x[i], z[j], acc[i][j], 0, 0, 0);
         }
-        if (k0 == 0 && tid < 64) {
-#pragma unroll 8
-            for (int i = 0; i < 32; ++i) colsum += bf16_to_f32(Zt[tid][i]);
+        if (do_colsum) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint4 v = *reinterpret_cast<const uint4 *>(&T[buf][1][tid][q * 8]);
+                const uint32_t w4[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) colsum += __uint_as_float(w4[i] << 16) + __uint_as_float(w4[i] & 0xFFFF0000u);
+            }
         }
+        if (t + 1 < nsteps) stage(slot_next_stage, buf ^ 1);
+        __syncthreads();
+    };
+    for (int t = 0; t < nsteps; t += 3) {
+        body(t, ring[0], ring[1]);
+        if (t + 1 < nsteps) body(t + 1, ring[1], ring[2]);
+        if (t + 2 < nsteps) body(t + 2, ring[2], ring[0]);
     }
 
     float *P = a.partial + (int64_t)split * a.K2 * a.N;
-    const int n = n0 + wn * 32 + (lane & 31);
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const int k = k0 + wk * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        P[(int64_t)k * a.N + n] = acc[r];
-    }
-    if (k0 == 0 && tid < 64) a.db_partial[(int64_t)split * a.N + n0 + tid] = colsum;
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int n = n0 + wn * 64 + j * 32 + lr;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int kl = wk * 64 + i * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+                if (kl < k_valid && n < a.N) P[(int64_t)(k0 + kl) * a.N + n] = acc[i][j][r];
+            }
+        }
+    if (do_colsum) a.db_partial[(int64_t)split * a.N + n0 + tid] = colsum;
 }
 
 // sums the partial products of the active splits in a fixed order, applies the SGD step to the float
@@ -226,15 +288,17 @@ __global__ __launch_bounds__(256) void sgd_reduce_kernel(SgdArgs a)
     const int k2 = (int)(idx / a.N_pad), n = (int)(idx % a.N_pad);
     const int kin = k2 % a.F_pad, part = k2 / a.F_pad;
     if (kin < a.F_in && n < a.F_out) {
-        float g4[4] = {0.f, 0.f, 0.f, 0.f};     // fixed association: split s goes to accumulator s % 4
+        float g8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};     // fixed association: split s goes to accumulator s % 8
         const float *pp = a.partial + (int64_t)k2 * a.N_pad + n;
         const int64_t ps = (int64_t)K2 * a.N_pad;
-        for (int s = 0; s < active; s += 4) {
+        for (int s = 0; s < active; s += 8) {
+            float x[8];
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-                if (s + i < active) g4[i] += pp[(int64_t)(s + i) * ps];
+            for (int i = 0; i < 8; ++i) x[i] = s + i < active ? pp[(int64_t)(s + i) * ps] : 0.f;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) g8[i] += x[i];
         }
-        const float g = (g4[0] + g4[1]) + (g4[2] + g4[3]);
+        const float g = ((g8[0] + g8[1]) + (g8[2] + g8[3])) + ((g8[4] + g8[5]) + (g8[6] + g8[7]));
         const int64_t wi = (int64_t)(part * a.F_in + kin) * a.F_out + n;
         float w = a.W[wi];
         if (a.dW_out) a.dW_out[wi] = g;
@@ -316,12 +380,12 @@ __global__ __launch_bounds__(1024) void xent_mean_kernel(const int32_t *hdr, int
 
 static void split_plan(int F_pad, int N_pad, int max_rows, int &rows_per_split, int &n_splits)
 {
-    const int tiles = (2 * F_pad / 64) * (N_pad / 64);
-    int target = 1024 / tiles;
+    const int tiles = (int)(2 * ceil_div(F_pad, 128) * ceil_div(N_pad, 128));
+    int target = 768 / tiles;
     if (target < 1) target = 1;
-    if (target > 128) target = 128;
-    int rows = (int)round_up(ceil_div(max_rows, target), 32);
-    if (rows < 64) rows = 64;
+    if (target > 64) target = 64;
+    int rows = (int)round_up(ceil_div(max_rows, target), 96);
+    if (rows < 96) rows = 96;
     rows_per_split = rows;
     n_splits = (int)ceil_div(max_rows, rows);
 }
@@ -418,6 +482,8 @@ extern "C" cr_status cr_sage_linear_bwd(const cr_sage_layer *layer, const int32_
     CR_REQUIRE((d_self == nullptr) == (d_agg == nullptr), CR_ERR_INVALID_ARG, "d_self and d_agg must be given together");
     CR_REQUIRE(aligned16(d_self) && aligned16(d_agg), CR_ERR_INVALID_ARG, "d_self / d_agg must be 16-byte aligned");
     CR_REQUIRE(lr == lr && weight_decay == weight_decay, CR_ERR_INVALID_ARG, "lr / weight_decay is NaN");
+    CR_REQUIRE((int64_t)max_rows * ld_in * 2 < 0x7FFFFFFFll && (int64_t)max_rows * N_pad * 2 < 0x7FFFFFFFll, CR_ERR_UNSUPPORTED,
+               "operand of %d rows exceeds the 2 GiB reach of 32-bit buffer offsets", max_rows);
     int rows, splits;
     split_plan(F_pad, N_pad, max_rows, rows, splits);
     Carver c(ws);
@@ -438,7 +504,7 @@ extern "C" cr_status cr_sage_linear_bwd(const cr_sage_layer *layer, const int32_
     TnArgs t;
     t.hdr = hdr; t.max_rows = max_rows; t.A0 = h_self; t.A1 = agg; t.lda = ld_in; t.K0 = F_pad; t.K2 = 2 * F_pad;
     t.Z = dz_bf16; t.N = N_pad; t.rows_per_split = rows; t.partial = partial; t.db_partial = db_partial;
-    hipLaunchKernelGGL(gemm_tn_kernel, dim3((2 * F_pad / 64) * (N_pad / 64), splits), dim3(256), 0, s, t);
+    hipLaunchKernelGGL(gemm_tn_kernel, dim3((unsigned)(2 * ceil_div(F_pad, 128) * ceil_div(N_pad, 128)), splits), dim3(256), 0, s, t);
     SgdArgs g;
     g.hdr = hdr; g.max_rows = max_rows; g.rows_per_split = rows; g.n_splits = splits; g.partial = partial; g.db_partial = db_partial;
     g.F_in = layer->F_in; g.F_out = layer->F_out; g.F_pad = F_pad; g.N_pad = N_pad; g.W = layer->W; g.bias = layer->bias;

@@ -296,6 +296,7 @@ struct DedupArgs {
     int64_t indptr_stride;
     int32_t *indices;
     int64_t indices_stride;
+    int32_t *gather_ids;      // [G][cap_nnz] or NULL
     int32_t *newcnt;          // [G][cap_dst]
     int32_t *newoff;          // [G][cap_dst+1]
     unsigned long long *newmask;
@@ -406,6 +407,7 @@ __global__ __launch_bounds__(256) void relabel_kernel(DedupArgs a)
     if (a.direct) local = (uint32_t)reinterpret_cast<const int32_t *>(table)[u];
     else table_find(table, a.table_bits, (uint32_t)u, local);
     a.indices[(int64_t)g * a.indices_stride + rstart + j] = (int32_t)local;
+    if (a.gather_ids) a.gather_ids[(int64_t)g * a.indices_stride + rstart + j] = u;
     if (a.tcount) atomicAdd(&a.tcount[(int64_t)g * a.t_stride + local], 1);
 }
 
@@ -629,7 +631,7 @@ extern "C" cr_status cr_sample_blocks(const cr_graph *graph, const cr_sample_cfg
         da.direct = p.direct ? 1 : 0;
         da.table = p.table; da.table_stride = p.table_stride; da.table_bits = p.table_bits[l];
         da.hdr = b.hdr; da.src_ids = b.src_ids; da.src_stride = b.cap_src;
-        da.indptr = b.indptr; da.indptr_stride = b.cap_dst + 1; da.indices = b.indices; da.indices_stride = b.cap_nnz;
+        da.indptr = b.indptr; da.indptr_stride = b.cap_dst + 1; da.indices = b.indices; da.indices_stride = b.cap_nnz; da.gather_ids = b.gather_ids;
         da.newcnt = p.cnt; da.newoff = p.newoff; da.newmask = p.newmask; da.row_stride = p.max_dst; da.off_stride = p.max_dst + 1;
         const bool tr = b.t_indptr != nullptr;
         da.tcount = tr ? p.tcount : nullptr; da.tfill = p.tfill; da.t_stride = p.max_src_t + 1;

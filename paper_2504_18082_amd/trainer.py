@@ -162,5 +162,5 @@ class _BlockSetView:
 
 def _view_block_set(b: B.BlockSet, n_batches: int) -> _BlockSetView:
     c = B.cr_block_set(n_batches, b.fanout, b.cap_dst, b.cap_src, b.cap_nnz, 0, B._ptr(b.hdr), B._ptr(b.src_ids),
-                       B._ptr(b.indptr), B._ptr(b.indices), B._ptr(b.t_indptr), B._ptr(b.t_indices))
+                       B._ptr(b.indptr), B._ptr(b.indices), B._ptr(b.t_indptr), B._ptr(b.t_indices), B._ptr(b.gather_ids))
     return _BlockSetView(c)

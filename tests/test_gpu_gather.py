@@ -44,7 +44,7 @@ def test_gather_fwd_indirect(torch_mod, tiny_workload, F, dtype):
         abs_table = np.abs(table)
     term_scale = oracle.gather_mean(blk, abs_table, indirect=True, F=F)      # mean |term| per element
 
-    bs = B.BlockSet.from_host(blk, 10)
+    bs = B.BlockSet.from_host(blk, 10, gather_ids=(F % 2 == 0))     # both index paths: per-edge ids / src_ids[indices]
     dev_table = torch.from_numpy(table.view(np.int16) if dtype == "bf16" else table).cuda()
     ldb = (F + 31) // 32 * 32
     agg = torch.full((bs.cap_dst, F), np.nan, dtype=torch.float32, device="cuda")

@@ -42,6 +42,7 @@ def compare(layers, n_batches, graph, roots, fanouts, p, strict, seed, epoch, fi
     pos = np.full(len(graph[0]) - 1, -1, dtype=np.int32)
     host = [dict(hdr=b.hdr.cpu().numpy(), src=b.src_ids.cpu().numpy(), indptr=b.indptr.cpu().numpy(),
                  indices=b.indices.cpu().numpy(),
+                 gather_ids=None if b.gather_ids is None else b.gather_ids.cpu().numpy(),
                  t_indptr=None if b.t_indptr is None else b.t_indptr.cpu().numpy(),
                  t_indices=None if b.t_indices is None else b.t_indices.cpu().numpy()) for b in layers]
     for g in range(n_batches):
@@ -54,6 +55,8 @@ def compare(layers, n_batches, graph, roots, fanouts, p, strict, seed, epoch, fi
             assert np.array_equal(h["src"][g, :blk.n_src], blk.src_ids), tag + " src_ids"
             assert np.array_equal(h["indptr"][g, :blk.n_dst + 1], blk.indptr), tag + " indptr"
             assert np.array_equal(h["indices"][g, :blk.nnz], blk.indices), tag + " indices"
+            if h["gather_ids"] is not None:
+                assert np.array_equal(h["gather_ids"][g, :blk.nnz], blk.src_ids[blk.indices]), tag + " gather_ids"
             if l >= 1:
                 assert np.array_equal(h["t_indptr"][g, :blk.n_src + 1], blk.t_indptr), tag + " t_indptr"
                 assert np.array_equal(h["t_indices"][g, :blk.nnz], blk.t_indices), tag + " t_indices"
