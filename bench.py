@@ -36,7 +36,7 @@ def gather0_bytes(hdr0, n_feat, elem_bytes, f_pad):
     return reads + writes, (nnz + n_dst) * n_feat * elem_bytes
 
 
-def run_setting(tr, policy, mix, p, steps, warmup, epoch0):
+def run_setting(tr, policy, mix, p, steps, warmup, epoch0, serial=False):
     """Times `steps` steps (after `warmup` untimed ones) of one knob setting."""
     import torch
     from paper_2504_18082_amd import binding as B
@@ -44,21 +44,25 @@ def run_setting(tr, policy, mix, p, steps, warmup, epoch0):
     stats = dict(gather_bytes=0, feat_bytes=0, n_src0=0, rows0=0, launches=0)
 
     def run(n_steps, epoch, timed):
-        # one "epoch" = build the permutation, then walk the batches group by group
+        # whole epochs (root partitioning, then the batches group by group) until n_steps steps are done
         done = 0
-        tr.build_batches(policy, mix, epoch)
+        collect = (lambda n, slot: hdrs.append((n, tr.block_slots[slot][0].hdr.clone()))) if timed else None
         while done < n_steps:
-            b = done % tr.n_batches
-            if b == 0 and done > 0:
-                epoch += 1
-                tr.build_batches(policy, mix, epoch)
-            n = min(G, n_steps - done, tr.n_batches - b)
-            tr.sample_group(b, n, p, epoch)
-            for g in range(n):
-                tr.train_batch(g)
-            if timed:
-                hdrs.append((n, tr.blocks[0].hdr.clone()))
-            done += n
+            if serial:
+                nb = tr.build_batches(policy, mix, epoch)
+                first = 0
+                while first < min(nb, n_steps - done):
+                    n = min(tr.G, min(nb, n_steps - done) - first)
+                    tr.sample_group(first, n, p, epoch, slot=0)
+                    for g in range(n):
+                        tr.train_batch(g, slot=0)
+                    if collect:
+                        collect(n, 0)
+                    first += n
+                done += first
+            else:
+                done += tr.run_epoch(policy, mix, p, epoch, max_batches=n_steps - done, on_group=collect)
+            epoch += 1
         return epoch
 
     hdrs = []
@@ -124,6 +128,9 @@ def main():
     ap.add_argument("--group", type=int, default=16)
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-sweep", action="store_true")
+    ap.add_argument("--overlap", action="store_true",
+                    help="issue sampling and the layer-0 gather on side streams so that they overlap with training "
+                         "(default: every call on one stream, which keeps the per-kernel timing clean)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-batches", type=int, default=1)
     ap.add_argument("--calibration-copy", action="store_true",
@@ -159,12 +166,12 @@ def main():
         del src, dst
 
     # headline: the fully random setting (RAND-ROOTS, p = 0.5), the paper's baseline
-    main_res = run_setting(tr, B.CR_ROOTS_RAND, 1, 0.5, steps, args.warmup, 0)
+    main_res = run_setting(tr, B.CR_ROOTS_RAND, 1, 0.5, steps, args.warmup, 0, not args.overlap)
     sweep = []
     if not args.no_sweep:
         for name, policy, mix, p in (("mid: COMM-RAND-MIX-12.5% p=1.0", B.CR_ROOTS_COMM_RAND, mix_mid, 1.0),
                                      ("fully community: NORAND-ROOTS p=1.0", B.CR_ROOTS_NORAND, 1, 1.0)):
-            r = run_setting(tr, policy, mix, p, steps, min(args.warmup, 4), 50)
+            r = run_setting(tr, policy, mix, p, steps, min(args.warmup, 4), 50, not args.overlap)
             sweep.append(dict(setting=name, ms_per_step=round(r["ms_per_step"], 4),
                               epoch_ms=round(r["ms_per_step"] * tr.n_batches, 3),
                               speedup_vs_random=round(main_res["ms_per_step"] / r["ms_per_step"], 3),
@@ -198,6 +205,7 @@ def main():
                                f"features, {len(cfg.fanouts)}-layer GraphSAGE-mean hidden {cfg.hidden}, fanout {cfg.fanouts}, "
                                f"batch {cfg.batch_size}, {tr.n_batches} batches/epoch",
                    "setting": "fully random: RAND-ROOTS p=0.5", "group_size": args.group,
+                   "schedule": "sampling and layer-0 gather on side streams, overlapped with training" if args.overlap else "one stream",
                    "value_definition": "layer-0 gathered feature bytes per second of whole-step time"},
         "epoch_ms": round(main_res["ms_per_step"] * tr.n_batches, 3),
         "mean_input_nodes": round(main_res["mean_input_nodes"], 1),

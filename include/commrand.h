@@ -199,13 +199,13 @@ cr_status cr_gather_aggregate_fwd(const cr_block_set *blocks, int32_t g, const v
  *   d_src[u] = sum_{v : u in N_s(v)} d_agg[v] / |N_s(v)|   (+ d_self[u] for u < n_dst)
  *   d_agg, d_self : device float [cap_dst][ld_in] (d_self may be NULL)
  *   d_src         : device float [cap_src][F] or NULL, rows 0..n_src-1 fully overwritten
- *   relu_out      : device float [cap_src][ld_relu] or NULL: forward output of the layer below; where it
- *                   is <= 0 the gradient is zeroed (ReLU backward)
+ *   relu_out      : device float or bf16 (relu_dtype) [cap_src][ld_relu] or NULL: forward output of the layer
+ *                   below; where it is <= 0 the gradient is zeroed (ReLU backward)
  *   d_src_bf16    : device bf16 [cap_src][ld_bf16] or NULL (same masking, zero padded columns) */
 cr_status cr_gather_aggregate_bwd(const cr_block_set *blocks, int32_t g, const float *d_agg,
-                                  const float *d_self, int64_t ld_in, int32_t F, const float *relu_out,
-                                  int64_t ld_relu, float *d_src, uint16_t *d_src_bf16, int64_t ld_bf16,
-                                  void *stream);
+                                  const float *d_self, int64_t ld_in, int32_t F, const void *relu_out,
+                                  int32_t relu_dtype, int64_t ld_relu, float *d_src, uint16_t *d_src_bf16,
+                                  int64_t ld_bf16, void *stream);
 
 /* One GraphSAGE layer's parameters.  F_pad = F_in rounded up to 32, N_pad = F_out rounded up to 64. */
 typedef struct {

@@ -94,7 +94,7 @@ def lib():
                                        vp, C.c_size_t, C.POINTER(cr_block_set), vp]
         L.cr_gather_aggregate_fwd.argtypes = [C.POINTER(cr_block_set), i32, vp, i32, i64, i32, i32, vp, vp,
                                               vp, i64, vp]
-        L.cr_gather_aggregate_bwd.argtypes = [C.POINTER(cr_block_set), i32, vp, vp, i64, i32, vp, i64, vp,
+        L.cr_gather_aggregate_bwd.argtypes = [C.POINTER(cr_block_set), i32, vp, vp, i64, i32, vp, i32, i64, vp,
                                               vp, i64, vp]
         L.cr_sage_padded_dims.argtypes = [i32, i32, C.POINTER(i32), C.POINTER(i32)]
         L.cr_sage_refresh_shadows.argtypes = [C.POINTER(cr_sage_layer), vp]
@@ -254,9 +254,9 @@ def cr_gather_aggregate_fwd(blocks: BlockSet, g, H_src, dtype, ld_src, F, indire
 
 
 def cr_gather_aggregate_bwd(blocks: BlockSet, g, d_agg, d_self, ld_in, F, relu_out=None, ld_relu=0, d_src=None,
-                            d_src_bf16=None, ld_bf16=0, stream=None):
+                            d_src_bf16=None, ld_bf16=0, stream=None, relu_dtype=CR_F32):
     _check(lib().cr_gather_aggregate_bwd(C.byref(blocks.c), g, _ptr(d_agg), _ptr(d_self), ld_in, F,
-                                         _ptr(relu_out), ld_relu, _ptr(d_src), _ptr(d_src_bf16), ld_bf16,
+                                         _ptr(relu_out), relu_dtype, ld_relu, _ptr(d_src), _ptr(d_src_bf16), ld_bf16,
                                          _stream(stream)))
 
 

@@ -64,7 +64,7 @@ __global__ __launch_bounds__(256) void gather_mean_fwd_kernel(
     constexpr int VEC = Vec16<T>::N;
     constexpr int U = NCHUNK == 1 ? 8 : (NCHUNK <= 3 ? 4 : 2);   // independent row loads in flight per lane
     constexpr int GPB = 256 / LPR;                                // groups (rows in progress) per workgroup
-    const int n_dst = hdr[CR_HDR_N_DST];
+    const int n_dst = hdr[CR_HDR_N_DST], n_src = hdr[CR_HDR_N_SRC];
     if (n_dst <= 0) return;
     const uint32_t lb = xcd_remap(blockIdx.x, gridDim.x);
     const int rows_per_block = (int)(((int64_t)n_dst + gridDim.x - 1) / gridDim.x + GPB - 1) / GPB * GPB;
@@ -85,7 +85,7 @@ __global__ __launch_bounds__(256) void gather_mean_fwd_kernel(
     auto load_ids = [&](int first, int e) -> int {
         const int idx = max(min(first + gl, e - 1), 0);
         int x = ids[idx];
-        if (edge_map) x = edge_map[x];
+        if (edge_map) x = edge_map[min(max(x, 0), n_src - 1)];   // (a lane past the row's end may have read a stale entry)
         return x;
     };
 
@@ -197,99 +197,136 @@ __global__ __launch_bounds__(256) void gather_mean_bwd_kernel(
     const int32_t *__restrict__ hdr, const int32_t *__restrict__ indptr,
     const int32_t *__restrict__ t_indptr, const int32_t *__restrict__ t_indices,
     const float *__restrict__ d_agg, const float *__restrict__ d_self, int64_t ld_in, int F,
-    const float *__restrict__ relu_out, int64_t ld_relu, float *__restrict__ d_src,
+    const void *__restrict__ relu_out, int relu_is_bf16, int64_t ld_relu, float *__restrict__ d_src,
     uint16_t *__restrict__ d_src_bf16, int64_t ld_bf16)
 {
     constexpr int VEC = 4;
     constexpr int U = NCHUNK == 1 ? 8 : (NCHUNK <= 3 ? 4 : 2);
-    constexpr int ROWS_PER_BLOCK = 256 / LPR;
+    constexpr int GPB = 256 / LPR;
     const int n_dst = hdr[CR_HDR_N_DST], n_src = hdr[CR_HDR_N_SRC];
+    if (n_src <= 0) return;
     const uint32_t lb = xcd_remap(blockIdx.x, gridDim.x);
-    const int s = (int)(lb * ROWS_PER_BLOCK + threadIdx.x / LPR);
-    if (s >= n_src) return;
+    const int rows_per_block = (int)(((int64_t)n_src + gridDim.x - 1) / gridDim.x + GPB - 1) / GPB * GPB;
+    const int block_first = (int)lb * rows_per_block;
+    const int block_end = min(n_src, block_first + rows_per_block);
     const int gl = (int)(threadIdx.x % LPR);
+    int s = block_first + (int)(threadIdx.x / LPR);
+    if (s >= block_end) return;
 
-    float acc[NCHUNK][VEC];
-#pragma unroll
-    for (int c = 0; c < NCHUNK; ++c)
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) acc[c][i] = 0.f;
+    // same pipelining as the forward kernel: destination ids and their 1/degree weights of the next
+    // source row, and the segment pointers of the one after, are fetched while the current rows stream in
+    auto load_ptrs = [&](int r, int &b, int &e) {
+        const int rc = min(r, n_src - 1);
+        const int x = t_indptr[rc], y = t_indptr[rc + 1];
+        b = r < block_end ? x : 0;
+        e = r < block_end ? y : 0;
+    };
+    auto load_ids = [&](int first, int e, int &v, float &w) {
+        const int idx = max(min(first + gl, e - 1), 0);
+        v = min(max(t_indices[idx], 0), n_dst - 1);               // (a lane past the segment's end may have read a stale entry)
+        const int deg = indptr[v + 1] - indptr[v];
+        w = 1.0f / (float)(deg > 0 ? deg : 1);
+    };
 
-    const int start = t_indptr[s], end = t_indptr[s + 1];
-    for (int base = start; base < end; base += LPR) {
-        const int e = base + gl;
-        int v = 0;
-        float w = 0.f;
-        if (e < end) {
-            v = t_indices[e];
-            w = 1.0f / (float)(indptr[v + 1] - indptr[v]);
-        }
-        const int cnt = min(LPR, end - base);
-        for (int t = 0; t < cnt; t += U) {
-            float4 x[U][NCHUNK];
-            float ww[U];
+    int b0, e0, b1, e1, v0, v1;
+    float w0, w1;
+    load_ptrs(s, b0, e0);
+    load_ids(b0, e0, v0, w0);
+    load_ptrs(s + GPB, b1, e1);
+
+    for (; s < block_end; s += GPB) {
+        load_ids(b1, e1, v1, w1);
+        int b2, e2;
+        load_ptrs(s + 2 * GPB, b2, e2);
+
+        float acc[NCHUNK][VEC];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int vv = __shfl(v, t + u, LPR);
-                ww[u] = __shfl(w, t + u, LPR);
-                const float *p = d_agg + (int64_t)vv * ld_in;
+        for (int c = 0; c < NCHUNK; ++c)
 #pragma unroll
-                for (int c = 0; c < NCHUNK; ++c) {
-                    const int col = (c * LPR + gl) * VEC;
-                    if (col < F && t + u < cnt) x[u][c] = *reinterpret_cast<const float4 *>(p + col);
-                }
-            }
+            for (int i = 0; i < VEC; ++i) acc[c][i] = 0.f;
+
+        int v = v0;
+        float w = w0;
+        for (int base = b0; base < e0; base += LPR) {
+            if (base > b0) load_ids(base, e0, v, w);
+            const int cnt = min(LPR, e0 - base);
+            for (int t = 0; t < cnt; t += U) {
+                float4 x[U][NCHUNK];
+                float ww[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u)
+                for (int u = 0; u < U; ++u) {
+                    const int vv = __shfl(v, t + u, LPR);
+                    ww[u] = __shfl(w, t + u, LPR);
+                    const float *p = d_agg + (int64_t)vv * ld_in;
 #pragma unroll
-                for (int c = 0; c < NCHUNK; ++c) {
-                    const int col = (c * LPR + gl) * VEC;
-                    if (col < F && t + u < cnt) {
-                        acc[c][0] += x[u][c].x * ww[u]; acc[c][1] += x[u][c].y * ww[u];
-                        acc[c][2] += x[u][c].z * ww[u]; acc[c][3] += x[u][c].w * ww[u];
+                    for (int c = 0; c < NCHUNK; ++c) {
+                        const int col = (c * LPR + gl) * VEC;
+                        if (col < F && t + u < cnt) x[u][c] = *reinterpret_cast<const float4 *>(p + col);
                     }
                 }
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+#pragma unroll
+                    for (int c = 0; c < NCHUNK; ++c) {
+                        const int col = (c * LPR + gl) * VEC;
+                        if (col < F && t + u < cnt) {
+                            acc[c][0] += x[u][c].x * ww[u]; acc[c][1] += x[u][c].y * ww[u];
+                            acc[c][2] += x[u][c].z * ww[u]; acc[c][3] += x[u][c].w * ww[u];
+                        }
+                    }
+            }
         }
-    }
 #pragma unroll
-    for (int c = 0; c < NCHUNK; ++c) {
-        const int col = (c * LPR + gl) * VEC;
-        if (col < F) {
-            if (d_self && s < n_dst) {
-                const float4 x = *reinterpret_cast<const float4 *>(d_self + (int64_t)s * ld_in + col);
-                acc[c][0] += x.x; acc[c][1] += x.y; acc[c][2] += x.z; acc[c][3] += x.w;
-            }
-            if (relu_out) {
-                const float4 y = *reinterpret_cast<const float4 *>(relu_out + (int64_t)s * ld_relu + col);
-                if (!(y.x > 0.f)) acc[c][0] = 0.f;
-                if (!(y.y > 0.f)) acc[c][1] = 0.f;
-                if (!(y.z > 0.f)) acc[c][2] = 0.f;
-                if (!(y.w > 0.f)) acc[c][3] = 0.f;
-            }
-            if (d_src) {
-                float *o = d_src + (int64_t)s * F + col;
-                if ((F & 3) == 0) {
-                    *reinterpret_cast<float4 *>(o) = make_float4(acc[c][0], acc[c][1], acc[c][2], acc[c][3]);
-                } else {
+        for (int c = 0; c < NCHUNK; ++c) {
+            const int col = (c * LPR + gl) * VEC;
+            if (col < F) {
+                if (d_self && s < n_dst) {
+                    const float4 x = *reinterpret_cast<const float4 *>(d_self + (int64_t)s * ld_in + col);
+                    acc[c][0] += x.x; acc[c][1] += x.y; acc[c][2] += x.z; acc[c][3] += x.w;
+                }
+                if (relu_out) {
+                    float4 y;
+                    if (relu_is_bf16) {
+                        const uint2 h = *reinterpret_cast<const uint2 *>(static_cast<const uint16_t *>(relu_out) + (int64_t)s * ld_relu + col);
+                        y = make_float4(__uint_as_float(h.x << 16), __uint_as_float(h.x & 0xFFFF0000u),
+                                        __uint_as_float(h.y << 16), __uint_as_float(h.y & 0xFFFF0000u));
+                    } else {
+                        y = *reinterpret_cast<const float4 *>(static_cast<const float *>(relu_out) + (int64_t)s * ld_relu + col);
+                    }
+                    if (!(y.x > 0.f)) acc[c][0] = 0.f;
+                    if (!(y.y > 0.f)) acc[c][1] = 0.f;
+                    if (!(y.z > 0.f)) acc[c][2] = 0.f;
+                    if (!(y.w > 0.f)) acc[c][3] = 0.f;
+                }
+                if (d_src) {
+                    float *o = d_src + (int64_t)s * F + col;
+                    if ((F & 3) == 0) {
+                        *reinterpret_cast<float4 *>(o) = make_float4(acc[c][0], acc[c][1], acc[c][2], acc[c][3]);
+                    } else {
 #pragma unroll
-                    for (int i = 0; i < VEC; ++i)
-                        if (col + i < F) o[i] = acc[c][i];
+                        for (int i = 0; i < VEC; ++i)
+                            if (col + i < F) o[i] = acc[c][i];
+                    }
                 }
             }
+            if (d_src_bf16 && col < ld_bf16) store_bf16_row<VEC>(d_src_bf16 + (int64_t)s * ld_bf16 + col, acc[c], col, F);
         }
-        if (d_src_bf16 && col < ld_bf16) store_bf16_row<VEC>(d_src_bf16 + (int64_t)s * ld_bf16 + col, acc[c], col, F);
+
+        b0 = b1; e0 = e1; v0 = v1; w0 = w1;
+        b1 = b2; e1 = e2;
     }
 }
 
 template <int LPR, int NCHUNK>
 static void launch_bwd(int cap_src, const int32_t *hdr, const int32_t *indptr, const int32_t *t_indptr,
                        const int32_t *t_indices, const float *d_agg, const float *d_self, int64_t ld_in, int F,
-                       const float *relu_out, int64_t ld_relu, float *d_src, uint16_t *d_src_bf16,
+                       const void *relu_out, int relu_is_bf16, int64_t ld_relu, float *d_src, uint16_t *d_src_bf16,
                        int64_t ld_bf16, hipStream_t st)
 {
-    const unsigned grid = (unsigned)ceil_div(cap_src, 256 / LPR);
-    hipLaunchKernelGGL((gather_mean_bwd_kernel<LPR, NCHUNK>), dim3(grid), dim3(256), 0, st, hdr, indptr, t_indptr,
-                       t_indices, d_agg, d_self, ld_in, F, relu_out, ld_relu, d_src, d_src_bf16, ld_bf16);
+    int64_t grid = ceil_div(cap_src, 256 / LPR);
+    if (grid > 1024) grid = 1024;
+    hipLaunchKernelGGL((gather_mean_bwd_kernel<LPR, NCHUNK>), dim3((unsigned)grid), dim3(256), 0, st, hdr, indptr, t_indptr,
+                       t_indices, d_agg, d_self, ld_in, F, relu_out, relu_is_bf16, ld_relu, d_src, d_src_bf16, ld_bf16);
 }
 
 }  // namespace cr
@@ -361,7 +398,7 @@ extern "C" cr_status cr_gather_aggregate_fwd(const cr_block_set *blocks, int32_t
 
 extern "C" cr_status cr_gather_aggregate_bwd(const cr_block_set *blocks, int32_t g, const float *d_agg,
                                              const float *d_self, int64_t ld_in, int32_t F,
-                                             const float *relu_out, int64_t ld_relu, float *d_src,
+                                             const void *relu_out, int32_t relu_dtype, int64_t ld_relu, float *d_src,
                                              uint16_t *d_src_bf16, int64_t ld_bf16, void *stream)
 {
     cr_status st = check_block_set(blocks, g, true);
@@ -369,7 +406,10 @@ extern "C" cr_status cr_gather_aggregate_bwd(const cr_block_set *blocks, int32_t
     CR_REQUIRE(d_agg != nullptr && aligned16(d_agg) && aligned16(d_self), CR_ERR_INVALID_ARG, "d_agg / d_self must be 16-byte aligned device pointers");
     CR_REQUIRE(F >= 1 && F <= 1024, CR_ERR_UNSUPPORTED, "F = %d outside 1..1024", F);
     CR_REQUIRE(ld_in >= round_up(F, 4) && ld_in % 4 == 0, CR_ERR_INVALID_ARG, "ld_in must be a multiple of 4 covering F");
-    if (relu_out) CR_REQUIRE(aligned16(relu_out) && ld_relu >= round_up(F, 4) && ld_relu % 4 == 0, CR_ERR_INVALID_ARG, "relu_out must be aligned with ld_relu a multiple of 4 covering F");
+    if (relu_out) {
+        CR_REQUIRE(relu_dtype == CR_F32 || relu_dtype == CR_BF16, CR_ERR_INVALID_ARG, "relu_dtype must be CR_F32 or CR_BF16");
+        CR_REQUIRE(aligned16(relu_out) && ld_relu >= round_up(F, 4) && ld_relu % 4 == 0, CR_ERR_INVALID_ARG, "relu_out must be aligned with ld_relu a multiple of 4 covering F");
+    }
     CR_REQUIRE(d_src || d_src_bf16, CR_ERR_INVALID_ARG, "no output requested");
     CR_REQUIRE(aligned16(d_src) && aligned16(d_src_bf16), CR_ERR_INVALID_ARG, "outputs must be 16-byte aligned");
     if (d_src_bf16)
@@ -383,7 +423,7 @@ extern "C" cr_status cr_gather_aggregate_bwd(const cr_block_set *blocks, int32_t
     const int32_t *t_indices = blocks->t_indices + (int64_t)g * blocks->cap_nnz;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int cap = blocks->cap_src;
-#define CR_BWD(LPR, NC) launch_bwd<LPR, NC>(cap, hdr, indptr, t_indptr, t_indices, d_agg, d_self, ld_in, F, relu_out, ld_relu, d_src, d_src_bf16, ld_bf16, s)
+#define CR_BWD(LPR, NC) launch_bwd<LPR, NC>(cap, hdr, indptr, t_indptr, t_indices, d_agg, d_self, ld_in, F, relu_out, relu_dtype == CR_BF16 ? 1 : 0, ld_relu, d_src, d_src_bf16, ld_bf16, s)
     if (F <= 64) CR_BWD(16, 1);
     else if (F <= 128) CR_BWD(32, 1);
     else if (F <= 256) CR_BWD(64, 1);

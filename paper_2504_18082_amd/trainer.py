@@ -1,6 +1,11 @@
 """Epoch driver: sequences the C-ABI calls of Algorithm 1 (root partitioning, grouped sub-graph
 sampling, then forward / loss / backward / SGD per mini-batch).  Call sequencing and buffer
 ownership only -- every arithmetic step runs inside libcommrand.so.
+
+Sampling and the layer-0 feature gather do not depend on the weights, so `run_epoch` issues them on
+two side streams (default priority) ahead of the training stream: while mini-batch b trains, the
+features of b+1 are being gathered and the next group of mini-batches is being sampled.  Block
+storage and the layer-0 operand buffers are double-buffered for this; HIP events order the hand-offs.
 """
 from __future__ import annotations
 
@@ -52,15 +57,20 @@ class Trainer:
 
         # step 2: block storage for one group of batches
         scfg = B.make_sample_cfg(cfg.fanouts, 0.5, seed, 0)
-        self.blocks = B.alloc_block_sets(scfg, self.n_nodes, self.B, self.G, device)
+        self.block_slots = [B.alloc_block_sets(scfg, self.n_nodes, self.B, self.G, device) for _ in range(2)]
+        self.blocks = self.block_slots[0]
         self.ws_sample = torch.empty(B.cr_sample_blocks_workspace_bytes(scfg, self.n_nodes, self.B, self.G), dtype=torch.uint8, device=device)
 
         # activations / gradients, sized by the per-batch capacities
         f32 = lambda r, c: torch.zeros((r, c), dtype=torch.float32, device=device)
         b16 = lambda r, c: torch.zeros((r, c), dtype=torch.int16, device=device)
-        self.self0 = b16(self.blocks[0].cap_dst, self.layers[0].F_pad)
+        self.self0_bufs = [b16(self.blocks[0].cap_dst, self.layers[0].F_pad) for _ in range(2)]
+        self.agg0_bufs = [b16(self.blocks[0].cap_dst, self.layers[0].F_pad) for _ in range(2)]
+        self.self0 = self.self0_bufs[0]
         self.agg = [b16(self.blocks[l].cap_dst, self.layers[l].F_pad if l == 0 else self.layers[l - 1].N_pad) for l in range(self.L)]
-        self.out = [f32(self.blocks[l].cap_dst, self.layers[l].N_pad) for l in range(self.L)]
+        # hidden activations are kept in bf16 only (next layer's self operand, aggregation input and
+        # ReLU mask); the logits of the last layer stay in float for the loss
+        self.out = [f32(self.blocks[l].cap_dst, self.layers[l].N_pad) if l == self.L - 1 else None for l in range(self.L)]
         self.out_b = [b16(self.blocks[l].cap_dst, self.layers[l].N_pad) if l < self.L - 1 else None for l in range(self.L)]
         self.dz = [b16(self.blocks[l].cap_dst, self.layers[l].N_pad) for l in range(self.L)]
         self.d_self = [f32(self.blocks[l].cap_dst, self.layers[l].F_pad) if l >= 1 else None for l in range(self.L)]
@@ -69,8 +79,11 @@ class Trainer:
                                    dtype=torch.uint8, device=device) for l in range(self.L)]
         self.loss = torch.zeros(1, dtype=torch.float32, device=device)
         self.row_loss = torch.zeros(self.B, dtype=torch.float32, device=device)
+        self.agg[0] = self.agg0_bufs[0]
         self.gather0_events = []          # (start, stop) pairs around the layer-0 gather when timing is on
         self.time_gather0 = False
+        self.stream_sample = torch.cuda.Stream(device=device)
+        self.stream_gather = torch.cuda.Stream(device=device)
 
     # ------------------------------------------------------------------ step 1
     def build_batches(self, policy: int, mix_count: int, epoch: int) -> int:
@@ -78,9 +91,11 @@ class Trainer:
                                   self.ws_batches, self.perm)
 
     # ------------------------------------------------------------------ step 2
-    def sample_group(self, first_batch: int, n_batches: int, p_intra: float, epoch: int, flags: int = 0):
-        """Samples mini-batches first_batch .. first_batch+n_batches-1 of the current permutation."""
+    def sample_group(self, first_batch: int, n_batches: int, p_intra: float, epoch: int, flags: int = 0, slot: int = 0):
+        """Samples mini-batches first_batch .. first_batch+n_batches-1 of the current permutation into
+        block storage `slot` (on the current stream)."""
         assert 1 <= n_batches <= self.G
+        self.blocks = self.block_slots[slot]
         scfg = B.make_sample_cfg(self.cfg.fanouts, p_intra, self.seed, epoch, first_batch, flags)
         start = first_batch * self.B
         n_roots = min(self.n_train, start + n_batches * self.B) - start
@@ -93,24 +108,36 @@ class Trainer:
                                           B._ptr(self.ws_sample), self.ws_sample.numel(), arr, B._stream()))
 
     # ------------------------------------------------------------------ training on one sub-graph
-    def train_batch(self, g: int, dW_out=None, db_out=None):
+    def gather_layer0(self, g: int, slot: int = 0, buf: int = 0):
+        """Feature gather + mean aggregation of mini-batch g of block slot `slot` into operand buffer `buf`."""
+        blk, lay = self.block_slots[slot][0], self.layers[0]
+        if self.time_gather0:
+            ev0, ev1 = self.torch.cuda.Event(enable_timing=True), self.torch.cuda.Event(enable_timing=True)
+            ev0.record()
+        B.cr_gather_aggregate_fwd(blk, g, self.table, self.feat_dtype, self.ld_table, self.cfg.n_feat, True,
+                                  None, self.agg0_bufs[buf], self.self0_bufs[buf], lay.F_pad)
+        if self.time_gather0:
+            ev1.record()
+            self.gather0_events.append((ev0, ev1))
+
+    def train_batch(self, g: int, dW_out=None, db_out=None, slot: Optional[int] = None, buf: int = 0, gather0: bool = True):
+        """Forward, loss, backward and SGD for mini-batch g of a sampled group (current stream)."""
+        if slot is not None:
+            self.blocks = self.block_slots[slot]
+        else:
+            slot = self.block_slots.index(self.blocks)
+        self.self0, self.agg[0] = self.self0_bufs[buf], self.agg0_bufs[buf]
         L, blocks, layers = self.L, self.blocks, self.layers
         # forward
         for l in range(L):
             blk, lay = blocks[l], layers[l]
             if l == 0:
-                if self.time_gather0:
-                    ev0, ev1 = self.torch.cuda.Event(enable_timing=True), self.torch.cuda.Event(enable_timing=True)
-                    ev0.record()
-                B.cr_gather_aggregate_fwd(blk, g, self.table, self.feat_dtype, self.ld_table, self.cfg.n_feat, True,
-                                          None, self.agg[0], self.self0, lay.F_pad)
-                if self.time_gather0:
-                    ev1.record()
-                    self.gather0_events.append((ev0, ev1))
+                if gather0:
+                    self.gather_layer0(g, slot, buf)
                 h_self, ld_in = self.self0, lay.F_pad
             else:
                 prev = layers[l - 1]
-                B.cr_gather_aggregate_fwd(blk, g, self.out[l - 1], B.CR_F32, prev.N_pad, prev.F_out, False,
+                B.cr_gather_aggregate_fwd(blk, g, self.out_b[l - 1], B.CR_BF16, prev.N_pad, prev.F_out, False,
                                           None, self.agg[l], None, prev.N_pad)
                 h_self, ld_in = self.out_b[l - 1], prev.N_pad
             B.cr_sage_linear_fwd(lay, blk.hdr_ptr(g), blk.cap_dst, h_self, self.agg[l], ld_in, l < L - 1,
@@ -131,11 +158,12 @@ class Trainer:
                                  None if dW_out is None else dW_out[l], None if db_out is None else db_out[l])
             if l >= 1:
                 prev = layers[l - 1]
-                B.cr_gather_aggregate_bwd(blk, g, self.d_agg[l], self.d_self[l], lay.F_pad, lay.F_in, self.out[l - 1],
-                                          prev.N_pad, None, self.dz[l - 1], prev.N_pad)
+                B.cr_gather_aggregate_bwd(blk, g, self.d_agg[l], self.d_self[l], lay.F_pad, lay.F_in, self.out_b[l - 1],
+                                          prev.N_pad, None, self.dz[l - 1], prev.N_pad, relu_dtype=B.CR_BF16)
 
     # ------------------------------------------------------------------ one epoch
-    def run_epoch(self, policy: int, mix_count: int, p_intra: float, epoch: int, max_batches: Optional[int] = None):
+    def run_epoch_serial(self, policy: int, mix_count: int, p_intra: float, epoch: int, max_batches: Optional[int] = None):
+        """Everything on the current stream, one call after the other."""
         nb = self.build_batches(policy, mix_count, epoch)
         if max_batches is not None:
             nb = min(nb, max_batches)
@@ -146,6 +174,74 @@ class Trainer:
             for g in range(n):
                 self.train_batch(g)
             done += n
+        return nb
+
+    def run_epoch(self, policy: int, mix_count: int, p_intra: float, epoch: int, max_batches: Optional[int] = None,
+                  on_group=None):
+        """Overlapped schedule: root partitioning and sampling on one side stream, the layer-0 gather on
+        another, training on the current stream.  Same calls, same arguments, same results as
+        run_epoch_serial.  on_group(n, slot), if given, is called after a group's work is enqueued."""
+        torch = self.torch
+        main = torch.cuda.current_stream()
+        ss, sg = self.stream_sample, self.stream_gather
+        ev = lambda: torch.cuda.Event()
+        ss.wait_stream(main)
+        sg.wait_stream(main)
+        with torch.cuda.stream(ss):
+            nb = self.build_batches(policy, mix_count, epoch)
+        if max_batches is not None:
+            nb = min(nb, max_batches)
+        groups = [(first, min(self.G, nb - first)) for first in range(0, nb, self.G)]
+        sampled = [None, None]           # event: block slot holds a freshly sampled group
+        slot_free = [None, None]         # event: training and gathering no longer read the slot
+        gathered = [None, None]          # event: layer-0 operand buffer holds a batch
+        buf_free = [None, None]          # event: training no longer reads the operand buffer
+
+        def enqueue_sample(k):
+            first, n = groups[k]
+            slot = k % 2
+            with torch.cuda.stream(ss):
+                if slot_free[slot] is not None:
+                    ss.wait_event(slot_free[slot])
+                self.sample_group(first, n, p_intra, epoch, slot=slot)
+                sampled[slot] = ev()
+                sampled[slot].record(ss)
+
+        if groups:
+            enqueue_sample(0)
+        step = 0
+        for k, (first, n) in enumerate(groups):
+            slot = k % 2
+            if k + 1 < len(groups):
+                enqueue_sample(k + 1)
+            with torch.cuda.stream(sg):
+                sg.wait_event(sampled[slot])
+            main.wait_event(sampled[slot])
+            for g in range(n):
+                buf = step % 2
+                with torch.cuda.stream(sg):
+                    if buf_free[buf] is not None:
+                        sg.wait_event(buf_free[buf])
+                    self.gather_layer0(g, slot, buf)
+                    gathered[buf] = ev()
+                    gathered[buf].record(sg)
+                main.wait_event(gathered[buf])
+                self.train_batch(g, slot=slot, buf=buf, gather0=False)
+                buf_free[buf] = ev()
+                buf_free[buf].record(main)
+                step += 1
+            if on_group is not None:
+                on_group(n, slot)
+            done = ev()
+            done.record(main)               # training of the group is enqueued up to here ...
+            with torch.cuda.stream(sg):
+                fin = ev()
+                fin.record(sg)              # ... and so is its gathering
+            with torch.cuda.stream(ss):
+                ss.wait_event(fin)
+            slot_free[slot] = done
+        main.wait_stream(ss)
+        main.wait_stream(sg)
         return nb
 
     def headers(self):

@@ -1,6 +1,6 @@
 """One training step of the L-layer GraphSAGE-mean model written with the oracle's pieces only
 (test infrastructure; mirrors the precision points of the GPU path: bf16 operands into every
-contraction, float hidden activations into the next aggregation)."""
+contraction, hidden activations stored in bf16)."""
 import numpy as np
 
 import oracle
@@ -19,7 +19,7 @@ def oracle_train_step(graph, table, n_feat, labels, roots, fanouts, p, seed, epo
         if l == 0:
             aggs[0], h_self[0] = oracle.gather_mean(blk, table, indirect=True, F=n_feat, want_self=True)
         else:
-            prev = np.ascontiguousarray(outs[l - 1].astype(np.float32))       # the GPU aggregates float activations
+            prev = np.ascontiguousarray(oracle.round_bf16(outs[l - 1]).astype(np.float32))   # hidden activations live in bf16
             aggs[l] = oracle.gather_mean(blk, prev, indirect=False)
             h_self[l] = outs[l - 1][:blk.n_dst]
         outs[l] = oracle.sage_linear_fwd(h_self[l], aggs[l], W, b, l < L - 1, True)
@@ -33,5 +33,5 @@ def oracle_train_step(graph, table, n_feat, labels, roots, fanouts, p, seed, epo
         new_params[l] = oracle.sgd_step(W, dW, b, db, lr, wd)
         if l > 0:
             d_src = oracle.gather_mean_bwd(blocks[l], d_agg, d_self)
-            dz = d_src * (outs[l - 1] > 0)
+            dz = d_src * (oracle.round_bf16(outs[l - 1]) > 0)
     return dict(blocks=blocks, loss=loss, logits=outs[L - 1], outs=outs, grads=grads, params=new_params)

@@ -132,6 +132,13 @@ def test_gather_bwd(torch_mod, tiny_workload, F):
     B.cr_gather_aggregate_bwd(bs, 0, up(d_agg), up(d_self), ld_in, F, up(relu_out), ld_in, d_src, d_src_b, ld_in)
     torch.cuda.synchronize()
     assert_close(d_src.cpu().numpy(), want_masked, RTOL, "d_src masked")
+    # the mask may also come from a bf16 copy of the forward output
+    relu_b = torch.from_numpy(synth.float_to_bf16_bits(relu_out).view(np.int16)).cuda()
+    d_src2 = torch.full((bs.cap_src, F), np.nan, dtype=torch.float32, device="cuda")
+    B.cr_gather_aggregate_bwd(bs, 0, up(d_agg), up(d_self), ld_in, F, relu_b, ld_in, d_src2, None, 0, relu_dtype=B.CR_BF16)
+    torch.cuda.synchronize()
+    want_masked_b = want * (synth.bf16_bits_to_float(synth.float_to_bf16_bits(relu_out))[:, :F] > 0)
+    assert_close(d_src2.cpu().numpy(), want_masked_b, RTOL, "d_src masked by bf16")
     got_b = bf16_tensor_to_float(d_src_b)
     assert_close(got_b[:, :F], want_masked, RTOL_BF16, "d_src bf16")
     assert np.all(got_b[:, F:] == 0)

@@ -96,3 +96,24 @@ def test_arxiv_one_step_three_layers(arxiv_workload):
     w = copy.copy(arxiv_workload)
     tr = run_case(w, oracle.COMM_RAND, 62, 1.0, n_steps=1, group=2, lr=0.01)
     assert tr.L == 3
+
+
+def test_overlapped_epoch_equals_serial_epoch(tiny_workload):
+    # the three-stream schedule must give bit-identical weights to the one-stream schedule
+    import torch
+    from paper_2504_18082_amd.trainer import Trainer
+    w = tiny_workload
+    results = []
+    for overlapped in (False, True):
+        tr = Trainer(w, group_size=3, lr=0.05, seed=0, weights=synth.init_weights(w.cfg, 0))
+        for epoch in range(2):
+            if overlapped:
+                nb = tr.run_epoch(oracle.COMM_RAND, 6, 0.9, epoch)
+            else:
+                nb = tr.run_epoch_serial(oracle.COMM_RAND, 6, 0.9, epoch)
+        torch.cuda.synchronize()
+        assert nb == tr.n_batches
+        results.append([l.W.cpu().numpy().copy() for l in tr.layers] + [float(tr.loss.cpu()[0])])
+    for a, b in zip(results[0][:-1], results[1][:-1]):
+        assert np.array_equal(a, b)
+    assert results[0][-1] == results[1][-1]
