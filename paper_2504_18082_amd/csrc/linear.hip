@@ -2,6 +2,8 @@
 //   Z = H_self W_self + Agg W_neigh + b  (ReLU on hidden layers), its backward, a fused SGD step,
 // and the softmax cross-entropy on the root rows.  The contractions run on the bf16 matrix cores
 // (v_mfma_f32_32x32x16_bf16) with float accumulation; operands are staged through LDS.
+#include <type_traits>
+
 #include "cr_common.h"
 
 namespace cr {
@@ -41,7 +43,60 @@ struct NtArgs {
     int64_t ldcb;
 };
 
-__global__ __launch_bounds__(256) void gemm_nt_kernel(NtArgs a)
+struct NtState {
+    const uint16_t *A0, *A1;
+    int K0;
+    int64_t ga0, ga1;
+    const uint16_t *gb;
+    int kc, a_row0, a_row1, b_row, act_row, lr, half;
+};
+
+// one 32-wide K step: stage the three fetched pieces, barrier, MFMA
+__device__ __forceinline__ void nt_step(const NtState &st, const uint4 &ra0, const uint4 &ra1, const uint4 &rb, int &buf,
+                                        uint16_t (&As)[2][128][LDS_ROW], uint16_t (&Bs)[2][64][LDS_ROW], f32x16 (&acc)[2])
+{
+    *reinterpret_cast<uint4 *>(&As[buf][st.a_row0][st.kc * 8]) = ra0;
+    *reinterpret_cast<uint4 *>(&As[buf][st.a_row1][st.kc * 8]) = ra1;
+    *reinterpret_cast<uint4 *>(&Bs[buf][st.b_row][st.kc * 8]) = rb;
+    __syncthreads();               // tile `buf` is complete; everyone is also done reading tile `buf ^ 1`
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) {
+        const int ko = kk * 16 + 8 * st.half;
+        const bf16x8 act = lds_read8(&As[buf][st.act_row][ko]);
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const bf16x8 wgt = lds_read8(&Bs[buf][t * 32 + st.lr][ko]);
+            acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wgt, act, acc[t], 0, 0, 0);
+        }
+    }
+    buf ^= 1;
+}
+
+#define CR_NT_FETCH(i)                                                                                         \
+    const int k_##i = (s0 + i) * 32;                                                                           \
+    const uint16_t *src_##i = k_##i < st.K0 ? st.A0 + k_##i : st.A1 + (k_##i - st.K0);                         \
+    const uint4 ra0_##i = *reinterpret_cast<const uint4 *>(src_##i + st.ga0 + st.kc * 8);                      \
+    const uint4 ra1_##i = *reinterpret_cast<const uint4 *>(src_##i + st.ga1 + st.kc * 8);                      \
+    const uint4 rb_##i = *reinterpret_cast<const uint4 *>(st.gb + k_##i);
+#define CR_NT_STEP(i) nt_step(st, ra0_##i, ra1_##i, rb_##i, buf, As, Bs, acc);
+
+// eight consecutive K steps: every global load is issued before the first one is used
+__device__ __forceinline__ void nt_chunk8(const NtState &st, int s0, int &buf, uint16_t (&As)[2][128][LDS_ROW],
+                                          uint16_t (&Bs)[2][64][LDS_ROW], f32x16 (&acc)[2])
+{
+    CR_NT_FETCH(0) CR_NT_FETCH(1) CR_NT_FETCH(2) CR_NT_FETCH(3) CR_NT_FETCH(4) CR_NT_FETCH(5) CR_NT_FETCH(6) CR_NT_FETCH(7)
+    CR_NT_STEP(0) CR_NT_STEP(1) CR_NT_STEP(2) CR_NT_STEP(3) CR_NT_STEP(4) CR_NT_STEP(5) CR_NT_STEP(6) CR_NT_STEP(7)
+}
+__device__ __forceinline__ void nt_chunk1(const NtState &st, int s0, int &buf, uint16_t (&As)[2][128][LDS_ROW],
+                                          uint16_t (&Bs)[2][64][LDS_ROW], f32x16 (&acc)[2])
+{
+    CR_NT_FETCH(0)
+    CR_NT_STEP(0)
+}
+#undef CR_NT_FETCH
+#undef CR_NT_STEP
+
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) void gemm_nt_kernel(NtArgs a)
 {
     __shared__ __attribute__((aligned(16))) uint16_t As[2][128][LDS_ROW];
     __shared__ __attribute__((aligned(16))) uint16_t Bs[2][64][LDS_ROW];
@@ -49,6 +104,7 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(NtArgs a)
     const int m0 = blockIdx.y * 128, n0 = blockIdx.x * 64;
     if (m0 >= M) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int half = lane >> 5, lr = lane & 31;
 
     // staging assignment: A 128 rows x 4 chunks of 8, two per thread; B 64 rows x 4 chunks, one per thread
     const int a_row0 = tid >> 2, a_row1 = (tid + 256) >> 2, kc = tid & 3;
@@ -56,58 +112,35 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(NtArgs a)
     const int64_t ga1 = (int64_t)min(m0 + a_row1, M - 1) * a.lda;
     const uint16_t *gb = a.B + (int64_t)(n0 + (tid >> 2)) * a.K + kc * 8;
 
-    uint4 ra0, ra1, rb;
-    auto load_step = [&](int k0) {
-        const uint16_t *src = k0 < a.K0 ? a.A0 + k0 : a.A1 + (k0 - a.K0);
-        ra0 = *reinterpret_cast<const uint4 *>(src + ga0 + kc * 8);
-        ra1 = *reinterpret_cast<const uint4 *>(src + ga1 + kc * 8);
-        rb = *reinterpret_cast<const uint4 *>(gb + k0);
-    };
-    auto store_step = [&](int buf) {
-        *reinterpret_cast<uint4 *>(&As[buf][a_row0][kc * 8]) = ra0;
-        *reinterpret_cast<uint4 *>(&As[buf][a_row1][kc * 8]) = ra1;
-        *reinterpret_cast<uint4 *>(&Bs[buf][tid >> 2][kc * 8]) = rb;
-    };
-
     f32x16 acc[2];
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
 
+    // K is consumed in chunks of eight 32-wide steps (single steps for the remainder).  All
+    // global loads of a chunk are issued before the first one is used, so a chunk costs one memory
+    // round trip; its steps then go through double-buffered LDS tiles with one barrier each.
     const int nsteps = a.K / 32;
-    load_step(0);
-    store_step(0);
-    __syncthreads();
-    for (int step = 0; step < nsteps; ++step) {
-        const int buf = step & 1;
-        if (step + 1 < nsteps) load_step((step + 1) * 32);
-#pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-            const int ko = kk * 16 + 8 * (lane >> 5);
-            const bf16x8 act = lds_read8(&As[buf][wave * 32 + (lane & 31)][ko]);
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                const bf16x8 wgt = lds_read8(&Bs[buf][t * 32 + (lane & 31)][ko]);
-                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wgt, act, acc[t], 0, 0, 0);
-            }
-        }
-        if (step + 1 < nsteps) store_step(buf ^ 1);
-        __syncthreads();
-    }
+    int buf = 0;
+    NtState st{a.A0, a.A1, a.K0, ga0, ga1, gb, kc, a_row0, a_row1, tid >> 2, wave * 32 + lr, lr, half};
+    int s0 = 0;
+    for (; s0 + 8 <= nsteps; s0 += 8) nt_chunk8(st, s0, buf, As, Bs, acc);
+    for (; s0 < nsteps; ++s0) nt_chunk1(st, s0, buf, As, Bs, acc);
 
-    const int m = m0 + wave * 32 + (lane & 31);
+    const int m = m0 + wave * 32 + lr;
     if (m >= M) return;
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
         for (int grp = 0; grp < 4; ++grp) {
-            const int n = n0 + t * 32 + 8 * grp + 4 * (lane >> 5);
-            float v[4];
+            const int n = n0 + t * 32 + 8 * grp + 4 * half;
+            const float4 bq = a.bias ? *reinterpret_cast<const float4 *>(a.bias + n) : make_float4(0.f, 0.f, 0.f, 0.f);
+            float v[4] = {acc[t][grp * 4 + 0] + bq.x, acc[t][grp * 4 + 1] + bq.y,
+                          acc[t][grp * 4 + 2] + bq.z, acc[t][grp * 4 + 3] + bq.w};
+            if (a.relu) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                v[i] = acc[t][grp * 4 + i] + (a.bias ? a.bias[n + i] : 0.f);
-                if (a.relu && v[i] < 0.f) v[i] = 0.f;
+                for (int i = 0; i < 4; ++i) v[i] = v[i] < 0.f ? 0.f : v[i];
             }
             if (a.C0) {
                 float *dst = n < a.N0 ? a.C0 + (int64_t)m * a.ldc + n : a.C1 + (int64_t)m * a.ldc + (n - a.N0);
@@ -138,13 +171,13 @@ struct TnArgs {
     const uint16_t *Z;       // [M][N]
     int32_t N;
     int32_t rows_per_split;
-    float *partial;          // [S][K2][N]
-    float *db_partial;       // [S][N]
+    float *partial;          // [S][K2 + 1][N]: row K2 holds the column sums of Z (bias gradient)
 };
 
 __global__ __launch_bounds__(256) void gemm_tn_kernel(TnArgs a)
 {
-    __shared__ __attribute__((aligned(16))) uint16_t T[2][2][128][LDS_ROW];   // [buffer][operand: 0 = A, 1 = Z][column][m]
+    // [buffer][operand: 0 = A, 1 = Z][group of four m][column] -> four consecutive m of one column (8 bytes)
+    __shared__ __attribute__((aligned(16))) uint2 T[2][2][8][128];
     const int M = min(a.hdr[CR_HDR_N_DST], a.max_rows);
     const int split = blockIdx.y;
     const int m_begin = split * a.rows_per_split;
@@ -184,18 +217,33 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(TnArgs a)
             r[i] = make_uint4(v[0], v[1], v[2], v[3]);
         }
     };
+    // A thread holds an 8-column chunk of four consecutive rows; transposed, that is eight 8-byte cells
+    // (four m of one column), contiguous along the column index.  They go out as four 16-byte stores; the
+    // store order is rotated by the thread's chunk index so that neighbouring threads (64 bytes apart)
+    // do not hit the same LDS banks in the same instruction.
+    const int crot = st & 3;
     auto stage = [&](const uint4 (&r)[4], int buf) {
-        const uint32_t w[4][4] = {{r[0].x, r[0].y, r[0].z, r[0].w}, {r[1].x, r[1].y, r[1].z, r[1].w},
-                                  {r[2].x, r[2].y, r[2].z, r[2].w}, {r[3].x, r[3].y, r[3].z, r[3].w}};
+        // pair q = columns 2q and 2q+1; word q of a row holds column 2q (low half) and 2q+1 (high half)
+#define CR_PAIR(q, f)                                                                                   \
+        const uint32_t p##q##x = (r[0].f & 0xFFFFu) | (r[1].f << 16), p##q##y = (r[2].f & 0xFFFFu) | (r[3].f << 16), \
+                       p##q##z = (r[0].f >> 16) | (r[1].f & 0xFFFF0000u), p##q##w = (r[2].f >> 16) | (r[3].f & 0xFFFF0000u);
+        CR_PAIR(0, x) CR_PAIR(1, y) CR_PAIR(2, z) CR_PAIR(3, w)
+#undef CR_PAIR
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {              // word q holds columns 2q (low half) and 2q+1 (high half)
-            const uint32_t e_lo = (w[0][q] & 0xFFFFu) | (w[1][q] << 16);
-            const uint32_t e_hi = (w[2][q] & 0xFFFFu) | (w[3][q] << 16);
-            const uint32_t o_lo = (w[0][q] >> 16) | (w[1][q] & 0xFFFF0000u);
-            const uint32_t o_hi = (w[2][q] >> 16) | (w[3][q] & 0xFFFF0000u);
-            *reinterpret_cast<uint2 *>(&T[buf][op][sc + 2 * q][mg * 4]) = make_uint2(e_lo, e_hi);
-            *reinterpret_cast<uint2 *>(&T[buf][op][sc + 2 * q + 1][mg * 4]) = make_uint2(o_lo, o_hi);
+        for (int i = 0; i < 4; ++i) {
+            const int q = (i + crot) & 3;
+            const bool q1 = q == 1, q2 = q == 2, q3 = q == 3;
+            const uint32_t vx = q3 ? p3x : (q2 ? p2x : (q1 ? p1x : p0x));
+            const uint32_t vy = q3 ? p3y : (q2 ? p2y : (q1 ? p1y : p0y));
+            const uint32_t vz = q3 ? p3z : (q2 ? p2z : (q1 ? p1z : p0z));
+            const uint32_t vw = q3 ? p3w : (q2 ? p2w : (q1 ? p1w : p0w));
+            *reinterpret_cast<uint4 *>(&T[buf][op][mg][sc + 2 * q]) = make_uint4(vx, vy, vz, vw);
         }
+    };
+    auto operand = [&](int buf, int which, int col, int mg0) -> bf16x8 {
+        const uint2 lo = T[buf][which][mg0][col], hi = T[buf][which][mg0 + 1][col];
+        u32x4v v = {lo.x, lo.y, hi.x, hi.y};
+        return __builtin_bit_cast(bf16x8, v);
     };
 
     f32x16 acc[2][2];
@@ -220,12 +268,12 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(TnArgs a)
         fetch(slot_next_fetch, t + 3);             // the slot that held step t (already staged)
 #pragma unroll
         for (int kk = 0; kk < 2; ++kk) {
-            const int mo = kk * 16 + 8 * half;
+            const int mg0 = kk * 4 + 2 * half;      // eight consecutive m = two groups of four
             bf16x8 x[2], z[2];
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
-                x[i] = lds_read8(&T[buf][0][wk * 64 + i * 32 + lr][mo]);
-                z[i] = lds_read8(&T[buf][1][wn * 64 + i * 32 + lr][mo]);
+                x[i] = operand(buf, 0, wk * 64 + i * 32 + lr, mg0);
+                z[i] = operand(buf, 1, wn * 64 + i * 32 + lr, mg0);
             }
 #pragma unroll
             for (int i = 0; i < 2; ++i)
@@ -234,11 +282,10 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(TnArgs a)
         }
         if (do_colsum) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const uint4 v = *reinterpret_cast<const uint4 *>(&T[buf][1][tid][q * 8]);
-                const uint32_t w4[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-                for (int i = 0; i < 4; ++i) colsum += __uint_as_float(w4[i] << 16) + __uint_as_float(w4[i] & 0xFFFF0000u);
+            for (int q = 0; q < 8; ++q) {
+                const uint2 v = T[buf][1][q][tid];
+                colsum += (__uint_as_float(v.x << 16) + __uint_as_float(v.x & 0xFFFF0000u)) +
+                          (__uint_as_float(v.y << 16) + __uint_as_float(v.y & 0xFFFF0000u));
             }
         }
         if (t + 1 < nsteps) stage(slot_next_stage, buf ^ 1);
@@ -250,7 +297,7 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(TnArgs a)
         if (t + 2 < nsteps) body(t + 2, ring[2], ring[0]);
     }
 
-    float *P = a.partial + (int64_t)split * a.K2 * a.N;
+    float *P = a.partial + (int64_t)split * (a.K2 + 1) * a.N;
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -262,7 +309,7 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(TnArgs a)
                 if (kl < k_valid && n < a.N) P[(int64_t)(k0 + kl) * a.N + n] = acc[i][j][r];
             }
         }
-    if (do_colsum) a.db_partial[(int64_t)split * a.N + n0 + tid] = colsum;
+    if (do_colsum) P[(int64_t)a.K2 * a.N + n0 + tid] = colsum;
 }
 
 // sums the partial products of the active splits in a fixed order, applies the SGD step to the float
@@ -270,7 +317,7 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(TnArgs a)
 struct SgdArgs {
     const int32_t *hdr;
     int32_t max_rows, rows_per_split, n_splits;
-    const float *partial, *db_partial;
+    const float *partial;
     int32_t F_in, F_out, F_pad, N_pad;
     float *W, *bias;
     uint16_t *W_bf16, *Wt_bf16;
@@ -278,42 +325,70 @@ struct SgdArgs {
     float *dW_out, *db_out;
 };
 
+// A workgroup owns 64 quadruples of consecutive n (256 outputs).  Its four waves each sum every fourth
+// split, eight loads in flight per lane; the four sums meet in LDS and wave 0 finishes in a fixed order.
 __global__ __launch_bounds__(256) void sgd_reduce_kernel(SgdArgs a)
 {
+    __shared__ float4 red[4][64];
     const int M = min(a.hdr[CR_HDR_N_DST], a.max_rows);
     const int active = min(a.n_splits, (M + a.rows_per_split - 1) / a.rows_per_split);
     const int K2 = 2 * a.F_pad;
-    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= (int64_t)K2 * a.N_pad) return;
-    const int k2 = (int)(idx / a.N_pad), n = (int)(idx % a.N_pad);
+    const int nq = a.N_pad / 4;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t q = (int64_t)blockIdx.x * 64 + lane;             // quadruple index over (K2 + 1) rows of nq quadruples
+    const bool in_range = q < (int64_t)(K2 + 1) * nq;
+    const int k2 = in_range ? (int)(q / nq) : 0, n = in_range ? (int)(q % nq) * 4 : 0;
+    const bool is_bias = k2 == K2;
     const int kin = k2 % a.F_pad, part = k2 / a.F_pad;
-    if (kin < a.F_in && n < a.F_out) {
-        float g8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};     // fixed association: split s goes to accumulator s % 8
+    const bool live = in_range && n < a.F_out && (is_bias || kin < a.F_in);
+
+    float4 g = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (live) {
         const float *pp = a.partial + (int64_t)k2 * a.N_pad + n;
-        const int64_t ps = (int64_t)K2 * a.N_pad;
-        for (int s = 0; s < active; s += 8) {
-            float x[8];
+        const int64_t ps = (int64_t)(K2 + 1) * a.N_pad;
+        const int last = active > 0 ? active - 1 : 0;
+        for (int s = wave; s < active; s += 32) {                 // this wave's splits: wave, wave+4, wave+8, ...
+            float4 x[8];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) x[i] = s + i < active ? pp[(int64_t)(s + i) * ps] : 0.f;
+            for (int i = 0; i < 8; ++i) x[i] = *reinterpret_cast<const float4 *>(pp + (int64_t)min(s + 4 * i, last) * ps);
 #pragma unroll
-            for (int i = 0; i < 8; ++i) g8[i] += x[i];
+            for (int i = 0; i < 8; ++i) {
+                const float keep = s + 4 * i < active ? 1.f : 0.f;
+                g.x += keep * x[i].x; g.y += keep * x[i].y; g.z += keep * x[i].z; g.w += keep * x[i].w;
+            }
         }
-        const float g = ((g8[0] + g8[1]) + (g8[2] + g8[3])) + ((g8[4] + g8[5]) + (g8[6] + g8[7]));
-        const int64_t wi = (int64_t)(part * a.F_in + kin) * a.F_out + n;
-        float w = a.W[wi];
-        if (a.dW_out) a.dW_out[wi] = g;
-        w -= a.lr * (g + a.wd * w);
-        a.W[wi] = w;
-        const uint16_t wb = f32_to_bf16(w);
-        a.W_bf16[(int64_t)k2 * a.N_pad + n] = wb;
-        a.Wt_bf16[(int64_t)n * K2 + k2] = wb;
     }
-    if (k2 == 0 && n < a.F_out) {
-        float g = 0.f;
-        for (int s = 0; s < active; ++s) g += a.db_partial[(int64_t)s * a.N_pad + n];
-        if (a.db_out) a.db_out[n] = g;
-        a.bias[n] -= a.lr * g;
+    red[wave][lane] = g;
+    __syncthreads();
+    if (wave != 0 || !live) return;
+    const float4 r0 = red[0][lane], r1 = red[1][lane], r2 = red[2][lane], r3 = red[3][lane];
+    const float gs[4] = {(r0.x + r1.x) + (r2.x + r3.x), (r0.y + r1.y) + (r2.y + r3.y),
+                         (r0.z + r1.z) + (r2.z + r3.z), (r0.w + r1.w) + (r2.w + r3.w)};
+    if (is_bias) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (n + i < a.F_out) {
+                if (a.db_out) a.db_out[n + i] = gs[i];
+                a.bias[n + i] -= a.lr * gs[i];
+            }
+        }
+        return;
     }
+    const int64_t wi = (int64_t)(part * a.F_in + kin) * a.F_out + n;
+    uint16_t wb[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        if (n + i < a.F_out) {
+            float w = a.W[wi + i];
+            if (a.dW_out) a.dW_out[wi + i] = gs[i];
+            w -= a.lr * (gs[i] + a.wd * w);
+            a.W[wi + i] = w;
+            wb[i] = f32_to_bf16(w);
+            a.Wt_bf16[(int64_t)(n + i) * K2 + k2] = wb[i];
+        }
+    }
+    *reinterpret_cast<uint2 *>(a.W_bf16 + (int64_t)k2 * a.N_pad + n) =
+        make_uint2((uint32_t)wb[0] | ((uint32_t)wb[1] << 16), (uint32_t)wb[2] | ((uint32_t)wb[3] << 16));
 }
 
 __global__ __launch_bounds__(256) void refresh_shadows_kernel(const float *W, int F_in, int F_out, int F_pad, int N_pad,
@@ -383,7 +458,7 @@ static void split_plan(int F_pad, int N_pad, int max_rows, int &rows_per_split, 
     const int tiles = (int)(2 * ceil_div(F_pad, 128) * ceil_div(N_pad, 128));
     int target = 768 / tiles;
     if (target < 1) target = 1;
-    if (target > 64) target = 64;
+    if (target > 128) target = 128;
     int rows = (int)round_up(ceil_div(max_rows, target), 96);
     if (rows < 96) rows = 96;
     rows_per_split = rows;
@@ -460,8 +535,7 @@ extern "C" cr_status cr_sage_linear_bwd_workspace_bytes(int32_t F_in, int32_t F_
     int rows, splits;
     split_plan(F_pad, N_pad, max_rows, rows, splits);
     Carver c(nullptr);
-    c.take<float>((size_t)splits * 2 * F_pad * N_pad);
-    c.take<float>((size_t)splits * N_pad);
+    c.take<float>((size_t)splits * (2 * F_pad + 1) * N_pad);
     *bytes = c.bytes();
     return CR_OK;
 }
@@ -487,8 +561,7 @@ extern "C" cr_status cr_sage_linear_bwd(const cr_sage_layer *layer, const int32_
     int rows, splits;
     split_plan(F_pad, N_pad, max_rows, rows, splits);
     Carver c(ws);
-    float *partial = c.take<float>((size_t)splits * 2 * F_pad * N_pad);
-    float *db_partial = c.take<float>((size_t)splits * N_pad);
+    float *partial = c.take<float>((size_t)splits * (2 * F_pad + 1) * N_pad);
     CR_REQUIRE(ws != nullptr && aligned16(ws), CR_ERR_INVALID_ARG, "workspace must be a 16-byte aligned device pointer");
     CR_REQUIRE(ws_bytes >= c.bytes(), CR_ERR_CAPACITY, "workspace of %zu bytes, %zu needed", ws_bytes, c.bytes());
     if (dry_run()) return CR_OK;
@@ -503,13 +576,13 @@ extern "C" cr_status cr_sage_linear_bwd(const cr_sage_layer *layer, const int32_
     }
     TnArgs t;
     t.hdr = hdr; t.max_rows = max_rows; t.A0 = h_self; t.A1 = agg; t.lda = ld_in; t.K0 = F_pad; t.K2 = 2 * F_pad;
-    t.Z = dz_bf16; t.N = N_pad; t.rows_per_split = rows; t.partial = partial; t.db_partial = db_partial;
+    t.Z = dz_bf16; t.N = N_pad; t.rows_per_split = rows; t.partial = partial;
     hipLaunchKernelGGL(gemm_tn_kernel, dim3((unsigned)(2 * ceil_div(F_pad, 128) * ceil_div(N_pad, 128)), splits), dim3(256), 0, s, t);
     SgdArgs g;
-    g.hdr = hdr; g.max_rows = max_rows; g.rows_per_split = rows; g.n_splits = splits; g.partial = partial; g.db_partial = db_partial;
+    g.hdr = hdr; g.max_rows = max_rows; g.rows_per_split = rows; g.n_splits = splits; g.partial = partial;
     g.F_in = layer->F_in; g.F_out = layer->F_out; g.F_pad = F_pad; g.N_pad = N_pad; g.W = layer->W; g.bias = layer->bias;
     g.W_bf16 = layer->W_bf16; g.Wt_bf16 = layer->Wt_bf16; g.lr = lr; g.wd = weight_decay; g.dW_out = dW_out; g.db_out = db_out;
-    hipLaunchKernelGGL(sgd_reduce_kernel, dim3((unsigned)ceil_div(2ll * F_pad * N_pad, 256)), dim3(256), 0, s, g);
+    hipLaunchKernelGGL(sgd_reduce_kernel, dim3((unsigned)ceil_div((2ll * F_pad + 1) * (N_pad / 4), 64)), dim3(256), 0, s, g);
     CR_LAUNCH_CHECK();
     return CR_OK;
 }
