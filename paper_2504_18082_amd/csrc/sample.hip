@@ -102,35 +102,38 @@ __global__ __launch_bounds__(256) void select_kernel(SelectArgs a)
 
     const int k = f;
     const uint32_t batch = a.first_batch + (uint32_t)g;
-    // ordering pair of slot j: (ck, cs); narrow mode packs (word << 32 | slot) into ck
-    auto key_of = [&](int j, int32_t &u_out, uint64_t &ck, uint32_t &cs) {
-        const int32_t u = a.g_indices[base + j];
-        u_out = u;
-        const u32x4 w = philox4x32_10((uint32_t)j >> 2, (uint32_t)v, batch, a.ctr3, a.seed_lo, a.seed_hi);
-        const uint32_t pick = (uint32_t)j & 3u;
-        const uint32_t r = pick == 0 ? w.x : (pick == 1 ? w.y : (pick == 2 ? w.z : w.w));
+    auto less = [&](uint64_t ka, uint32_t sa, uint64_t kb, uint32_t sb) -> bool {
+        if (!WIDE) return ka < kb;
+        return ka < kb || (ka == kb && sa < sb);
+    };
+    // ordering pair of slot j given its random word (and, in wide mode, its class):
+    // narrow mode packs (word << 32 | slot) into ck
+    auto make_key = [&](uint32_t r, int j, bool intra, uint64_t &ck, uint32_t &cs) {
         if (!WIDE) {
             ck = ((uint64_t)r << 32) | (uint32_t)j;
             cs = 0;
         } else {
-            const bool intra = a.comm[u] == cv;
             if (a.q_out == 0) ck = (intra ? 0ull : (1ull << 62)) + (uint64_t)r;
             else ck = (uint64_t)exp_clock_q24(r) * (uint64_t)(intra ? a.q_out : a.q_in);
             cs = (uint32_t)j;
         }
     };
-    auto less = [&](uint64_t ka, uint32_t sa, uint64_t kb, uint32_t sb) -> bool {
-        if (!WIDE) return ka < kb;
-        return ka < kb || (ka == kb && sa < sb);
+    auto word_of = [&](int j) -> uint32_t {
+        const u32x4 w = philox4x32_10((uint32_t)j >> 2, (uint32_t)v, batch, a.ctr3, a.seed_lo, a.seed_hi);
+        const uint32_t pick = (uint32_t)j & 3u;
+        return pick == 0 ? w.x : (pick == 1 ? w.y : (pick == 2 ? w.z : w.w));
     };
+    // neighbour class look-ups are clamped to the row, so they can be issued ahead unconditionally
+    auto load_u = [&](int j) -> int32_t { return a.g_indices[base + min(j, deg - 1)]; };
 
     // first chunk: rank the first min(deg, 64) slots by counting, then move rank r to lane r
     uint64_t ck = KEY_MAX;
     uint32_t cs = 0xFFFFFFFFu;
-    int32_t cu = 0;
     const int n0 = deg < WAVE ? deg : WAVE;
-    if (lane < n0) key_of(lane, cu, ck, cs);
     {
+        bool intra = false;
+        if (WIDE) intra = a.comm[load_u(lane)] == cv;
+        if (lane < n0) make_key(word_of(lane), lane, intra, ck, cs);
         int rank = 0;
         for (int j = 0; j < n0; ++j) {
             const uint64_t kj = rl64(ck, j);
@@ -140,36 +143,56 @@ __global__ __launch_bounds__(256) void select_kernel(SelectArgs a)
         if (lane >= n0) rank = lane;
         ck = push64(ck, rank);
         if (WIDE) cs = push32(cs, rank);
-        cu = (int32_t)push32((uint32_t)cu, rank);
     }
 
-    // later chunks
+    // later chunks: a slot that beats the current k-th pair is inserted by shifting the sorted lanes
+    uint64_t tk = rl64(ck, k - 1);
+    uint32_t ts = WIDE ? rl32(cs, k - 1) : 0u;
+    auto offer = [&](bool have, uint64_t nk, uint32_t ns) {
+        uint64_t pass = __ballot(have && less(nk, ns, tk, ts));
+        while (pass) {
+            const int src = __ffsll((long long)pass) - 1;
+            pass &= pass - 1;
+            const uint64_t xk = rl64(nk, src);
+            const uint32_t xs = WIDE ? rl32(ns, src) : 0u;
+            if (less(xk, xs, tk, ts)) {
+                const int pos = __popcll(__ballot(lane < k && less(ck, cs, xk, xs)));
+                const uint64_t upk = __shfl_up(ck, 1);
+                const uint32_t ups = WIDE ? __shfl_up(cs, 1) : 0u;
+                if (lane > pos) { ck = upk; cs = ups; }
+                if (lane == pos) { ck = xk; cs = xs; }
+                tk = rl64(ck, k - 1);
+                ts = WIDE ? rl32(cs, k - 1) : 0u;
+            }
+        }
+    };
     if (deg > WAVE) {
-        uint64_t tk = rl64(ck, k - 1);
-        uint32_t ts = WIDE ? rl32(cs, k - 1) : 0u;
-        for (int j0 = WAVE; j0 < deg; j0 += WAVE) {
-            const int j = j0 + lane;
-            uint64_t nk = KEY_MAX;
-            uint32_t ns = 0xFFFFFFFFu;
-            int32_t nu = 0;
-            if (j < deg) key_of(j, nu, nk, ns);
-            uint64_t pass = __ballot(j < deg && less(nk, ns, tk, ts));
-            while (pass) {
-                const int src = __ffsll((long long)pass) - 1;
-                pass &= pass - 1;
-                const uint64_t xk = rl64(nk, src);
-                const uint32_t xs = WIDE ? rl32(ns, src) : 0u;
-                if (less(xk, xs, tk, ts)) {
-                    const int32_t xu = (int32_t)rl32((uint32_t)nu, src);
-                    const int pos = __popcll(__ballot(lane < k && less(ck, cs, xk, xs)));
-                    const uint64_t upk = __shfl_up(ck, 1);
-                    const uint32_t ups = WIDE ? __shfl_up(cs, 1) : 0u;
-                    const int32_t upu = __shfl_up(cu, 1);
-                    if (lane > pos) { ck = upk; cs = ups; cu = upu; }
-                    if (lane == pos) { ck = xk; cs = xs; cu = xu; }
-                    tk = rl64(ck, k - 1);
-                    ts = WIDE ? rl32(cs, k - 1) : 0u;
-                }
+        if (!WIDE) {
+            // uniform sampling needs no neighbour data at all: one Philox block gives a lane the words of
+            // four consecutive slots, so an iteration covers 256 slots with arithmetic only
+            for (int j0 = WAVE; j0 < deg; j0 += 4 * WAVE) {
+                const int jb = j0 + 4 * lane;
+                const u32x4 w = philox4x32_10((uint32_t)jb >> 2, (uint32_t)v, batch, a.ctr3, a.seed_lo, a.seed_hi);
+                const uint32_t wr[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) offer(jb + i < deg, ((uint64_t)wr[i] << 32) | (uint32_t)(jb + i), 0u);
+            }
+        } else {
+            // biased sampling needs the class of every neighbour: ids are fetched two chunks ahead and
+            // classes one chunk ahead, so the dependent look-ups overlap the arithmetic
+            int32_t u1 = load_u(WAVE + lane);
+            int32_t c1 = a.comm[u1];
+            int32_t u2 = load_u(2 * WAVE + lane);
+            for (int j0 = WAVE; j0 < deg; j0 += WAVE) {
+                const int32_t c2 = a.comm[u2];
+                const int32_t u3 = load_u(j0 + 2 * WAVE + lane);
+                const int j = j0 + lane;
+                uint64_t nk = KEY_MAX;
+                uint32_t ns = 0xFFFFFFFFu;
+                if (j < deg) make_key(word_of(j), j, c1 == cv, nk, ns);
+                offer(j < deg, nk, ns);
+                c1 = c2;
+                u2 = u3;
             }
         }
     }
@@ -177,6 +200,8 @@ __global__ __launch_bounds__(256) void select_kernel(SelectArgs a)
     // emit in ascending slot order
     const uint32_t slot = WIDE ? cs : (uint32_t)ck;
     const bool valid = lane < k && !(WIDE && a.strict_p1 && ck >= (1ull << 62));
+    int32_t cu = 0;
+    if (valid) cu = a.g_indices[base + slot];
     int rank = 0;
     for (int i = 0; i < k; ++i) {
         const uint32_t si = rl32(slot, i);
