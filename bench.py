@@ -125,6 +125,7 @@ def main():
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default="arxiv")
+    ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload's node / edge / community counts by this factor")
     ap.add_argument("--group", type=int, default=16)
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-sweep", action="store_true")
@@ -150,7 +151,10 @@ def main():
         sys.exit(2)
     B.lib()                                   # fail loudly if the HIP library was not built
 
-    w = synth.make_workload(args.workload, seed=args.seed)
+    wl_cfg = synth.CONFIGS[args.workload]
+    if args.scale != 1.0:
+        wl_cfg = synth.scaled(wl_cfg, args.scale)
+    w = synth.make_workload(wl_cfg, seed=args.seed)
     cfg = w.cfg
     tr = Trainer(w, group_size=args.group, lr=0.01, weight_decay=5e-4, seed=args.seed)
     steps = args.steps if args.steps is not None else tr.n_batches          # default: one epoch

@@ -136,6 +136,8 @@ typedef struct {
 } cr_block_set;
 
 #define CR_SAMPLE_STRICT_INTRA 1u /* at p = 1 never take an inter-community neighbour (rows may be short) */
+#define CR_SAMPLE_HASH_DEDUP 2u   /* de-duplicate the frontier with the open-addressing table even when the graph is small
+                                     enough for the direct-address table (less workspace; same results) */
 
 typedef struct {
     int32_t n_layers;              /* 1..CR_MAX_LAYERS */

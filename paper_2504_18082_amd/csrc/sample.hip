@@ -536,7 +536,7 @@ static cr_status make_plan(const cr_sample_cfg *cfg, int64_t n_nodes, int32_t ba
     p.cnt = c.take<int32_t>(G * p.max_dst);
     p.newoff = c.take<int32_t>(G * (p.max_dst + 1));
     p.newmask = c.take<unsigned long long>(G * p.max_dst);
-    p.direct = n_nodes <= 4 * p.max_table;
+    p.direct = n_nodes <= 4 * p.max_table && !(cfg->flags & CR_SAMPLE_HASH_DEDUP);
     p.table_stride = p.direct ? round_up(ceil_div(n_nodes, 2), 2) : p.max_table;
     p.table = c.take<unsigned long long>(G * (size_t)p.table_stride);
     p.tcount = c.take<int32_t>(G * (p.max_src_t + 1));

@@ -26,10 +26,11 @@ class DeviceGraph:
         self.n_nodes = len(indptr) - 1
 
 
-def run_gpu(torch, dg, roots, fanouts, p, strict, seed, epoch, first_batch, batch_size):
+def run_gpu(torch, dg, roots, fanouts, p, strict, seed, epoch, first_batch, batch_size, hash_dedup=False):
     from paper_2504_18082_amd import binding as B
     n_batches = -(-len(roots) // batch_size)
-    cfg = B.make_sample_cfg(fanouts, p, seed, epoch, first_batch, B.CR_SAMPLE_STRICT_INTRA if strict else 0)
+    flags = (B.CR_SAMPLE_STRICT_INTRA if strict else 0) | (B.CR_SAMPLE_HASH_DEDUP if hash_dedup else 0)
+    cfg = B.make_sample_cfg(fanouts, p, seed, epoch, first_batch, flags)
     layers = B.alloc_block_sets(cfg, dg.n_nodes, batch_size, n_batches)
     ws = torch.empty(B.cr_sample_blocks_workspace_bytes(cfg, dg.n_nodes, batch_size, n_batches), dtype=torch.uint8, device="cuda")
     d_roots = torch.from_numpy(np.ascontiguousarray(roots, dtype=np.int32)).cuda()
@@ -74,14 +75,15 @@ def test_tiny_group_of_batches(torch_mod, tiny_workload, p, strict):
     compare(layers, nb, w.graph, roots, w.cfg.fanouts, p, strict, 0, 2, 5, 256, f"tiny p={p}")
 
 
-@pytest.mark.parametrize("p", [0.5, 0.9, 1.0])
-def test_arxiv_three_layers(torch_mod, arxiv_workload, p):
+@pytest.mark.parametrize("p,hash_dedup", [(0.5, False), (0.9, False), (1.0, False), (0.5, True), (1.0, True)])
+def test_arxiv_three_layers(torch_mod, arxiv_workload, p, hash_dedup):
+    # both frontier de-duplication tables: direct-address (default at this size) and open addressing
     w = arxiv_workload
     dg = DeviceGraph(torch_mod, w.graph, w.cfg.n_comm)
     perm = oracle.build_batches(oracle.RAND, 1, 3, 1, w.train_ids, w.comm, w.cfg.n_comm)
     roots = perm[:1024 + 1000]
-    print(f"case arxiv p={p}", flush=True)
-    layers, nb = run_gpu(torch_mod, dg, roots, w.cfg.fanouts, p, False, 3, 1, 0, 1024)
+    print(f"case arxiv p={p} hash_dedup={hash_dedup}", flush=True)
+    layers, nb = run_gpu(torch_mod, dg, roots, w.cfg.fanouts, p, False, 3, 1, 0, 1024, hash_dedup)
     compare(layers, nb, w.graph, roots, w.cfg.fanouts, p, False, 3, 1, 0, 1024, f"arxiv p={p}")
 
 
@@ -96,7 +98,7 @@ def test_hub_rows_and_isolated_nodes(torch_mod):
     for p, strict in ((0.5, False), (0.9, False), (1.0, False), (1.0, True)):
         for fan in ([3, 64], [64, 7]):
             print(f"case hub p={p} strict={strict} fanouts={fan}", flush=True)
-            layers, nb = run_gpu(torch_mod, dg, roots, fan, p, strict, 9, 0, 3, 8)
+            layers, nb = run_gpu(torch_mod, dg, roots, fan, p, strict, 9, 0, 3, 8, hash_dedup=(fan[0] == 3))
             compare(layers, nb, graph, roots, fan, p, strict, 9, 0, 3, 8, f"hub p={p} {fan}")
 
 
