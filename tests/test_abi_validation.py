@@ -1,0 +1,171 @@
+"""CPU-only: every entry point validates its arguments on the host before touching the GPU.
+With cr_set_dry_run(1) a call stops after validation, so error paths run without a device."""
+import ctypes as C
+
+import pytest
+
+from paper_2504_18082_amd import binding as B
+
+FAKE = 0x10000          # a non-null, 16-byte aligned "device" address (never dereferenced in dry-run mode)
+
+
+@pytest.fixture(autouse=True)
+def dry_run():
+    B.cr_set_dry_run(True)
+    yield
+    B.cr_set_dry_run(False)
+
+
+def status_of(call):
+    try:
+        call()
+        return B.CR_OK
+    except B.CrError as e:
+        assert str(e)            # carries cr_last_error()
+        return e.status
+
+
+def vp(x=FAKE):
+    return C.c_void_p(x)
+
+
+def block_set(n_batches=1, fanout=5, cap_dst=8, cap_src=48, cap_nnz=40, t=True, null=None):
+    ptrs = dict(hdr=FAKE, src_ids=FAKE, indptr=FAKE, indices=FAKE, t_indptr=FAKE if t else None,
+                t_indices=FAKE if t else None, gather_ids=None)
+    if null:
+        ptrs[null] = None
+    return B.cr_block_set(n_batches, fanout, cap_dst, cap_src, cap_nnz, 0, ptrs["hdr"], ptrs["src_ids"], ptrs["indptr"],
+                          ptrs["indices"], ptrs["t_indptr"], ptrs["t_indices"], ptrs["gather_ids"])
+
+
+def build_batches(policy=1, mix=1, batch=256, epoch=0, n_train=1000, n_comm=10, ws_bytes=None, train=FAKE, out=FAKE, ws=FAKE):
+    lib = B.lib()
+    cfg = B.cr_batch_cfg(policy, mix, batch, epoch, 0)
+    need = C.c_size_t(0)
+    lib.cr_build_batches_workspace_bytes(max(n_train, 0), max(n_comm, 1), C.byref(need))
+    nb = C.c_int64(-1)
+    st = lib.cr_build_batches(C.byref(cfg), vp(train), n_train, vp(), n_comm, vp(ws), need.value if ws_bytes is None else ws_bytes,
+                              vp(out), C.byref(nb), None)
+    return st, nb.value
+
+
+def test_build_batches_validation():
+    assert build_batches() == (B.CR_OK, 4)
+    assert build_batches(n_train=1025) == (B.CR_OK, 5)                 # the short last batch is kept
+    assert build_batches(policy=3)[0] == B.CR_ERR_INVALID_ARG
+    assert build_batches(policy=1, mix=0)[0] == B.CR_ERR_INVALID_ARG
+    assert build_batches(policy=0, mix=0)[0] == B.CR_OK                # mix_count only matters for COMM-RAND
+    assert build_batches(batch=0)[0] == B.CR_ERR_INVALID_ARG
+    assert build_batches(epoch=1 << 24)[0] == B.CR_ERR_INVALID_ARG
+    assert build_batches(n_comm=0)[0] == B.CR_ERR_INVALID_ARG
+    assert build_batches(train=None)[0] == B.CR_ERR_INVALID_ARG
+    assert build_batches(ws=FAKE + 4)[0] == B.CR_ERR_INVALID_ARG       # misaligned workspace
+    assert build_batches(ws_bytes=16)[0] == B.CR_ERR_CAPACITY
+    assert b"workspace" in B.lib().cr_last_error()
+
+
+def sample(fanouts=(10, 5), p=0.9, epoch=0, n_nodes=10000, batch=8, n_batches=1, n_roots=8, flags=0, layers=None,
+           ws_bytes=None, graph_null=None):
+    lib = B.lib()
+    cfg = B.make_sample_cfg(list(fanouts), p, 0, epoch, 0, flags)
+    graph = B.cr_graph(n_nodes, 100, FAKE, FAKE, FAKE, 5)
+    if graph_null:
+        setattr(graph, graph_null, None)
+    need = C.c_size_t(0)
+    lib.cr_sample_blocks_workspace_bytes(C.byref(cfg), n_nodes, batch, n_batches, C.byref(need))
+    if layers is None:
+        a, b, c = (C.c_int32 * 8)(), (C.c_int32 * 8)(), (C.c_int32 * 8)()
+        if lib.cr_block_capacities(C.byref(cfg), n_nodes, batch, a, b, c) != B.CR_OK:
+            a[0] = b[0] = c[0] = 1
+        layers = [block_set(n_batches, fanouts[l], a[l], b[l], c[l], t=(l >= 1)) for l in range(len(fanouts))]
+    arr = (B.cr_block_set * len(layers))(*layers)
+    return lib.cr_sample_blocks(C.byref(graph), C.byref(cfg), vp(), n_roots, batch, n_batches, vp(), need.value if ws_bytes is None else ws_bytes,
+                                arr, None)
+
+
+def test_sample_blocks_validation():
+    assert sample() == B.CR_OK
+    assert sample(n_batches=3, n_roots=17) == B.CR_OK                   # 8 + 8 + 1
+    assert sample(n_batches=3, n_roots=16) == B.CR_ERR_INVALID_ARG      # would leave the last batch empty
+    assert sample(n_batches=3, n_roots=25) == B.CR_ERR_INVALID_ARG
+    assert sample(p=0.4) == B.CR_ERR_INVALID_ARG
+    assert sample(p=1.1) == B.CR_ERR_INVALID_ARG
+    assert sample(fanouts=(10, 0)) == B.CR_ERR_INVALID_ARG
+    assert sample(fanouts=(10, 65)) == B.CR_ERR_INVALID_ARG
+    assert sample(fanouts=()) == B.CR_ERR_INVALID_ARG
+    assert sample(epoch=1 << 24) == B.CR_ERR_INVALID_ARG
+    assert sample(graph_null="comm") == B.CR_ERR_INVALID_ARG
+    assert sample(ws_bytes=64) == B.CR_ERR_CAPACITY
+    small = [block_set(1, 10, 48, 10, 480, t=False), block_set(1, 5, 8, 48, 40)]
+    assert sample(layers=small) == B.CR_ERR_CAPACITY                    # frontier capacity below the bound
+    with_t0 = [block_set(1, 10, 48, 528, 480, t=True), block_set(1, 5, 8, 48, 40)]
+    assert sample(layers=with_t0) == B.CR_ERR_UNSUPPORTED               # layer 0 takes no transposed block
+    wrong_fanout = [block_set(1, 9, 48, 528, 480, t=False), block_set(1, 5, 8, 48, 40)]
+    assert sample(layers=wrong_fanout) == B.CR_ERR_INVALID_ARG
+
+
+def test_block_capacities_are_the_worst_case_bounds():
+    cfg = B.make_sample_cfg([15, 10, 5], 0.5, 0, 0)
+    cap_dst, cap_src, cap_nnz = B.cr_block_capacities(cfg, 2_450_000, 1024)
+    assert cap_dst == [67584, 6144, 1024] and cap_src == [1081344, 67584, 6144] and cap_nnz == [1013760, 61440, 5120]
+    cap_dst, cap_src, cap_nnz = B.cr_block_capacities(cfg, 170_000, 1024)
+    assert cap_src == [170000, 67584, 6144]                             # a frontier cannot exceed the graph
+
+
+def test_gather_validation():
+    lib = B.lib()
+    bs = block_set()
+    ok = lambda **kw: lib.cr_gather_aggregate_fwd(C.byref(kw.get("bs", bs)), kw.get("g", 0), vp(kw.get("H", FAKE)), kw.get("dtype", 0),
+                                                  kw.get("ld", 64), kw.get("F", 64), 1, vp(kw.get("agg", FAKE)), None, None, 0, None)
+    assert ok() == B.CR_OK
+    assert ok(g=1) == B.CR_ERR_INVALID_ARG
+    assert ok(H=None) == B.CR_ERR_INVALID_ARG
+    assert ok(H=FAKE + 8) == B.CR_ERR_INVALID_ARG
+    assert ok(dtype=2) == B.CR_ERR_INVALID_ARG
+    assert ok(F=1025, ld=1028) == B.CR_ERR_UNSUPPORTED
+    assert ok(F=100, ld=98) == B.CR_ERR_INVALID_ARG
+    assert ok(agg=None) == B.CR_ERR_INVALID_ARG                          # no output requested
+    assert ok(bs=block_set(null="indptr")) == B.CR_ERR_INVALID_ARG
+    # bf16 outputs need a padded stride
+    bad_ld = lib.cr_gather_aggregate_fwd(C.byref(bs), 0, vp(), 0, 100, 100, 1, None, vp(), None, 100, None)
+    assert bad_ld == B.CR_ERR_INVALID_ARG
+    good_ld = lib.cr_gather_aggregate_fwd(C.byref(bs), 0, vp(), 0, 100, 100, 1, None, vp(), None, 128, None)
+    assert good_ld == B.CR_OK
+    # backward needs the transposed block
+    no_t = block_set(t=False)
+    st = lib.cr_gather_aggregate_bwd(C.byref(no_t), 0, vp(), None, 64, 64, None, 0, 0, vp(), None, 0, None)
+    assert st == B.CR_ERR_INVALID_ARG
+    st = lib.cr_gather_aggregate_bwd(C.byref(bs), 0, vp(), None, 64, 64, vp(), 7, 64, vp(), None, 0, None)
+    assert st == B.CR_ERR_INVALID_ARG                                    # unknown relu_dtype
+    st = lib.cr_gather_aggregate_bwd(C.byref(bs), 0, vp(), None, 64, 64, vp(), B.CR_BF16, 64, vp(), None, 0, None)
+    assert st == B.CR_OK
+
+
+def test_linear_and_loss_validation():
+    lib = B.lib()
+    layer = B.cr_sage_layer(100, 47, FAKE, FAKE, FAKE, FAKE)
+    fp, np_ = B.cr_sage_padded_dims(100, 47)
+    assert (fp, np_) == (128, 64)
+    fwd = lambda **kw: lib.cr_sage_linear_fwd(C.byref(kw.get("layer", layer)), vp(kw.get("hdr", FAKE)), kw.get("rows", 100), vp(kw.get("h", FAKE)),
+                                              vp(), kw.get("ld", 128), 1, vp(kw.get("out", FAKE)), None, None)
+    assert fwd() == B.CR_OK
+    assert fwd(hdr=None) == B.CR_ERR_INVALID_ARG
+    assert fwd(rows=0) == B.CR_ERR_INVALID_ARG
+    assert fwd(ld=96) == B.CR_ERR_INVALID_ARG                            # operands narrower than F_pad
+    assert fwd(h=FAKE + 2) == B.CR_ERR_INVALID_ARG
+    assert fwd(out=None) == B.CR_ERR_INVALID_ARG
+    assert fwd(layer=B.cr_sage_layer(0, 47, FAKE, FAKE, FAKE, FAKE)) == B.CR_ERR_INVALID_ARG
+    assert fwd(layer=B.cr_sage_layer(100, 47, None, FAKE, FAKE, FAKE)) == B.CR_ERR_INVALID_ARG
+    need = B.cr_sage_linear_bwd_workspace_bytes(100, 47, 1000)
+    bwd = lambda **kw: lib.cr_sage_linear_bwd(C.byref(layer), vp(), 1000, vp(), vp(), 128, vp(), C.c_float(kw.get("lr", 0.01)), C.c_float(0.0),
+                                              vp(kw.get("ds", FAKE)), vp(kw.get("da", FAKE)), None, None, vp(), kw.get("ws", need), None)
+    assert bwd() == B.CR_OK
+    assert bwd(ds=None, da=None) == B.CR_OK                              # layer 0: no input gradient
+    assert bwd(ds=None) == B.CR_ERR_INVALID_ARG                          # only one of the two
+    assert bwd(ws=need - 1) == B.CR_ERR_CAPACITY
+    assert bwd(lr=float("nan")) == B.CR_ERR_INVALID_ARG
+    xent = lambda **kw: lib.cr_softmax_xent(vp(), 100, vp(kw.get("logits", FAKE)), kw.get("ld", 64), kw.get("C", 47), vp(), vp(), vp(), vp(), None, None, None)
+    assert xent() == B.CR_OK
+    assert xent(C=65) == B.CR_ERR_INVALID_ARG
+    assert xent(C=0) == B.CR_ERR_INVALID_ARG
+    assert xent(logits=None) == B.CR_ERR_INVALID_ARG
