@@ -45,26 +45,59 @@ struct NtArgs {
 
 struct NtState {
     const uint16_t *A0, *A1;
-    int K0;
+    int K0, K;
     int64_t ga0, ga1;
-    const uint16_t *gb;
+    const uint16_t *gb;       // B row (n0 + tid/4), chunk column kc*8
     int kc, a_row0, a_row1, b_row, act_row, lr, half;
 };
 
-// one 32-wide K step: stage the three fetched pieces, barrier, MFMA
-__device__ __forceinline__ void nt_step(const NtState &st, const uint4 &ra0, const uint4 &ra1, const uint4 &rb, int &buf,
-                                        uint16_t (&As)[2][128][LDS_ROW], uint16_t (&Bs)[2][64][LDS_ROW], f32x16 (&acc)[2])
+// the pieces one thread fetches for one 32-wide K step: two of A, NB of B (rows b_row + 64*i)
+template <int NB>
+struct NtFetch {
+    u32x4v a0, a1, b0, b1, b2, b3;
+};
+
+template <int NB>
+__device__ __forceinline__ NtFetch<NB> nt_fetch(const NtState &st, int step)
 {
-    *reinterpret_cast<uint4 *>(&As[buf][st.a_row0][st.kc * 8]) = ra0;
-    *reinterpret_cast<uint4 *>(&As[buf][st.a_row1][st.kc * 8]) = ra1;
-    *reinterpret_cast<uint4 *>(&Bs[buf][st.b_row][st.kc * 8]) = rb;
+    NtFetch<NB> f;
+    const int k0 = step * 32;
+    const uint16_t *src = k0 < st.K0 ? st.A0 + k0 : st.A1 + (k0 - st.K0);
+    f.a0 = *reinterpret_cast<const u32x4v *>(src + st.ga0 + st.kc * 8);
+    f.a1 = *reinterpret_cast<const u32x4v *>(src + st.ga1 + st.kc * 8);
+    const uint16_t *b = st.gb + k0;
+    f.b0 = *reinterpret_cast<const u32x4v *>(b);
+    f.b1 = f.b2 = f.b3 = f.b0;
+    if constexpr (NB > 1) f.b1 = *reinterpret_cast<const u32x4v *>(b + (int64_t)64 * st.K);
+    if constexpr (NB > 2) {
+        f.b2 = *reinterpret_cast<const u32x4v *>(b + (int64_t)128 * st.K);
+        f.b3 = *reinterpret_cast<const u32x4v *>(b + (int64_t)192 * st.K);
+    }
+    return f;
+}
+
+// one K step: stage the fetched pieces, barrier, MFMA (wave tile 32 m x NTILES*32 n)
+template <int NTILES>
+__device__ __forceinline__ void nt_step(const NtState &st, const NtFetch<NTILES / 2> &f, int &buf,
+                                        uint16_t (&As)[2][128][LDS_ROW], uint16_t (&Bs)[2][NTILES * 32][LDS_ROW],
+                                        f32x16 (&acc)[NTILES])
+{
+    constexpr int NB = NTILES / 2;
+    *reinterpret_cast<u32x4v *>(&As[buf][st.a_row0][st.kc * 8]) = f.a0;
+    *reinterpret_cast<u32x4v *>(&As[buf][st.a_row1][st.kc * 8]) = f.a1;
+    *reinterpret_cast<u32x4v *>(&Bs[buf][st.b_row][st.kc * 8]) = f.b0;
+    if constexpr (NB > 1) *reinterpret_cast<u32x4v *>(&Bs[buf][st.b_row + 64][st.kc * 8]) = f.b1;
+    if constexpr (NB > 2) {
+        *reinterpret_cast<u32x4v *>(&Bs[buf][st.b_row + 128][st.kc * 8]) = f.b2;
+        *reinterpret_cast<u32x4v *>(&Bs[buf][st.b_row + 192][st.kc * 8]) = f.b3;
+    }
     __syncthreads();               // tile `buf` is complete; everyone is also done reading tile `buf ^ 1`
 #pragma unroll
     for (int kk = 0; kk < 2; ++kk) {
         const int ko = kk * 16 + 8 * st.half;
         const bf16x8 act = lds_read8(&As[buf][st.act_row][ko]);
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
+        for (int t = 0; t < NTILES; ++t) {
             const bf16x8 wgt = lds_read8(&Bs[buf][t * 32 + st.lr][ko]);
             acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wgt, act, acc[t], 0, 0, 0);
         }
@@ -72,66 +105,72 @@ __device__ __forceinline__ void nt_step(const NtState &st, const uint4 &ra0, con
     buf ^= 1;
 }
 
-#define CR_NT_FETCH(i)                                                                                         \
-    const int k_##i = (s0 + i) * 32;                                                                           \
-    const uint16_t *src_##i = k_##i < st.K0 ? st.A0 + k_##i : st.A1 + (k_##i - st.K0);                         \
-    const uint4 ra0_##i = *reinterpret_cast<const uint4 *>(src_##i + st.ga0 + st.kc * 8);                      \
-    const uint4 ra1_##i = *reinterpret_cast<const uint4 *>(src_##i + st.ga1 + st.kc * 8);                      \
-    const uint4 rb_##i = *reinterpret_cast<const uint4 *>(st.gb + k_##i);
-#define CR_NT_STEP(i) nt_step(st, ra0_##i, ra1_##i, rb_##i, buf, As, Bs, acc);
-
-// eight consecutive K steps: every global load is issued before the first one is used
-__device__ __forceinline__ void nt_chunk8(const NtState &st, int s0, int &buf, uint16_t (&As)[2][128][LDS_ROW],
-                                          uint16_t (&Bs)[2][64][LDS_ROW], f32x16 (&acc)[2])
-{
-    CR_NT_FETCH(0) CR_NT_FETCH(1) CR_NT_FETCH(2) CR_NT_FETCH(3) CR_NT_FETCH(4) CR_NT_FETCH(5) CR_NT_FETCH(6) CR_NT_FETCH(7)
-    CR_NT_STEP(0) CR_NT_STEP(1) CR_NT_STEP(2) CR_NT_STEP(3) CR_NT_STEP(4) CR_NT_STEP(5) CR_NT_STEP(6) CR_NT_STEP(7)
-}
-__device__ __forceinline__ void nt_chunk1(const NtState &st, int s0, int &buf, uint16_t (&As)[2][128][LDS_ROW],
-                                          uint16_t (&Bs)[2][64][LDS_ROW], f32x16 (&acc)[2])
-{
-    CR_NT_FETCH(0)
-    CR_NT_STEP(0)
-}
-#undef CR_NT_FETCH
-#undef CR_NT_STEP
-
+// ------------------------------------------------------------------------------------------------
+// Workgroup tile 128 (m) x NTILES*32 (n), four waves of 32 x NTILES*32; the weights are the first MFMA
+// operand so that a lane ends up with four consecutive n of one row m (vector stores along the row).
+// K is consumed in chunks of CH 32-wide steps (single steps for the remainder): every global load of a
+// chunk is issued before the first one is used, so a chunk costs one memory round trip; its steps then
+// go through double-buffered LDS tiles with one barrier each.  NTILES = 8 covers a whole 256-wide
+// layer, so the activations are read once (see launch_nt for why it is not the default).
+// ------------------------------------------------------------------------------------------------
+template <int NTILES, int CH>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) void gemm_nt_kernel(NtArgs a)
 {
+    constexpr int BN = NTILES * 32, NB = NTILES / 2;
     __shared__ __attribute__((aligned(16))) uint16_t As[2][128][LDS_ROW];
-    __shared__ __attribute__((aligned(16))) uint16_t Bs[2][64][LDS_ROW];
+    __shared__ __attribute__((aligned(16))) uint16_t Bs[2][BN][LDS_ROW];
     const int M = min(a.hdr[CR_HDR_N_DST], a.max_rows);
-    const int m0 = blockIdx.y * 128, n0 = blockIdx.x * 64;
+    const int m0 = blockIdx.y * 128, n0 = blockIdx.x * BN;
     if (m0 >= M) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, lr = lane & 31;
 
-    // staging assignment: A 128 rows x 4 chunks of 8, two per thread; B 64 rows x 4 chunks, one per thread
+    // staging assignment: A 128 rows x 4 chunks of 8, two per thread; B BN rows x 4 chunks, NB per thread
     const int a_row0 = tid >> 2, a_row1 = (tid + 256) >> 2, kc = tid & 3;
     const int64_t ga0 = (int64_t)min(m0 + a_row0, M - 1) * a.lda;
     const int64_t ga1 = (int64_t)min(m0 + a_row1, M - 1) * a.lda;
     const uint16_t *gb = a.B + (int64_t)(n0 + (tid >> 2)) * a.K + kc * 8;
 
-    f32x16 acc[2];
+    f32x16 acc[NTILES];
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
+    for (int t = 0; t < NTILES; ++t)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
 
-    // K is consumed in chunks of eight 32-wide steps (single steps for the remainder).  All
-    // global loads of a chunk are issued before the first one is used, so a chunk costs one memory
-    // round trip; its steps then go through double-buffered LDS tiles with one barrier each.
     const int nsteps = a.K / 32;
     int buf = 0;
-    NtState st{a.A0, a.A1, a.K0, ga0, ga1, gb, kc, a_row0, a_row1, tid >> 2, wave * 32 + lr, lr, half};
+    NtState st{a.A0, a.A1, a.K0, a.K, ga0, ga1, gb, kc, a_row0, a_row1, tid >> 2, wave * 32 + lr, lr, half};
     int s0 = 0;
-    for (; s0 + 8 <= nsteps; s0 += 8) nt_chunk8(st, s0, buf, As, Bs, acc);
-    for (; s0 < nsteps; ++s0) nt_chunk1(st, s0, buf, As, Bs, acc);
+    for (; s0 + CH <= nsteps; s0 += CH) {
+        const NtFetch<NB> f0 = nt_fetch<NB>(st, s0 + 0), f1 = nt_fetch<NB>(st, s0 + 1), f2 = nt_fetch<NB>(st, s0 + 2),
+                          f3 = nt_fetch<NB>(st, s0 + 3);
+        if constexpr (CH == 8) {
+            const NtFetch<NB> f4 = nt_fetch<NB>(st, s0 + 4), f5 = nt_fetch<NB>(st, s0 + 5), f6 = nt_fetch<NB>(st, s0 + 6),
+                              f7 = nt_fetch<NB>(st, s0 + 7);
+            nt_step<NTILES>(st, f0, buf, As, Bs, acc);
+            nt_step<NTILES>(st, f1, buf, As, Bs, acc);
+            nt_step<NTILES>(st, f2, buf, As, Bs, acc);
+            nt_step<NTILES>(st, f3, buf, As, Bs, acc);
+            nt_step<NTILES>(st, f4, buf, As, Bs, acc);
+            nt_step<NTILES>(st, f5, buf, As, Bs, acc);
+            nt_step<NTILES>(st, f6, buf, As, Bs, acc);
+            nt_step<NTILES>(st, f7, buf, As, Bs, acc);
+        } else {
+            nt_step<NTILES>(st, f0, buf, As, Bs, acc);
+            nt_step<NTILES>(st, f1, buf, As, Bs, acc);
+            nt_step<NTILES>(st, f2, buf, As, Bs, acc);
+            nt_step<NTILES>(st, f3, buf, As, Bs, acc);
+        }
+    }
+    for (; s0 < nsteps; ++s0) {
+        const NtFetch<NB> f = nt_fetch<NB>(st, s0);
+        nt_step<NTILES>(st, f, buf, As, Bs, acc);
+    }
 
     const int m = m0 + wave * 32 + lr;
     if (m >= M) return;
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
+    for (int t = 0; t < NTILES; ++t)
 #pragma unroll
         for (int grp = 0; grp < 4; ++grp) {
             const int n = n0 + t * 32 + 8 * grp + 4 * half;
@@ -152,6 +191,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) voi
                 *reinterpret_cast<uint2 *>(a.Cb + (int64_t)m * a.ldcb + n) = make_uint2(lo, hi);
             }
         }
+}
+
+// Wider tiles (NTILES = 4, 8) read the activations fewer times but measured slower on MI355X for the
+// layer widths of this path (K = 256..512, N = 256): these products are bound by memory round trips
+// and occupancy, not by the matrix cores, so the smallest tile with the deepest prefetch wins.
+static void launch_nt(const NtArgs &a, hipStream_t s)
+{
+    hipLaunchKernelGGL((gemm_nt_kernel<2, 8>), dim3(a.N / 64, (unsigned)ceil_div(a.max_rows, 128)), dim3(256), 0, s, a);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -521,8 +568,7 @@ extern "C" cr_status cr_sage_linear_fwd(const cr_sage_layer *layer, const int32_
     a.hdr = hdr; a.max_rows = max_rows; a.A0 = h_self; a.A1 = agg; a.lda = ld_in; a.K0 = F_pad; a.K = 2 * F_pad;
     a.B = layer->Wt_bf16; a.N = N_pad; a.bias = layer->bias; a.relu = relu ? 1 : 0;
     a.C0 = out; a.C1 = nullptr; a.ldc = N_pad; a.N0 = N_pad; a.Cb = out_bf16; a.ldcb = N_pad;
-    hipLaunchKernelGGL(gemm_nt_kernel, dim3(N_pad / 64, (unsigned)ceil_div(max_rows, 128)), dim3(256), 0,
-                       static_cast<hipStream_t>(stream), a);
+    launch_nt(a, static_cast<hipStream_t>(stream));
     CR_LAUNCH_CHECK();
     return CR_OK;
 }
@@ -572,7 +618,7 @@ extern "C" cr_status cr_sage_linear_bwd(const cr_sage_layer *layer, const int32_
         a.hdr = hdr; a.max_rows = max_rows; a.A0 = dz_bf16; a.A1 = nullptr; a.lda = N_pad; a.K0 = N_pad; a.K = N_pad;
         a.B = layer->W_bf16; a.N = 2 * F_pad; a.bias = nullptr; a.relu = 0;
         a.C0 = d_self; a.C1 = d_agg; a.ldc = F_pad; a.N0 = F_pad; a.Cb = nullptr; a.ldcb = 0;
-        hipLaunchKernelGGL(gemm_nt_kernel, dim3(2 * F_pad / 64, (unsigned)ceil_div(max_rows, 128)), dim3(256), 0, s, a);
+        launch_nt(a, s);
     }
     TnArgs t;
     t.hdr = hdr; t.max_rows = max_rows; t.A0 = h_self; t.A1 = agg; t.lda = ld_in; t.K0 = F_pad; t.K2 = 2 * F_pad;
