@@ -36,7 +36,7 @@ def gather0_bytes(hdr0, n_feat, elem_bytes, f_pad):
     return reads + writes, (nnz + n_dst) * n_feat * elem_bytes
 
 
-def run_setting(tr, policy, mix, p, steps, warmup, epoch0, serial=False):
+def run_setting(tr, policy, mix, p, steps, warmup, epoch0, serial="none"):
     """Times `steps` steps (after `warmup` untimed ones) of one knob setting."""
     import torch
     from paper_2504_18082_amd import binding as B
@@ -48,7 +48,7 @@ def run_setting(tr, policy, mix, p, steps, warmup, epoch0, serial=False):
         done = 0
         collect = (lambda n, slot: hdrs.append((n, tr.block_slots[slot][0].hdr.clone()))) if timed else None
         while done < n_steps:
-            if serial:
+            if serial == "none":
                 nb = tr.build_batches(policy, mix, epoch)
                 first = 0
                 while first < min(nb, n_steps - done):
@@ -61,7 +61,8 @@ def run_setting(tr, policy, mix, p, steps, warmup, epoch0, serial=False):
                     first += n
                 done += first
             else:
-                done += tr.run_epoch(policy, mix, p, epoch, max_batches=n_steps - done, on_group=collect)
+                done += tr.run_epoch(policy, mix, p, epoch, max_batches=n_steps - done, on_group=collect,
+                                     gather_on_side_stream=(serial == "all"), weights_on_side_stream=(serial in ("sample+weights", "all")))
             epoch += 1
         return epoch
 
@@ -129,9 +130,10 @@ def main():
     ap.add_argument("--group", type=int, default=16)
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-sweep", action="store_true")
-    ap.add_argument("--overlap", action="store_true",
-                    help="issue sampling and the layer-0 gather on side streams so that they overlap with training "
-                         "(default: every call on one stream, which keeps the per-kernel timing clean)")
+    ap.add_argument("--overlap", default="none", choices=["none", "sample", "sample+weights", "all"],
+                    help="side streams: 'sample' = sampling of the next group overlaps training; '+weights' = weight "
+                         "gradients and SGD leave the backward pass's critical path; 'all' = also the layer-0 gather "
+                         "(default none: every call on one stream, which keeps the per-kernel timing clean)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-batches", type=int, default=1)
     ap.add_argument("--calibration-copy", action="store_true",
@@ -170,12 +172,12 @@ def main():
         del src, dst
 
     # headline: the fully random setting (RAND-ROOTS, p = 0.5), the paper's baseline
-    main_res = run_setting(tr, B.CR_ROOTS_RAND, 1, 0.5, steps, args.warmup, 0, not args.overlap)
+    main_res = run_setting(tr, B.CR_ROOTS_RAND, 1, 0.5, steps, args.warmup, 0, args.overlap)
     sweep = []
     if not args.no_sweep:
         for name, policy, mix, p in (("mid: COMM-RAND-MIX-12.5% p=1.0", B.CR_ROOTS_COMM_RAND, mix_mid, 1.0),
                                      ("fully community: NORAND-ROOTS p=1.0", B.CR_ROOTS_NORAND, 1, 1.0)):
-            r = run_setting(tr, policy, mix, p, steps, min(args.warmup, 4), 50, not args.overlap)
+            r = run_setting(tr, policy, mix, p, steps, min(args.warmup, 4), 50, args.overlap)
             sweep.append(dict(setting=name, ms_per_step=round(r["ms_per_step"], 4),
                               epoch_ms=round(r["ms_per_step"] * tr.n_batches, 3),
                               speedup_vs_random=round(main_res["ms_per_step"] / r["ms_per_step"], 3),
@@ -209,7 +211,7 @@ def main():
                                f"features, {len(cfg.fanouts)}-layer GraphSAGE-mean hidden {cfg.hidden}, fanout {cfg.fanouts}, "
                                f"batch {cfg.batch_size}, {tr.n_batches} batches/epoch",
                    "setting": "fully random: RAND-ROOTS p=0.5", "group_size": args.group,
-                   "schedule": "sampling and layer-0 gather on side streams, overlapped with training" if args.overlap else "one stream",
+                   "schedule": "one stream" if args.overlap == "none" else "side streams: " + args.overlap,
                    "value_definition": "layer-0 gathered feature bytes per second of whole-step time"},
         "epoch_ms": round(main_res["ms_per_step"] * tr.n_batches, 3),
         "mean_input_nodes": round(main_res["mean_input_nodes"], 1),

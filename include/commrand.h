@@ -246,6 +246,13 @@ cr_status cr_sage_linear_bwd(const cr_sage_layer *layer, const int32_t *hdr, int
                              float *d_agg, float *dW_out, float *db_out, void *ws, size_t ws_bytes,
                              void *stream);
 
+/* Only the input gradients of cr_sage_linear_bwd (d_self = dZ W_self^T, d_agg = dZ W_neigh^T, device float
+ * [max_rows][F_pad]); no weight is touched.  Lets a caller put the weight-gradient part (cr_sage_linear_bwd with
+ * d_self = d_agg = NULL) on another stream, off the critical path of the backward pass; that call must then be
+ * ordered after this one, which reads the weights from before the step. */
+cr_status cr_sage_linear_bwd_input(const cr_sage_layer *layer, const int32_t *hdr, int32_t max_rows,
+                                   const uint16_t *dz_bf16, float *d_self, float *d_agg, void *stream);
+
 /* Mean softmax cross-entropy over the root rows (labels exist for roots only) and its gradient.
  *   hdr      : device block header of the root block; n = hdr[CR_HDR_N_DST] <= max_rows
  *   logits   : device float [max_rows][ld], only columns 0..n_classes-1 take part

@@ -28,7 +28,7 @@ EXPORTS = [
     "cr_block_capacities", "cr_sample_blocks_workspace_bytes", "cr_sample_blocks",
     "cr_gather_aggregate_fwd", "cr_gather_aggregate_bwd",
     "cr_sage_padded_dims", "cr_sage_refresh_shadows", "cr_sage_linear_fwd",
-    "cr_sage_linear_bwd_workspace_bytes", "cr_sage_linear_bwd", "cr_softmax_xent",
+    "cr_sage_linear_bwd_workspace_bytes", "cr_sage_linear_bwd", "cr_sage_linear_bwd_input", "cr_softmax_xent",
 ]
 
 
@@ -103,6 +103,7 @@ def lib():
         L.cr_sage_linear_bwd_workspace_bytes.argtypes = [i32, i32, i32, C.POINTER(C.c_size_t)]
         L.cr_sage_linear_bwd.argtypes = [C.POINTER(cr_sage_layer), vp, i32, vp, vp, i64, vp, C.c_float,
                                          C.c_float, vp, vp, vp, vp, vp, C.c_size_t, vp]
+        L.cr_sage_linear_bwd_input.argtypes = [C.POINTER(cr_sage_layer), vp, i32, vp, vp, vp, vp]
         L.cr_softmax_xent.argtypes = [vp, i32, vp, i64, i32, vp, vp, vp, vp, vp, vp, vp]
         for name in EXPORTS:
             fn = getattr(L, name)
@@ -304,6 +305,11 @@ def cr_sage_linear_bwd(layer: SageLayer, hdr_ptr, max_rows, h_self, agg, ld_in, 
     _check(lib().cr_sage_linear_bwd(C.byref(layer.c), hdr_ptr, max_rows, _ptr(h_self), _ptr(agg), ld_in,
                                     _ptr(dz_bf16), lr, weight_decay, _ptr(d_self), _ptr(d_agg), _ptr(dW_out),
                                     _ptr(db_out), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)))
+
+
+def cr_sage_linear_bwd_input(layer: SageLayer, hdr_ptr, max_rows, dz_bf16, d_self, d_agg, stream=None):
+    _check(lib().cr_sage_linear_bwd_input(C.byref(layer.c), hdr_ptr, max_rows, _ptr(dz_bf16), _ptr(d_self), _ptr(d_agg),
+                                          _stream(stream)))
 
 
 def cr_softmax_xent(hdr_ptr, max_rows, logits, ld, n_classes, labels, root_ids_ptr, loss, row_loss,

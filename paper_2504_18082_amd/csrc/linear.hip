@@ -633,6 +633,25 @@ extern "C" cr_status cr_sage_linear_bwd(const cr_sage_layer *layer, const int32_
     return CR_OK;
 }
 
+extern "C" cr_status cr_sage_linear_bwd_input(const cr_sage_layer *layer, const int32_t *hdr, int32_t max_rows,
+                                              const uint16_t *dz_bf16, float *d_self, float *d_agg, void *stream)
+{
+    int F_pad, N_pad;
+    cr_status st = check_layer(layer, F_pad, N_pad);
+    if (st != CR_OK) return st;
+    CR_REQUIRE(hdr != nullptr && max_rows >= 1, CR_ERR_INVALID_ARG, "hdr must not be NULL and max_rows must be positive");
+    CR_REQUIRE(dz_bf16 && aligned16(dz_bf16), CR_ERR_INVALID_ARG, "dz_bf16 must be a 16-byte aligned device pointer");
+    CR_REQUIRE(d_self && d_agg && aligned16(d_self) && aligned16(d_agg), CR_ERR_INVALID_ARG, "d_self / d_agg must be 16-byte aligned device pointers");
+    if (dry_run()) return CR_OK;
+    NtArgs a;
+    a.hdr = hdr; a.max_rows = max_rows; a.A0 = dz_bf16; a.A1 = nullptr; a.lda = N_pad; a.K0 = N_pad; a.K = N_pad;
+    a.B = layer->W_bf16; a.N = 2 * F_pad; a.bias = nullptr; a.relu = 0;
+    a.C0 = d_self; a.C1 = d_agg; a.ldc = F_pad; a.N0 = F_pad; a.Cb = nullptr; a.ldcb = 0;
+    launch_nt(a, static_cast<hipStream_t>(stream));
+    CR_LAUNCH_CHECK();
+    return CR_OK;
+}
+
 extern "C" cr_status cr_softmax_xent(const int32_t *hdr, int32_t max_rows, const float *logits, int64_t ld,
                                      int32_t n_classes, const int32_t *labels, const int32_t *root_ids, float *loss,
                                      float *row_loss, float *d_logits, uint16_t *d_logits_bf16, void *stream)

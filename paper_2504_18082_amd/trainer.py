@@ -84,6 +84,9 @@ class Trainer:
         self.time_gather0 = False
         self.stream_sample = torch.cuda.Stream(device=device)
         self.stream_gather = torch.cuda.Stream(device=device)
+        self.stream_weights = torch.cuda.Stream(device=device)
+        self.weights_on_side_stream = False     # set by run_epoch(weights_on_side_stream=True)
+        self.ev_weights = [None] * self.L        # event: layer l's weights are updated and its operands are free again
 
     # ------------------------------------------------------------------ step 1
     def build_batches(self, policy: int, mix_count: int, epoch: int) -> int:
@@ -134,6 +137,9 @@ class Trainer:
             if l == 0:
                 if gather0:
                     self.gather_layer0(g, slot, buf)
+                # weight updates of the previous step that ran on the side stream: every layer's operands
+                # (hidden activations, aggregates, dZ) are overwritten from here on
+                self.wait_weights()
                 h_self, ld_in = self.self0, lay.F_pad
             else:
                 prev = layers[l - 1]
@@ -147,19 +153,42 @@ class Trainer:
         B.cr_softmax_xent(top.hdr_ptr(g), top.cap_dst, self.out[L - 1], layers[L - 1].N_pad, self.cfg.n_classes,
                           self.labels, top.src_ids_ptr(g), self.loss, self.row_loss, None, self.dz[L - 1])
         # backward + SGD
+        side = self.stream_weights if self.weights_on_side_stream else None
         for l in range(L - 1, -1, -1):
             blk, lay = blocks[l], layers[l]
             if l == 0:
                 h_self, ld_in = self.self0, lay.F_pad
             else:
                 h_self, ld_in = self.out_b[l - 1], layers[l - 1].N_pad
-            B.cr_sage_linear_bwd(lay, blk.hdr_ptr(g), blk.cap_dst, h_self, self.agg[l], ld_in, self.dz[l], self.lr, self.wd,
-                                 self.d_self[l], self.d_agg[l], self.ws_bwd[l],
-                                 None if dW_out is None else dW_out[l], None if db_out is None else db_out[l])
+            grads = (None if dW_out is None else dW_out[l], None if db_out is None else db_out[l])
+            if side is None:
+                B.cr_sage_linear_bwd(lay, blk.hdr_ptr(g), blk.cap_dst, h_self, self.agg[l], ld_in, self.dz[l], self.lr, self.wd,
+                                     self.d_self[l], self.d_agg[l], self.ws_bwd[l], *grads)
+            else:
+                # the input gradients stay on the critical path; the weight gradient and the SGD step of this
+                # layer go to the side stream, after the input-gradient product has read the old weights
+                if l >= 1:
+                    B.cr_sage_linear_bwd_input(lay, blk.hdr_ptr(g), blk.cap_dst, self.dz[l], self.d_self[l], self.d_agg[l])
+                ready = self.torch.cuda.Event()
+                ready.record()
+                with self.torch.cuda.stream(side):
+                    side.wait_event(ready)
+                    B.cr_sage_linear_bwd(lay, blk.hdr_ptr(g), blk.cap_dst, h_self, self.agg[l], ld_in, self.dz[l], self.lr, self.wd,
+                                         None, None, self.ws_bwd[l], *grads)
+                    self.ev_weights[l] = self.torch.cuda.Event()
+                    self.ev_weights[l].record(side)
             if l >= 1:
                 prev = layers[l - 1]
                 B.cr_gather_aggregate_bwd(blk, g, self.d_agg[l], self.d_self[l], lay.F_pad, lay.F_in, self.out_b[l - 1],
                                           prev.N_pad, None, self.dz[l - 1], prev.N_pad, relu_dtype=B.CR_BF16)
+
+    def wait_weights(self, layers=None):
+        """Makes the current stream wait for the side-stream weight updates of the given layers (all by default)."""
+        cur = self.torch.cuda.current_stream()
+        for l in (range(self.L) if layers is None else layers):
+            if self.ev_weights[l] is not None:
+                cur.wait_event(self.ev_weights[l])
+                self.ev_weights[l] = None
 
     # ------------------------------------------------------------------ one epoch
     def run_epoch_serial(self, policy: int, mix_count: int, p_intra: float, epoch: int, max_batches: Optional[int] = None):
@@ -177,13 +206,18 @@ class Trainer:
         return nb
 
     def run_epoch(self, policy: int, mix_count: int, p_intra: float, epoch: int, max_batches: Optional[int] = None,
-                  on_group=None):
-        """Overlapped schedule: root partitioning and sampling on one side stream, the layer-0 gather on
-        another, training on the current stream.  Same calls, same arguments, same results as
-        run_epoch_serial.  on_group(n, slot), if given, is called after a group's work is enqueued."""
+                  on_group=None, gather_on_side_stream: bool = False, weights_on_side_stream: bool = False):
+        """Overlapped schedule: root partitioning and sampling of the next group of mini-batches run on a
+        side stream while the current group trains; with gather_on_side_stream the layer-0 gather of the
+        next mini-batch runs on a second side stream as well; with weights_on_side_stream every layer's
+        weight gradient + SGD step leaves the critical path of the backward pass for a third one.  Same
+        calls, same arguments, same results as run_epoch_serial.  on_group(n, slot), if given, is called
+        after a group's work is enqueued."""
         torch = self.torch
+        self.weights_on_side_stream = weights_on_side_stream
         main = torch.cuda.current_stream()
-        ss, sg = self.stream_sample, self.stream_gather
+        ss = self.stream_sample
+        sg = self.stream_gather if gather_on_side_stream else main
         ev = lambda: torch.cuda.Event()
         ss.wait_stream(main)
         sg.wait_stream(main)
@@ -220,18 +254,20 @@ class Trainer:
             for g in range(n):
                 buf = step % 2
                 with torch.cuda.stream(sg):
-                    if buf_free[buf] is not None:
-                        sg.wait_event(buf_free[buf])
+                    for e in buf_free[buf] or ():
+                        sg.wait_event(e)
                     self.gather_layer0(g, slot, buf)
                     gathered[buf] = ev()
                     gathered[buf].record(sg)
                 main.wait_event(gathered[buf])
                 self.train_batch(g, slot=slot, buf=buf, gather0=False)
-                buf_free[buf] = ev()
-                buf_free[buf].record(main)
+                e = ev()
+                e.record(main)
+                buf_free[buf] = [e] + ([self.ev_weights[0]] if self.ev_weights[0] is not None else [])
                 step += 1
             if on_group is not None:
                 on_group(n, slot)
+            self.wait_weights()             # side-stream weight updates still read this slot's headers
             done = ev()
             done.record(main)               # training of the group is enqueued up to here ...
             with torch.cuda.stream(sg):
@@ -242,6 +278,8 @@ class Trainer:
             slot_free[slot] = done
         main.wait_stream(ss)
         main.wait_stream(sg)
+        self.wait_weights()
+        self.weights_on_side_stream = False
         return nb
 
     def headers(self):

@@ -104,16 +104,18 @@ def test_overlapped_epoch_equals_serial_epoch(tiny_workload):
     from paper_2504_18082_amd.trainer import Trainer
     w = tiny_workload
     results = []
-    for overlapped in (False, True):
+    for mode in ("serial", "sample", "sample+weights", "all"):
         tr = Trainer(w, group_size=3, lr=0.05, seed=0, weights=synth.init_weights(w.cfg, 0))
         for epoch in range(2):
-            if overlapped:
-                nb = tr.run_epoch(oracle.COMM_RAND, 6, 0.9, epoch)
-            else:
+            if mode == "serial":
                 nb = tr.run_epoch_serial(oracle.COMM_RAND, 6, 0.9, epoch)
+            else:
+                nb = tr.run_epoch(oracle.COMM_RAND, 6, 0.9, epoch, gather_on_side_stream=(mode == "all"),
+                                  weights_on_side_stream=(mode != "sample"))
         torch.cuda.synchronize()
         assert nb == tr.n_batches
         results.append([l.W.cpu().numpy().copy() for l in tr.layers] + [float(tr.loss.cpu()[0])])
-    for a, b in zip(results[0][:-1], results[1][:-1]):
-        assert np.array_equal(a, b)
-    assert results[0][-1] == results[1][-1]
+    for other in results[1:]:
+        for a, b in zip(results[0][:-1], other[:-1]):
+            assert np.array_equal(a, b)
+        assert results[0][-1] == other[-1]
