@@ -119,3 +119,21 @@ def test_overlapped_epoch_equals_serial_epoch(tiny_workload):
         for a, b in zip(results[0][:-1], other[:-1]):
             assert np.array_equal(a, b)
         assert results[0][-1] == other[-1]
+
+
+def test_two_runs_are_bit_identical(tiny_workload):
+    # no kernel of the path depends on scheduling: atomics only take minima / integer counts, split-K sums and
+    # the transposed blocks have a fixed order
+    import torch
+    from paper_2504_18082_amd.trainer import Trainer
+    w = tiny_workload
+    outs = []
+    for _ in range(2):
+        tr = Trainer(w, group_size=4, lr=0.05, seed=3, weights=synth.init_weights(w.cfg, 3))
+        tr.run_epoch_serial(oracle.COMM_RAND, 3, 0.9, 1, max_batches=6)
+        torch.cuda.synchronize()
+        outs.append(([l.W.cpu().numpy().copy() for l in tr.layers], [b.t_indices.cpu().numpy().copy() for b in tr.blocks if b.t_indices is not None],
+                     [b.indices.cpu().numpy().copy() for b in tr.blocks], float(tr.loss.cpu()[0])))
+    for a, b in zip(outs[0][0] + outs[0][1] + outs[0][2], outs[1][0] + outs[1][1] + outs[1][2]):
+        assert np.array_equal(a, b)
+    assert outs[0][3] == outs[1][3]
