@@ -265,6 +265,14 @@ cr_status cr_softmax_xent(const int32_t *hdr, int32_t max_rows, const float *log
                           float *loss, float *row_loss, float *d_logits, uint16_t *d_logits_bf16,
                           void *stream);
 
+/* Validation pass of the training protocol (Section 5 "Training methodology": final validation accuracy, early
+ * stopping on the validation loss): adds to *count the number of root rows whose largest logit (lowest class index
+ * on ties) equals the label.  Same arguments as cr_softmax_xent; count is a device int32 that the caller zeroes.
+ * The validation loss comes from cr_softmax_xent with both gradient outputs NULL. */
+cr_status cr_count_correct(const int32_t *hdr, int32_t max_rows, const float *logits, int64_t ld,
+                           int32_t n_classes, const int32_t *labels, const int32_t *root_ids,
+                           int32_t *count, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

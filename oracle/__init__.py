@@ -70,6 +70,8 @@ def lib():
         L.orc_softmax_xent.restype = C.c_double
         L.orc_softmax_xent.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p,
                                        C.c_void_p]
+        L.orc_count_correct.restype = C.c_int32
+        L.orc_count_correct.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p]
         _lib = L
     return _lib
 
@@ -265,3 +267,10 @@ def softmax_xent(logits, labels, n_classes=None):
     d = np.zeros_like(logits)
     loss = lib().orc_softmax_xent(n, Cn, _p(logits), ld, _p(labels), _p(d))
     return float(loss), d
+
+
+def count_correct(logits, labels, n_classes=None):
+    logits = _arr(logits, np.float64)
+    labels = _arr(labels, np.int32)
+    n, ld = logits.shape
+    return int(lib().orc_count_correct(n, ld if n_classes is None else n_classes, _p(logits), ld, _p(labels)))

@@ -489,3 +489,17 @@ double orc_softmax_xent(int32_t n, int32_t C, const double *logits, int64_t ld,
     }
     return n ? loss / (double)n : 0.0;
 }
+
+/* Number of rows whose largest logit (lowest index on ties) is the label: the accuracy numerator of the
+ * validation pass of the training protocol (Section 5 "Training methodology"). */
+int32_t orc_count_correct(int32_t n, int32_t C, const double *logits, int64_t ld, const int32_t *labels)
+{
+    int32_t ok = 0;
+    for (int32_t i = 0; i < n; ++i) {
+        const double *z = logits + (int64_t)i * ld;
+        int32_t best = 0;
+        for (int32_t c = 1; c < C; ++c) if (z[c] > z[best]) best = c;
+        ok += best == labels[i];
+    }
+    return ok;
+}

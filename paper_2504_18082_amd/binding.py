@@ -29,6 +29,7 @@ EXPORTS = [
     "cr_gather_aggregate_fwd", "cr_gather_aggregate_bwd",
     "cr_sage_padded_dims", "cr_sage_refresh_shadows", "cr_sage_linear_fwd",
     "cr_sage_linear_bwd_workspace_bytes", "cr_sage_linear_bwd", "cr_sage_linear_bwd_input", "cr_softmax_xent",
+    "cr_count_correct",
 ]
 
 
@@ -105,6 +106,7 @@ def lib():
                                          C.c_float, vp, vp, vp, vp, vp, C.c_size_t, vp]
         L.cr_sage_linear_bwd_input.argtypes = [C.POINTER(cr_sage_layer), vp, i32, vp, vp, vp, vp]
         L.cr_softmax_xent.argtypes = [vp, i32, vp, i64, i32, vp, vp, vp, vp, vp, vp, vp]
+        L.cr_count_correct.argtypes = [vp, i32, vp, i64, i32, vp, vp, vp, vp]
         for name in EXPORTS:
             fn = getattr(L, name)
             if name not in ("cr_last_error", "cr_version", "cr_set_dry_run", "cr_mix_count_from_percent"):
@@ -317,3 +319,8 @@ def cr_softmax_xent(hdr_ptr, max_rows, logits, ld, n_classes, labels, root_ids_p
     _check(lib().cr_softmax_xent(hdr_ptr, max_rows, _ptr(logits), ld, n_classes, _ptr(labels), root_ids_ptr,
                                  _ptr(loss), _ptr(row_loss), _ptr(d_logits), _ptr(d_logits_bf16),
                                  _stream(stream)))
+
+
+def cr_count_correct(hdr_ptr, max_rows, logits, ld, n_classes, labels, root_ids_ptr, count, stream=None):
+    _check(lib().cr_count_correct(hdr_ptr, max_rows, _ptr(logits), ld, n_classes, _ptr(labels), root_ids_ptr, _ptr(count),
+                                  _stream(stream)))

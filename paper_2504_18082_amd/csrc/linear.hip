@@ -500,6 +500,39 @@ __global__ __launch_bounds__(1024) void xent_mean_kernel(const int32_t *hdr, int
     }
 }
 
+// arg-max of every root row against its label; the workgroup's count is added to a device counter
+__global__ __launch_bounds__(256) void count_correct_kernel(const int32_t *hdr, int max_rows, const float *logits, int64_t ld,
+                                                            int C, const int32_t *labels, const int32_t *root_ids, int32_t *count)
+{
+    __shared__ int hits[4];
+    const int n = min(hdr[CR_HDR_N_DST], max_rows);
+    const int row = blockIdx.x * 4 + threadIdx.x / WAVE;
+    const int lane = lane_id();
+    int hit = 0;
+    if (row < n) {
+        const float *z = logits + (int64_t)row * ld;
+        float best = -INFINITY;
+        int arg = 0x7FFFFFFF;
+        for (int c = lane; c < C; c += WAVE) {
+            const float x = z[c];
+            if (x > best) { best = x; arg = c; }          // ascending c per lane: the first maximum stays
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            const float ob = __shfl_xor(best, off);
+            const int oa = __shfl_xor(arg, off);
+            if (ob > best || (ob == best && oa < arg)) { best = ob; arg = oa; }
+        }
+        hit = arg == labels[root_ids[row]] ? 1 : 0;
+    }
+    if (lane == 0) hits[threadIdx.x / WAVE] = hit;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const int s = hits[0] + hits[1] + hits[2] + hits[3];
+        if (s) atomicAdd(count, s);
+    }
+}
+
 static void split_plan(int F_pad, int N_pad, int max_rows, int &rows_per_split, int &n_splits)
 {
     const int tiles = (int)(2 * ceil_div(F_pad, 128) * ceil_div(N_pad, 128));
@@ -664,6 +697,20 @@ extern "C" cr_status cr_softmax_xent(const int32_t *hdr, int32_t max_rows, const
     hipLaunchKernelGGL(xent_rows_kernel, dim3((unsigned)ceil_div(max_rows, 4)), dim3(256), 0, s, hdr, max_rows, logits, ld, n_classes,
                        labels, root_ids, row_loss, d_logits, d_logits_bf16);
     hipLaunchKernelGGL(xent_mean_kernel, dim3(1), dim3(1024), 0, s, hdr, max_rows, row_loss, loss);
+    CR_LAUNCH_CHECK();
+    return CR_OK;
+}
+
+extern "C" cr_status cr_count_correct(const int32_t *hdr, int32_t max_rows, const float *logits, int64_t ld,
+                                      int32_t n_classes, const int32_t *labels, const int32_t *root_ids,
+                                      int32_t *count, void *stream)
+{
+    CR_REQUIRE(hdr != nullptr && max_rows >= 1, CR_ERR_INVALID_ARG, "hdr must not be NULL and max_rows must be positive");
+    CR_REQUIRE(logits && labels && root_ids && count, CR_ERR_INVALID_ARG, "logits / labels / root_ids / count must not be NULL");
+    CR_REQUIRE(n_classes >= 1 && ld >= n_classes, CR_ERR_INVALID_ARG, "need 1 <= n_classes <= ld");
+    if (dry_run()) return CR_OK;
+    hipLaunchKernelGGL(count_correct_kernel, dim3((unsigned)ceil_div(max_rows, 4)), dim3(256), 0, static_cast<hipStream_t>(stream), hdr,
+                       max_rows, logits, ld, n_classes, labels, root_ids, count);
     CR_LAUNCH_CHECK();
     return CR_OK;
 }

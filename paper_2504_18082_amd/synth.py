@@ -38,6 +38,7 @@ class WorkloadConfig:
     batch_size: int = 1024
     feat_comm_offset: float = 0.0
     label_noise: float = 0.1
+    val_fraction: float = 0.1      # of all nodes, drawn among the nodes outside the training set
 
 
 CONFIGS = {
@@ -81,6 +82,7 @@ class Workload:
     features: np.ndarray      # float32 [N, ld]  (ld = n_feat rounded up to 4) or uint16 (bf16)
     labels: np.ndarray        # int32 [N]
     train_ids: np.ndarray     # int32, ascending
+    val_ids: np.ndarray = None  # int32, ascending, disjoint from train_ids
     achieved_intra_fraction: float = 0.0
 
     @property
@@ -190,8 +192,12 @@ def make_workload(cfg: WorkloadConfig | str, seed: int = 0, with_features: bool 
         noisy = rng.random(N) < cfg.label_noise
         labels = np.where(noisy, rng.integers(0, cfg.n_classes, size=N, dtype=np.int32), labels).astype(np.int32)
     rng = np.random.default_rng([seed, 0x7EA1, 4])
-    train_ids = np.nonzero(rng.random(N) < cfg.train_fraction)[0].astype(np.int32)
-    return Workload(cfg, indptr, indices, comm, comm_ptr, feats, labels, train_ids, intra)
+    is_train = rng.random(N) < cfg.train_fraction
+    train_ids = np.nonzero(is_train)[0].astype(np.int32)
+    rng = np.random.default_rng([seed, 0x7A1D, 6])
+    p_val = min(1.0, cfg.val_fraction / max(1e-9, 1.0 - cfg.train_fraction))
+    val_ids = np.nonzero(~is_train & (rng.random(N) < p_val))[0].astype(np.int32)
+    return Workload(cfg, indptr, indices, comm, comm_ptr, feats, labels, train_ids, val_ids, intra)
 
 
 def layer_dims(cfg: WorkloadConfig):

@@ -123,15 +123,14 @@ class Trainer:
             ev1.record()
             self.gather0_events.append((ev0, ev1))
 
-    def train_batch(self, g: int, dW_out=None, db_out=None, slot: Optional[int] = None, buf: int = 0, gather0: bool = True):
-        """Forward, loss, backward and SGD for mini-batch g of a sampled group (current stream)."""
+    def forward_batch(self, g: int, slot: Optional[int] = None, buf: int = 0, gather0: bool = True):
+        """Forward pass of mini-batch g of a sampled group (current stream); leaves the logits in self.out[L-1]."""
         if slot is not None:
             self.blocks = self.block_slots[slot]
         else:
             slot = self.block_slots.index(self.blocks)
         self.self0, self.agg[0] = self.self0_bufs[buf], self.agg0_bufs[buf]
         L, blocks, layers = self.L, self.blocks, self.layers
-        # forward
         for l in range(L):
             blk, lay = blocks[l], layers[l]
             if l == 0:
@@ -148,6 +147,11 @@ class Trainer:
                 h_self, ld_in = self.out_b[l - 1], prev.N_pad
             B.cr_sage_linear_fwd(lay, blk.hdr_ptr(g), blk.cap_dst, h_self, self.agg[l], ld_in, l < L - 1,
                                  self.out[l], self.out_b[l])
+
+    def train_batch(self, g: int, dW_out=None, db_out=None, slot: Optional[int] = None, buf: int = 0, gather0: bool = True):
+        """Forward, loss, backward and SGD for mini-batch g of a sampled group (current stream)."""
+        self.forward_batch(g, slot, buf, gather0)
+        L, blocks, layers = self.L, self.blocks, self.layers
         # loss on the roots
         top = blocks[L - 1]
         B.cr_softmax_xent(top.hdr_ptr(g), top.cap_dst, self.out[L - 1], layers[L - 1].N_pad, self.cfg.n_classes,
@@ -282,9 +286,74 @@ class Trainer:
         self.weights_on_side_stream = False
         return nb
 
+    # ------------------------------------------------------------------ validation pass and training protocol
+    def evaluate(self, node_ids, epoch: int = 0, p_intra: float = 0.5):
+        """Forward-only pass over `node_ids` (device int32 tensor) in mini-batches of the training batch size,
+        neighbours sampled uniformly with the same fanouts.  Returns (mean loss, accuracy).  Validation batches
+        are numbered after the epoch's training batches, so they draw their own random streams."""
+        torch = self.torch
+        n = int(node_ids.numel())
+        if n == 0:
+            return float("nan"), float("nan")
+        nb = -(-n // self.B)
+        losses = torch.zeros(nb, dtype=torch.float32, device=node_ids.device)
+        correct = torch.zeros(1, dtype=torch.int32, device=node_ids.device)
+        top_l = self.L - 1
+        for first in range(0, nb, self.G):
+            cnt = min(self.G, nb - first)
+            scfg = B.make_sample_cfg(self.cfg.fanouts, p_intra, self.seed, epoch, self.n_batches + first, 0)
+            start = first * self.B
+            n_roots = min(n, start + cnt * self.B) - start
+            layers = self.block_slots[0] if cnt == self.G else [_view_block_set(b, cnt) for b in self.block_slots[0]]
+            arr = (B.cr_block_set * self.L)(*[b.c for b in layers])
+            B._check(B.lib().cr_sample_blocks(C.byref(self.graph), C.byref(scfg), C.c_void_p(node_ids.data_ptr() + 4 * start), n_roots,
+                                              self.B, cnt, B._ptr(self.ws_sample), self.ws_sample.numel(), arr, B._stream()))
+            for g in range(cnt):
+                self.forward_batch(g, slot=0, buf=0)
+                top = self.block_slots[0][top_l]
+                B.cr_softmax_xent(top.hdr_ptr(g), top.cap_dst, self.out[top_l], self.layers[top_l].N_pad, self.cfg.n_classes,
+                                  self.labels, top.src_ids_ptr(g), losses[first + g:first + g + 1], self.row_loss)
+                B.cr_count_correct(top.hdr_ptr(g), top.cap_dst, self.out[top_l], self.layers[top_l].N_pad, self.cfg.n_classes,
+                                   self.labels, top.src_ids_ptr(g), correct)
+        per_batch = losses.cpu().numpy().astype(np.float64)
+        sizes = np.full(nb, self.B, dtype=np.float64)
+        sizes[-1] = n - (nb - 1) * self.B
+        return float((per_batch * sizes).sum() / n), float(int(correct.cpu()[0]) / n)
+
+    def fit(self, policy: int, mix_count: int, p_intra: float, val_ids, max_epochs: int = 100, patience: int = 6,
+            lr_patience: int = 3, lr_factor: float = 0.1, first_epoch: int = 0):
+        """The paper's protocol: up to max_epochs epochs, early stop when the validation loss has not improved for
+        `patience` epochs, learning rate cut after `lr_patience` epochs on a plateau.  Returns a protocol.History."""
+        from . import protocol
+        torch = self.torch
+        sched = protocol.PlateauScheduler(self.lr, lr_patience, lr_factor)
+        stop = protocol.EarlyStopping(patience)
+        hist = protocol.History()
+        for e in range(first_epoch, first_epoch + max_epochs):
+            torch.cuda.synchronize()
+            t0 = _now()
+            self.run_epoch_serial(policy, mix_count, p_intra, e)
+            torch.cuda.synchronize()
+            hist.epoch_ms.append((_now() - t0) * 1e3)
+            hist.train_loss.append(float(self.loss.cpu()[0]))
+            vl, va = self.evaluate(val_ids, e)
+            hist.val_loss.append(vl)
+            hist.val_acc.append(va)
+            hist.lr.append(self.lr)
+            self.lr = sched.step(vl)
+            if stop.step(vl, e):
+                hist.stopped_early = True
+                break
+        return hist
+
     def headers(self):
         """Host copy of the current group's block headers: [layer][batch] -> (n_dst, n_src, nnz, status)."""
         return [b.hdr.cpu().numpy()[:, :4].copy() for b in self.blocks]
+
+
+def _now():
+    import time
+    return time.perf_counter()
 
 
 class _BlockSetView:

@@ -6,10 +6,8 @@ import numpy as np
 import oracle
 
 
-def oracle_train_step(graph, table, n_feat, labels, roots, fanouts, p, seed, epoch, batch, params, lr, wd,
-                      pos_map=None, strict=False):
-    """params: list of (W float64 [2F_in, F_out], b float64 [F_out]); returns dict with loss, logits,
-    grads and the updated params (inputs are not modified)."""
+def oracle_forward(graph, table, n_feat, roots, fanouts, p, seed, epoch, batch, params, pos_map=None, strict=False):
+    """Sampling and forward pass only; returns (blocks, h_self, aggs, outs)."""
     L = len(fanouts)
     blocks = oracle.sample_blocks(graph, roots, fanouts, p, strict, seed, epoch, batch, pos_map)
     h_self, aggs, outs = [None] * L, [None] * L, [None] * L
@@ -23,6 +21,15 @@ def oracle_train_step(graph, table, n_feat, labels, roots, fanouts, p, seed, epo
             aggs[l] = oracle.gather_mean(blk, prev, indirect=False)
             h_self[l] = outs[l - 1][:blk.n_dst]
         outs[l] = oracle.sage_linear_fwd(h_self[l], aggs[l], W, b, l < L - 1, True)
+    return blocks, h_self, aggs, outs
+
+
+def oracle_train_step(graph, table, n_feat, labels, roots, fanouts, p, seed, epoch, batch, params, lr, wd,
+                      pos_map=None, strict=False):
+    """params: list of (W float64 [2F_in, F_out], b float64 [F_out]); returns dict with loss, logits,
+    grads and the updated params (inputs are not modified)."""
+    L = len(fanouts)
+    blocks, h_self, aggs, outs = oracle_forward(graph, table, n_feat, roots, fanouts, p, seed, epoch, batch, params, pos_map, strict)
     loss, dz = oracle.softmax_xent(outs[L - 1], labels[np.asarray(roots)])
     grads, new_params = [None] * L, [None] * L
     for l in range(L - 1, -1, -1):

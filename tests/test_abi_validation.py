@@ -169,3 +169,10 @@ def test_linear_and_loss_validation():
     assert xent(C=65) == B.CR_ERR_INVALID_ARG
     assert xent(C=0) == B.CR_ERR_INVALID_ARG
     assert xent(logits=None) == B.CR_ERR_INVALID_ARG
+    cnt = lambda **kw: lib.cr_count_correct(vp(), kw.get("rows", 100), vp(kw.get("logits", FAKE)), kw.get("ld", 64), kw.get("C", 47), vp(), vp(),
+                                            vp(kw.get("count", FAKE)), None)
+    assert cnt() == B.CR_OK
+    assert cnt(C=65) == B.CR_ERR_INVALID_ARG
+    assert cnt(rows=0) == B.CR_ERR_INVALID_ARG
+    assert cnt(logits=None) == B.CR_ERR_INVALID_ARG
+    assert cnt(count=None) == B.CR_ERR_INVALID_ARG

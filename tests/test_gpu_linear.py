@@ -156,3 +156,30 @@ def test_softmax_xent(torch_mod, n, Cn):
     assert_close(got[:n], want_d, RTOL_F32, "d_logits")
     assert np.all(got[:n, Cn:] == 0) and np.all(np.isnan(got[n:]))
     assert_close(bf16_tensor_to_float(db)[:n], want_d, 2.0 ** -8, "d_logits bf16")
+
+
+@pytest.mark.parametrize("n,Cn", [(256, 10), (1024, 40), (1000, 172), (1, 7), (3, 1)])
+def test_count_correct(torch_mod, n, Cn):
+    """Integer result: the same float32 logits go to both sides, so the counts must agree exactly
+    (ties included: the lowest class index wins on both sides)."""
+    torch = torch_mod
+    from paper_2504_18082_amd import binding as B
+    rng = np.random.default_rng(7 * n + Cn)
+    ld = (Cn + 63) // 64 * 64
+    logits = np.zeros((n + 5, ld), dtype=np.float32)
+    logits[:, :Cn] = np.round(rng.standard_normal((n + 5, Cn)) * 2).astype(np.float32)    # coarse values: many exact ties
+    logits[:, Cn:] = 99.0                               # padded columns must be ignored
+    n_nodes = 5000
+    labels_all = rng.integers(0, Cn, size=n_nodes).astype(np.int32)
+    roots = rng.choice(n_nodes, size=n + 5, replace=False).astype(np.int32)
+    # make about half of the rows correct so that the count is not trivially small
+    for i in range(0, n, 2):
+        labels_all[roots[i]] = int(np.argmax(logits[i, :Cn]))
+    want = oracle.count_correct(logits[:n, :Cn].astype(np.float64), labels_all[roots[:n]])
+    up = lambda a: torch.from_numpy(a).cuda()
+    d_roots = up(roots)
+    count = torch.full((1,), 11, dtype=torch.int32, device="cuda")     # accumulates on top of what is there
+    hdr = hdr_for(torch, n)
+    B.cr_count_correct(C.c_void_p(hdr.data_ptr()), n + 5, up(logits), ld, Cn, up(labels_all), C.c_void_p(d_roots.data_ptr()), count)
+    torch.cuda.synchronize()
+    assert int(count.cpu()[0]) == 11 + want

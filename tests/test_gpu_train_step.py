@@ -137,3 +137,51 @@ def test_two_runs_are_bit_identical(tiny_workload):
     for a, b in zip(outs[0][0] + outs[0][1] + outs[0][2], outs[1][0] + outs[1][1] + outs[1][2]):
         assert np.array_equal(a, b)
     assert outs[0][3] == outs[1][3]
+
+
+def test_evaluate_matches_oracle_forward(tiny_workload):
+    """Validation pass (forward only, uniform neighbour sampling, batches numbered after the training batches):
+    mean loss and number of correct predictions against the oracle's forward pass over the same batches."""
+    import torch
+    from paper_2504_18082_amd.trainer import Trainer
+    from oracle_step import oracle_forward
+    w, seed, epoch = tiny_workload, 0, 2
+    cfg = w.cfg
+    weights = synth.init_weights(cfg, seed)
+    tr = Trainer(w, group_size=3, seed=seed, weights=weights)
+    val = w.val_ids[:cfg.batch_size * 3 + 100]          # 4 batches: one full group of 3 and a short group with a short batch
+    got_loss, got_acc = tr.evaluate(torch.from_numpy(val).cuda(), epoch)
+    params = [(W.astype(np.float64), b.astype(np.float64)) for W, b in weights]
+    pos = np.full(cfg.n_nodes, -1, dtype=np.int32)
+    loss_sum, correct, close_calls = 0.0, 0, 0
+    for b in range(0, -(-len(val) // cfg.batch_size)):
+        roots = val[b * cfg.batch_size:(b + 1) * cfg.batch_size]
+        _, _, _, outs = oracle_forward(w.graph, w.features, cfg.n_feat, roots, cfg.fanouts, 0.5, seed, epoch, tr.n_batches + b, params, pos)
+        logits = outs[-1]
+        loss, _ = oracle.softmax_xent(logits, w.labels[roots])
+        loss_sum += loss * len(roots)
+        correct += oracle.count_correct(logits, w.labels[roots])
+        top2 = np.sort(logits, axis=1)[:, -2:]
+        close_calls += int(np.sum(top2[:, 1] - top2[:, 0] < 2e-2 * np.abs(top2[:, 1]).clip(1e-3)))
+    want_loss = loss_sum / len(val)
+    assert abs(got_loss - want_loss) <= 1e-3 * abs(want_loss)
+    # the arg-max is decided on logits that differ by rounding: rows whose two best logits are closer than the
+    # floating-point tolerance may fall either way
+    assert abs(round(got_acc * len(val)) - correct) <= close_calls
+
+
+def test_fit_protocol_on_tiny(tiny_workload):
+    """The training protocol end to end on the small planted-community graph: the loss falls, validation
+    accuracy ends far above chance, the scheduler and early stopping act on the validation loss."""
+    import torch
+    from paper_2504_18082_amd.trainer import Trainer
+    w = tiny_workload
+    tr = Trainer(w, group_size=8, lr=0.1, weight_decay=5e-4, seed=0)
+    val = torch.from_numpy(w.val_ids).cuda()
+    loss0, acc0 = tr.evaluate(val, 0)
+    hist = tr.fit(oracle.COMM_RAND, 6, 0.9, val, max_epochs=12, patience=6, lr_patience=3)
+    print("val loss", [round(v, 4) for v in hist.val_loss], "val acc", [round(v, 4) for v in hist.val_acc], flush=True)
+    assert hist.epochs >= 6 and len(hist.epoch_ms) == hist.epochs
+    assert min(hist.val_loss) < 0.8 * loss0
+    assert max(hist.val_acc) > 3.0 / w.cfg.n_classes and max(hist.val_acc) > acc0
+    assert all(np.isfinite(hist.val_loss)) and all(np.isfinite(hist.train_loss))

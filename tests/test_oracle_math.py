@@ -194,3 +194,15 @@ def test_gradients_match_finite_differences(tiny_workload):
     # weight decay shrinks weights, leaves the bias alone
     W, b = oracle.sgd_step(np.ones((2, 2)), np.zeros((2, 2)), np.ones(2), np.zeros(2), 0.1, 0.5)
     assert np.allclose(W, 0.95) and np.allclose(b, 1.0)
+
+
+def test_count_correct_matches_numpy_argmax():
+    rng = np.random.default_rng(6)
+    z = rng.standard_normal((200, 13))
+    z[5, 3] = z[5, 7] = 9.0                       # a tie: the lower index wins, as numpy's argmax does
+    labels = rng.integers(0, 13, size=200).astype(np.int32)
+    labels[5] = 3
+    assert oracle.count_correct(z, labels) == int((np.argmax(z, axis=1) == labels).sum())
+    zp = np.concatenate([z, np.full((200, 3), 50.0)], axis=1)            # padded columns are ignored
+    assert oracle.count_correct(zp, labels, n_classes=13) == oracle.count_correct(z, labels)
+    assert oracle.count_correct(np.eye(4), np.arange(4, dtype=np.int32)) == 4
