@@ -47,16 +47,16 @@ CONFIGS = {
                            0.50, [10, 5], 64, 256, 0.5, 0.0),
     # sparse citation-like graph
     "arxiv": WorkloadConfig("arxiv", 170_000, 1_200_000, 500, 1.0, "powerlaw", 2.5, 0.75, 128,
-                            "f32", 40, 0.55, [15, 10, 5], 256, 1024),
+                            "f32", 40, 0.55, [15, 10, 5], 256, 1024, 0.3),
     # dense social-like graph (reddit's shape)
     "reddit": WorkloadConfig("reddit", 233_000, 57_000_000, 50, 0.5, "lognormal", 1.0, 0.85, 602,
-                             "f32", 41, 0.66, [25, 10], 256, 1024),
+                             "f32", 41, 0.66, [25, 10], 256, 1024, 0.3),
     # co-purchase-like graph (ogbn-products' shape)
     "products": WorkloadConfig("products", 2_450_000, 62_000_000, 5000, 1.0, "powerlaw", 2.5, 0.80,
-                               100, "f32", 47, 0.08, [15, 10, 5], 256, 1024),
+                               100, "f32", 47, 0.08, [15, 10, 5], 256, 1024, 0.3),
     # large citation-like graph (ogbn-papers100M's shape); see scaled()
     "papers": WorkloadConfig("papers", 111_000_000, 1_600_000_000, 100_000, 1.0, "powerlaw", 2.5,
-                             0.70, 128, "bf16", 172, 0.011, [15, 10, 5], 256, 1024),
+                             0.70, 128, "bf16", 172, 0.011, [15, 10, 5], 256, 1024, 0.3),
 }
 CONFIG_ORDER = ["tiny", "arxiv", "reddit", "products", "papers"]
 
