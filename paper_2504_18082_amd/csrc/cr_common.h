@@ -113,6 +113,18 @@ __device__ __forceinline__ uint32_t xcd_remap(uint32_t bid, uint32_t nblocks)
     return (bid % XCDS) * per + bid / XCDS;
 }
 
+// Same idea for grids sized by a capacity of which only the first `nwork` logical tiles exist (the
+// count is read from a device-side header): the first 8 * ceil(nwork / 8) blocks share the tiles so that
+// every XCD walks one contiguous range; returns false for a block that has no tile.
+__device__ __forceinline__ bool xcd_compact(uint32_t bid, uint32_t nwork, uint32_t &logical)
+{
+    constexpr uint32_t XCDS = 8;
+    const uint32_t per = (nwork + XCDS - 1) / XCDS;
+    if (bid >= per * XCDS) return false;
+    logical = (bid % XCDS) * per + bid / XCDS;
+    return logical < nwork;
+}
+
 // ---------------------------------------------------------------------------------------------
 // exclusive scan of n ints by one workgroup of 1024 threads (one workgroup per batch)
 // ---------------------------------------------------------------------------------------------

@@ -120,8 +120,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) voi
     __shared__ __attribute__((aligned(16))) uint16_t As[2][128][LDS_ROW];
     __shared__ __attribute__((aligned(16))) uint16_t Bs[2][BN][LDS_ROW];
     const int M = min(a.hdr[CR_HDR_N_DST], a.max_rows);
-    const int m0 = blockIdx.y * 128, n0 = blockIdx.x * BN;
-    if (m0 >= M) return;
+    // the column tiles of one row tile run next to each other on one XCD: the activations come from HBM once
+    uint32_t tile;
+    if (!xcd_compact(blockIdx.y * gridDim.x + blockIdx.x, (uint32_t)((M + 127) / 128) * gridDim.x, tile)) return;
+    const int m0 = (int)(tile / gridDim.x) * 128, n0 = (int)(tile % gridDim.x) * BN;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, lr = lane & 31;
 
@@ -198,7 +200,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) voi
 // and occupancy, not by the matrix cores, so the smallest tile with the deepest prefetch wins.
 static void launch_nt(const NtArgs &a, hipStream_t s)
 {
-    hipLaunchKernelGGL((gemm_nt_kernel<2, 8>), dim3(a.N / 64, (unsigned)ceil_div(a.max_rows, 128)), dim3(256), 0, s, a);
+    // xcd_compact needs the grid rounded up to a multiple of eight blocks
+    const unsigned ncol = (unsigned)(a.N / 64);
+    hipLaunchKernelGGL((gemm_nt_kernel<2, 8>), dim3(ncol, (unsigned)ceil_div(a.max_rows, 128) + (7 + ncol - 1) / ncol), dim3(256), 0, s, a);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -226,18 +230,21 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(TnArgs a)
     // [buffer][operand: 0 = A, 1 = Z][group of four m][column] -> four consecutive m of one column (8 bytes)
     __shared__ __attribute__((aligned(16))) uint2 T[2][2][8][128];
     const int M = min(a.hdr[CR_HDR_N_DST], a.max_rows);
-    const int split = blockIdx.y;
+    // the tiles of one split run next to each other on one XCD (they share the split's rows of A and Z);
+    // splits past the last row stay inactive, and the reduction skips them too
+    uint32_t work;
+    if (!xcd_compact(blockIdx.y * gridDim.x + blockIdx.x, (uint32_t)((M + a.rows_per_split - 1) / a.rows_per_split) * gridDim.x, work)) return;
+    const int split = (int)(work / gridDim.x), tile_id = (int)(work % gridDim.x);
     const int m_begin = split * a.rows_per_split;
-    if (m_begin >= M) return;                      // inactive split: the reduction skips it too
     const int m_end = min(M, m_begin + a.rows_per_split);
     const int n_tiles = (a.N + 127) / 128;
     const int k_tiles_part = (a.K0 + 127) / 128;   // k-tiles per operand part (self | agg): a tile never straddles the two
-    const int kt = blockIdx.x / n_tiles;
+    const int kt = tile_id / n_tiles;
     const int part = kt / k_tiles_part;
     const int kp0 = (kt % k_tiles_part) * 128;     // first column of the tile inside its part
     const int k0 = part * a.K0 + kp0;              // first row of the output tile
     const int k_valid = min(128, a.K0 - kp0);
-    const int n0 = (blockIdx.x % n_tiles) * 128;
+    const int n0 = (tile_id % n_tiles) * 128;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, lr = lane & 31;
     const int wk = wave >> 1, wn = wave & 1;
@@ -656,7 +663,8 @@ extern "C" cr_status cr_sage_linear_bwd(const cr_sage_layer *layer, const int32_
     TnArgs t;
     t.hdr = hdr; t.max_rows = max_rows; t.A0 = h_self; t.A1 = agg; t.lda = ld_in; t.K0 = F_pad; t.K2 = 2 * F_pad;
     t.Z = dz_bf16; t.N = N_pad; t.rows_per_split = rows; t.partial = partial;
-    hipLaunchKernelGGL(gemm_tn_kernel, dim3((unsigned)(2 * ceil_div(F_pad, 128) * ceil_div(N_pad, 128)), splits), dim3(256), 0, s, t);
+    const unsigned tn_tiles = (unsigned)(2 * ceil_div(F_pad, 128) * ceil_div(N_pad, 128));
+    hipLaunchKernelGGL(gemm_tn_kernel, dim3(tn_tiles, (unsigned)splits + (7 + tn_tiles - 1) / tn_tiles), dim3(256), 0, s, t);
     SgdArgs g;
     g.hdr = hdr; g.max_rows = max_rows; g.rows_per_split = rows; g.n_splits = splits; g.partial = partial;
     g.F_in = layer->F_in; g.F_out = layer->F_out; g.F_pad = F_pad; g.N_pad = N_pad; g.W = layer->W; g.bias = layer->bias;
