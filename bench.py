@@ -41,7 +41,7 @@ def run_setting(tr, policy, mix, p, steps, warmup, epoch0, serial="none"):
     import torch
     from paper_2504_18082_amd import binding as B
     G = tr.G
-    stats = dict(gather_bytes=0, feat_bytes=0, n_src0=0, rows0=0, launches=0)
+    stats = dict(gather_bytes=0, feat_bytes=0, rows0=0, launches=0)
 
     def run(n_steps, epoch, timed):
         # whole epochs (root partitioning, then the batches group by group) until n_steps steps are done
@@ -85,14 +85,14 @@ def run_setting(tr, policy, mix, p, steps, warmup, epoch0, serial="none"):
             tot, feat = gather0_bytes(h[g], tr.cfg.n_feat, elem, tr.layers[0].F_pad)
             stats["gather_bytes"] += tot
             stats["feat_bytes"] += feat
-            stats["n_src0"] += int(h[g][1])
             stats["rows0"] += int(h[g][2]) + int(h[g][0])
             stats["launches"] += 1
+    # distinct input nodes per batch: counted outside the timed region (a training step does not need them)
+    mean_input_nodes, unique_row_ratio = tr.input_node_stats(policy, mix, p, epoch0 + 1000)
     return dict(ms_per_step=dt * 1e3 / steps, total_s=dt, gather_ms_per_launch=gather_ms / max(1, stats["launches"]),
                 gather_bytes_per_launch=stats["gather_bytes"] / max(1, stats["launches"]),
                 feat_bytes_per_step=stats["feat_bytes"] / max(1, stats["launches"]),
-                unique_row_ratio=stats["n_src0"] / max(1, stats["rows0"]),
-                mean_input_nodes=stats["n_src0"] / max(1, stats["launches"]))
+                unique_row_ratio=unique_row_ratio, mean_input_nodes=mean_input_nodes)
 
 
 def cpu_baseline(w, n_batches_sample, seed):

@@ -139,6 +139,14 @@ typedef struct {
 #define CR_SAMPLE_HASH_DEDUP 2u   /* de-duplicate the frontier with the open-addressing table even when the graph is small
                                      enough for the direct-address table (less workspace; same results) */
 
+#define CR_SAMPLE_INPUT_GLOBAL_IDS 4u /* leave the input-side block (layer 0) in global ids: its frontier is not
+                                     de-duplicated or relabelled.  Produced for layer 0: hdr (N_DST, NNZ, STATUS;
+                                     N_SRC = -1), indptr, gather_ids (required) and src_ids[0..n_dst) (the destination
+                                     nodes); src_ids beyond n_dst and indices are left untouched.  For a caller that
+                                     reads the resident feature table through gather_ids and needs no gradient of the
+                                     input features: the blocks of the layers above, and every result computed from
+                                     them, are unchanged. */
+
 typedef struct {
     int32_t n_layers;              /* 1..CR_MAX_LAYERS */
     int32_t fanout[CR_MAX_LAYERS]; /* by GNN layer, 0 = input side; the roots are expanded with fanout[n_layers-1] */

@@ -21,6 +21,7 @@ CR_ROOTS_NORAND, CR_ROOTS_COMM_RAND, CR_ROOTS_RAND = 0, 1, 2
 CR_F32, CR_BF16 = 0, 1
 CR_SAMPLE_STRICT_INTRA = 1
 CR_SAMPLE_HASH_DEDUP = 2
+CR_SAMPLE_INPUT_GLOBAL_IDS = 4
 
 EXPORTS = [
     "cr_last_error", "cr_version", "cr_set_dry_run", "cr_mix_count_from_percent",

@@ -65,82 +65,66 @@ __device__ __forceinline__ uint64_t push64(uint64_t v, int dst_lane)
     return ((uint64_t)push32((uint32_t)(v >> 32), dst_lane) << 32) | push32((uint32_t)v, dst_lane);
 }
 
-// One wave per destination row.  A slot's ordering value is the pair (key, slot); with WIDE == false
-// (p = 0.5, 32-bit keys) the pair is packed into one 64-bit word.  Lanes 0..k-1 hold the k smallest
-// pairs seen so far in ascending order: the first 64 slots are ranked by counting and permuted into
-// place, later chunks of 64 slots are tested against the k-th pair and inserted by shifting.  Every
-// pair is distinct, so the surviving set is unique.
+__device__ __forceinline__ uint32_t pull32(uint32_t v, int src_lane) { return (uint32_t)__builtin_amdgcn_ds_bpermute(src_lane << 2, (int)v); }
+
+// ordering key of slot j of node v given its random word: narrow mode (p = 0.5) uses the word itself
 template <bool WIDE>
-__global__ __launch_bounds__(256) void select_kernel(SelectArgs a)
+__device__ __forceinline__ uint64_t slot_key(const SelectArgs &a, uint32_t r, bool intra)
 {
-    const int g = blockIdx.y;
-    const int n_dst = group_n_dst(a.prev_hdr, g, a.n_roots_total, a.batch_size);
-    const int row = (int)(blockIdx.x * 4 + threadIdx.x / WAVE);
-    if (row >= n_dst) return;
-    const int lane = lane_id();
+    if (!WIDE) return r;
+    if (a.q_out == 0) return (intra ? 0ull : (1ull << 62)) + (uint64_t)r;
+    return (uint64_t)exp_clock_q24(r) * (uint64_t)(intra ? a.q_out : a.q_in);
+}
+
+__device__ __forceinline__ uint32_t slot_word(const SelectArgs &a, int j, int32_t v, uint32_t batch)
+{
+    const u32x4 w = philox4x32_10((uint32_t)j >> 2, (uint32_t)v, batch, a.ctr3, a.seed_lo, a.seed_hi);
+    const uint32_t pick = (uint32_t)j & 3u;
+    return pick == 0 ? w.x : (pick == 1 ? w.y : (pick == 2 ? w.z : w.w));
+}
+
+// A row with more than 64 neighbours, handled by a whole wave.  A slot's ordering value is the pair
+// (key, slot); with WIDE == false (p = 0.5, 32-bit keys) the pair is packed into one 64-bit word.
+// Lanes 0..k-1 hold the k smallest pairs seen so far in ascending order: the first 64 slots are ranked
+// by counting and permuted into place, later chunks of 64 slots are tested against the k-th pair and
+// inserted by shifting.  Every pair is distinct, so the surviving set is unique.
+template <bool WIDE>
+__device__ __forceinline__ void select_big_row(const SelectArgs &a, int g, int row, int32_t v, int64_t base, int deg, int32_t cv,
+                                               int lane)
+{
     const int f = a.fanout;
-    const int32_t v = a.dst_ids[(int64_t)g * a.dst_stride + row];
-    const int64_t base = a.g_indptr[v];
-    const int64_t deg64 = a.g_indptr[v + 1] - base;
-    const int deg = (int)(deg64 > 0x7FFFFFFF ? 0x7FFFFFFF : deg64);
-    const int32_t cv = WIDE ? a.comm[v] : 0;
     int32_t *sel_row = a.sel + (int64_t)g * a.sel_stride + (int64_t)row * f;
-    const uint64_t lt_mask = (1ull << lane) - 1ull;
-
-    if (deg <= f) {   // every neighbour is taken (minus inter-community ones in strict mode): no keys needed
-        int32_t u = 0;
-        bool valid = lane < deg;
-        if (valid) {
-            u = a.g_indices[base + lane];
-            if (WIDE && a.strict_p1) valid = a.comm[u] == cv;
-        }
-        const uint64_t vmask = __ballot(valid);
-        if (valid) sel_row[__popcll(vmask & lt_mask)] = u;
-        if (lane == 0) a.cnt[(int64_t)g * a.cnt_stride + row] = __popcll(vmask);
-        return;
-    }
-
     const int k = f;
     const uint32_t batch = a.first_batch + (uint32_t)g;
     auto less = [&](uint64_t ka, uint32_t sa, uint64_t kb, uint32_t sb) -> bool {
         if (!WIDE) return ka < kb;
         return ka < kb || (ka == kb && sa < sb);
     };
-    // ordering pair of slot j given its random word (and, in wide mode, its class):
-    // narrow mode packs (word << 32 | slot) into ck
     auto make_key = [&](uint32_t r, int j, bool intra, uint64_t &ck, uint32_t &cs) {
         if (!WIDE) {
             ck = ((uint64_t)r << 32) | (uint32_t)j;
             cs = 0;
         } else {
-            if (a.q_out == 0) ck = (intra ? 0ull : (1ull << 62)) + (uint64_t)r;
-            else ck = (uint64_t)exp_clock_q24(r) * (uint64_t)(intra ? a.q_out : a.q_in);
+            ck = slot_key<true>(a, r, intra);
             cs = (uint32_t)j;
         }
-    };
-    auto word_of = [&](int j) -> uint32_t {
-        const u32x4 w = philox4x32_10((uint32_t)j >> 2, (uint32_t)v, batch, a.ctr3, a.seed_lo, a.seed_hi);
-        const uint32_t pick = (uint32_t)j & 3u;
-        return pick == 0 ? w.x : (pick == 1 ? w.y : (pick == 2 ? w.z : w.w));
     };
     // neighbour class look-ups are clamped to the row, so they can be issued ahead unconditionally
     auto load_u = [&](int j) -> int32_t { return a.g_indices[base + min(j, deg - 1)]; };
 
-    // first chunk: rank the first min(deg, 64) slots by counting, then move rank r to lane r
+    // first chunk: rank the first 64 slots by counting, then move rank r to lane r
     uint64_t ck = KEY_MAX;
     uint32_t cs = 0xFFFFFFFFu;
-    const int n0 = deg < WAVE ? deg : WAVE;
     {
         bool intra = false;
         if (WIDE) intra = a.comm[load_u(lane)] == cv;
-        if (lane < n0) make_key(word_of(lane), lane, intra, ck, cs);
+        make_key(slot_word(a, lane, v, batch), lane, intra, ck, cs);
         int rank = 0;
-        for (int j = 0; j < n0; ++j) {
+        for (int j = 0; j < WAVE; ++j) {
             const uint64_t kj = rl64(ck, j);
             const uint32_t sj = WIDE ? rl32(cs, j) : 0u;
             rank += less(kj, sj, ck, cs) ? 1 : 0;
         }
-        if (lane >= n0) rank = lane;
         ck = push64(ck, rank);
         if (WIDE) cs = push32(cs, rank);
     }
@@ -166,34 +150,32 @@ __global__ __launch_bounds__(256) void select_kernel(SelectArgs a)
             }
         }
     };
-    if (deg > WAVE) {
-        if (!WIDE) {
-            // uniform sampling needs no neighbour data at all: one Philox block gives a lane the words of
-            // four consecutive slots, so an iteration covers 256 slots with arithmetic only
-            for (int j0 = WAVE; j0 < deg; j0 += 4 * WAVE) {
-                const int jb = j0 + 4 * lane;
-                const u32x4 w = philox4x32_10((uint32_t)jb >> 2, (uint32_t)v, batch, a.ctr3, a.seed_lo, a.seed_hi);
-                const uint32_t wr[4] = {w.x, w.y, w.z, w.w};
+    if (!WIDE) {
+        // uniform sampling needs no neighbour data at all: one Philox block gives a lane the words of
+        // four consecutive slots, so an iteration covers 256 slots with arithmetic only
+        for (int j0 = WAVE; j0 < deg; j0 += 4 * WAVE) {
+            const int jb = j0 + 4 * lane;
+            const u32x4 w = philox4x32_10((uint32_t)jb >> 2, (uint32_t)v, batch, a.ctr3, a.seed_lo, a.seed_hi);
+            const uint32_t wr[4] = {w.x, w.y, w.z, w.w};
 #pragma unroll
-                for (int i = 0; i < 4; ++i) offer(jb + i < deg, ((uint64_t)wr[i] << 32) | (uint32_t)(jb + i), 0u);
-            }
-        } else {
-            // biased sampling needs the class of every neighbour: ids are fetched two chunks ahead and
-            // classes one chunk ahead, so the dependent look-ups overlap the arithmetic
-            int32_t u1 = load_u(WAVE + lane);
-            int32_t c1 = a.comm[u1];
-            int32_t u2 = load_u(2 * WAVE + lane);
-            for (int j0 = WAVE; j0 < deg; j0 += WAVE) {
-                const int32_t c2 = a.comm[u2];
-                const int32_t u3 = load_u(j0 + 2 * WAVE + lane);
-                const int j = j0 + lane;
-                uint64_t nk = KEY_MAX;
-                uint32_t ns = 0xFFFFFFFFu;
-                if (j < deg) make_key(word_of(j), j, c1 == cv, nk, ns);
-                offer(j < deg, nk, ns);
-                c1 = c2;
-                u2 = u3;
-            }
+            for (int i = 0; i < 4; ++i) offer(jb + i < deg, ((uint64_t)wr[i] << 32) | (uint32_t)(jb + i), 0u);
+        }
+    } else {
+        // biased sampling needs the class of every neighbour: ids are fetched two chunks ahead and
+        // classes one chunk ahead, so the dependent look-ups overlap the arithmetic
+        int32_t u1 = load_u(WAVE + lane);
+        int32_t c1 = a.comm[u1];
+        int32_t u2 = load_u(2 * WAVE + lane);
+        for (int j0 = WAVE; j0 < deg; j0 += WAVE) {
+            const int32_t c2 = a.comm[u2];
+            const int32_t u3 = load_u(j0 + 2 * WAVE + lane);
+            const int j = j0 + lane;
+            uint64_t nk = KEY_MAX;
+            uint32_t ns = 0xFFFFFFFFu;
+            if (j < deg) make_key(slot_word(a, j, v, batch), j, c1 == cv, nk, ns);
+            offer(j < deg, nk, ns);
+            c1 = c2;
+            u2 = u3;
         }
     }
 
@@ -211,6 +193,105 @@ __global__ __launch_bounds__(256) void select_kernel(SelectArgs a)
     const uint64_t vmask = __ballot(valid);
     if (valid) sel_row[rank] = cu;
     if (lane == 0) a.cnt[(int64_t)g * a.cnt_stride + row] = __popcll(vmask);
+}
+
+// A wave takes SEL_ROWS consecutive destination rows.  Rows with at most 64 neighbours are packed side
+// by side into the wave's lanes (lane = one neighbour slot of one row; as many consecutive rows per pass
+// as fit), so that the random words, the keys and the ranking of several short rows cost one pass of
+// instructions: a row with deg <= fanout keeps every neighbour, otherwise the slots whose (key, slot)
+// pair ranks below the fanout inside their row survive; output keeps slot order.  Longer rows go through
+// select_big_row one at a time.
+constexpr int SEL_ROWS = 4;
+
+template <bool WIDE>
+__global__ __launch_bounds__(256) void select_kernel(SelectArgs a)
+{
+    const int g = blockIdx.y;
+    const int n_dst = group_n_dst(a.prev_hdr, g, a.n_roots_total, a.batch_size);
+    const int row0 = (int)(blockIdx.x * 4 + threadIdx.x / WAVE) * SEL_ROWS;
+    if (row0 >= n_dst) return;
+    const int lane = lane_id();
+    const int f = a.fanout;
+    const uint32_t batch = a.first_batch + (uint32_t)g;
+
+    // lanes 0..SEL_ROWS-1 fetch one row's node id, adjacency range and community each
+    int32_t mv = 0, mcv = 0;
+    int64_t mbase = 0;
+    int mdeg = 0;
+    if (lane < SEL_ROWS && row0 + lane < n_dst) {
+        mv = a.dst_ids[(int64_t)g * a.dst_stride + row0 + lane];
+        mbase = a.g_indptr[mv];
+        const int64_t d = a.g_indptr[mv + 1] - mbase;
+        mdeg = (int)(d > 0x7FFFFFFF ? 0x7FFFFFFF : d);
+        if (WIDE) mcv = a.comm[mv];
+        if (mdeg == 0) a.cnt[(int64_t)g * a.cnt_stride + row0 + lane] = 0;
+    }
+    int32_t v[SEL_ROWS], cv[SEL_ROWS];
+    int deg[SEL_ROWS], start[SEL_ROWS], pass[SEL_ROWS];
+    int64_t base[SEL_ROWS];
+    int off = 0, last_pass = 0;
+#pragma unroll
+    for (int i = 0; i < SEL_ROWS; ++i) {
+        v[i] = (int32_t)rl32((uint32_t)mv, i);
+        cv[i] = WIDE ? (int32_t)rl32((uint32_t)mcv, i) : 0;
+        deg[i] = (int)rl32((uint32_t)mdeg, i);
+        base[i] = (int64_t)rl64((uint64_t)mbase, i);
+        // greedy packing of the short rows into passes of at most 64 lanes
+        pass[i] = -1;
+        start[i] = 0;
+        if (deg[i] > 0 && deg[i] <= WAVE) {
+            if (off + deg[i] > WAVE) { ++last_pass; off = 0; }
+            pass[i] = last_pass;
+            start[i] = off;
+            off += deg[i];
+        }
+    }
+
+    for (int p = 0; p <= last_pass; ++p) {
+        int ri = -1, my_start = 0, my_len = 0, maxlen = 0;
+        int32_t my_v = 0, my_cv = 0;
+        int64_t my_base = 0;
+#pragma unroll
+        for (int i = 0; i < SEL_ROWS; ++i) {
+            if (pass[i] != p) continue;                       // uniform
+            if (deg[i] > f) maxlen = max(maxlen, deg[i]);
+            if (lane >= start[i] && lane < start[i] + deg[i]) {
+                ri = i; my_start = start[i]; my_len = deg[i]; my_v = v[i]; my_cv = cv[i]; my_base = base[i];
+            }
+        }
+        const bool active = ri >= 0;
+        if (__ballot(active) == 0) continue;
+        const int j = lane - my_start;
+        int32_t u = 0;
+        if (active) u = a.g_indices[my_base + j];
+        bool intra = false;
+        if (WIDE && active && (maxlen > 0 || a.strict_p1)) intra = a.comm[u] == my_cv;
+        bool survivor = active && !(WIDE && a.strict_p1 && !intra);
+        if (maxlen > 0) {
+            // every lane computes its slot's key; lanes of rows that keep all their neighbours ignore it
+            const uint64_t ck = slot_key<WIDE>(a, slot_word(a, j, my_v, batch), intra);
+            int rank = 0;
+            for (int d = 0; d < maxlen; ++d) {
+                const int src = my_start + d;
+                uint64_t ok;
+                if (WIDE) ok = ((uint64_t)pull32((uint32_t)(ck >> 32), src) << 32) | pull32((uint32_t)ck, src);
+                else ok = pull32((uint32_t)ck, src);
+                rank += (d < my_len && (ok < ck || (ok == ck && d < j))) ? 1 : 0;
+            }
+            if (active && my_len > f) survivor = rank < f && !(WIDE && a.strict_p1 && ck >= (1ull << 62));
+        }
+        const uint64_t seg = (my_len >= WAVE ? ~0ull : ((1ull << my_len) - 1ull)) << my_start;
+        const uint64_t smask = __ballot(survivor) & seg;
+        if (active) {
+            const int row = row0 + ri;
+            if (survivor) a.sel[(int64_t)g * a.sel_stride + (int64_t)row * f + __popcll(smask & ((1ull << lane) - 1ull))] = u;
+            if (j == 0) a.cnt[(int64_t)g * a.cnt_stride + row] = __popcll(smask);
+        }
+    }
+
+#pragma unroll
+    for (int i = 0; i < SEL_ROWS; ++i)
+        if (deg[i] > WAVE) select_big_row<WIDE>(a, g, row0 + i, v[i], base[i], deg[i], cv[i], lane);
 }
 
 struct ScanArgs {
@@ -436,6 +517,17 @@ __global__ __launch_bounds__(256) void relabel_kernel(DedupArgs a)
     if (a.tcount) atomicAdd(&a.tcount[(int64_t)g * a.t_stride + local], 1);
 }
 
+// input-side block left in global ids: compact the chosen neighbours into CSR order, copy the
+// destination nodes into the head of the frontier, mark the frontier size as not computed
+__global__ __launch_bounds__(256) void compact_ids_kernel(DedupArgs a)
+{
+    CR_ROW_LANE();
+    if (blockIdx.x == 0 && threadIdx.x == 0) hdr[CR_HDR_N_SRC] = -1;
+    if (in_row && j == 0) a.src_ids[(int64_t)g * a.src_stride + row] = a.dst_ids[(int64_t)g * a.dst_stride + row];
+    if (!active) return;
+    a.gather_ids[(int64_t)g * a.indices_stride + rstart + j] = a.sel[(int64_t)g * a.sel_stride + ell];
+}
+
 // direct-address table: put the entries this hop touched back to "absent"
 __global__ __launch_bounds__(256) void reset_kernel(DedupArgs a)
 {
@@ -605,6 +697,8 @@ extern "C" cr_status cr_sample_blocks(const cr_graph *graph, const cr_sample_cfg
         CR_REQUIRE((b.t_indptr == nullptr) == (b.t_indices == nullptr), CR_ERR_INVALID_ARG,
                    "layers[%d]: t_indptr and t_indices must be given together", l);
         CR_REQUIRE(l >= 1 || b.t_indptr == nullptr, CR_ERR_UNSUPPORTED, "layer 0 takes no transposed block (its input needs no gradient)");
+        CR_REQUIRE(l >= 1 || !(cfg->flags & CR_SAMPLE_INPUT_GLOBAL_IDS) || b.gather_ids != nullptr, CR_ERR_INVALID_ARG,
+                   "CR_SAMPLE_INPUT_GLOBAL_IDS needs layers[0].gather_ids");
     }
     if (dry_run()) return CR_OK;
 
@@ -631,23 +725,14 @@ extern "C" cr_status cr_sample_blocks(const cr_graph *graph, const cr_sample_cfg
         sa.ctr3 = (cfg->epoch << 8) | (DOMAIN_NEIGHBOUR << 4) | (uint32_t)l;
         sa.first_batch = cfg->first_batch;
         sa.sel = p.sel; sa.sel_stride = p.max_nnz; sa.cnt = p.cnt; sa.cnt_stride = p.max_dst;
-        if (q_in == q_out) hipLaunchKernelGGL(select_kernel<false>, dim3((unsigned)ceil_div(cap_dst, 4), n_batches), blk, 0, s, sa);
-        else hipLaunchKernelGGL(select_kernel<true>, dim3((unsigned)ceil_div(cap_dst, 4), n_batches), blk, 0, s, sa);
+        if (q_in == q_out) hipLaunchKernelGGL(select_kernel<false>, dim3((unsigned)ceil_div(cap_dst, 4 * SEL_ROWS), n_batches), blk, 0, s, sa);
+        else hipLaunchKernelGGL(select_kernel<true>, dim3((unsigned)ceil_div(cap_dst, 4 * SEL_ROWS), n_batches), blk, 0, s, sa);
 
         ScanArgs sc;
         sc.prev_hdr = prev_hdr; sc.n_roots_total = n_roots_total; sc.batch_size = batch_size;
         sc.mode = 0; sc.in = p.cnt; sc.in_stride = p.max_dst; sc.out = b.indptr; sc.out_stride = b.cap_dst + 1;
         sc.out_copy = nullptr; sc.copy_stride = 0; sc.hdr = b.hdr;
         hipLaunchKernelGGL(scan_kernel, dim3(n_batches), dim3(1024), 0, s, sc);
-
-        if (!p.direct) {
-            const int64_t table_size = 1ll << p.table_bits[l];
-            hipLaunchKernelGGL(fill_u64_kernel, dim3((unsigned)(ceil_div(table_size, 512) < 4096 ? ceil_div(table_size, 512) : 4096), n_batches), blk, 0, s,
-                               p.table, p.table_stride, table_size, EMPTY);
-        } else if (root) {   // once per call; every hop puts the entries it touched back
-            hipLaunchKernelGGL(fill_u64_kernel, dim3((unsigned)(ceil_div(p.table_stride, 512) < 4096 ? ceil_div(p.table_stride, 512) : 4096), n_batches), blk, 0, s,
-                               p.table, p.table_stride, p.table_stride, 0x7FFFFFFF7FFFFFFFull);
-        }
 
         DedupArgs da;
         da.prev_hdr = prev_hdr; da.n_roots_total = n_roots_total; da.batch_size = batch_size; da.fanout = f;
@@ -658,11 +743,27 @@ extern "C" cr_status cr_sample_blocks(const cr_graph *graph, const cr_sample_cfg
         da.hdr = b.hdr; da.src_ids = b.src_ids; da.src_stride = b.cap_src;
         da.indptr = b.indptr; da.indptr_stride = b.cap_dst + 1; da.indices = b.indices; da.indices_stride = b.cap_nnz; da.gather_ids = b.gather_ids;
         da.newcnt = p.cnt; da.newoff = p.newoff; da.newmask = p.newmask; da.row_stride = p.max_dst; da.off_stride = p.max_dst + 1;
+        const dim3 grid((unsigned)ceil_div((int64_t)cap_dst * da.gw, 256), n_batches);
+        if (l == 0 && (cfg->flags & CR_SAMPLE_INPUT_GLOBAL_IDS)) {
+            da.tcount = nullptr; da.tfill = nullptr; da.t_stride = 0; da.t_indptr = nullptr; da.t_indptr_stride = 0;
+            da.t_indices = nullptr; da.t_tmp = nullptr; da.t_pos = nullptr; da.tt_stride = 0;
+            hipLaunchKernelGGL(compact_ids_kernel, grid, blk, 0, s, da);
+            continue;
+        }
+
+        if (!p.direct) {
+            const int64_t table_size = 1ll << p.table_bits[l];
+            hipLaunchKernelGGL(fill_u64_kernel, dim3((unsigned)(ceil_div(table_size, 512) < 4096 ? ceil_div(table_size, 512) : 4096), n_batches), blk, 0, s,
+                               p.table, p.table_stride, table_size, EMPTY);
+        } else if (root) {   // once per call; every hop puts the entries it touched back
+            hipLaunchKernelGGL(fill_u64_kernel, dim3((unsigned)(ceil_div(p.table_stride, 512) < 4096 ? ceil_div(p.table_stride, 512) : 4096), n_batches), blk, 0, s,
+                               p.table, p.table_stride, p.table_stride, 0x7FFFFFFF7FFFFFFFull);
+        }
+
         const bool tr = b.t_indptr != nullptr;
         da.tcount = tr ? p.tcount : nullptr; da.tfill = p.tfill; da.t_stride = p.max_src_t + 1;
         da.t_indptr = b.t_indptr; da.t_indptr_stride = b.cap_src + 1; da.t_indices = b.t_indices;
         da.t_tmp = p.t_tmp; da.t_pos = p.t_pos; da.tt_stride = p.max_nnz_t + 1;
-        const dim3 grid((unsigned)ceil_div((int64_t)cap_dst * da.gw, 256), n_batches);
         hipLaunchKernelGGL(insert_kernel, grid, blk, 0, s, da);
         hipLaunchKernelGGL(mark_new_kernel, grid, blk, 0, s, da);
         sc.mode = 1; sc.in = p.cnt; sc.in_stride = p.max_dst; sc.out = p.newoff; sc.out_stride = p.max_dst + 1;

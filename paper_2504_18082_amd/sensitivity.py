@@ -39,15 +39,8 @@ def time_setting(tr, policy, mix, p, steps, warmup, epoch0):
     tr.time_gather0 = False
     gather_ms = sum(a.elapsed_time(b) for a, b in tr.gather0_events) / max(1, len(tr.gather0_events))
     # input nodes per batch (the rows of X a batch touches), over the first groups of one more epoch
-    nb = tr.build_batches(policy, mix, epoch0 + 2000)
-    n_src, n_seen = 0, 0
-    for first in range(0, min(nb, 4 * tr.G), tr.G):
-        n = min(tr.G, nb - first)
-        tr.sample_group(first, n, p, epoch0 + 2000)
-        h = tr.headers()[0]
-        n_src += int(h[:n, 1].sum())
-        n_seen += n
-    return dt * 1e3 / steps, gather_ms, n_src / max(1, n_seen)
+    n_in, _ = tr.input_node_stats(policy, mix, p, epoch0 + 2000)
+    return dt * 1e3 / steps, gather_ms, n_in
 
 
 def main(argv=None):

@@ -20,7 +20,8 @@ from . import synth
 
 class Trainer:
     def __init__(self, workload: synth.Workload, group_size: int = 16, lr: float = 0.01,
-                 weight_decay: float = 5e-4, seed: int = 0, device: str = "cuda", weights=None):
+                 weight_decay: float = 5e-4, seed: int = 0, device: str = "cuda", weights=None,
+                 relabel_input: bool = False):
         import torch
         self.torch = torch
         self.w = workload
@@ -30,6 +31,10 @@ class Trainer:
         self.B = cfg.batch_size
         self.G = group_size
         self.lr, self.wd, self.seed = lr, weight_decay, seed
+        # The layer-0 gather reads the feature table through per-edge global ids and the features take no
+        # gradient, so nothing in a training step needs the input frontier de-duplicated or relabelled
+        # (relabel_input=True asks for it anyway, e.g. to count the distinct input nodes of a batch).
+        self.sample_flags = 0 if relabel_input else B.CR_SAMPLE_INPUT_GLOBAL_IDS
         up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(device)
         self.indptr = up(workload.indptr.astype(np.int64))
         self.indices = up(workload.indices.astype(np.int32))
@@ -94,11 +99,12 @@ class Trainer:
                                   self.ws_batches, self.perm)
 
     # ------------------------------------------------------------------ step 2
-    def sample_group(self, first_batch: int, n_batches: int, p_intra: float, epoch: int, flags: int = 0, slot: int = 0):
+    def sample_group(self, first_batch: int, n_batches: int, p_intra: float, epoch: int, flags: Optional[int] = None, slot: int = 0):
         """Samples mini-batches first_batch .. first_batch+n_batches-1 of the current permutation into
         block storage `slot` (on the current stream)."""
         assert 1 <= n_batches <= self.G
         self.blocks = self.block_slots[slot]
+        flags = self.sample_flags if flags is None else flags
         scfg = B.make_sample_cfg(self.cfg.fanouts, p_intra, self.seed, epoch, first_batch, flags)
         start = first_batch * self.B
         n_roots = min(self.n_train, start + n_batches * self.B) - start
@@ -301,7 +307,7 @@ class Trainer:
         top_l = self.L - 1
         for first in range(0, nb, self.G):
             cnt = min(self.G, nb - first)
-            scfg = B.make_sample_cfg(self.cfg.fanouts, p_intra, self.seed, epoch, self.n_batches + first, 0)
+            scfg = B.make_sample_cfg(self.cfg.fanouts, p_intra, self.seed, epoch, self.n_batches + first, self.sample_flags)
             start = first * self.B
             n_roots = min(n, start + cnt * self.B) - start
             layers = self.block_slots[0] if cnt == self.G else [_view_block_set(b, cnt) for b in self.block_slots[0]]
@@ -345,6 +351,21 @@ class Trainer:
                 hist.stopped_early = True
                 break
         return hist
+
+    def input_node_stats(self, policy: int, mix_count: int, p_intra: float, epoch: int, max_groups: int = 4):
+        """Distinct input nodes and gathered rows per batch over the first groups of an epoch (sampled once more
+        with the input frontier de-duplicated; bookkeeping, not part of a training step).  Returns
+        (mean distinct input nodes, distinct / gathered rows)."""
+        nb = self.build_batches(policy, mix_count, epoch)
+        n_src = rows = seen = 0
+        for first in range(0, min(nb, max_groups * self.G), self.G):
+            n = min(self.G, nb - first)
+            self.sample_group(first, n, p_intra, epoch, flags=0)
+            h = self.headers()[0][:n]
+            n_src += int(h[:, 1].sum())
+            rows += int(h[:, 2].sum() + h[:, 0].sum())
+            seen += n
+        return n_src / max(1, seen), n_src / max(1, rows)
 
     def headers(self):
         """Host copy of the current group's block headers: [layer][batch] -> (n_dst, n_src, nnz, status)."""

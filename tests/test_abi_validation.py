@@ -102,6 +102,11 @@ def test_sample_blocks_validation():
     assert sample(layers=with_t0) == B.CR_ERR_UNSUPPORTED               # layer 0 takes no transposed block
     wrong_fanout = [block_set(1, 9, 48, 528, 480, t=False), block_set(1, 5, 8, 48, 40)]
     assert sample(layers=wrong_fanout) == B.CR_ERR_INVALID_ARG
+    # leaving the input-side block in global ids needs somewhere to put them
+    assert sample(flags=B.CR_SAMPLE_INPUT_GLOBAL_IDS) == B.CR_ERR_INVALID_ARG
+    with_ids = [block_set(1, 10, 48, 528, 480, t=False), block_set(1, 5, 8, 48, 40)]
+    with_ids[0].gather_ids = FAKE
+    assert sample(layers=with_ids, flags=B.CR_SAMPLE_INPUT_GLOBAL_IDS) == B.CR_OK
 
 
 def test_block_capacities_are_the_worst_case_bounds():

@@ -11,13 +11,15 @@ from gpu_util import assert_close, bf16_tensor_to_float
 pytestmark = pytest.mark.gpu
 
 
-def test_arxiv_group_of_16(arxiv_workload):
+@pytest.mark.parametrize("relabel_input", [False, True])
+def test_arxiv_group_of_16(arxiv_workload, relabel_input):
+    # relabel_input=False is what the benchmark runs: the input-side block stays in global ids
     import torch
     from paper_2504_18082_amd import binding as B
     from paper_2504_18082_amd.trainer import Trainer
     w = arxiv_workload
     cfg = w.cfg
-    tr = Trainer(w, group_size=16, lr=0.01, seed=0)
+    tr = Trainer(w, group_size=16, lr=0.01, seed=0, relabel_input=relabel_input)
     epoch, p = 5, 0.5
     tr.build_batches(B.CR_ROOTS_RAND, 1, epoch)
     perm = tr.perm.cpu().numpy()
@@ -35,6 +37,21 @@ def test_arxiv_group_of_16(arxiv_workload):
             n_dst, n_src, nnz, status = hdrs[l][g]
             assert status == 0
             blk = tr.blocks[l]
+            if l == 0 and not relabel_input:
+                assert n_src == -1 and n_dst == hdrs[1][g][1]
+                indptr = blk.indptr[g, :n_dst + 1].cpu().numpy()
+                dst = blk.src_ids[g, :n_dst].cpu().numpy()
+                assert np.array_equal(dst, tr.blocks[1].src_ids[g, :n_dst].cpu().numpy())
+                assert indptr[0] == 0 and indptr[-1] == nnz
+                assert np.array_equal(np.diff(indptr), np.minimum(np.diff(w.indptr)[dst], cfg.fanouts[0]))
+                gid = blk.gather_ids[g, :nnz].cpu().numpy()
+                rows = np.repeat(np.arange(n_dst), np.diff(indptr))
+                # every chosen id is a neighbour of its row's node
+                some = np.random.default_rng(g).integers(0, nnz, size=2000)
+                for e in some:
+                    v = dst[rows[e]]
+                    assert gid[e] in w.indices[w.indptr[v]:w.indptr[v + 1]]
+                continue
             src = blk.src_ids[g, :n_src].cpu().numpy()
             indptr = blk.indptr[g, :n_dst + 1].cpu().numpy()
             idx = blk.indices[g, :nnz].cpu().numpy()
@@ -59,6 +76,12 @@ def test_arxiv_group_of_16(arxiv_workload):
         want[g] = blocks
         for l, ob in enumerate(blocks):
             blk = tr.blocks[l]
+            if l == 0 and not relabel_input:
+                assert hdrs[0][g].tolist() == [ob.n_dst, -1, ob.nnz, 0]
+                assert np.array_equal(blk.indptr[g, :ob.n_dst + 1].cpu().numpy(), ob.indptr)
+                assert np.array_equal(blk.gather_ids[g, :ob.nnz].cpu().numpy(), ob.src_ids[ob.indices])
+                assert np.array_equal(blk.src_ids[g, :ob.n_dst].cpu().numpy(), ob.src_ids[:ob.n_dst])
+                continue
             assert hdrs[l][g].tolist() == [ob.n_dst, ob.n_src, ob.nnz, 0]
             assert np.array_equal(blk.src_ids[g, :ob.n_src].cpu().numpy(), ob.src_ids)
             assert np.array_equal(blk.indptr[g, :ob.n_dst + 1].cpu().numpy(), ob.indptr)

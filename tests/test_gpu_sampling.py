@@ -26,10 +26,11 @@ class DeviceGraph:
         self.n_nodes = len(indptr) - 1
 
 
-def run_gpu(torch, dg, roots, fanouts, p, strict, seed, epoch, first_batch, batch_size, hash_dedup=False):
+def run_gpu(torch, dg, roots, fanouts, p, strict, seed, epoch, first_batch, batch_size, hash_dedup=False, input_global=False):
     from paper_2504_18082_amd import binding as B
     n_batches = -(-len(roots) // batch_size)
     flags = (B.CR_SAMPLE_STRICT_INTRA if strict else 0) | (B.CR_SAMPLE_HASH_DEDUP if hash_dedup else 0)
+    flags |= B.CR_SAMPLE_INPUT_GLOBAL_IDS if input_global else 0
     cfg = B.make_sample_cfg(fanouts, p, seed, epoch, first_batch, flags)
     layers = B.alloc_block_sets(cfg, dg.n_nodes, batch_size, n_batches)
     ws = torch.empty(B.cr_sample_blocks_workspace_bytes(cfg, dg.n_nodes, batch_size, n_batches), dtype=torch.uint8, device="cuda")
@@ -39,7 +40,7 @@ def run_gpu(torch, dg, roots, fanouts, p, strict, seed, epoch, first_batch, batc
     return layers, n_batches
 
 
-def compare(layers, n_batches, graph, roots, fanouts, p, strict, seed, epoch, first_batch, batch_size, what):
+def compare(layers, n_batches, graph, roots, fanouts, p, strict, seed, epoch, first_batch, batch_size, what, input_global=False):
     pos = np.full(len(graph[0]) - 1, -1, dtype=np.int32)
     host = [dict(hdr=b.hdr.cpu().numpy(), src=b.src_ids.cpu().numpy(), indptr=b.indptr.cpu().numpy(),
                  indices=b.indices.cpu().numpy(),
@@ -52,6 +53,13 @@ def compare(layers, n_batches, graph, roots, fanouts, p, strict, seed, epoch, fi
         for l, blk in enumerate(want):
             h = host[l]
             tag = f"{what} batch {g} layer {l}"
+            if l == 0 and input_global:
+                # input-side block left in global ids: sizes, row pointers, per-edge global ids, destination nodes
+                assert h["hdr"][g, :4].tolist() == [blk.n_dst, -1, blk.nnz, 0], tag
+                assert np.array_equal(h["src"][g, :blk.n_dst], blk.src_ids[:blk.n_dst]), tag + " src_ids head"
+                assert np.array_equal(h["indptr"][g, :blk.n_dst + 1], blk.indptr), tag + " indptr"
+                assert np.array_equal(h["gather_ids"][g, :blk.nnz], blk.src_ids[blk.indices]), tag + " gather_ids"
+                continue
             assert h["hdr"][g, :4].tolist() == [blk.n_dst, blk.n_src, blk.nnz, 0], tag
             assert np.array_equal(h["src"][g, :blk.n_src], blk.src_ids), tag + " src_ids"
             assert np.array_equal(h["indptr"][g, :blk.n_dst + 1], blk.indptr), tag + " indptr"
@@ -119,3 +127,17 @@ def test_single_layer_and_determinism(torch_mod, tiny_workload):
             assert np.array_equal(x.indices[g, :nnz].cpu().numpy(), y.indices[g, :nnz].cpu().numpy())
             if x.t_indices is not None:
                 assert np.array_equal(x.t_indices[g, :nnz].cpu().numpy(), y.t_indices[g, :nnz].cpu().numpy())
+
+
+@pytest.mark.parametrize("p,hash_dedup", [(0.5, False), (0.9, True)])
+def test_input_block_in_global_ids(torch_mod, tiny_workload, p, hash_dedup):
+    """CR_SAMPLE_INPUT_GLOBAL_IDS: the layers above are unchanged, the input-side block carries row pointers and
+    per-edge global ids only; also with a single layer (the roots' own block is the input-side one)."""
+    w = tiny_workload
+    dg = DeviceGraph(torch_mod, w.graph, w.cfg.n_comm)
+    perm = oracle.build_batches(oracle.RAND, 1, 0, 4, w.train_ids, w.comm, w.cfg.n_comm)
+    roots = perm[:256 * 2 + 31]
+    for fanouts in (w.cfg.fanouts, [7, 4, 3], [12]):
+        print(f"case input-global p={p} fanouts={fanouts}", flush=True)
+        layers, nb = run_gpu(torch_mod, dg, roots, fanouts, p, False, 0, 4, 2, 256, hash_dedup, input_global=True)
+        compare(layers, nb, w.graph, roots, fanouts, p, False, 0, 4, 2, 256, f"input-global {fanouts}", input_global=True)

@@ -12,12 +12,12 @@ pytestmark = pytest.mark.gpu
 RTOL_BF16 = 2e-2
 
 
-def run_case(w, policy, mix, p, n_steps, group, lr=0.05, wd=5e-4, seed=0, epoch=3):
+def run_case(w, policy, mix, p, n_steps, group, lr=0.05, wd=5e-4, seed=0, epoch=3, relabel_input=False):
     import torch
     from paper_2504_18082_amd.trainer import Trainer
     cfg = w.cfg
     weights = synth.init_weights(cfg, seed)
-    tr = Trainer(w, group_size=group, lr=lr, weight_decay=wd, seed=seed, weights=weights)
+    tr = Trainer(w, group_size=group, lr=lr, weight_decay=wd, seed=seed, weights=weights, relabel_input=relabel_input)
     nb = tr.build_batches(policy, mix, epoch)
     perm = tr.perm.cpu().numpy()
     want_perm = oracle.build_batches(policy, mix, seed, epoch, w.train_ids, w.comm, cfg.n_comm)
@@ -40,7 +40,8 @@ def run_case(w, policy, mix, p, n_steps, group, lr=0.05, wd=5e-4, seed=0, epoch=
                                     params, lr, wd, pos)
             hdrs = tr.headers()
             for l in range(tr.L):
-                assert hdrs[l][g].tolist() == [ref["blocks"][l].n_dst, ref["blocks"][l].n_src, ref["blocks"][l].nnz, 0]
+                n_src = -1 if l == 0 and not relabel_input else ref["blocks"][l].n_src     # input frontier not counted by default
+                assert hdrs[l][g].tolist() == [ref["blocks"][l].n_dst, n_src, ref["blocks"][l].nnz, 0]
             assert abs(float(tr.loss.cpu()[0]) - ref["loss"]) <= RTOL_BF16 * abs(ref["loss"])
             assert abs(float(tr.loss.cpu()[0]) - ref["loss"]) <= 1e-3 * abs(ref["loss"])       # in practice far tighter
             n_roots = len(roots)
@@ -185,3 +186,20 @@ def test_fit_protocol_on_tiny(tiny_workload):
     assert min(hist.val_loss) < 0.8 * loss0
     assert max(hist.val_acc) > 3.0 / w.cfg.n_classes and max(hist.val_acc) > acc0
     assert all(np.isfinite(hist.val_loss)) and all(np.isfinite(hist.train_loss))
+
+
+def test_input_frontier_relabelling_changes_nothing(tiny_workload):
+    """The input-side block may stay in global ids (the default) or be de-duplicated and relabelled: every
+    weight after an epoch is bit-identical, and the relabelled variant passes the same oracle comparison."""
+    import torch
+    from paper_2504_18082_amd.trainer import Trainer
+    run_case(tiny_workload, oracle.COMM_RAND, 6, 0.9, n_steps=2, group=2, relabel_input=True)
+    w = tiny_workload
+    out = []
+    for relabel in (False, True):
+        tr = Trainer(w, group_size=4, lr=0.05, seed=0, relabel_input=relabel)
+        tr.run_epoch_serial(oracle.COMM_RAND, 6, 0.9, 1, max_batches=6)
+        torch.cuda.synchronize()
+        out.append([l.W.cpu().numpy().copy() for l in tr.layers] + [tr.loss.cpu().numpy().copy()])
+    for a, b in zip(*out):
+        assert np.array_equal(a, b)
