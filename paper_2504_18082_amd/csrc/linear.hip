@@ -26,6 +26,14 @@ __device__ __forceinline__ bf16x8 lds_read8(const uint16_t *p)
 // Workgroup tile 128 (m) x 64 (n), four waves of 32 x 64; the weights are the first MFMA operand so
 // that a lane ends up with four consecutive n of one row m (vector stores along the row).
 // ------------------------------------------------------------------------------------------------
+// Rows of one split of the weight-gradient product, from the block's actual row count (read on the
+// device) and the number of partial slots the workspace holds: at most `slots` splits, at least 96 rows each.
+__host__ __device__ __forceinline__ int rows_per_split_for(int M, int slots)
+{
+    int rows = ((M + slots - 1) / slots + 95) / 96 * 96;
+    return rows < 96 ? 96 : rows;
+}
+
 struct NtArgs {
     const int32_t *hdr;
     int32_t max_rows;
@@ -114,11 +122,9 @@ __device__ __forceinline__ void nt_step(const NtState &st, const NtFetch<NTILES 
 // layer, so the activations are read once (see launch_nt for why it is not the default).
 // ------------------------------------------------------------------------------------------------
 template <int NTILES, int CH>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) void gemm_nt_kernel(NtArgs a)
+__device__ __forceinline__ void gemm_nt_body(const NtArgs &a, uint16_t (&As)[2][128][LDS_ROW], uint16_t (&Bs)[2][NTILES * 32][LDS_ROW])
 {
     constexpr int BN = NTILES * 32, NB = NTILES / 2;
-    __shared__ __attribute__((aligned(16))) uint16_t As[2][128][LDS_ROW];
-    __shared__ __attribute__((aligned(16))) uint16_t Bs[2][BN][LDS_ROW];
     const int M = min(a.hdr[CR_HDR_N_DST], a.max_rows);
     // the column tiles of one row tile run next to each other on one XCD: the activations come from HBM once
     uint32_t tile;
@@ -195,14 +201,25 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) voi
         }
 }
 
+// Register budget: up to four waves per SIMD.  Four K steps of prefetch at this occupancy measured faster
+// than eight steps at two waves per SIMD.
+template <int NTILES, int CH>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) void gemm_nt_kernel(NtArgs a)
+{
+    __shared__ __attribute__((aligned(16))) uint16_t As[2][128][LDS_ROW];
+    __shared__ __attribute__((aligned(16))) uint16_t Bs[2][NTILES * 32][LDS_ROW];
+    gemm_nt_body<NTILES, CH>(a, As, Bs);
+}
+
 // Wider tiles (NTILES = 4, 8) read the activations fewer times but measured slower on MI355X for the
 // layer widths of this path (K = 256..512, N = 256): these products are bound by memory round trips
-// and occupancy, not by the matrix cores, so the smallest tile with the deepest prefetch wins.
+// and occupancy, not by the matrix cores, so the smallest tile at the highest occupancy wins.
 static void launch_nt(const NtArgs &a, hipStream_t s)
 {
     // xcd_compact needs the grid rounded up to a multiple of eight blocks
     const unsigned ncol = (unsigned)(a.N / 64);
-    hipLaunchKernelGGL((gemm_nt_kernel<2, 8>), dim3(ncol, (unsigned)ceil_div(a.max_rows, 128) + (7 + ncol - 1) / ncol), dim3(256), 0, s, a);
+    const dim3 grid(ncol, (unsigned)ceil_div(a.max_rows, 128) + (7 + ncol - 1) / ncol);
+    hipLaunchKernelGGL((gemm_nt_kernel<2, 4>), grid, dim3(256), 0, s, a);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -221,7 +238,7 @@ struct TnArgs {
     int32_t K0, K2;
     const uint16_t *Z;       // [M][N]
     int32_t N;
-    int32_t rows_per_split;
+    int32_t slots;           // partial slots available
     float *partial;          // [S][K2 + 1][N]: row K2 holds the column sums of Z (bias gradient)
 };
 
@@ -233,10 +250,11 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(TnArgs a)
     // the tiles of one split run next to each other on one XCD (they share the split's rows of A and Z);
     // splits past the last row stay inactive, and the reduction skips them too
     uint32_t work;
-    if (!xcd_compact(blockIdx.y * gridDim.x + blockIdx.x, (uint32_t)((M + a.rows_per_split - 1) / a.rows_per_split) * gridDim.x, work)) return;
+    const int rows_per_split = rows_per_split_for(M, a.slots);
+    if (!xcd_compact(blockIdx.y * gridDim.x + blockIdx.x, (uint32_t)((M + rows_per_split - 1) / rows_per_split) * gridDim.x, work)) return;
     const int split = (int)(work / gridDim.x), tile_id = (int)(work % gridDim.x);
-    const int m_begin = split * a.rows_per_split;
-    const int m_end = min(M, m_begin + a.rows_per_split);
+    const int m_begin = split * rows_per_split;
+    const int m_end = min(M, m_begin + rows_per_split);
     const int n_tiles = (a.N + 127) / 128;
     const int k_tiles_part = (a.K0 + 127) / 128;   // k-tiles per operand part (self | agg): a tile never straddles the two
     const int kt = tile_id / n_tiles;
@@ -370,7 +388,7 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(TnArgs a)
 // master and refreshes both bf16 shadows
 struct SgdArgs {
     const int32_t *hdr;
-    int32_t max_rows, rows_per_split, n_splits;
+    int32_t max_rows, n_splits;
     const float *partial;
     int32_t F_in, F_out, F_pad, N_pad;
     float *W, *bias;
@@ -385,7 +403,8 @@ __global__ __launch_bounds__(256) void sgd_reduce_kernel(SgdArgs a)
 {
     __shared__ float4 red[4][64];
     const int M = min(a.hdr[CR_HDR_N_DST], a.max_rows);
-    const int active = min(a.n_splits, (M + a.rows_per_split - 1) / a.rows_per_split);
+    const int rows_per_split = rows_per_split_for(M, a.n_splits);
+    const int active = min(a.n_splits, (M + rows_per_split - 1) / rows_per_split);
     const int K2 = 2 * a.F_pad;
     const int nq = a.N_pad / 4;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -662,11 +681,11 @@ extern "C" cr_status cr_sage_linear_bwd(const cr_sage_layer *layer, const int32_
     }
     TnArgs t;
     t.hdr = hdr; t.max_rows = max_rows; t.A0 = h_self; t.A1 = agg; t.lda = ld_in; t.K0 = F_pad; t.K2 = 2 * F_pad;
-    t.Z = dz_bf16; t.N = N_pad; t.rows_per_split = rows; t.partial = partial;
+    t.Z = dz_bf16; t.N = N_pad; t.slots = splits; t.partial = partial;
     const unsigned tn_tiles = (unsigned)(2 * ceil_div(F_pad, 128) * ceil_div(N_pad, 128));
     hipLaunchKernelGGL(gemm_tn_kernel, dim3(tn_tiles, (unsigned)splits + (7 + tn_tiles - 1) / tn_tiles), dim3(256), 0, s, t);
     SgdArgs g;
-    g.hdr = hdr; g.max_rows = max_rows; g.rows_per_split = rows; g.n_splits = splits; g.partial = partial;
+    g.hdr = hdr; g.max_rows = max_rows; g.n_splits = splits; g.partial = partial;
     g.F_in = layer->F_in; g.F_out = layer->F_out; g.F_pad = F_pad; g.N_pad = N_pad; g.W = layer->W; g.bias = layer->bias;
     g.W_bf16 = layer->W_bf16; g.Wt_bf16 = layer->Wt_bf16; g.lr = lr; g.wd = weight_decay; g.dW_out = dW_out; g.db_out = db_out;
     hipLaunchKernelGGL(sgd_reduce_kernel, dim3((unsigned)ceil_div((2ll * F_pad + 1) * (N_pad / 4), 64)), dim3(256), 0, s, g);
