@@ -207,15 +207,16 @@ cr_status cr_gather_aggregate_fwd(const cr_block_set *blocks, int32_t g, const v
 
 /* Backward of the aggregation w.r.t. the source rows, atomic-free over the transposed block:
  *   d_src[u] = sum_{v : u in N_s(v)} d_agg[v] / |N_s(v)|   (+ d_self[u] for u < n_dst)
- *   d_agg, d_self : device float [cap_dst][ld_in] (d_self may be NULL)
+ *   d_agg, d_self : device float or bf16 (in_dtype) [cap_dst][ld_in] (d_self may be NULL); ld_in a multiple of 4
+ *                   (float) or 8 (bf16); sums are accumulated in float either way
  *   d_src         : device float [cap_src][F] or NULL, rows 0..n_src-1 fully overwritten
  *   relu_out      : device float or bf16 (relu_dtype) [cap_src][ld_relu] or NULL: forward output of the layer
  *                   below; where it is <= 0 the gradient is zeroed (ReLU backward)
  *   d_src_bf16    : device bf16 [cap_src][ld_bf16] or NULL (same masking, zero padded columns) */
-cr_status cr_gather_aggregate_bwd(const cr_block_set *blocks, int32_t g, const float *d_agg,
-                                  const float *d_self, int64_t ld_in, int32_t F, const void *relu_out,
-                                  int32_t relu_dtype, int64_t ld_relu, float *d_src, uint16_t *d_src_bf16,
-                                  int64_t ld_bf16, void *stream);
+cr_status cr_gather_aggregate_bwd(const cr_block_set *blocks, int32_t g, const void *d_agg,
+                                  const void *d_self, int32_t in_dtype, int64_t ld_in, int32_t F,
+                                  const void *relu_out, int32_t relu_dtype, int64_t ld_relu, float *d_src,
+                                  uint16_t *d_src_bf16, int64_t ld_bf16, void *stream);
 
 /* One GraphSAGE layer's parameters.  F_pad = F_in rounded up to 32, N_pad = F_out rounded up to 64. */
 typedef struct {
@@ -244,22 +245,25 @@ cr_status cr_sage_linear_bwd_workspace_bytes(int32_t F_in, int32_t F_out, int32_
 /* Backward of cr_sage_linear_fwd followed by one SGD step W <- W - lr*(dW + weight_decay*W),
  * b <- b - lr*db on the master weights; both bf16 shadows are refreshed.
  *   dz_bf16 : device bf16 [max_rows][N_pad]: dL/dZ with the ReLU mask already applied, padded columns zero
- *   d_self, d_agg : device float [max_rows][F_pad] or both NULL (layer 0: the features need no gradient);
- *                   they are computed with the weights from before the step
+ *   d_self, d_agg : device float [max_rows][F_pad] or both NULL; computed with the weights from before the step
+ *   d_in_bf16 : device bf16 [max_rows][2*F_pad] or NULL: the same input gradients rounded to bf16 (nearest even),
+ *               d_self in columns 0..F_pad-1, d_agg in F_pad..2*F_pad-1.  With all three NULL no input gradient
+ *               is computed (layer 0: the features need none)
  *   dW_out  : device float [2*F_in][F_out] or NULL, db_out: device float [F_out] or NULL: the gradients
  *   ws      : device workspace of cr_sage_linear_bwd_workspace_bytes() bytes */
 cr_status cr_sage_linear_bwd(const cr_sage_layer *layer, const int32_t *hdr, int32_t max_rows,
                              const uint16_t *h_self, const uint16_t *agg, int64_t ld_in,
                              const uint16_t *dz_bf16, float lr, float weight_decay, float *d_self,
-                             float *d_agg, float *dW_out, float *db_out, void *ws, size_t ws_bytes,
-                             void *stream);
+                             float *d_agg, uint16_t *d_in_bf16, float *dW_out, float *db_out, void *ws,
+                             size_t ws_bytes, void *stream);
 
-/* Only the input gradients of cr_sage_linear_bwd (d_self = dZ W_self^T, d_agg = dZ W_neigh^T, device float
- * [max_rows][F_pad]); no weight is touched.  Lets a caller put the weight-gradient part (cr_sage_linear_bwd with
- * d_self = d_agg = NULL) on another stream, off the critical path of the backward pass; that call must then be
- * ordered after this one, which reads the weights from before the step. */
+/* Only the input gradients of cr_sage_linear_bwd (d_self = dZ W_self^T, d_agg = dZ W_neigh^T; float pair and/or
+ * the bf16 array, as there; at least one of the two forms); no weight is touched.  Lets a caller put the
+ * weight-gradient part (cr_sage_linear_bwd without input gradients) on another stream, off the critical path of
+ * the backward pass; that call must then be ordered after this one, which reads the weights from before the step. */
 cr_status cr_sage_linear_bwd_input(const cr_sage_layer *layer, const int32_t *hdr, int32_t max_rows,
-                                   const uint16_t *dz_bf16, float *d_self, float *d_agg, void *stream);
+                                   const uint16_t *dz_bf16, float *d_self, float *d_agg, uint16_t *d_in_bf16,
+                                   void *stream);
 
 /* Mean softmax cross-entropy over the root rows (labels exist for roots only) and its gradient.
  *   hdr      : device block header of the root block; n = hdr[CR_HDR_N_DST] <= max_rows

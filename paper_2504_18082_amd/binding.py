@@ -97,15 +97,15 @@ def lib():
                                        vp, C.c_size_t, C.POINTER(cr_block_set), vp]
         L.cr_gather_aggregate_fwd.argtypes = [C.POINTER(cr_block_set), i32, vp, i32, i64, i32, i32, vp, vp,
                                               vp, i64, vp]
-        L.cr_gather_aggregate_bwd.argtypes = [C.POINTER(cr_block_set), i32, vp, vp, i64, i32, vp, i32, i64, vp,
+        L.cr_gather_aggregate_bwd.argtypes = [C.POINTER(cr_block_set), i32, vp, vp, i32, i64, i32, vp, i32, i64, vp,
                                               vp, i64, vp]
         L.cr_sage_padded_dims.argtypes = [i32, i32, C.POINTER(i32), C.POINTER(i32)]
         L.cr_sage_refresh_shadows.argtypes = [C.POINTER(cr_sage_layer), vp]
         L.cr_sage_linear_fwd.argtypes = [C.POINTER(cr_sage_layer), vp, i32, vp, vp, i64, C.c_int, vp, vp, vp]
         L.cr_sage_linear_bwd_workspace_bytes.argtypes = [i32, i32, i32, C.POINTER(C.c_size_t)]
         L.cr_sage_linear_bwd.argtypes = [C.POINTER(cr_sage_layer), vp, i32, vp, vp, i64, vp, C.c_float,
-                                         C.c_float, vp, vp, vp, vp, vp, C.c_size_t, vp]
-        L.cr_sage_linear_bwd_input.argtypes = [C.POINTER(cr_sage_layer), vp, i32, vp, vp, vp, vp]
+                                         C.c_float, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+        L.cr_sage_linear_bwd_input.argtypes = [C.POINTER(cr_sage_layer), vp, i32, vp, vp, vp, vp, vp]
         L.cr_softmax_xent.argtypes = [vp, i32, vp, i64, i32, vp, vp, vp, vp, vp, vp, vp]
         L.cr_count_correct.argtypes = [vp, i32, vp, i64, i32, vp, vp, vp, vp]
         for name in EXPORTS:
@@ -259,8 +259,10 @@ def cr_gather_aggregate_fwd(blocks: BlockSet, g, H_src, dtype, ld_src, F, indire
 
 
 def cr_gather_aggregate_bwd(blocks: BlockSet, g, d_agg, d_self, ld_in, F, relu_out=None, ld_relu=0, d_src=None,
-                            d_src_bf16=None, ld_bf16=0, stream=None, relu_dtype=CR_F32):
-    _check(lib().cr_gather_aggregate_bwd(C.byref(blocks.c), g, _ptr(d_agg), _ptr(d_self), ld_in, F,
+                            d_src_bf16=None, ld_bf16=0, stream=None, relu_dtype=CR_F32, in_dtype=CR_F32):
+    """d_agg / d_self: tensors, or raw device addresses (ctypes.c_void_p) for views into a shared buffer."""
+    as_ptr = lambda t: t if isinstance(t, C.c_void_p) else _ptr(t)
+    _check(lib().cr_gather_aggregate_bwd(C.byref(blocks.c), g, as_ptr(d_agg), as_ptr(d_self), in_dtype, ld_in, F,
                                          _ptr(relu_out), relu_dtype, ld_relu, _ptr(d_src), _ptr(d_src_bf16), ld_bf16,
                                          _stream(stream)))
 
@@ -304,15 +306,15 @@ def cr_sage_linear_bwd_workspace_bytes(F_in, F_out, max_rows) -> int:
 
 
 def cr_sage_linear_bwd(layer: SageLayer, hdr_ptr, max_rows, h_self, agg, ld_in, dz_bf16, lr, weight_decay,
-                       d_self, d_agg, ws, dW_out=None, db_out=None, stream=None):
+                       d_self, d_agg, ws, dW_out=None, db_out=None, stream=None, d_in_bf16=None):
     _check(lib().cr_sage_linear_bwd(C.byref(layer.c), hdr_ptr, max_rows, _ptr(h_self), _ptr(agg), ld_in,
-                                    _ptr(dz_bf16), lr, weight_decay, _ptr(d_self), _ptr(d_agg), _ptr(dW_out),
+                                    _ptr(dz_bf16), lr, weight_decay, _ptr(d_self), _ptr(d_agg), _ptr(d_in_bf16), _ptr(dW_out),
                                     _ptr(db_out), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)))
 
 
-def cr_sage_linear_bwd_input(layer: SageLayer, hdr_ptr, max_rows, dz_bf16, d_self, d_agg, stream=None):
+def cr_sage_linear_bwd_input(layer: SageLayer, hdr_ptr, max_rows, dz_bf16, d_self, d_agg, stream=None, d_in_bf16=None):
     _check(lib().cr_sage_linear_bwd_input(C.byref(layer.c), hdr_ptr, max_rows, _ptr(dz_bf16), _ptr(d_self), _ptr(d_agg),
-                                          _stream(stream)))
+                                          _ptr(d_in_bf16), _stream(stream)))
 
 
 def cr_softmax_xent(hdr_ptr, max_rows, logits, ld, n_classes, labels, root_ids_ptr, loss, row_loss,

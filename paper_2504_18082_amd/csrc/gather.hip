@@ -192,15 +192,15 @@ static void launch_fwd(int cap_dst, const int32_t *hdr, const int32_t *indptr, c
 // ------------------------------------------------------------------------------------------------
 // backward: one sub-wave group per source row pulls from the destination rows that used it
 // ------------------------------------------------------------------------------------------------
-template <int LPR, int NCHUNK>
+template <typename T, int LPR, int NCHUNK>
 __global__ __launch_bounds__(256) void gather_mean_bwd_kernel(
     const int32_t *__restrict__ hdr, const int32_t *__restrict__ indptr,
     const int32_t *__restrict__ t_indptr, const int32_t *__restrict__ t_indices,
-    const float *__restrict__ d_agg, const float *__restrict__ d_self, int64_t ld_in, int F,
+    const T *__restrict__ d_agg, const T *__restrict__ d_self, int64_t ld_in, int F,
     const void *__restrict__ relu_out, int relu_is_bf16, int64_t ld_relu, float *__restrict__ d_src,
     uint16_t *__restrict__ d_src_bf16, int64_t ld_bf16)
 {
-    constexpr int VEC = 4;
+    constexpr int VEC = Vec16<T>::N;
     constexpr int U = NCHUNK == 1 ? 8 : (NCHUNK <= 3 ? 4 : 2);
     constexpr int GPB = 256 / LPR;
     const int n_dst = hdr[CR_HDR_N_DST], n_src = hdr[CR_HDR_N_SRC];
@@ -251,17 +251,17 @@ __global__ __launch_bounds__(256) void gather_mean_bwd_kernel(
             if (base > b0) load_ids(base, e0, v, w);
             const int cnt = min(LPR, e0 - base);
             for (int t = 0; t < cnt; t += U) {
-                float4 x[U][NCHUNK];
+                float x[U][NCHUNK][VEC];
                 float ww[U];
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     const int vv = __shfl(v, t + u, LPR);
                     ww[u] = __shfl(w, t + u, LPR);
-                    const float *p = d_agg + (int64_t)vv * ld_in;
+                    const T *p = d_agg + (int64_t)vv * ld_in;
 #pragma unroll
                     for (int c = 0; c < NCHUNK; ++c) {
                         const int col = (c * LPR + gl) * VEC;
-                        if (col < F && t + u < cnt) x[u][c] = *reinterpret_cast<const float4 *>(p + col);
+                        if (col < F && t + u < cnt) Vec16<T>::load(p + col, x[u][c]);
                     }
                 }
 #pragma unroll
@@ -270,8 +270,8 @@ __global__ __launch_bounds__(256) void gather_mean_bwd_kernel(
                     for (int c = 0; c < NCHUNK; ++c) {
                         const int col = (c * LPR + gl) * VEC;
                         if (col < F && t + u < cnt) {
-                            acc[c][0] += x[u][c].x * ww[u]; acc[c][1] += x[u][c].y * ww[u];
-                            acc[c][2] += x[u][c].z * ww[u]; acc[c][3] += x[u][c].w * ww[u];
+#pragma unroll
+                            for (int i = 0; i < VEC; ++i) acc[c][i] += x[u][c][i] * ww[u];
                         }
                     }
             }
@@ -281,27 +281,41 @@ __global__ __launch_bounds__(256) void gather_mean_bwd_kernel(
             const int col = (c * LPR + gl) * VEC;
             if (col < F) {
                 if (d_self && s < n_dst) {
-                    const float4 x = *reinterpret_cast<const float4 *>(d_self + (int64_t)s * ld_in + col);
-                    acc[c][0] += x.x; acc[c][1] += x.y; acc[c][2] += x.z; acc[c][3] += x.w;
+                    float x[VEC];
+                    Vec16<T>::load(d_self + (int64_t)s * ld_in + col, x);
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) acc[c][i] += x[i];
                 }
                 if (relu_out) {
-                    float4 y;
+                    float y[VEC];
                     if (relu_is_bf16) {
-                        const uint2 h = *reinterpret_cast<const uint2 *>(static_cast<const uint16_t *>(relu_out) + (int64_t)s * ld_relu + col);
-                        y = make_float4(__uint_as_float(h.x << 16), __uint_as_float(h.x & 0xFFFF0000u),
-                                        __uint_as_float(h.y << 16), __uint_as_float(h.y & 0xFFFF0000u));
+                        const uint16_t *r = static_cast<const uint16_t *>(relu_out) + (int64_t)s * ld_relu + col;
+                        if constexpr (VEC == 8) {
+                            Vec16<uint16_t>::load(r, y);
+                        } else {
+                            const uint2 h = *reinterpret_cast<const uint2 *>(r);
+                            y[0] = __uint_as_float(h.x << 16); y[1] = __uint_as_float(h.x & 0xFFFF0000u);
+                            y[2] = __uint_as_float(h.y << 16); y[3] = __uint_as_float(h.y & 0xFFFF0000u);
+                        }
                     } else {
-                        y = *reinterpret_cast<const float4 *>(static_cast<const float *>(relu_out) + (int64_t)s * ld_relu + col);
+                        const float *r = static_cast<const float *>(relu_out) + (int64_t)s * ld_relu + col;
+#pragma unroll
+                        for (int i = 0; i < VEC; i += 4) {
+                            float4 q = make_float4(1.f, 1.f, 1.f, 1.f);
+                            if (col + i < F) q = *reinterpret_cast<const float4 *>(r + i);     // stays inside the row's stride
+                            y[i] = q.x; y[i + 1] = q.y; y[i + 2] = q.z; y[i + 3] = q.w;
+                        }
                     }
-                    if (!(y.x > 0.f)) acc[c][0] = 0.f;
-                    if (!(y.y > 0.f)) acc[c][1] = 0.f;
-                    if (!(y.z > 0.f)) acc[c][2] = 0.f;
-                    if (!(y.w > 0.f)) acc[c][3] = 0.f;
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i)
+                        if (!(y[i] > 0.f)) acc[c][i] = 0.f;
                 }
                 if (d_src) {
                     float *o = d_src + (int64_t)s * F + col;
                     if ((F & 3) == 0) {
-                        *reinterpret_cast<float4 *>(o) = make_float4(acc[c][0], acc[c][1], acc[c][2], acc[c][3]);
+#pragma unroll
+                        for (int i = 0; i < VEC; i += 4)
+                            if (col + i < F) *reinterpret_cast<float4 *>(o + i) = make_float4(acc[c][i], acc[c][i + 1], acc[c][i + 2], acc[c][i + 3]);
                     } else {
 #pragma unroll
                         for (int i = 0; i < VEC; ++i)
@@ -317,16 +331,17 @@ __global__ __launch_bounds__(256) void gather_mean_bwd_kernel(
     }
 }
 
-template <int LPR, int NCHUNK>
+template <typename T, int LPR, int NCHUNK>
 static void launch_bwd(int cap_src, const int32_t *hdr, const int32_t *indptr, const int32_t *t_indptr,
-                       const int32_t *t_indices, const float *d_agg, const float *d_self, int64_t ld_in, int F,
+                       const int32_t *t_indices, const void *d_agg, const void *d_self, int64_t ld_in, int F,
                        const void *relu_out, int relu_is_bf16, int64_t ld_relu, float *d_src, uint16_t *d_src_bf16,
                        int64_t ld_bf16, hipStream_t st)
 {
     int64_t grid = ceil_div(cap_src, 256 / LPR);
     if (grid > 1024) grid = 1024;
-    hipLaunchKernelGGL((gather_mean_bwd_kernel<LPR, NCHUNK>), dim3((unsigned)grid), dim3(256), 0, st, hdr, indptr, t_indptr,
-                       t_indices, d_agg, d_self, ld_in, F, relu_out, relu_is_bf16, ld_relu, d_src, d_src_bf16, ld_bf16);
+    hipLaunchKernelGGL((gather_mean_bwd_kernel<T, LPR, NCHUNK>), dim3((unsigned)grid), dim3(256), 0, st, hdr, indptr, t_indptr,
+                       t_indices, static_cast<const T *>(d_agg), static_cast<const T *>(d_self), ld_in, F, relu_out, relu_is_bf16,
+                       ld_relu, d_src, d_src_bf16, ld_bf16);
 }
 
 }  // namespace cr
@@ -396,8 +411,8 @@ extern "C" cr_status cr_gather_aggregate_fwd(const cr_block_set *blocks, int32_t
     return CR_OK;
 }
 
-extern "C" cr_status cr_gather_aggregate_bwd(const cr_block_set *blocks, int32_t g, const float *d_agg,
-                                             const float *d_self, int64_t ld_in, int32_t F,
+extern "C" cr_status cr_gather_aggregate_bwd(const cr_block_set *blocks, int32_t g, const void *d_agg,
+                                             const void *d_self, int32_t in_dtype, int64_t ld_in, int32_t F,
                                              const void *relu_out, int32_t relu_dtype, int64_t ld_relu, float *d_src,
                                              uint16_t *d_src_bf16, int64_t ld_bf16, void *stream)
 {
@@ -405,10 +420,14 @@ extern "C" cr_status cr_gather_aggregate_bwd(const cr_block_set *blocks, int32_t
     if (st != CR_OK) return st;
     CR_REQUIRE(d_agg != nullptr && aligned16(d_agg) && aligned16(d_self), CR_ERR_INVALID_ARG, "d_agg / d_self must be 16-byte aligned device pointers");
     CR_REQUIRE(F >= 1 && F <= 1024, CR_ERR_UNSUPPORTED, "F = %d outside 1..1024", F);
-    CR_REQUIRE(ld_in >= round_up(F, 4) && ld_in % 4 == 0, CR_ERR_INVALID_ARG, "ld_in must be a multiple of 4 covering F");
+    CR_REQUIRE(in_dtype == CR_F32 || in_dtype == CR_BF16, CR_ERR_INVALID_ARG, "in_dtype must be CR_F32 or CR_BF16");
+    const int in_vec = in_dtype == CR_BF16 ? 8 : 4;
+    CR_REQUIRE(ld_in >= round_up(F, in_vec) && ld_in % in_vec == 0, CR_ERR_INVALID_ARG, "ld_in must be a multiple of %d covering F", in_vec);
     if (relu_out) {
         CR_REQUIRE(relu_dtype == CR_F32 || relu_dtype == CR_BF16, CR_ERR_INVALID_ARG, "relu_dtype must be CR_F32 or CR_BF16");
         CR_REQUIRE(aligned16(relu_out) && ld_relu >= round_up(F, 4) && ld_relu % 4 == 0, CR_ERR_INVALID_ARG, "relu_out must be aligned with ld_relu a multiple of 4 covering F");
+        CR_REQUIRE(!(in_dtype == CR_BF16 && relu_dtype == CR_BF16) || ld_relu % 8 == 0, CR_ERR_INVALID_ARG,
+                   "with bf16 gradients a bf16 relu_out needs ld_relu to be a multiple of 8");
     }
     CR_REQUIRE(d_src || d_src_bf16, CR_ERR_INVALID_ARG, "no output requested");
     CR_REQUIRE(aligned16(d_src) && aligned16(d_src_bf16), CR_ERR_INVALID_ARG, "outputs must be 16-byte aligned");
@@ -423,13 +442,20 @@ extern "C" cr_status cr_gather_aggregate_bwd(const cr_block_set *blocks, int32_t
     const int32_t *t_indices = blocks->t_indices + (int64_t)g * blocks->cap_nnz;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int cap = blocks->cap_src;
-#define CR_BWD(LPR, NC) launch_bwd<LPR, NC>(cap, hdr, indptr, t_indptr, t_indices, d_agg, d_self, ld_in, F, relu_out, relu_dtype == CR_BF16 ? 1 : 0, ld_relu, d_src, d_src_bf16, ld_bf16, s)
-    if (F <= 64) CR_BWD(16, 1);
-    else if (F <= 128) CR_BWD(32, 1);
-    else if (F <= 256) CR_BWD(64, 1);
-    else if (F <= 512) CR_BWD(64, 2);
-    else if (F <= 768) CR_BWD(64, 3);
-    else CR_BWD(64, 4);
+#define CR_BWD(T, LPR, NC) launch_bwd<T, LPR, NC>(cap, hdr, indptr, t_indptr, t_indices, d_agg, d_self, ld_in, F, relu_out, relu_dtype == CR_BF16 ? 1 : 0, ld_relu, d_src, d_src_bf16, ld_bf16, s)
+    if (in_dtype == CR_F32) {
+        if (F <= 64) CR_BWD(float, 16, 1);
+        else if (F <= 128) CR_BWD(float, 32, 1);
+        else if (F <= 256) CR_BWD(float, 64, 1);
+        else if (F <= 512) CR_BWD(float, 64, 2);
+        else if (F <= 768) CR_BWD(float, 64, 3);
+        else CR_BWD(float, 64, 4);
+    } else {
+        if (F <= 128) CR_BWD(uint16_t, 16, 1);
+        else if (F <= 256) CR_BWD(uint16_t, 32, 1);
+        else if (F <= 512) CR_BWD(uint16_t, 64, 1);
+        else CR_BWD(uint16_t, 64, 2);
+    }
 #undef CR_BWD
     CR_LAUNCH_CHECK();
     return CR_OK;

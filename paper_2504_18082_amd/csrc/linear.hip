@@ -648,8 +648,8 @@ extern "C" cr_status cr_sage_linear_bwd_workspace_bytes(int32_t F_in, int32_t F_
 extern "C" cr_status cr_sage_linear_bwd(const cr_sage_layer *layer, const int32_t *hdr, int32_t max_rows,
                                         const uint16_t *h_self, const uint16_t *agg, int64_t ld_in,
                                         const uint16_t *dz_bf16, float lr, float weight_decay, float *d_self,
-                                        float *d_agg, float *dW_out, float *db_out, void *ws, size_t ws_bytes,
-                                        void *stream)
+                                        float *d_agg, uint16_t *d_in_bf16, float *dW_out, float *db_out, void *ws,
+                                        size_t ws_bytes, void *stream)
 {
     int F_pad, N_pad;
     cr_status st = check_layer(layer, F_pad, N_pad);
@@ -659,7 +659,7 @@ extern "C" cr_status cr_sage_linear_bwd(const cr_sage_layer *layer, const int32_
                "h_self / agg / dz_bf16 must be 16-byte aligned device pointers");
     CR_REQUIRE(ld_in >= F_pad && ld_in % 8 == 0, CR_ERR_INVALID_ARG, "ld_in = %lld must be a multiple of 8 and >= %d", (long long)ld_in, F_pad);
     CR_REQUIRE((d_self == nullptr) == (d_agg == nullptr), CR_ERR_INVALID_ARG, "d_self and d_agg must be given together");
-    CR_REQUIRE(aligned16(d_self) && aligned16(d_agg), CR_ERR_INVALID_ARG, "d_self / d_agg must be 16-byte aligned");
+    CR_REQUIRE(aligned16(d_self) && aligned16(d_agg) && aligned16(d_in_bf16), CR_ERR_INVALID_ARG, "d_self / d_agg / d_in_bf16 must be 16-byte aligned");
     CR_REQUIRE(lr == lr && weight_decay == weight_decay, CR_ERR_INVALID_ARG, "lr / weight_decay is NaN");
     CR_REQUIRE((int64_t)max_rows * ld_in * 2 < 0x7FFFFFFFll && (int64_t)max_rows * N_pad * 2 < 0x7FFFFFFFll, CR_ERR_UNSUPPORTED,
                "operand of %d rows exceeds the 2 GiB reach of 32-bit buffer offsets", max_rows);
@@ -672,11 +672,11 @@ extern "C" cr_status cr_sage_linear_bwd(const cr_sage_layer *layer, const int32_
     if (dry_run()) return CR_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
 
-    if (d_self) {   // gradient w.r.t. the layer's inputs, with the weights from before the step
+    if (d_self || d_in_bf16) {   // gradient w.r.t. the layer's inputs, with the weights from before the step
         NtArgs a;
         a.hdr = hdr; a.max_rows = max_rows; a.A0 = dz_bf16; a.A1 = nullptr; a.lda = N_pad; a.K0 = N_pad; a.K = N_pad;
         a.B = layer->W_bf16; a.N = 2 * F_pad; a.bias = nullptr; a.relu = 0;
-        a.C0 = d_self; a.C1 = d_agg; a.ldc = F_pad; a.N0 = F_pad; a.Cb = nullptr; a.ldcb = 0;
+        a.C0 = d_self; a.C1 = d_agg; a.ldc = F_pad; a.N0 = F_pad; a.Cb = d_in_bf16; a.ldcb = 2 * F_pad;
         launch_nt(a, s);
     }
     TnArgs t;
@@ -694,19 +694,22 @@ extern "C" cr_status cr_sage_linear_bwd(const cr_sage_layer *layer, const int32_
 }
 
 extern "C" cr_status cr_sage_linear_bwd_input(const cr_sage_layer *layer, const int32_t *hdr, int32_t max_rows,
-                                              const uint16_t *dz_bf16, float *d_self, float *d_agg, void *stream)
+                                              const uint16_t *dz_bf16, float *d_self, float *d_agg, uint16_t *d_in_bf16,
+                                              void *stream)
 {
     int F_pad, N_pad;
     cr_status st = check_layer(layer, F_pad, N_pad);
     if (st != CR_OK) return st;
     CR_REQUIRE(hdr != nullptr && max_rows >= 1, CR_ERR_INVALID_ARG, "hdr must not be NULL and max_rows must be positive");
     CR_REQUIRE(dz_bf16 && aligned16(dz_bf16), CR_ERR_INVALID_ARG, "dz_bf16 must be a 16-byte aligned device pointer");
-    CR_REQUIRE(d_self && d_agg && aligned16(d_self) && aligned16(d_agg), CR_ERR_INVALID_ARG, "d_self / d_agg must be 16-byte aligned device pointers");
+    CR_REQUIRE((d_self == nullptr) == (d_agg == nullptr), CR_ERR_INVALID_ARG, "d_self and d_agg must be given together");
+    CR_REQUIRE(d_self || d_in_bf16, CR_ERR_INVALID_ARG, "no output requested");
+    CR_REQUIRE(aligned16(d_self) && aligned16(d_agg) && aligned16(d_in_bf16), CR_ERR_INVALID_ARG, "d_self / d_agg / d_in_bf16 must be 16-byte aligned");
     if (dry_run()) return CR_OK;
     NtArgs a;
     a.hdr = hdr; a.max_rows = max_rows; a.A0 = dz_bf16; a.A1 = nullptr; a.lda = N_pad; a.K0 = N_pad; a.K = N_pad;
     a.B = layer->W_bf16; a.N = 2 * F_pad; a.bias = nullptr; a.relu = 0;
-    a.C0 = d_self; a.C1 = d_agg; a.ldc = F_pad; a.N0 = F_pad; a.Cb = nullptr; a.ldcb = 0;
+    a.C0 = d_self; a.C1 = d_agg; a.ldc = F_pad; a.N0 = F_pad; a.Cb = d_in_bf16; a.ldcb = 2 * F_pad;
     launch_nt(a, static_cast<hipStream_t>(stream));
     CR_LAUNCH_CHECK();
     return CR_OK;

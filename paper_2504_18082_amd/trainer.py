@@ -78,8 +78,9 @@ class Trainer:
         self.out = [f32(self.blocks[l].cap_dst, self.layers[l].N_pad) if l == self.L - 1 else None for l in range(self.L)]
         self.out_b = [b16(self.blocks[l].cap_dst, self.layers[l].N_pad) if l < self.L - 1 else None for l in range(self.L)]
         self.dz = [b16(self.blocks[l].cap_dst, self.layers[l].N_pad) for l in range(self.L)]
-        self.d_self = [f32(self.blocks[l].cap_dst, self.layers[l].F_pad) if l >= 1 else None for l in range(self.L)]
-        self.d_agg = [f32(self.blocks[l].cap_dst, self.layers[l].F_pad) if l >= 1 else None for l in range(self.L)]
+        # input gradients [d_self | d_agg] of the layers above the first, kept in bf16: the scatter back over the
+        # block reads them once per edge, so their width is what that kernel's traffic is made of
+        self.d_in = [b16(self.blocks[l].cap_dst, 2 * self.layers[l].F_pad) if l >= 1 else None for l in range(self.L)]
         self.ws_bwd = [torch.empty(B.cr_sage_linear_bwd_workspace_bytes(self.layers[l].F_in, self.layers[l].F_out, self.blocks[l].cap_dst),
                                    dtype=torch.uint8, device=device) for l in range(self.L)]
         self.loss = torch.zeros(1, dtype=torch.float32, device=device)
@@ -173,12 +174,12 @@ class Trainer:
             grads = (None if dW_out is None else dW_out[l], None if db_out is None else db_out[l])
             if side is None:
                 B.cr_sage_linear_bwd(lay, blk.hdr_ptr(g), blk.cap_dst, h_self, self.agg[l], ld_in, self.dz[l], self.lr, self.wd,
-                                     self.d_self[l], self.d_agg[l], self.ws_bwd[l], *grads)
+                                     None, None, self.ws_bwd[l], *grads, d_in_bf16=self.d_in[l])
             else:
                 # the input gradients stay on the critical path; the weight gradient and the SGD step of this
                 # layer go to the side stream, after the input-gradient product has read the old weights
                 if l >= 1:
-                    B.cr_sage_linear_bwd_input(lay, blk.hdr_ptr(g), blk.cap_dst, self.dz[l], self.d_self[l], self.d_agg[l])
+                    B.cr_sage_linear_bwd_input(lay, blk.hdr_ptr(g), blk.cap_dst, self.dz[l], None, None, d_in_bf16=self.d_in[l])
                 ready = self.torch.cuda.Event()
                 ready.record()
                 with self.torch.cuda.stream(side):
@@ -189,8 +190,9 @@ class Trainer:
                     self.ev_weights[l].record(side)
             if l >= 1:
                 prev = layers[l - 1]
-                B.cr_gather_aggregate_bwd(blk, g, self.d_agg[l], self.d_self[l], lay.F_pad, lay.F_in, self.out_b[l - 1],
-                                          prev.N_pad, None, self.dz[l - 1], prev.N_pad, relu_dtype=B.CR_BF16)
+                d_agg = C.c_void_p(self.d_in[l].data_ptr() + 2 * lay.F_pad)      # second half of every row
+                B.cr_gather_aggregate_bwd(blk, g, d_agg, self.d_in[l], 2 * lay.F_pad, lay.F_in, self.out_b[l - 1],
+                                          prev.N_pad, None, self.dz[l - 1], prev.N_pad, relu_dtype=B.CR_BF16, in_dtype=B.CR_BF16)
 
     def wait_weights(self, layers=None):
         """Makes the current stream wait for the side-stream weight updates of the given layers (all by default)."""

@@ -39,6 +39,7 @@ def oracle_train_step(graph, table, n_feat, labels, roots, fanouts, p, seed, epo
         grads[l] = (dW, db)
         new_params[l] = oracle.sgd_step(W, dW, b, db, lr, wd)
         if l > 0:
+            d_agg, d_self = oracle.round_bf16(d_agg), oracle.round_bf16(d_self)     # the GPU path stores them in bf16
             d_src = oracle.gather_mean_bwd(blocks[l], d_agg, d_self)
             dz = d_src * (oracle.round_bf16(outs[l - 1]) > 0)
     return dict(blocks=blocks, loss=loss, logits=outs[L - 1], outs=outs, grads=grads, params=new_params)

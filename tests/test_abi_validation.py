@@ -138,11 +138,17 @@ def test_gather_validation():
     assert good_ld == B.CR_OK
     # backward needs the transposed block
     no_t = block_set(t=False)
-    st = lib.cr_gather_aggregate_bwd(C.byref(no_t), 0, vp(), None, 64, 64, None, 0, 0, vp(), None, 0, None)
+    st = lib.cr_gather_aggregate_bwd(C.byref(no_t), 0, vp(), None, B.CR_F32, 64, 64, None, 0, 0, vp(), None, 0, None)
     assert st == B.CR_ERR_INVALID_ARG
-    st = lib.cr_gather_aggregate_bwd(C.byref(bs), 0, vp(), None, 64, 64, vp(), 7, 64, vp(), None, 0, None)
+    st = lib.cr_gather_aggregate_bwd(C.byref(bs), 0, vp(), None, B.CR_F32, 64, 64, vp(), 7, 64, vp(), None, 0, None)
     assert st == B.CR_ERR_INVALID_ARG                                    # unknown relu_dtype
-    st = lib.cr_gather_aggregate_bwd(C.byref(bs), 0, vp(), None, 64, 64, vp(), B.CR_BF16, 64, vp(), None, 0, None)
+    st = lib.cr_gather_aggregate_bwd(C.byref(bs), 0, vp(), None, 9, 64, 64, None, 0, 0, vp(), None, 0, None)
+    assert st == B.CR_ERR_INVALID_ARG                                    # unknown in_dtype
+    st = lib.cr_gather_aggregate_bwd(C.byref(bs), 0, vp(), None, B.CR_BF16, 68, 64, None, 0, 0, vp(), None, 0, None)
+    assert st == B.CR_ERR_INVALID_ARG                                    # bf16 rows need a stride that is a multiple of 8
+    st = lib.cr_gather_aggregate_bwd(C.byref(bs), 0, vp(), None, B.CR_BF16, 128, 64, vp(), B.CR_BF16, 64, vp(), None, 0, None)
+    assert st == B.CR_OK
+    st = lib.cr_gather_aggregate_bwd(C.byref(bs), 0, vp(), None, B.CR_F32, 64, 64, vp(), B.CR_BF16, 64, vp(), None, 0, None)
     assert st == B.CR_OK
 
 
@@ -163,9 +169,15 @@ def test_linear_and_loss_validation():
     assert fwd(layer=B.cr_sage_layer(100, 47, None, FAKE, FAKE, FAKE)) == B.CR_ERR_INVALID_ARG
     need = B.cr_sage_linear_bwd_workspace_bytes(100, 47, 1000)
     bwd = lambda **kw: lib.cr_sage_linear_bwd(C.byref(layer), vp(), 1000, vp(), vp(), 128, vp(), C.c_float(kw.get("lr", 0.01)), C.c_float(0.0),
-                                              vp(kw.get("ds", FAKE)), vp(kw.get("da", FAKE)), None, None, vp(), kw.get("ws", need), None)
+                                              vp(kw.get("ds", FAKE)), vp(kw.get("da", FAKE)), vp(kw.get("db", None)), None, None, vp(),
+                                              kw.get("ws", need), None)
     assert bwd() == B.CR_OK
     assert bwd(ds=None, da=None) == B.CR_OK                              # layer 0: no input gradient
+    assert bwd(ds=None, da=None, db=FAKE) == B.CR_OK                     # input gradient in bf16 only
+    assert bwd(db=FAKE + 8) == B.CR_ERR_INVALID_ARG                      # misaligned
+    bwd_in = lambda ds, da, db: lib.cr_sage_linear_bwd_input(C.byref(layer), vp(), 1000, vp(), vp(ds), vp(da), vp(db), None)
+    assert bwd_in(FAKE, FAKE, None) == B.CR_OK and bwd_in(None, None, FAKE) == B.CR_OK
+    assert bwd_in(None, None, None) == B.CR_ERR_INVALID_ARG and bwd_in(FAKE, None, FAKE) == B.CR_ERR_INVALID_ARG
     assert bwd(ds=None) == B.CR_ERR_INVALID_ARG                          # only one of the two
     assert bwd(ws=need - 1) == B.CR_ERR_CAPACITY
     assert bwd(lr=float("nan")) == B.CR_ERR_INVALID_ARG

@@ -1,4 +1,6 @@
 """GPU parity: cr_gather_aggregate_fwd / _bwd against the oracle on oracle-sampled blocks."""
+import ctypes as C
+
 import numpy as np
 import pytest
 
@@ -142,6 +144,20 @@ def test_gather_bwd(torch_mod, tiny_workload, F):
     got_b = bf16_tensor_to_float(d_src_b)
     assert_close(got_b[:, :F], want_masked, RTOL_BF16, "d_src bf16")
     assert np.all(got_b[:, F:] == 0)
+    # bf16 input gradients, [d_self | d_agg] side by side in one array: the oracle gets the same rounded values
+    both = np.concatenate([d_self, d_agg], axis=1)
+    both_b = torch.from_numpy(synth.float_to_bf16_bits(both).view(np.int16)).cuda()
+    rounded = synth.bf16_bits_to_float(synth.float_to_bf16_bits(both))
+    want_b = oracle.gather_mean_bwd(blk, rounded[:, ld_in:ld_in + F], rounded[:, :F]) * (relu_out[:, :F] > 0)
+    d_src3 = torch.full((bs.cap_src, F), np.nan, dtype=torch.float32, device="cuda")
+    d_src3_b = torch.full((bs.cap_src, ld_in), 0x7FC0, dtype=torch.int16, device="cuda")
+    B.cr_gather_aggregate_bwd(bs, 0, C.c_void_p(both_b.data_ptr() + 2 * ld_in), both_b, 2 * ld_in, F, up(relu_out), ld_in, d_src3,
+                              d_src3_b, ld_in, in_dtype=B.CR_BF16)
+    torch.cuda.synchronize()
+    assert_close(d_src3.cpu().numpy(), want_b, RTOL, "d_src from bf16 inputs")
+    got_b3 = bf16_tensor_to_float(d_src3_b)
+    assert_close(got_b3[:, :F], want_b, RTOL_BF16, "d_src bf16 from bf16 inputs")
+    assert np.all(got_b3[:, F:] == 0)
     # without the self path
     B.cr_gather_aggregate_bwd(bs, 0, up(d_agg), None, ld_in, F, d_src=d_src)
     torch.cuda.synchronize()

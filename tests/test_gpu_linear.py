@@ -103,7 +103,9 @@ def test_linear_bwd_and_sgd(torch_mod, M, F_in, F_out, need_dx):
     dW_out = torch.zeros((2 * F_in, F_out), dtype=torch.float32, device="cuda")
     db_out = torch.zeros(F_out, dtype=torch.float32, device="cuda")
     hdr = hdr_for(torch, M)
-    B.cr_sage_linear_bwd(layer, C.c_void_p(hdr.data_ptr()), cap, d_hs, d_ag, ld_in, d_dz, lr, wd, g_self, g_agg, ws, dW_out, db_out)
+    g_in_b = torch.full((cap, 2 * layer.F_pad), 0x7FC0, dtype=torch.int16, device="cuda") if need_dx else None
+    B.cr_sage_linear_bwd(layer, C.c_void_p(hdr.data_ptr()), cap, d_hs, d_ag, ld_in, d_dz, lr, wd, g_self, g_agg, ws, dW_out, db_out,
+                         d_in_bf16=g_in_b)
     torch.cuda.synchronize()
     assert_close(dW_out.cpu().numpy(), dW, RTOL_BF16, "dW")
     assert_close(dW_out.cpu().numpy(), dW, 1e-4, "dW (accumulation only)")
@@ -126,6 +128,9 @@ def test_linear_bwd_and_sgd(torch_mod, M, F_in, F_out, need_dx):
         assert_close(g_agg.cpu().numpy()[:M, :F_in], d_agg, RTOL_BF16, "d_agg")
         assert_close(g_self.cpu().numpy()[:M, :F_in], d_self, 1e-4, "d_self (accumulation only)")
         assert np.all(g_self.cpu().numpy()[:M, F_in:] == 0)
+        # the bf16 copy is the float result rounded to nearest even, [d_self | d_agg] side by side
+        both = np.concatenate([g_self.cpu().numpy()[:M], g_agg.cpu().numpy()[:M]], axis=1)
+        np.testing.assert_array_equal(g_in_b.cpu().numpy()[:M].view(np.uint16), synth.float_to_bf16_bits(both))
 
 
 @pytest.mark.parametrize("n,Cn", [(256, 10), (1024, 40), (1000, 172), (1, 7)])
