@@ -36,7 +36,7 @@ def gather0_bytes(hdr0, n_feat, elem_bytes, f_pad):
     return reads + writes, (nnz + n_dst) * n_feat * elem_bytes
 
 
-def run_setting(tr, policy, mix, p, steps, warmup, epoch0, serial="none"):
+def run_setting(tr, policy, mix, p, steps, warmup, epoch0, serial="none", input_stats=True):
     """Times `steps` steps (after `warmup` untimed ones) of one knob setting."""
     import torch
     from paper_2504_18082_amd import binding as B
@@ -74,9 +74,11 @@ def run_setting(tr, policy, mix, p, steps, warmup, epoch0, serial="none"):
     tr.gather0_events = []
     t0 = time.perf_counter()
     run(steps, epoch0 + 1000, True)
+    t_enq = time.perf_counter()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     tr.time_gather0 = False
+    stats["enqueue_s"] = t_enq - t0
     gather_ms = sum(a.elapsed_time(b) for a, b in tr.gather0_events)
     elem = 2 if tr.feat_dtype == B.CR_BF16 else 4
     for n, h in hdrs:
@@ -88,8 +90,8 @@ def run_setting(tr, policy, mix, p, steps, warmup, epoch0, serial="none"):
             stats["rows0"] += int(h[g][2]) + int(h[g][0])
             stats["launches"] += 1
     # distinct input nodes per batch: counted outside the timed region (a training step does not need them)
-    mean_input_nodes, unique_row_ratio = tr.input_node_stats(policy, mix, p, epoch0 + 1000)
-    return dict(ms_per_step=dt * 1e3 / steps, total_s=dt, gather_ms_per_launch=gather_ms / max(1, stats["launches"]),
+    mean_input_nodes, unique_row_ratio = tr.input_node_stats(policy, mix, p, epoch0 + 1000) if input_stats else (float("nan"), float("nan"))
+    return dict(ms_per_step=dt * 1e3 / steps, total_s=dt, host_enqueue_ms_per_step=stats["enqueue_s"] * 1e3 / steps, gather_ms_per_launch=gather_ms / max(1, stats["launches"]),
                 gather_bytes_per_launch=stats["gather_bytes"] / max(1, stats["launches"]),
                 feat_bytes_per_step=stats["feat_bytes"] / max(1, stats["launches"]),
                 unique_row_ratio=unique_row_ratio, mean_input_nodes=mean_input_nodes)
@@ -130,6 +132,9 @@ def main():
     ap.add_argument("--group", type=int, default=16)
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-sweep", action="store_true")
+    ap.add_argument("--no-input-stats", action="store_true",
+                    help="skip the untimed extra sampling pass that counts the distinct input nodes per batch (keeps a "
+                         "kernel trace down to the timed path)")
     ap.add_argument("--overlap", default="none", choices=["none", "sample", "sample+weights", "all"],
                     help="side streams: 'sample' = sampling of the next group overlaps training; '+weights' = weight "
                          "gradients and SGD leave the backward pass's critical path; 'all' = also the layer-0 gather "
@@ -172,12 +177,12 @@ def main():
         del src, dst
 
     # headline: the fully random setting (RAND-ROOTS, p = 0.5), the paper's baseline
-    main_res = run_setting(tr, B.CR_ROOTS_RAND, 1, 0.5, steps, args.warmup, 0, args.overlap)
+    main_res = run_setting(tr, B.CR_ROOTS_RAND, 1, 0.5, steps, args.warmup, 0, args.overlap, not args.no_input_stats)
     sweep = []
     if not args.no_sweep:
         for name, policy, mix, p in (("mid: COMM-RAND-MIX-12.5% p=1.0", B.CR_ROOTS_COMM_RAND, mix_mid, 1.0),
                                      ("fully community: NORAND-ROOTS p=1.0", B.CR_ROOTS_NORAND, 1, 1.0)):
-            r = run_setting(tr, policy, mix, p, steps, min(args.warmup, 4), 50, args.overlap)
+            r = run_setting(tr, policy, mix, p, steps, min(args.warmup, 4), 50, args.overlap, not args.no_input_stats)
             sweep.append(dict(setting=name, ms_per_step=round(r["ms_per_step"], 4),
                               epoch_ms=round(r["ms_per_step"] * tr.n_batches, 3),
                               speedup_vs_random=round(main_res["ms_per_step"] / r["ms_per_step"], 3),
@@ -214,8 +219,9 @@ def main():
                    "schedule": "one stream" if args.overlap == "none" else "side streams: " + args.overlap,
                    "value_definition": "layer-0 gathered feature bytes per second of whole-step time"},
         "epoch_ms": round(main_res["ms_per_step"] * tr.n_batches, 3),
-        "mean_input_nodes": round(main_res["mean_input_nodes"], 1),
-        "unique_row_ratio": round(main_res["unique_row_ratio"], 4),
+        "host_enqueue_ms_per_step": round(main_res["host_enqueue_ms_per_step"], 4),
+        "mean_input_nodes": None if main_res["mean_input_nodes"] != main_res["mean_input_nodes"] else round(main_res["mean_input_nodes"], 1),
+        "unique_row_ratio": None if main_res["unique_row_ratio"] != main_res["unique_row_ratio"] else round(main_res["unique_row_ratio"], 4),
         "roofline": {"bound": "hbm", "kernel": "gather_mean_fwd_kernel (layer 0)", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "traffic": traffic, "bytes_per_launch": round(main_res["gather_bytes_per_launch"]),

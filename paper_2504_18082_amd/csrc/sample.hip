@@ -45,6 +45,7 @@ struct SelectArgs {
     int64_t sel_stride;
     int32_t *cnt;             // [G][cap_dst]
     int64_t cnt_stride;
+    uint32_t cand_target;     // long rows, uniform sampling: expected number of slots below the pre-filter threshold
 };
 
 __device__ __forceinline__ int group_n_dst(const int32_t *prev_hdr, int g, int64_t n_roots_total, int batch_size)
@@ -195,6 +196,74 @@ __device__ __forceinline__ void select_big_row(const SelectArgs &a, int g, int r
     if (lane == 0) a.cnt[(int64_t)g * a.cnt_stride + row] = __popcll(vmask);
 }
 
+// Uniform sampling of a row with more than 64 neighbours, the common way: slots whose random word falls
+// below a threshold chosen so that about cand_target of them do (far more than the fanout, far fewer than
+// the wave's candidate buffer holds) are compacted in slot order into LDS, ranked among themselves by
+// counting, and the fanout smallest (word, slot) pairs are emitted in slot order.  Exact whenever it
+// applies: every slot left out has a word >= the threshold > every candidate's word.  Returns false when
+// the candidates are fewer than the fanout or more than the buffer holds (then the caller takes the
+// general path, which needs no threshold).
+constexpr int CAND_CAP = 128;
+
+__device__ __forceinline__ bool select_big_row_uniform(const SelectArgs &a, int g, int row, int32_t v, int64_t base, int deg,
+                                                       int lane, uint2 *cand)
+{
+    const int k = a.fanout;
+    const uint32_t batch = a.first_batch + (uint32_t)g;
+    const uint64_t lt_mask = (1ull << lane) - 1ull;
+    uint64_t thr = ((uint64_t)a.cand_target << 32) / (uint64_t)deg;     // > 2^32 - 1 keeps every slot
+    int n = 0;
+    for (int j0 = 0; j0 < deg; j0 += 4 * WAVE) {
+        const int jb = j0 + 4 * lane;
+        const u32x4 w = philox4x32_10((uint32_t)jb >> 2, (uint32_t)v, batch, a.ctr3, a.seed_lo, a.seed_hi);
+        const uint32_t wr[4] = {w.x, w.y, w.z, w.w};
+        bool c[4];
+        uint64_t b[4];
+        int before = n, total = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            c[i] = jb + i < deg && (uint64_t)wr[i] < thr;
+            b[i] = __ballot(c[i]);
+            before += __popcll(b[i] & lt_mask);
+            total += __popcll(b[i]);
+        }
+        if (n + total > CAND_CAP) return false;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (c[i]) cand[before] = make_uint2(wr[i], (uint32_t)(jb + i));
+            before += c[i] ? 1 : 0;
+        }
+        n += total;
+    }
+    if (n < k) return false;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+
+    // candidate t sits at index t in slot order; a lane owns candidates lane and lane + 64
+    const uint2 c0 = cand[min(lane, n - 1)], c1 = cand[min(lane + WAVE, n - 1)];
+    const bool have0 = lane < n, have1 = lane + WAVE < n;
+    int r0 = 0, r1 = 0;
+    if (n <= WAVE) {
+        for (int t = 0; t < n; ++t) {
+            const uint32_t wt = cand[t].x;
+            r0 += (wt < c0.x || (wt == c0.x && t < lane)) ? 1 : 0;
+        }
+    } else {
+        for (int t = 0; t < n; ++t) {
+            const uint32_t wt = cand[t].x;
+            r0 += (wt < c0.x || (wt == c0.x && t < lane)) ? 1 : 0;
+            r1 += (wt < c1.x || (wt == c1.x && t < lane + WAVE)) ? 1 : 0;
+        }
+    }
+    const bool s0 = have0 && r0 < k, s1 = have1 && r1 < k;
+    const uint64_t m0 = __ballot(s0), m1 = __ballot(s1);
+    int32_t *sel_row = a.sel + (int64_t)g * a.sel_stride + (int64_t)row * k;
+    if (s0) sel_row[__popcll(m0 & lt_mask)] = a.g_indices[base + c0.y];
+    if (s1) sel_row[__popcll(m0) + __popcll(m1 & lt_mask)] = a.g_indices[base + c1.y];
+    if (lane == 0) a.cnt[(int64_t)g * a.cnt_stride + row] = k;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");      // the buffer is reused by this wave's next long row
+    return true;
+}
+
 // A wave takes SEL_ROWS consecutive destination rows.  Rows with at most 64 neighbours are packed side
 // by side into the wave's lanes (lane = one neighbour slot of one row; as many consecutive rows per pass
 // as fit), so that the random words, the keys and the ranking of several short rows cost one pass of
@@ -206,6 +275,7 @@ constexpr int SEL_ROWS = 4;
 template <bool WIDE>
 __global__ __launch_bounds__(256) void select_kernel(SelectArgs a)
 {
+    __shared__ uint2 cand[4][CAND_CAP];
     const int g = blockIdx.y;
     const int n_dst = group_n_dst(a.prev_hdr, g, a.n_roots_total, a.batch_size);
     const int row0 = (int)(blockIdx.x * 4 + threadIdx.x / WAVE) * SEL_ROWS;
@@ -291,7 +361,10 @@ __global__ __launch_bounds__(256) void select_kernel(SelectArgs a)
 
 #pragma unroll
     for (int i = 0; i < SEL_ROWS; ++i)
-        if (deg[i] > WAVE) select_big_row<WIDE>(a, g, row0 + i, v[i], base[i], deg[i], cv[i], lane);
+        if (deg[i] > WAVE) {
+            if (!WIDE && select_big_row_uniform(a, g, row0 + i, v[i], base[i], deg[i], lane, cand[threadIdx.x / WAVE])) continue;
+            select_big_row<WIDE>(a, g, row0 + i, v[i], base[i], deg[i], cv[i], lane);
+        }
 }
 
 struct ScanArgs {
@@ -725,6 +798,11 @@ extern "C" cr_status cr_sample_blocks(const cr_graph *graph, const cr_sample_cfg
         sa.ctr3 = (cfg->epoch << 8) | (DOMAIN_NEIGHBOUR << 4) | (uint32_t)l;
         sa.first_batch = cfg->first_batch;
         sa.sel = p.sel; sa.sel_stride = p.max_nnz; sa.cnt = p.cnt; sa.cnt_stride = p.max_dst;
+        {   // fanout + four standard deviations and a little more: short about once in a few thousand long rows (those
+            // take the general path), never near the buffer's end
+            int target = f + (int)(4.0 * sqrt((double)f)) + 4;
+            sa.cand_target = (uint32_t)(target > 96 ? 96 : target);
+        }
         if (q_in == q_out) hipLaunchKernelGGL(select_kernel<false>, dim3((unsigned)ceil_div(cap_dst, 4 * SEL_ROWS), n_batches), blk, 0, s, sa);
         else hipLaunchKernelGGL(select_kernel<true>, dim3((unsigned)ceil_div(cap_dst, 4 * SEL_ROWS), n_batches), blk, 0, s, sa);
 
