@@ -106,7 +106,16 @@ typedef struct {
     const int32_t *indices; /* device int32[n_entries]; row v = neighbours of v (symmetrised graph) */
     const int32_t *comm;    /* device int32[n_nodes] */
     int32_t n_comm;
+    int32_t reserved;
+    const uint32_t *edge_intra; /* device uint32[ceil(n_entries/32)] or NULL: bit (e & 31) of word e >> 5 is set iff
+                                   entry e joins two nodes of one community (filled by cr_graph_edge_classes).  Static
+                                   per graph; lets biased sampling read a neighbour's class without touching
+                                   indices[] and comm[].  Results are identical with and without it. */
 } cr_graph;
+
+/* Fills edge_intra (device uint32[ceil(n_entries/32)], every word fully written) from indptr / indices / comm;
+ * graph->edge_intra itself is ignored here. */
+cr_status cr_graph_edge_classes(const cr_graph *graph, uint32_t *edge_intra, void *stream);
 
 /* The sampled blocks of ONE GNN layer for a group of n_batches mini-batches that are sampled
  * together.  Every array is laid out [n_batches][capacity]; batch g of the group owns slice g.

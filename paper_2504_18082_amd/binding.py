@@ -26,7 +26,7 @@ CR_SAMPLE_INPUT_GLOBAL_IDS = 4
 EXPORTS = [
     "cr_last_error", "cr_version", "cr_set_dry_run", "cr_mix_count_from_percent",
     "cr_build_batches_workspace_bytes", "cr_build_batches",
-    "cr_block_capacities", "cr_sample_blocks_workspace_bytes", "cr_sample_blocks",
+    "cr_graph_edge_classes", "cr_block_capacities", "cr_sample_blocks_workspace_bytes", "cr_sample_blocks",
     "cr_gather_aggregate_fwd", "cr_gather_aggregate_bwd",
     "cr_sage_padded_dims", "cr_sage_refresh_shadows", "cr_sage_linear_fwd",
     "cr_sage_linear_bwd_workspace_bytes", "cr_sage_linear_bwd", "cr_sage_linear_bwd_input", "cr_softmax_xent",
@@ -47,7 +47,8 @@ class cr_batch_cfg(C.Structure):
 
 class cr_graph(C.Structure):
     _fields_ = [("n_nodes", C.c_int64), ("n_entries", C.c_int64), ("indptr", C.c_void_p),
-                ("indices", C.c_void_p), ("comm", C.c_void_p), ("n_comm", C.c_int32)]
+                ("indices", C.c_void_p), ("comm", C.c_void_p), ("n_comm", C.c_int32), ("reserved", C.c_int32),
+                ("edge_intra", C.c_void_p)]
 
 
 class cr_block_set(C.Structure):
@@ -93,6 +94,7 @@ def lib():
                                           C.POINTER(i32), C.POINTER(i32)]
         L.cr_sample_blocks_workspace_bytes.argtypes = [C.POINTER(cr_sample_cfg), i64, i32, i32,
                                                        C.POINTER(C.c_size_t)]
+        L.cr_graph_edge_classes.argtypes = [C.POINTER(cr_graph), vp, vp]
         L.cr_sample_blocks.argtypes = [C.POINTER(cr_graph), C.POINTER(cr_sample_cfg), vp, i64, i32, i32,
                                        vp, C.c_size_t, C.POINTER(cr_block_set), vp]
         L.cr_gather_aggregate_fwd.argtypes = [C.POINTER(cr_block_set), i32, vp, i32, i64, i32, i32, vp, vp,
@@ -234,8 +236,18 @@ def cr_build_batches(policy, mix_count, batch_size, seed, epoch, train_ids, comm
 
 
 # --------------------------------------------------------------------------- step 2
-def make_graph(indptr, indices, comm, n_comm) -> cr_graph:
-    return cr_graph(indptr.numel() - 1, indices.numel(), _ptr(indptr), _ptr(indices), _ptr(comm), n_comm)
+def make_graph(indptr, indices, comm, n_comm, edge_intra=None) -> cr_graph:
+    return cr_graph(indptr.numel() - 1, indices.numel(), _ptr(indptr), _ptr(indices), _ptr(comm), n_comm, 0, _ptr(edge_intra))
+
+
+def cr_graph_edge_classes(graph: cr_graph, stream=None):
+    """Allocates and fills the per-entry class bits of a graph; returns the tensor (int32 words); the caller stores
+    its address in graph.edge_intra (and keeps the tensor alive)."""
+    import torch
+    words = max(1, -(-graph.n_entries // 32))
+    bits = torch.zeros(words, dtype=torch.int32, device="cuda")
+    _check(lib().cr_graph_edge_classes(C.byref(graph), _ptr(bits), _stream(stream)))
+    return bits
 
 
 def cr_sample_blocks_workspace_bytes(cfg, n_nodes, batch_size, n_batches) -> int:

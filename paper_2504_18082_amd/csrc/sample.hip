@@ -32,6 +32,8 @@ struct SelectArgs {
     const int64_t *g_indptr;
     const int32_t *g_indices;
     const int32_t *comm;
+    const uint32_t *edge_intra;   // one bit per adjacency entry (same community), or NULL
+    int64_t n_entries;
     const int32_t *dst_ids;   // roots, or the frontier of the layer above
     int64_t dst_stride;
     const int32_t *prev_hdr;  // header array of the layer above, NULL for the root layer
@@ -65,6 +67,8 @@ __device__ __forceinline__ uint64_t push64(uint64_t v, int dst_lane)
 {
     return ((uint64_t)push32((uint32_t)(v >> 32), dst_lane) << 32) | push32((uint32_t)v, dst_lane);
 }
+
+__device__ __forceinline__ bool edge_is_intra(const SelectArgs &a, int64_t e) { return (a.edge_intra[e >> 5] >> (e & 31)) & 1u; }
 
 __device__ __forceinline__ uint32_t pull32(uint32_t v, int src_lane) { return (uint32_t)__builtin_amdgcn_ds_bpermute(src_lane << 2, (int)v); }
 
@@ -116,9 +120,14 @@ __device__ __forceinline__ void select_big_row(const SelectArgs &a, int g, int r
     // first chunk: rank the first 64 slots by counting, then move rank r to lane r
     uint64_t ck = KEY_MAX;
     uint32_t cs = 0xFFFFFFFFu;
+    // class of slot j (clamped to the row): one bit when the graph carries them, else two dependent look-ups
+    auto cls = [&](int j) -> bool {
+        if (a.edge_intra) return edge_is_intra(a, base + min(j, deg - 1));
+        return a.comm[load_u(j)] == cv;
+    };
     {
         bool intra = false;
-        if (WIDE) intra = a.comm[load_u(lane)] == cv;
+        if (WIDE) intra = cls(lane);
         make_key(slot_word(a, lane, v, batch), lane, intra, ck, cs);
         int rank = 0;
         for (int j = 0; j < WAVE; ++j) {
@@ -161,9 +170,21 @@ __device__ __forceinline__ void select_big_row(const SelectArgs &a, int g, int r
 #pragma unroll
             for (int i = 0; i < 4; ++i) offer(jb + i < deg, ((uint64_t)wr[i] << 32) | (uint32_t)(jb + i), 0u);
         }
+    } else if (a.edge_intra) {
+        // biased sampling needs the class of every neighbour; here it is one bit, fetched one chunk ahead
+        bool c1 = cls(WAVE + lane);
+        for (int j0 = WAVE; j0 < deg; j0 += WAVE) {
+            const bool c2 = cls(j0 + WAVE + lane);
+            const int j = j0 + lane;
+            uint64_t nk = KEY_MAX;
+            uint32_t ns = 0xFFFFFFFFu;
+            if (j < deg) make_key(slot_word(a, j, v, batch), j, c1, nk, ns);
+            offer(j < deg, nk, ns);
+            c1 = c2;
+        }
     } else {
-        // biased sampling needs the class of every neighbour: ids are fetched two chunks ahead and
-        // classes one chunk ahead, so the dependent look-ups overlap the arithmetic
+        // without the bits: ids are fetched two chunks ahead and classes one chunk ahead, so the dependent
+        // look-ups overlap the arithmetic
         int32_t u1 = load_u(WAVE + lane);
         int32_t c1 = a.comm[u1];
         int32_t u2 = load_u(2 * WAVE + lane);
@@ -205,24 +226,52 @@ __device__ __forceinline__ void select_big_row(const SelectArgs &a, int g, int r
 // general path, which needs no threshold).
 constexpr int CAND_CAP = 128;
 
-__device__ __forceinline__ bool select_big_row_uniform(const SelectArgs &a, int g, int row, int32_t v, int64_t base, int deg,
-                                                       int lane, uint2 *cand)
+//
+// INTRA_ONLY is the same for p = 1 when the graph carries its edge-class bits: the pool is the row's
+// intra-community slots (counted from the bits first); with fewer of them than the fanout the caller's general
+// path fills up with inter-community ones.
+template <bool INTRA_ONLY>
+__device__ __forceinline__ bool select_big_row_filtered(const SelectArgs &a, int g, int row, int32_t v, int64_t base, int deg,
+                                                        int lane, uint2 *cand)
 {
     const int k = a.fanout;
     const uint32_t batch = a.first_batch + (uint32_t)g;
     const uint64_t lt_mask = (1ull << lane) - 1ull;
-    uint64_t thr = ((uint64_t)a.cand_target << 32) / (uint64_t)deg;     // > 2^32 - 1 keeps every slot
+    int pool = deg;
+    if (INTRA_ONLY) {
+        const int64_t w_first = base >> 5, e_last = base + deg, w_last = (e_last - 1) >> 5;
+        int n_in = 0;
+        for (int64_t w = w_first + lane; w <= w_last; w += WAVE) {
+            uint32_t bits = a.edge_intra[w];
+            if (w == w_first) bits &= ~0u << (base & 31);
+            if (w == w_last && (e_last & 31)) bits &= (1u << (e_last & 31)) - 1u;
+            n_in += __popc(bits);
+        }
+#pragma unroll
+        for (int o = 32; o; o >>= 1) n_in += __shfl_xor(n_in, o);
+        if (n_in < k) return false;
+        pool = n_in;
+    }
+    const int64_t w_max = (a.n_entries - 1) >> 5;
+    uint64_t thr = ((uint64_t)a.cand_target << 32) / (uint64_t)pool;     // > 2^32 - 1 keeps every slot of the pool
     int n = 0;
     for (int j0 = 0; j0 < deg; j0 += 4 * WAVE) {
         const int jb = j0 + 4 * lane;
         const u32x4 w = philox4x32_10((uint32_t)jb >> 2, (uint32_t)v, batch, a.ctr3, a.seed_lo, a.seed_hi);
         const uint32_t wr[4] = {w.x, w.y, w.z, w.w};
+        uint32_t nib = 0xFu;          // class bits of the lane's four slots
+        if (INTRA_ONLY) {
+            const int64_t e = base + min(jb, deg - 1);
+            const int64_t wi = e >> 5;
+            const uint64_t win = (uint64_t)a.edge_intra[wi] | ((uint64_t)a.edge_intra[min(wi + 1, w_max)] << 32);
+            nib = (uint32_t)(win >> (e & 31)) & 0xFu;
+        }
         bool c[4];
         uint64_t b[4];
         int before = n, total = 0;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            c[i] = jb + i < deg && (uint64_t)wr[i] < thr;
+            c[i] = jb + i < deg && (uint64_t)wr[i] < thr && ((nib >> i) & 1u);
             b[i] = __ballot(c[i]);
             before += __popcll(b[i] & lt_mask);
             total += __popcll(b[i]);
@@ -335,7 +384,7 @@ __global__ __launch_bounds__(256) void select_kernel(SelectArgs a)
         int32_t u = 0;
         if (active) u = a.g_indices[my_base + j];
         bool intra = false;
-        if (WIDE && active && (maxlen > 0 || a.strict_p1)) intra = a.comm[u] == my_cv;
+        if (WIDE && active && (maxlen > 0 || a.strict_p1)) intra = a.edge_intra ? edge_is_intra(a, my_base + j) : a.comm[u] == my_cv;
         bool survivor = active && !(WIDE && a.strict_p1 && !intra);
         if (maxlen > 0) {
             // every lane computes its slot's key; lanes of rows that keep all their neighbours ignore it
@@ -362,7 +411,9 @@ __global__ __launch_bounds__(256) void select_kernel(SelectArgs a)
 #pragma unroll
     for (int i = 0; i < SEL_ROWS; ++i)
         if (deg[i] > WAVE) {
-            if (!WIDE && select_big_row_uniform(a, g, row0 + i, v[i], base[i], deg[i], lane, cand[threadIdx.x / WAVE])) continue;
+            uint2 *buf = cand[threadIdx.x / WAVE];
+            if (!WIDE && select_big_row_filtered<false>(a, g, row0 + i, v[i], base[i], deg[i], lane, buf)) continue;
+            if (WIDE && a.q_out == 0 && a.edge_intra && select_big_row_filtered<true>(a, g, row0 + i, v[i], base[i], deg[i], lane, buf)) continue;
             select_big_row<WIDE>(a, g, row0 + i, v[i], base[i], deg[i], cv[i], lane);
         }
 }
@@ -642,6 +693,30 @@ __global__ __launch_bounds__(256) void t_rank_kernel(DedupArgs a)
     a.t_indices[(int64_t)g * a.indices_stride + s0 + rank] = row;
 }
 
+// one thread per 32 adjacency entries: find the row of the first one, then walk
+__global__ __launch_bounds__(256) void edge_classes_kernel(const int64_t *__restrict__ indptr, const int32_t *__restrict__ indices,
+                                                           const int32_t *__restrict__ comm, int64_t n_nodes, int64_t n_entries,
+                                                           uint32_t *__restrict__ out)
+{
+    const int64_t w = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t e0 = w * 32;
+    if (e0 >= n_entries) return;
+    int64_t lo = 0, hi = n_nodes;            // last row r with indptr[r] <= e0
+    while (hi - lo > 1) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (indptr[mid] <= e0) lo = mid; else hi = mid;
+    }
+    int64_t r = lo, r_end = indptr[r + 1];
+    int32_t cr = comm[r];
+    uint32_t bits = 0;
+    for (int b = 0; b < 32 && e0 + b < n_entries; ++b) {
+        const int64_t e = e0 + b;
+        while (e >= r_end) { ++r; r_end = indptr[r + 1]; cr = comm[r]; }
+        if (comm[indices[e]] == cr) bits |= 1u << b;
+    }
+    out[w] = bits;
+}
+
 // ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
@@ -742,6 +817,20 @@ extern "C" cr_status cr_sample_blocks_workspace_bytes(const cr_sample_cfg *cfg, 
     return CR_OK;
 }
 
+extern "C" cr_status cr_graph_edge_classes(const cr_graph *graph, uint32_t *edge_intra, void *stream)
+{
+    CR_REQUIRE(graph != nullptr, CR_ERR_INVALID_ARG, "graph is NULL");
+    CR_REQUIRE(graph->indptr && graph->indices && graph->comm, CR_ERR_INVALID_ARG, "graph has a NULL array");
+    CR_REQUIRE(graph->n_nodes >= 1 && graph->n_entries >= 0, CR_ERR_INVALID_ARG, "graph sizes must be positive");
+    CR_REQUIRE(edge_intra != nullptr, CR_ERR_INVALID_ARG, "edge_intra must not be NULL");
+    if (dry_run() || graph->n_entries == 0) return CR_OK;
+    const int64_t words = ceil_div(graph->n_entries, 32);
+    hipLaunchKernelGGL(edge_classes_kernel, dim3((unsigned)ceil_div(words, 256)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       graph->indptr, graph->indices, graph->comm, graph->n_nodes, graph->n_entries, edge_intra);
+    CR_LAUNCH_CHECK();
+    return CR_OK;
+}
+
 extern "C" cr_status cr_sample_blocks(const cr_graph *graph, const cr_sample_cfg *cfg, const int32_t *roots,
                                       int64_t n_roots_total, int32_t batch_size, int32_t n_batches, void *ws,
                                       size_t ws_bytes, cr_block_set *layers, void *stream)
@@ -790,6 +879,7 @@ extern "C" cr_status cr_sample_blocks(const cr_graph *graph, const cr_sample_cfg
 
         SelectArgs sa;
         sa.g_indptr = graph->indptr; sa.g_indices = graph->indices; sa.comm = graph->comm;
+        sa.edge_intra = graph->edge_intra; sa.n_entries = graph->n_entries;
         sa.dst_ids = dst_ids; sa.dst_stride = dst_stride; sa.prev_hdr = prev_hdr;
         sa.n_roots_total = n_roots_total; sa.batch_size = batch_size; sa.fanout = f;
         sa.q_in = q_in; sa.q_out = q_out;

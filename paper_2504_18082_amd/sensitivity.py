@@ -16,7 +16,7 @@ import json
 import sys
 import time
 
-SETTINGS = [("rand:0.5", "rand", 0.0, 0.5), ("mix12.5:0.9", "mix", 12.5, 0.9), ("mix0:1.0", "mix", 0.0, 1.0)]
+DEFAULT_SETTINGS = ["rand:0.5", "mix12.5:0.9", "mix0:1.0"]      # <root policy>:<p>, as in fit.py; the first is the baseline
 
 
 def time_setting(tr, policy, mix, p, steps, warmup, epoch0):
@@ -52,12 +52,13 @@ def main(argv=None):
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--group", type=int, default=16)
     ap.add_argument("--seed", type=int, default=0)
-    ap.add_argument("--only", nargs="+", default=None, help="subset of the settings to run (no speed-ups then)")
+    ap.add_argument("--settings", nargs="+", default=DEFAULT_SETTINGS)
     args = ap.parse_args(argv)
 
     import numpy as np
     import torch
-    from . import binding as B, synth
+    from . import synth
+    from .fit import parse_setting
     from .trainer import Trainer
     if not torch.cuda.is_available():
         sys.exit("sensitivity needs a GPU: the path has no CPU fallback")
@@ -71,17 +72,14 @@ def main(argv=None):
             tr = Trainer(w, group_size=args.group, seed=args.seed)
             out = dict(workload=cfg.name, n_nodes=cfg.n_nodes, n_feat=cfg.n_feat,
                        table_MB=round(w.features.nbytes / 1e6, 1), steps=args.steps, settings={})
-            for i, (name, kind, pct, p) in enumerate(SETTINGS):
-                if args.only and name not in args.only:
-                    continue
-                policy = B.CR_ROOTS_RAND if kind == "rand" else B.CR_ROOTS_COMM_RAND
-                mix = synth.mix_count_from_percent(pct, n_comm_train) if kind == "mix" else 1
+            for i, name in enumerate(args.settings):
+                policy, mix, p = parse_setting(name, n_comm_train)
                 ms, gather_ms, n_in = time_setting(tr, policy, mix, p, args.steps, args.warmup, 10 * i)
                 row_bytes = cfg.n_feat * (2 if cfg.feat_dtype == "bf16" else 4)
                 out["settings"][name] = dict(ms_per_step=round(ms, 4), gather0_ms=round(gather_ms, 4),
                                              input_nodes=round(n_in), input_MB=round(n_in * row_bytes / 1e6, 2))
-            base = out["settings"].get("rand:0.5")
-            for name in ("mix12.5:0.9", "mix0:1.0") if base and len(out["settings"]) == len(SETTINGS) else ():
+            base = out["settings"][args.settings[0]]
+            for name in args.settings[1:]:
                 s = out["settings"][name]
                 s["speedup_step"] = round(base["ms_per_step"] / s["ms_per_step"], 3)
                 s["speedup_gather0"] = round(base["gather0_ms"] / s["gather0_ms"], 3)

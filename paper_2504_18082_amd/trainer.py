@@ -21,7 +21,7 @@ from . import synth
 class Trainer:
     def __init__(self, workload: synth.Workload, group_size: int = 16, lr: float = 0.01,
                  weight_decay: float = 5e-4, seed: int = 0, device: str = "cuda", weights=None,
-                 relabel_input: bool = False):
+                 relabel_input: bool = False, edge_classes: bool = True):
         import torch
         self.torch = torch
         self.w = workload
@@ -46,6 +46,9 @@ class Trainer:
         self.table = up(feats.view(np.int16) if feats.dtype == np.uint16 else feats)
         self.ld_table = feats.shape[1]
         self.graph = B.make_graph(self.indptr, self.indices, self.comm, cfg.n_comm)
+        if edge_classes:     # static per graph: one bit per adjacency entry, read by the biased selection
+            self.edge_bits = B.cr_graph_edge_classes(self.graph)
+            self.graph.edge_intra = self.edge_bits.data_ptr()
         self.n_nodes = cfg.n_nodes
         self.n_train = int(self.train_ids.numel())
         self.n_batches = -(-self.n_train // self.B)

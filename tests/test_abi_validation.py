@@ -68,7 +68,7 @@ def sample(fanouts=(10, 5), p=0.9, epoch=0, n_nodes=10000, batch=8, n_batches=1,
            ws_bytes=None, graph_null=None):
     lib = B.lib()
     cfg = B.make_sample_cfg(list(fanouts), p, 0, epoch, 0, flags)
-    graph = B.cr_graph(n_nodes, 100, FAKE, FAKE, FAKE, 5)
+    graph = B.cr_graph(n_nodes, 100, FAKE, FAKE, FAKE, 5, 0, None)
     if graph_null:
         setattr(graph, graph_null, None)
     need = C.c_size_t(0)
@@ -107,6 +107,15 @@ def test_sample_blocks_validation():
     with_ids = [block_set(1, 10, 48, 528, 480, t=False), block_set(1, 5, 8, 48, 40)]
     with_ids[0].gather_ids = FAKE
     assert sample(layers=with_ids, flags=B.CR_SAMPLE_INPUT_GLOBAL_IDS) == B.CR_OK
+
+
+def test_edge_classes_validation():
+    lib = B.lib()
+    graph = B.cr_graph(1000, 100, FAKE, FAKE, FAKE, 5, 0, None)
+    assert lib.cr_graph_edge_classes(C.byref(graph), vp(), None) == B.CR_OK
+    assert lib.cr_graph_edge_classes(C.byref(graph), None, None) == B.CR_ERR_INVALID_ARG
+    graph.comm = None
+    assert lib.cr_graph_edge_classes(C.byref(graph), vp(), None) == B.CR_ERR_INVALID_ARG
 
 
 def test_block_capacities_are_the_worst_case_bounds():

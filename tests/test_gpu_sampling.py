@@ -16,7 +16,7 @@ def torch_mod():
 
 
 class DeviceGraph:
-    def __init__(self, torch, graph, n_comm):
+    def __init__(self, torch, graph, n_comm, edge_classes=False):
         from paper_2504_18082_amd import binding as B
         indptr, indices, comm = graph
         self.indptr = torch.from_numpy(np.ascontiguousarray(indptr, dtype=np.int64)).cuda()
@@ -24,6 +24,9 @@ class DeviceGraph:
         self.comm = torch.from_numpy(np.ascontiguousarray(comm, dtype=np.int32)).cuda()
         self.c = B.make_graph(self.indptr, self.indices, self.comm, n_comm)
         self.n_nodes = len(indptr) - 1
+        if edge_classes:
+            self.bits = B.cr_graph_edge_classes(self.c)
+            self.c.edge_intra = self.bits.data_ptr()
 
 
 def run_gpu(torch, dg, roots, fanouts, p, strict, seed, epoch, first_batch, batch_size, hash_dedup=False, input_global=False):
@@ -141,3 +144,25 @@ def test_input_block_in_global_ids(torch_mod, tiny_workload, p, hash_dedup):
         print(f"case input-global p={p} fanouts={fanouts}", flush=True)
         layers, nb = run_gpu(torch_mod, dg, roots, fanouts, p, False, 0, 4, 2, 256, hash_dedup, input_global=True)
         compare(layers, nb, w.graph, roots, fanouts, p, False, 0, 4, 2, 256, f"input-global {fanouts}", input_global=True)
+
+
+def test_edge_class_bits(torch_mod, tiny_workload, arxiv_workload):
+    """cr_graph_edge_classes against its definition (bit e = both ends of entry e in one community), and sampling
+    with the bits against the oracle: same blocks as without them, for every p and also for long rows."""
+    for w in (tiny_workload, arxiv_workload):
+        dg = DeviceGraph(torch_mod, w.graph, w.cfg.n_comm, edge_classes=True)
+        torch_mod.cuda.synchronize()
+        rows = np.repeat(np.arange(w.cfg.n_nodes), np.diff(w.indptr))
+        want = (w.comm[rows] == w.comm[w.indices]).astype(np.uint8)
+        got = np.unpackbits(dg.bits.cpu().numpy().view(np.uint8), bitorder="little")[:len(want)]
+        assert np.array_equal(got, want)
+        tail = np.unpackbits(dg.bits.cpu().numpy().view(np.uint8), bitorder="little")[len(want):]
+        assert not tail.any()                              # padding bits of the last word are zero
+    w = arxiv_workload
+    dg = DeviceGraph(torch_mod, w.graph, w.cfg.n_comm, edge_classes=True)
+    perm = oracle.build_batches(oracle.COMM_RAND, 60, 0, 1, w.train_ids, w.comm, w.cfg.n_comm)
+    roots = perm[:1024 + 77]
+    for p, strict in ((0.9, False), (1.0, False), (1.0, True), (0.5, False)):
+        print(f"case edge bits p={p} strict={strict}", flush=True)
+        layers, nb = run_gpu(torch_mod, dg, roots, w.cfg.fanouts, p, strict, 0, 1, 3, 1024)
+        compare(layers, nb, w.graph, roots, w.cfg.fanouts, p, strict, 0, 1, 3, 1024, f"edge bits p={p}")
