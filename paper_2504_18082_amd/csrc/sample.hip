@@ -73,11 +73,12 @@ __device__ __forceinline__ bool edge_is_intra(const SelectArgs &a, int64_t e) { 
 __device__ __forceinline__ uint32_t pull32(uint32_t v, int src_lane) { return (uint32_t)__builtin_amdgcn_ds_bpermute(src_lane << 2, (int)v); }
 
 // ordering key of slot j of node v given its random word: narrow mode (p = 0.5) uses the word itself
-template <bool WIDE>
+// MODE: 0 uniform (p = 0.5), 1 p = 1 (classes only, no clock), 2 weighted (0.5 < p < 1)
+template <int MODE>
 __device__ __forceinline__ uint64_t slot_key(const SelectArgs &a, uint32_t r, bool intra)
 {
-    if (!WIDE) return r;
-    if (a.q_out == 0) return (intra ? 0ull : (1ull << 62)) + (uint64_t)r;
+    if (MODE == 0) return r;
+    if (MODE == 1) return (intra ? 0ull : (1ull << 62)) + (uint64_t)r;
     return (uint64_t)exp_clock_q24(r) * (uint64_t)(intra ? a.q_out : a.q_in);
 }
 
@@ -93,10 +94,11 @@ __device__ __forceinline__ uint32_t slot_word(const SelectArgs &a, int j, int32_
 // Lanes 0..k-1 hold the k smallest pairs seen so far in ascending order: the first 64 slots are ranked
 // by counting and permuted into place, later chunks of 64 slots are tested against the k-th pair and
 // inserted by shifting.  Every pair is distinct, so the surviving set is unique.
-template <bool WIDE>
+template <int MODE>
 __device__ __forceinline__ void select_big_row(const SelectArgs &a, int g, int row, int32_t v, int64_t base, int deg, int32_t cv,
-                                               int lane)
+                                            int lane)
 {
+    constexpr bool WIDE = MODE != 0;
     const int f = a.fanout;
     int32_t *sel_row = a.sel + (int64_t)g * a.sel_stride + (int64_t)row * f;
     const int k = f;
@@ -110,7 +112,7 @@ __device__ __forceinline__ void select_big_row(const SelectArgs &a, int g, int r
             ck = ((uint64_t)r << 32) | (uint32_t)j;
             cs = 0;
         } else {
-            ck = slot_key<true>(a, r, intra);
+            ck = slot_key<MODE>(a, r, intra);
             cs = (uint32_t)j;
         }
     };
@@ -313,6 +315,129 @@ __device__ __forceinline__ bool select_big_row_filtered(const SelectArgs &a, int
     return true;
 }
 
+// Long rows for 0.5 < p < 1, with the graph's edge-class bits.  A slot's key is E(r) * m with m = 1-p for an
+// intra-community slot and p for an inter-community one, E a non-increasing function of the random word r, so
+// "key below kappa" is "r at or above a per-class threshold".  kappa is chosen (float arithmetic, a few Newton steps
+// on the expected candidate count; its value only affects how many candidates there are) so that about cand_target
+// slots pass; only those get the 24-squaring clock.  The result is exact iff the fanout-th smallest candidate key
+// is below the smallest key any left-out slot can have, E(threshold - 1) * m per class in integer arithmetic: that is
+// checked, and otherwise (or with too few / too many candidates) the caller takes the general path.
+__device__ __forceinline__ bool select_big_row_weighted(const SelectArgs &a, int g, int row, int32_t v, int64_t base, int deg,
+                                                        int lane, uint2 *cand, unsigned long long *ckey)
+{
+    const int k = a.fanout;
+    const uint32_t batch = a.first_batch + (uint32_t)g;
+    const uint64_t lt_mask = (1ull << lane) - 1ull;
+    const int64_t w_first = base >> 5, e_last = base + deg, w_last = (e_last - 1) >> 5;
+    int n_in = 0;
+    for (int64_t w = w_first + lane; w <= w_last; w += WAVE) {
+        uint32_t bits = a.edge_intra[w];
+        if (w == w_first) bits &= ~0u << (base & 31);
+        if (w == w_last && (e_last & 31)) bits &= (1u << (e_last & 31)) - 1u;
+        n_in += __popc(bits);
+    }
+#pragma unroll
+    for (int o = 32; o; o >>= 1) n_in += __shfl_xor(n_in, o);
+    const int n_out = deg - n_in;
+
+    // per-class thresholds on the random word: candidate iff r >= t_class
+    uint64_t t_in = 0, t_out = 0;
+    if ((int)a.cand_target < deg) {
+        const float ln2 = 0.69314718f, target = (float)a.cand_target;
+        const float s_in = 1.0f / ((float)a.q_out * 16777216.0f), s_out = 1.0f / ((float)a.q_in * 16777216.0f);
+        const float fi = (float)n_in, fo = (float)n_out;
+        float kappa = target / (ln2 * (fi * s_in + fo * s_out));       // tangent at zero: never past the root
+#pragma unroll
+        for (int it = 0; it < 3; ++it) {
+            const float ei = exp2f(-kappa * s_in), eo = exp2f(-kappa * s_out);
+            const float gv = fi * (1.0f - ei) + fo * (1.0f - eo) - target;
+            const float gd = ln2 * (fi * s_in * ei + fo * s_out * eo);
+            if (gd > 0.0f) kappa -= gv / gd;
+        }
+        const float pi = exp2f(-kappa * s_in) * 4294967296.0f, po = exp2f(-kappa * s_out) * 4294967296.0f;
+        t_in = pi >= 4294967296.0f ? 0x100000000ull : (uint64_t)(pi > 0.0f ? pi : 0.0f);
+        t_out = po >= 4294967296.0f ? 0x100000000ull : (uint64_t)(po > 0.0f ? po : 0.0f);
+    }
+    // smallest key a slot that is left out can have (lane 0: intra, lane 1: inter), exact integers
+    uint64_t bound;
+    {
+        const uint64_t t = lane == 0 ? t_in : t_out;
+        const uint32_t m = lane == 0 ? a.q_out : a.q_in;
+        const int pool = lane == 0 ? n_in : n_out;
+        const uint64_t e = (uint64_t)exp_clock_q24((uint32_t)(t > 0 ? t - 1 : 0)) * m;
+        const uint64_t mine = (t == 0 || pool == 0) ? KEY_MAX : e;
+        const uint64_t b0 = rl64(mine, 0), b1 = rl64(mine, 1);
+        bound = b0 < b1 ? b0 : b1;
+    }
+
+    const int64_t w_max = (a.n_entries - 1) >> 5;
+    int n = 0;
+    for (int j0 = 0; j0 < deg; j0 += 4 * WAVE) {
+        const int jb = j0 + 4 * lane;
+        const u32x4 w = philox4x32_10((uint32_t)jb >> 2, (uint32_t)v, batch, a.ctr3, a.seed_lo, a.seed_hi);
+        const uint32_t wr[4] = {w.x, w.y, w.z, w.w};
+        const int64_t e = base + min(jb, deg - 1);
+        const int64_t wi = e >> 5;
+        const uint64_t win = (uint64_t)a.edge_intra[wi] | ((uint64_t)a.edge_intra[min(wi + 1, w_max)] << 32);
+        const uint32_t nib = (uint32_t)(win >> (e & 31)) & 0xFu;
+        bool c[4];
+        uint64_t b[4];
+        int before = n, total = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            c[i] = jb + i < deg && (uint64_t)wr[i] >= (((nib >> i) & 1u) ? t_in : t_out);
+            b[i] = __ballot(c[i]);
+            before += __popcll(b[i] & lt_mask);
+            total += __popcll(b[i]);
+        }
+        if (n + total > CAND_CAP) return false;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (c[i]) cand[before] = make_uint2(wr[i], (uint32_t)(jb + i) | (((nib >> i) & 1u) << 31));
+            before += c[i] ? 1 : 0;
+        }
+        n += total;
+    }
+    if (n < k) return false;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+
+    // keys of the candidates only; candidate t sits at index t in slot order, a lane owns candidates lane and lane + 64
+    const uint2 c0 = cand[min(lane, n - 1)], c1 = cand[min(lane + WAVE, n - 1)];
+    const bool have0 = lane < n, have1 = lane + WAVE < n;
+    const uint64_t key0 = (uint64_t)exp_clock_q24(c0.x) * ((c0.y >> 31) ? a.q_out : a.q_in);
+    uint64_t key1 = KEY_MAX;
+    if (n > WAVE) key1 = (uint64_t)exp_clock_q24(c1.x) * ((c1.y >> 31) ? a.q_out : a.q_in);
+    if (have0) ckey[lane] = key0;
+    if (have1) ckey[lane + WAVE] = key1;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    int r0 = 0, r1 = 0;
+    if (n <= WAVE) {
+        for (int t = 0; t < n; ++t) {
+            const uint64_t kt = ckey[t];
+            r0 += (kt < key0 || (kt == key0 && t < lane)) ? 1 : 0;
+        }
+    } else {
+        for (int t = 0; t < n; ++t) {
+            const uint64_t kt = ckey[t];
+            r0 += (kt < key0 || (kt == key0 && t < lane)) ? 1 : 0;
+            r1 += (kt < key1 || (kt == key1 && t < lane + WAVE)) ? 1 : 0;
+        }
+    }
+    // the fanout-th smallest candidate key must beat everything that was left out
+    const uint64_t q0 = __ballot(have0 && r0 == k - 1), q1 = __ballot(have1 && r1 == k - 1);
+    const uint64_t kth = q0 ? rl64(key0, __ffsll((long long)q0) - 1) : rl64(key1, __ffsll((long long)q1) - 1);
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");      // both buffers are reused by this wave's next long row
+    if (!(kth < bound)) return false;
+
+    const bool s0 = have0 && r0 < k, s1 = have1 && r1 < k;
+    const uint64_t m0 = __ballot(s0), m1 = __ballot(s1);
+    int32_t *sel_row = a.sel + (int64_t)g * a.sel_stride + (int64_t)row * k;
+    if (s0) sel_row[__popcll(m0 & lt_mask)] = a.g_indices[base + (c0.y & 0x7FFFFFFFu)];
+    if (s1) sel_row[__popcll(m0) + __popcll(m1 & lt_mask)] = a.g_indices[base + (c1.y & 0x7FFFFFFFu)];
+    if (lane == 0) a.cnt[(int64_t)g * a.cnt_stride + row] = k;
+    return true;
+}
+
 // A wave takes SEL_ROWS consecutive destination rows.  Rows with at most 64 neighbours are packed side
 // by side into the wave's lanes (lane = one neighbour slot of one row; as many consecutive rows per pass
 // as fit), so that the random words, the keys and the ranking of several short rows cost one pass of
@@ -321,10 +446,12 @@ __device__ __forceinline__ bool select_big_row_filtered(const SelectArgs &a, int
 // select_big_row one at a time.
 constexpr int SEL_ROWS = 4;
 
-template <bool WIDE>
-__global__ __launch_bounds__(256) void select_kernel(SelectArgs a)
+template <int MODE>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))) void select_kernel(SelectArgs a)
 {
+    constexpr bool WIDE = MODE != 0;
     __shared__ uint2 cand[4][CAND_CAP];
+    __shared__ unsigned long long ckey[MODE == 2 ? 4 : 1][MODE == 2 ? CAND_CAP : 1];
     const int g = blockIdx.y;
     const int n_dst = group_n_dst(a.prev_hdr, g, a.n_roots_total, a.batch_size);
     const int row0 = (int)(blockIdx.x * 4 + threadIdx.x / WAVE) * SEL_ROWS;
@@ -388,7 +515,7 @@ __global__ __launch_bounds__(256) void select_kernel(SelectArgs a)
         bool survivor = active && !(WIDE && a.strict_p1 && !intra);
         if (maxlen > 0) {
             // every lane computes its slot's key; lanes of rows that keep all their neighbours ignore it
-            const uint64_t ck = slot_key<WIDE>(a, slot_word(a, j, my_v, batch), intra);
+            const uint64_t ck = slot_key<MODE>(a, slot_word(a, j, my_v, batch), intra);
             int rank = 0;
             for (int d = 0; d < maxlen; ++d) {
                 const int src = my_start + d;
@@ -412,9 +539,11 @@ __global__ __launch_bounds__(256) void select_kernel(SelectArgs a)
     for (int i = 0; i < SEL_ROWS; ++i)
         if (deg[i] > WAVE) {
             uint2 *buf = cand[threadIdx.x / WAVE];
-            if (!WIDE && select_big_row_filtered<false>(a, g, row0 + i, v[i], base[i], deg[i], lane, buf)) continue;
-            if (WIDE && a.q_out == 0 && a.edge_intra && select_big_row_filtered<true>(a, g, row0 + i, v[i], base[i], deg[i], lane, buf)) continue;
-            select_big_row<WIDE>(a, g, row0 + i, v[i], base[i], deg[i], cv[i], lane);
+            if (MODE == 0 && select_big_row_filtered<false>(a, g, row0 + i, v[i], base[i], deg[i], lane, buf)) continue;
+            if (MODE == 1 && a.edge_intra && select_big_row_filtered<true>(a, g, row0 + i, v[i], base[i], deg[i], lane, buf)) continue;
+            if (MODE == 2 && a.edge_intra &&
+                select_big_row_weighted(a, g, row0 + i, v[i], base[i], deg[i], lane, buf, ckey[threadIdx.x / WAVE])) continue;
+            select_big_row<MODE>(a, g, row0 + i, v[i], base[i], deg[i], cv[i], lane);
         }
 }
 
@@ -893,8 +1022,10 @@ extern "C" cr_status cr_sample_blocks(const cr_graph *graph, const cr_sample_cfg
             int target = f + (int)(4.0 * sqrt((double)f)) + 4;
             sa.cand_target = (uint32_t)(target > 96 ? 96 : target);
         }
-        if (q_in == q_out) hipLaunchKernelGGL(select_kernel<false>, dim3((unsigned)ceil_div(cap_dst, 4 * SEL_ROWS), n_batches), blk, 0, s, sa);
-        else hipLaunchKernelGGL(select_kernel<true>, dim3((unsigned)ceil_div(cap_dst, 4 * SEL_ROWS), n_batches), blk, 0, s, sa);
+        const dim3 sel_grid((unsigned)ceil_div(cap_dst, 4 * SEL_ROWS), n_batches);
+        if (q_in == q_out) hipLaunchKernelGGL(select_kernel<0>, sel_grid, blk, 0, s, sa);
+        else if (q_out == 0) hipLaunchKernelGGL(select_kernel<1>, sel_grid, blk, 0, s, sa);
+        else hipLaunchKernelGGL(select_kernel<2>, sel_grid, blk, 0, s, sa);
 
         ScanArgs sc;
         sc.prev_hdr = prev_hdr; sc.n_roots_total = n_roots_total; sc.batch_size = batch_size;
