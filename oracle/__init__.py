@@ -71,6 +71,8 @@ def lib():
         L.orc_softmax_xent.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p,
                                        C.c_void_p]
         L.orc_count_correct.restype = C.c_int32
+        L.orc_cache_fetch.restype = C.c_int32
+        L.orc_cache_fetch.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
         L.orc_count_correct.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p]
         _lib = L
     return _lib
@@ -274,3 +276,24 @@ def count_correct(logits, labels, n_classes=None):
     labels = _arr(labels, np.int32)
     n, ld = logits.shape
     return int(lib().orc_count_correct(n, ld if n_classes is None else n_classes, _p(logits), ld, _p(labels)))
+
+
+class FeatureCacheModel:
+    """State of the set-associative, batch-synchronous LRU cache model (orc_cache_fetch)."""
+
+    def __init__(self, n_sets, ways):
+        self.n_sets, self.ways = int(n_sets), int(ways)
+        self.keys = np.full(self.n_sets * self.ways, -1, dtype=np.int32)
+        self.stamps = np.full(self.n_sets * self.ways, -1, dtype=np.int32)
+        self.queries = 0
+        self.misses = 0
+
+    def fetch(self, ids, stamp):
+        """Looks up / inserts the distinct node ids of one batch; returns (slots, n_miss); slot -1 = not cached."""
+        ids = _arr(ids, np.int32)
+        assert len(np.unique(ids)) == len(ids), "the ids of a batch must be distinct"
+        slots = np.empty(len(ids), dtype=np.int32)
+        n_miss = int(lib().orc_cache_fetch(self.n_sets, self.ways, _p(self.keys), _p(self.stamps), _p(ids), len(ids), int(stamp), _p(slots)))
+        self.queries += len(ids)
+        self.misses += n_miss
+        return slots, n_miss

@@ -503,3 +503,48 @@ int32_t orc_count_correct(int32_t n, int32_t C, const double *logits, int64_t ld
     }
     return ok;
 }
+
+/* Software-managed feature cache in front of a slower feature store (Section 6.5, impact of software-managed
+ * caches: an LRU cache of node-feature rows in GPU memory).  The paper names the policy (LRU) and the capacity, not
+ * the organisation; the reading here is a set-associative cache (set = node id mod n_sets, `ways` rows per set)
+ * that is updated once per mini-batch:
+ *   1. every distinct input node of the batch is looked up; a hit refreshes its row's stamp to this batch's stamp;
+ *   2. the misses of a set, in the order the nodes appear in the batch, replace that set's rows in order of
+ *      (stamp ascending, way ascending), never a row hit or filled in this same batch (empty rows carry stamp -1,
+ *      so they go first);
+ *   3. misses that find no such row in their set are served from the store without being cached (slot -1 here).
+ * With one set, and batches of a single node, this is textbook LRU.
+ * keys / stamps: [n_sets*ways], -1 = empty.  ids: n distinct node ids.  slot_out[i] = n_sets-major slot of ids[i]
+ * after the update, or -1.  Returns the number of misses. */
+int32_t orc_cache_fetch(int32_t n_sets, int32_t ways, int32_t *keys, int32_t *stamps, const int32_t *ids, int32_t n,
+                        int32_t stamp, int32_t *slot_out)
+{
+    int32_t n_miss = 0;
+    /* 1. look-ups */
+    for (int32_t i = 0; i < n; ++i) {
+        const int32_t set = ids[i] % n_sets;
+        slot_out[i] = -2;                                   /* miss, not yet placed */
+        for (int32_t w = 0; w < ways; ++w) {
+            const int64_t s = (int64_t)set * ways + w;
+            if (keys[s] == ids[i]) { slot_out[i] = (int32_t)s; stamps[s] = stamp; break; }
+        }
+        if (slot_out[i] == -2) ++n_miss;
+    }
+    /* 2. + 3. replacements, set by set; the misses of a set are visited in batch order */
+    for (int32_t i = 0; i < n; ++i) {
+        if (slot_out[i] != -2) continue;
+        const int32_t set = ids[i] % n_sets;
+        int32_t best = -1;
+        for (int32_t w = 0; w < ways; ++w) {
+            const int64_t s = (int64_t)set * ways + w;
+            if (stamps[s] == stamp) continue;               /* hit or filled in this batch */
+            if (best < 0 || stamps[s] < stamps[(int64_t)set * ways + best]) best = w;
+        }
+        if (best < 0) { slot_out[i] = -1; continue; }
+        const int64_t s = (int64_t)set * ways + best;
+        keys[s] = ids[i];
+        stamps[s] = stamp;
+        slot_out[i] = (int32_t)s;
+    }
+    return n_miss;
+}
