@@ -294,6 +294,59 @@ cr_status cr_count_correct(const int32_t *hdr, int32_t max_rows, const float *lo
                            int32_t n_classes, const int32_t *labels, const int32_t *root_ids,
                            int32_t *count, void *stream);
 
+/* ------------------------------------------------------------------------- */
+/* Software-managed feature cache (Section 6.5, impact of software-managed     */
+/* caches: feature rows kept in a slower store, an LRU cache of rows in GPU    */
+/* memory in front of it).                                                     */
+/* ------------------------------------------------------------------------- */
+/* Set-associative (set = node id mod n_sets, `ways` rows per set), updated once per mini-batch:
+ *   1. every distinct input node of the batch is looked up; a hit refreshes its row's stamp;
+ *   2. the misses of a set, in the order the nodes appear in the batch, replace that set's rows in order of
+ *      (stamp ascending, way ascending), never a row hit or filled in this batch (empty rows have stamp -1);
+ *   3. misses that find no such row are copied to a per-batch overflow area behind the cached rows instead.
+ * After a fetch, rows[slot_out[i]] holds the feature row of ids[i] for every i, so the feature gather can read the
+ * cache's row array through slot_out in place of the store through the node ids.  All arrays are the caller's. */
+#define CR_CACHE_MAX_WAYS 64
+#define CR_CACHE_LIST_CAP 32 /* misses one set can take in one batch; more raise counters[3] (use more sets) */
+
+typedef struct {
+    int32_t n_sets;     /* >= 1 */
+    int32_t ways;       /* 1..CR_CACHE_MAX_WAYS */
+    int32_t row_bytes;  /* bytes per feature row, multiple of 16 */
+    int32_t n_overflow; /* rows of the overflow area, >= the largest batch's number of distinct input nodes */
+    int32_t *keys;      /* device int32[n_sets*ways]: node id, or -1 */
+    int32_t *stamps;    /* device int32[n_sets*ways]: stamp of the last batch that used the row, or -1 */
+    void *rows;         /* device [(n_sets*ways + n_overflow)][row_bytes], 16-byte aligned */
+    int32_t *set_count; /* device int32[n_sets]: scratch, zero between calls */
+    int32_t *set_list;  /* device int32[n_sets][CR_CACHE_LIST_CAP]: scratch */
+    int32_t *counters;  /* device int32[8], cumulative since cr_cache_reset: [0] look-ups, [1] misses, [2] misses that
+                           went to the overflow area, [3] nonzero = a set took more than CR_CACHE_LIST_CAP misses in
+                           one batch or the overflow area was too small (results invalid); [4..7] scratch */
+} cr_feature_cache;
+
+/* Empties the cache and zeroes its scratch and counters. */
+cr_status cr_cache_reset(const cr_feature_cache *cache, void *stream);
+
+cr_status cr_cache_fetch_workspace_bytes(int32_t max_n, size_t *bytes /*host*/);
+
+/* One batch's look-ups and replacements.
+ *   store     : the feature store, [n_nodes][store_ld_bytes] bytes, readable by the GPU: device memory, or host memory
+ *               from cr_host_alloc (its device_ptr); only the rows of missing nodes are read, once each
+ *   ids       : device int32[>= n]: the batch's distinct input nodes; n = min(hdr[hdr_word], max_n) read on the device
+ *               (a block header with hdr_word = CR_HDR_N_SRC, or any device int32)
+ *   stamp     : the batch's stamp, increasing from batch to batch, >= 0
+ *   slot_out  : device int32[max_n]: row of `rows` that holds ids[i]'s features
+ *   ws        : device workspace of cr_cache_fetch_workspace_bytes(max_n) bytes */
+cr_status cr_cache_fetch(const cr_feature_cache *cache, const void *store, int64_t store_ld_bytes,
+                         const int32_t *ids, const int32_t *hdr, int32_t hdr_word, int32_t max_n,
+                         int32_t stamp, int32_t *slot_out, void *ws, size_t ws_bytes, void *stream);
+
+/* Pinned host memory that kernels can read (for a feature store that stays on the host, as in the paper's
+ * mixed CPU+GPU set-up for its largest graph).  *host_ptr is the address for the CPU, *device_ptr the one for
+ * kernels.  Synchronous; free with cr_host_free(host_ptr). */
+cr_status cr_host_alloc(size_t bytes, void **host_ptr, void **device_ptr);
+cr_status cr_host_free(void *host_ptr);
+
 #ifdef __cplusplus
 }
 #endif

@@ -31,6 +31,7 @@ EXPORTS = [
     "cr_sage_padded_dims", "cr_sage_refresh_shadows", "cr_sage_linear_fwd",
     "cr_sage_linear_bwd_workspace_bytes", "cr_sage_linear_bwd", "cr_sage_linear_bwd_input", "cr_softmax_xent",
     "cr_count_correct",
+    "cr_cache_reset", "cr_cache_fetch_workspace_bytes", "cr_cache_fetch", "cr_host_alloc", "cr_host_free",
 ]
 
 
@@ -49,6 +50,15 @@ class cr_graph(C.Structure):
     _fields_ = [("n_nodes", C.c_int64), ("n_entries", C.c_int64), ("indptr", C.c_void_p),
                 ("indices", C.c_void_p), ("comm", C.c_void_p), ("n_comm", C.c_int32), ("reserved", C.c_int32),
                 ("edge_intra", C.c_void_p)]
+
+
+class cr_feature_cache(C.Structure):
+    _fields_ = [("n_sets", C.c_int32), ("ways", C.c_int32), ("row_bytes", C.c_int32), ("n_overflow", C.c_int32),
+                ("keys", C.c_void_p), ("stamps", C.c_void_p), ("rows", C.c_void_p), ("set_count", C.c_void_p),
+                ("set_list", C.c_void_p), ("counters", C.c_void_p)]
+
+
+CR_CACHE_LIST_CAP = 32
 
 
 class cr_block_set(C.Structure):
@@ -110,6 +120,11 @@ def lib():
         L.cr_sage_linear_bwd_input.argtypes = [C.POINTER(cr_sage_layer), vp, i32, vp, vp, vp, vp, vp]
         L.cr_softmax_xent.argtypes = [vp, i32, vp, i64, i32, vp, vp, vp, vp, vp, vp, vp]
         L.cr_count_correct.argtypes = [vp, i32, vp, i64, i32, vp, vp, vp, vp]
+        L.cr_cache_reset.argtypes = [C.POINTER(cr_feature_cache), vp]
+        L.cr_cache_fetch_workspace_bytes.argtypes = [i32, C.POINTER(C.c_size_t)]
+        L.cr_cache_fetch.argtypes = [C.POINTER(cr_feature_cache), vp, i64, vp, vp, i32, i32, i32, vp, vp, C.c_size_t, vp]
+        L.cr_host_alloc.argtypes = [C.c_size_t, C.POINTER(vp), C.POINTER(vp)]
+        L.cr_host_free.argtypes = [vp]
         for name in EXPORTS:
             fn = getattr(L, name)
             if name not in ("cr_last_error", "cr_version", "cr_set_dry_run", "cr_mix_count_from_percent"):
@@ -339,3 +354,62 @@ def cr_softmax_xent(hdr_ptr, max_rows, logits, ld, n_classes, labels, root_ids_p
 def cr_count_correct(hdr_ptr, max_rows, logits, ld, n_classes, labels, root_ids_ptr, count, stream=None):
     _check(lib().cr_count_correct(hdr_ptr, max_rows, _ptr(logits), ld, n_classes, _ptr(labels), root_ids_ptr, _ptr(count),
                                   _stream(stream)))
+
+
+class FeatureCache:
+    """Device storage of a software-managed feature cache (set-associative LRU, updated once per batch)."""
+
+    def __init__(self, n_sets: int, ways: int, row_bytes: int, max_batch_nodes: int, device="cuda"):
+        import torch
+        self.n_sets, self.ways, self.row_bytes, self.max_n = n_sets, ways, row_bytes, max_batch_nodes
+        slots = n_sets * ways
+        i32 = lambda n: torch.zeros(n, dtype=torch.int32, device=device)
+        self.keys, self.stamps = i32(slots), i32(slots)
+        self.rows = torch.zeros((slots + max_batch_nodes, row_bytes), dtype=torch.uint8, device=device)
+        self.set_count, self.set_list, self.counters = i32(n_sets), i32(n_sets * CR_CACHE_LIST_CAP), i32(8)
+        self.slot_out = i32(max_batch_nodes)
+        n = C.c_size_t(0)
+        _check(lib().cr_cache_fetch_workspace_bytes(max_batch_nodes, C.byref(n)))
+        self.ws = torch.empty(n.value, dtype=torch.uint8, device=device)
+        self.c = cr_feature_cache(n_sets, ways, row_bytes, max_batch_nodes, _ptr(self.keys), _ptr(self.stamps), _ptr(self.rows),
+                                  _ptr(self.set_count), _ptr(self.set_list), _ptr(self.counters))
+        self.reset()
+
+    def reset(self, stream=None):
+        _check(lib().cr_cache_reset(C.byref(self.c), _stream(stream)))
+
+    def fetch(self, store_ptr, store_ld_bytes, ids_ptr, hdr_ptr, hdr_word, stamp, stream=None):
+        """store_ptr / ids_ptr / hdr_ptr: raw addresses (ctypes.c_void_p) the GPU can read."""
+        _check(lib().cr_cache_fetch(C.byref(self.c), store_ptr, store_ld_bytes, ids_ptr, hdr_ptr, hdr_word, self.max_n, stamp,
+                                    _ptr(self.slot_out), _ptr(self.ws), self.ws.numel(), _stream(stream)))
+
+    def stats(self):
+        """(look-ups, misses, misses served from the overflow area, status) since the last reset."""
+        c = self.counters.cpu().numpy()
+        return int(c[0]), int(c[1]), int(c[2]), int(c[3])
+
+
+class HostBuffer:
+    """Pinned host memory that kernels can read (cr_host_alloc); .array is a numpy view for the CPU side."""
+
+    def __init__(self, shape, dtype):
+        import numpy as np
+        self.shape, self.dtype = tuple(shape), np.dtype(dtype)
+        self.nbytes = int(np.prod(self.shape)) * self.dtype.itemsize
+        h, d = C.c_void_p(), C.c_void_p()
+        _check(lib().cr_host_alloc(self.nbytes, C.byref(h), C.byref(d)))
+        self.host_ptr, self.device_ptr = h, d
+        buf = (C.c_char * self.nbytes).from_address(h.value)
+        self.array = np.frombuffer(buf, dtype=self.dtype).reshape(self.shape)
+
+    def free(self):
+        if self.host_ptr is not None and self.host_ptr.value:
+            self.array = None
+            _check(lib().cr_host_free(self.host_ptr))
+            self.host_ptr = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass

@@ -1,0 +1,80 @@
+"""GPU parity of the software-managed feature cache (cr_cache_fetch) against the oracle's model: keys, stamps and
+slots bit for bit after every batch, rows equal to the store's, miss counters equal."""
+import ctypes as C
+
+import numpy as np
+import pytest
+
+import oracle
+
+pytestmark = pytest.mark.gpu
+
+
+def run_trace(torch, B, batches, n_sets, ways, store, max_n, host_store=None):
+    n_nodes, row_bytes = store.shape
+    cache = B.FeatureCache(n_sets, ways, row_bytes, max_n)
+    model = oracle.FeatureCacheModel(n_sets, ways)
+    if host_store is None:
+        d_store = torch.from_numpy(store).cuda()
+        store_ptr = C.c_void_p(d_store.data_ptr())
+    else:
+        store_ptr = host_store.device_ptr
+    ids_dev = torch.zeros(max_n, dtype=torch.int32, device="cuda")
+    hdr = torch.zeros(8, dtype=torch.int32, device="cuda")
+    n_slots = n_sets * ways
+    for t, ids in enumerate(batches):
+        print(f"cache batch {t}: {len(ids)} nodes, {n_sets} sets x {ways} ways", flush=True)
+        ids = np.asarray(ids, dtype=np.int32)
+        ids_dev[:len(ids)] = torch.from_numpy(ids).cuda()
+        hdr[1] = len(ids)
+        cache.fetch(store_ptr, row_bytes, C.c_void_p(ids_dev.data_ptr()), C.c_void_p(hdr.data_ptr()), 1, t)
+        torch.cuda.synchronize()
+        want_slots, _ = model.fetch(ids, t)
+        got_slots = cache.slot_out.cpu().numpy()[:len(ids)]
+        cached = want_slots >= 0
+        assert np.array_equal(got_slots[cached], want_slots[cached])
+        over = got_slots[~cached]
+        assert np.all(over >= n_slots) and len(np.unique(over)) == len(over)          # overflow rows, one each
+        assert np.array_equal(cache.keys.cpu().numpy(), model.keys)
+        assert np.array_equal(cache.stamps.cpu().numpy(), model.stamps)
+        rows = cache.rows.cpu().numpy()
+        assert np.array_equal(rows[got_slots], store[ids])                              # every node's row is where slot_out says
+        assert not cache.set_count.cpu().numpy().any()                                  # scratch is clean again
+        q, m, u, status = cache.stats()
+        assert (q, m, status) == (model.queries, model.misses, 0)
+    return cache, model
+
+
+@pytest.mark.parametrize("n_sets,ways,universe,batch", [(64, 16, 3000, 300), (1, 64, 200, 20), (37, 1, 500, 40), (256, 32, 20000, 2000),
+                                                        (8, 4, 400, 60)])
+def test_cache_matches_model(n_sets, ways, universe, batch):
+    import torch
+    from paper_2504_18082_amd import binding as B
+    rng = np.random.default_rng(n_sets * 1000 + ways)
+    store = rng.integers(0, 256, size=(universe, 64), dtype=np.uint8)
+    # a mix of fresh and recurring nodes: half of every batch is drawn from a slowly moving window
+    batches = []
+    for t in range(12):
+        lo = (t * batch // 3) % max(1, universe - 2 * batch)
+        window = lo + rng.choice(2 * batch, size=batch // 2, replace=False)
+        rest = rng.choice(universe, size=batch, replace=False)
+        ids = np.unique(np.concatenate([window, rest]))[:batch + batch // 2]
+        batches.append(rng.permutation(ids))
+    batches.append(np.zeros(0, dtype=np.int32))                                         # an empty batch changes nothing
+    batches.append(batches[0])
+    cache, model = run_trace(torch, B, batches, n_sets, ways, store, max_n=2 * batch)
+    assert model.misses < model.queries                                                 # the trace does produce hits
+
+
+def test_cache_over_host_memory():
+    """The store may stay in pinned host memory (the paper's set-up for its largest graph): same results."""
+    import torch
+    from paper_2504_18082_amd import binding as B
+    rng = np.random.default_rng(5)
+    universe, row_bytes = 5000, 256
+    host = B.HostBuffer((universe, row_bytes), np.uint8)
+    host.array[:] = rng.integers(0, 256, size=(universe, row_bytes), dtype=np.uint8)
+    batches = [rng.choice(universe, size=700, replace=False) for _ in range(6)]
+    run_trace(torch, B, batches, 128, 16, np.array(host.array), max_n=1024, host_store=host)
+    torch.cuda.synchronize()
+    host.free()
