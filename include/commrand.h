@@ -341,6 +341,13 @@ cr_status cr_cache_fetch(const cr_feature_cache *cache, const void *store, int64
                          const int32_t *ids, const int32_t *hdr, int32_t hdr_word, int32_t max_n,
                          int32_t stamp, int32_t *slot_out, void *ws, size_t ws_bytes, void *stream);
 
+/* The store without a cache: copies the rows of the batch's distinct input nodes, rows_out[i] = store[ids[i]] for
+ * i < n = min(hdr[hdr_word], max_n), each row read once (what a unified-addressing gather of the input features
+ * does); the feature gather then reads rows_out as a dense [n_src][row_bytes] array (indirect = 0).
+ *   rows_out : device [max_n][row_bytes], 16-byte aligned; row_bytes a multiple of 16 */
+cr_status cr_stage_rows(const void *store, int64_t store_ld_bytes, const int32_t *ids, const int32_t *hdr,
+                        int32_t hdr_word, int32_t max_n, void *rows_out, int32_t row_bytes, void *stream);
+
 /* Pinned host memory that kernels can read (for a feature store that stays on the host, as in the paper's
  * mixed CPU+GPU set-up for its largest graph).  *host_ptr is the address for the CPU, *device_ptr the one for
  * kernels.  Synchronous; free with cr_host_free(host_ptr). */

@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(HERE, "libcommrand.so")
 CR_MAX_LAYERS = 8
 CR_MAX_FANOUT = 64
 CR_HDR_WORDS = 8
+CR_HDR_N_DST, CR_HDR_N_SRC, CR_HDR_NNZ, CR_HDR_STATUS = 0, 1, 2, 3
 CR_OK, CR_ERR_INVALID_ARG, CR_ERR_CAPACITY, CR_ERR_UNSUPPORTED, CR_ERR_HIP = range(5)
 CR_ROOTS_NORAND, CR_ROOTS_COMM_RAND, CR_ROOTS_RAND = 0, 1, 2
 CR_F32, CR_BF16 = 0, 1
@@ -31,7 +32,7 @@ EXPORTS = [
     "cr_sage_padded_dims", "cr_sage_refresh_shadows", "cr_sage_linear_fwd",
     "cr_sage_linear_bwd_workspace_bytes", "cr_sage_linear_bwd", "cr_sage_linear_bwd_input", "cr_softmax_xent",
     "cr_count_correct",
-    "cr_cache_reset", "cr_cache_fetch_workspace_bytes", "cr_cache_fetch", "cr_host_alloc", "cr_host_free",
+    "cr_cache_reset", "cr_cache_fetch_workspace_bytes", "cr_cache_fetch", "cr_stage_rows", "cr_host_alloc", "cr_host_free",
 ]
 
 
@@ -123,6 +124,7 @@ def lib():
         L.cr_cache_reset.argtypes = [C.POINTER(cr_feature_cache), vp]
         L.cr_cache_fetch_workspace_bytes.argtypes = [i32, C.POINTER(C.c_size_t)]
         L.cr_cache_fetch.argtypes = [C.POINTER(cr_feature_cache), vp, i64, vp, vp, i32, i32, i32, vp, vp, C.c_size_t, vp]
+        L.cr_stage_rows.argtypes = [vp, i64, vp, vp, i32, i32, vp, i32, vp]
         L.cr_host_alloc.argtypes = [C.c_size_t, C.POINTER(vp), C.POINTER(vp)]
         L.cr_host_free.argtypes = [vp]
         for name in EXPORTS:
@@ -281,7 +283,8 @@ def cr_sample_blocks(graph: cr_graph, cfg: cr_sample_cfg, roots, n_roots_total, 
 # --------------------------------------------------------------------------- training on the sub-graph
 def cr_gather_aggregate_fwd(blocks: BlockSet, g, H_src, dtype, ld_src, F, indirect, agg=None, agg_bf16=None,
                             self_bf16=None, ld_bf16=0, stream=None):
-    _check(lib().cr_gather_aggregate_fwd(C.byref(blocks.c), g, _ptr(H_src), dtype, ld_src, F, int(indirect),
+    H_ptr = H_src if isinstance(H_src, C.c_void_p) else _ptr(H_src)
+    _check(lib().cr_gather_aggregate_fwd(C.byref(blocks.c), g, H_ptr, dtype, ld_src, F, int(indirect),
                                          _ptr(agg), _ptr(agg_bf16), _ptr(self_bf16), ld_bf16, _stream(stream)))
 
 
@@ -354,6 +357,10 @@ def cr_softmax_xent(hdr_ptr, max_rows, logits, ld, n_classes, labels, root_ids_p
 def cr_count_correct(hdr_ptr, max_rows, logits, ld, n_classes, labels, root_ids_ptr, count, stream=None):
     _check(lib().cr_count_correct(hdr_ptr, max_rows, _ptr(logits), ld, n_classes, _ptr(labels), root_ids_ptr, _ptr(count),
                                   _stream(stream)))
+
+
+def cr_stage_rows(store_ptr, store_ld_bytes, ids_ptr, hdr_ptr, hdr_word, max_n, rows_out, row_bytes, stream=None):
+    _check(lib().cr_stage_rows(store_ptr, store_ld_bytes, ids_ptr, hdr_ptr, hdr_word, max_n, _ptr(rows_out), row_bytes, _stream(stream)))
 
 
 class FeatureCache:

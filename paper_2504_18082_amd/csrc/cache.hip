@@ -125,6 +125,19 @@ __global__ __launch_bounds__(256) void cache_fill_kernel(CacheArgs a)
     *reinterpret_cast<uint4 *>(static_cast<char *>(a.c.rows) + (int64_t)a.fill_dst[f] * a.c.row_bytes + (int64_t)c * 16) = v;
 }
 
+__global__ __launch_bounds__(256) void stage_rows_kernel(const char *__restrict__ store, int64_t store_ld, const int32_t *__restrict__ ids,
+                                                        const int32_t *__restrict__ n_ptr, int max_n, char *__restrict__ out, int row_bytes)
+{
+    const int chunks = row_bytes / 16;
+    const int n = min(max(*n_ptr, 0), max_n);
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t i = gid / chunks;
+    const int c = (int)(gid % chunks);
+    if (i >= n) return;
+    const uint4 v = *reinterpret_cast<const uint4 *>(store + (int64_t)ids[i] * store_ld + (int64_t)c * 16);
+    *reinterpret_cast<uint4 *>(out + i * row_bytes + (int64_t)c * 16) = v;
+}
+
 __global__ __launch_bounds__(256) void cache_reset_kernel(cr_feature_cache c)
 {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -206,6 +219,24 @@ extern "C" cr_status cr_cache_fetch(const cr_feature_cache *cache, const void *s
     const int64_t max_dirty = max_n < cache->n_sets ? max_n : cache->n_sets;
     hipLaunchKernelGGL(cache_resolve_kernel, dim3((unsigned)ceil_div(max_dirty, 4)), dim3(256), 0, s, a);
     hipLaunchKernelGGL(cache_fill_kernel, dim3((unsigned)ceil_div((int64_t)max_n * (cache->row_bytes / 16), 256)), dim3(256), 0, s, a);
+    CR_LAUNCH_CHECK();
+    return CR_OK;
+}
+
+extern "C" cr_status cr_stage_rows(const void *store, int64_t store_ld_bytes, const int32_t *ids, const int32_t *hdr,
+                                   int32_t hdr_word, int32_t max_n, void *rows_out, int32_t row_bytes, void *stream)
+{
+    CR_REQUIRE(store != nullptr && aligned16(store), CR_ERR_INVALID_ARG, "store must be a 16-byte aligned pointer the GPU can read");
+    CR_REQUIRE(row_bytes >= 16 && row_bytes % 16 == 0, CR_ERR_INVALID_ARG, "row_bytes = %d must be a positive multiple of 16", row_bytes);
+    CR_REQUIRE(store_ld_bytes >= row_bytes && store_ld_bytes % 16 == 0, CR_ERR_INVALID_ARG,
+               "store_ld_bytes = %lld must be a multiple of 16 covering row_bytes = %d", (long long)store_ld_bytes, row_bytes);
+    CR_REQUIRE(ids && hdr && rows_out && aligned16(rows_out), CR_ERR_INVALID_ARG, "ids / hdr / rows_out must not be NULL (rows_out 16-byte aligned)");
+    CR_REQUIRE(hdr_word >= 0 && hdr_word < CR_HDR_WORDS, CR_ERR_INVALID_ARG, "hdr_word outside 0..%d", CR_HDR_WORDS - 1);
+    CR_REQUIRE(max_n >= 1, CR_ERR_INVALID_ARG, "max_n must be positive");
+    if (dry_run()) return CR_OK;
+    hipLaunchKernelGGL(stage_rows_kernel, dim3((unsigned)ceil_div((int64_t)max_n * (row_bytes / 16), 256)), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), static_cast<const char *>(store), store_ld_bytes, ids, hdr + hdr_word, max_n,
+                       static_cast<char *>(rows_out), row_bytes);
     CR_LAUNCH_CHECK();
     return CR_OK;
 }

@@ -21,7 +21,8 @@ from . import synth
 class Trainer:
     def __init__(self, workload: synth.Workload, group_size: int = 16, lr: float = 0.01,
                  weight_decay: float = 5e-4, seed: int = 0, device: str = "cuda", weights=None,
-                 relabel_input: bool = False, edge_classes: bool = True):
+                 relabel_input: bool = False, edge_classes: bool = True, host_features: bool = False,
+                 cache_rows: int = 0, cache_ways: int = 16):
         import torch
         self.torch = torch
         self.w = workload
@@ -34,6 +35,9 @@ class Trainer:
         # The layer-0 gather reads the feature table through per-edge global ids and the features take no
         # gradient, so nothing in a training step needs the input frontier de-duplicated or relabelled
         # (relabel_input=True asks for it anyway, e.g. to count the distinct input nodes of a batch).
+        # A feature store on the host (and the cache in front of it) works on the batch's distinct input nodes,
+        # so those set-ups do need the input frontier de-duplicated.
+        relabel_input = relabel_input or host_features or cache_rows > 0
         self.sample_flags = 0 if relabel_input else B.CR_SAMPLE_INPUT_GLOBAL_IDS
         up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(device)
         self.indptr = up(workload.indptr.astype(np.int64))
@@ -43,8 +47,17 @@ class Trainer:
         self.train_ids = up(workload.train_ids.astype(np.int32))
         feats = workload.features
         self.feat_dtype = B.CR_BF16 if feats.dtype == np.uint16 else B.CR_F32
-        self.table = up(feats.view(np.int16) if feats.dtype == np.uint16 else feats)
         self.ld_table = feats.shape[1]
+        self.row_bytes = feats.shape[1] * feats.dtype.itemsize
+        self.host_store = None
+        if host_features:      # the table stays in pinned host memory; kernels read it over the host link
+            self.host_store = B.HostBuffer(feats.shape, feats.dtype)
+            self.host_store.array[:] = feats
+            self.table = None
+            self.table_ptr = self.host_store.device_ptr
+        else:
+            self.table = up(feats.view(np.int16) if feats.dtype == np.uint16 else feats)
+            self.table_ptr = C.c_void_p(self.table.data_ptr())
         self.graph = B.make_graph(self.indptr, self.indices, self.comm, cfg.n_comm)
         if edge_classes:     # static per graph: one bit per adjacency entry, read by the biased selection
             self.edge_bits = B.cr_graph_edge_classes(self.graph)
@@ -91,6 +104,15 @@ class Trainer:
         self.agg[0] = self.agg0_bufs[0]
         self.gather0_events = []          # (start, stop) pairs around the layer-0 gather when timing is on
         self.time_gather0 = False
+        # software-managed cache of feature rows (set-associative LRU) and / or a staging area for the distinct
+        # input rows of one batch when the store is on the host
+        self.cache, self.cache_stamp, self.staged = None, 0, None
+        cap_src0 = self.blocks[0].cap_src
+        if cache_rows > 0:
+            assert self.row_bytes % 16 == 0
+            self.cache = B.FeatureCache(max(1, cache_rows // cache_ways), cache_ways, self.row_bytes, cap_src0, device)
+        elif host_features:
+            self.staged = torch.zeros((cap_src0, self.row_bytes), dtype=torch.uint8, device=device)
         self.stream_sample = torch.cuda.Stream(device=device)
         self.stream_gather = torch.cuda.Stream(device=device)
         self.stream_weights = torch.cuda.Stream(device=device)
@@ -127,8 +149,23 @@ class Trainer:
         if self.time_gather0:
             ev0, ev1 = self.torch.cuda.Event(enable_timing=True), self.torch.cuda.Event(enable_timing=True)
             ev0.record()
-        B.cr_gather_aggregate_fwd(blk, g, self.table, self.feat_dtype, self.ld_table, self.cfg.n_feat, True,
-                                  None, self.agg0_bufs[buf], self.self0_bufs[buf], lay.F_pad)
+        if self.cache is not None:
+            # look the batch's distinct input nodes up, bring the missing rows in, then gather from the cache's rows
+            # through the slots (a one-batch view of the block whose frontier array is the slot array)
+            self.cache.fetch(self.table_ptr, self.row_bytes, blk.src_ids_ptr(g), blk.hdr_ptr(g), B.CR_HDR_N_SRC, self.cache_stamp)
+            self.cache_stamp += 1
+            view = _one_batch_view(blk, g, self.cache.slot_out)
+            B.cr_gather_aggregate_fwd(view, 0, self.cache.rows, self.feat_dtype, self.ld_table, self.cfg.n_feat, True,
+                                      None, self.agg0_bufs[buf], self.self0_bufs[buf], lay.F_pad)
+        elif self.staged is not None:
+            # no cache: every distinct input row crosses the host link once, then a dense gather
+            B.cr_stage_rows(self.table_ptr, self.row_bytes, blk.src_ids_ptr(g), blk.hdr_ptr(g), B.CR_HDR_N_SRC, blk.cap_src,
+                            self.staged, self.row_bytes)
+            B.cr_gather_aggregate_fwd(blk, g, self.staged, self.feat_dtype, self.ld_table, self.cfg.n_feat, False,
+                                      None, self.agg0_bufs[buf], self.self0_bufs[buf], lay.F_pad)
+        else:
+            B.cr_gather_aggregate_fwd(blk, g, self.table_ptr, self.feat_dtype, self.ld_table, self.cfg.n_feat, True,
+                                      None, self.agg0_bufs[buf], self.self0_bufs[buf], lay.F_pad)
         if self.time_gather0:
             ev1.record()
             self.gather0_events.append((ev0, ev1))
@@ -387,6 +424,14 @@ class _BlockSetView:
 
     def __init__(self, c):
         self.c = c
+
+
+def _one_batch_view(b: B.BlockSet, g: int, frontier) -> _BlockSetView:
+    """Batch g of a block set as a block set of its own, with `frontier` (device int32[cap_src]) in place of src_ids."""
+    off = lambda t, stride: None if t is None else C.c_void_p(t.data_ptr() + 4 * g * stride)
+    c = B.cr_block_set(1, b.fanout, b.cap_dst, b.cap_src, b.cap_nnz, 0, off(b.hdr, B.CR_HDR_WORDS), B._ptr(frontier),
+                       off(b.indptr, b.cap_dst + 1), off(b.indices, b.cap_nnz), None, None, None)
+    return _BlockSetView(c)
 
 
 def _view_block_set(b: B.BlockSet, n_batches: int) -> _BlockSetView:

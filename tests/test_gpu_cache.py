@@ -78,3 +78,39 @@ def test_cache_over_host_memory():
     run_trace(torch, B, batches, 128, 16, np.array(host.array), max_n=1024, host_store=host)
     torch.cuda.synchronize()
     host.free()
+
+
+@pytest.mark.parametrize("host_features,cache_rows", [(False, 2048), (True, 0), (True, 4096)])
+def test_training_with_cache_or_host_store_changes_nothing(tiny_workload, host_features, cache_rows):
+    """Features from the resident table, from a host-resident store row by row, or through the cache: the same
+    weights bit for bit after a few steps; the cache's miss count equals the model's on the same frontiers."""
+    import torch
+    from paper_2504_18082_amd.trainer import Trainer
+    w = tiny_workload
+    steps, group = 6, 4
+    ref = Trainer(w, group_size=group, lr=0.05, seed=0, relabel_input=True)
+    tr = Trainer(w, group_size=group, lr=0.05, seed=0, host_features=host_features, cache_rows=cache_rows, cache_ways=8)
+    model = oracle.FeatureCacheModel(max(1, cache_rows // 8), 8) if cache_rows else None
+    ref.build_batches(oracle.COMM_RAND, 6, 2)
+    tr.build_batches(oracle.COMM_RAND, 6, 2)
+    done = 0
+    while done < steps:
+        n = min(group, steps - done)
+        ref.sample_group(done, n, 0.9, 2)
+        tr.sample_group(done, n, 0.9, 2)
+        hdrs = ref.headers()[0]
+        for g in range(n):
+            print(f"step {done + g} host={host_features} cache_rows={cache_rows}", flush=True)
+            ref.train_batch(g)
+            tr.train_batch(g)
+            if model is not None:
+                model.fetch(ref.blocks[0].src_ids[g, :hdrs[g][1]].cpu().numpy(), done + g)
+        done += n
+    torch.cuda.synchronize()
+    for a, b in zip(ref.layers, tr.layers):
+        assert torch.equal(a.W, b.W) and torch.equal(a.bias, b.bias)
+    assert torch.equal(ref.loss, tr.loss)
+    if model is not None:
+        q, m, u, status = tr.cache.stats()
+        assert (q, m, status) == (model.queries, model.misses, 0)
+        assert 0 < m < q                                       # consecutive community batches do hit
