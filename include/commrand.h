@@ -303,7 +303,8 @@ cr_status cr_count_correct(const int32_t *hdr, int32_t max_rows, const float *lo
  *   1. every distinct input node of the batch is looked up; a hit refreshes its row's stamp;
  *   2. the misses of a set, in the order the nodes appear in the batch, replace that set's rows in order of
  *      (stamp ascending, way ascending), never a row hit or filled in this batch (empty rows have stamp -1);
- *   3. misses that find no such row are copied to a per-batch overflow area behind the cached rows instead.
+ *   3. misses that find no such row are copied to a per-batch overflow area behind the cached rows instead (the
+ *      node at position i of the batch to overflow row i).
  * After a fetch, rows[slot_out[i]] holds the feature row of ids[i] for every i, so the feature gather can read the
  * cache's row array through slot_out in place of the store through the node ids.  All arrays are the caller's. */
 #define CR_CACHE_MAX_WAYS 64
@@ -321,13 +322,11 @@ typedef struct {
     int32_t *set_list;  /* device int32[n_sets][CR_CACHE_LIST_CAP]: scratch */
     int32_t *counters;  /* device int32[8], cumulative since cr_cache_reset: [0] look-ups, [1] misses, [2] misses that
                            went to the overflow area, [3] nonzero = a set took more than CR_CACHE_LIST_CAP misses in
-                           one batch or the overflow area was too small (results invalid); [4..7] scratch */
+                           one batch (results invalid); [4..7] unused */
 } cr_feature_cache;
 
 /* Empties the cache and zeroes its scratch and counters. */
 cr_status cr_cache_reset(const cr_feature_cache *cache, void *stream);
-
-cr_status cr_cache_fetch_workspace_bytes(int32_t max_n, size_t *bytes /*host*/);
 
 /* One batch's look-ups and replacements.
  *   store     : the feature store, [n_nodes][store_ld_bytes] bytes, readable by the GPU: device memory, or host memory
@@ -335,11 +334,10 @@ cr_status cr_cache_fetch_workspace_bytes(int32_t max_n, size_t *bytes /*host*/);
  *   ids       : device int32[>= n]: the batch's distinct input nodes; n = min(hdr[hdr_word], max_n) read on the device
  *               (a block header with hdr_word = CR_HDR_N_SRC, or any device int32)
  *   stamp     : the batch's stamp, increasing from batch to batch, >= 0
- *   slot_out  : device int32[max_n]: row of `rows` that holds ids[i]'s features
- *   ws        : device workspace of cr_cache_fetch_workspace_bytes(max_n) bytes */
+ *   slot_out  : device int32[max_n]: row of `rows` that holds ids[i]'s features */
 cr_status cr_cache_fetch(const cr_feature_cache *cache, const void *store, int64_t store_ld_bytes,
                          const int32_t *ids, const int32_t *hdr, int32_t hdr_word, int32_t max_n,
-                         int32_t stamp, int32_t *slot_out, void *ws, size_t ws_bytes, void *stream);
+                         int32_t stamp, int32_t *slot_out, void *stream);
 
 /* The store without a cache: copies the rows of the batch's distinct input nodes, rows_out[i] = store[ids[i]] for
  * i < n = min(hdr[hdr_word], max_n), each row read once (what a unified-addressing gather of the input features

@@ -32,7 +32,7 @@ EXPORTS = [
     "cr_sage_padded_dims", "cr_sage_refresh_shadows", "cr_sage_linear_fwd",
     "cr_sage_linear_bwd_workspace_bytes", "cr_sage_linear_bwd", "cr_sage_linear_bwd_input", "cr_softmax_xent",
     "cr_count_correct",
-    "cr_cache_reset", "cr_cache_fetch_workspace_bytes", "cr_cache_fetch", "cr_stage_rows", "cr_host_alloc", "cr_host_free",
+    "cr_cache_reset", "cr_cache_fetch", "cr_stage_rows", "cr_host_alloc", "cr_host_free",
 ]
 
 
@@ -122,8 +122,7 @@ def lib():
         L.cr_softmax_xent.argtypes = [vp, i32, vp, i64, i32, vp, vp, vp, vp, vp, vp, vp]
         L.cr_count_correct.argtypes = [vp, i32, vp, i64, i32, vp, vp, vp, vp]
         L.cr_cache_reset.argtypes = [C.POINTER(cr_feature_cache), vp]
-        L.cr_cache_fetch_workspace_bytes.argtypes = [i32, C.POINTER(C.c_size_t)]
-        L.cr_cache_fetch.argtypes = [C.POINTER(cr_feature_cache), vp, i64, vp, vp, i32, i32, i32, vp, vp, C.c_size_t, vp]
+        L.cr_cache_fetch.argtypes = [C.POINTER(cr_feature_cache), vp, i64, vp, vp, i32, i32, i32, vp, vp]
         L.cr_stage_rows.argtypes = [vp, i64, vp, vp, i32, i32, vp, i32, vp]
         L.cr_host_alloc.argtypes = [C.c_size_t, C.POINTER(vp), C.POINTER(vp)]
         L.cr_host_free.argtypes = [vp]
@@ -375,9 +374,6 @@ class FeatureCache:
         self.rows = torch.zeros((slots + max_batch_nodes, row_bytes), dtype=torch.uint8, device=device)
         self.set_count, self.set_list, self.counters = i32(n_sets), i32(n_sets * CR_CACHE_LIST_CAP), i32(8)
         self.slot_out = i32(max_batch_nodes)
-        n = C.c_size_t(0)
-        _check(lib().cr_cache_fetch_workspace_bytes(max_batch_nodes, C.byref(n)))
-        self.ws = torch.empty(n.value, dtype=torch.uint8, device=device)
         self.c = cr_feature_cache(n_sets, ways, row_bytes, max_batch_nodes, _ptr(self.keys), _ptr(self.stamps), _ptr(self.rows),
                                   _ptr(self.set_count), _ptr(self.set_list), _ptr(self.counters))
         self.reset()
@@ -388,7 +384,7 @@ class FeatureCache:
     def fetch(self, store_ptr, store_ld_bytes, ids_ptr, hdr_ptr, hdr_word, stamp, stream=None):
         """store_ptr / ids_ptr / hdr_ptr: raw addresses (ctypes.c_void_p) the GPU can read."""
         _check(lib().cr_cache_fetch(C.byref(self.c), store_ptr, store_ld_bytes, ids_ptr, hdr_ptr, hdr_word, self.max_n, stamp,
-                                    _ptr(self.slot_out), _ptr(self.ws), self.ws.numel(), _stream(stream)))
+                                    _ptr(self.slot_out), _stream(stream)))
 
     def stats(self):
         """(look-ups, misses, misses served from the overflow area, status) since the last reset."""

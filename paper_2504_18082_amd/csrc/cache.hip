@@ -6,7 +6,7 @@
 
 namespace cr {
 
-constexpr int CNT_QUERIES = 0, CNT_MISSES = 1, CNT_UNCACHED = 2, CNT_STATUS = 3, CNT_DIRTY = 4, CNT_FILL = 5, CNT_OVER = 6;
+constexpr int CNT_QUERIES = 0, CNT_MISSES = 1, CNT_UNCACHED = 2, CNT_STATUS = 3;
 
 struct CacheArgs {
     cr_feature_cache c;
@@ -17,27 +17,15 @@ struct CacheArgs {
     int32_t max_n;
     int32_t stamp;
     int32_t *slot_out;
-    int32_t *dirty;       // [max_n] sets that took a miss in this batch
-    int32_t *fill_src;    // [max_n] node id of every row to copy
-    int32_t *fill_dst;    // [max_n] its destination row
 };
 
-__global__ void cache_begin_kernel(CacheArgs a)
-{
-    if (threadIdx.x == 0 && blockIdx.x == 0) {
-        const int n = min(max(*a.n_ptr, 0), a.max_n);
-        a.c.counters[CNT_QUERIES] += n;
-        a.c.counters[CNT_DIRTY] = 0;
-        a.c.counters[CNT_FILL] = 0;
-        a.c.counters[CNT_OVER] = 0;
-    }
-}
-
-// GW lanes (a power of two >= ways) look one node up: lane w compares way w
+// GW lanes (a power of two >= ways) look one node up: lane w compares way w.  A miss is appended to its set's
+// list (one atomic per miss, on the set's own counter).
 template <int GW>
 __global__ __launch_bounds__(256) void cache_lookup_kernel(CacheArgs a)
 {
     const int n = min(max(*a.n_ptr, 0), a.max_n);
+    if (blockIdx.x == 0 && threadIdx.x == 0) a.c.counters[CNT_QUERIES] += n;
     const int i = (int)(blockIdx.x * (256 / GW) + threadIdx.x / GW);
     if (i >= n) return;
     const int w = threadIdx.x % GW, lane = lane_id();
@@ -56,73 +44,91 @@ __global__ __launch_bounds__(256) void cache_lookup_kernel(CacheArgs a)
         const int r = atomicAdd(&a.c.set_count[set], 1);
         if (r < CR_CACHE_LIST_CAP) a.c.set_list[(int64_t)set * CR_CACHE_LIST_CAP + r] = i;
         else atomicOr(&a.c.counters[CNT_STATUS], 1);
-        if (r == 0) a.dirty[atomicAdd(&a.c.counters[CNT_DIRTY], 1)] = set;
     }
 }
 
-// One wave per set that took misses: the misses in batch order take the set's rows in (stamp, way) order,
-// except rows used in this batch; what is left over goes to the overflow area.
+// Replacement and row copies.  A fixed grid of waves walks the sets, 64 set counters per load; for a set that took
+// misses, the misses in batch order take the set's rows in (stamp, way) order, except rows used in this batch; what
+// is left over goes to the overflow area at the node's position in the batch.  The wave then copies its sets'
+// missing rows from the store, 16 bytes per lane.  Counters are accumulated per wave and added once.
 __global__ __launch_bounds__(256) void cache_resolve_kernel(CacheArgs a)
 {
     __shared__ int way_of_rank[4][WAVE];
-    const int d = (int)(blockIdx.x * 4 + threadIdx.x / WAVE);
-    if (d >= a.c.counters[CNT_DIRTY]) return;
     const int lane = lane_id(), wv = threadIdx.x / WAVE;
-    const int set = a.dirty[d];
-    const int m_all = a.c.set_count[set];
-    const int m = min(m_all, (int)CR_CACHE_LIST_CAP);
-    const int64_t s0 = (int64_t)set * a.c.ways;
-
-    const int pos = lane < m ? a.c.set_list[(int64_t)set * CR_CACHE_LIST_CAP + lane] : 0x7FFFFFFF;
-    int miss_rank = 0;
-    for (int j = 0; j < m; ++j) miss_rank += __builtin_amdgcn_readlane(pos, j) < pos ? 1 : 0;
-
-    const int st = lane < a.c.ways ? a.c.stamps[s0 + lane] : a.stamp;
-    const bool elig = lane < a.c.ways && st != a.stamp;
-    int way_rank = 0;
-    for (int j = 0; j < a.c.ways; ++j) {
-        const int sj = __builtin_amdgcn_readlane(st, j);
-        way_rank += (sj != a.stamp && (sj < st || (sj == st && j < lane))) ? 1 : 0;
-    }
-    const int n_avail = __popcll(__ballot(elig));
-    if (elig) way_of_rank[wv][way_rank] = lane;
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-
-    if (lane < m) {
-        const int32_t id = a.ids[pos];
-        int32_t slot;
-        if (miss_rank < n_avail) {
-            slot = (int32_t)(s0 + way_of_rank[wv][miss_rank]);
-            a.c.keys[slot] = id;
-            a.c.stamps[slot] = a.stamp;
-        } else {
-            const int o = atomicAdd(&a.c.counters[CNT_OVER], 1);
-            if (o >= a.c.n_overflow) atomicOr(&a.c.counters[CNT_STATUS], 2);
-            slot = a.c.n_sets * a.c.ways + min(o, a.c.n_overflow - 1);
-        }
-        a.slot_out[pos] = slot;
-        const int f = atomicAdd(&a.c.counters[CNT_FILL], 1);
-        a.fill_src[f] = id;
-        a.fill_dst[f] = slot;
-    }
-    if (lane == 0) {
-        a.c.set_count[set] = 0;
-        atomicAdd(&a.c.counters[CNT_MISSES], m_all);
-    }
-}
-
-// copies the missing rows from the store, 16 bytes per thread
-__global__ __launch_bounds__(256) void cache_fill_kernel(CacheArgs a)
-{
+    const int n_waves = gridDim.x * 4;
+    const int wave_id = blockIdx.x * 4 + wv;
     const int chunks = a.c.row_bytes / 16;
-    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    const int64_t f = gid / chunks;
-    const int c = (int)(gid % chunks);
-    const int n_fill = a.c.counters[CNT_FILL];
-    if (gid == 0) a.c.counters[CNT_UNCACHED] += a.c.counters[CNT_OVER];
-    if (f >= n_fill) return;
-    const uint4 v = *reinterpret_cast<const uint4 *>(a.store + (int64_t)a.fill_src[f] * a.store_ld + (int64_t)c * 16);
-    *reinterpret_cast<uint4 *>(static_cast<char *>(a.c.rows) + (int64_t)a.fill_dst[f] * a.c.row_bytes + (int64_t)c * 16) = v;
+    const int n_slots = a.c.n_sets * a.c.ways;
+    int misses = 0, uncached = 0;
+    for (int base = wave_id * WAVE; base < a.c.n_sets; base += n_waves * WAVE) {
+        const int my_cnt = base + lane < a.c.n_sets ? a.c.set_count[base + lane] : 0;
+        uint64_t dirty = __ballot(my_cnt > 0);
+        while (dirty) {
+            const int j = __ffsll((long long)dirty) - 1;
+            dirty &= dirty - 1;
+            const int set = base + j;
+            const int m_all = __builtin_amdgcn_readlane(my_cnt, j);
+            const int m = min(m_all, (int)CR_CACHE_LIST_CAP);
+            const int64_t s0 = (int64_t)set * a.c.ways;
+
+            const int pos = lane < m ? a.c.set_list[(int64_t)set * CR_CACHE_LIST_CAP + lane] : 0x7FFFFFFF;
+            int miss_rank = 0;
+            for (int t = 0; t < m; ++t) miss_rank += __builtin_amdgcn_readlane(pos, t) < pos ? 1 : 0;
+
+            const int st = lane < a.c.ways ? a.c.stamps[s0 + lane] : a.stamp;
+            const bool elig = lane < a.c.ways && st != a.stamp;
+            int way_rank = 0;
+            for (int t = 0; t < a.c.ways; ++t) {
+                const int sj = __builtin_amdgcn_readlane(st, t);
+                way_rank += (sj != a.stamp && (sj < st || (sj == st && t < lane))) ? 1 : 0;
+            }
+            const int n_avail = __popcll(__ballot(elig));
+            if (elig) way_of_rank[wv][way_rank] = lane;
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+
+            int32_t id = 0, slot = 0;
+            if (lane < m) {
+                id = a.ids[pos];
+                if (miss_rank < n_avail) {
+                    slot = (int32_t)(s0 + way_of_rank[wv][miss_rank]);
+                    a.c.keys[slot] = id;
+                    a.c.stamps[slot] = a.stamp;
+                } else {
+                    slot = n_slots + pos;                 // overflow area: one row per batch position
+                }
+                a.slot_out[pos] = slot;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // way_of_rank is reused for the next set
+            if (lane == 0) a.c.set_count[set] = 0;
+            misses += m_all;
+            uncached += m - min(m, n_avail);
+
+            // copy the m rows: 64 / chunks rows per step when a row is at most 64 lanes wide
+            if (chunks <= WAVE) {
+                const int per = WAVE / chunks;
+                for (int r0 = 0; r0 < m; r0 += per) {
+                    const int r = r0 + lane / chunks, c = lane % chunks;
+                    const int32_t rid = __shfl(id, r), rslot = __shfl(slot, r);
+                    if (lane < per * chunks && r < m) {
+                        const uint4 v = *reinterpret_cast<const uint4 *>(a.store + (int64_t)rid * a.store_ld + (int64_t)c * 16);
+                        *reinterpret_cast<uint4 *>(static_cast<char *>(a.c.rows) + (int64_t)rslot * a.c.row_bytes + (int64_t)c * 16) = v;
+                    }
+                }
+            } else {
+                for (int r = 0; r < m; ++r) {
+                    const int32_t rid = __builtin_amdgcn_readlane(id, r), rslot = __builtin_amdgcn_readlane(slot, r);
+                    for (int c = lane; c < chunks; c += WAVE) {
+                        const uint4 v = *reinterpret_cast<const uint4 *>(a.store + (int64_t)rid * a.store_ld + (int64_t)c * 16);
+                        *reinterpret_cast<uint4 *>(static_cast<char *>(a.c.rows) + (int64_t)rslot * a.c.row_bytes + (int64_t)c * 16) = v;
+                    }
+                }
+            }
+        }
+    }
+    if (lane == 0 && misses) {
+        atomicAdd(&a.c.counters[CNT_MISSES], misses);
+        if (uncached) atomicAdd(&a.c.counters[CNT_UNCACHED], uncached);
+    }
 }
 
 __global__ __launch_bounds__(256) void stage_rows_kernel(const char *__restrict__ store, int64_t store_ld, const int32_t *__restrict__ ids,
@@ -176,20 +182,9 @@ extern "C" cr_status cr_cache_reset(const cr_feature_cache *cache, void *stream)
     return CR_OK;
 }
 
-extern "C" cr_status cr_cache_fetch_workspace_bytes(int32_t max_n, size_t *bytes)
-{
-    CR_REQUIRE(bytes != nullptr && max_n >= 1, CR_ERR_INVALID_ARG, "bytes must not be NULL and max_n must be positive");
-    Carver c(nullptr);
-    c.take<int32_t>((size_t)max_n);
-    c.take<int32_t>((size_t)max_n);
-    c.take<int32_t>((size_t)max_n);
-    *bytes = c.bytes();
-    return CR_OK;
-}
-
 extern "C" cr_status cr_cache_fetch(const cr_feature_cache *cache, const void *store, int64_t store_ld_bytes,
                                     const int32_t *ids, const int32_t *hdr, int32_t hdr_word, int32_t max_n,
-                                    int32_t stamp, int32_t *slot_out, void *ws, size_t ws_bytes, void *stream)
+                                    int32_t stamp, int32_t *slot_out, void *stream)
 {
     cr_status st = check_cache(cache);
     if (st != CR_OK) return st;
@@ -200,25 +195,18 @@ extern "C" cr_status cr_cache_fetch(const cr_feature_cache *cache, const void *s
     CR_REQUIRE(hdr_word >= 0 && hdr_word < CR_HDR_WORDS, CR_ERR_INVALID_ARG, "hdr_word outside 0..%d", CR_HDR_WORDS - 1);
     CR_REQUIRE(max_n >= 1 && stamp >= 0, CR_ERR_INVALID_ARG, "max_n must be positive and stamp non-negative");
     CR_REQUIRE(cache->n_overflow >= max_n, CR_ERR_CAPACITY, "overflow area of %d rows, %d needed (max_n)", cache->n_overflow, max_n);
-    Carver c(ws);
     CacheArgs a;
     a.c = *cache; a.store = static_cast<const char *>(store); a.store_ld = store_ld_bytes; a.ids = ids; a.n_ptr = hdr + hdr_word;
     a.max_n = max_n; a.stamp = stamp; a.slot_out = slot_out;
-    a.dirty = c.take<int32_t>((size_t)max_n);
-    a.fill_src = c.take<int32_t>((size_t)max_n);
-    a.fill_dst = c.take<int32_t>((size_t)max_n);
-    CR_REQUIRE(ws != nullptr && aligned16(ws), CR_ERR_INVALID_ARG, "workspace must be a 16-byte aligned device pointer");
-    CR_REQUIRE(ws_bytes >= c.bytes(), CR_ERR_CAPACITY, "workspace of %zu bytes, %zu needed", ws_bytes, c.bytes());
     if (dry_run()) return CR_OK;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
-    hipLaunchKernelGGL(cache_begin_kernel, dim3(1), dim3(64), 0, s, a);
     if (cache->ways <= 16) hipLaunchKernelGGL(cache_lookup_kernel<16>, dim3((unsigned)ceil_div(max_n, 16)), dim3(256), 0, s, a);
     else if (cache->ways <= 32) hipLaunchKernelGGL(cache_lookup_kernel<32>, dim3((unsigned)ceil_div(max_n, 8)), dim3(256), 0, s, a);
     else hipLaunchKernelGGL(cache_lookup_kernel<64>, dim3((unsigned)ceil_div(max_n, 4)), dim3(256), 0, s, a);
-    const int64_t max_dirty = max_n < cache->n_sets ? max_n : cache->n_sets;
-    hipLaunchKernelGGL(cache_resolve_kernel, dim3((unsigned)ceil_div(max_dirty, 4)), dim3(256), 0, s, a);
-    hipLaunchKernelGGL(cache_fill_kernel, dim3((unsigned)ceil_div((int64_t)max_n * (cache->row_bytes / 16), 256)), dim3(256), 0, s, a);
+    int64_t blocks = ceil_div(cache->n_sets, 4 * WAVE);
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(cache_resolve_kernel, dim3((unsigned)blocks), dim3(256), 0, s, a);
     CR_LAUNCH_CHECK();
     return CR_OK;
 }

@@ -115,8 +115,10 @@ def bf16_bits_to_float(b: np.ndarray) -> np.ndarray:
     return (b.astype(np.uint32) << 16).view(np.float32)
 
 
-def make_graph(cfg: WorkloadConfig, seed: int = 0):
+def make_graph(cfg: WorkloadConfig, seed: int = 0, verbose: bool = False):
     """Degree-corrected planted-partition graph.  Returns (indptr, indices, comm, comm_ptr, intra)."""
+    import sys
+    say = (lambda msg: print(f"# synth: {msg}", file=sys.stderr, flush=True)) if verbose else (lambda msg: None)
     rng = np.random.default_rng([seed, 0xC0DE, 1])
     N, E = cfg.n_nodes, cfg.n_edges_undirected
     sizes = _community_sizes(N, cfg.n_comm, cfg.comm_size_exponent)
@@ -154,7 +156,9 @@ def make_graph(cfg: WorkloadConfig, seed: int = 0):
         n_intra_kept += int(same[keep].sum())
         keys.append(a * N + b)
         keys.append(b * N + a)
+        say(f"edges drawn {start + m} / {E}")
     key = np.unique(np.concatenate(keys))
+    say(f"{key.size} directed entries after symmetrising and de-duplicating")
     del keys
     rows = key // N
     indices = (key - rows * N).astype(np.int32)
@@ -164,10 +168,10 @@ def make_graph(cfg: WorkloadConfig, seed: int = 0):
     return indptr, indices, comm, comm_ptr, intra
 
 
-def make_workload(cfg: WorkloadConfig | str, seed: int = 0, with_features: bool = True) -> Workload:
+def make_workload(cfg: WorkloadConfig | str, seed: int = 0, with_features: bool = True, verbose: bool = False) -> Workload:
     if isinstance(cfg, str):
         cfg = CONFIGS[cfg]
-    indptr, indices, comm, comm_ptr, intra = make_graph(cfg, seed)
+    indptr, indices, comm, comm_ptr, intra = make_graph(cfg, seed, verbose)
     N = cfg.n_nodes
     rng = np.random.default_rng([seed, 0xFEA7, 2])
     ld = (cfg.n_feat + 3) // 4 * 4

@@ -209,12 +209,8 @@ def test_feature_cache_validation():
     def cache(**kw):
         return B.cr_feature_cache(kw.get("n_sets", 64), kw.get("ways", 16), kw.get("row_bytes", 256), kw.get("n_overflow", 1000),
                                   FAKE, FAKE, kw.get("rows", FAKE), FAKE, FAKE, FAKE)
-    need = C.c_size_t(0)
-    assert lib.cr_cache_fetch_workspace_bytes(1000, C.byref(need)) == B.CR_OK and need.value >= 3 * 4 * 1000
-    assert lib.cr_cache_fetch_workspace_bytes(0, C.byref(need)) == B.CR_ERR_INVALID_ARG
     fetch = lambda c, **kw: lib.cr_cache_fetch(C.byref(c), vp(kw.get("store", FAKE)), kw.get("ld", 256), vp(), vp(), kw.get("word", 1),
-                                               kw.get("max_n", 1000), kw.get("stamp", 0), vp(), vp(), kw.get("ws", need.value), None)
-    lib.cr_cache_fetch_workspace_bytes(1000, C.byref(need))
+                                               kw.get("max_n", 1000), kw.get("stamp", 0), vp(), None)
     assert lib.cr_cache_reset(C.byref(cache()), None) == B.CR_OK
     assert fetch(cache()) == B.CR_OK
     assert fetch(cache(ways=65)) == B.CR_ERR_INVALID_ARG
@@ -227,7 +223,6 @@ def test_feature_cache_validation():
     assert fetch(cache(), word=8) == B.CR_ERR_INVALID_ARG
     assert fetch(cache(), stamp=-1) == B.CR_ERR_INVALID_ARG
     assert fetch(cache(), store=None) == B.CR_ERR_INVALID_ARG
-    assert fetch(cache(), ws=need.value - 1) == B.CR_ERR_CAPACITY
     h, d = C.c_void_p(), C.c_void_p()
     assert lib.cr_host_alloc(0, C.byref(h), C.byref(d)) == B.CR_ERR_INVALID_ARG
     assert lib.cr_host_alloc(1024, C.byref(h), C.byref(d)) == B.CR_OK   # dry run: validated, nothing allocated
