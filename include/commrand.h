@@ -227,13 +227,18 @@ cr_status cr_gather_aggregate_bwd(const cr_block_set *blocks, int32_t g, const v
                                   const void *relu_out, int32_t relu_dtype, int64_t ld_relu, float *d_src,
                                   uint16_t *d_src_bf16, int64_t ld_bf16, void *stream);
 
-/* One GraphSAGE layer's parameters.  F_pad = F_in rounded up to 32, N_pad = F_out rounded up to 64. */
+/* One layer's dense parameters.  F_pad = F_in rounded up to 32, N_pad = F_out rounded up to 64.
+ * n_operands = 2: GraphSAGE, Z = H_self W_self + Agg W_neigh + b;  n_operands = 1: one aggregated input (GCN,
+ * Section 6.4), Z = Agg W + b: every h_self / d_self argument below must then be NULL and the [.. 2*F ..] shapes
+ * read [.. F ..]. */
 typedef struct {
     int32_t F_in, F_out;
-    float *W;          /* device float [2*F_in][F_out]: rows 0..F_in-1 = W_self, F_in..2F_in-1 = W_neigh (master) */
+    int32_t n_operands; /* 1 or 2 */
+    int32_t reserved;
+    float *W;          /* device float [n_operands*F_in][F_out]: rows 0..F_in-1 = W_self, F_in..2F_in-1 = W_neigh (master) */
     float *bias;       /* device float [N_pad] (entries >= F_out stay 0) */
-    uint16_t *W_bf16;  /* device bf16 [2*F_pad][N_pad], zero padded shadow of W (row F_pad+k = W_neigh row k) */
-    uint16_t *Wt_bf16; /* device bf16 [N_pad][2*F_pad], its transpose */
+    uint16_t *W_bf16;  /* device bf16 [n_operands*F_pad][N_pad], zero padded shadow of W (row F_pad+k = W_neigh row k) */
+    uint16_t *Wt_bf16; /* device bf16 [N_pad][n_operands*F_pad], its transpose */
 } cr_sage_layer;
 
 cr_status cr_sage_padded_dims(int32_t F_in, int32_t F_out, int32_t *F_pad, int32_t *N_pad);

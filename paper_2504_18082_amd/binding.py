@@ -77,8 +77,8 @@ class cr_sample_cfg(C.Structure):
 
 
 class cr_sage_layer(C.Structure):
-    _fields_ = [("F_in", C.c_int32), ("F_out", C.c_int32), ("W", C.c_void_p), ("bias", C.c_void_p),
-                ("W_bf16", C.c_void_p), ("Wt_bf16", C.c_void_p)]
+    _fields_ = [("F_in", C.c_int32), ("F_out", C.c_int32), ("n_operands", C.c_int32), ("reserved", C.c_int32),
+                ("W", C.c_void_p), ("bias", C.c_void_p), ("W_bf16", C.c_void_p), ("Wt_bf16", C.c_void_p)]
 
 
 _lib = None
@@ -303,19 +303,21 @@ def cr_sage_padded_dims(F_in, F_out):
 
 
 class SageLayer:
-    """Device storage of one layer's parameters: float master + two bf16 shadows."""
+    """Device storage of one layer's parameters: float master + two bf16 shadows.  n_operands = 2: GraphSAGE
+    (W = [W_self; W_neigh]); 1: a single aggregated input (GCN)."""
 
-    def __init__(self, W_host, b_host, device="cuda"):
+    def __init__(self, W_host, b_host, device="cuda", n_operands=2):
         import torch
         F2, F_out = W_host.shape
-        self.F_in, self.F_out = F2 // 2, F_out
+        self.n_operands = n_operands
+        self.F_in, self.F_out = F2 // n_operands, F_out
         self.F_pad, self.N_pad = cr_sage_padded_dims(self.F_in, F_out)
         self.W = torch.from_numpy(W_host).to(device=device, dtype=torch.float32).contiguous()
         self.bias = torch.zeros(self.N_pad, dtype=torch.float32, device=device)
         self.bias[:F_out] = torch.from_numpy(b_host).to(device)
-        self.W_bf16 = torch.zeros((2 * self.F_pad, self.N_pad), dtype=torch.int16, device=device)
-        self.Wt_bf16 = torch.zeros((self.N_pad, 2 * self.F_pad), dtype=torch.int16, device=device)
-        self.c = cr_sage_layer(self.F_in, self.F_out, _ptr(self.W), _ptr(self.bias), _ptr(self.W_bf16),
+        self.W_bf16 = torch.zeros((n_operands * self.F_pad, self.N_pad), dtype=torch.int16, device=device)
+        self.Wt_bf16 = torch.zeros((self.N_pad, n_operands * self.F_pad), dtype=torch.int16, device=device)
+        self.c = cr_sage_layer(self.F_in, self.F_out, n_operands, 0, _ptr(self.W), _ptr(self.bias), _ptr(self.W_bf16),
                                _ptr(self.Wt_bf16))
 
     def refresh(self, stream=None):

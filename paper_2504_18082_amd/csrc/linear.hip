@@ -390,7 +390,7 @@ struct SgdArgs {
     const int32_t *hdr;
     int32_t max_rows, n_splits;
     const float *partial;
-    int32_t F_in, F_out, F_pad, N_pad;
+    int32_t F_in, F_out, F_pad, N_pad, n_op;
     float *W, *bias;
     uint16_t *W_bf16, *Wt_bf16;
     float lr, wd;
@@ -405,7 +405,7 @@ __global__ __launch_bounds__(256) void sgd_reduce_kernel(SgdArgs a)
     const int M = min(a.hdr[CR_HDR_N_DST], a.max_rows);
     const int rows_per_split = rows_per_split_for(M, a.n_splits);
     const int active = min(a.n_splits, (M + rows_per_split - 1) / rows_per_split);
-    const int K2 = 2 * a.F_pad;
+    const int K2 = a.n_op * a.F_pad;
     const int nq = a.N_pad / 4;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t q = (int64_t)blockIdx.x * 64 + lane;             // quadruple index over (K2 + 1) rows of nq quadruples
@@ -464,10 +464,10 @@ __global__ __launch_bounds__(256) void sgd_reduce_kernel(SgdArgs a)
         make_uint2((uint32_t)wb[0] | ((uint32_t)wb[1] << 16), (uint32_t)wb[2] | ((uint32_t)wb[3] << 16));
 }
 
-__global__ __launch_bounds__(256) void refresh_shadows_kernel(const float *W, int F_in, int F_out, int F_pad, int N_pad,
+__global__ __launch_bounds__(256) void refresh_shadows_kernel(const float *W, int F_in, int F_out, int F_pad, int N_pad, int n_op,
                                                               uint16_t *W_bf16, uint16_t *Wt_bf16)
 {
-    const int K2 = 2 * F_pad;
+    const int K2 = n_op * F_pad;
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= (int64_t)K2 * N_pad) return;
     const int k2 = (int)(idx / N_pad), n = (int)(idx % N_pad);
@@ -559,9 +559,9 @@ __global__ __launch_bounds__(256) void count_correct_kernel(const int32_t *hdr, 
     }
 }
 
-static void split_plan(int F_pad, int N_pad, int max_rows, int &rows_per_split, int &n_splits)
+static void split_plan(int F_pad, int N_pad, int n_op, int max_rows, int &rows_per_split, int &n_splits)
 {
-    const int tiles = (int)(2 * ceil_div(F_pad, 128) * ceil_div(N_pad, 128));
+    const int tiles = (int)(n_op * ceil_div(F_pad, 128) * ceil_div(N_pad, 128));
     int target = 768 / tiles;
     if (target < 1) target = 1;
     if (target > 128) target = 128;
@@ -580,6 +580,7 @@ static cr_status check_layer(const cr_sage_layer *L, int &F_pad, int &N_pad)
     CR_REQUIRE(L != nullptr, CR_ERR_INVALID_ARG, "layer is NULL");
     CR_REQUIRE(L->F_in >= 1 && L->F_in <= 8192 && L->F_out >= 1 && L->F_out <= 8192, CR_ERR_INVALID_ARG,
                "layer dims (%d, %d) outside 1..8192", L->F_in, L->F_out);
+    CR_REQUIRE(L->n_operands == 1 || L->n_operands == 2, CR_ERR_INVALID_ARG, "layer n_operands = %d must be 1 or 2", L->n_operands);
     CR_REQUIRE(L->W && L->bias && L->W_bf16 && L->Wt_bf16, CR_ERR_INVALID_ARG, "layer has a NULL array");
     CR_REQUIRE(aligned16(L->W) && aligned16(L->bias) && aligned16(L->W_bf16) && aligned16(L->Wt_bf16), CR_ERR_INVALID_ARG,
                "layer arrays must be 16-byte aligned");
@@ -603,9 +604,9 @@ extern "C" cr_status cr_sage_refresh_shadows(const cr_sage_layer *layer, void *s
     cr_status st = check_layer(layer, F_pad, N_pad);
     if (st != CR_OK) return st;
     if (dry_run()) return CR_OK;
-    const int64_t n = 2ll * F_pad * N_pad;
+    const int64_t n = (int64_t)layer->n_operands * F_pad * N_pad;
     hipLaunchKernelGGL(refresh_shadows_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, static_cast<hipStream_t>(stream),
-                       layer->W, layer->F_in, layer->F_out, F_pad, N_pad, layer->W_bf16, layer->Wt_bf16);
+                       layer->W, layer->F_in, layer->F_out, F_pad, N_pad, layer->n_operands, layer->W_bf16, layer->Wt_bf16);
     CR_LAUNCH_CHECK();
     return CR_OK;
 }
@@ -618,13 +619,15 @@ extern "C" cr_status cr_sage_linear_fwd(const cr_sage_layer *layer, const int32_
     cr_status st = check_layer(layer, F_pad, N_pad);
     if (st != CR_OK) return st;
     CR_REQUIRE(hdr != nullptr && max_rows >= 1, CR_ERR_INVALID_ARG, "hdr must not be NULL and max_rows must be positive");
-    CR_REQUIRE(h_self && agg && aligned16(h_self) && aligned16(agg), CR_ERR_INVALID_ARG, "h_self / agg must be 16-byte aligned device pointers");
+    const int n_op = layer->n_operands;
+    CR_REQUIRE(agg && aligned16(h_self) && aligned16(agg), CR_ERR_INVALID_ARG, "h_self / agg must be 16-byte aligned device pointers");
+    CR_REQUIRE((h_self != nullptr) == (n_op == 2), CR_ERR_INVALID_ARG, "h_self must be given for a two-operand layer and NULL for a one-operand layer");
     CR_REQUIRE(ld_in >= F_pad && ld_in % 8 == 0, CR_ERR_INVALID_ARG, "ld_in = %lld must be a multiple of 8 and >= %d", (long long)ld_in, F_pad);
     CR_REQUIRE(out || out_bf16, CR_ERR_INVALID_ARG, "no output requested");
     CR_REQUIRE(aligned16(out) && aligned16(out_bf16), CR_ERR_INVALID_ARG, "outputs must be 16-byte aligned");
     if (dry_run()) return CR_OK;
     NtArgs a;
-    a.hdr = hdr; a.max_rows = max_rows; a.A0 = h_self; a.A1 = agg; a.lda = ld_in; a.K0 = F_pad; a.K = 2 * F_pad;
+    a.hdr = hdr; a.max_rows = max_rows; a.A0 = n_op == 2 ? h_self : agg; a.A1 = agg; a.lda = ld_in; a.K0 = F_pad; a.K = n_op * F_pad;
     a.B = layer->Wt_bf16; a.N = N_pad; a.bias = layer->bias; a.relu = relu ? 1 : 0;
     a.C0 = out; a.C1 = nullptr; a.ldc = N_pad; a.N0 = N_pad; a.Cb = out_bf16; a.ldcb = N_pad;
     launch_nt(a, static_cast<hipStream_t>(stream));
@@ -637,10 +640,12 @@ extern "C" cr_status cr_sage_linear_bwd_workspace_bytes(int32_t F_in, int32_t F_
     CR_REQUIRE(F_in >= 1 && F_in <= 8192 && F_out >= 1 && F_out <= 8192, CR_ERR_INVALID_ARG, "layer dims (%d, %d) outside 1..8192", F_in, F_out);
     CR_REQUIRE(max_rows >= 1 && bytes != nullptr, CR_ERR_INVALID_ARG, "max_rows must be positive and bytes not NULL");
     const int F_pad = (int)round_up(F_in, 32), N_pad = (int)round_up(F_out, 64);
-    int rows, splits;
-    split_plan(F_pad, N_pad, max_rows, rows, splits);
+    int rows, splits, splits1;
+    split_plan(F_pad, N_pad, 2, max_rows, rows, splits);
+    split_plan(F_pad, N_pad, 1, max_rows, rows, splits1);       // enough for either kind of layer
+    const size_t need2 = (size_t)splits * (2 * F_pad + 1) * N_pad, need1 = (size_t)splits1 * (F_pad + 1) * N_pad;
     Carver c(nullptr);
-    c.take<float>((size_t)splits * (2 * F_pad + 1) * N_pad);
+    c.take<float>(need2 > need1 ? need2 : need1);
     *bytes = c.bytes();
     return CR_OK;
 }
@@ -655,40 +660,45 @@ extern "C" cr_status cr_sage_linear_bwd(const cr_sage_layer *layer, const int32_
     cr_status st = check_layer(layer, F_pad, N_pad);
     if (st != CR_OK) return st;
     CR_REQUIRE(hdr != nullptr && max_rows >= 1, CR_ERR_INVALID_ARG, "hdr must not be NULL and max_rows must be positive");
-    CR_REQUIRE(h_self && agg && dz_bf16 && aligned16(h_self) && aligned16(agg) && aligned16(dz_bf16), CR_ERR_INVALID_ARG,
+    const int n_op = layer->n_operands;
+    CR_REQUIRE(agg && dz_bf16 && aligned16(h_self) && aligned16(agg) && aligned16(dz_bf16), CR_ERR_INVALID_ARG,
                "h_self / agg / dz_bf16 must be 16-byte aligned device pointers");
+    CR_REQUIRE((h_self != nullptr) == (n_op == 2), CR_ERR_INVALID_ARG, "h_self must be given for a two-operand layer and NULL for a one-operand layer");
+    CR_REQUIRE(n_op == 2 || d_self == nullptr, CR_ERR_INVALID_ARG, "a one-operand layer has no d_self");
     CR_REQUIRE(ld_in >= F_pad && ld_in % 8 == 0, CR_ERR_INVALID_ARG, "ld_in = %lld must be a multiple of 8 and >= %d", (long long)ld_in, F_pad);
-    CR_REQUIRE((d_self == nullptr) == (d_agg == nullptr), CR_ERR_INVALID_ARG, "d_self and d_agg must be given together");
+    CR_REQUIRE(n_op == 1 || (d_self == nullptr) == (d_agg == nullptr), CR_ERR_INVALID_ARG, "d_self and d_agg must be given together");
     CR_REQUIRE(aligned16(d_self) && aligned16(d_agg) && aligned16(d_in_bf16), CR_ERR_INVALID_ARG, "d_self / d_agg / d_in_bf16 must be 16-byte aligned");
     CR_REQUIRE(lr == lr && weight_decay == weight_decay, CR_ERR_INVALID_ARG, "lr / weight_decay is NaN");
+    CR_REQUIRE(!(d_agg || d_in_bf16) || (n_op * F_pad) % 64 == 0, CR_ERR_UNSUPPORTED,
+               "input gradients of a one-operand layer need F_in rounded up to 32 to be a multiple of 64");
     CR_REQUIRE((int64_t)max_rows * ld_in * 2 < 0x7FFFFFFFll && (int64_t)max_rows * N_pad * 2 < 0x7FFFFFFFll, CR_ERR_UNSUPPORTED,
                "operand of %d rows exceeds the 2 GiB reach of 32-bit buffer offsets", max_rows);
     int rows, splits;
-    split_plan(F_pad, N_pad, max_rows, rows, splits);
+    split_plan(F_pad, N_pad, n_op, max_rows, rows, splits);
     Carver c(ws);
-    float *partial = c.take<float>((size_t)splits * (2 * F_pad + 1) * N_pad);
+    float *partial = c.take<float>((size_t)splits * (n_op * F_pad + 1) * N_pad);
     CR_REQUIRE(ws != nullptr && aligned16(ws), CR_ERR_INVALID_ARG, "workspace must be a 16-byte aligned device pointer");
     CR_REQUIRE(ws_bytes >= c.bytes(), CR_ERR_CAPACITY, "workspace of %zu bytes, %zu needed", ws_bytes, c.bytes());
     if (dry_run()) return CR_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
 
-    if (d_self || d_in_bf16) {   // gradient w.r.t. the layer's inputs, with the weights from before the step
+    if (d_agg || d_in_bf16) {   // gradient w.r.t. the layer's inputs, with the weights from before the step
         NtArgs a;
         a.hdr = hdr; a.max_rows = max_rows; a.A0 = dz_bf16; a.A1 = nullptr; a.lda = N_pad; a.K0 = N_pad; a.K = N_pad;
-        a.B = layer->W_bf16; a.N = 2 * F_pad; a.bias = nullptr; a.relu = 0;
-        a.C0 = d_self; a.C1 = d_agg; a.ldc = F_pad; a.N0 = F_pad; a.Cb = d_in_bf16; a.ldcb = 2 * F_pad;
+        a.B = layer->W_bf16; a.N = n_op * F_pad; a.bias = nullptr; a.relu = 0;
+        a.C0 = n_op == 2 ? d_self : d_agg; a.C1 = d_agg; a.ldc = F_pad; a.N0 = F_pad; a.Cb = d_in_bf16; a.ldcb = n_op * F_pad;
         launch_nt(a, s);
     }
     TnArgs t;
-    t.hdr = hdr; t.max_rows = max_rows; t.A0 = h_self; t.A1 = agg; t.lda = ld_in; t.K0 = F_pad; t.K2 = 2 * F_pad;
+    t.hdr = hdr; t.max_rows = max_rows; t.A0 = n_op == 2 ? h_self : agg; t.A1 = agg; t.lda = ld_in; t.K0 = F_pad; t.K2 = n_op * F_pad;
     t.Z = dz_bf16; t.N = N_pad; t.slots = splits; t.partial = partial;
-    const unsigned tn_tiles = (unsigned)(2 * ceil_div(F_pad, 128) * ceil_div(N_pad, 128));
+    const unsigned tn_tiles = (unsigned)(n_op * ceil_div(F_pad, 128) * ceil_div(N_pad, 128));
     hipLaunchKernelGGL(gemm_tn_kernel, dim3(tn_tiles, (unsigned)splits + (7 + tn_tiles - 1) / tn_tiles), dim3(256), 0, s, t);
     SgdArgs g;
     g.hdr = hdr; g.max_rows = max_rows; g.n_splits = splits; g.partial = partial;
-    g.F_in = layer->F_in; g.F_out = layer->F_out; g.F_pad = F_pad; g.N_pad = N_pad; g.W = layer->W; g.bias = layer->bias;
+    g.F_in = layer->F_in; g.F_out = layer->F_out; g.F_pad = F_pad; g.N_pad = N_pad; g.n_op = n_op; g.W = layer->W; g.bias = layer->bias;
     g.W_bf16 = layer->W_bf16; g.Wt_bf16 = layer->Wt_bf16; g.lr = lr; g.wd = weight_decay; g.dW_out = dW_out; g.db_out = db_out;
-    hipLaunchKernelGGL(sgd_reduce_kernel, dim3((unsigned)ceil_div((2ll * F_pad + 1) * (N_pad / 4), 64)), dim3(256), 0, s, g);
+    hipLaunchKernelGGL(sgd_reduce_kernel, dim3((unsigned)ceil_div(((int64_t)n_op * F_pad + 1) * (N_pad / 4), 64)), dim3(256), 0, s, g);
     CR_LAUNCH_CHECK();
     return CR_OK;
 }
@@ -702,14 +712,17 @@ extern "C" cr_status cr_sage_linear_bwd_input(const cr_sage_layer *layer, const 
     if (st != CR_OK) return st;
     CR_REQUIRE(hdr != nullptr && max_rows >= 1, CR_ERR_INVALID_ARG, "hdr must not be NULL and max_rows must be positive");
     CR_REQUIRE(dz_bf16 && aligned16(dz_bf16), CR_ERR_INVALID_ARG, "dz_bf16 must be a 16-byte aligned device pointer");
-    CR_REQUIRE((d_self == nullptr) == (d_agg == nullptr), CR_ERR_INVALID_ARG, "d_self and d_agg must be given together");
-    CR_REQUIRE(d_self || d_in_bf16, CR_ERR_INVALID_ARG, "no output requested");
+    const int n_op = layer->n_operands;
+    CR_REQUIRE(n_op == 2 || d_self == nullptr, CR_ERR_INVALID_ARG, "a one-operand layer has no d_self");
+    CR_REQUIRE(n_op == 1 || (d_self == nullptr) == (d_agg == nullptr), CR_ERR_INVALID_ARG, "d_self and d_agg must be given together");
+    CR_REQUIRE(d_agg || d_in_bf16, CR_ERR_INVALID_ARG, "no output requested");
     CR_REQUIRE(aligned16(d_self) && aligned16(d_agg) && aligned16(d_in_bf16), CR_ERR_INVALID_ARG, "d_self / d_agg / d_in_bf16 must be 16-byte aligned");
+    CR_REQUIRE((n_op * F_pad) % 64 == 0, CR_ERR_UNSUPPORTED, "input gradients of a one-operand layer need F_in rounded up to 32 to be a multiple of 64");
     if (dry_run()) return CR_OK;
     NtArgs a;
     a.hdr = hdr; a.max_rows = max_rows; a.A0 = dz_bf16; a.A1 = nullptr; a.lda = N_pad; a.K0 = N_pad; a.K = N_pad;
-    a.B = layer->W_bf16; a.N = 2 * F_pad; a.bias = nullptr; a.relu = 0;
-    a.C0 = d_self; a.C1 = d_agg; a.ldc = F_pad; a.N0 = F_pad; a.Cb = d_in_bf16; a.ldcb = 2 * F_pad;
+    a.B = layer->W_bf16; a.N = n_op * F_pad; a.bias = nullptr; a.relu = 0;
+    a.C0 = n_op == 2 ? d_self : d_agg; a.C1 = d_agg; a.ldc = F_pad; a.N0 = F_pad; a.Cb = d_in_bf16; a.ldcb = n_op * F_pad;
     launch_nt(a, static_cast<hipStream_t>(stream));
     CR_LAUNCH_CHECK();
     return CR_OK;

@@ -163,7 +163,7 @@ def test_gather_validation():
 
 def test_linear_and_loss_validation():
     lib = B.lib()
-    layer = B.cr_sage_layer(100, 47, FAKE, FAKE, FAKE, FAKE)
+    layer = B.cr_sage_layer(100, 47, 2, 0, FAKE, FAKE, FAKE, FAKE)
     fp, np_ = B.cr_sage_padded_dims(100, 47)
     assert (fp, np_) == (128, 64)
     fwd = lambda **kw: lib.cr_sage_linear_fwd(C.byref(kw.get("layer", layer)), vp(kw.get("hdr", FAKE)), kw.get("rows", 100), vp(kw.get("h", FAKE)),
@@ -174,8 +174,21 @@ def test_linear_and_loss_validation():
     assert fwd(ld=96) == B.CR_ERR_INVALID_ARG                            # operands narrower than F_pad
     assert fwd(h=FAKE + 2) == B.CR_ERR_INVALID_ARG
     assert fwd(out=None) == B.CR_ERR_INVALID_ARG
-    assert fwd(layer=B.cr_sage_layer(0, 47, FAKE, FAKE, FAKE, FAKE)) == B.CR_ERR_INVALID_ARG
-    assert fwd(layer=B.cr_sage_layer(100, 47, None, FAKE, FAKE, FAKE)) == B.CR_ERR_INVALID_ARG
+    # one-operand (GCN) layers take no h_self; their input gradients need the padded input width to be a multiple of 64
+    one = B.cr_sage_layer(256, 47, 1, 0, FAKE, FAKE, FAKE, FAKE)
+    assert fwd(layer=one, ld=256) == B.CR_ERR_INVALID_ARG
+    assert fwd(layer=one, ld=256, h=None) == B.CR_OK
+    assert fwd(h=None) == B.CR_ERR_INVALID_ARG                           # two operands need both
+    assert fwd(layer=B.cr_sage_layer(100, 47, 3, 0, FAKE, FAKE, FAKE, FAKE)) == B.CR_ERR_INVALID_ARG
+    one_bwd = lambda lay, **kw: lib.cr_sage_linear_bwd(C.byref(lay), vp(), 1000, None, vp(), kw.get("ld", 256), vp(), C.c_float(0.01), C.c_float(0.0),
+                                                       vp(kw.get("ds", None)), vp(kw.get("da", None)), vp(kw.get("db", None)), None, None, vp(),
+                                                       B.cr_sage_linear_bwd_workspace_bytes(256, 47, 1000), None)
+    assert one_bwd(one) == B.CR_OK and one_bwd(one, da=FAKE) == B.CR_OK and one_bwd(one, db=FAKE) == B.CR_OK
+    assert one_bwd(one, ds=FAKE, da=FAKE) == B.CR_ERR_INVALID_ARG
+    odd = B.cr_sage_layer(96, 47, 1, 0, FAKE, FAKE, FAKE, FAKE)
+    assert one_bwd(odd, ld=96) == B.CR_OK and one_bwd(odd, ld=96, db=FAKE) == B.CR_ERR_UNSUPPORTED
+    assert fwd(layer=B.cr_sage_layer(0, 47, 2, 0, FAKE, FAKE, FAKE, FAKE)) == B.CR_ERR_INVALID_ARG
+    assert fwd(layer=B.cr_sage_layer(100, 47, 2, 0, None, FAKE, FAKE, FAKE)) == B.CR_ERR_INVALID_ARG
     need = B.cr_sage_linear_bwd_workspace_bytes(100, 47, 1000)
     bwd = lambda **kw: lib.cr_sage_linear_bwd(C.byref(layer), vp(), 1000, vp(), vp(), 128, vp(), C.c_float(kw.get("lr", 0.01)), C.c_float(0.0),
                                               vp(kw.get("ds", FAKE)), vp(kw.get("da", FAKE)), vp(kw.get("db", None)), None, None, vp(),

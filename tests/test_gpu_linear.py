@@ -188,3 +188,59 @@ def test_count_correct(torch_mod, n, Cn):
     B.cr_count_correct(C.c_void_p(hdr.data_ptr()), n + 5, up(logits), ld, Cn, up(labels_all), C.c_void_p(d_roots.data_ptr()), count)
     torch.cuda.synchronize()
     assert int(count.cpu()[0]) == 11 + want
+
+
+@pytest.mark.parametrize("M,F_in,F_out,relu,need_dx", [(300, 64, 64, True, True), (1000, 100, 256, True, False), (517, 256, 40, False, True),
+                                                       (2500, 128, 256, True, True), (1, 64, 64, True, True)])
+def test_one_operand_layer(torch_mod, M, F_in, F_out, relu, need_dx):
+    """A layer with a single aggregated input (GCN): Z = Agg W + b, its backward and SGD step.  The oracle is the
+    two-operand one with a zero self operand and zero W_self rows, which adds exact zeros."""
+    torch = torch_mod
+    from paper_2504_18082_amd import binding as B
+    rng = np.random.default_rng(M * 7 + F_in)
+    print(f"case one-operand M={M} F_in={F_in} F_out={F_out}", flush=True)
+    ag = rng.standard_normal((M, F_in)).astype(np.float32)
+    W = (rng.standard_normal((F_in, F_out)) / np.sqrt(F_in)).astype(np.float32)
+    b = rng.standard_normal(F_out).astype(np.float32) * 0.1
+    zeros, W2 = np.zeros_like(ag), np.vstack([np.zeros_like(W), W])
+    want = oracle.sage_linear_fwd(zeros, ag, W2, b, relu, True)
+    dz = (rng.standard_normal((M, F_out)) / M).astype(np.float32)
+    dz[rng.random((M, F_out)) < 0.4] = 0.0
+    dW2, _, _, d_agg = oracle.sage_linear_bwd(zeros, ag, W2, np.ones((M, F_out)), dz, False, True, need_dx=need_dx)
+    dW = dW2[F_in:]
+    db = oracle.round_bf16(dz).sum(axis=0)
+    lr, wd = 0.05, 5e-4
+    W_new2, b_new = oracle.sgd_step(W2, dW2, b, db, lr, wd)
+
+    layer = B.SageLayer(W, b, n_operands=1)
+    layer.refresh()
+    cap = M + 37
+    ld_in = layer.F_pad
+    d_ag = to_bf16_dev(torch, np.pad(ag, ((0, 37), (0, 0)), constant_values=2.0), ld_in)
+    out = torch.full((cap, layer.N_pad), np.nan, dtype=torch.float32, device="cuda")
+    hdr = hdr_for(torch, M)
+    B.cr_sage_linear_fwd(layer, C.c_void_p(hdr.data_ptr()), cap, None, d_ag, ld_in, relu, out, None)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert_close(got[:M, :F_out], want, 1e-4, "out")
+    assert np.all(np.isnan(got[M:]))
+
+    d_dz = to_bf16_dev(torch, np.pad(dz, ((0, 37), (0, 0)), constant_values=3.0), layer.N_pad)
+    ws = torch.empty(B.cr_sage_linear_bwd_workspace_bytes(F_in, F_out, cap), dtype=torch.uint8, device="cuda")
+    g_agg = torch.full((cap, layer.F_pad), np.nan, dtype=torch.float32, device="cuda") if need_dx else None
+    g_in_b = torch.full((cap, layer.F_pad), 0x7FC0, dtype=torch.int16, device="cuda") if need_dx else None
+    dW_out = torch.zeros((F_in, F_out), dtype=torch.float32, device="cuda")
+    db_out = torch.zeros(F_out, dtype=torch.float32, device="cuda")
+    B.cr_sage_linear_bwd(layer, C.c_void_p(hdr.data_ptr()), cap, None, d_ag, ld_in, d_dz, lr, wd, None, g_agg, ws, dW_out, db_out,
+                         d_in_bf16=g_in_b)
+    torch.cuda.synchronize()
+    assert_close(dW_out.cpu().numpy(), dW, 1e-4, "dW")
+    assert_close(db_out.cpu().numpy(), db, 1e-4, "db")
+    assert_close(layer.W.cpu().numpy(), W_new2[F_in:], RTOL_F32, "W after SGD")
+    assert_close(layer.bias.cpu().numpy()[:F_out], b_new, RTOL_F32, "bias after SGD")
+    wb = bf16_tensor_to_float(layer.W_bf16)
+    np.testing.assert_array_equal(wb[:F_in, :F_out].astype(np.float64), oracle.round_bf16(layer.W.cpu().numpy()))
+    np.testing.assert_array_equal(bf16_tensor_to_float(layer.Wt_bf16), wb.T)
+    if need_dx:
+        assert_close(g_agg.cpu().numpy()[:M, :F_in], d_agg, 1e-4, "d_agg")
+        np.testing.assert_array_equal(g_in_b.cpu().numpy()[:M].view(np.uint16), synth.float_to_bf16_bits(g_agg.cpu().numpy()[:M]))
