@@ -227,6 +227,34 @@ cr_status cr_gather_aggregate_bwd(const cr_block_set *blocks, int32_t g, const v
                                   const void *relu_out, int32_t relu_dtype, int64_t ld_relu, float *d_src,
                                   uint16_t *d_src_bf16, int64_t ld_bf16, void *stream);
 
+/* ------------------------------------------------------------------------- */
+/* GCN on the same blocks (Section 6.4: the method generalises to other models; Kipf & Welling's propagation rule     */
+/* with the renormalisation trick, d~ = degree in the full graph + 1):                                                 */
+/*   exact : out[v] = sum_{u in N(v) + {v}} H[u] / sqrt(d~_v d~_u)                                                     */
+/*   block : out[v] = H[v] / d~_v + (deg_v / |N_s(v)|) / sqrt(d~_v) * sum_{u in N_s(v)} H[u] / sqrt(d~_u)              */
+/* (the neighbour sum is estimated from the sampled neighbours; exact when all were taken, unbiased under uniform       */
+/* sampling).  The dense part is a one-operand layer, Z = out W + b.                                                    */
+/* ------------------------------------------------------------------------- */
+/* norm: device float[2*n_nodes], norm[2v] = 1/sqrt(d~_v), norm[2v+1] = deg_v; static per graph. */
+cr_status cr_graph_gcn_norm(const cr_graph *graph, float *norm, void *stream);
+
+/* Per-batch normalisation of block g: blk_norm is a device float[cap_src + 2*cap_dst] scratch that the two calls below
+ * read (source weights, destination scales, destination self weights); compute it once per sampled block and batch. */
+cr_status cr_gcn_block_norm(const cr_block_set *blocks, int32_t g, const float *norm, float *blk_norm, void *stream);
+
+/* Arguments as cr_gather_aggregate_fwd (no self output: the destination's own row is part of the sum).  indirect != 0
+ * needs blocks->gather_ids. */
+cr_status cr_gcn_aggregate_fwd(const cr_block_set *blocks, int32_t g, const float *norm, const float *blk_norm,
+                               const void *H_src, int32_t dtype, int64_t ld_src, int32_t F, int32_t indirect,
+                               float *agg, uint16_t *agg_bf16, int64_t ld_bf16, void *stream);
+
+/* Transpose of cr_gcn_aggregate_fwd (dense addressing): gradient with respect to the source rows, atomic-free over the
+ * transposed block.  d_out: device float or bf16 (in_dtype) [cap_dst][ld_in]; other arguments as
+ * cr_gather_aggregate_bwd. */
+cr_status cr_gcn_aggregate_bwd(const cr_block_set *blocks, int32_t g, const float *blk_norm, const void *d_out,
+                               int32_t in_dtype, int64_t ld_in, int32_t F, const void *relu_out, int32_t relu_dtype,
+                               int64_t ld_relu, float *d_src, uint16_t *d_src_bf16, int64_t ld_bf16, void *stream);
+
 /* One layer's dense parameters.  F_pad = F_in rounded up to 32, N_pad = F_out rounded up to 64.
  * n_operands = 2: GraphSAGE, Z = H_self W_self + Agg W_neigh + b;  n_operands = 1: one aggregated input (GCN,
  * Section 6.4), Z = Agg W + b: every h_self / d_self argument below must then be NULL and the [.. 2*F ..] shapes

@@ -297,3 +297,56 @@ class FeatureCacheModel:
         self.queries += len(ids)
         self.misses += n_miss
         return slots, n_miss
+
+
+def _as_float_table(table):
+    """float64 view of a float32 / raw-bf16 (uint16) table."""
+    if table.dtype == np.uint16:
+        return (table.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    return np.asarray(table, dtype=np.float64)
+
+
+def gcn_aggregate(blk: Block, table, graph_deg, indirect: bool, F=None):
+    """GCN propagation on a sampled block (Section 6.4: the method applied to GCN; Kipf & Welling's rule with
+    the renormalisation trick, A~ = A + I, d~ = deg + 1 taken on the full graph):
+
+        exact :  out[v] = sum_{u in N(v) + {v}} H[u] / sqrt(d~_v d~_u)
+        block :  out[v] = H[v] / d~_v + (deg_v / |N_s(v)|) / sqrt(d~_v) * sum_{u in N_s(v)} H[u] / sqrt(d~_u)
+
+    i.e. the neighbour sum is estimated from the sampled neighbours (exact when all of them were taken; unbiased
+    under uniform sampling), the self term is exact.  graph_deg: degrees of the full graph by global id.
+    indirect: table rows are addressed by global id (input layer), else by local source position."""
+    H = _as_float_table(table)
+    F = H.shape[1] if F is None else F
+    deg = np.asarray(graph_deg, dtype=np.float64)
+    isd = 1.0 / np.sqrt(deg + 1.0)
+    nodes = blk.src_ids.astype(np.int64)
+    dst = nodes[:blk.n_dst]
+    n_s = np.diff(blk.indptr).astype(np.float64)
+    rows_e = np.repeat(np.arange(blk.n_dst), np.diff(blk.indptr))
+    u_local = blk.indices[:blk.nnz].astype(np.int64)
+    u_node = nodes[u_local]
+    H_e = H[u_node, :F] if indirect else H[u_local, :F]
+    acc = np.zeros((blk.n_dst, F), dtype=np.float64)
+    np.add.at(acc, rows_e, H_e * isd[u_node][:, None])
+    scale = np.where(n_s > 0, deg[dst] / np.maximum(n_s, 1.0) * isd[dst], 0.0)
+    H_self = H[dst, :F] if indirect else H[:blk.n_dst, :F]
+    return H_self / (deg[dst] + 1.0)[:, None] + scale[:, None] * acc
+
+
+def gcn_aggregate_bwd(blk: Block, d_out, graph_deg):
+    """Gradient of gcn_aggregate (dense addressing) with respect to the source rows: its transpose."""
+    d_out = np.asarray(d_out, dtype=np.float64)
+    F = d_out.shape[1]
+    deg = np.asarray(graph_deg, dtype=np.float64)
+    isd = 1.0 / np.sqrt(deg + 1.0)
+    nodes = blk.src_ids.astype(np.int64)
+    dst = nodes[:blk.n_dst]
+    n_s = np.diff(blk.indptr).astype(np.float64)
+    rows_e = np.repeat(np.arange(blk.n_dst), np.diff(blk.indptr))
+    u_local = blk.indices[:blk.nnz].astype(np.int64)
+    scale = np.where(n_s > 0, deg[dst] / np.maximum(n_s, 1.0) * isd[dst], 0.0)
+    d_src = np.zeros((blk.n_src, F), dtype=np.float64)
+    np.add.at(d_src, u_local, (scale[rows_e] * isd[nodes[u_local]])[:, None] * d_out[rows_e])
+    d_src[:blk.n_dst] += d_out / (deg[dst] + 1.0)[:, None]
+    return d_src

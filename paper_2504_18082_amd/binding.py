@@ -29,6 +29,7 @@ EXPORTS = [
     "cr_build_batches_workspace_bytes", "cr_build_batches",
     "cr_graph_edge_classes", "cr_block_capacities", "cr_sample_blocks_workspace_bytes", "cr_sample_blocks",
     "cr_gather_aggregate_fwd", "cr_gather_aggregate_bwd",
+    "cr_graph_gcn_norm", "cr_gcn_block_norm", "cr_gcn_aggregate_fwd", "cr_gcn_aggregate_bwd",
     "cr_sage_padded_dims", "cr_sage_refresh_shadows", "cr_sage_linear_fwd",
     "cr_sage_linear_bwd_workspace_bytes", "cr_sage_linear_bwd", "cr_sage_linear_bwd_input", "cr_softmax_xent",
     "cr_count_correct",
@@ -112,6 +113,10 @@ def lib():
                                               vp, i64, vp]
         L.cr_gather_aggregate_bwd.argtypes = [C.POINTER(cr_block_set), i32, vp, vp, i32, i64, i32, vp, i32, i64, vp,
                                               vp, i64, vp]
+        L.cr_graph_gcn_norm.argtypes = [C.POINTER(cr_graph), vp, vp]
+        L.cr_gcn_block_norm.argtypes = [C.POINTER(cr_block_set), i32, vp, vp, vp]
+        L.cr_gcn_aggregate_fwd.argtypes = [C.POINTER(cr_block_set), i32, vp, vp, vp, i32, i64, i32, i32, vp, vp, i64, vp]
+        L.cr_gcn_aggregate_bwd.argtypes = [C.POINTER(cr_block_set), i32, vp, vp, i32, i64, i32, vp, i32, i64, vp, vp, i64, vp]
         L.cr_sage_padded_dims.argtypes = [i32, i32, C.POINTER(i32), C.POINTER(i32)]
         L.cr_sage_refresh_shadows.argtypes = [C.POINTER(cr_sage_layer), vp]
         L.cr_sage_linear_fwd.argtypes = [C.POINTER(cr_sage_layer), vp, i32, vp, vp, i64, C.c_int, vp, vp, vp]
@@ -294,6 +299,30 @@ def cr_gather_aggregate_bwd(blocks: BlockSet, g, d_agg, d_self, ld_in, F, relu_o
     _check(lib().cr_gather_aggregate_bwd(C.byref(blocks.c), g, as_ptr(d_agg), as_ptr(d_self), in_dtype, ld_in, F,
                                          _ptr(relu_out), relu_dtype, ld_relu, _ptr(d_src), _ptr(d_src_bf16), ld_bf16,
                                          _stream(stream)))
+
+
+def cr_graph_gcn_norm(graph: cr_graph, stream=None):
+    """Allocates and fills the per-node GCN normalisation of a graph: float tensor [n_nodes, 2]."""
+    import torch
+    norm = torch.zeros((graph.n_nodes, 2), dtype=torch.float32, device="cuda")
+    _check(lib().cr_graph_gcn_norm(C.byref(graph), _ptr(norm), _stream(stream)))
+    return norm
+
+
+def cr_gcn_block_norm(blocks, g, norm, blk_norm, stream=None):
+    _check(lib().cr_gcn_block_norm(C.byref(blocks.c), g, _ptr(norm), _ptr(blk_norm), _stream(stream)))
+
+
+def cr_gcn_aggregate_fwd(blocks, g, norm, blk_norm, H_src, dtype, ld_src, F, indirect, agg=None, agg_bf16=None, ld_bf16=0, stream=None):
+    H_ptr = H_src if isinstance(H_src, C.c_void_p) else _ptr(H_src)
+    _check(lib().cr_gcn_aggregate_fwd(C.byref(blocks.c), g, _ptr(norm), _ptr(blk_norm), H_ptr, dtype, ld_src, F, int(indirect),
+                                      _ptr(agg), _ptr(agg_bf16), ld_bf16, _stream(stream)))
+
+
+def cr_gcn_aggregate_bwd(blocks, g, blk_norm, d_out, ld_in, F, relu_out=None, ld_relu=0, d_src=None, d_src_bf16=None, ld_bf16=0,
+                         stream=None, relu_dtype=CR_F32, in_dtype=CR_F32):
+    _check(lib().cr_gcn_aggregate_bwd(C.byref(blocks.c), g, _ptr(blk_norm), _ptr(d_out), in_dtype, ld_in, F, _ptr(relu_out), relu_dtype,
+                                      ld_relu, _ptr(d_src), _ptr(d_src_bf16), ld_bf16, _stream(stream)))
 
 
 def cr_sage_padded_dims(F_in, F_out):

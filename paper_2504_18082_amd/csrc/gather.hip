@@ -54,12 +54,24 @@ __device__ __forceinline__ void store_bf16_row(uint16_t *dst, const float (&v)[N
 // one after are already being fetched, so a destination costs one memory round trip instead of a
 // chain of four.  Look-ahead loads are unconditional (clamped to valid addresses).
 // ------------------------------------------------------------------------------------------------
-template <typename T, int LPR, int NCHUNK>
+// GCN == true turns the mean into the GCN propagation of a sampled block: every gathered row is weighted by
+// 1/sqrt(d~_u) (gcn.edge_w: by local source position, or gcn.node_norm[2u] by global id), the sum is scaled by the
+// destination's (deg_v / |N_s(v)|) / sqrt(d~_v) (gcn.dst_scale) and the destination's own row enters with 1/d~_v
+// (gcn.dst_self); d~ = degree in the full graph + 1.
+struct GcnFwd {
+    const float *edge_w;      // [n_src] or NULL
+    const float *node_norm;   // [2 * n_nodes] (1/sqrt(d~), degree) or NULL
+    const float *dst_scale;   // [n_dst]
+    const float *dst_self;    // [n_dst]
+};
+
+template <typename T, int LPR, int NCHUNK, bool GCN = false>
 __global__ __launch_bounds__(256) void gather_mean_fwd_kernel(
     const int32_t *__restrict__ hdr, const int32_t *__restrict__ indptr,
     const int32_t *__restrict__ ids, const int32_t *__restrict__ edge_map,
     const int32_t *__restrict__ self_map, const T *__restrict__ table, int64_t ld, int F,
-    float *__restrict__ agg, uint16_t *__restrict__ agg_bf16, uint16_t *__restrict__ self_bf16, int64_t ld_bf16)
+    float *__restrict__ agg, uint16_t *__restrict__ agg_bf16, uint16_t *__restrict__ self_bf16, int64_t ld_bf16,
+    GcnFwd gcn = GcnFwd{nullptr, nullptr, nullptr, nullptr})
 {
     constexpr int VEC = Vec16<T>::N;
     constexpr int U = NCHUNK == 1 ? 8 : (NCHUNK <= 3 ? 4 : 2);   // independent row loads in flight per lane
@@ -74,31 +86,38 @@ __global__ __launch_bounds__(256) void gather_mean_fwd_kernel(
     int row = block_first + (int)(threadIdx.x / LPR);
     if (row >= block_end) return;
 
-    auto load_ptrs = [&](int r, int &s, int &e, int &self_row) {
+    float sc0 = 0.f, sf0 = 0.f, sc1 = 0.f, sf1 = 0.f, sc2 = 0.f, sf2 = 0.f;     // GCN: destination scale / self weight
+    auto load_ptrs = [&](int r, int &s, int &e, int &self_row, float &sc, float &sf) {
         const int rc = min(r, n_dst - 1);
         const int a = indptr[rc], b = indptr[rc + 1];
         const int sr = self_map ? self_map[rc] : rc;
+        if constexpr (GCN) { sc = gcn.dst_scale[rc]; sf = gcn.dst_self[rc]; }
         s = r < block_end ? a : 0;
         e = r < block_end ? b : 0;
         self_row = sr;
     };
-    auto load_ids = [&](int first, int e) -> int {
+    auto load_ids = [&](int first, int e, float &w) -> int {
         const int idx = max(min(first + gl, e - 1), 0);
         int x = ids[idx];
+        if constexpr (GCN) {
+            // ids are local source positions (weights by position) or, through gather_ids, global ids (weights by node)
+            w = gcn.edge_w ? gcn.edge_w[min(max(x, 0), max(n_src, 1) - 1)] : gcn.node_norm[2 * (int64_t)max(x, 0)];
+        }
         if (edge_map) x = edge_map[min(max(x, 0), n_src - 1)];   // (a lane past the row's end may have read a stale entry)
         return x;
     };
 
     int s0, e0, self0, s1, e1, self1;
-    load_ptrs(row, s0, e0, self0);
-    int rid0 = load_ids(s0, e0);
-    load_ptrs(row + GPB, s1, e1, self1);
+    float w0 = 1.f, w1 = 1.f;
+    load_ptrs(row, s0, e0, self0, sc0, sf0);
+    int rid0 = load_ids(s0, e0, w0);
+    load_ptrs(row + GPB, s1, e1, self1, sc1, sf1);
 
     for (; row < block_end; row += GPB) {
         // look ahead: ids of the next destination, pointers of the one after
-        const int rid1 = load_ids(s1, e1);
+        const int rid1 = load_ids(s1, e1, w1);
         int s2, e2, self2;
-        load_ptrs(row + 2 * GPB, s2, e2, self2);
+        load_ptrs(row + 2 * GPB, s2, e2, self2, sc2, sf2);
 
         float acc[NCHUNK][VEC];
 #pragma unroll
@@ -107,14 +126,17 @@ __global__ __launch_bounds__(256) void gather_mean_fwd_kernel(
             for (int i = 0; i < VEC; ++i) acc[c][i] = 0.f;
 
         int rid = rid0;
+        float wgt = w0;
         for (int base = s0; base < e0; base += LPR) {
-            if (base > s0) rid = load_ids(base, e0);            // rows longer than the group width
+            if (base > s0) rid = load_ids(base, e0, wgt);       // rows longer than the group width
             const int cnt = min(LPR, e0 - base);
             for (int t = 0; t < cnt; t += U) {
                 float v[U][NCHUNK][VEC];
+                float wu[U];
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     const int r = __shfl(rid, t + u, LPR);
+                    if constexpr (GCN) wu[u] = __shfl(wgt, t + u, LPR);
                     const T *p = table + (int64_t)r * ld;
 #pragma unroll
                     for (int c = 0; c < NCHUNK; ++c) {
@@ -129,7 +151,10 @@ __global__ __launch_bounds__(256) void gather_mean_fwd_kernel(
                         const int col = (c * LPR + gl) * VEC;
                         if (col < F && t + u < cnt) {
 #pragma unroll
-                            for (int i = 0; i < VEC; ++i) acc[c][i] += v[u][c][i];
+                            for (int i = 0; i < VEC; ++i) {
+                                if constexpr (GCN) acc[c][i] += wu[u] * v[u][c][i];
+                                else acc[c][i] += v[u][c][i];
+                            }
                         }
                     }
             }
@@ -140,8 +165,17 @@ __global__ __launch_bounds__(256) void gather_mean_fwd_kernel(
 #pragma unroll
         for (int c = 0; c < NCHUNK; ++c) {
             const int col = (c * LPR + gl) * VEC;
+            if constexpr (GCN) {
+                float sv[VEC];
 #pragma unroll
-            for (int i = 0; i < VEC; ++i) acc[c][i] = acc[c][i] / fdeg;
+                for (int i = 0; i < VEC; ++i) sv[i] = 0.f;
+                if (col < F) Vec16<T>::load(table + (int64_t)self0 * ld + col, sv);
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) acc[c][i] = acc[c][i] * sc0 + sv[i] * sf0;
+            } else {
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) acc[c][i] = acc[c][i] / fdeg;
+            }
             if (agg && col < F) {
                 float *o = agg + (int64_t)row * F + col;
                 if ((F & 3) == 0) {
@@ -172,33 +206,42 @@ __global__ __launch_bounds__(256) void gather_mean_fwd_kernel(
             }
         }
 
-        s0 = s1; e0 = e1; self0 = self1; rid0 = rid1;
-        s1 = s2; e1 = e2; self1 = self2;
+        s0 = s1; e0 = e1; self0 = self1; rid0 = rid1; w0 = w1; sc0 = sc1; sf0 = sf1;
+        s1 = s2; e1 = e2; self1 = self2; sc1 = sc2; sf1 = sf2;
     }
 }
 
 template <typename T, int LPR, int NCHUNK>
 static void launch_fwd(int cap_dst, const int32_t *hdr, const int32_t *indptr, const int32_t *ids,
                        const int32_t *edge_map, const int32_t *self_map, const void *table, int64_t ld, int F,
-                       float *agg, uint16_t *agg_bf16, uint16_t *self_bf16, int64_t ld_bf16, hipStream_t st)
+                       float *agg, uint16_t *agg_bf16, uint16_t *self_bf16, int64_t ld_bf16, hipStream_t st,
+                       const GcnFwd *gcn = nullptr)
 {
     constexpr int GPB = 256 / LPR;
     int64_t grid = ceil_div(cap_dst, GPB);
     if (grid > 1024) grid = 1024;          // 4 workgroups per CU; each group then walks several rows
-    hipLaunchKernelGGL((gather_mean_fwd_kernel<T, LPR, NCHUNK>), dim3((unsigned)grid), dim3(256), 0, st, hdr, indptr,
-                       ids, edge_map, self_map, static_cast<const T *>(table), ld, F, agg, agg_bf16, self_bf16, ld_bf16);
+    if (gcn)
+        hipLaunchKernelGGL((gather_mean_fwd_kernel<T, LPR, NCHUNK, true>), dim3((unsigned)grid), dim3(256), 0, st, hdr, indptr,
+                           ids, edge_map, self_map, static_cast<const T *>(table), ld, F, agg, agg_bf16, self_bf16, ld_bf16, *gcn);
+    else
+        hipLaunchKernelGGL((gather_mean_fwd_kernel<T, LPR, NCHUNK, false>), dim3((unsigned)grid), dim3(256), 0, st, hdr, indptr,
+                           ids, edge_map, self_map, static_cast<const T *>(table), ld, F, agg, agg_bf16, self_bf16, ld_bf16,
+                           GcnFwd{nullptr, nullptr, nullptr, nullptr});
 }
 
 // ------------------------------------------------------------------------------------------------
 // backward: one sub-wave group per source row pulls from the destination rows that used it
 // ------------------------------------------------------------------------------------------------
-template <typename T, int LPR, int NCHUNK>
+// GCN == true is the transpose of the GCN forward: destination v contributes with gcn.dst_scale[v], the sum is
+// scaled by the source's 1/sqrt(d~) (gcn.edge_w), and a source that is also a destination adds gcn.dst_self * its own
+// gradient row (d_self is then the same array as d_agg).
+template <typename T, int LPR, int NCHUNK, bool GCN = false>
 __global__ __launch_bounds__(256) void gather_mean_bwd_kernel(
     const int32_t *__restrict__ hdr, const int32_t *__restrict__ indptr,
     const int32_t *__restrict__ t_indptr, const int32_t *__restrict__ t_indices,
     const T *__restrict__ d_agg, const T *__restrict__ d_self, int64_t ld_in, int F,
     const void *__restrict__ relu_out, int relu_is_bf16, int64_t ld_relu, float *__restrict__ d_src,
-    uint16_t *__restrict__ d_src_bf16, int64_t ld_bf16)
+    uint16_t *__restrict__ d_src_bf16, int64_t ld_bf16, GcnFwd gcn = GcnFwd{nullptr, nullptr, nullptr, nullptr})
 {
     constexpr int VEC = Vec16<T>::N;
     constexpr int U = NCHUNK == 1 ? 8 : (NCHUNK <= 3 ? 4 : 2);
@@ -224,8 +267,12 @@ __global__ __launch_bounds__(256) void gather_mean_bwd_kernel(
     auto load_ids = [&](int first, int e, int &v, float &w) {
         const int idx = max(min(first + gl, e - 1), 0);
         v = min(max(t_indices[idx], 0), n_dst - 1);               // (a lane past the segment's end may have read a stale entry)
-        const int deg = indptr[v + 1] - indptr[v];
-        w = 1.0f / (float)(deg > 0 ? deg : 1);
+        if constexpr (GCN) {
+            w = gcn.dst_scale[v];
+        } else {
+            const int deg = indptr[v + 1] - indptr[v];
+            w = 1.0f / (float)(deg > 0 ? deg : 1);
+        }
     };
 
     int b0, e0, b1, e1, v0, v1;
@@ -280,11 +327,17 @@ __global__ __launch_bounds__(256) void gather_mean_bwd_kernel(
         for (int c = 0; c < NCHUNK; ++c) {
             const int col = (c * LPR + gl) * VEC;
             if (col < F) {
+                if constexpr (GCN) {
+                    const float ws = gcn.edge_w[s];
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) acc[c][i] *= ws;
+                }
                 if (d_self && s < n_dst) {
                     float x[VEC];
                     Vec16<T>::load(d_self + (int64_t)s * ld_in + col, x);
+                    const float wself = GCN ? gcn.dst_self[s] : 1.0f;
 #pragma unroll
-                    for (int i = 0; i < VEC; ++i) acc[c][i] += x[i];
+                    for (int i = 0; i < VEC; ++i) acc[c][i] += wself * x[i];
                 }
                 if (relu_out) {
                     float y[VEC];
@@ -335,13 +388,46 @@ template <typename T, int LPR, int NCHUNK>
 static void launch_bwd(int cap_src, const int32_t *hdr, const int32_t *indptr, const int32_t *t_indptr,
                        const int32_t *t_indices, const void *d_agg, const void *d_self, int64_t ld_in, int F,
                        const void *relu_out, int relu_is_bf16, int64_t ld_relu, float *d_src, uint16_t *d_src_bf16,
-                       int64_t ld_bf16, hipStream_t st)
+                       int64_t ld_bf16, hipStream_t st, const GcnFwd *gcn = nullptr)
 {
     int64_t grid = ceil_div(cap_src, 256 / LPR);
     if (grid > 1024) grid = 1024;
-    hipLaunchKernelGGL((gather_mean_bwd_kernel<T, LPR, NCHUNK>), dim3((unsigned)grid), dim3(256), 0, st, hdr, indptr, t_indptr,
-                       t_indices, static_cast<const T *>(d_agg), static_cast<const T *>(d_self), ld_in, F, relu_out, relu_is_bf16,
-                       ld_relu, d_src, d_src_bf16, ld_bf16);
+    if (gcn)
+        hipLaunchKernelGGL((gather_mean_bwd_kernel<T, LPR, NCHUNK, true>), dim3((unsigned)grid), dim3(256), 0, st, hdr, indptr, t_indptr,
+                           t_indices, static_cast<const T *>(d_agg), static_cast<const T *>(d_self), ld_in, F, relu_out, relu_is_bf16,
+                           ld_relu, d_src, d_src_bf16, ld_bf16, *gcn);
+    else
+        hipLaunchKernelGGL((gather_mean_bwd_kernel<T, LPR, NCHUNK, false>), dim3((unsigned)grid), dim3(256), 0, st, hdr, indptr, t_indptr,
+                           t_indices, static_cast<const T *>(d_agg), static_cast<const T *>(d_self), ld_in, F, relu_out, relu_is_bf16,
+                           ld_relu, d_src, d_src_bf16, ld_bf16, GcnFwd{nullptr, nullptr, nullptr, nullptr});
+}
+
+// per-node normalisation of the full graph: norm[2v] = 1/sqrt(deg_v + 1), norm[2v + 1] = deg_v
+__global__ __launch_bounds__(256) void gcn_node_norm_kernel(const int64_t *__restrict__ indptr, int64_t n_nodes, float *__restrict__ norm)
+{
+    const int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (v >= n_nodes) return;
+    const float deg = (float)(indptr[v + 1] - indptr[v]);
+    norm[2 * v] = 1.0f / sqrtf(deg + 1.0f);
+    norm[2 * v + 1] = deg;
+}
+
+// per-block normalisation of one batch: source weights, destination scales and self weights (see GcnFwd)
+__global__ __launch_bounds__(256) void gcn_block_norm_kernel(const int32_t *__restrict__ hdr, const int32_t *__restrict__ indptr,
+                                                             const int32_t *__restrict__ node_ids, const float *__restrict__ norm,
+                                                             float *__restrict__ edge_w, float *__restrict__ dst_scale,
+                                                             float *__restrict__ dst_self)
+{
+    const int n_dst = hdr[CR_HDR_N_DST], n_src = hdr[CR_HDR_N_SRC];
+    const int i = (int)(blockIdx.x * 256 + threadIdx.x);
+    if (i < n_src) edge_w[i] = norm[2 * (int64_t)node_ids[i]];
+    if (i < n_dst) {
+        const int64_t v = node_ids[i];
+        const float isd = norm[2 * v], deg = norm[2 * v + 1];
+        const int n_s = indptr[i + 1] - indptr[i];
+        dst_scale[i] = n_s > 0 ? deg / (float)n_s * isd : 0.0f;
+        dst_self[i] = 1.0f / (deg + 1.0f);
+    }
 }
 
 }  // namespace cr
@@ -358,6 +444,38 @@ static cr_status check_block_set(const cr_block_set *b, int32_t g, bool need_t)
     CR_REQUIRE(b->hdr && b->src_ids && b->indptr && b->indices, CR_ERR_INVALID_ARG, "block set has a NULL array");
     if (need_t) CR_REQUIRE(b->t_indptr && b->t_indices, CR_ERR_INVALID_ARG, "block set carries no transposed block");
     return CR_OK;
+}
+
+static void run_fwd(const cr_block_set *blocks, int32_t g, const void *H_src, int32_t dtype, int64_t ld_src, int32_t F,
+                    int32_t indirect, float *agg, uint16_t *agg_bf16, uint16_t *self_bf16, int64_t ld_bf16, hipStream_t s,
+                    const GcnFwd *gcn)
+{
+    const int32_t *hdr = blocks->hdr + (int64_t)g * CR_HDR_WORDS;
+    const int32_t *indptr = blocks->indptr + (int64_t)g * (blocks->cap_dst + 1);
+    const int32_t *src_ids = blocks->src_ids + (int64_t)g * blocks->cap_src;
+    const int32_t *ids = blocks->indices + (int64_t)g * blocks->cap_nnz;
+    const int32_t *edge_map = nullptr, *self_map = nullptr;
+    if (indirect) {
+        self_map = src_ids;
+        if (blocks->gather_ids) ids = blocks->gather_ids + (int64_t)g * blocks->cap_nnz;   // per-edge table rows, one level less
+        else edge_map = src_ids;
+    }
+    const int cap = blocks->cap_dst;
+#define CR_FWD(T, LPR, NC) launch_fwd<T, LPR, NC>(cap, hdr, indptr, ids, edge_map, self_map, H_src, ld_src, F, agg, agg_bf16, self_bf16, ld_bf16, s, gcn)
+    if (dtype == CR_F32) {
+        if (F <= 64) CR_FWD(float, 16, 1);
+        else if (F <= 128) CR_FWD(float, 32, 1);
+        else if (F <= 256) CR_FWD(float, 64, 1);
+        else if (F <= 512) CR_FWD(float, 64, 2);
+        else if (F <= 768) CR_FWD(float, 64, 3);
+        else CR_FWD(float, 64, 4);
+    } else {
+        if (F <= 128) CR_FWD(uint16_t, 16, 1);
+        else if (F <= 256) CR_FWD(uint16_t, 32, 1);
+        else if (F <= 512) CR_FWD(uint16_t, 64, 1);
+        else CR_FWD(uint16_t, 64, 2);
+    }
+#undef CR_FWD
 }
 
 extern "C" cr_status cr_gather_aggregate_fwd(const cr_block_set *blocks, int32_t g, const void *H_src,
@@ -380,35 +498,35 @@ extern "C" cr_status cr_gather_aggregate_fwd(const cr_block_set *blocks, int32_t
                    "ld_bf16 = %lld must be a multiple of 32 in [F, F rounded up to 64]", (long long)ld_bf16);
     if (dry_run()) return CR_OK;
 
-    const int32_t *hdr = blocks->hdr + (int64_t)g * CR_HDR_WORDS;
-    const int32_t *indptr = blocks->indptr + (int64_t)g * (blocks->cap_dst + 1);
-    const int32_t *src_ids = blocks->src_ids + (int64_t)g * blocks->cap_src;
-    const int32_t *ids = blocks->indices + (int64_t)g * blocks->cap_nnz;
-    const int32_t *edge_map = nullptr, *self_map = nullptr;
-    if (indirect) {
-        self_map = src_ids;
-        if (blocks->gather_ids) ids = blocks->gather_ids + (int64_t)g * blocks->cap_nnz;   // per-edge table rows, one level less
-        else edge_map = src_ids;
-    }
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    const int cap = blocks->cap_dst;
-#define CR_FWD(T, LPR, NC) launch_fwd<T, LPR, NC>(cap, hdr, indptr, ids, edge_map, self_map, H_src, ld_src, F, agg, agg_bf16, self_bf16, ld_bf16, s)
-    if (dtype == CR_F32) {
-        if (F <= 64) CR_FWD(float, 16, 1);
-        else if (F <= 128) CR_FWD(float, 32, 1);
-        else if (F <= 256) CR_FWD(float, 64, 1);
-        else if (F <= 512) CR_FWD(float, 64, 2);
-        else if (F <= 768) CR_FWD(float, 64, 3);
-        else CR_FWD(float, 64, 4);
-    } else {
-        if (F <= 128) CR_FWD(uint16_t, 16, 1);
-        else if (F <= 256) CR_FWD(uint16_t, 32, 1);
-        else if (F <= 512) CR_FWD(uint16_t, 64, 1);
-        else CR_FWD(uint16_t, 64, 2);
-    }
-#undef CR_FWD
+    run_fwd(blocks, g, H_src, dtype, ld_src, F, indirect, agg, agg_bf16, self_bf16, ld_bf16, static_cast<hipStream_t>(stream), nullptr);
     CR_LAUNCH_CHECK();
     return CR_OK;
+}
+
+static void run_bwd(const cr_block_set *blocks, int32_t g, const void *d_agg, const void *d_self, int32_t in_dtype, int64_t ld_in,
+                    int32_t F, const void *relu_out, int32_t relu_dtype, int64_t ld_relu, float *d_src, uint16_t *d_src_bf16,
+                    int64_t ld_bf16, hipStream_t s, const GcnFwd *gcn)
+{
+    const int32_t *hdr = blocks->hdr + (int64_t)g * CR_HDR_WORDS;
+    const int32_t *indptr = blocks->indptr + (int64_t)g * (blocks->cap_dst + 1);
+    const int32_t *t_indptr = blocks->t_indptr + (int64_t)g * (blocks->cap_src + 1);
+    const int32_t *t_indices = blocks->t_indices + (int64_t)g * blocks->cap_nnz;
+    const int cap = blocks->cap_src;
+#define CR_BWD(T, LPR, NC) launch_bwd<T, LPR, NC>(cap, hdr, indptr, t_indptr, t_indices, d_agg, d_self, ld_in, F, relu_out, relu_dtype == CR_BF16 ? 1 : 0, ld_relu, d_src, d_src_bf16, ld_bf16, s, gcn)
+    if (in_dtype == CR_F32) {
+        if (F <= 64) CR_BWD(float, 16, 1);
+        else if (F <= 128) CR_BWD(float, 32, 1);
+        else if (F <= 256) CR_BWD(float, 64, 1);
+        else if (F <= 512) CR_BWD(float, 64, 2);
+        else if (F <= 768) CR_BWD(float, 64, 3);
+        else CR_BWD(float, 64, 4);
+    } else {
+        if (F <= 128) CR_BWD(uint16_t, 16, 1);
+        else if (F <= 256) CR_BWD(uint16_t, 32, 1);
+        else if (F <= 512) CR_BWD(uint16_t, 64, 1);
+        else CR_BWD(uint16_t, 64, 2);
+    }
+#undef CR_BWD
 }
 
 extern "C" cr_status cr_gather_aggregate_bwd(const cr_block_set *blocks, int32_t g, const void *d_agg,
@@ -436,27 +554,105 @@ extern "C" cr_status cr_gather_aggregate_bwd(const cr_block_set *blocks, int32_t
                    "ld_bf16 = %lld must be a multiple of 32 in [F, F rounded up to 64]", (long long)ld_bf16);
     if (dry_run()) return CR_OK;
 
-    const int32_t *hdr = blocks->hdr + (int64_t)g * CR_HDR_WORDS;
-    const int32_t *indptr = blocks->indptr + (int64_t)g * (blocks->cap_dst + 1);
-    const int32_t *t_indptr = blocks->t_indptr + (int64_t)g * (blocks->cap_src + 1);
-    const int32_t *t_indices = blocks->t_indices + (int64_t)g * blocks->cap_nnz;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    const int cap = blocks->cap_src;
-#define CR_BWD(T, LPR, NC) launch_bwd<T, LPR, NC>(cap, hdr, indptr, t_indptr, t_indices, d_agg, d_self, ld_in, F, relu_out, relu_dtype == CR_BF16 ? 1 : 0, ld_relu, d_src, d_src_bf16, ld_bf16, s)
-    if (in_dtype == CR_F32) {
-        if (F <= 64) CR_BWD(float, 16, 1);
-        else if (F <= 128) CR_BWD(float, 32, 1);
-        else if (F <= 256) CR_BWD(float, 64, 1);
-        else if (F <= 512) CR_BWD(float, 64, 2);
-        else if (F <= 768) CR_BWD(float, 64, 3);
-        else CR_BWD(float, 64, 4);
-    } else {
-        if (F <= 128) CR_BWD(uint16_t, 16, 1);
-        else if (F <= 256) CR_BWD(uint16_t, 32, 1);
-        else if (F <= 512) CR_BWD(uint16_t, 64, 1);
-        else CR_BWD(uint16_t, 64, 2);
+    run_bwd(blocks, g, d_agg, d_self, in_dtype, ld_in, F, relu_out, relu_dtype, ld_relu, d_src, d_src_bf16, ld_bf16,
+            static_cast<hipStream_t>(stream), nullptr);
+    CR_LAUNCH_CHECK();
+    return CR_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// GCN propagation on the same blocks
+// ------------------------------------------------------------------------------------------------
+extern "C" cr_status cr_graph_gcn_norm(const cr_graph *graph, float *norm, void *stream)
+{
+    CR_REQUIRE(graph != nullptr && graph->indptr != nullptr && graph->n_nodes >= 1, CR_ERR_INVALID_ARG, "graph must carry indptr and at least one node");
+    CR_REQUIRE(norm != nullptr && aligned16(norm), CR_ERR_INVALID_ARG, "norm must be a 16-byte aligned device pointer");
+    if (dry_run()) return CR_OK;
+    hipLaunchKernelGGL(gcn_node_norm_kernel, dim3((unsigned)ceil_div(graph->n_nodes, 256)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       graph->indptr, graph->n_nodes, norm);
+    CR_LAUNCH_CHECK();
+    return CR_OK;
+}
+
+static GcnFwd block_norm_views(const cr_block_set *b, float *blk_norm)
+{
+    GcnFwd v;
+    v.edge_w = blk_norm;
+    v.node_norm = nullptr;
+    v.dst_scale = blk_norm + b->cap_src;
+    v.dst_self = blk_norm + b->cap_src + b->cap_dst;
+    return v;
+}
+
+extern "C" cr_status cr_gcn_block_norm(const cr_block_set *blocks, int32_t g, const float *norm, float *blk_norm, void *stream)
+{
+    cr_status st = check_block_set(blocks, g, false);
+    if (st != CR_OK) return st;
+    CR_REQUIRE(norm && blk_norm, CR_ERR_INVALID_ARG, "norm / blk_norm must not be NULL");
+    if (dry_run()) return CR_OK;
+    const GcnFwd v = block_norm_views(blocks, blk_norm);
+    hipLaunchKernelGGL(gcn_block_norm_kernel, dim3((unsigned)ceil_div(blocks->cap_src, 256)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       blocks->hdr + (int64_t)g * CR_HDR_WORDS, blocks->indptr + (int64_t)g * (blocks->cap_dst + 1),
+                       blocks->src_ids + (int64_t)g * blocks->cap_src, norm, const_cast<float *>(v.edge_w),
+                       const_cast<float *>(v.dst_scale), const_cast<float *>(v.dst_self));
+    CR_LAUNCH_CHECK();
+    return CR_OK;
+}
+
+extern "C" cr_status cr_gcn_aggregate_fwd(const cr_block_set *blocks, int32_t g, const float *norm, const float *blk_norm,
+                                          const void *H_src, int32_t dtype, int64_t ld_src, int32_t F, int32_t indirect,
+                                          float *agg, uint16_t *agg_bf16, int64_t ld_bf16, void *stream)
+{
+    cr_status st = check_block_set(blocks, g, false);
+    if (st != CR_OK) return st;
+    CR_REQUIRE(norm && blk_norm, CR_ERR_INVALID_ARG, "norm / blk_norm must not be NULL");
+    CR_REQUIRE(!indirect || blocks->gather_ids, CR_ERR_UNSUPPORTED, "table addressing by global id needs the block's gather_ids");
+    CR_REQUIRE(H_src != nullptr && aligned16(H_src), CR_ERR_INVALID_ARG, "H_src must be a 16-byte aligned device pointer");
+    CR_REQUIRE(dtype == CR_F32 || dtype == CR_BF16, CR_ERR_INVALID_ARG, "dtype must be CR_F32 or CR_BF16");
+    const int vec = dtype == CR_F32 ? 4 : 8;
+    CR_REQUIRE(F >= 1 && F <= 1024, CR_ERR_UNSUPPORTED, "F = %d outside 1..1024", F);
+    CR_REQUIRE(ld_src >= round_up(F, vec) && ld_src % vec == 0, CR_ERR_INVALID_ARG,
+               "ld_src = %lld must be a multiple of %d and cover F rounded up to it", (long long)ld_src, vec);
+    CR_REQUIRE(agg || agg_bf16, CR_ERR_INVALID_ARG, "no output requested");
+    CR_REQUIRE(aligned16(agg) && aligned16(agg_bf16), CR_ERR_INVALID_ARG, "outputs must be 16-byte aligned");
+    if (agg_bf16)
+        CR_REQUIRE(ld_bf16 % 32 == 0 && ld_bf16 >= F && ld_bf16 <= round_up(F, 64), CR_ERR_INVALID_ARG,
+                   "ld_bf16 = %lld must be a multiple of 32 in [F, F rounded up to 64]", (long long)ld_bf16);
+    if (dry_run()) return CR_OK;
+    GcnFwd v = block_norm_views(blocks, const_cast<float *>(blk_norm));
+    if (indirect) { v.edge_w = nullptr; v.node_norm = norm; }       // per-edge ids are global: weights by node
+    run_fwd(blocks, g, H_src, dtype, ld_src, F, indirect, agg, agg_bf16, nullptr, ld_bf16, static_cast<hipStream_t>(stream), &v);
+    CR_LAUNCH_CHECK();
+    return CR_OK;
+}
+
+extern "C" cr_status cr_gcn_aggregate_bwd(const cr_block_set *blocks, int32_t g, const float *blk_norm, const void *d_out,
+                                          int32_t in_dtype, int64_t ld_in, int32_t F, const void *relu_out, int32_t relu_dtype,
+                                          int64_t ld_relu, float *d_src, uint16_t *d_src_bf16, int64_t ld_bf16, void *stream)
+{
+    cr_status st = check_block_set(blocks, g, true);
+    if (st != CR_OK) return st;
+    CR_REQUIRE(blk_norm != nullptr, CR_ERR_INVALID_ARG, "blk_norm must not be NULL");
+    CR_REQUIRE(d_out != nullptr && aligned16(d_out), CR_ERR_INVALID_ARG, "d_out must be a 16-byte aligned device pointer");
+    CR_REQUIRE(F >= 1 && F <= 1024, CR_ERR_UNSUPPORTED, "F = %d outside 1..1024", F);
+    CR_REQUIRE(in_dtype == CR_F32 || in_dtype == CR_BF16, CR_ERR_INVALID_ARG, "in_dtype must be CR_F32 or CR_BF16");
+    const int in_vec = in_dtype == CR_BF16 ? 8 : 4;
+    CR_REQUIRE(ld_in >= round_up(F, in_vec) && ld_in % in_vec == 0, CR_ERR_INVALID_ARG, "ld_in must be a multiple of %d covering F", in_vec);
+    if (relu_out) {
+        CR_REQUIRE(relu_dtype == CR_F32 || relu_dtype == CR_BF16, CR_ERR_INVALID_ARG, "relu_dtype must be CR_F32 or CR_BF16");
+        CR_REQUIRE(aligned16(relu_out) && ld_relu >= round_up(F, 4) && ld_relu % 4 == 0, CR_ERR_INVALID_ARG, "relu_out must be aligned with ld_relu a multiple of 4 covering F");
+        CR_REQUIRE(!(in_dtype == CR_BF16 && relu_dtype == CR_BF16) || ld_relu % 8 == 0, CR_ERR_INVALID_ARG,
+                   "with bf16 gradients a bf16 relu_out needs ld_relu to be a multiple of 8");
     }
-#undef CR_BWD
+    CR_REQUIRE(d_src || d_src_bf16, CR_ERR_INVALID_ARG, "no output requested");
+    CR_REQUIRE(aligned16(d_src) && aligned16(d_src_bf16), CR_ERR_INVALID_ARG, "outputs must be 16-byte aligned");
+    if (d_src_bf16)
+        CR_REQUIRE(ld_bf16 % 32 == 0 && ld_bf16 >= F && ld_bf16 <= round_up(F, 64), CR_ERR_INVALID_ARG,
+                   "ld_bf16 = %lld must be a multiple of 32 in [F, F rounded up to 64]", (long long)ld_bf16);
+    if (dry_run()) return CR_OK;
+    const GcnFwd v = block_norm_views(blocks, const_cast<float *>(blk_norm));
+    run_bwd(blocks, g, d_out, d_out, in_dtype, ld_in, F, relu_out, relu_dtype, ld_relu, d_src, d_src_bf16, ld_bf16,
+            static_cast<hipStream_t>(stream), &v);
     CR_LAUNCH_CHECK();
     return CR_OK;
 }
