@@ -215,13 +215,13 @@ def layer_dims(cfg: WorkloadConfig):
     return dims
 
 
-def init_weights(cfg: WorkloadConfig, seed: int = 0):
-    """Glorot-uniform [2*F_in, F_out] (rows: W_self then W_neigh) and zero biases, float32."""
+def init_weights(cfg: WorkloadConfig, seed: int = 0, n_operands: int = 2):
+    """Glorot-uniform [n_operands*F_in, F_out] (two operands: rows of W_self then W_neigh) and zero biases, float32."""
     rng = np.random.default_rng([seed, 0x3E16, 5])
     out = []
     for fin, fout in layer_dims(cfg):
         a = np.sqrt(6.0 / (fin + fout))
-        W = rng.uniform(-a, a, size=(2 * fin, fout)).astype(np.float32)
+        W = rng.uniform(-a, a, size=(n_operands * fin, fout)).astype(np.float32)
         b = np.zeros(fout, dtype=np.float32)
         out.append((W, b))
     return out

@@ -22,7 +22,7 @@ class Trainer:
     def __init__(self, workload: synth.Workload, group_size: int = 16, lr: float = 0.01,
                  weight_decay: float = 5e-4, seed: int = 0, device: str = "cuda", weights=None,
                  relabel_input: bool = False, edge_classes: bool = True, host_features: bool = False,
-                 cache_rows: int = 0, cache_ways: int = 16):
+                 cache_rows: int = 0, cache_ways: int = 16, model: str = "sage"):
         import torch
         self.torch = torch
         self.w = workload
@@ -32,6 +32,10 @@ class Trainer:
         self.B = cfg.batch_size
         self.G = group_size
         self.lr, self.wd, self.seed = lr, weight_decay, seed
+        assert model in ("sage", "gcn")
+        self.model = model
+        self.n_op = 2 if model == "sage" else 1
+        assert model == "sage" or not (host_features or cache_rows), "the GCN path reads the resident table"
         # The layer-0 gather reads the feature table through per-edge global ids and the features take no
         # gradient, so nothing in a training step needs the input frontier de-duplicated or relabelled
         # (relabel_input=True asks for it anyway, e.g. to count the distinct input nodes of a batch).
@@ -67,8 +71,8 @@ class Trainer:
         self.n_batches = -(-self.n_train // self.B)
 
         # parameters
-        weights = weights if weights is not None else synth.init_weights(cfg, seed)
-        self.layers: List[B.SageLayer] = [B.SageLayer(W, b, device) for (W, b) in weights]
+        weights = weights if weights is not None else synth.init_weights(cfg, seed, self.n_op)
+        self.layers: List[B.SageLayer] = [B.SageLayer(W, b, device, self.n_op) for (W, b) in weights]
         for layer in self.layers:
             layer.refresh()
 
@@ -96,7 +100,11 @@ class Trainer:
         self.dz = [b16(self.blocks[l].cap_dst, self.layers[l].N_pad) for l in range(self.L)]
         # input gradients [d_self | d_agg] of the layers above the first, kept in bf16: the scatter back over the
         # block reads them once per edge, so their width is what that kernel's traffic is made of
-        self.d_in = [b16(self.blocks[l].cap_dst, 2 * self.layers[l].F_pad) if l >= 1 else None for l in range(self.L)]
+        self.d_in = [b16(self.blocks[l].cap_dst, self.n_op * self.layers[l].F_pad) if l >= 1 else None for l in range(self.L)]
+        if model == "gcn":     # per-node normalisation of the graph, per-block normalisation scratch of every layer
+            self.gcn_norm = B.cr_graph_gcn_norm(self.graph)
+            self.blk_norm = [torch.zeros(self.blocks[l].cap_src + 2 * self.blocks[l].cap_dst, dtype=torch.float32, device=device)
+                             for l in range(self.L)]
         self.ws_bwd = [torch.empty(B.cr_sage_linear_bwd_workspace_bytes(self.layers[l].F_in, self.layers[l].F_out, self.blocks[l].cap_dst),
                                    dtype=torch.uint8, device=device) for l in range(self.L)]
         self.loss = torch.zeros(1, dtype=torch.float32, device=device)
@@ -178,6 +186,8 @@ class Trainer:
             slot = self.block_slots.index(self.blocks)
         self.self0, self.agg[0] = self.self0_bufs[buf], self.agg0_bufs[buf]
         L, blocks, layers = self.L, self.blocks, self.layers
+        if self.model == "gcn":
+            return self._forward_batch_gcn(g)
         for l in range(L):
             blk, lay = blocks[l], layers[l]
             if l == 0:
@@ -195,6 +205,37 @@ class Trainer:
             B.cr_sage_linear_fwd(lay, blk.hdr_ptr(g), blk.cap_dst, h_self, self.agg[l], ld_in, l < L - 1,
                                  self.out[l], self.out_b[l])
 
+    def _forward_batch_gcn(self, g: int):
+        """GCN layers: normalised aggregation over the block (the destination's own row included), one-operand layer."""
+        L, blocks, layers = self.L, self.blocks, self.layers
+        self.wait_weights()
+        for l in range(L):
+            blk, lay = blocks[l], layers[l]
+            B.cr_gcn_block_norm(blk, g, self.gcn_norm, self.blk_norm[l])
+            if l == 0:
+                B.cr_gcn_aggregate_fwd(blk, g, self.gcn_norm, self.blk_norm[0], self.table_ptr, self.feat_dtype, self.ld_table,
+                                       self.cfg.n_feat, True, None, self.agg[0], lay.F_pad)
+                ld_in = lay.F_pad
+            else:
+                prev = layers[l - 1]
+                B.cr_gcn_aggregate_fwd(blk, g, self.gcn_norm, self.blk_norm[l], self.out_b[l - 1], B.CR_BF16, prev.N_pad, prev.F_out,
+                                       False, None, self.agg[l], prev.N_pad)
+                ld_in = prev.N_pad
+            B.cr_sage_linear_fwd(lay, blk.hdr_ptr(g), blk.cap_dst, None, self.agg[l], ld_in, l < L - 1, self.out[l], self.out_b[l])
+
+    def _backward_batch_gcn(self, g: int, dW_out, db_out):
+        L, blocks, layers = self.L, self.blocks, self.layers
+        for l in range(L - 1, -1, -1):
+            blk, lay = blocks[l], layers[l]
+            ld_in = lay.F_pad if l == 0 else layers[l - 1].N_pad
+            grads = (None if dW_out is None else dW_out[l], None if db_out is None else db_out[l])
+            B.cr_sage_linear_bwd(lay, blk.hdr_ptr(g), blk.cap_dst, None, self.agg[l], ld_in, self.dz[l], self.lr, self.wd,
+                                 None, None, self.ws_bwd[l], *grads, d_in_bf16=self.d_in[l])
+            if l >= 1:
+                prev = layers[l - 1]
+                B.cr_gcn_aggregate_bwd(blk, g, self.blk_norm[l], self.d_in[l], lay.F_pad, lay.F_in, self.out_b[l - 1], prev.N_pad,
+                                       None, self.dz[l - 1], prev.N_pad, relu_dtype=B.CR_BF16, in_dtype=B.CR_BF16)
+
     def train_batch(self, g: int, dW_out=None, db_out=None, slot: Optional[int] = None, buf: int = 0, gather0: bool = True):
         """Forward, loss, backward and SGD for mini-batch g of a sampled group (current stream)."""
         self.forward_batch(g, slot, buf, gather0)
@@ -204,6 +245,8 @@ class Trainer:
         B.cr_softmax_xent(top.hdr_ptr(g), top.cap_dst, self.out[L - 1], layers[L - 1].N_pad, self.cfg.n_classes,
                           self.labels, top.src_ids_ptr(g), self.loss, self.row_loss, None, self.dz[L - 1])
         # backward + SGD
+        if self.model == "gcn":
+            return self._backward_batch_gcn(g, dW_out, db_out)
         side = self.stream_weights if self.weights_on_side_stream else None
         for l in range(L - 1, -1, -1):
             blk, lay = blocks[l], layers[l]

@@ -43,3 +43,36 @@ def oracle_train_step(graph, table, n_feat, labels, roots, fanouts, p, seed, epo
             d_src = oracle.gather_mean_bwd(blocks[l], d_agg, d_self)
             dz = d_src * (oracle.round_bf16(outs[l - 1]) > 0)
     return dict(blocks=blocks, loss=loss, logits=outs[L - 1], outs=outs, grads=grads, params=new_params)
+
+
+def oracle_train_step_gcn(graph, table, n_feat, labels, roots, fanouts, p, seed, epoch, batch, params, lr, wd, pos_map=None):
+    """The same step for GCN layers: params are (W float64 [F_in, F_out], b).  The dense part goes through the
+    two-operand oracle with a zero self operand and zero W_self rows (adds exact zeros)."""
+    L = len(fanouts)
+    deg = np.diff(graph[0])
+    blocks = oracle.sample_blocks(graph, roots, fanouts, p, False, seed, epoch, batch, pos_map)
+    aggs, outs = [None] * L, [None] * L
+    two = lambda W: np.vstack([np.zeros_like(W), W])
+    for l in range(L):
+        W, b = params[l]
+        if l == 0:
+            aggs[0] = oracle.gcn_aggregate(blocks[0], table, deg, indirect=True, F=n_feat)
+        else:
+            prev = np.ascontiguousarray(oracle.round_bf16(outs[l - 1]).astype(np.float32))
+            aggs[l] = oracle.gcn_aggregate(blocks[l], prev, deg, indirect=False)
+        outs[l] = oracle.sage_linear_fwd(np.zeros_like(aggs[l]), aggs[l], two(W), b, l < L - 1, True)
+    loss, dz = oracle.softmax_xent(outs[L - 1], labels[np.asarray(roots)])
+    grads, new_params = [None] * L, [None] * L
+    for l in range(L - 1, -1, -1):
+        W, b = params[l]
+        F_in = W.shape[0]
+        dW2, _, _, d_agg = oracle.sage_linear_bwd(np.zeros_like(aggs[l]), aggs[l], two(W), outs[l], dz, False, True, need_dx=l > 0)
+        dW = dW2[F_in:]
+        db = oracle.round_bf16(dz).sum(axis=0)
+        grads[l] = (dW, db)
+        W_new2, b_new = oracle.sgd_step(two(W), dW2, b, db, lr, wd)
+        new_params[l] = (W_new2[F_in:], b_new)
+        if l > 0:
+            d_src = oracle.gcn_aggregate_bwd(blocks[l], oracle.round_bf16(d_agg), deg)
+            dz = d_src * (oracle.round_bf16(outs[l - 1]) > 0)
+    return dict(blocks=blocks, loss=loss, logits=outs[L - 1], outs=outs, grads=grads, params=new_params)

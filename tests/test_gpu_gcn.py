@@ -109,3 +109,51 @@ def test_gcn_bwd(tiny_workload, F, in_dtype):
     gb = bf16_tensor_to_float(d_src_b)
     assert_close(gb[:blk.n_src, :F], want, RTOL_BF16, "gcn d_src bf16", RTOL / RTOL_BF16 * scale)
     assert np.all(gb[:blk.n_src, F:] == 0)
+
+
+def test_gcn_train_steps_match_oracle(tiny_workload):
+    """Three consecutive GCN training steps (sampling, propagation, one-operand layers, loss, backward, SGD)."""
+    import torch
+    from paper_2504_18082_amd.trainer import Trainer
+    from oracle_step import oracle_train_step_gcn
+    w, seed, epoch, p, lr, wd = tiny_workload, 0, 3, 0.9, 0.05, 5e-4
+    cfg = w.cfg
+    weights = synth.init_weights(cfg, seed, n_operands=1)
+    tr = Trainer(w, group_size=2, lr=lr, weight_decay=wd, seed=seed, weights=weights, model="gcn")
+    tr.build_batches(oracle.COMM_RAND, 6, epoch)
+    perm = oracle.build_batches(oracle.COMM_RAND, 6, seed, epoch, w.train_ids, w.comm, cfg.n_comm)
+    params = [(W.astype(np.float64), b.astype(np.float64)) for W, b in weights]
+    pos = np.full(cfg.n_nodes, -1, dtype=np.int32)
+    dW_out = [torch.zeros_like(l.W) for l in tr.layers]
+    db_out = [torch.zeros(l.F_out, dtype=torch.float32, device="cuda") for l in tr.layers]
+    done = 0
+    while done < 3:
+        n = min(2, 3 - done)
+        tr.sample_group(done, n, p, epoch)
+        for g in range(n):
+            b = done + g
+            print(f"gcn step batch={b}", flush=True)
+            tr.train_batch(g, dW_out, db_out)
+            torch.cuda.synchronize()
+            roots = perm[b * cfg.batch_size:(b + 1) * cfg.batch_size]
+            ref = oracle_train_step_gcn(w.graph, w.features, cfg.n_feat, w.labels, roots, cfg.fanouts, p, seed, epoch, b, params, lr, wd, pos)
+            assert abs(float(tr.loss.cpu()[0]) - ref["loss"]) <= 1e-3 * abs(ref["loss"])
+            assert_close(tr.out[tr.L - 1].cpu().numpy()[:len(roots), :cfg.n_classes], ref["logits"], 2e-2, f"logits batch {b}")
+            for l in range(tr.L):
+                assert_close(dW_out[l].cpu().numpy(), ref["grads"][l][0], 2e-2, f"dW layer {l} batch {b}")
+                assert_close(db_out[l].cpu().numpy(), ref["grads"][l][1], 2e-2, f"db layer {l} batch {b}")
+                assert_close(tr.layers[l].W.cpu().numpy(), ref["params"][l][0], 2e-2, f"W layer {l} batch {b}")
+            params = [(l.W.cpu().numpy().astype(np.float64), l.bias.cpu().numpy()[:l.F_out].astype(np.float64)) for l in tr.layers]
+        done += n
+
+
+def test_gcn_fit_on_tiny(tiny_workload):
+    import torch
+    from paper_2504_18082_amd.trainer import Trainer
+    w = tiny_workload
+    tr = Trainer(w, group_size=8, lr=0.1, seed=0, model="gcn")
+    val = torch.from_numpy(w.val_ids).cuda()
+    loss0, acc0 = tr.evaluate(val, 0)
+    hist = tr.fit(oracle.COMM_RAND, 6, 0.9, val, max_epochs=10, patience=6, lr_patience=3)
+    print("gcn val acc", [round(v, 4) for v in hist.val_acc], flush=True)
+    assert min(hist.val_loss) < 0.8 * loss0 and max(hist.val_acc) > 3.0 / w.cfg.n_classes
