@@ -38,6 +38,7 @@ def main(argv=None):
     ap.add_argument("--weight-decay", type=float, default=5e-4)
     ap.add_argument("--group", type=int, default=16)
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--model", default="sage", choices=["sage", "gcn"])
     args = ap.parse_args(argv)
 
     import numpy as np
@@ -54,9 +55,9 @@ def main(argv=None):
     val = torch.from_numpy(w.val_ids).cuda()
     for text in args.settings:
         policy, mix, p = parse_setting(text, n_comm_train)
-        tr = Trainer(w, group_size=args.group, lr=args.lr, weight_decay=args.weight_decay, seed=args.seed)
+        tr = Trainer(w, group_size=args.group, lr=args.lr, weight_decay=args.weight_decay, seed=args.seed, model=args.model)
         hist = tr.fit(policy, mix, p, val, args.max_epochs, args.patience, args.lr_patience)
-        out = dict(workload=cfg.name, setting=text, mix_count=mix, **hist.summary())
+        out = dict(workload=cfg.name, model=args.model, setting=text, mix_count=mix, **hist.summary())
         out["val_acc_by_epoch"] = [round(v, 4) for v in hist.val_acc]
         print(json.dumps(out), flush=True)
         del tr

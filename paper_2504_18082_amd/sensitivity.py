@@ -52,6 +52,7 @@ def main(argv=None):
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--group", type=int, default=16)
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--model", default="sage", choices=["sage", "gcn"])
     ap.add_argument("--settings", nargs="+", default=DEFAULT_SETTINGS)
     args = ap.parse_args(argv)
 
@@ -69,8 +70,8 @@ def main(argv=None):
                 cfg.n_feat = width
             w = synth.make_workload(cfg, args.seed)
             n_comm_train = int(np.unique(w.comm[w.train_ids]).size)
-            tr = Trainer(w, group_size=args.group, seed=args.seed)
-            out = dict(workload=cfg.name, n_nodes=cfg.n_nodes, n_feat=cfg.n_feat,
+            tr = Trainer(w, group_size=args.group, seed=args.seed, model=args.model)
+            out = dict(workload=cfg.name, model=args.model, n_nodes=cfg.n_nodes, n_feat=cfg.n_feat,
                        table_MB=round(w.features.nbytes / 1e6, 1), steps=args.steps, settings={})
             for i, name in enumerate(args.settings):
                 policy, mix, p = parse_setting(name, n_comm_train)

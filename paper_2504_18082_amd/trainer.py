@@ -213,8 +213,14 @@ class Trainer:
             blk, lay = blocks[l], layers[l]
             B.cr_gcn_block_norm(blk, g, self.gcn_norm, self.blk_norm[l])
             if l == 0:
+                if self.time_gather0:
+                    ev0, ev1 = self.torch.cuda.Event(enable_timing=True), self.torch.cuda.Event(enable_timing=True)
+                    ev0.record()
                 B.cr_gcn_aggregate_fwd(blk, g, self.gcn_norm, self.blk_norm[0], self.table_ptr, self.feat_dtype, self.ld_table,
                                        self.cfg.n_feat, True, None, self.agg[0], lay.F_pad)
+                if self.time_gather0:
+                    ev1.record()
+                    self.gather0_events.append((ev0, ev1))
                 ld_in = lay.F_pad
             else:
                 prev = layers[l - 1]
