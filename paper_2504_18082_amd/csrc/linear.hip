@@ -175,30 +175,67 @@ __device__ __forceinline__ void gemm_nt_body(const NtArgs &a, uint16_t (&As)[2][
         nt_step<NTILES>(st, f, buf, As, Bs, acc);
     }
 
-    const int m = m0 + wave * 32 + lr;
-    if (m >= M) return;
+    // Epilogue through LDS (the staging tiles are free after one more barrier): a lane holds 4-column pieces of one
+    // row, which would go out as 8/16-byte stores scattered over 32 rows; staged, a wave writes whole 128-byte row
+    // segments.  Each wave uses its own quarter of As.
+    static_assert(NTILES == 2, "the staged epilogue is laid out for a 32 x 64 wave tile");
+    __syncthreads();
+    char *region = reinterpret_cast<char *>(&As[0][0][0]) + wave * (2 * 128 * LDS_ROW * 2 / 4);     // 5120 bytes
+    const int mw = m0 + wave * 32;
+    float v[2][4][4];
 #pragma unroll
-    for (int t = 0; t < NTILES; ++t)
+    for (int t = 0; t < 2; ++t)
 #pragma unroll
         for (int grp = 0; grp < 4; ++grp) {
             const int n = n0 + t * 32 + 8 * grp + 4 * half;
             const float4 bq = a.bias ? *reinterpret_cast<const float4 *>(a.bias + n) : make_float4(0.f, 0.f, 0.f, 0.f);
-            float v[4] = {acc[t][grp * 4 + 0] + bq.x, acc[t][grp * 4 + 1] + bq.y,
-                          acc[t][grp * 4 + 2] + bq.z, acc[t][grp * 4 + 3] + bq.w};
+            v[t][grp][0] = acc[t][grp * 4 + 0] + bq.x; v[t][grp][1] = acc[t][grp * 4 + 1] + bq.y;
+            v[t][grp][2] = acc[t][grp * 4 + 2] + bq.z; v[t][grp][3] = acc[t][grp * 4 + 3] + bq.w;
             if (a.relu) {
 #pragma unroll
-                for (int i = 0; i < 4; ++i) v[i] = v[i] < 0.f ? 0.f : v[i];
-            }
-            if (a.C0) {
-                float *dst = n < a.N0 ? a.C0 + (int64_t)m * a.ldc + n : a.C1 + (int64_t)m * a.ldc + (n - a.N0);
-                *reinterpret_cast<float4 *>(dst) = make_float4(v[0], v[1], v[2], v[3]);
-            }
-            if (a.Cb) {
-                const uint32_t lo = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
-                const uint32_t hi = (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16);
-                *reinterpret_cast<uint2 *>(a.Cb + (int64_t)m * a.ldcb + n) = make_uint2(lo, hi);
+                for (int i = 0; i < 4; ++i) v[t][grp][i] = v[t][grp][i] < 0.f ? 0.f : v[t][grp][i];
             }
         }
+    if (a.Cb) {      // both 32-column halves at once: rows of 64 bf16 (+8 of padding)
+        uint16_t (*ob)[72] = reinterpret_cast<uint16_t (*)[72]>(region);
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int grp = 0; grp < 4; ++grp) {
+                const uint32_t lo = (uint32_t)f32_to_bf16(v[t][grp][0]) | ((uint32_t)f32_to_bf16(v[t][grp][1]) << 16);
+                const uint32_t hi = (uint32_t)f32_to_bf16(v[t][grp][2]) | ((uint32_t)f32_to_bf16(v[t][grp][3]) << 16);
+                *reinterpret_cast<uint2 *>(&ob[lr][t * 32 + 8 * grp + 4 * half]) = make_uint2(lo, hi);
+            }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int c = it * 64 + lane, row = c >> 3, c8 = (c & 7) * 8;
+            const u32x4v x = *reinterpret_cast<const u32x4v *>(&ob[row][c8]);
+            if (mw + row < M) *reinterpret_cast<u32x4v *>(a.Cb + (int64_t)(mw + row) * a.ldcb + n0 + c8) = x;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    }
+    if (a.C0) {      // one 32-column half at a time: rows of 32 floats (+4 of padding)
+        float (*of)[36] = reinterpret_cast<float (*)[36]>(region);
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+#pragma unroll
+            for (int grp = 0; grp < 4; ++grp)
+                *reinterpret_cast<float4 *>(&of[lr][8 * grp + 4 * half]) = make_float4(v[t][grp][0], v[t][grp][1], v[t][grp][2], v[t][grp][3]);
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+#pragma unroll
+            for (int it = 0; it < 4; ++it) {
+                const int c = it * 64 + lane, row = c >> 3, c4 = (c & 7) * 4;
+                const float4 x = *reinterpret_cast<const float4 *>(&of[row][c4]);
+                const int n = n0 + t * 32 + c4;
+                if (mw + row < M) {
+                    float *dst = n < a.N0 ? a.C0 + (int64_t)(mw + row) * a.ldc + n : a.C1 + (int64_t)(mw + row) * a.ldc + (n - a.N0);
+                    *reinterpret_cast<float4 *>(dst) = x;
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        }
+    }
 }
 
 // Register budget: up to four waves per SIMD.  Four K steps of prefetch at this occupancy measured faster
