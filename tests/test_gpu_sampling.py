@@ -166,3 +166,42 @@ def test_edge_class_bits(torch_mod, tiny_workload, arxiv_workload):
         print(f"case edge bits p={p} strict={strict}", flush=True)
         layers, nb = run_gpu(torch_mod, dg, roots, w.cfg.fanouts, p, strict, 0, 1, 3, 1024)
         compare(layers, nb, w.graph, roots, w.cfg.fanouts, p, strict, 0, 1, 3, 1024, f"edge bits p={p}")
+
+
+def many_hubs_graph(seed=0, n_hubs=48, n_leaves=6000, n_comm=4):
+    """Hubs of degree 65..3000 whose neighbours are 0 %, a few, half, most or all in the hub's own community
+    (symmetrised); exercises every long-row path of the selection kernels."""
+    rng = np.random.default_rng(seed)
+    n = n_hubs + n_leaves
+    comm = np.concatenate([rng.integers(0, n_comm, n_hubs), rng.integers(0, n_comm, n_leaves)]).astype(np.int32)
+    leaves_of = [n_hubs + np.nonzero(comm[n_hubs:] == c)[0] for c in range(n_comm)]
+    others_of = [n_hubs + np.nonzero(comm[n_hubs:] != c)[0] for c in range(n_comm)]
+    rows, cols = [], []
+    for h in range(n_hubs):
+        deg = int(rng.choice([65, 66, 100, 128, 129, 255, 257, 700, 3000]))
+        frac = float(rng.choice([0.0, 0.02, 0.1, 0.5, 0.9, 1.0]))
+        n_in = min(int(round(deg * frac)), len(leaves_of[comm[h]]))
+        n_out = min(deg - n_in, len(others_of[comm[h]]))
+        nb = np.concatenate([rng.choice(leaves_of[comm[h]], n_in, replace=False), rng.choice(others_of[comm[h]], n_out, replace=False)])
+        rows += [np.full(len(nb), h), nb]
+        cols += [nb, np.full(len(nb), h)]
+    r, c = np.concatenate(rows), np.concatenate(cols)
+    key = np.unique(r.astype(np.int64) * n + c)
+    r, c = key // n, (key % n).astype(np.int32)
+    indptr = np.zeros(n + 1, dtype=np.int64)
+    np.cumsum(np.bincount(r, minlength=n), out=indptr[1:])
+    return (indptr, c, comm), n_hubs
+
+
+@pytest.mark.parametrize("edge_classes", [True, False])
+def test_long_rows_all_paths(torch_mod, edge_classes):
+    graph, n_hubs = many_hubs_graph()
+    dg = DeviceGraph(torch_mod, graph, 4, edge_classes=edge_classes)
+    roots = np.arange(n_hubs, dtype=np.int32)
+    for p in (0.5, 0.75, 0.9, 0.99, 1.0):
+        for fan in ([5], [15], [25], [64]):
+            print(f"case long rows p={p} fanout={fan} bits={edge_classes}", flush=True)
+            layers, nb = run_gpu(torch_mod, dg, roots, fan, p, False, 5, 1, 0, 16)
+            compare(layers, nb, graph, roots, fan, p, False, 5, 1, 0, 16, f"long rows p={p} {fan}")
+    layers, nb = run_gpu(torch_mod, dg, roots, [15], 1.0, True, 5, 1, 0, 16)
+    compare(layers, nb, graph, roots, [15], 1.0, True, 5, 1, 0, 16, "long rows strict")
