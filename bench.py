@@ -6,8 +6,8 @@ sub-graph sampling, feature gather + mean aggregation, SAGE projections on the m
 backward and SGD.  Inputs (graph, feature table, labels, weights) are resident in HBM before the
 timed region.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload arxiv|tiny|reddit|products]
-                    [--group G] [--no-sweep] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload arxiv|tiny|reddit|products|papers]
+                    [--scale S] [--group G] [--no-sweep] [--no-cpu-baseline] [--no-input-stats]
 """
 from __future__ import annotations
 

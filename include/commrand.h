@@ -6,7 +6,10 @@
  * The calls follow Algorithm 1 of the paper (mini-batch training of an L-layer
  * GNN): Step-1 root node partitioning (cr_build_batches), Step-2 sub-graph
  * construction (cr_sample_blocks), then training on the sub-graph
- * (cr_gather_aggregate_*, cr_sage_linear_*, cr_softmax_xent).
+ * (cr_gather_aggregate_*, cr_sage_linear_*, cr_softmax_xent).  Further down:
+ * the validation pass (cr_count_correct), GCN on the same blocks (cr_gcn_*) and
+ * the software-managed feature cache of the paper's sensitivity study
+ * (cr_cache_*, cr_stage_rows, cr_host_alloc).
  *
  * Conventions
  *  - Every function returns a cr_status; cr_last_error() gives the text of the
@@ -14,7 +17,8 @@
  *  - "device" pointers are HIP device memory on the current device; "host"
  *    pointers are ordinary memory.  The library never allocates or frees device
  *    memory: graph, table, outputs and workspaces are caller-owned and only
- *    borrowed for the duration of the enqueued work.
+ *    borrowed for the duration of the enqueued work.  (The one allocation the
+ *    library makes, on request, is pinned host memory: cr_host_alloc.)
  *  - All work is enqueued on the given hipStream_t (passed as void*, NULL = the
  *    default stream) and the call returns without synchronising, except where
  *    stated.  Arguments are validated on the host before anything is launched;

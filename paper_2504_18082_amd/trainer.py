@@ -2,10 +2,15 @@
 sampling, then forward / loss / backward / SGD per mini-batch).  Call sequencing and buffer
 ownership only -- every arithmetic step runs inside libcommrand.so.
 
-Sampling and the layer-0 feature gather do not depend on the weights, so `run_epoch` issues them on
-two side streams (default priority) ahead of the training stream: while mini-batch b trains, the
-features of b+1 are being gathered and the next group of mini-batches is being sampled.  Block
-storage and the layer-0 operand buffers are double-buffered for this; HIP events order the hand-offs.
+`run_epoch_serial` (the default everywhere) issues every call on the current stream.  `run_epoch` is
+the optional overlapped schedule: sampling and the layer-0 feature gather do not depend on the
+weights, so it issues them on side streams (default priority) ahead of the training stream; block
+storage and the layer-0 operand buffers are double-buffered for this and HIP events order the
+hand-offs.  It gives the same weights bit for bit and measured no faster on one MI355X.
+
+Beyond the GraphSAGE path the same driver runs GCN layers (`model="gcn"`), the validation pass and
+training protocol of the paper (`evaluate`, `fit`), and a feature store in pinned host memory with or
+without the software-managed cache in front of it (`host_features`, `cache_rows`).
 """
 from __future__ import annotations
 
