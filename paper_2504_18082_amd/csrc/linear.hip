@@ -11,6 +11,9 @@ namespace cr {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4v __attribute__((ext_vector_type(4)));
+typedef short v4s16 __attribute__((ext_vector_type(4)));
+
+constexpr int TN_ROW = 144;   // staged row of the TN product: 128 columns + 16 of padding (288 bytes)
 
 constexpr int LDS_ROW = 40;   // 32 bf16 of payload + 8 of padding per staged row (80 bytes)
 
@@ -281,8 +284,11 @@ struct TnArgs {
 
 __global__ __launch_bounds__(256) void gemm_tn_kernel(TnArgs a)
 {
-    // [buffer][operand: 0 = A, 1 = Z][group of four m][column] -> four consecutive m of one column (8 bytes)
-    __shared__ __attribute__((aligned(16))) uint2 T[2][2][8][128];
+    // [buffer][operand: 0 = A, 1 = Z][m][column]: the tiles are staged as they come from memory (row-major);
+    // the transposition the MFMA operands need (eight consecutive m of one column per lane) is done by the LDS
+    // transpose read of gfx950.  Row stride 288 bytes: the four 32-byte row pieces a 16-lane group reads
+    // fall into disjoint banks.
+    __shared__ __attribute__((aligned(16))) uint16_t T[2][2][32][TN_ROW];
     const int M = min(a.hdr[CR_HDR_N_DST], a.max_rows);
     // the tiles of one split run next to each other on one XCD (they share the split's rows of A and Z);
     // splits past the last row stay inactive, and the reduction skips them too
@@ -326,33 +332,33 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(TnArgs a)
             r[i] = make_uint4(v[0], v[1], v[2], v[3]);
         }
     };
-    // A thread holds an 8-column chunk of four consecutive rows; transposed, that is eight 8-byte cells
-    // (four m of one column), contiguous along the column index.  They go out as four 16-byte stores; the
-    // store order is rotated by the thread's chunk index so that neighbouring threads (64 bytes apart)
-    // do not hit the same LDS banks in the same instruction.
-    const int crot = st & 3;
+    // a thread holds an 8-column chunk of four consecutive rows: four plain 16-byte stores
+    float cacc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};      // column sums of Z over this thread's rows (kt == 0 only)
+    const bool do_colsum = kt == 0 && op == 1;
     auto stage = [&](const uint4 (&r)[4], int buf) {
-        // pair q = columns 2q and 2q+1; word q of a row holds column 2q (low half) and 2q+1 (high half)
-#define CR_PAIR(q, f)                                                                                   \
-        const uint32_t p##q##x = (r[0].f & 0xFFFFu) | (r[1].f << 16), p##q##y = (r[2].f & 0xFFFFu) | (r[3].f << 16), \
-                       p##q##z = (r[0].f >> 16) | (r[1].f & 0xFFFF0000u), p##q##w = (r[2].f >> 16) | (r[3].f & 0xFFFF0000u);
-        CR_PAIR(0, x) CR_PAIR(1, y) CR_PAIR(2, z) CR_PAIR(3, w)
-#undef CR_PAIR
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int q = (i + crot) & 3;
-            const bool q1 = q == 1, q2 = q == 2, q3 = q == 3;
-            const uint32_t vx = q3 ? p3x : (q2 ? p2x : (q1 ? p1x : p0x));
-            const uint32_t vy = q3 ? p3y : (q2 ? p2y : (q1 ? p1y : p0y));
-            const uint32_t vz = q3 ? p3z : (q2 ? p2z : (q1 ? p1z : p0z));
-            const uint32_t vw = q3 ? p3w : (q2 ? p2w : (q1 ? p1w : p0w));
-            *reinterpret_cast<uint4 *>(&T[buf][op][mg][sc + 2 * q]) = make_uint4(vx, vy, vz, vw);
+        for (int i = 0; i < 4; ++i) *reinterpret_cast<uint4 *>(&T[buf][op][mg * 4 + i][sc]) = r[i];
+        if (do_colsum) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                cacc[0] += __uint_as_float(r[i].x << 16); cacc[1] += __uint_as_float(r[i].x & 0xFFFF0000u);
+                cacc[2] += __uint_as_float(r[i].y << 16); cacc[3] += __uint_as_float(r[i].y & 0xFFFF0000u);
+                cacc[4] += __uint_as_float(r[i].z << 16); cacc[5] += __uint_as_float(r[i].z & 0xFFFF0000u);
+                cacc[6] += __uint_as_float(r[i].w << 16); cacc[7] += __uint_as_float(r[i].w & 0xFFFF0000u);
+            }
         }
     };
-    auto operand = [&](int buf, int which, int col, int mg0) -> bf16x8 {
-        const uint2 lo = T[buf][which][mg0][col], hi = T[buf][which][mg0 + 1][col];
-        u32x4v v = {lo.x, lo.y, hi.x, hi.y};
-        return __builtin_bit_cast(bf16x8, v);
+    // MFMA operand of lane (lr, half) for the 32-column sub-tile at col0: rows m0 + 8 half .. + 8 of column
+    // col0 + lr.  A 16-lane group reads a 4 (m) x 16 (columns) piece: lane i of the group supplies the address of
+    // row i / 4, columns 4 (i % 4) .. + 4 and receives column i's four rows.
+    const int tl = lane & 15, tcol = ((lane >> 4) & 1) * 16;
+    auto operand = [&](int buf, int which, int col0, int m0) -> bf16x8 {
+        const uint16_t *p = &T[buf][which][m0 + 8 * half + (tl >> 2)][col0 + tcol + 4 * (tl & 3)];
+        const v4s16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((v4s16 __attribute__((address_space(3))) *)p);
+        const v4s16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((v4s16 __attribute__((address_space(3))) *)(p + 4 * TN_ROW));
+        typedef short v8s16 __attribute__((ext_vector_type(8)));
+        const v8s16 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        return __builtin_bit_cast(bf16x8, both);
     };
 
     f32x16 acc[2][2];
@@ -362,8 +368,6 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(TnArgs a)
         for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-    float colsum = 0.f;
-    const bool do_colsum = kt == 0 && tid < 128 && n0 + tid < a.N;
 
     const int nsteps = (m_end - m_begin + 31) / 32;
     fetch(ring[0], 0);
@@ -377,25 +381,16 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(TnArgs a)
         fetch(slot_next_fetch, t + 3);             // the slot that held step t (already staged)
 #pragma unroll
         for (int kk = 0; kk < 2; ++kk) {
-            const int mg0 = kk * 4 + 2 * half;      // eight consecutive m = two groups of four
             bf16x8 x[2], z[2];
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
-                x[i] = operand(buf, 0, wk * 64 + i * 32 + lr, mg0);
-                z[i] = operand(buf, 1, wn * 64 + i * 32 + lr, mg0);
+                x[i] = operand(buf, 0, wk * 64 + i * 32, kk * 16);
+                z[i] = operand(buf, 1, wn * 64 + i * 32, kk * 16);
             }
 #pragma unroll
             for (int i = 0; i < 2; ++i)
 #pragma unroll
                 for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x[i], z[j], acc[i][j], 0, 0, 0);
-        }
-        if (do_colsum) {
-#pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                const uint2 v = T[buf][1][q][tid];
-                colsum += (__uint_as_float(v.x << 16) + __uint_as_float(v.x & 0xFFFF0000u)) +
-                          (__uint_as_float(v.y << 16) + __uint_as_float(v.y & 0xFFFF0000u));
-            }
         }
         if (t + 1 < nsteps) stage(slot_next_stage, buf ^ 1);
         __syncthreads();
@@ -418,7 +413,21 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(TnArgs a)
                 if (kl < k_valid && n < a.N) P[(int64_t)(k0 + kl) * a.N + n] = acc[i][j][r];
             }
         }
-    if (do_colsum) P[(int64_t)a.K2 * a.N + n0 + tid] = colsum;
+    // bias gradient: the eight row groups' column sums meet in LDS and are added in a fixed order
+    if (kt == 0) {
+        float (*csum)[128] = reinterpret_cast<float (*)[128]>(&T[0][0][0][0]);     // the staging tiles are free now
+        if (op == 1) {
+#pragma unroll
+            for (int c = 0; c < 8; ++c) csum[mg][sc + c] = cacc[c];
+        }
+        __syncthreads();
+        if (tid < 128 && n0 + tid < a.N) {
+            float tot = 0.f;
+#pragma unroll
+            for (int g8 = 0; g8 < 8; ++g8) tot += csum[g8][tid];
+            P[(int64_t)a.K2 * a.N + n0 + tid] = tot;
+        }
+    }
 }
 
 // sums the partial products of the active splits in a fixed order, applies the SGD step to the float
