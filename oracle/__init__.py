@@ -2,7 +2,8 @@
 
 TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
 benchmark's cpu_baseline leg.  Nothing in the product package imports this.
-The functions here only marshal numpy arrays; all arithmetic is in oracle.c.
+The functions of the GraphSAGE path only marshal numpy arrays, their arithmetic is in oracle.c; the GCN and GAT
+layers at the end of this file are written out in numpy, in float64.
 """
 from __future__ import annotations
 
@@ -350,3 +351,74 @@ def gcn_aggregate_bwd(blk: Block, d_out, graph_deg):
     np.add.at(d_src, u_local, (scale[rows_e] * isd[nodes[u_local]])[:, None] * d_out[rows_e])
     d_src[:blk.n_dst] += d_out / (deg[dst] + 1.0)[:, None]
     return d_src
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# Graph attention layer on a sampled block (Section 6.4 names GAT as the second model the method is applied to and
+# gives no architecture; the layer is the one of Velickovic et al., "Graph Attention Networks", their equations
+# for the attention coefficients, the neighbourhood softmax and the multi-head output with concatenated heads):
+#     z[u]        = x[u] W                                    (shared linear map, split into `heads` groups of D columns)
+#     e[v,u,h]    = LeakyReLU_slope( a_l[h] . z[u,h] + a_r[h] . z[v,h] )      for u in N_s(v)
+#     alpha[v,.,h]= softmax of e[v,.,h] over N_s(v)
+#     out[v,h]    = sum_u alpha[v,u,h] z[u,h] + bias[h]       (a row without sampled neighbours gets the bias alone)
+# The attention vector of the original paper acts on the concatenation [z_v || z_u]; a_r and a_l are its two halves.
+# The neighbourhood is the block's sampled in-neighbours, without an added self loop.
+# ---------------------------------------------------------------------------------------------------------------
+def gat_attention_fwd(blk: Block, z, a_l, a_r, bias, heads, slope=0.2):
+    """z: [n_src, heads*D] projected source rows (destination v is source row v).  Returns (out [n_dst, heads*D],
+    alpha: list over destinations of [deg, heads] arrays)."""
+    z = np.asarray(z, dtype=np.float64)
+    HD = z.shape[1]
+    D = HD // heads
+    a_l = np.asarray(a_l, dtype=np.float64).reshape(heads, D)
+    a_r = np.asarray(a_r, dtype=np.float64).reshape(heads, D)
+    bias = np.asarray(bias, dtype=np.float64).reshape(HD)
+    z3 = z.reshape(-1, heads, D)
+    out = np.zeros((blk.n_dst, HD))
+    alphas = []
+    for v in range(blk.n_dst):
+        nb = blk.indices[blk.indptr[v]:blk.indptr[v + 1]].astype(np.int64)
+        if len(nb) == 0:
+            out[v] = bias
+            alphas.append(np.zeros((0, heads)))
+            continue
+        s = np.einsum("uhd,hd->uh", z3[nb], a_l) + np.einsum("hd,hd->h", z3[v], a_r)[None, :]
+        e = np.where(s > 0, s, slope * s)
+        w = np.exp(e - e.max(axis=0, keepdims=True))
+        alpha = w / w.sum(axis=0, keepdims=True)
+        out[v] = np.einsum("uh,uhd->hd", alpha, z3[nb]).reshape(HD) + bias
+        alphas.append(alpha)
+    return out, alphas
+
+
+def gat_attention_bwd(blk: Block, z, a_l, a_r, heads, d_out, slope=0.2):
+    """Gradients of gat_attention_fwd for a given d_out = dL/d out: returns (d_z [n_src, heads*D], d_a_l, d_a_r,
+    d_bias).  Chain rule written out per destination: value path (alpha z), softmax, LeakyReLU, the two dot products."""
+    z = np.asarray(z, dtype=np.float64)
+    d_out = np.asarray(d_out, dtype=np.float64)
+    HD = z.shape[1]
+    D = HD // heads
+    a_l = np.asarray(a_l, dtype=np.float64).reshape(heads, D)
+    a_r = np.asarray(a_r, dtype=np.float64).reshape(heads, D)
+    z3 = z.reshape(-1, heads, D)
+    g3 = d_out.reshape(-1, heads, D)
+    d_z = np.zeros_like(z3)
+    d_al = np.zeros_like(a_l)
+    d_ar = np.zeros_like(a_r)
+    d_bias = d_out.sum(axis=0)
+    for v in range(blk.n_dst):
+        nb = blk.indices[blk.indptr[v]:blk.indptr[v + 1]].astype(np.int64)
+        if len(nb) == 0:
+            continue
+        s = np.einsum("uhd,hd->uh", z3[nb], a_l) + np.einsum("hd,hd->h", z3[v], a_r)[None, :]
+        e = np.where(s > 0, s, slope * s)
+        w = np.exp(e - e.max(axis=0, keepdims=True))
+        alpha = w / w.sum(axis=0, keepdims=True)
+        d_alpha = np.einsum("hd,uhd->uh", g3[v], z3[nb])                 # out = sum alpha z
+        d_e = alpha * (d_alpha - (alpha * d_alpha).sum(axis=0, keepdims=True))   # softmax Jacobian
+        d_s = d_e * np.where(s > 0, 1.0, slope)
+        np.add.at(d_z, nb, alpha[:, :, None] * g3[v][None, :, :] + d_s[:, :, None] * a_l[None, :, :])
+        d_z[v] += d_s.sum(axis=0)[:, None] * a_r
+        d_al += np.einsum("uh,uhd->hd", d_s, z3[nb])
+        d_ar += d_s.sum(axis=0)[:, None] * z3[v]
+    return d_z.reshape(-1, HD), d_al.reshape(-1), d_ar.reshape(-1), d_bias
