@@ -129,7 +129,7 @@ cr_status cr_graph_edge_classes(const cr_graph *graph, uint32_t *edge_intra, voi
  * slot ascending); indptr/indices are a CSR over local source positions.  t_indptr/t_indices hold
  * the transposed block (for every source position the destination rows that use it, ascending);
  * they may be NULL when the layer's input needs no gradient, and must be NULL for layer 0 (the
- * feature table takes no gradient).  gather_ids is optional for every layer. */
+ * feature table takes no gradient) unless CR_SAMPLE_TRANSPOSE_INPUT is set.  gather_ids is optional for every layer. */
 typedef struct {
     int32_t n_batches;
     int32_t fanout;
@@ -159,6 +159,9 @@ typedef struct {
                                      reads the resident feature table through gather_ids and needs no gradient of the
                                      input features: the blocks of the layers above, and every result computed from
                                      them, are unchanged. */
+#define CR_SAMPLE_TRANSPOSE_INPUT 8u /* layers[0] may carry t_indptr / t_indices too (a model whose first layer needs a
+                                     gradient per source row: graph attention projects the source rows before it
+                                     aggregates).  Not together with CR_SAMPLE_INPUT_GLOBAL_IDS. */
 
 typedef struct {
     int32_t n_layers;              /* 1..CR_MAX_LAYERS */
@@ -259,6 +262,57 @@ cr_status cr_gcn_aggregate_bwd(const cr_block_set *blocks, int32_t g, const floa
                                int32_t in_dtype, int64_t ld_in, int32_t F, const void *relu_out, int32_t relu_dtype,
                                int64_t ld_relu, float *d_src, uint16_t *d_src_bf16, int64_t ld_bf16, void *stream);
 
+/* ------------------------------------------------------------------------- */
+/* Graph attention on the same blocks (Section 6.4 names GAT as the second other model; the layer is the one of         */
+/* Velickovic et al., "Graph Attention Networks"):                                                                      */
+/*   z[u]      = x[u] W                       a one-operand layer without bias over the block's SOURCE rows             */
+/*   e[v,u,h]  = LeakyReLU_slope(a_l[h] . z[u,h] + a_r[h] . z[v,h])   for u in N_s(v), head h = columns h*D..h*D+D-1    */
+/*   alpha     = softmax of e over N_s(v)     (sampled in-neighbours, no added self loop)                               */
+/*   out[v,h]  = sum_u alpha[v,u,h] z[u,h] + bias[h]     (ReLU on hidden layers; a row without neighbours: the bias)    */
+/* The projection and its backward are cr_sage_linear_fwd / cr_sage_linear_bwd on a layer with n_operands = 1 and       */
+/* bias = NULL, run over the source rows (header + CR_HDR_N_SRC); the calls below are the attention part.               */
+/* ------------------------------------------------------------------------- */
+typedef struct {
+    int32_t heads, D;  /* heads * D = the layer's F_out; with several heads D must be 8 times a power of two */
+    float slope;       /* negative slope of the LeakyReLU, in [0, 1] */
+    int32_t reserved;
+    float *attn;       /* device float [3][ld]: a_l, a_r and the bias by output column (ld = the layer's N_pad; entries
+                          >= heads*D must be 0) */
+} cr_gat_params;
+
+/* rows_out[i] = store[ids[i]] converted to bf16 and zero padded to ld_out columns, for i < n = min(hdr[hdr_word],
+ * max_n): the first layer's projection operand (one row per distinct input node of the batch).
+ *   store : device [n_nodes][ld_src] of CR_F32 or CR_BF16, F real columns;  rows_out : device bf16 [max_n][ld_out] */
+cr_status cr_gather_rows_bf16(const void *store, int32_t dtype, int64_t ld_src, int32_t F, const int32_t *ids,
+                              const int32_t *hdr, int32_t hdr_word, int32_t max_n, uint16_t *rows_out,
+                              int64_t ld_out, void *stream);
+
+/* Attention scores, neighbourhood softmax and weighted sum for batch g.
+ *   z_bf16 : device bf16 [cap_src][ld], the projected source rows (padded columns zero); ld = 64..512, multiple of 64
+ *   el, er : device float [cap_src][heads]: written (the two halves of every score)
+ *   stat   : device float [cap_dst][heads][4], 16-byte aligned: written; per destination and head what the backward
+ *            pass needs to recompute alpha (er, largest score, 1 / sum of exponentials, one word for its own use)
+ *   out    : device float [cap_dst][ld] or NULL;  out_bf16 : device bf16 [cap_dst][ld] or NULL */
+cr_status cr_gat_attention_fwd(const cr_block_set *blocks, int32_t g, const cr_gat_params *params,
+                               const uint16_t *z_bf16, int64_t ld, int32_t relu, float *el, float *er,
+                               float *stat, float *out, uint16_t *out_bf16, void *stream);
+
+cr_status cr_gat_attention_bwd_workspace_bytes(int32_t cap_dst, int64_t ld, int32_t heads, size_t *bytes);
+
+/* Backward of cr_gat_attention_fwd and one SGD step on a_l, a_r (with weight decay) and the bias (without).  Needs the
+ * transposed block (for layer 0: sample with CR_SAMPLE_TRANSPOSE_INPUT); no atomics, bit-reproducible.
+ *   z_bf16, el, stat : as left by the forward call of the same batch (stat's spare word is overwritten)
+ *   d_out_bf16    : device bf16 [cap_dst][ld_dout]: dL/d out (after the ReLU, if any)
+ *   relu_out_bf16 : device bf16 [cap_dst][ld] or NULL: the forward output; where it is <= 0 the gradient is zeroed
+ *   dz_bf16       : device bf16 [cap_src][ld]: dL/dz for rows 0..n_src-1 (the dz operand of cr_sage_linear_bwd)
+ *   d_attn_out    : device float [3][ld] or NULL: the gradients of a_l, a_r and the bias
+ *   ws            : device workspace of cr_gat_attention_bwd_workspace_bytes(cap_dst, ld, heads) bytes */
+cr_status cr_gat_attention_bwd(const cr_block_set *blocks, int32_t g, const cr_gat_params *params,
+                               const uint16_t *z_bf16, int64_t ld, const float *el, float *stat,
+                               const uint16_t *d_out_bf16, int64_t ld_dout, const uint16_t *relu_out_bf16,
+                               float lr, float weight_decay, uint16_t *dz_bf16, float *d_attn_out, void *ws,
+                               size_t ws_bytes, void *stream);
+
 /* One layer's dense parameters.  F_pad = F_in rounded up to 32, N_pad = F_out rounded up to 64.
  * n_operands = 2: GraphSAGE, Z = H_self W_self + Agg W_neigh + b;  n_operands = 1: one aggregated input (GCN,
  * Section 6.4), Z = Agg W + b: every h_self / d_self argument below must then be NULL and the [.. 2*F ..] shapes
@@ -268,7 +322,8 @@ typedef struct {
     int32_t n_operands; /* 1 or 2 */
     int32_t reserved;
     float *W;          /* device float [n_operands*F_in][F_out]: rows 0..F_in-1 = W_self, F_in..2F_in-1 = W_neigh (master) */
-    float *bias;       /* device float [N_pad] (entries >= F_out stay 0) */
+    float *bias;       /* device float [N_pad] (entries >= F_out stay 0), or NULL: a layer without a bias term (none added,
+                          none updated) */
     uint16_t *W_bf16;  /* device bf16 [n_operands*F_pad][N_pad], zero padded shadow of W (row F_pad+k = W_neigh row k) */
     uint16_t *Wt_bf16; /* device bf16 [N_pad][n_operands*F_pad], its transpose */
 } cr_sage_layer;
@@ -279,7 +334,8 @@ cr_status cr_sage_refresh_shadows(const cr_sage_layer *layer, void *stream);
 
 /* out[v] = h_self[v] W_self + agg[v] W_neigh + bias (ReLU if relu != 0), bf16 operands on the matrix
  * cores with float accumulation.
- *   hdr     : device block header; rows = hdr[CR_HDR_N_DST]; max_rows bounds the launch
+ *   hdr     : device block header; rows = hdr[CR_HDR_N_DST]; max_rows bounds the launch.  Only that one word is read,
+ *             so a product over a block's source rows (the graph-attention projection) passes header + CR_HDR_N_SRC
  *   h_self, agg : device bf16 [max_rows][ld_in], ld_in >= F_pad, padded columns zero
  *   out     : device float [max_rows][N_pad] or NULL;  out_bf16 : device bf16 [max_rows][N_pad] or NULL */
 cr_status cr_sage_linear_fwd(const cr_sage_layer *layer, const int32_t *hdr, int32_t max_rows,

@@ -23,6 +23,7 @@ CR_F32, CR_BF16 = 0, 1
 CR_SAMPLE_STRICT_INTRA = 1
 CR_SAMPLE_HASH_DEDUP = 2
 CR_SAMPLE_INPUT_GLOBAL_IDS = 4
+CR_SAMPLE_TRANSPOSE_INPUT = 8
 
 EXPORTS = [
     "cr_last_error", "cr_version", "cr_set_dry_run", "cr_mix_count_from_percent",
@@ -33,6 +34,7 @@ EXPORTS = [
     "cr_sage_padded_dims", "cr_sage_refresh_shadows", "cr_sage_linear_fwd",
     "cr_sage_linear_bwd_workspace_bytes", "cr_sage_linear_bwd", "cr_sage_linear_bwd_input", "cr_softmax_xent",
     "cr_count_correct",
+    "cr_gather_rows_bf16", "cr_gat_attention_fwd", "cr_gat_attention_bwd_workspace_bytes", "cr_gat_attention_bwd",
     "cr_cache_reset", "cr_cache_fetch", "cr_stage_rows", "cr_host_alloc", "cr_host_free",
 ]
 
@@ -82,6 +84,10 @@ class cr_sage_layer(C.Structure):
                 ("W", C.c_void_p), ("bias", C.c_void_p), ("W_bf16", C.c_void_p), ("Wt_bf16", C.c_void_p)]
 
 
+class cr_gat_params(C.Structure):
+    _fields_ = [("heads", C.c_int32), ("D", C.c_int32), ("slope", C.c_float), ("reserved", C.c_int32), ("attn", C.c_void_p)]
+
+
 _lib = None
 
 
@@ -126,6 +132,11 @@ def lib():
         L.cr_sage_linear_bwd_input.argtypes = [C.POINTER(cr_sage_layer), vp, i32, vp, vp, vp, vp, vp]
         L.cr_softmax_xent.argtypes = [vp, i32, vp, i64, i32, vp, vp, vp, vp, vp, vp, vp]
         L.cr_count_correct.argtypes = [vp, i32, vp, i64, i32, vp, vp, vp, vp]
+        L.cr_gather_rows_bf16.argtypes = [vp, i32, i64, i32, vp, vp, i32, i32, vp, i64, vp]
+        L.cr_gat_attention_fwd.argtypes = [C.POINTER(cr_block_set), i32, C.POINTER(cr_gat_params), vp, i64, i32, vp, vp, vp, vp, vp, vp]
+        L.cr_gat_attention_bwd_workspace_bytes.argtypes = [i32, i64, i32, C.POINTER(C.c_size_t)]
+        L.cr_gat_attention_bwd.argtypes = [C.POINTER(cr_block_set), i32, C.POINTER(cr_gat_params), vp, i64, vp, vp, vp, i64, vp,
+                                           C.c_float, C.c_float, vp, vp, vp, C.c_size_t, vp]
         L.cr_cache_reset.argtypes = [C.POINTER(cr_feature_cache), vp]
         L.cr_cache_fetch.argtypes = [C.POINTER(cr_feature_cache), vp, i64, vp, vp, i32, i32, i32, vp, vp]
         L.cr_stage_rows.argtypes = [vp, i64, vp, vp, i32, i32, vp, i32, vp]
@@ -233,9 +244,10 @@ class BlockSet:
 
 
 def alloc_block_sets(cfg: cr_sample_cfg, n_nodes: int, batch_size: int, n_batches: int,
-                     device="cuda") -> List[BlockSet]:
+                     device="cuda", transpose_input: bool = False) -> List[BlockSet]:
+    """transpose_input: layer 0 gets a transposed block too (sampling then needs CR_SAMPLE_TRANSPOSE_INPUT)."""
     cap_dst, cap_src, cap_nnz = cr_block_capacities(cfg, n_nodes, batch_size)
-    return [BlockSet(n_batches, cfg.fanout[l], cap_dst[l], cap_src[l], cap_nnz[l], l >= 1, device, gather_ids=(l == 0))
+    return [BlockSet(n_batches, cfg.fanout[l], cap_dst[l], cap_src[l], cap_nnz[l], l >= 1 or transpose_input, device, gather_ids=(l == 0))
             for l in range(cfg.n_layers)]
 
 
@@ -352,6 +364,11 @@ class SageLayer:
     def refresh(self, stream=None):
         _check(lib().cr_sage_refresh_shadows(C.byref(self.c), _stream(stream)))
 
+    def drop_bias(self):
+        """Turns the layer into one without a bias term (the graph-attention projection)."""
+        self.bias = None
+        self.c.bias = None
+
 
 def cr_sage_linear_fwd(layer: SageLayer, hdr_ptr, max_rows, h_self, agg, ld_in, relu, out=None, out_bf16=None,
                        stream=None):
@@ -387,6 +404,45 @@ def cr_softmax_xent(hdr_ptr, max_rows, logits, ld, n_classes, labels, root_ids_p
 def cr_count_correct(hdr_ptr, max_rows, logits, ld, n_classes, labels, root_ids_ptr, count, stream=None):
     _check(lib().cr_count_correct(hdr_ptr, max_rows, _ptr(logits), ld, n_classes, _ptr(labels), root_ids_ptr, _ptr(count),
                                   _stream(stream)))
+
+
+class GatParams:
+    """Device storage of one graph-attention layer's attention vectors and bias: float [3][N_pad] = a_l, a_r, bias."""
+
+    def __init__(self, a_l, a_r, bias, heads, N_pad, slope=0.2, device="cuda"):
+        import numpy as np
+        import torch
+        HD = len(bias)
+        assert HD % heads == 0 and len(a_l) == HD and len(a_r) == HD and HD <= N_pad
+        host = np.zeros((3, N_pad), dtype=np.float32)
+        host[0, :HD], host[1, :HD], host[2, :HD] = a_l, a_r, bias
+        self.heads, self.D, self.N_pad, self.slope = heads, HD // heads, N_pad, slope
+        self.attn = torch.from_numpy(host).to(device)
+        self.c = cr_gat_params(heads, HD // heads, slope, 0, _ptr(self.attn))
+
+
+def cr_gather_rows_bf16(store, dtype, ld_src, F, ids_ptr, hdr_ptr, hdr_word, max_n, rows_out, ld_out, stream=None):
+    store_ptr = store if isinstance(store, C.c_void_p) else _ptr(store)
+    _check(lib().cr_gather_rows_bf16(store_ptr, dtype, ld_src, F, ids_ptr, hdr_ptr, hdr_word, max_n, _ptr(rows_out), ld_out,
+                                     _stream(stream)))
+
+
+def cr_gat_attention_fwd(blocks, g, params: GatParams, z_bf16, ld, relu, el, er, stat, out=None, out_bf16=None, stream=None):
+    _check(lib().cr_gat_attention_fwd(C.byref(blocks.c), g, C.byref(params.c), _ptr(z_bf16), ld, int(relu), _ptr(el), _ptr(er),
+                                      _ptr(stat), _ptr(out), _ptr(out_bf16), _stream(stream)))
+
+
+def cr_gat_attention_bwd_workspace_bytes(cap_dst, ld, heads) -> int:
+    n = C.c_size_t(0)
+    _check(lib().cr_gat_attention_bwd_workspace_bytes(cap_dst, ld, heads, C.byref(n)))
+    return n.value
+
+
+def cr_gat_attention_bwd(blocks, g, params: GatParams, z_bf16, ld, el, stat, d_out_bf16, ld_dout, relu_out_bf16, lr, weight_decay,
+                         dz_bf16, ws, d_attn_out=None, stream=None):
+    _check(lib().cr_gat_attention_bwd(C.byref(blocks.c), g, C.byref(params.c), _ptr(z_bf16), ld, _ptr(el), _ptr(stat),
+                                      _ptr(d_out_bf16), ld_dout, _ptr(relu_out_bf16), lr, weight_decay, _ptr(dz_bf16),
+                                      _ptr(d_attn_out), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)))
 
 
 def cr_stage_rows(store_ptr, store_ld_bytes, ids_ptr, hdr_ptr, hdr_word, max_n, rows_out, row_bytes, stream=None):

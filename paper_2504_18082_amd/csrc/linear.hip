@@ -488,7 +488,7 @@ __global__ __launch_bounds__(256) void sgd_reduce_kernel(SgdArgs a)
         for (int i = 0; i < 4; ++i) {
             if (n + i < a.F_out) {
                 if (a.db_out) a.db_out[n + i] = gs[i];
-                a.bias[n + i] -= a.lr * gs[i];
+                if (a.bias) a.bias[n + i] -= a.lr * gs[i];
             }
         }
         return;
@@ -627,7 +627,7 @@ static cr_status check_layer(const cr_sage_layer *L, int &F_pad, int &N_pad)
     CR_REQUIRE(L->F_in >= 1 && L->F_in <= 8192 && L->F_out >= 1 && L->F_out <= 8192, CR_ERR_INVALID_ARG,
                "layer dims (%d, %d) outside 1..8192", L->F_in, L->F_out);
     CR_REQUIRE(L->n_operands == 1 || L->n_operands == 2, CR_ERR_INVALID_ARG, "layer n_operands = %d must be 1 or 2", L->n_operands);
-    CR_REQUIRE(L->W && L->bias && L->W_bf16 && L->Wt_bf16, CR_ERR_INVALID_ARG, "layer has a NULL array");
+    CR_REQUIRE(L->W && L->W_bf16 && L->Wt_bf16, CR_ERR_INVALID_ARG, "layer has a NULL array");
     CR_REQUIRE(aligned16(L->W) && aligned16(L->bias) && aligned16(L->W_bf16) && aligned16(L->Wt_bf16), CR_ERR_INVALID_ARG,
                "layer arrays must be 16-byte aligned");
     F_pad = (int)round_up(L->F_in, 32);

@@ -873,6 +873,8 @@ static cr_status make_plan(const cr_sample_cfg *cfg, int64_t n_nodes, int32_t ba
     CR_REQUIRE(n_batches >= 1 && n_batches <= 65535, CR_ERR_INVALID_ARG, "n_batches must be in 1..65535");
     CR_REQUIRE(cfg->p_intra >= 0.5 && cfg->p_intra <= 1.0, CR_ERR_INVALID_ARG, "p_intra = %g outside [0.5, 1]", cfg->p_intra);
     CR_REQUIRE(cfg->epoch < (1u << 24), CR_ERR_INVALID_ARG, "epoch must be below 2^24");
+    CR_REQUIRE(!((cfg->flags & CR_SAMPLE_TRANSPOSE_INPUT) && (cfg->flags & CR_SAMPLE_INPUT_GLOBAL_IDS)), CR_ERR_INVALID_ARG,
+               "CR_SAMPLE_TRANSPOSE_INPUT and CR_SAMPLE_INPUT_GLOBAL_IDS exclude each other");
     p.L = cfg->n_layers;
     int64_t dst = batch_size;
     for (int l = p.L - 1; l >= 0; --l) {
@@ -893,7 +895,7 @@ static cr_status make_plan(const cr_sample_cfg *cfg, int64_t n_nodes, int32_t ba
         p.max_dst = dst > p.max_dst ? dst : p.max_dst;
         p.max_nnz = nnz > p.max_nnz ? nnz : p.max_nnz;
         p.max_table = (1ll << bits) > p.max_table ? (1ll << bits) : p.max_table;
-        if (l >= 1) {
+        if (l >= 1 || (cfg->flags & CR_SAMPLE_TRANSPOSE_INPUT)) {
             p.max_src_t = src > p.max_src_t ? src : p.max_src_t;
             p.max_nnz_t = nnz > p.max_nnz_t ? nnz : p.max_nnz_t;
         }
@@ -987,7 +989,8 @@ extern "C" cr_status cr_sample_blocks(const cr_graph *graph, const cr_sample_cfg
         CR_REQUIRE(b.hdr && b.src_ids && b.indptr && b.indices, CR_ERR_INVALID_ARG, "layers[%d] has a NULL array", l);
         CR_REQUIRE((b.t_indptr == nullptr) == (b.t_indices == nullptr), CR_ERR_INVALID_ARG,
                    "layers[%d]: t_indptr and t_indices must be given together", l);
-        CR_REQUIRE(l >= 1 || b.t_indptr == nullptr, CR_ERR_UNSUPPORTED, "layer 0 takes no transposed block (its input needs no gradient)");
+        CR_REQUIRE(l >= 1 || b.t_indptr == nullptr || (cfg->flags & CR_SAMPLE_TRANSPOSE_INPUT), CR_ERR_UNSUPPORTED,
+                   "layer 0 takes a transposed block only with CR_SAMPLE_TRANSPOSE_INPUT");
         CR_REQUIRE(l >= 1 || !(cfg->flags & CR_SAMPLE_INPUT_GLOBAL_IDS) || b.gather_ids != nullptr, CR_ERR_INVALID_ARG,
                    "CR_SAMPLE_INPUT_GLOBAL_IDS needs layers[0].gather_ids");
     }
