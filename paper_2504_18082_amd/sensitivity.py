@@ -52,7 +52,7 @@ def main(argv=None):
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--group", type=int, default=16)
     ap.add_argument("--seed", type=int, default=0)
-    ap.add_argument("--model", default="sage", choices=["sage", "gcn"])
+    ap.add_argument("--model", default="sage", choices=["sage", "gcn", "gat"])
     ap.add_argument("--settings", nargs="+", default=DEFAULT_SETTINGS)
     args = ap.parse_args(argv)
 

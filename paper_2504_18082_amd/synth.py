@@ -227,6 +227,26 @@ def init_weights(cfg: WorkloadConfig, seed: int = 0, n_operands: int = 2):
     return out
 
 
+def init_gat_weights(cfg: WorkloadConfig, seed: int = 0, heads: int = 4):
+    """Per layer (W [F_in, heads*D], a_l [heads*D], a_r [heads*D], bias [heads*D]) in float32: `heads` heads of width
+    hidden/heads on hidden layers (concatenated), one head of width n_classes on the last.  Glorot-uniform W and
+    attention vectors, zero bias."""
+    rng = np.random.default_rng([seed, 0x6A7, 5])
+    out = []
+    dims = layer_dims(cfg)
+    for l, (fin, fout) in enumerate(dims):
+        h = heads if l < len(dims) - 1 else 1
+        assert fout % h == 0
+        D = fout // h
+        a = np.sqrt(6.0 / (fin + fout))
+        W = rng.uniform(-a, a, size=(fin, fout)).astype(np.float32)
+        c = np.sqrt(6.0 / (D + 1))
+        a_l = rng.uniform(-c, c, size=fout).astype(np.float32)
+        a_r = rng.uniform(-c, c, size=fout).astype(np.float32)
+        out.append((W, a_l, a_r, np.zeros(fout, dtype=np.float32)))
+    return out
+
+
 def mix_count_from_percent(k_percent: float, n_comm_in_train: int) -> int:
     """Number of communities per super-block for COMM-RAND-MIX-k% (k% of the
     communities present in the training set, at least one)."""

@@ -27,7 +27,7 @@ class Trainer:
     def __init__(self, workload: synth.Workload, group_size: int = 16, lr: float = 0.01,
                  weight_decay: float = 5e-4, seed: int = 0, device: str = "cuda", weights=None,
                  relabel_input: bool = False, edge_classes: bool = True, host_features: bool = False,
-                 cache_rows: int = 0, cache_ways: int = 16, model: str = "sage"):
+                 cache_rows: int = 0, cache_ways: int = 16, model: str = "sage", gat_heads: int = 4):
         import torch
         self.torch = torch
         self.w = workload
@@ -37,17 +37,21 @@ class Trainer:
         self.B = cfg.batch_size
         self.G = group_size
         self.lr, self.wd, self.seed = lr, weight_decay, seed
-        assert model in ("sage", "gcn")
+        assert model in ("sage", "gcn", "gat")
         self.model = model
         self.n_op = 2 if model == "sage" else 1
-        assert model == "sage" or not (host_features or cache_rows), "the GCN path reads the resident table"
+        assert model == "sage" or not (host_features or cache_rows), "the GCN and GAT paths read the resident table"
         # The layer-0 gather reads the feature table through per-edge global ids and the features take no
         # gradient, so nothing in a training step needs the input frontier de-duplicated or relabelled
         # (relabel_input=True asks for it anyway, e.g. to count the distinct input nodes of a batch).
         # A feature store on the host (and the cache in front of it) works on the batch's distinct input nodes,
         # so those set-ups do need the input frontier de-duplicated.
-        relabel_input = relabel_input or host_features or cache_rows > 0
+        # Graph attention projects every distinct input node once and needs the gradient per source row of every
+        # layer, the first included: de-duplicated input frontier and a transposed input block.
+        relabel_input = relabel_input or host_features or cache_rows > 0 or model == "gat"
         self.sample_flags = 0 if relabel_input else B.CR_SAMPLE_INPUT_GLOBAL_IDS
+        if model == "gat":
+            self.sample_flags |= B.CR_SAMPLE_TRANSPOSE_INPUT
         up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(device)
         self.indptr = up(workload.indptr.astype(np.int64))
         self.indices = up(workload.indices.astype(np.int32))
@@ -76,8 +80,18 @@ class Trainer:
         self.n_batches = -(-self.n_train // self.B)
 
         # parameters
-        weights = weights if weights is not None else synth.init_weights(cfg, seed, self.n_op)
-        self.layers: List[B.SageLayer] = [B.SageLayer(W, b, device, self.n_op) for (W, b) in weights]
+        if model == "gat":
+            # weights: per layer (W [F_in, heads*D], a_l, a_r, bias); `gat_heads` heads on hidden layers, one on the last
+            weights = weights if weights is not None else synth.init_gat_weights(cfg, seed, gat_heads)
+            assert cfg.hidden % 64 == 0 and cfg.hidden % gat_heads == 0, "GAT path: hidden width must be a multiple of 64 and of the head count"
+            self.layers = [B.SageLayer(W, np.zeros(W.shape[1], dtype=np.float32), device, 1) for (W, _, _, _) in weights]
+            for layer in self.layers:
+                layer.drop_bias()
+            self.gat = [B.GatParams(a_l, a_r, b, gat_heads if l < self.L - 1 else 1, self.layers[l].N_pad, 0.2, device)
+                        for l, (_, a_l, a_r, b) in enumerate(weights)]
+        else:
+            weights = weights if weights is not None else synth.init_weights(cfg, seed, self.n_op)
+            self.layers: List[B.SageLayer] = [B.SageLayer(W, b, device, self.n_op) for (W, b) in weights]
         for layer in self.layers:
             layer.refresh()
 
@@ -87,8 +101,10 @@ class Trainer:
 
         # step 2: block storage for one group of batches
         scfg = B.make_sample_cfg(cfg.fanouts, 0.5, seed, 0)
-        self.block_slots = [B.alloc_block_sets(scfg, self.n_nodes, self.B, self.G, device) for _ in range(2)]
+        self.block_slots = [B.alloc_block_sets(scfg, self.n_nodes, self.B, self.G, device, transpose_input=model == "gat")
+                            for _ in range(2)]
         self.blocks = self.block_slots[0]
+        scfg.flags = self.sample_flags
         self.ws_sample = torch.empty(B.cr_sample_blocks_workspace_bytes(scfg, self.n_nodes, self.B, self.G), dtype=torch.uint8, device=device)
 
         # activations / gradients, sized by the per-batch capacities
@@ -110,7 +126,19 @@ class Trainer:
             self.gcn_norm = B.cr_graph_gcn_norm(self.graph)
             self.blk_norm = [torch.zeros(self.blocks[l].cap_src + 2 * self.blocks[l].cap_dst, dtype=torch.float32, device=device)
                              for l in range(self.L)]
-        self.ws_bwd = [torch.empty(B.cr_sage_linear_bwd_workspace_bytes(self.layers[l].F_in, self.layers[l].F_out, self.blocks[l].cap_dst),
+        if model == "gat":     # the dense part runs over the source rows of every block
+            lay, blk = self.layers, self.blocks
+            self.x0 = b16(blk[0].cap_src, lay[0].F_pad)                                   # bf16 rows of the distinct input nodes
+            self.gat_z = [b16(blk[l].cap_src, lay[l].N_pad) for l in range(self.L)]       # projected source rows
+            self.gat_dz = [b16(blk[l].cap_src, lay[l].N_pad) for l in range(self.L)]      # their gradients
+            self.gat_el = [f32(blk[l].cap_src, self.gat[l].heads) for l in range(self.L)]
+            self.gat_er = [f32(blk[l].cap_src, self.gat[l].heads) for l in range(self.L)]
+            self.gat_stat = [f32(blk[l].cap_dst, 4 * self.gat[l].heads) for l in range(self.L)]
+            self.gat_din = [b16(blk[l].cap_src, lay[l].F_pad) if l >= 1 else None for l in range(self.L)]   # dL/d (output of layer l-1)
+            self.ws_gat = [torch.empty(B.cr_gat_attention_bwd_workspace_bytes(blk[l].cap_dst, lay[l].N_pad, self.gat[l].heads),
+                                       dtype=torch.uint8, device=device) for l in range(self.L)]
+        rows_of = lambda l: self.blocks[l].cap_src if model == "gat" else self.blocks[l].cap_dst
+        self.ws_bwd = [torch.empty(B.cr_sage_linear_bwd_workspace_bytes(self.layers[l].F_in, self.layers[l].F_out, rows_of(l)),
                                    dtype=torch.uint8, device=device) for l in range(self.L)]
         self.loss = torch.zeros(1, dtype=torch.float32, device=device)
         self.row_loss = torch.zeros(self.B, dtype=torch.float32, device=device)
@@ -193,6 +221,8 @@ class Trainer:
         L, blocks, layers = self.L, self.blocks, self.layers
         if self.model == "gcn":
             return self._forward_batch_gcn(g)
+        if self.model == "gat":
+            return self._forward_batch_gat(g)
         for l in range(L):
             blk, lay = blocks[l], layers[l]
             if l == 0:
@@ -247,7 +277,50 @@ class Trainer:
                 B.cr_gcn_aggregate_bwd(blk, g, self.blk_norm[l], self.d_in[l], lay.F_pad, lay.F_in, self.out_b[l - 1], prev.N_pad,
                                        None, self.dz[l - 1], prev.N_pad, relu_dtype=B.CR_BF16, in_dtype=B.CR_BF16)
 
-    def train_batch(self, g: int, dW_out=None, db_out=None, slot: Optional[int] = None, buf: int = 0, gather0: bool = True):
+    # graph attention: project the source rows, then attend over the block (the dense layer runs on n_src rows)
+    @staticmethod
+    def _src_rows_hdr(blk, g):
+        """Address of the header word that holds the block's number of source rows (the dense calls read one word)."""
+        return C.c_void_p(blk.hdr_ptr(g).value + 4 * B.CR_HDR_N_SRC)
+
+    def _forward_batch_gat(self, g: int):
+        L, blocks, layers = self.L, self.blocks, self.layers
+        self.wait_weights()
+        for l in range(L):
+            blk, lay, par = blocks[l], layers[l], self.gat[l]
+            if l == 0:
+                if self.time_gather0:
+                    ev0, ev1 = self.torch.cuda.Event(enable_timing=True), self.torch.cuda.Event(enable_timing=True)
+                    ev0.record()
+                B.cr_gather_rows_bf16(self.table_ptr, self.feat_dtype, self.ld_table, self.cfg.n_feat, blk.src_ids_ptr(g), blk.hdr_ptr(g),
+                                      B.CR_HDR_N_SRC, blk.cap_src, self.x0, lay.F_pad)
+                if self.time_gather0:
+                    ev1.record()
+                    self.gather0_events.append((ev0, ev1))
+                x, ld_in = self.x0, lay.F_pad
+            else:
+                x, ld_in = self.out_b[l - 1], layers[l - 1].N_pad
+            B.cr_sage_linear_fwd(lay, self._src_rows_hdr(blk, g), blk.cap_src, None, x, ld_in, False, None, self.gat_z[l])
+            B.cr_gat_attention_fwd(blk, g, par, self.gat_z[l], lay.N_pad, l < L - 1, self.gat_el[l], self.gat_er[l], self.gat_stat[l],
+                                   self.out[l], self.out_b[l])
+
+    def _backward_batch_gat(self, g: int, dW_out, d_attn_out):
+        L, blocks, layers = self.L, self.blocks, self.layers
+        for l in range(L - 1, -1, -1):
+            blk, lay, par = blocks[l], layers[l], self.gat[l]
+            if l == L - 1:
+                d_out, ld_dout = self.dz[l], lay.N_pad
+            else:
+                d_out, ld_dout = self.gat_din[l + 1], layers[l + 1].F_pad
+            B.cr_gat_attention_bwd(blk, g, par, self.gat_z[l], lay.N_pad, self.gat_el[l], self.gat_stat[l], d_out, ld_dout,
+                                   self.out_b[l] if l < L - 1 else None, self.lr, self.wd, self.gat_dz[l], self.ws_gat[l],
+                                   None if d_attn_out is None else d_attn_out[l])
+            x, ld_in = (self.x0, lay.F_pad) if l == 0 else (self.out_b[l - 1], layers[l - 1].N_pad)
+            B.cr_sage_linear_bwd(lay, self._src_rows_hdr(blk, g), blk.cap_src, None, x, ld_in, self.gat_dz[l], self.lr, self.wd,
+                                 None, None, self.ws_bwd[l], None if dW_out is None else dW_out[l], None, d_in_bf16=self.gat_din[l])
+
+    def train_batch(self, g: int, dW_out=None, db_out=None, slot: Optional[int] = None, buf: int = 0, gather0: bool = True,
+                    d_attn_out=None):
         """Forward, loss, backward and SGD for mini-batch g of a sampled group (current stream)."""
         self.forward_batch(g, slot, buf, gather0)
         L, blocks, layers = self.L, self.blocks, self.layers
@@ -258,6 +331,8 @@ class Trainer:
         # backward + SGD
         if self.model == "gcn":
             return self._backward_batch_gcn(g, dW_out, db_out)
+        if self.model == "gat":
+            return self._backward_batch_gat(g, dW_out, d_attn_out)
         side = self.stream_weights if self.weights_on_side_stream else None
         for l in range(L - 1, -1, -1):
             blk, lay = blocks[l], layers[l]
@@ -456,7 +531,7 @@ class Trainer:
         n_src = rows = seen = 0
         for first in range(0, min(nb, max_groups * self.G), self.G):
             n = min(self.G, nb - first)
-            self.sample_group(first, n, p_intra, epoch, flags=0)
+            self.sample_group(first, n, p_intra, epoch, flags=self.sample_flags & ~B.CR_SAMPLE_INPUT_GLOBAL_IDS)
             h = self.headers()[0][:n]
             n_src += int(h[:, 1].sum())
             rows += int(h[:, 2].sum() + h[:, 0].sum())

@@ -76,3 +76,45 @@ def oracle_train_step_gcn(graph, table, n_feat, labels, roots, fanouts, p, seed,
             d_src = oracle.gcn_aggregate_bwd(blocks[l], oracle.round_bf16(d_agg), deg)
             dz = d_src * (oracle.round_bf16(outs[l - 1]) > 0)
     return dict(blocks=blocks, loss=loss, logits=outs[L - 1], outs=outs, grads=grads, params=new_params)
+
+
+def oracle_train_step_gat(graph, table, n_feat, labels, roots, fanouts, p, seed, epoch, batch, params, heads, lr, wd,
+                          pos_map=None, slope=0.2):
+    """The same step for graph-attention layers: params are (W float64 [F_in, heads_l*D_l], a_l, a_r, bias) with
+    `heads` heads on hidden layers and one on the last.  Precision points of the GPU path: bf16 operands into
+    every contraction, projected rows z and hidden activations stored in bf16, gradients handed from one
+    kernel to the next (d logits, d z, d input) stored in bf16."""
+    L = len(fanouts)
+    rb = oracle.round_bf16
+    two = lambda W: np.vstack([np.zeros_like(W), W])
+    blocks = oracle.sample_blocks(graph, roots, fanouts, p, False, seed, epoch, batch, pos_map)
+    H = [heads if l < L - 1 else 1 for l in range(L)]
+    xs, zs, outs = [None] * L, [None] * L, [None] * L
+    for l in range(L):
+        W, a_l, a_r, b = params[l]
+        blk = blocks[l]
+        if l == 0:
+            xs[0] = oracle._as_float_table(table)[blk.src_ids.astype(np.int64), :n_feat]
+        else:
+            xs[l] = rb(outs[l - 1])
+        proj = oracle.sage_linear_fwd(np.zeros_like(xs[l]), xs[l], two(W), np.zeros(W.shape[1]), False, True)
+        zs[l] = rb(proj)
+        out, _ = oracle.gat_attention_fwd(blk, zs[l], a_l, a_r, b, H[l], slope)
+        outs[l] = np.maximum(out, 0.0) if l < L - 1 else out
+    loss, d_logits = oracle.softmax_xent(outs[L - 1], labels[np.asarray(roots)])
+    d_out = rb(d_logits)
+    grads, new_params = [None] * L, [None] * L
+    for l in range(L - 1, -1, -1):
+        W, a_l, a_r, b = params[l]
+        F_in = W.shape[0]
+        g = d_out * (rb(outs[l]) > 0) if l < L - 1 else d_out
+        d_z, d_al, d_ar, d_b = oracle.gat_attention_bwd(blocks[l], zs[l], a_l, a_r, H[l], g, slope)
+        dz_b = rb(d_z)
+        dW2, _, _, d_x = oracle.sage_linear_bwd(np.zeros_like(xs[l]), xs[l], two(W), np.zeros((len(xs[l]), W.shape[1])), dz_b,
+                                                False, True, need_dx=l > 0)
+        dW = dW2[F_in:]
+        grads[l] = (dW, d_al, d_ar, d_b)
+        new_params[l] = (W - lr * (dW + wd * W), a_l - lr * (d_al + wd * a_l), a_r - lr * (d_ar + wd * a_r), b - lr * d_b)
+        if l > 0:
+            d_out = rb(d_x)
+    return dict(blocks=blocks, loss=loss, logits=outs[L - 1], outs=outs, grads=grads, params=new_params)

@@ -169,3 +169,85 @@ def test_gat_backward_is_bit_reproducible(tiny_workload):
         results.append((dz.cpu().numpy().copy(), d_attn.cpu().numpy().copy(), par.attn.cpu().numpy().copy()))
     for a, b in zip(results[0], results[1]):
         np.testing.assert_array_equal(a, b)
+
+
+def test_gat_train_steps_match_oracle(tiny_workload):
+    """Three consecutive GAT training steps (sampling with a transposed input block, row gather, projection,
+    attention, loss, backward through attention and projection, SGD on every parameter)."""
+    import torch
+    from paper_2504_18082_amd.trainer import Trainer
+    from oracle_step import oracle_train_step_gat
+    w, seed, epoch, p, lr, wd, heads = tiny_workload, 0, 3, 0.9, 0.05, 5e-4, 4
+    cfg = w.cfg
+    weights = synth.init_gat_weights(cfg, seed, heads)
+    tr = Trainer(w, group_size=2, lr=lr, weight_decay=wd, seed=seed, weights=weights, model="gat", gat_heads=heads)
+    tr.build_batches(oracle.COMM_RAND, 6, epoch)
+    perm = oracle.build_batches(oracle.COMM_RAND, 6, seed, epoch, w.train_ids, w.comm, cfg.n_comm)
+    params = [tuple(a.astype(np.float64) for a in t) for t in weights]
+    pos = np.full(cfg.n_nodes, -1, dtype=np.int32)
+    dW_out = [torch.zeros_like(l.W) for l in tr.layers]
+    d_attn = [torch.zeros_like(gp.attn) for gp in tr.gat]
+    done = 0
+    while done < 3:
+        n = min(2, 3 - done)
+        tr.sample_group(done, n, p, epoch)
+        for g in range(n):
+            b = done + g
+            print(f"gat step batch={b}", flush=True)
+            tr.train_batch(g, dW_out, None, d_attn_out=d_attn)
+            torch.cuda.synchronize()
+            roots = perm[b * cfg.batch_size:(b + 1) * cfg.batch_size]
+            ref = oracle_train_step_gat(w.graph, w.features, cfg.n_feat, w.labels, roots, cfg.fanouts, p, seed, epoch, b, params, heads,
+                                        lr, wd, pos)
+            hdrs = tr.headers()
+            for l in range(tr.L):       # the sampled blocks, the transposed input block included
+                assert tuple(hdrs[l][g][:3]) == (ref["blocks"][l].n_dst, ref["blocks"][l].n_src, ref["blocks"][l].nnz)
+            assert abs(float(tr.loss.cpu()[0]) - ref["loss"]) <= 1e-3 * abs(ref["loss"])
+            assert_close(tr.out[tr.L - 1].cpu().numpy()[:len(roots), :cfg.n_classes], ref["logits"], 2e-2, f"logits batch {b}")
+            for l in range(tr.L):
+                HD = tr.layers[l].F_out
+                dW, d_al, d_ar, d_b = ref["grads"][l]
+                assert_close(dW_out[l].cpu().numpy(), dW, 2e-2, f"dW layer {l} batch {b}")
+                ga = d_attn[l].cpu().numpy()
+                assert_close(ga[0, :HD], d_al, 2e-2, f"d a_l layer {l} batch {b}")
+                assert_close(ga[1, :HD], d_ar, 2e-2, f"d a_r layer {l} batch {b}")
+                assert_close(ga[2, :HD], d_b, 2e-2, f"d bias layer {l} batch {b}")
+                assert_close(tr.layers[l].W.cpu().numpy(), ref["params"][l][0], 2e-2, f"W layer {l} batch {b}")
+                new = tr.gat[l].attn.cpu().numpy()
+                for k in range(3):
+                    assert_close(new[k, :HD], ref["params"][l][1 + k], 2e-2, f"attn[{k}] layer {l} batch {b}")
+            params = [(tr.layers[l].W.cpu().numpy().astype(np.float64),) +
+                      tuple(tr.gat[l].attn.cpu().numpy()[k, :tr.layers[l].F_out].astype(np.float64) for k in range(3))
+                      for l in range(tr.L)]
+        done += n
+
+
+def test_transposed_input_block_matches_oracle(tiny_workload):
+    """CR_SAMPLE_TRANSPOSE_INPUT: the input-side block comes with its transpose, bit for bit the oracle's."""
+    import torch
+    from paper_2504_18082_amd.trainer import Trainer
+    w, seed, epoch, p = tiny_workload, 5, 1, 0.9
+    cfg = w.cfg
+    tr = Trainer(w, group_size=2, seed=seed, model="gat")
+    tr.build_batches(oracle.RAND, 1, epoch)
+    perm = oracle.build_batches(oracle.RAND, 1, seed, epoch, w.train_ids, w.comm, cfg.n_comm)
+    tr.sample_group(0, 2, p, epoch)
+    torch.cuda.synchronize()
+    for g in range(2):
+        roots = perm[g * cfg.batch_size:(g + 1) * cfg.batch_size]
+        blk = oracle.transpose_block(oracle.sample_blocks(w.graph, roots, cfg.fanouts, p, False, seed, epoch, g)[0])
+        bs = tr.blocks[0]
+        np.testing.assert_array_equal(bs.t_indptr[g, :blk.n_src + 1].cpu().numpy(), blk.t_indptr)
+        np.testing.assert_array_equal(bs.t_indices[g, :blk.nnz].cpu().numpy(), blk.t_indices)
+
+
+def test_gat_fit_on_tiny(tiny_workload):
+    import torch
+    from paper_2504_18082_amd.trainer import Trainer
+    w = tiny_workload
+    tr = Trainer(w, group_size=8, lr=0.1, seed=0, model="gat")
+    val = torch.from_numpy(w.val_ids).cuda()
+    loss0, acc0 = tr.evaluate(val, 0)
+    hist = tr.fit(oracle.COMM_RAND, 6, 0.9, val, max_epochs=10, patience=6, lr_patience=3)
+    print("gat val acc", [round(v, 4) for v in hist.val_acc], flush=True)
+    assert min(hist.val_loss) < 0.8 * loss0 and max(hist.val_acc) > 3.0 / w.cfg.n_classes
