@@ -241,3 +241,66 @@ def test_feature_cache_validation():
     assert lib.cr_host_alloc(1024, C.byref(h), C.byref(d)) == B.CR_OK   # dry run: validated, nothing allocated
     assert h.value is None and d.value is None
     assert lib.cr_host_free(None) == B.CR_OK
+
+
+def test_graph_attention_validation():
+    lib = B.lib()
+    # the transposed input block needs its flag, and excludes the global-id input block
+    with_t0 = [block_set(1, 10, 48, 528, 480, t=True), block_set(1, 5, 8, 48, 40)]
+    assert sample(layers=with_t0, flags=B.CR_SAMPLE_TRANSPOSE_INPUT) == B.CR_OK
+    with_t0[0].gather_ids = FAKE
+    assert sample(layers=with_t0, flags=B.CR_SAMPLE_TRANSPOSE_INPUT | B.CR_SAMPLE_INPUT_GLOBAL_IDS) == B.CR_ERR_INVALID_ARG
+
+    rows = lambda **kw: lib.cr_gather_rows_bf16(vp(kw.get("store", FAKE)), kw.get("dtype", 0), kw.get("ld_src", 604), kw.get("F", 602), vp(),
+                                                vp(), kw.get("word", 1), kw.get("max_n", 100), vp(), kw.get("ld_out", 608), None)
+    assert rows() == B.CR_OK
+    assert rows(dtype=2) == B.CR_ERR_INVALID_ARG
+    assert rows(ld_src=602) == B.CR_ERR_INVALID_ARG            # float rows must keep 16-byte alignment
+    assert rows(ld_out=600) == B.CR_ERR_INVALID_ARG            # narrower than F
+    assert rows(ld_out=604) == B.CR_ERR_INVALID_ARG            # not a multiple of 8
+    assert rows(store=None) == B.CR_ERR_INVALID_ARG
+    assert rows(word=8) == B.CR_ERR_INVALID_ARG
+    assert rows(max_n=0) == B.CR_ERR_INVALID_ARG
+
+    def params(heads=4, D=64, slope=0.2, attn=FAKE):
+        return B.cr_gat_params(heads, D, slope, 0, attn)
+    bs = block_set()
+    fwd = lambda p, **kw: lib.cr_gat_attention_fwd(C.byref(kw.get("blocks", bs)), kw.get("g", 0), C.byref(p), vp(kw.get("z", FAKE)),
+                                                   kw.get("ld", 256), 1, vp(), vp(), vp(kw.get("stat", FAKE)), vp(kw.get("out", FAKE)),
+                                                   vp(kw.get("out_b", FAKE)), None)
+    assert fwd(params()) == B.CR_OK
+    assert fwd(params(heads=1, D=41), ld=64) == B.CR_OK
+    assert fwd(params(heads=0)) == B.CR_ERR_INVALID_ARG
+    assert fwd(params(heads=4, D=65)) == B.CR_ERR_INVALID_ARG         # heads * D wider than the row
+    assert fwd(params(heads=4, D=24), ld=128) == B.CR_ERR_UNSUPPORTED  # several heads: D must be 8 * 2^k
+    assert fwd(params(), ld=100) == B.CR_ERR_UNSUPPORTED
+    assert fwd(params(heads=16, D=64), ld=1024) == B.CR_ERR_UNSUPPORTED
+    assert fwd(params(slope=1.5)) == B.CR_ERR_INVALID_ARG
+    assert fwd(params(attn=None)) == B.CR_ERR_INVALID_ARG
+    assert fwd(params(), z=None) == B.CR_ERR_INVALID_ARG
+    assert fwd(params(), stat=FAKE + 4) == B.CR_ERR_INVALID_ARG
+    assert fwd(params(), out=None, out_b=None) == B.CR_ERR_INVALID_ARG
+    assert fwd(params(), g=1) == B.CR_ERR_INVALID_ARG
+    assert fwd(params(), blocks=block_set(null="indices")) == B.CR_ERR_INVALID_ARG
+
+    need = C.c_size_t(0)
+    assert lib.cr_gat_attention_bwd_workspace_bytes(8, 256, 4, C.byref(need)) == B.CR_OK and need.value > 0
+    assert lib.cr_gat_attention_bwd_workspace_bytes(0, 256, 4, C.byref(need)) == B.CR_ERR_INVALID_ARG
+    bwd = lambda p, **kw: lib.cr_gat_attention_bwd(C.byref(kw.get("blocks", bs)), 0, C.byref(p), vp(), kw.get("ld", 256), vp(), vp(),
+                                                   vp(kw.get("d_out", FAKE)), kw.get("ld_dout", 256), vp(), kw.get("lr", 0.1), 0.0,
+                                                   vp(kw.get("dz", FAKE)), None, vp(kw.get("ws", FAKE)), kw.get("ws_bytes", need.value), None)
+    lib.cr_gat_attention_bwd_workspace_bytes(8, 256, 4, C.byref(need))
+    assert bwd(params()) == B.CR_OK
+    assert bwd(params(), blocks=block_set(t=False)) == B.CR_ERR_INVALID_ARG     # needs the transposed block
+    assert bwd(params(), ld_dout=128) == B.CR_ERR_INVALID_ARG
+    assert bwd(params(), d_out=None) == B.CR_ERR_INVALID_ARG
+    assert bwd(params(), dz=None) == B.CR_ERR_INVALID_ARG
+    assert bwd(params(), lr=float("nan")) == B.CR_ERR_INVALID_ARG
+    assert bwd(params(), ws=None) == B.CR_ERR_INVALID_ARG
+    assert bwd(params(), ws_bytes=need.value - 1) == B.CR_ERR_CAPACITY
+
+    # a dense layer without a bias term is valid; one without weights is not
+    layer = B.cr_sage_layer(64, 64, 1, 0, FAKE, None, FAKE, FAKE)
+    assert lib.cr_sage_linear_fwd(C.byref(layer), vp(), 8, None, vp(), 64, 0, vp(), None, None) == B.CR_OK
+    layer.W = None
+    assert lib.cr_sage_linear_fwd(C.byref(layer), vp(), 8, None, vp(), 64, 0, vp(), None, None) == B.CR_ERR_INVALID_ARG
