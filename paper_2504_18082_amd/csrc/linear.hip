@@ -173,9 +173,14 @@ __device__ __forceinline__ void gemm_nt_body(const NtArgs &a, uint16_t (&As)[2][
             nt_step<NTILES>(st, f3, buf, As, Bs, acc);
         }
     }
-    for (; s0 < nsteps; ++s0) {
-        const NtFetch<NB> f = nt_fetch<NB>(st, s0);
-        nt_step<NTILES>(st, f, buf, As, Bs, acc);
+    while (s0 < nsteps) {         // the remaining steps (K not a multiple of 32 * CH), again fetched together: up to three at a time
+        const int rem = nsteps - s0;
+        const NtFetch<NB> f0 = nt_fetch<NB>(st, s0), f1 = nt_fetch<NB>(st, min(s0 + 1, nsteps - 1)),
+                          f2 = nt_fetch<NB>(st, min(s0 + 2, nsteps - 1));
+        nt_step<NTILES>(st, f0, buf, As, Bs, acc);
+        if (rem > 1) nt_step<NTILES>(st, f1, buf, As, Bs, acc);
+        if (rem > 2) nt_step<NTILES>(st, f2, buf, As, Bs, acc);
+        s0 += 3;
     }
 
     // Epilogue through LDS (the staging tiles are free after one more barrier): a lane holds 4-column pieces of one
