@@ -126,9 +126,10 @@ __device__ __forceinline__ bool xcd_compact(uint32_t bid, uint32_t nwork, uint32
 }
 
 // ---------------------------------------------------------------------------------------------
-// exclusive scan of n ints by one workgroup of 1024 threads (one workgroup per batch)
+// exclusive scan of one int per thread over a workgroup of NW waves (NW <= 16)
 // ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ int block_exclusive_scan_1024(int x, int *lds /*[17]*/, int &total)
+template <int NW>
+__device__ __forceinline__ int block_exclusive_scan(int x, int *lds /*[17]*/, int &total)
 {
     const int lane = lane_id(), wave = threadIdx.x / WAVE;
     int incl = x;
@@ -140,19 +141,24 @@ __device__ __forceinline__ int block_exclusive_scan_1024(int x, int *lds /*[17]*
     if (lane == WAVE - 1) lds[wave] = incl;
     __syncthreads();
     if (wave == 0) {
-        const int t = lane < 16 ? lds[lane] : 0;
+        const int t = lane < NW ? lds[lane] : 0;
         int inc = t;
 #pragma unroll
         for (int off = 1; off < 16; off <<= 1) {
             const int y = __shfl_up(inc, off);
             if (lane >= off) inc += y;
         }
-        if (lane < 16) lds[lane] = inc - t;
+        if (lane < NW) lds[lane] = inc - t;
         if (lane == 15) lds[16] = inc;
     }
     __syncthreads();
     total = lds[16];
     return lds[wave] + incl - x;
+}
+
+__device__ __forceinline__ int block_exclusive_scan_1024(int x, int *lds /*[17]*/, int &total)
+{
+    return block_exclusive_scan<16>(x, lds, total);
 }
 
 // out[0..n] = exclusive prefix sums of in[0..n) (out[n] = total), by one workgroup of 1024 threads.

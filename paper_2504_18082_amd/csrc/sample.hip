@@ -561,16 +561,60 @@ struct ScanArgs {
     int32_t *hdr;
 };
 
-__global__ __launch_bounds__(1024) void scan_kernel(ScanArgs a)
+// out[0..n] = exclusive prefix sums of in[0..n) per batch (blockIdx.y).  A workgroup owns one tile of 256 x 16
+// elements (blockIdx.x): it first adds up everything in front of its tile (the input is a few hundred KB at most and
+// sits in L2, so the tiles of a batch need no hand-off between workgroups and all of them run at once), then scans
+// its own tile.  The workgroup of the last tile also writes out[n] and the block header.
+constexpr int SCAN_ITEMS = 16;
+constexpr int SCAN_THREADS = 256;
+constexpr int SCAN_TILE = SCAN_THREADS * SCAN_ITEMS;
+
+__global__ __launch_bounds__(SCAN_THREADS) void scan_kernel(ScanArgs a)
 {
     __shared__ int lds[17];
-    const int g = blockIdx.x;
+    const int g = blockIdx.y;
     int32_t *hdr = a.hdr + (int64_t)g * CR_HDR_WORDS;
     const int n_dst = group_n_dst(a.prev_hdr, g, a.n_roots_total, a.batch_size);
     const int n = a.mode == 2 ? hdr[CR_HDR_N_SRC] : n_dst;
-    const int total = scan_chunked(a.in + (int64_t)g * a.in_stride, a.out + (int64_t)g * a.out_stride,
-                                   a.out_copy ? a.out_copy + (int64_t)g * a.copy_stride : nullptr, n, lds);
-    if (threadIdx.x == 0) {
+    const int first = (int)blockIdx.x * SCAN_TILE;
+    if (first >= n && blockIdx.x != 0) return;              // (the first workgroup also handles an empty batch)
+    const int32_t *in = a.in + (int64_t)g * a.in_stride;
+    int32_t *out = a.out + (int64_t)g * a.out_stride;
+    int32_t *out_copy = a.out_copy ? a.out_copy + (int64_t)g * a.copy_stride : nullptr;
+
+    int before = 0;                                          // sum of in[0..first)
+    if (first > 0) {
+        int part = 0;
+        for (int i0 = (int)threadIdx.x; i0 < first; i0 += SCAN_TILE) {      // first is a multiple of the tile size
+            int x[SCAN_ITEMS];
+#pragma unroll
+            for (int k = 0; k < SCAN_ITEMS; ++k) x[k] = in[i0 + k * SCAN_THREADS];
+#pragma unroll
+            for (int k = 0; k < SCAN_ITEMS; ++k) part += x[k];
+        }
+        block_exclusive_scan<SCAN_THREADS / WAVE>(part, lds, before);
+        __syncthreads();                                     // lds is reused below
+    }
+    const int start = first + (int)threadIdx.x * SCAN_ITEMS;
+    int x[SCAN_ITEMS];
+#pragma unroll
+    for (int i = 0; i < SCAN_ITEMS; ++i) x[i] = start + i < n ? in[start + i] : 0;
+    int sum = 0;
+#pragma unroll
+    for (int i = 0; i < SCAN_ITEMS; ++i) sum += x[i];
+    int tile_total;
+    int run = before + block_exclusive_scan<SCAN_THREADS / WAVE>(sum, lds, tile_total);
+#pragma unroll
+    for (int i = 0; i < SCAN_ITEMS; ++i) {
+        if (start + i < n) {
+            out[start + i] = run;
+            if (out_copy) out_copy[start + i] = run;
+        }
+        run += x[i];
+    }
+    if (threadIdx.x == 0 && n <= first + SCAN_TILE) {        // the last tile
+        const int total = before + tile_total;
+        out[n] = total;
         if (a.mode == 0) {
             hdr[CR_HDR_N_DST] = n_dst;
             hdr[CR_HDR_NNZ] = total;
@@ -1034,7 +1078,8 @@ extern "C" cr_status cr_sample_blocks(const cr_graph *graph, const cr_sample_cfg
         sc.prev_hdr = prev_hdr; sc.n_roots_total = n_roots_total; sc.batch_size = batch_size;
         sc.mode = 0; sc.in = p.cnt; sc.in_stride = p.max_dst; sc.out = b.indptr; sc.out_stride = b.cap_dst + 1;
         sc.out_copy = nullptr; sc.copy_stride = 0; sc.hdr = b.hdr;
-        hipLaunchKernelGGL(scan_kernel, dim3(n_batches), dim3(1024), 0, s, sc);
+        const dim3 scan_grid((unsigned)ceil_div(cap_dst, SCAN_TILE), n_batches);
+        hipLaunchKernelGGL(scan_kernel, scan_grid, dim3(SCAN_THREADS), 0, s, sc);
 
         DedupArgs da;
         da.prev_hdr = prev_hdr; da.n_roots_total = n_roots_total; da.batch_size = batch_size; da.fanout = f;
@@ -1069,7 +1114,7 @@ extern "C" cr_status cr_sample_blocks(const cr_graph *graph, const cr_sample_cfg
         hipLaunchKernelGGL(insert_kernel, grid, blk, 0, s, da);
         hipLaunchKernelGGL(mark_new_kernel, grid, blk, 0, s, da);
         sc.mode = 1; sc.in = p.cnt; sc.in_stride = p.max_dst; sc.out = p.newoff; sc.out_stride = p.max_dst + 1;
-        hipLaunchKernelGGL(scan_kernel, dim3(n_batches), dim3(1024), 0, s, sc);
+        hipLaunchKernelGGL(scan_kernel, scan_grid, dim3(SCAN_THREADS), 0, s, sc);
         hipLaunchKernelGGL(assign_kernel, grid, blk, 0, s, da);
         hipLaunchKernelGGL(relabel_kernel, grid, blk, 0, s, da);
         if (p.direct)
@@ -1077,7 +1122,7 @@ extern "C" cr_status cr_sample_blocks(const cr_graph *graph, const cr_sample_cfg
         if (tr) {
             sc.mode = 2; sc.in = p.tcount; sc.in_stride = p.max_src_t + 1; sc.out = b.t_indptr; sc.out_stride = b.cap_src + 1;
             sc.out_copy = p.tfill; sc.copy_stride = p.max_src_t + 1;
-            hipLaunchKernelGGL(scan_kernel, dim3(n_batches), dim3(1024), 0, s, sc);
+            hipLaunchKernelGGL(scan_kernel, dim3((unsigned)ceil_div(b.cap_src, SCAN_TILE), n_batches), dim3(SCAN_THREADS), 0, s, sc);
             hipLaunchKernelGGL(t_fill_kernel, grid, blk, 0, s, da);
             hipLaunchKernelGGL(t_rank_kernel, grid, blk, 0, s, da);
         }
