@@ -5,9 +5,14 @@
 
 namespace cr {
 
+// load_raw / unpack split a row-chunk load from its conversion: inside the edge loops the loads sit under a
+// condition, and a conversion in the same branch would make every load wait for its data before the next is issued.
 template <typename T> struct Vec16;
 template <> struct Vec16<float> {
     static constexpr int N = 4;
+    using Raw = float4;
+    __device__ static __forceinline__ Raw load_raw(const float *p) { return *reinterpret_cast<const float4 *>(p); }
+    __device__ static __forceinline__ void unpack(const Raw &x, float (&v)[4]) { v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w; }
     __device__ static __forceinline__ void load(const float *p, float (&v)[4])
     {
         const float4 x = *reinterpret_cast<const float4 *>(p);
@@ -16,6 +21,15 @@ template <> struct Vec16<float> {
 };
 template <> struct Vec16<uint16_t> {
     static constexpr int N = 8;
+    using Raw = uint4;
+    __device__ static __forceinline__ Raw load_raw(const uint16_t *p) { return *reinterpret_cast<const uint4 *>(p); }
+    __device__ static __forceinline__ void unpack(const Raw &x, float (&v)[8])
+    {
+        v[0] = __uint_as_float(x.x << 16); v[1] = __uint_as_float(x.x & 0xFFFF0000u);
+        v[2] = __uint_as_float(x.y << 16); v[3] = __uint_as_float(x.y & 0xFFFF0000u);
+        v[4] = __uint_as_float(x.z << 16); v[5] = __uint_as_float(x.z & 0xFFFF0000u);
+        v[6] = __uint_as_float(x.w << 16); v[7] = __uint_as_float(x.w & 0xFFFF0000u);
+    }
     __device__ static __forceinline__ void load(const uint16_t *p, float (&v)[8])
     {
         const uint4 x = *reinterpret_cast<const uint4 *>(p);
@@ -131,7 +145,7 @@ __global__ __launch_bounds__(256) void gather_mean_fwd_kernel(
             if (base > s0) rid = load_ids(base, e0, wgt);       // rows longer than the group width
             const int cnt = min(LPR, e0 - base);
             for (int t = 0; t < cnt; t += U) {
-                float v[U][NCHUNK][VEC];
+                typename Vec16<T>::Raw v[U][NCHUNK];
                 float wu[U];
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
@@ -141,7 +155,7 @@ __global__ __launch_bounds__(256) void gather_mean_fwd_kernel(
 #pragma unroll
                     for (int c = 0; c < NCHUNK; ++c) {
                         const int col = (c * LPR + gl) * VEC;
-                        if (col < F && t + u < cnt) Vec16<T>::load(p + col, v[u][c]);
+                        if (col < F && t + u < cnt) v[u][c] = Vec16<T>::load_raw(p + col);
                     }
                 }
 #pragma unroll
@@ -150,10 +164,12 @@ __global__ __launch_bounds__(256) void gather_mean_fwd_kernel(
                     for (int c = 0; c < NCHUNK; ++c) {
                         const int col = (c * LPR + gl) * VEC;
                         if (col < F && t + u < cnt) {
+                            float f[VEC];
+                            Vec16<T>::unpack(v[u][c], f);
 #pragma unroll
                             for (int i = 0; i < VEC; ++i) {
-                                if constexpr (GCN) acc[c][i] += wu[u] * v[u][c][i];
-                                else acc[c][i] += v[u][c][i];
+                                if constexpr (GCN) acc[c][i] += wu[u] * f[i];
+                                else acc[c][i] += f[i];
                             }
                         }
                     }
@@ -292,34 +308,57 @@ __global__ __launch_bounds__(256) void gather_mean_bwd_kernel(
 #pragma unroll
             for (int i = 0; i < VEC; ++i) acc[c][i] = 0.f;
 
+        // bf16 gradients: the row's own d_self chunk and its ReLU mask are requested here, branch-free (a stand-in
+        // address when there is none, applied with weight 0 / ignored), so that they travel while the edge loop runs
+        // instead of costing two more round trips after it
+        constexpr bool PRE = VEC == 8;
+        const bool mask_bf16 = relu_out != nullptr && relu_is_bf16 != 0;
+        uint4 self_raw[NCHUNK], mask_raw[NCHUNK];
+        if constexpr (PRE) {
+            const int sd = max(min(s, n_dst - 1), 0);
+            const uint16_t *sp = reinterpret_cast<const uint16_t *>(d_self ? d_self : d_agg) + (int64_t)sd * ld_in;
+            const uint16_t *mp = mask_bf16 ? static_cast<const uint16_t *>(relu_out) + (int64_t)s * ld_relu
+                                           : reinterpret_cast<const uint16_t *>(d_agg) + (int64_t)sd * ld_in;
+#pragma unroll
+            for (int c = 0; c < NCHUNK; ++c) {
+                const int col = (c * LPR + gl) * VEC;
+                const int colc = col < F ? col : 0;
+                self_raw[c] = *reinterpret_cast<const uint4 *>(sp + colc);
+                mask_raw[c] = *reinterpret_cast<const uint4 *>(mp + colc);
+            }
+        }
+
         int v = v0;
         float w = w0;
         for (int base = b0; base < e0; base += LPR) {
             if (base > b0) load_ids(base, e0, v, w);
             const int cnt = min(LPR, e0 - base);
             for (int t = 0; t < cnt; t += U) {
-                float x[U][NCHUNK][VEC];
+                // branch-free: a slot past the segment's end re-reads the segment's last row with weight 0, a lane past
+                // the row's end reads column 0; so the U loads are issued back to back
+                typename Vec16<T>::Raw x[U][NCHUNK];
                 float ww[U];
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
-                    const int vv = __shfl(v, t + u, LPR);
-                    ww[u] = __shfl(w, t + u, LPR);
+                    const int src = min(t + u, cnt - 1);
+                    const int vv = __shfl(v, src, LPR);
+                    const float wv = __shfl(w, src, LPR);
+                    ww[u] = t + u < cnt ? wv : 0.f;
                     const T *p = d_agg + (int64_t)vv * ld_in;
 #pragma unroll
                     for (int c = 0; c < NCHUNK; ++c) {
                         const int col = (c * LPR + gl) * VEC;
-                        if (col < F && t + u < cnt) Vec16<T>::load(p + col, x[u][c]);
+                        x[u][c] = Vec16<T>::load_raw(p + (col < F ? col : 0));
                     }
                 }
 #pragma unroll
                 for (int u = 0; u < U; ++u)
 #pragma unroll
                     for (int c = 0; c < NCHUNK; ++c) {
-                        const int col = (c * LPR + gl) * VEC;
-                        if (col < F && t + u < cnt) {
+                        float f[VEC];
+                        Vec16<T>::unpack(x[u][c], f);
 #pragma unroll
-                            for (int i = 0; i < VEC; ++i) acc[c][i] += x[u][c][i] * ww[u];
-                        }
+                        for (int i = 0; i < VEC; ++i) acc[c][i] += f[i] * ww[u];
                     }
             }
         }
@@ -332,14 +371,28 @@ __global__ __launch_bounds__(256) void gather_mean_bwd_kernel(
 #pragma unroll
                     for (int i = 0; i < VEC; ++i) acc[c][i] *= ws;
                 }
-                if (d_self && s < n_dst) {
+                if constexpr (PRE) {
+                    if (d_self && s < n_dst) {
+                        float x[8];
+                        Vec16<uint16_t>::unpack(self_raw[c], x);
+                        const float wself = GCN ? gcn.dst_self[s] : 1.0f;
+#pragma unroll
+                        for (int i = 0; i < VEC; ++i) acc[c][i] += wself * x[i];
+                    }
+                } else if (d_self && s < n_dst) {
                     float x[VEC];
                     Vec16<T>::load(d_self + (int64_t)s * ld_in + col, x);
                     const float wself = GCN ? gcn.dst_self[s] : 1.0f;
 #pragma unroll
                     for (int i = 0; i < VEC; ++i) acc[c][i] += wself * x[i];
                 }
-                if (relu_out) {
+                if (PRE && mask_bf16) {
+                    float y[8];
+                    Vec16<uint16_t>::unpack(mask_raw[c], y);
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i)
+                        if (!(y[i] > 0.f)) acc[c][i] = 0.f;
+                } else if (relu_out) {
                     float y[VEC];
                     if (relu_is_bf16) {
                         const uint16_t *r = static_cast<const uint16_t *>(relu_out) + (int64_t)s * ld_relu + col;
