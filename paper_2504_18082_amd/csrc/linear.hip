@@ -466,6 +466,13 @@ __global__ __launch_bounds__(256) void sgd_reduce_kernel(SgdArgs a)
     const int kin = k2 % a.F_pad, part = k2 / a.F_pad;
     const bool live = in_range && n < a.F_out && (is_bias || kin < a.F_in);
 
+    // the master weights this lane will update are requested now (one 16-byte load when the rows allow it), so that
+    // they arrive while the partial sums are added up
+    const int64_t wi = (int64_t)(part * a.F_in + kin) * a.F_out + n;
+    const bool w_vec = (a.F_out & 3) == 0;
+    float4 wq = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (w_vec) wq = *reinterpret_cast<const float4 *>(a.W + ((live && !is_bias) ? wi : 0));      // (uniform condition)
+
     float4 g = make_float4(0.f, 0.f, 0.f, 0.f);
     if (live) {
         const float *pp = a.partial + (int64_t)k2 * a.N_pad + n;
@@ -498,12 +505,12 @@ __global__ __launch_bounds__(256) void sgd_reduce_kernel(SgdArgs a)
         }
         return;
     }
-    const int64_t wi = (int64_t)(part * a.F_in + kin) * a.F_out + n;
+    const float wv[4] = {wq.x, wq.y, wq.z, wq.w};
     uint16_t wb[4] = {0, 0, 0, 0};
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         if (n + i < a.F_out) {
-            float w = a.W[wi + i];
+            float w = w_vec ? wv[i] : a.W[wi + i];
             if (a.dW_out) a.dW_out[wi + i] = gs[i];
             w -= a.lr * (gs[i] + a.wd * w);
             a.W[wi + i] = w;
