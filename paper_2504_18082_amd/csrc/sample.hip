@@ -517,12 +517,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
             // every lane computes its slot's key; lanes of rows that keep all their neighbours ignore it
             const uint64_t ck = slot_key<MODE>(a, slot_word(a, j, my_v, batch), intra);
             int rank = 0;
-            for (int d = 0; d < maxlen; ++d) {
-                const int src = my_start + d;
-                uint64_t ok;
-                if (WIDE) ok = ((uint64_t)pull32((uint32_t)(ck >> 32), src) << 32) | pull32((uint32_t)ck, src);
-                else ok = pull32((uint32_t)ck, src);
-                rank += (d < my_len && (ok < ck || (ok == ck && d < j))) ? 1 : 0;
+            for (int d0 = 0; d0 < maxlen; d0 += 4) {          // four independent lane exchanges in flight per step
+                uint64_t ok[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int src = my_start + d0 + q;
+                    if (WIDE) ok[q] = ((uint64_t)pull32((uint32_t)(ck >> 32), src) << 32) | pull32((uint32_t)ck, src);
+                    else ok[q] = pull32((uint32_t)ck, src);
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int d = d0 + q;
+                    rank += (d < my_len && (ok[q] < ck || (ok[q] == ck && d < j))) ? 1 : 0;
+                }
             }
             if (active && my_len > f) survivor = rank < f && !(WIDE && a.strict_p1 && ck >= (1ull << 62));
         }
