@@ -157,3 +157,29 @@ def test_gcn_fit_on_tiny(tiny_workload):
     hist = tr.fit(oracle.COMM_RAND, 6, 0.9, val, max_epochs=10, patience=6, lr_patience=3)
     print("gcn val acc", [round(v, 4) for v in hist.val_acc], flush=True)
     assert min(hist.val_loss) < 0.8 * loss0 and max(hist.val_acc) > 3.0 / w.cfg.n_classes
+
+
+def test_gcn_forward_at_benchmark_size(arxiv_workload):
+    """The GCN forward pass in the measured configuration (arxiv-like workload, groups of 16 mini-batches of 1024 roots,
+    three layers), checked on sampled outputs: a node's sampled neighbours depend on (seed, epoch, batch, layer, node)
+    only, so the oracle computes the logits of a few roots of the batch from their own three-hop trees."""
+    import torch
+    from paper_2504_18082_amd.trainer import Trainer
+    from oracle_step import oracle_train_step_gcn
+    w, seed, epoch, p, g = arxiv_workload, 0, 2, 0.5, 9
+    cfg = w.cfg
+    weights = synth.init_weights(cfg, seed, n_operands=1)
+    tr = Trainer(w, group_size=16, lr=0.05, seed=seed, weights=weights, model="gcn")
+    tr.build_batches(oracle.RAND, 1, epoch)
+    perm = oracle.build_batches(oracle.RAND, 1, seed, epoch, w.train_ids, w.comm, cfg.n_comm)
+    tr.sample_group(0, 16, p, epoch)
+    print("gcn forward at benchmark size", flush=True)
+    tr.forward_batch(g)
+    torch.cuda.synchronize()
+    logits = tr.out[tr.L - 1].cpu().numpy()
+    roots = perm[g * cfg.batch_size:(g + 1) * cfg.batch_size]
+    assert np.array_equal(tr.blocks[tr.L - 1].src_ids[g, :len(roots)].cpu().numpy(), roots)
+    params = [(W.astype(np.float64), b.astype(np.float64)) for W, b in weights]
+    pick = np.arange(0, len(roots), 128)
+    ref = oracle_train_step_gcn(w.graph, w.features, cfg.n_feat, w.labels, roots[pick], cfg.fanouts, p, seed, epoch, g, params, 0.0, 0.0)
+    assert_close(logits[pick, :cfg.n_classes], ref["logits"], 2e-2, "logits of sampled roots")
