@@ -135,6 +135,8 @@ def main():
     ap.add_argument("--no-input-stats", action="store_true",
                     help="skip the untimed extra sampling pass that counts the distinct input nodes per batch (keeps a "
                          "kernel trace down to the timed path)")
+    ap.add_argument("--row-order", default="auto", choices=["auto", "on", "off"],
+                    help="process the input-side block's rows in community order (auto: when a batch holds >= 32 rows per community)")
     ap.add_argument("--overlap", default="none", choices=["none", "sample", "sample+weights", "all"],
                     help="side streams: 'sample' = sampling of the next group overlaps training; '+weights' = weight "
                          "gradients and SGD leave the backward pass's critical path; 'all' = also the layer-0 gather "
@@ -163,7 +165,8 @@ def main():
         wl_cfg = synth.scaled(wl_cfg, args.scale)
     w = synth.make_workload(wl_cfg, seed=args.seed)
     cfg = w.cfg
-    tr = Trainer(w, group_size=args.group, lr=0.01, weight_decay=5e-4, seed=args.seed)
+    tr = Trainer(w, group_size=args.group, lr=0.01, weight_decay=5e-4, seed=args.seed,
+                 order_rows={"auto": "auto", "on": True, "off": False}[args.row_order])
     steps = args.steps if args.steps is not None else tr.n_batches          # default: one epoch
     c_train = int(len(np.unique(w.comm[w.train_ids])))
     mix_mid = B.cr_mix_count_from_percent(12.5, c_train)
@@ -217,6 +220,7 @@ def main():
                                f"batch {cfg.batch_size}, {tr.n_batches} batches/epoch",
                    "setting": "fully random: RAND-ROOTS p=0.5", "group_size": args.group,
                    "schedule": "one stream" if args.overlap == "none" else "side streams: " + args.overlap,
+                   "row_order": "input-side rows processed in community order" if tr.order_rows else "input-side rows processed in block order",
                    "value_definition": "layer-0 gathered feature bytes per second of whole-step time"},
         "epoch_ms": round(main_res["ms_per_step"] * tr.n_batches, 3),
         "host_enqueue_ms_per_step": round(main_res["host_enqueue_ms_per_step"], 4),

@@ -129,7 +129,8 @@ cr_status cr_graph_edge_classes(const cr_graph *graph, uint32_t *edge_intra, voi
  * slot ascending); indptr/indices are a CSR over local source positions.  t_indptr/t_indices hold
  * the transposed block (for every source position the destination rows that use it, ascending);
  * they may be NULL when the layer's input needs no gradient, and must be NULL for layer 0 (the
- * feature table takes no gradient) unless CR_SAMPLE_TRANSPOSE_INPUT is set.  gather_ids is optional for every layer. */
+ * feature table takes no gradient) unless CR_SAMPLE_TRANSPOSE_INPUT is set.  gather_ids is optional for every layer.
+ * row_order is optional too: a processing order for the destination rows (see the field). */
 typedef struct {
     int32_t n_batches;
     int32_t fanout;
@@ -146,6 +147,14 @@ typedef struct {
     int32_t *gather_ids;/* device int32[n_batches][cap_nnz] or NULL: global id of every edge's source,
                            gather_ids[e] == src_ids[indices[e]]; lets the layer-0 feature gather skip one
                            level of indirection */
+    int32_t *row_order; /* device int32[n_batches][cap_dst] or NULL: per batch a permutation of 0..n_dst-1.  Filled by
+                           cr_sample_blocks (with CR_SAMPLE_ROW_ORDER) where it is given: destination rows grouped by the community of
+                           their node
+                           (communities ascending; the order inside a community is unspecified and may differ from run
+                           to run).  cr_gather_aggregate_fwd and cr_gcn_aggregate_fwd walk the rows in this order, so
+                           that rows which share source rows are worked on next to each other and meet in L1/L2 (the
+                           locality Section 3 of the paper gets from the batch's composition, here from the order of
+                           the work inside a batch).  A scheduling hint only: no result depends on it. */
 } cr_block_set;
 
 #define CR_SAMPLE_STRICT_INTRA 1u /* at p = 1 never take an inter-community neighbour (rows may be short) */
@@ -162,6 +171,9 @@ typedef struct {
 #define CR_SAMPLE_TRANSPOSE_INPUT 8u /* layers[0] may carry t_indptr / t_indices too (a model whose first layer needs a
                                      gradient per source row: graph attention projects the source rows before it
                                      aggregates).  Not together with CR_SAMPLE_INPUT_GLOBAL_IDS. */
+
+#define CR_SAMPLE_ROW_ORDER 16u /* fill the row_order array of every layer whose block set carries one (the workspace is
+                                  then larger: set the flag for cr_sample_blocks_workspace_bytes too) */
 
 typedef struct {
     int32_t n_layers;              /* 1..CR_MAX_LAYERS */

@@ -24,6 +24,7 @@ CR_SAMPLE_STRICT_INTRA = 1
 CR_SAMPLE_HASH_DEDUP = 2
 CR_SAMPLE_INPUT_GLOBAL_IDS = 4
 CR_SAMPLE_TRANSPOSE_INPUT = 8
+CR_SAMPLE_ROW_ORDER = 16
 
 EXPORTS = [
     "cr_last_error", "cr_version", "cr_set_dry_run", "cr_mix_count_from_percent",
@@ -70,7 +71,7 @@ class cr_block_set(C.Structure):
                 ("cap_src", C.c_int32), ("cap_nnz", C.c_int32), ("reserved", C.c_int32),
                 ("hdr", C.c_void_p), ("src_ids", C.c_void_p), ("indptr", C.c_void_p),
                 ("indices", C.c_void_p), ("t_indptr", C.c_void_p), ("t_indices", C.c_void_p),
-                ("gather_ids", C.c_void_p)]
+                ("gather_ids", C.c_void_p), ("row_order", C.c_void_p)]
 
 
 class cr_sample_cfg(C.Structure):
@@ -199,7 +200,7 @@ def cr_block_capacities(cfg: cr_sample_cfg, n_nodes: int, batch_size: int):
 class BlockSet:
     """Device storage of one layer's blocks for a group of batches (torch int32 tensors)."""
 
-    def __init__(self, n_batches, fanout, cap_dst, cap_src, cap_nnz, transposed, device="cuda", gather_ids=False):
+    def __init__(self, n_batches, fanout, cap_dst, cap_src, cap_nnz, transposed, device="cuda", gather_ids=False, row_order=False):
         import torch
         z = lambda *shape: torch.zeros(shape, dtype=torch.int32, device=device)
         self.n_batches, self.fanout = n_batches, fanout
@@ -211,9 +212,10 @@ class BlockSet:
         self.t_indptr = z(n_batches, cap_src + 1) if transposed else None
         self.t_indices = z(n_batches, cap_nnz) if transposed else None
         self.gather_ids = z(n_batches, cap_nnz) if gather_ids else None
+        self.row_order = z(n_batches, cap_dst) if row_order else None       # processing order of the destination rows
         self.c = cr_block_set(n_batches, fanout, cap_dst, cap_src, cap_nnz, 0, _ptr(self.hdr),
                               _ptr(self.src_ids), _ptr(self.indptr), _ptr(self.indices),
-                              _ptr(self.t_indptr), _ptr(self.t_indices), _ptr(self.gather_ids))
+                              _ptr(self.t_indptr), _ptr(self.t_indices), _ptr(self.gather_ids), _ptr(self.row_order))
 
     def hdr_ptr(self, g):
         return C.c_void_p(self.hdr.data_ptr() + g * CR_HDR_WORDS * 4)
@@ -229,7 +231,10 @@ class BlockSet:
         import torch
         tr = getattr(blk, "t_indptr", None) is not None
         cap_dst, cap_src, cap_nnz = max(1, blk.n_dst), max(1, blk.n_src, blk.n_dst), max(1, blk.nnz)
-        bs = cls(1, fanout, cap_dst, cap_src, cap_nnz, tr, device, gather_ids)
+        order = getattr(blk, "row_order", None)
+        bs = cls(1, fanout, cap_dst, cap_src, cap_nnz, tr, device, gather_ids, row_order=order is not None)
+        if order is not None:
+            bs.row_order[0, :blk.n_dst] = torch.from_numpy(np.ascontiguousarray(order, dtype=np.int32)).to(device)
         up = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(device)
         bs.hdr[0, :3] = up([blk.n_dst, blk.n_src, blk.nnz])
         bs.src_ids[0, :blk.n_src] = up(blk.src_ids)
@@ -244,10 +249,12 @@ class BlockSet:
 
 
 def alloc_block_sets(cfg: cr_sample_cfg, n_nodes: int, batch_size: int, n_batches: int,
-                     device="cuda", transpose_input: bool = False) -> List[BlockSet]:
-    """transpose_input: layer 0 gets a transposed block too (sampling then needs CR_SAMPLE_TRANSPOSE_INPUT)."""
+                     device="cuda", transpose_input: bool = False, order_input: bool = False) -> List[BlockSet]:
+    """transpose_input: layer 0 gets a transposed block too (sampling then needs CR_SAMPLE_TRANSPOSE_INPUT);
+    order_input: layer 0 gets a processing order of its destination rows (grouped by community)."""
     cap_dst, cap_src, cap_nnz = cr_block_capacities(cfg, n_nodes, batch_size)
-    return [BlockSet(n_batches, cfg.fanout[l], cap_dst[l], cap_src[l], cap_nnz[l], l >= 1 or transpose_input, device, gather_ids=(l == 0))
+    return [BlockSet(n_batches, cfg.fanout[l], cap_dst[l], cap_src[l], cap_nnz[l], l >= 1 or transpose_input, device, gather_ids=(l == 0),
+                     row_order=(order_input and l == 0))
             for l in range(cfg.n_layers)]
 
 

@@ -85,7 +85,7 @@ __global__ __launch_bounds__(256) void gather_mean_fwd_kernel(
     const int32_t *__restrict__ ids, const int32_t *__restrict__ edge_map,
     const int32_t *__restrict__ self_map, const T *__restrict__ table, int64_t ld, int F,
     float *__restrict__ agg, uint16_t *__restrict__ agg_bf16, uint16_t *__restrict__ self_bf16, int64_t ld_bf16,
-    GcnFwd gcn = GcnFwd{nullptr, nullptr, nullptr, nullptr})
+    GcnFwd gcn = GcnFwd{nullptr, nullptr, nullptr, nullptr}, const int32_t *__restrict__ order = nullptr)
 {
     constexpr int VEC = Vec16<T>::N;
     constexpr int U = NCHUNK == 1 ? 8 : (NCHUNK <= 3 ? 4 : 2);   // independent row loads in flight per lane
@@ -100,9 +100,15 @@ __global__ __launch_bounds__(256) void gather_mean_fwd_kernel(
     int row = block_first + (int)(threadIdx.x / LPR);
     if (row >= block_end) return;
 
-    float sc0 = 0.f, sf0 = 0.f, sc1 = 0.f, sf1 = 0.f, sc2 = 0.f, sf2 = 0.f;     // GCN: destination scale / self weight
-    auto load_ptrs = [&](int r, int &s, int &e, int &self_row, float &sc, float &sf) {
+    // `order` (optional) is a permutation of the destination rows: position i of the walk handles row order[i].  It only
+    // changes which workgroup computes a row and when (rows that share sources next to each other hit in L1/L2); the
+    // row ids are fetched one more stage ahead of the pointers.
+    auto load_row = [&](int r) -> int {
         const int rc = min(r, n_dst - 1);
+        return order ? order[rc] : rc;
+    };
+    float sc0 = 0.f, sf0 = 0.f, sc1 = 0.f, sf1 = 0.f, sc2 = 0.f, sf2 = 0.f;     // GCN: destination scale / self weight
+    auto load_ptrs = [&](int r, int rc, int &s, int &e, int &self_row, float &sc, float &sf) {
         const int a = indptr[rc], b = indptr[rc + 1];
         const int sr = self_map ? self_map[rc] : rc;
         if constexpr (GCN) { sc = gcn.dst_scale[rc]; sf = gcn.dst_self[rc]; }
@@ -123,15 +129,17 @@ __global__ __launch_bounds__(256) void gather_mean_fwd_kernel(
 
     int s0, e0, self0, s1, e1, self1;
     float w0 = 1.f, w1 = 1.f;
-    load_ptrs(row, s0, e0, self0, sc0, sf0);
+    int out0 = load_row(row), out1 = load_row(row + GPB), out2 = load_row(row + 2 * GPB);   // rows handled now, next, after next
+    load_ptrs(row, out0, s0, e0, self0, sc0, sf0);
     int rid0 = load_ids(s0, e0, w0);
-    load_ptrs(row + GPB, s1, e1, self1, sc1, sf1);
+    load_ptrs(row + GPB, out1, s1, e1, self1, sc1, sf1);
 
     for (; row < block_end; row += GPB) {
         // look ahead: ids of the next destination, pointers of the one after
         const int rid1 = load_ids(s1, e1, w1);
         int s2, e2, self2;
-        load_ptrs(row + 2 * GPB, s2, e2, self2, sc2, sf2);
+        load_ptrs(row + 2 * GPB, out2, s2, e2, self2, sc2, sf2);
+        const int out3 = load_row(row + 3 * GPB);
 
         float acc[NCHUNK][VEC];
 #pragma unroll
@@ -193,7 +201,7 @@ __global__ __launch_bounds__(256) void gather_mean_fwd_kernel(
                 for (int i = 0; i < VEC; ++i) acc[c][i] = acc[c][i] / fdeg;
             }
             if (agg && col < F) {
-                float *o = agg + (int64_t)row * F + col;
+                float *o = agg + (int64_t)out0 * F + col;
                 if ((F & 3) == 0) {
 #pragma unroll
                     for (int i = 0; i < VEC; i += 4)
@@ -204,7 +212,7 @@ __global__ __launch_bounds__(256) void gather_mean_fwd_kernel(
                         if (col + i < F) o[i] = acc[c][i];
                 }
             }
-            if (agg_bf16 && col < ld_bf16) store_bf16_row<VEC>(agg_bf16 + (int64_t)row * ld_bf16 + col, acc[c], col, F);
+            if (agg_bf16 && col < ld_bf16) store_bf16_row<VEC>(agg_bf16 + (int64_t)out0 * ld_bf16 + col, acc[c], col, F);
         }
 
         if (self_bf16) {
@@ -217,13 +225,13 @@ __global__ __launch_bounds__(256) void gather_mean_fwd_kernel(
 #pragma unroll
                     for (int i = 0; i < VEC; ++i) v[i] = 0.f;
                     if (col < F) Vec16<T>::load(p + col, v);
-                    store_bf16_row<VEC>(self_bf16 + (int64_t)row * ld_bf16 + col, v, col, F);
+                    store_bf16_row<VEC>(self_bf16 + (int64_t)out0 * ld_bf16 + col, v, col, F);
                 }
             }
         }
 
-        s0 = s1; e0 = e1; self0 = self1; rid0 = rid1; w0 = w1; sc0 = sc1; sf0 = sf1;
-        s1 = s2; e1 = e2; self1 = self2; sc1 = sc2; sf1 = sf2;
+        s0 = s1; e0 = e1; self0 = self1; rid0 = rid1; w0 = w1; sc0 = sc1; sf0 = sf1; out0 = out1;
+        s1 = s2; e1 = e2; self1 = self2; sc1 = sc2; sf1 = sf2; out1 = out2; out2 = out3;
     }
 }
 
@@ -231,18 +239,18 @@ template <typename T, int LPR, int NCHUNK>
 static void launch_fwd(int cap_dst, const int32_t *hdr, const int32_t *indptr, const int32_t *ids,
                        const int32_t *edge_map, const int32_t *self_map, const void *table, int64_t ld, int F,
                        float *agg, uint16_t *agg_bf16, uint16_t *self_bf16, int64_t ld_bf16, hipStream_t st,
-                       const GcnFwd *gcn = nullptr)
+                       const GcnFwd *gcn = nullptr, const int32_t *order = nullptr)
 {
     constexpr int GPB = 256 / LPR;
     int64_t grid = ceil_div(cap_dst, GPB);
     if (grid > 1024) grid = 1024;          // 4 workgroups per CU; each group then walks several rows
     if (gcn)
         hipLaunchKernelGGL((gather_mean_fwd_kernel<T, LPR, NCHUNK, true>), dim3((unsigned)grid), dim3(256), 0, st, hdr, indptr,
-                           ids, edge_map, self_map, static_cast<const T *>(table), ld, F, agg, agg_bf16, self_bf16, ld_bf16, *gcn);
+                           ids, edge_map, self_map, static_cast<const T *>(table), ld, F, agg, agg_bf16, self_bf16, ld_bf16, *gcn, order);
     else
         hipLaunchKernelGGL((gather_mean_fwd_kernel<T, LPR, NCHUNK, false>), dim3((unsigned)grid), dim3(256), 0, st, hdr, indptr,
                            ids, edge_map, self_map, static_cast<const T *>(table), ld, F, agg, agg_bf16, self_bf16, ld_bf16,
-                           GcnFwd{nullptr, nullptr, nullptr, nullptr});
+                           GcnFwd{nullptr, nullptr, nullptr, nullptr}, order);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -514,7 +522,8 @@ static void run_fwd(const cr_block_set *blocks, int32_t g, const void *H_src, in
         else edge_map = src_ids;
     }
     const int cap = blocks->cap_dst;
-#define CR_FWD(T, LPR, NC) launch_fwd<T, LPR, NC>(cap, hdr, indptr, ids, edge_map, self_map, H_src, ld_src, F, agg, agg_bf16, self_bf16, ld_bf16, s, gcn)
+    const int32_t *order = blocks->row_order ? blocks->row_order + (int64_t)g * blocks->cap_dst : nullptr;
+#define CR_FWD(T, LPR, NC) launch_fwd<T, LPR, NC>(cap, hdr, indptr, ids, edge_map, self_map, H_src, ld_src, F, agg, agg_bf16, self_bf16, ld_bf16, s, gcn, order)
     if (dtype == CR_F32) {
         if (F <= 64) CR_FWD(float, 16, 1);
         else if (F <= 128) CR_FWD(float, 32, 1);

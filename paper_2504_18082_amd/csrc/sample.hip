@@ -558,7 +558,8 @@ struct ScanArgs {
     const int32_t *prev_hdr;
     int64_t n_roots_total;
     int32_t batch_size;
-    int32_t mode;          // 0: row counts -> indptr ; 1: new-node counts -> offsets ; 2: source counts -> t_indptr
+    int32_t mode;          // 0: row counts -> indptr ; 1: new-node counts -> offsets ; 2: source counts -> t_indptr ;
+                           // 3: n_fixed values per batch, no header involved
     const int32_t *in;
     int64_t in_stride;
     int32_t *out;
@@ -566,6 +567,7 @@ struct ScanArgs {
     int32_t *out_copy;     // mode 2: fill cursors
     int64_t copy_stride;
     int32_t *hdr;
+    int32_t n_fixed;
 };
 
 // out[0..n] = exclusive prefix sums of in[0..n) per batch (blockIdx.y).  A workgroup owns one tile of 256 x 16
@@ -582,7 +584,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_kernel(ScanArgs a)
     const int g = blockIdx.y;
     int32_t *hdr = a.hdr + (int64_t)g * CR_HDR_WORDS;
     const int n_dst = group_n_dst(a.prev_hdr, g, a.n_roots_total, a.batch_size);
-    const int n = a.mode == 2 ? hdr[CR_HDR_N_SRC] : n_dst;
+    const int n = a.mode == 3 ? a.n_fixed : (a.mode == 2 ? hdr[CR_HDR_N_SRC] : n_dst);
     const int first = (int)blockIdx.x * SCAN_TILE;
     if (first >= n && blockIdx.x != 0) return;              // (the first workgroup also handles an empty batch)
     const int32_t *in = a.in + (int64_t)g * a.in_stride;
@@ -630,6 +632,71 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_kernel(ScanArgs a)
         } else if (a.mode == 1) {
             hdr[CR_HDR_N_SRC] = n_dst + total;
         }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Processing order of a block's destination rows (cr_block_set.row_order): rows grouped by the community of their
+// node, a counting sort per batch over at most ORDER_BUCKETS buckets (communities are folded onto the buckets in
+// order when there are more).  No global atomics (they resolve at the memory side on this part and cost ~200 ns
+// each): a workgroup counts its ORDER_TILE rows per bucket in LDS and writes the counts bucket-major, one prefix sum
+// per batch over (bucket, workgroup) gives every workgroup its first position in every bucket, and a second pass
+// hands out positions from LDS cursors.  The order inside a (bucket, workgroup) cell follows the LDS atomics and is
+// not reproducible, which is fine: the order only says which workgroup of the gather handles a row and when.
+// ---------------------------------------------------------------------------------------------
+constexpr int ORDER_BUCKETS = 4096;
+constexpr int ORDER_TILE = 2048;          // rows per workgroup of 256 threads
+
+struct OrderArgs {
+    const int32_t *prev_hdr;
+    int64_t n_roots_total;
+    int32_t batch_size;
+    const int32_t *dst_ids;
+    int64_t dst_stride;
+    const int32_t *comm;
+    int32_t n_comm;
+    int32_t n_buckets;        // min(n_comm, ORDER_BUCKETS)
+    int32_t n_tiles;          // workgroups per batch (gridDim.x)
+    int32_t *cells;           // [n_batches][n_buckets * n_tiles + 1]: counts, then (scanned, in `offsets`) first positions
+    int32_t *offsets;
+    int32_t *order;
+    int64_t order_stride;
+};
+
+__device__ __forceinline__ int order_bucket(const OrderArgs &a, int node)
+{
+    const int cm = a.comm[node];
+    const int c = a.n_comm <= ORDER_BUCKETS ? cm : (int)((int64_t)cm * ORDER_BUCKETS / a.n_comm);
+    return min(max(c, 0), a.n_buckets - 1);
+}
+
+template <bool SCATTER>
+__global__ __launch_bounds__(256) void order_pass_kernel(OrderArgs a)
+{
+    __shared__ int lds[ORDER_BUCKETS];
+    const int g = blockIdx.y, tile = blockIdx.x;
+    const int n_dst = group_n_dst(a.prev_hdr, g, a.n_roots_total, a.batch_size);
+    const int64_t cell0 = (int64_t)g * ((int64_t)a.n_buckets * a.n_tiles + 1);
+    for (int b = threadIdx.x; b < a.n_buckets; b += 256) lds[b] = SCATTER ? a.offsets[cell0 + (int64_t)b * a.n_tiles + tile] : 0;
+    __syncthreads();
+    constexpr int PER = ORDER_TILE / 256;
+    int node[PER];
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        const int r = tile * ORDER_TILE + i * 256 + (int)threadIdx.x;
+        node[i] = a.dst_ids[(int64_t)g * a.dst_stride + min(r, max(n_dst - 1, 0))];
+    }
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        const int r = tile * ORDER_TILE + i * 256 + (int)threadIdx.x;
+        if (r < n_dst) {
+            const int pos = atomicAdd(&lds[order_bucket(a, node[i])], 1);
+            if (SCATTER) a.order[(int64_t)g * a.order_stride + pos] = r;
+        }
+    }
+    if (!SCATTER) {
+        __syncthreads();
+        for (int b = threadIdx.x; b < a.n_buckets; b += 256) a.cells[cell0 + (int64_t)b * a.n_tiles + tile] = lds[b];
     }
 }
 
@@ -908,7 +975,7 @@ struct SamplePlan {
     bool direct = false;      // direct-address de-duplication table (one int32 per node) instead of hashing
     int64_t table_stride = 0; // per batch, in 8-byte units
     // workspace slices
-    int32_t *sel, *cnt, *newoff, *tcount, *tfill, *t_tmp, *t_pos;
+    int32_t *sel, *cnt, *newoff, *tcount, *tfill, *t_tmp, *t_pos, *order_hist, *order_cursor;
     unsigned long long *newmask, *table;
     size_t bytes;
 };
@@ -965,6 +1032,13 @@ static cr_status make_plan(const cr_sample_cfg *cfg, int64_t n_nodes, int32_t ba
     p.tfill = c.take<int32_t>(G * (p.max_src_t + 1));
     p.t_tmp = c.take<int32_t>(G * (p.max_nnz_t + 1));
     p.t_pos = c.take<int32_t>(G * (p.max_nnz_t + 1));
+    if (cfg->flags & CR_SAMPLE_ROW_ORDER) {          // cells of the row-order counting sort, sized for 4096 buckets
+        const size_t cells = (size_t)ORDER_BUCKETS * (size_t)ceil_div(p.max_dst, ORDER_TILE) + 1;
+        p.order_hist = c.take<int32_t>(G * cells);
+        p.order_cursor = c.take<int32_t>(G * cells);
+    } else {
+        p.order_hist = p.order_cursor = nullptr;
+    }
     p.bytes = c.bytes();
     return CR_OK;
 }
@@ -1044,6 +1118,8 @@ extern "C" cr_status cr_sample_blocks(const cr_graph *graph, const cr_sample_cfg
                    "layer 0 takes a transposed block only with CR_SAMPLE_TRANSPOSE_INPUT");
         CR_REQUIRE(l >= 1 || !(cfg->flags & CR_SAMPLE_INPUT_GLOBAL_IDS) || b.gather_ids != nullptr, CR_ERR_INVALID_ARG,
                    "CR_SAMPLE_INPUT_GLOBAL_IDS needs layers[0].gather_ids");
+        CR_REQUIRE(b.row_order == nullptr || (cfg->flags & CR_SAMPLE_ROW_ORDER), CR_ERR_INVALID_ARG,
+                   "layers[%d].row_order needs CR_SAMPLE_ROW_ORDER (it sizes the workspace)", l);
     }
     if (dry_run()) return CR_OK;
 
@@ -1080,6 +1156,24 @@ extern "C" cr_status cr_sample_blocks(const cr_graph *graph, const cr_sample_cfg
         if (q_in == q_out) hipLaunchKernelGGL(select_kernel<0>, sel_grid, blk, 0, s, sa);
         else if (q_out == 0) hipLaunchKernelGGL(select_kernel<1>, sel_grid, blk, 0, s, sa);
         else hipLaunchKernelGGL(select_kernel<2>, sel_grid, blk, 0, s, sa);
+
+        if (b.row_order) {       // processing order of this layer's destination rows (their ids are known already)
+            OrderArgs oa;
+            oa.prev_hdr = prev_hdr; oa.n_roots_total = n_roots_total; oa.batch_size = batch_size;
+            oa.dst_ids = dst_ids; oa.dst_stride = dst_stride; oa.comm = graph->comm; oa.n_comm = graph->n_comm;
+            oa.n_buckets = graph->n_comm < ORDER_BUCKETS ? graph->n_comm : ORDER_BUCKETS;
+            oa.n_tiles = (int32_t)ceil_div(cap_dst, ORDER_TILE);
+            oa.cells = p.order_hist; oa.offsets = p.order_cursor; oa.order = b.row_order; oa.order_stride = b.cap_dst;
+            const int n_cells = oa.n_buckets * oa.n_tiles;
+            const dim3 og((unsigned)oa.n_tiles, n_batches);
+            hipLaunchKernelGGL(order_pass_kernel<false>, og, blk, 0, s, oa);
+            ScanArgs so;
+            so.prev_hdr = prev_hdr; so.n_roots_total = n_roots_total; so.batch_size = batch_size;
+            so.mode = 3; so.n_fixed = n_cells; so.in = p.order_hist; so.in_stride = n_cells + 1; so.out = p.order_cursor;
+            so.out_stride = n_cells + 1; so.out_copy = nullptr; so.copy_stride = 0; so.hdr = b.hdr;
+            hipLaunchKernelGGL(scan_kernel, dim3((unsigned)ceil_div(n_cells, SCAN_TILE), n_batches), dim3(SCAN_THREADS), 0, s, so);
+            hipLaunchKernelGGL(order_pass_kernel<true>, og, blk, 0, s, oa);
+        }
 
         ScanArgs sc;
         sc.prev_hdr = prev_hdr; sc.n_roots_total = n_roots_total; sc.batch_size = batch_size;

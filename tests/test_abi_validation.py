@@ -107,6 +107,10 @@ def test_sample_blocks_validation():
     with_ids = [block_set(1, 10, 48, 528, 480, t=False), block_set(1, 5, 8, 48, 40)]
     with_ids[0].gather_ids = FAKE
     assert sample(layers=with_ids, flags=B.CR_SAMPLE_INPUT_GLOBAL_IDS) == B.CR_OK
+    # a processing order of the rows is filled on request only: the flag sizes the workspace
+    with_ids[0].row_order = FAKE
+    assert sample(layers=with_ids, flags=B.CR_SAMPLE_INPUT_GLOBAL_IDS) == B.CR_ERR_INVALID_ARG
+    assert sample(layers=with_ids, flags=B.CR_SAMPLE_INPUT_GLOBAL_IDS | B.CR_SAMPLE_ROW_ORDER) == B.CR_OK
 
 
 def test_edge_classes_validation():

@@ -162,3 +162,45 @@ def test_gather_bwd(torch_mod, tiny_workload, F):
     B.cr_gather_aggregate_bwd(bs, 0, up(d_agg), None, ld_in, F, d_src=d_src)
     torch.cuda.synchronize()
     assert_close(d_src.cpu().numpy(), oracle.gather_mean_bwd(blk, d_agg[:, :F]), RTOL, "d_src no self")
+
+
+@pytest.mark.parametrize("F,dtype,gcn", [(128, "f32", False), (602, "f32", False), (256, "bf16", False), (100, "f32", True)])
+def test_gather_fwd_with_a_processing_order(torch_mod, tiny_workload, F, dtype, gcn):
+    """A block set that carries a row order (any permutation of the destination rows) gives bit-identical outputs:
+    the order only says which workgroup handles a row and when."""
+    torch = torch_mod
+    from paper_2504_18082_amd import binding as B
+    w = tiny_workload
+    rng = np.random.default_rng(F + 1)
+    table = _features(rng, w.cfg.n_nodes, F, dtype)
+    roots = w.train_ids[:700]
+    blk = oracle.sample_blocks(w.graph, roots, [10, 5], 0.9, False, 0, 0, 0)[0]
+    print(f"case order F={F} dtype={dtype} gcn={gcn} n_dst={blk.n_dst}", flush=True)
+    dev_table = torch.from_numpy(table.view(np.int16) if dtype == "bf16" else table).cuda()
+    ldb = (F + 31) // 32 * 32
+    if gcn:
+        indptr = torch.from_numpy(w.indptr.astype(np.int64)).cuda()
+        indices = torch.from_numpy(w.indices.astype(np.int32)).cuda()
+        comm = torch.from_numpy(w.comm.astype(np.int32)).cuda()
+        norm = B.cr_graph_gcn_norm(B.make_graph(indptr, indices, comm, w.cfg.n_comm))
+    results = []
+    for order in (None, rng.permutation(blk.n_dst), np.arange(blk.n_dst)[::-1]):
+        blk.row_order = order
+        bs = B.BlockSet.from_host(blk, 10, gather_ids=True)
+        agg = torch.full((bs.cap_dst, F), np.nan, dtype=torch.float32, device="cuda")
+        agg_b = torch.full((bs.cap_dst, ldb), 0x7FC0, dtype=torch.int16, device="cuda")
+        self_b = torch.full((bs.cap_dst, ldb), 0x7FC0, dtype=torch.int16, device="cuda")
+        dt = B.CR_BF16 if dtype == "bf16" else B.CR_F32
+        if gcn:
+            blk_norm = torch.zeros(bs.cap_src + 2 * bs.cap_dst, dtype=torch.float32, device="cuda")
+            B.cr_gcn_block_norm(bs, 0, norm, blk_norm)
+            B.cr_gcn_aggregate_fwd(bs, 0, norm, blk_norm, dev_table, dt, table.shape[1], F, True, agg, agg_b, ldb)
+        else:
+            B.cr_gather_aggregate_fwd(bs, 0, dev_table, dt, table.shape[1], F, True, agg, agg_b, self_b, ldb)
+        torch.cuda.synchronize()
+        results.append((agg.cpu().numpy().copy(), agg_b.cpu().numpy().copy(), self_b.cpu().numpy().copy()))
+    blk.row_order = None
+    assert not np.isnan(results[0][0][:blk.n_dst]).any()
+    for other in results[1:]:
+        for a, b in zip(results[0], other):
+            np.testing.assert_array_equal(a, b)

@@ -205,3 +205,45 @@ def test_long_rows_all_paths(torch_mod, edge_classes):
             compare(layers, nb, graph, roots, fan, p, False, 5, 1, 0, 16, f"long rows p={p} {fan}")
     layers, nb = run_gpu(torch_mod, dg, roots, [15], 1.0, True, 5, 1, 0, 16)
     compare(layers, nb, graph, roots, [15], 1.0, True, 5, 1, 0, 16, "long rows strict")
+
+
+@pytest.mark.parametrize("n_comm,input_global", [(50, True), (50, False), (9000, True)])
+def test_row_order_groups_destinations_by_community(torch_mod, tiny_workload, n_comm, input_global):
+    """cr_block_set.row_order: per batch a permutation of the destination rows, communities ascending (folded onto
+    4096 buckets in order when there are more communities); everything else of the blocks is unchanged."""
+    from paper_2504_18082_amd import binding as B
+    torch = torch_mod
+    w = tiny_workload
+    rng = np.random.default_rng(n_comm)
+    comm = w.comm if n_comm == 50 else rng.integers(0, n_comm, size=w.cfg.n_nodes).astype(np.int32)
+    graph = (w.indptr, w.indices, comm)
+    dg = DeviceGraph(torch, graph, n_comm)
+    fanouts, batch_size, seed, epoch = [10, 5], 256, 3, 1
+    roots = w.train_ids[:3 * batch_size + 77]
+    n_batches = 4
+    flags = (B.CR_SAMPLE_INPUT_GLOBAL_IDS if input_global else 0) | B.CR_SAMPLE_ROW_ORDER
+    cfg = B.make_sample_cfg(fanouts, 0.5, seed, epoch, 0, flags)
+    print(f"case row order n_comm={n_comm} input_global={input_global}", flush=True)
+    layers = B.alloc_block_sets(cfg, dg.n_nodes, batch_size, n_batches, order_input=True)
+    layers[1] = B.BlockSet(n_batches, fanouts[1], layers[1].cap_dst, layers[1].cap_src, layers[1].cap_nnz, True, row_order=True)
+    for b in layers:
+        b.row_order.fill_(-7)
+    ws = torch.empty(B.cr_sample_blocks_workspace_bytes(cfg, dg.n_nodes, batch_size, n_batches), dtype=torch.uint8, device="cuda")
+    ws.fill_(0xAB)                                       # nothing may rely on a clean workspace
+    d_roots = torch.from_numpy(np.ascontiguousarray(roots, dtype=np.int32)).cuda()
+    for rep in range(2):
+        B.cr_sample_blocks(dg.c, cfg, d_roots, len(roots), batch_size, n_batches, ws, layers)
+        torch.cuda.synchronize()
+        for l, b in enumerate(layers):
+            hdr = b.hdr.cpu().numpy()
+            order = b.row_order.cpu().numpy()
+            src = b.src_ids.cpu().numpy()
+            for g in range(n_batches):
+                n_dst = hdr[g, 0]
+                o = order[g, :n_dst]
+                assert np.array_equal(np.sort(o), np.arange(n_dst)), f"layer {l} batch {g}: not a permutation"
+                assert np.all(order[g, n_dst:] == -7)
+                c = comm[src[g, :n_dst]][o].astype(np.int64)
+                bucket = c if n_comm <= 4096 else c * 4096 // n_comm
+                assert np.all(np.diff(bucket) >= 0), f"layer {l} batch {g}: buckets not ascending"
+    compare(layers, n_batches, graph, roots, fanouts, 0.5, False, seed, epoch, 0, batch_size, "row order", input_global=input_global)

@@ -203,3 +203,25 @@ def test_input_frontier_relabelling_changes_nothing(tiny_workload):
         out.append([l.W.cpu().numpy().copy() for l in tr.layers] + [tr.loss.cpu().numpy().copy()])
     for a, b in zip(*out):
         assert np.array_equal(a, b)
+
+
+@pytest.mark.parametrize("model", ["sage", "gcn"])
+def test_row_processing_order_changes_nothing(tiny_workload, model):
+    """The layer-0 gather may walk its rows in community order (cr_block_set.row_order): every weight after some
+    steps is bit-identical to the run without it."""
+    import torch
+    from paper_2504_18082_amd.trainer import Trainer
+    w = tiny_workload
+    out = []
+    for order in (False, True):
+        tr = Trainer(w, group_size=4, lr=0.05, seed=0, model=model, order_rows=order)
+        assert tr.order_rows == order and (tr.blocks[0].row_order is not None) == order
+        tr.run_epoch_serial(oracle.RAND, 1, 0.5, 1, max_batches=6)          # (the trainer skips the order for NORAND roots only)
+        torch.cuda.synchronize()
+        assert bool(tr.blocks[0].c.row_order) == order
+        if order:
+            hdr, o = tr.headers()[0], tr.blocks[0].row_order.cpu().numpy()
+            assert np.array_equal(np.sort(o[0, :hdr[0][0]]), np.arange(hdr[0][0]))
+        out.append([l.W.cpu().numpy().copy() for l in tr.layers] + [tr.loss.cpu().numpy().copy()])
+    for a, b in zip(*out):
+        assert np.array_equal(a, b)
