@@ -161,10 +161,20 @@ def _ptr(t):
     return None if t is None else C.c_void_p(t.data_ptr())
 
 
+_raw_stream = None
+
+
 def _stream(stream=None):
+    """The HIP stream to launch on: the given torch stream, else torch's current one (looked up through the raw
+    accessor when this torch has it: a fraction of the cost of building a Stream object per call)."""
+    global _raw_stream
+    if stream is not None:
+        return C.c_void_p(stream.cuda_stream)
     import torch
-    s = torch.cuda.current_stream() if stream is None else stream
-    return C.c_void_p(s.cuda_stream)
+    if _raw_stream is None:
+        get = getattr(torch._C, "_cuda_getCurrentRawStream", None)
+        _raw_stream = (lambda: get(torch.cuda.current_device())) if get is not None else (lambda: torch.cuda.current_stream().cuda_stream)
+    return C.c_void_p(_raw_stream())
 
 
 # --------------------------------------------------------------------------- small host helpers
