@@ -155,6 +155,11 @@ typedef struct {
                            that rows which share source rows are worked on next to each other and meet in L1/L2 (the
                            locality Section 3 of the paper gets from the batch's composition, here from the order of
                            the work inside a batch).  A scheduling hint only: no result depends on it. */
+    int32_t *group_order; /* device int32[n_batches*cap_dst + 1] or NULL: the same over the whole group of batches: entries
+                           batch * cap_dst + row for every destination row of every batch, grouped by community (so the
+                           rows of one community from all batches of the group are neighbours), followed, at index
+                           n_batches*cap_dst, by their number.  Filled like row_order; read by
+                           cr_gather_aggregate_fwd_group. */
 } cr_block_set;
 
 #define CR_SAMPLE_STRICT_INTRA 1u /* at p = 1 never take an inter-community neighbour (rows may be short) */
@@ -232,6 +237,16 @@ cr_status cr_gather_aggregate_fwd(const cr_block_set *blocks, int32_t g, const v
                                   int32_t dtype, int64_t ld_src, int32_t F, int32_t indirect,
                                   float *agg, uint16_t *agg_bf16, uint16_t *self_bf16,
                                   int64_t ld_bf16, void *stream);
+
+/* The same for every batch of the group in one launch (indirect addressing through blocks->gather_ids, bf16 outputs
+ * only): the input features take no gradient and no weight enters here, so the aggregation of a whole sampled group
+ * can run ahead of the training steps, and walking blocks->group_order (required) puts the rows of one community from
+ * all batches next to each other: a feature row is then fetched once for the group rather than once per batch.
+ *   agg_bf16, self_bf16 : device bf16 [n_batches][batch_stride_rows][ld_bf16]; batch g's rows start at row
+ *                         g * batch_stride_rows (>= cap_dst); same contents as cr_gather_aggregate_fwd writes */
+cr_status cr_gather_aggregate_fwd_group(const cr_block_set *blocks, const void *H_src, int32_t dtype, int64_t ld_src,
+                                        int32_t F, uint16_t *agg_bf16, uint16_t *self_bf16, int64_t batch_stride_rows,
+                                        int64_t ld_bf16, void *stream);
 
 /* Backward of the aggregation w.r.t. the source rows, atomic-free over the transposed block:
  *   d_src[u] = sum_{v : u in N_s(v)} d_agg[v] / |N_s(v)|   (+ d_self[u] for u < n_dst)

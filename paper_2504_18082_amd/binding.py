@@ -30,7 +30,7 @@ EXPORTS = [
     "cr_last_error", "cr_version", "cr_set_dry_run", "cr_mix_count_from_percent",
     "cr_build_batches_workspace_bytes", "cr_build_batches",
     "cr_graph_edge_classes", "cr_block_capacities", "cr_sample_blocks_workspace_bytes", "cr_sample_blocks",
-    "cr_gather_aggregate_fwd", "cr_gather_aggregate_bwd",
+    "cr_gather_aggregate_fwd", "cr_gather_aggregate_fwd_group", "cr_gather_aggregate_bwd",
     "cr_graph_gcn_norm", "cr_gcn_block_norm", "cr_gcn_aggregate_fwd", "cr_gcn_aggregate_bwd",
     "cr_sage_padded_dims", "cr_sage_refresh_shadows", "cr_sage_linear_fwd",
     "cr_sage_linear_bwd_workspace_bytes", "cr_sage_linear_bwd", "cr_sage_linear_bwd_input", "cr_softmax_xent",
@@ -71,7 +71,7 @@ class cr_block_set(C.Structure):
                 ("cap_src", C.c_int32), ("cap_nnz", C.c_int32), ("reserved", C.c_int32),
                 ("hdr", C.c_void_p), ("src_ids", C.c_void_p), ("indptr", C.c_void_p),
                 ("indices", C.c_void_p), ("t_indptr", C.c_void_p), ("t_indices", C.c_void_p),
-                ("gather_ids", C.c_void_p), ("row_order", C.c_void_p)]
+                ("gather_ids", C.c_void_p), ("row_order", C.c_void_p), ("group_order", C.c_void_p)]
 
 
 class cr_sample_cfg(C.Structure):
@@ -118,6 +118,7 @@ def lib():
                                        vp, C.c_size_t, C.POINTER(cr_block_set), vp]
         L.cr_gather_aggregate_fwd.argtypes = [C.POINTER(cr_block_set), i32, vp, i32, i64, i32, i32, vp, vp,
                                               vp, i64, vp]
+        L.cr_gather_aggregate_fwd_group.argtypes = [C.POINTER(cr_block_set), vp, i32, i64, i32, vp, vp, i64, i64, vp]
         L.cr_gather_aggregate_bwd.argtypes = [C.POINTER(cr_block_set), i32, vp, vp, i32, i64, i32, vp, i32, i64, vp,
                                               vp, i64, vp]
         L.cr_graph_gcn_norm.argtypes = [C.POINTER(cr_graph), vp, vp]
@@ -210,7 +211,8 @@ def cr_block_capacities(cfg: cr_sample_cfg, n_nodes: int, batch_size: int):
 class BlockSet:
     """Device storage of one layer's blocks for a group of batches (torch int32 tensors)."""
 
-    def __init__(self, n_batches, fanout, cap_dst, cap_src, cap_nnz, transposed, device="cuda", gather_ids=False, row_order=False):
+    def __init__(self, n_batches, fanout, cap_dst, cap_src, cap_nnz, transposed, device="cuda", gather_ids=False, row_order=False,
+                 group_order=False):
         import torch
         z = lambda *shape: torch.zeros(shape, dtype=torch.int32, device=device)
         self.n_batches, self.fanout = n_batches, fanout
@@ -223,9 +225,11 @@ class BlockSet:
         self.t_indices = z(n_batches, cap_nnz) if transposed else None
         self.gather_ids = z(n_batches, cap_nnz) if gather_ids else None
         self.row_order = z(n_batches, cap_dst) if row_order else None       # processing order of the destination rows
+        self.group_order = z(n_batches * cap_dst + 1) if group_order else None   # the same over the whole group (+ count)
         self.c = cr_block_set(n_batches, fanout, cap_dst, cap_src, cap_nnz, 0, _ptr(self.hdr),
                               _ptr(self.src_ids), _ptr(self.indptr), _ptr(self.indices),
-                              _ptr(self.t_indptr), _ptr(self.t_indices), _ptr(self.gather_ids), _ptr(self.row_order))
+                              _ptr(self.t_indptr), _ptr(self.t_indices), _ptr(self.gather_ids), _ptr(self.row_order),
+                              _ptr(self.group_order))
 
     def hdr_ptr(self, g):
         return C.c_void_p(self.hdr.data_ptr() + g * CR_HDR_WORDS * 4)
@@ -259,12 +263,14 @@ class BlockSet:
 
 
 def alloc_block_sets(cfg: cr_sample_cfg, n_nodes: int, batch_size: int, n_batches: int,
-                     device="cuda", transpose_input: bool = False, order_input: bool = False) -> List[BlockSet]:
+                     device="cuda", transpose_input: bool = False, order_input: bool = False,
+                     group_order_input: bool = False) -> List[BlockSet]:
     """transpose_input: layer 0 gets a transposed block too (sampling then needs CR_SAMPLE_TRANSPOSE_INPUT);
-    order_input: layer 0 gets a processing order of its destination rows (grouped by community)."""
+    order_input / group_order_input: layer 0 gets a processing order of its destination rows (grouped by community),
+    per batch / over the whole group."""
     cap_dst, cap_src, cap_nnz = cr_block_capacities(cfg, n_nodes, batch_size)
     return [BlockSet(n_batches, cfg.fanout[l], cap_dst[l], cap_src[l], cap_nnz[l], l >= 1 or transpose_input, device, gather_ids=(l == 0),
-                     row_order=(order_input and l == 0))
+                     row_order=(order_input and l == 0), group_order=(group_order_input and l == 0))
             for l in range(cfg.n_layers)]
 
 
@@ -319,6 +325,13 @@ def cr_gather_aggregate_fwd(blocks: BlockSet, g, H_src, dtype, ld_src, F, indire
     H_ptr = H_src if isinstance(H_src, C.c_void_p) else _ptr(H_src)
     _check(lib().cr_gather_aggregate_fwd(C.byref(blocks.c), g, H_ptr, dtype, ld_src, F, int(indirect),
                                          _ptr(agg), _ptr(agg_bf16), _ptr(self_bf16), ld_bf16, _stream(stream)))
+
+
+def cr_gather_aggregate_fwd_group(blocks, H_src, dtype, ld_src, F, agg_bf16, self_bf16, batch_stride_rows, ld_bf16, stream=None):
+    """blocks: a BlockSet or a view of its first batches (anything with a .c descriptor)."""
+    H_ptr = H_src if isinstance(H_src, C.c_void_p) else _ptr(H_src)
+    _check(lib().cr_gather_aggregate_fwd_group(C.byref(blocks.c), H_ptr, dtype, ld_src, F, _ptr(agg_bf16), _ptr(self_bf16),
+                                               batch_stride_rows, ld_bf16, _stream(stream)))
 
 
 def cr_gather_aggregate_bwd(blocks: BlockSet, g, d_agg, d_self, ld_in, F, relu_out=None, ld_relu=0, d_src=None,

@@ -79,23 +79,38 @@ struct GcnFwd {
     const float *dst_self;    // [n_dst]
 };
 
-template <typename T, int LPR, int NCHUNK, bool GCN = false>
+// GROUPED == true walks the rows of a whole group of batches in one launch: `order` then holds entries
+// batch * cap_dst + row followed (at index n_batches * cap_dst) by their number, the per-batch arrays are the group's
+// (batch g's slice at g times its capacity) and batch g's outputs start at row g * out_stride.
+struct GroupInfo {
+    int32_t n_batches, cap_dst, cap_src, cap_nnz;
+    int64_t out_stride;       // output rows per batch
+};
+
+template <typename T, int LPR, int NCHUNK, bool GCN = false, bool GROUPED = false>
 __global__ __launch_bounds__(256) void gather_mean_fwd_kernel(
     const int32_t *__restrict__ hdr, const int32_t *__restrict__ indptr,
     const int32_t *__restrict__ ids, const int32_t *__restrict__ edge_map,
     const int32_t *__restrict__ self_map, const T *__restrict__ table, int64_t ld, int F,
     float *__restrict__ agg, uint16_t *__restrict__ agg_bf16, uint16_t *__restrict__ self_bf16, int64_t ld_bf16,
-    GcnFwd gcn = GcnFwd{nullptr, nullptr, nullptr, nullptr}, const int32_t *__restrict__ order = nullptr)
+    GcnFwd gcn = GcnFwd{nullptr, nullptr, nullptr, nullptr}, const int32_t *__restrict__ order = nullptr,
+    GroupInfo grp = GroupInfo{0, 0, 0, 0, 0})
 {
     constexpr int VEC = Vec16<T>::N;
     constexpr int U = NCHUNK == 1 ? 8 : (NCHUNK <= 3 ? 4 : 2);   // independent row loads in flight per lane
     constexpr int GPB = 256 / LPR;                                // groups (rows in progress) per workgroup
-    const int n_dst = hdr[CR_HDR_N_DST], n_src = hdr[CR_HDR_N_SRC];
+    const int n_dst = GROUPED ? min(order[(int64_t)grp.n_batches * grp.cap_dst], grp.n_batches * grp.cap_dst) : hdr[CR_HDR_N_DST];
+    const int n_src = GROUPED ? grp.cap_src : hdr[CR_HDR_N_SRC];
     if (n_dst <= 0) return;
-    const uint32_t lb = xcd_remap(blockIdx.x, gridDim.x);
-    const int rows_per_block = (int)(((int64_t)n_dst + gridDim.x - 1) / gridDim.x + GPB - 1) / GPB * GPB;
-    const int block_first = (int)lb * rows_per_block;
-    const int block_end = min(n_dst, block_first + rows_per_block);
+    // Each XCD (the workgroups with the same blockIdx.x mod 8; the grid is a multiple of 8) owns one contiguous eighth
+    // of the rows and its workgroups sweep it together: workgroup j of the XCD takes rows j*GPB.., then steps by the
+    // XCD's whole front.  The rows in flight on an XCD at any time are then neighbours, which is what makes a
+    // processing order by community pay: their sources meet in that XCD's L2.
+    const int per_xcd = (int)(gridDim.x / 8);
+    const int xcd_rows = ((n_dst + 7) / 8 + GPB - 1) / GPB * GPB;
+    const int block_first = (int)(blockIdx.x % 8) * xcd_rows + (int)(blockIdx.x / 8) * GPB;
+    const int block_end = min(n_dst, (int)(blockIdx.x % 8 + 1) * xcd_rows);
+    const int STEP = per_xcd * GPB;
     const int gl = (int)(threadIdx.x % LPR);
     int row = block_first + (int)(threadIdx.x / LPR);
     if (row >= block_end) return;
@@ -108,13 +123,24 @@ __global__ __launch_bounds__(256) void gather_mean_fwd_kernel(
         return order ? order[rc] : rc;
     };
     float sc0 = 0.f, sf0 = 0.f, sc1 = 0.f, sf1 = 0.f, sc2 = 0.f, sf2 = 0.f;     // GCN: destination scale / self weight
-    auto load_ptrs = [&](int r, int rc, int &s, int &e, int &self_row, float &sc, float &sf) {
-        const int a = indptr[rc], b = indptr[rc + 1];
-        const int sr = self_map ? self_map[rc] : rc;
-        if constexpr (GCN) { sc = gcn.dst_scale[rc]; sf = gcn.dst_self[rc]; }
-        s = r < block_end ? a : 0;
-        e = r < block_end ? b : 0;
-        self_row = sr;
+    auto load_ptrs = [&](int r, int &rc, int &s, int &e, int &self_row, float &sc, float &sf) {
+        if constexpr (GROUPED) {
+            // rc comes in as batch * cap_dst + row and goes out as the output row
+            const int g = min(max(rc, 0) / grp.cap_dst, grp.n_batches - 1), rr = max(rc, 0) - g * grp.cap_dst;
+            const int32_t *ip = indptr + (int64_t)g * (grp.cap_dst + 1);
+            const int a = ip[rr] + g * grp.cap_nnz, b = ip[rr + 1] + g * grp.cap_nnz;
+            self_row = self_map[(int64_t)g * grp.cap_src + rr];
+            rc = (int)(g * grp.out_stride + rr);
+            s = r < block_end ? a : 0;
+            e = r < block_end ? b : 0;
+        } else {
+            const int a = indptr[rc], b = indptr[rc + 1];
+            const int sr = self_map ? self_map[rc] : rc;
+            if constexpr (GCN) { sc = gcn.dst_scale[rc]; sf = gcn.dst_self[rc]; }
+            s = r < block_end ? a : 0;
+            e = r < block_end ? b : 0;
+            self_row = sr;
+        }
     };
     auto load_ids = [&](int first, int e, float &w) -> int {
         const int idx = max(min(first + gl, e - 1), 0);
@@ -129,17 +155,17 @@ __global__ __launch_bounds__(256) void gather_mean_fwd_kernel(
 
     int s0, e0, self0, s1, e1, self1;
     float w0 = 1.f, w1 = 1.f;
-    int out0 = load_row(row), out1 = load_row(row + GPB), out2 = load_row(row + 2 * GPB);   // rows handled now, next, after next
+    int out0 = load_row(row), out1 = load_row(row + STEP), out2 = load_row(row + 2 * STEP);   // rows handled now, next, after next
     load_ptrs(row, out0, s0, e0, self0, sc0, sf0);
     int rid0 = load_ids(s0, e0, w0);
-    load_ptrs(row + GPB, out1, s1, e1, self1, sc1, sf1);
+    load_ptrs(row + STEP, out1, s1, e1, self1, sc1, sf1);
 
-    for (; row < block_end; row += GPB) {
+    for (; row < block_end; row += STEP) {
         // look ahead: ids of the next destination, pointers of the one after
         const int rid1 = load_ids(s1, e1, w1);
         int s2, e2, self2;
-        load_ptrs(row + 2 * GPB, out2, s2, e2, self2, sc2, sf2);
-        const int out3 = load_row(row + 3 * GPB);
+        load_ptrs(row + 2 * STEP, out2, s2, e2, self2, sc2, sf2);
+        const int out3 = load_row(row + 3 * STEP);
 
         float acc[NCHUNK][VEC];
 #pragma unroll
@@ -242,7 +268,7 @@ static void launch_fwd(int cap_dst, const int32_t *hdr, const int32_t *indptr, c
                        const GcnFwd *gcn = nullptr, const int32_t *order = nullptr)
 {
     constexpr int GPB = 256 / LPR;
-    int64_t grid = ceil_div(cap_dst, GPB);
+    int64_t grid = round_up(ceil_div(cap_dst, GPB), 8);
     if (grid > 1024) grid = 1024;          // 4 workgroups per CU; each group then walks several rows
     if (gcn)
         hipLaunchKernelGGL((gather_mean_fwd_kernel<T, LPR, NCHUNK, true>), dim3((unsigned)grid), dim3(256), 0, st, hdr, indptr,
@@ -251,6 +277,19 @@ static void launch_fwd(int cap_dst, const int32_t *hdr, const int32_t *indptr, c
         hipLaunchKernelGGL((gather_mean_fwd_kernel<T, LPR, NCHUNK, false>), dim3((unsigned)grid), dim3(256), 0, st, hdr, indptr,
                            ids, edge_map, self_map, static_cast<const T *>(table), ld, F, agg, agg_bf16, self_bf16, ld_bf16,
                            GcnFwd{nullptr, nullptr, nullptr, nullptr}, order);
+}
+
+template <typename T, int LPR, int NCHUNK>
+static void launch_fwd_group(const cr_block_set *b, const void *table, int64_t ld, int F, uint16_t *agg_bf16, uint16_t *self_bf16,
+                             int64_t out_stride, int64_t ld_bf16, hipStream_t st)
+{
+    constexpr int GPB = 256 / LPR;
+    int64_t grid = round_up(ceil_div((int64_t)b->n_batches * b->cap_dst, GPB), 8);
+    if (grid > 1024) grid = 1024;
+    const GroupInfo gi{b->n_batches, b->cap_dst, b->cap_src, b->cap_nnz, out_stride};
+    hipLaunchKernelGGL((gather_mean_fwd_kernel<T, LPR, NCHUNK, false, true>), dim3((unsigned)grid), dim3(256), 0, st, b->hdr, b->indptr,
+                       b->gather_ids, (const int32_t *)nullptr, b->src_ids, static_cast<const T *>(table), ld, F, (float *)nullptr, agg_bf16,
+                       self_bf16, ld_bf16, GcnFwd{nullptr, nullptr, nullptr, nullptr}, b->group_order, gi);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -272,10 +311,12 @@ __global__ __launch_bounds__(256) void gather_mean_bwd_kernel(
     constexpr int GPB = 256 / LPR;
     const int n_dst = hdr[CR_HDR_N_DST], n_src = hdr[CR_HDR_N_SRC];
     if (n_src <= 0) return;
-    const uint32_t lb = xcd_remap(blockIdx.x, gridDim.x);
-    const int rows_per_block = (int)(((int64_t)n_src + gridDim.x - 1) / gridDim.x + GPB - 1) / GPB * GPB;
-    const int block_first = (int)lb * rows_per_block;
-    const int block_end = min(n_src, block_first + rows_per_block);
+    // the same walk as in the forward kernel: an eighth of the rows per XCD, swept by its workgroups together
+    const int per_xcd = (int)(gridDim.x / 8);
+    const int xcd_rows = ((n_src + 7) / 8 + GPB - 1) / GPB * GPB;
+    const int block_first = (int)(blockIdx.x % 8) * xcd_rows + (int)(blockIdx.x / 8) * GPB;
+    const int block_end = min(n_src, (int)(blockIdx.x % 8 + 1) * xcd_rows);
+    const int STEP = per_xcd * GPB;
     const int gl = (int)(threadIdx.x % LPR);
     int s = block_first + (int)(threadIdx.x / LPR);
     if (s >= block_end) return;
@@ -303,12 +344,12 @@ __global__ __launch_bounds__(256) void gather_mean_bwd_kernel(
     float w0, w1;
     load_ptrs(s, b0, e0);
     load_ids(b0, e0, v0, w0);
-    load_ptrs(s + GPB, b1, e1);
+    load_ptrs(s + STEP, b1, e1);
 
-    for (; s < block_end; s += GPB) {
+    for (; s < block_end; s += STEP) {
         load_ids(b1, e1, v1, w1);
         int b2, e2;
-        load_ptrs(s + 2 * GPB, b2, e2);
+        load_ptrs(s + 2 * STEP, b2, e2);
 
         float acc[NCHUNK][VEC];
 #pragma unroll
@@ -451,7 +492,7 @@ static void launch_bwd(int cap_src, const int32_t *hdr, const int32_t *indptr, c
                        const void *relu_out, int relu_is_bf16, int64_t ld_relu, float *d_src, uint16_t *d_src_bf16,
                        int64_t ld_bf16, hipStream_t st, const GcnFwd *gcn = nullptr)
 {
-    int64_t grid = ceil_div(cap_src, 256 / LPR);
+    int64_t grid = round_up(ceil_div(cap_src, 256 / LPR), 8);
     if (grid > 1024) grid = 1024;
     if (gcn)
         hipLaunchKernelGGL((gather_mean_bwd_kernel<T, LPR, NCHUNK, true>), dim3((unsigned)grid), dim3(256), 0, st, hdr, indptr, t_indptr,
@@ -589,6 +630,51 @@ static void run_bwd(const cr_block_set *blocks, int32_t g, const void *d_agg, co
         else CR_BWD(uint16_t, 64, 2);
     }
 #undef CR_BWD
+}
+
+extern "C" cr_status cr_gather_aggregate_fwd_group(const cr_block_set *blocks, const void *H_src, int32_t dtype, int64_t ld_src,
+                                                   int32_t F, uint16_t *agg_bf16, uint16_t *self_bf16, int64_t batch_stride_rows,
+                                                   int64_t ld_bf16, void *stream)
+{
+    CR_REQUIRE(blocks != nullptr, CR_ERR_INVALID_ARG, "blocks is NULL");
+    CR_REQUIRE(blocks->n_batches >= 1 && blocks->cap_dst >= 1 && blocks->cap_src >= blocks->cap_dst && blocks->cap_nnz >= 1,
+               CR_ERR_INVALID_ARG, "blocks capacities are not positive");
+    CR_REQUIRE(blocks->hdr && blocks->indptr && blocks->src_ids, CR_ERR_INVALID_ARG, "blocks has a NULL array");
+    CR_REQUIRE(blocks->gather_ids && blocks->group_order, CR_ERR_INVALID_ARG, "the grouped gather needs blocks->gather_ids and blocks->group_order");
+    CR_REQUIRE((int64_t)blocks->n_batches * blocks->cap_dst < 0x7FFFFFFF && (int64_t)blocks->n_batches * blocks->cap_nnz < 0x7FFFFFFF,
+               CR_ERR_UNSUPPORTED, "the group's rows or edges do not fit 31 bits");
+    CR_REQUIRE(H_src != nullptr && aligned16(H_src), CR_ERR_INVALID_ARG, "H_src must be a 16-byte aligned device pointer");
+    CR_REQUIRE(dtype == CR_F32 || dtype == CR_BF16, CR_ERR_INVALID_ARG, "dtype must be CR_F32 or CR_BF16");
+    const int vec = dtype == CR_F32 ? 4 : 8;
+    CR_REQUIRE(F >= 1 && F <= 1024, CR_ERR_INVALID_ARG, "F = %d outside 1..1024", F);
+    CR_REQUIRE(ld_src >= round_up(F, vec) && ld_src % vec == 0, CR_ERR_INVALID_ARG,
+               "ld_src = %lld must be a multiple of %d and >= F rounded up to it", (long long)ld_src, vec);
+    CR_REQUIRE(agg_bf16 && self_bf16 && aligned16(agg_bf16) && aligned16(self_bf16), CR_ERR_INVALID_ARG,
+               "agg_bf16 / self_bf16 must be 16-byte aligned device pointers");
+    CR_REQUIRE(ld_bf16 % 32 == 0 && ld_bf16 >= F && ld_bf16 <= round_up(F, 64), CR_ERR_INVALID_ARG,
+               "ld_bf16 = %lld must be a multiple of 32 in [F, F rounded up to 64]", (long long)ld_bf16);
+    CR_REQUIRE(batch_stride_rows >= blocks->cap_dst, CR_ERR_INVALID_ARG, "batch_stride_rows = %lld below cap_dst = %d",
+               (long long)batch_stride_rows, blocks->cap_dst);
+    CR_REQUIRE(batch_stride_rows * blocks->n_batches < 0x7FFFFFFF, CR_ERR_UNSUPPORTED, "output rows do not fit 31 bits");
+    if (dry_run()) return CR_OK;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+#define CR_FWDG(T, LPR, NC) launch_fwd_group<T, LPR, NC>(blocks, H_src, ld_src, F, agg_bf16, self_bf16, batch_stride_rows, ld_bf16, s)
+    if (dtype == CR_F32) {
+        if (F <= 64) CR_FWDG(float, 16, 1);
+        else if (F <= 128) CR_FWDG(float, 32, 1);
+        else if (F <= 256) CR_FWDG(float, 64, 1);
+        else if (F <= 512) CR_FWDG(float, 64, 2);
+        else if (F <= 768) CR_FWDG(float, 64, 3);
+        else CR_FWDG(float, 64, 4);
+    } else {
+        if (F <= 128) CR_FWDG(uint16_t, 16, 1);
+        else if (F <= 256) CR_FWDG(uint16_t, 32, 1);
+        else if (F <= 512) CR_FWDG(uint16_t, 64, 1);
+        else CR_FWDG(uint16_t, 64, 2);
+    }
+#undef CR_FWDG
+    CR_LAUNCH_CHECK();
+    return CR_OK;
 }
 
 extern "C" cr_status cr_gather_aggregate_bwd(const cr_block_set *blocks, int32_t g, const void *d_agg,

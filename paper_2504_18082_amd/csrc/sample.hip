@@ -661,6 +661,8 @@ struct OrderArgs {
     int32_t *offsets;
     int32_t *order;
     int64_t order_stride;
+    int32_t grouped;          // 1: one order over all batches of the group, entries batch * cap_dst + row, count at the end
+    int32_t cap_dst;
 };
 
 __device__ __forceinline__ int order_bucket(const OrderArgs &a, int node)
@@ -676,8 +678,13 @@ __global__ __launch_bounds__(256) void order_pass_kernel(OrderArgs a)
     __shared__ int lds[ORDER_BUCKETS];
     const int g = blockIdx.y, tile = blockIdx.x;
     const int n_dst = group_n_dst(a.prev_hdr, g, a.n_roots_total, a.batch_size);
-    const int64_t cell0 = (int64_t)g * ((int64_t)a.n_buckets * a.n_tiles + 1);
-    for (int b = threadIdx.x; b < a.n_buckets; b += 256) lds[b] = SCATTER ? a.offsets[cell0 + (int64_t)b * a.n_tiles + tile] : 0;
+    // per batch: cells [bucket][tile] of this batch; grouped: cells [bucket][batch][tile] of the whole group
+    const int col = a.grouped ? g * a.n_tiles + tile : tile;
+    const int cols = a.grouped ? (int)gridDim.y * a.n_tiles : a.n_tiles;
+    const int64_t cell0 = a.grouped ? 0 : (int64_t)g * ((int64_t)a.n_buckets * a.n_tiles + 1);
+    for (int b = threadIdx.x; b < a.n_buckets; b += 256) lds[b] = SCATTER ? a.offsets[cell0 + (int64_t)b * cols + col] : 0;
+    if (SCATTER && a.grouped && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0)
+        a.order[(int64_t)gridDim.y * a.cap_dst] = a.offsets[(int64_t)a.n_buckets * cols];      // number of entries
     __syncthreads();
     constexpr int PER = ORDER_TILE / 256;
     int node[PER];
@@ -691,12 +698,15 @@ __global__ __launch_bounds__(256) void order_pass_kernel(OrderArgs a)
         const int r = tile * ORDER_TILE + i * 256 + (int)threadIdx.x;
         if (r < n_dst) {
             const int pos = atomicAdd(&lds[order_bucket(a, node[i])], 1);
-            if (SCATTER) a.order[(int64_t)g * a.order_stride + pos] = r;
+            if (SCATTER) {
+                if (a.grouped) a.order[pos] = g * a.cap_dst + r;
+                else a.order[(int64_t)g * a.order_stride + pos] = r;
+            }
         }
     }
     if (!SCATTER) {
         __syncthreads();
-        for (int b = threadIdx.x; b < a.n_buckets; b += 256) a.cells[cell0 + (int64_t)b * a.n_tiles + tile] = lds[b];
+        for (int b = threadIdx.x; b < a.n_buckets; b += 256) a.cells[cell0 + (int64_t)b * cols + col] = lds[b];
     }
 }
 
@@ -1118,8 +1128,10 @@ extern "C" cr_status cr_sample_blocks(const cr_graph *graph, const cr_sample_cfg
                    "layer 0 takes a transposed block only with CR_SAMPLE_TRANSPOSE_INPUT");
         CR_REQUIRE(l >= 1 || !(cfg->flags & CR_SAMPLE_INPUT_GLOBAL_IDS) || b.gather_ids != nullptr, CR_ERR_INVALID_ARG,
                    "CR_SAMPLE_INPUT_GLOBAL_IDS needs layers[0].gather_ids");
-        CR_REQUIRE(b.row_order == nullptr || (cfg->flags & CR_SAMPLE_ROW_ORDER), CR_ERR_INVALID_ARG,
-                   "layers[%d].row_order needs CR_SAMPLE_ROW_ORDER (it sizes the workspace)", l);
+        CR_REQUIRE((b.row_order == nullptr && b.group_order == nullptr) || (cfg->flags & CR_SAMPLE_ROW_ORDER), CR_ERR_INVALID_ARG,
+                   "layers[%d].row_order / group_order need CR_SAMPLE_ROW_ORDER (it sizes the workspace)", l);
+        CR_REQUIRE(b.group_order == nullptr || (int64_t)n_batches * b.cap_dst < 0x7FFFFFFF, CR_ERR_UNSUPPORTED,
+                   "layers[%d].group_order: n_batches * cap_dst does not fit 31 bits", l);
     }
     if (dry_run()) return CR_OK;
 
@@ -1157,21 +1169,24 @@ extern "C" cr_status cr_sample_blocks(const cr_graph *graph, const cr_sample_cfg
         else if (q_out == 0) hipLaunchKernelGGL(select_kernel<1>, sel_grid, blk, 0, s, sa);
         else hipLaunchKernelGGL(select_kernel<2>, sel_grid, blk, 0, s, sa);
 
-        if (b.row_order) {       // processing order of this layer's destination rows (their ids are known already)
+        for (int grouped = 0; grouped < 2; ++grouped) {       // processing orders of this layer's destination rows
+            int32_t *order = grouped ? b.group_order : b.row_order;
+            if (!order) continue;
             OrderArgs oa;
             oa.prev_hdr = prev_hdr; oa.n_roots_total = n_roots_total; oa.batch_size = batch_size;
             oa.dst_ids = dst_ids; oa.dst_stride = dst_stride; oa.comm = graph->comm; oa.n_comm = graph->n_comm;
             oa.n_buckets = graph->n_comm < ORDER_BUCKETS ? graph->n_comm : ORDER_BUCKETS;
             oa.n_tiles = (int32_t)ceil_div(cap_dst, ORDER_TILE);
-            oa.cells = p.order_hist; oa.offsets = p.order_cursor; oa.order = b.row_order; oa.order_stride = b.cap_dst;
-            const int n_cells = oa.n_buckets * oa.n_tiles;
+            oa.cells = p.order_hist; oa.offsets = p.order_cursor; oa.order = order; oa.order_stride = b.cap_dst;
+            oa.grouped = grouped; oa.cap_dst = b.cap_dst;
+            const int n_cells = oa.n_buckets * oa.n_tiles * (grouped ? n_batches : 1);
             const dim3 og((unsigned)oa.n_tiles, n_batches);
             hipLaunchKernelGGL(order_pass_kernel<false>, og, blk, 0, s, oa);
             ScanArgs so;
             so.prev_hdr = prev_hdr; so.n_roots_total = n_roots_total; so.batch_size = batch_size;
             so.mode = 3; so.n_fixed = n_cells; so.in = p.order_hist; so.in_stride = n_cells + 1; so.out = p.order_cursor;
             so.out_stride = n_cells + 1; so.out_copy = nullptr; so.copy_stride = 0; so.hdr = b.hdr;
-            hipLaunchKernelGGL(scan_kernel, dim3((unsigned)ceil_div(n_cells, SCAN_TILE), n_batches), dim3(SCAN_THREADS), 0, s, so);
+            hipLaunchKernelGGL(scan_kernel, dim3((unsigned)ceil_div(n_cells, SCAN_TILE), grouped ? 1 : n_batches), dim3(SCAN_THREADS), 0, s, so);
             hipLaunchKernelGGL(order_pass_kernel<true>, og, blk, 0, s, oa);
         }
 

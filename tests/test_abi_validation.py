@@ -308,3 +308,24 @@ def test_graph_attention_validation():
     assert lib.cr_sage_linear_fwd(C.byref(layer), vp(), 8, None, vp(), 64, 0, vp(), None, None) == B.CR_OK
     layer.W = None
     assert lib.cr_sage_linear_fwd(C.byref(layer), vp(), 8, None, vp(), 64, 0, vp(), None, None) == B.CR_ERR_INVALID_ARG
+
+
+def test_grouped_gather_validation():
+    lib = B.lib()
+    def blocks(**kw):
+        b = block_set(4, 10, 48, 528, 480, t=False)
+        b.gather_ids = kw.get("gather_ids", FAKE)
+        b.group_order = kw.get("group_order", FAKE)
+        return b
+    call = lambda b, **kw: lib.cr_gather_aggregate_fwd_group(C.byref(b), vp(kw.get("H", FAKE)), kw.get("dtype", 0), kw.get("ld_src", 128),
+                                                             kw.get("F", 128), vp(kw.get("agg", FAKE)), vp(kw.get("self_", FAKE)),
+                                                             kw.get("stride", 48), kw.get("ld", 128), None)
+    assert call(blocks()) == B.CR_OK
+    assert call(blocks(group_order=None)) == B.CR_ERR_INVALID_ARG       # needs the group's order ...
+    assert call(blocks(gather_ids=None)) == B.CR_ERR_INVALID_ARG        # ... and the per-edge global ids
+    assert call(blocks(), stride=47) == B.CR_ERR_INVALID_ARG            # batches would overlap
+    assert call(blocks(), agg=None) == B.CR_ERR_INVALID_ARG
+    assert call(blocks(), ld=100) == B.CR_ERR_INVALID_ARG
+    assert call(blocks(), ld_src=126) == B.CR_ERR_INVALID_ARG
+    assert call(blocks(), dtype=3) == B.CR_ERR_INVALID_ARG
+    assert call(blocks(), H=None) == B.CR_ERR_INVALID_ARG

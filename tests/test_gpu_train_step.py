@@ -215,13 +215,55 @@ def test_row_processing_order_changes_nothing(tiny_workload, model):
     out = []
     for order in (False, True):
         tr = Trainer(w, group_size=4, lr=0.05, seed=0, model=model, order_rows=order)
-        assert tr.order_rows == order and (tr.blocks[0].row_order is not None) == order
+        b0 = tr.blocks[0]
+        assert tr.order_rows == order and (b0.row_order is not None or b0.group_order is not None) == order
+        assert tr.group_gather == (order and model == "sage")        # GraphSAGE gathers once per sampled group
         tr.run_epoch_serial(oracle.RAND, 1, 0.5, 1, max_batches=6)          # (the trainer skips the order for NORAND roots only)
         torch.cuda.synchronize()
-        assert bool(tr.blocks[0].c.row_order) == order
-        if order:
-            hdr, o = tr.headers()[0], tr.blocks[0].row_order.cpu().numpy()
+        b0 = tr.blocks[0]
+        assert bool(b0.c.row_order or b0.c.group_order) == order
+        if order and b0.row_order is not None:
+            hdr, o = tr.headers()[0], b0.row_order.cpu().numpy()
             assert np.array_equal(np.sort(o[0, :hdr[0][0]]), np.arange(hdr[0][0]))
         out.append([l.W.cpu().numpy().copy() for l in tr.layers] + [tr.loss.cpu().numpy().copy()])
     for a, b in zip(*out):
         assert np.array_equal(a, b)
+
+
+@pytest.mark.parametrize("n_batches", [4, 3])
+def test_grouped_gather_matches_the_per_batch_gather(tiny_workload, n_batches):
+    """cr_gather_aggregate_fwd_group over a sampled group (rows of all batches in community order) writes, batch by
+    batch, bit for bit what cr_gather_aggregate_fwd writes; the group order lists every row of every batch once,
+    communities ascending."""
+    import torch
+    from paper_2504_18082_amd import binding as B
+    from paper_2504_18082_amd.trainer import Trainer
+    w = tiny_workload
+    tr = Trainer(w, group_size=4, seed=0, order_rows=True)
+    assert tr.group_gather
+    tr.build_batches(oracle.RAND, 1, 2)
+    tr.agg0_all[0].fill_(0x7FC0)
+    tr.self0_all[0].fill_(0x7FC0)
+    tr.sample_group(4, n_batches, 0.5, 2)               # a full group, or a short one in the same storage
+    torch.cuda.synchronize()
+    assert tr.group_gathered[0]
+    blk, lay = tr.blocks[0], tr.layers[0]
+    hdr = tr.headers()[0]
+    n_dst = [int(hdr[g][0]) for g in range(n_batches)]
+    order = blk.group_order.cpu().numpy()
+    total = int(order[n_batches * blk.cap_dst])
+    assert total == sum(n_dst)
+    e = order[:total].astype(np.int64)
+    gg, rr = e // blk.cap_dst, e % blk.cap_dst
+    assert np.array_equal(np.sort(e), np.sort(np.concatenate([g * blk.cap_dst + np.arange(n_dst[g]) for g in range(n_batches)])))
+    src = blk.src_ids.cpu().numpy()
+    assert np.all(np.diff(w.comm[src[gg, rr]]) >= 0)
+    agg = torch.zeros((blk.cap_dst, lay.F_pad), dtype=torch.int16, device="cuda")
+    slf = torch.zeros_like(agg)
+    for g in range(n_batches):
+        B.cr_gather_aggregate_fwd(blk, g, tr.table_ptr, tr.feat_dtype, tr.ld_table, w.cfg.n_feat, True, None, agg, slf, lay.F_pad)
+        torch.cuda.synchronize()
+        assert torch.equal(tr.agg0_all[0][g, :n_dst[g]], agg[:n_dst[g]]), f"agg batch {g}"
+        assert torch.equal(tr.self0_all[0][g, :n_dst[g]], slf[:n_dst[g]]), f"self batch {g}"
+        assert bool((tr.agg0_all[0][g, n_dst[g]:] == 0x7FC0).all())      # rows past the batch's count are not touched
+    assert bool((tr.agg0_all[0][n_batches:] == 0x7FC0).all())
