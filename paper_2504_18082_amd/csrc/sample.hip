@@ -568,6 +568,7 @@ struct ScanArgs {
     int64_t copy_stride;
     int32_t *hdr;
     int32_t n_fixed;
+    const int32_t *tile_before;   // optional (one batch only): sum of everything in front of each tile, computed beforehand
 };
 
 // out[0..n] = exclusive prefix sums of in[0..n) per batch (blockIdx.y).  A workgroup owns one tile of 256 x 16
@@ -592,7 +593,9 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_kernel(ScanArgs a)
     int32_t *out_copy = a.out_copy ? a.out_copy + (int64_t)g * a.copy_stride : nullptr;
 
     int before = 0;                                          // sum of in[0..first)
-    if (first > 0) {
+    if (a.tile_before) {
+        before = a.tile_before[blockIdx.x];
+    } else if (first > 0) {
         int part = 0;
         for (int i0 = (int)threadIdx.x; i0 < first; i0 += SCAN_TILE) {      // first is a multiple of the tile size
             int x[SCAN_ITEMS];
@@ -635,6 +638,44 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_kernel(ScanArgs a)
     }
 }
 
+// For long inputs (the cells of a group-level row order: several hundred thousand) summing everything in front of
+// every tile would read the input a hundred times over; two small kernels give the tiles their starting sums instead.
+__global__ __launch_bounds__(SCAN_THREADS) void scan_tile_sums_kernel(const int32_t *in, int n, int32_t *tile_sum)
+{
+    __shared__ int lds[17];
+    const int start = (int)blockIdx.x * SCAN_TILE + (int)threadIdx.x;
+    int part = 0;
+#pragma unroll
+    for (int k = 0; k < SCAN_ITEMS; ++k) {
+        const int i = start + k * SCAN_THREADS;
+        part += i < n ? in[i] : 0;
+    }
+    int total;
+    block_exclusive_scan<SCAN_THREADS / WAVE>(part, lds, total);
+    if (threadIdx.x == 0) tile_sum[blockIdx.x] = total;
+}
+
+// exclusive prefix sums of at most 1024 * 16 tile sums, in place, by one workgroup
+__global__ __launch_bounds__(1024) void scan_tile_offsets_kernel(int32_t *tile_sum, int n_tiles)
+{
+    __shared__ int lds[17];
+    int x[16], sum = 0;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+        const int i = (int)threadIdx.x * 16 + k;
+        x[k] = i < n_tiles ? tile_sum[i] : 0;
+        sum += x[k];
+    }
+    int total;
+    int run = block_exclusive_scan_1024(sum, lds, total);
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+        const int i = (int)threadIdx.x * 16 + k;
+        if (i < n_tiles) tile_sum[i] = run;
+        run += x[k];
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // Processing order of a block's destination rows (cr_block_set.row_order): rows grouped by the community of their
 // node, a counting sort per batch over at most ORDER_BUCKETS buckets (communities are folded onto the buckets in
@@ -645,7 +686,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_kernel(ScanArgs a)
 // not reproducible, which is fine: the order only says which workgroup of the gather handles a row and when.
 // ---------------------------------------------------------------------------------------------
 constexpr int ORDER_BUCKETS = 4096;
-constexpr int ORDER_TILE = 2048;          // rows per workgroup of 256 threads
+constexpr int ORDER_TILE = 8192;          // rows per workgroup of 256 threads
 
 struct OrderArgs {
     const int32_t *prev_hdr;
@@ -985,7 +1026,7 @@ struct SamplePlan {
     bool direct = false;      // direct-address de-duplication table (one int32 per node) instead of hashing
     int64_t table_stride = 0; // per batch, in 8-byte units
     // workspace slices
-    int32_t *sel, *cnt, *newoff, *tcount, *tfill, *t_tmp, *t_pos, *order_hist, *order_cursor;
+    int32_t *sel, *cnt, *newoff, *tcount, *tfill, *t_tmp, *t_pos, *order_hist, *order_cursor, *order_tiles;
     unsigned long long *newmask, *table;
     size_t bytes;
 };
@@ -1046,8 +1087,9 @@ static cr_status make_plan(const cr_sample_cfg *cfg, int64_t n_nodes, int32_t ba
         const size_t cells = (size_t)ORDER_BUCKETS * (size_t)ceil_div(p.max_dst, ORDER_TILE) + 1;
         p.order_hist = c.take<int32_t>(G * cells);
         p.order_cursor = c.take<int32_t>(G * cells);
+        p.order_tiles = c.take<int32_t>(16384);
     } else {
-        p.order_hist = p.order_cursor = nullptr;
+        p.order_hist = p.order_cursor = p.order_tiles = nullptr;
     }
     p.bytes = c.bytes();
     return CR_OK;
@@ -1186,11 +1228,19 @@ extern "C" cr_status cr_sample_blocks(const cr_graph *graph, const cr_sample_cfg
             so.prev_hdr = prev_hdr; so.n_roots_total = n_roots_total; so.batch_size = batch_size;
             so.mode = 3; so.n_fixed = n_cells; so.in = p.order_hist; so.in_stride = n_cells + 1; so.out = p.order_cursor;
             so.out_stride = n_cells + 1; so.out_copy = nullptr; so.copy_stride = 0; so.hdr = b.hdr;
-            hipLaunchKernelGGL(scan_kernel, dim3((unsigned)ceil_div(n_cells, SCAN_TILE), grouped ? 1 : n_batches), dim3(SCAN_THREADS), 0, s, so);
+            so.tile_before = nullptr;
+            const int scan_tiles = (int)ceil_div(n_cells, SCAN_TILE);
+            if (grouped && scan_tiles > 8 && scan_tiles <= 16384) {
+                hipLaunchKernelGGL(scan_tile_sums_kernel, dim3((unsigned)scan_tiles), dim3(SCAN_THREADS), 0, s, p.order_hist, n_cells, p.order_tiles);
+                hipLaunchKernelGGL(scan_tile_offsets_kernel, dim3(1), dim3(1024), 0, s, p.order_tiles, scan_tiles);
+                so.tile_before = p.order_tiles;
+            }
+            hipLaunchKernelGGL(scan_kernel, dim3((unsigned)scan_tiles, grouped ? 1 : n_batches), dim3(SCAN_THREADS), 0, s, so);
             hipLaunchKernelGGL(order_pass_kernel<true>, og, blk, 0, s, oa);
         }
 
         ScanArgs sc;
+        sc.tile_before = nullptr;
         sc.prev_hdr = prev_hdr; sc.n_roots_total = n_roots_total; sc.batch_size = batch_size;
         sc.mode = 0; sc.in = p.cnt; sc.in_stride = p.max_dst; sc.out = b.indptr; sc.out_stride = b.cap_dst + 1;
         sc.out_copy = nullptr; sc.copy_stride = 0; sc.hdr = b.hdr;
