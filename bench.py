@@ -133,7 +133,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default="arxiv")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload's node / edge / community counts by this factor")
-    ap.add_argument("--group", type=int, default=16)
+    ap.add_argument("--group", type=int, default=32)
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-input-stats", action="store_true",
