@@ -125,14 +125,15 @@ __device__ __forceinline__ void nt_step(const NtState &st, const NtFetch<NTILES 
 // layer, so the activations are read once (see launch_nt for why it is not the default).
 // ------------------------------------------------------------------------------------------------
 template <int NTILES, int CH>
-__device__ __forceinline__ void gemm_nt_body(const NtArgs &a, uint16_t (&As)[2][128][LDS_ROW], uint16_t (&Bs)[2][NTILES * 32][LDS_ROW])
+__device__ __forceinline__ void gemm_nt_body(const NtArgs &a, uint32_t bid, uint32_t ncol, uint16_t (&As)[2][128][LDS_ROW],
+                                             uint16_t (&Bs)[2][NTILES * 32][LDS_ROW])
 {
     constexpr int BN = NTILES * 32, NB = NTILES / 2;
     const int M = min(a.hdr[CR_HDR_N_DST], a.max_rows);
     // the column tiles of one row tile run next to each other on one XCD: the activations come from HBM once
     uint32_t tile;
-    if (!xcd_compact(blockIdx.y * gridDim.x + blockIdx.x, (uint32_t)((M + 127) / 128) * gridDim.x, tile)) return;
-    const int m0 = (int)(tile / gridDim.x) * 128, n0 = (int)(tile % gridDim.x) * BN;
+    if (!xcd_compact(bid, (uint32_t)((M + 127) / 128) * ncol, tile)) return;
+    const int m0 = (int)(tile / ncol) * 128, n0 = (int)(tile % ncol) * BN;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, lr = lane & 31;
 
@@ -253,7 +254,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
 {
     __shared__ __attribute__((aligned(16))) uint16_t As[2][128][LDS_ROW];
     __shared__ __attribute__((aligned(16))) uint16_t Bs[2][NTILES * 32][LDS_ROW];
-    gemm_nt_body<NTILES, CH>(a, As, Bs);
+    gemm_nt_body<NTILES, CH>(a, blockIdx.y * gridDim.x + blockIdx.x, gridDim.x, As, Bs);
 }
 
 // Wider tiles (NTILES = 4, 8) read the activations fewer times but measured slower on MI355X for the
@@ -287,20 +288,19 @@ struct TnArgs {
     float *partial;          // [S][K2 + 1][N]: row K2 holds the column sums of Z (bias gradient)
 };
 
-__global__ __launch_bounds__(256) void gemm_tn_kernel(TnArgs a)
+// T = [buffer][operand: 0 = A, 1 = Z][m][column]: the tiles are staged as they come from memory (row-major);
+// the transposition the MFMA operands need (eight consecutive m of one column per lane) is done by the LDS
+// transpose read of gfx950.  Row stride 288 bytes: the four 32-byte row pieces a 16-lane group reads
+// fall into disjoint banks.  `bid` is the workgroup's number among the `ntile` x (splits) workgroups of the product.
+__device__ __forceinline__ void gemm_tn_body(const TnArgs &a, uint32_t bid, uint32_t ntile, uint16_t (&T)[2][2][32][TN_ROW])
 {
-    // [buffer][operand: 0 = A, 1 = Z][m][column]: the tiles are staged as they come from memory (row-major);
-    // the transposition the MFMA operands need (eight consecutive m of one column per lane) is done by the LDS
-    // transpose read of gfx950.  Row stride 288 bytes: the four 32-byte row pieces a 16-lane group reads
-    // fall into disjoint banks.
-    __shared__ __attribute__((aligned(16))) uint16_t T[2][2][32][TN_ROW];
     const int M = min(a.hdr[CR_HDR_N_DST], a.max_rows);
     // the tiles of one split run next to each other on one XCD (they share the split's rows of A and Z);
     // splits past the last row stay inactive, and the reduction skips them too
     uint32_t work;
     const int rows_per_split = rows_per_split_for(M, a.slots);
-    if (!xcd_compact(blockIdx.y * gridDim.x + blockIdx.x, (uint32_t)((M + rows_per_split - 1) / rows_per_split) * gridDim.x, work)) return;
-    const int split = (int)(work / gridDim.x), tile_id = (int)(work % gridDim.x);
+    if (!xcd_compact(bid, (uint32_t)((M + rows_per_split - 1) / rows_per_split) * ntile, work)) return;
+    const int split = (int)(work / ntile), tile_id = (int)(work % ntile);
     const int m_begin = split * rows_per_split;
     const int m_end = min(M, m_begin + rows_per_split);
     const int n_tiles = (a.N + 127) / 128;
@@ -432,6 +432,28 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(TnArgs a)
             for (int g8 = 0; g8 < 8; ++g8) tot += csum[g8][tid];
             P[(int64_t)a.K2 * a.N + n0 + tid] = tot;
         }
+    }
+}
+
+__global__ __launch_bounds__(256) void gemm_tn_kernel(TnArgs a)
+{
+    __shared__ __attribute__((aligned(16))) uint16_t T[2][2][32][TN_ROW];
+    gemm_tn_body(a, blockIdx.y * gridDim.x + blockIdx.x, gridDim.x, T);
+}
+
+// The two products of a layer's backward pass that need nothing from each other (weight gradient, input
+// gradient) in one launch: both are short and bound by memory round trips, so side by side they take about as
+// long as the longer one.  The first `tn_blocks` workgroups (a multiple of eight, so that both parts keep their
+// XCD mapping) run the weight-gradient product, the rest the input-gradient product.
+__global__ __launch_bounds__(256) void gemm_tn_nt_kernel(TnArgs t, NtArgs n, uint32_t tn_blocks, uint32_t tn_tiles, uint32_t nt_cols)
+{
+    __shared__ __attribute__((aligned(16))) uint16_t lds[2 * 2 * 32 * TN_ROW];
+    static_assert(sizeof(lds) >= sizeof(uint16_t) * (2 * 128 * LDS_ROW + 2 * 64 * LDS_ROW), "the staging tiles of either product fit");
+    if (blockIdx.x < tn_blocks) {
+        gemm_tn_body(t, blockIdx.x, tn_tiles, *reinterpret_cast<uint16_t (*)[2][2][32][TN_ROW]>(lds));
+    } else {
+        gemm_nt_body<2, 4>(n, blockIdx.x - tn_blocks, nt_cols, *reinterpret_cast<uint16_t (*)[2][128][LDS_ROW]>(lds),
+                           *reinterpret_cast<uint16_t (*)[2][64][LDS_ROW]>(lds + 2 * 128 * LDS_ROW));
     }
 }
 
@@ -740,18 +762,22 @@ extern "C" cr_status cr_sage_linear_bwd(const cr_sage_layer *layer, const int32_
     if (dry_run()) return CR_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
 
-    if (d_agg || d_in_bf16) {   // gradient w.r.t. the layer's inputs, with the weights from before the step
-        NtArgs a;
-        a.hdr = hdr; a.max_rows = max_rows; a.A0 = dz_bf16; a.A1 = nullptr; a.lda = N_pad; a.K0 = N_pad; a.K = N_pad;
-        a.B = layer->W_bf16; a.N = n_op * F_pad; a.bias = nullptr; a.relu = 0;
-        a.C0 = n_op == 2 ? d_self : d_agg; a.C1 = d_agg; a.ldc = F_pad; a.N0 = F_pad; a.Cb = d_in_bf16; a.ldcb = n_op * F_pad;
-        launch_nt(a, s);
-    }
     TnArgs t;
     t.hdr = hdr; t.max_rows = max_rows; t.A0 = n_op == 2 ? h_self : agg; t.A1 = agg; t.lda = ld_in; t.K0 = F_pad; t.K2 = n_op * F_pad;
     t.Z = dz_bf16; t.N = N_pad; t.slots = splits; t.partial = partial;
     const unsigned tn_tiles = (unsigned)(n_op * ceil_div(F_pad, 128) * ceil_div(N_pad, 128));
-    hipLaunchKernelGGL(gemm_tn_kernel, dim3(tn_tiles, (unsigned)splits + (7 + tn_tiles - 1) / tn_tiles), dim3(256), 0, s, t);
+    if (d_agg || d_in_bf16) {   // also the gradient w.r.t. the layer's inputs (weights from before the step), in the same launch
+        NtArgs a;
+        a.hdr = hdr; a.max_rows = max_rows; a.A0 = dz_bf16; a.A1 = nullptr; a.lda = N_pad; a.K0 = N_pad; a.K = N_pad;
+        a.B = layer->W_bf16; a.N = n_op * F_pad; a.bias = nullptr; a.relu = 0;
+        a.C0 = n_op == 2 ? d_self : d_agg; a.C1 = d_agg; a.ldc = F_pad; a.N0 = F_pad; a.Cb = d_in_bf16; a.ldcb = n_op * F_pad;
+        const unsigned nt_cols = (unsigned)(a.N / 64);
+        const unsigned tn_blocks = (unsigned)round_up((int64_t)tn_tiles * splits + 7, 8);
+        const unsigned nt_blocks = (unsigned)round_up((int64_t)nt_cols * ceil_div(max_rows, 128) + 7, 8);
+        hipLaunchKernelGGL(gemm_tn_nt_kernel, dim3(tn_blocks + nt_blocks), dim3(256), 0, s, t, a, tn_blocks, tn_tiles, nt_cols);
+    } else {
+        hipLaunchKernelGGL(gemm_tn_kernel, dim3(tn_tiles, (unsigned)splits + (7 + tn_tiles - 1) / tn_tiles), dim3(256), 0, s, t);
+    }
     SgdArgs g;
     g.hdr = hdr; g.max_rows = max_rows; g.n_splits = splits; g.partial = partial;
     g.F_in = layer->F_in; g.F_out = layer->F_out; g.F_pad = F_pad; g.N_pad = N_pad; g.n_op = n_op; g.W = layer->W; g.bias = layer->bias;
