@@ -394,6 +394,26 @@ cr_status cr_sage_linear_bwd_input(const cr_sage_layer *layer, const int32_t *hd
                                    const uint16_t *dz_bf16, float *d_self, float *d_agg, uint16_t *d_in_bf16,
                                    void *stream);
 
+/* Backward pass of one whole GraphSAGE-mean layer above the input layer (Eq. 1, differentiated) in two launches
+ * instead of four.  Same results, bit for bit, as
+ *   cr_sage_linear_bwd(layer, header of batch g, blocks->cap_dst, h_self, agg, ld_in, dz_bf16, lr, weight_decay,
+ *                      NULL, NULL, d_in_bf16, dW_out, db_out, ws, ws_bytes)
+ * followed by
+ *   cr_gather_aggregate_bwd(blocks, g, d_agg = d_in_bf16 + F_pad, d_self = d_in_bf16, CR_BF16, 2*F_pad, layer->F_in,
+ *                           relu_out_bf16, CR_BF16, ld_relu, NULL, d_src_bf16, ld_bf16):
+ * the first launch holds the two products (weight gradient, input gradient), the second the aggregation's backward
+ * pass together with the reduction + SGD step of the weights; the members of each pair need nothing from each other.
+ *   layer         : a two-operand layer;  blocks : needs the transposed block
+ *   d_in_bf16     : device bf16 [cap_dst][2*F_pad], scratch that holds the layer's input gradients afterwards
+ *   relu_out_bf16 : device bf16 [cap_src][ld_relu] or NULL, forward output of the layer below (ReLU mask)
+ *   d_src_bf16    : device bf16 [cap_src][ld_bf16]: dL/dZ of the layer below
+ * Everything else as in the two calls above. */
+cr_status cr_sage_layer_bwd(const cr_sage_layer *layer, const cr_block_set *blocks, int32_t g,
+                            const uint16_t *h_self, const uint16_t *agg, int64_t ld_in, const uint16_t *dz_bf16,
+                            float lr, float weight_decay, uint16_t *d_in_bf16, const uint16_t *relu_out_bf16,
+                            int64_t ld_relu, uint16_t *d_src_bf16, int64_t ld_bf16, float *dW_out, float *db_out,
+                            void *ws, size_t ws_bytes, void *stream);
+
 /* Mean softmax cross-entropy over the root rows (labels exist for roots only) and its gradient.
  *   hdr      : device block header of the root block; n = hdr[CR_HDR_N_DST] <= max_rows
  *   logits   : device float [max_rows][ld], only columns 0..n_classes-1 take part

@@ -33,7 +33,7 @@ EXPORTS = [
     "cr_gather_aggregate_fwd", "cr_gather_aggregate_fwd_group", "cr_gather_aggregate_bwd",
     "cr_graph_gcn_norm", "cr_gcn_block_norm", "cr_gcn_aggregate_fwd", "cr_gcn_aggregate_bwd",
     "cr_sage_padded_dims", "cr_sage_refresh_shadows", "cr_sage_linear_fwd",
-    "cr_sage_linear_bwd_workspace_bytes", "cr_sage_linear_bwd", "cr_sage_linear_bwd_input", "cr_softmax_xent",
+    "cr_sage_linear_bwd_workspace_bytes", "cr_sage_linear_bwd", "cr_sage_linear_bwd_input", "cr_sage_layer_bwd", "cr_softmax_xent",
     "cr_count_correct",
     "cr_gather_rows_bf16", "cr_gat_attention_fwd", "cr_gat_attention_bwd_workspace_bytes", "cr_gat_attention_bwd",
     "cr_cache_reset", "cr_cache_fetch", "cr_stage_rows", "cr_host_alloc", "cr_host_free",
@@ -132,6 +132,8 @@ def lib():
         L.cr_sage_linear_bwd.argtypes = [C.POINTER(cr_sage_layer), vp, i32, vp, vp, i64, vp, C.c_float,
                                          C.c_float, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
         L.cr_sage_linear_bwd_input.argtypes = [C.POINTER(cr_sage_layer), vp, i32, vp, vp, vp, vp, vp]
+        L.cr_sage_layer_bwd.argtypes = [C.POINTER(cr_sage_layer), C.POINTER(cr_block_set), i32, vp, vp, i64, vp, C.c_float, C.c_float,
+                                        vp, vp, i64, vp, i64, vp, vp, vp, C.c_size_t, vp]
         L.cr_softmax_xent.argtypes = [vp, i32, vp, i64, i32, vp, vp, vp, vp, vp, vp, vp]
         L.cr_count_correct.argtypes = [vp, i32, vp, i64, i32, vp, vp, vp, vp]
         L.cr_gather_rows_bf16.argtypes = [vp, i32, i64, i32, vp, vp, i32, i32, vp, i64, vp]
@@ -422,6 +424,13 @@ def cr_sage_linear_bwd(layer: SageLayer, hdr_ptr, max_rows, h_self, agg, ld_in, 
 def cr_sage_linear_bwd_input(layer: SageLayer, hdr_ptr, max_rows, dz_bf16, d_self, d_agg, stream=None, d_in_bf16=None):
     _check(lib().cr_sage_linear_bwd_input(C.byref(layer.c), hdr_ptr, max_rows, _ptr(dz_bf16), _ptr(d_self), _ptr(d_agg),
                                           _ptr(d_in_bf16), _stream(stream)))
+
+
+def cr_sage_layer_bwd(layer: SageLayer, blocks: BlockSet, g, h_self, agg, ld_in, dz_bf16, lr, weight_decay, d_in_bf16,
+                      relu_out_bf16, ld_relu, d_src_bf16, ld_bf16, ws, dW_out=None, db_out=None, stream=None):
+    _check(lib().cr_sage_layer_bwd(C.byref(layer.c), C.byref(blocks.c), g, _ptr(h_self), _ptr(agg), ld_in, _ptr(dz_bf16), lr,
+                                   weight_decay, _ptr(d_in_bf16), _ptr(relu_out_bf16), ld_relu, _ptr(d_src_bf16), ld_bf16,
+                                   _ptr(dW_out), _ptr(db_out), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)))
 
 
 def cr_softmax_xent(hdr_ptr, max_rows, logits, ld, n_classes, labels, root_ids_ptr, loss, row_loss,

@@ -2,6 +2,7 @@
 // the transposed block.  HBM-bound: every lane moves 16 bytes per load, a sub-wave group of LPR
 // lanes owns one output row and keeps several independent row loads in flight.
 #include "cr_common.h"
+#include "linear_bwd.h"
 
 namespace cr {
 
@@ -298,13 +299,14 @@ static void launch_fwd_group(const cr_block_set *b, const void *table, int64_t l
 // GCN == true is the transpose of the GCN forward: destination v contributes with gcn.dst_scale[v], the sum is
 // scaled by the source's 1/sqrt(d~) (gcn.edge_w), and a source that is also a destination adds gcn.dst_self * its own
 // gradient row (d_self is then the same array as d_agg).
-template <typename T, int LPR, int NCHUNK, bool GCN = false>
-__global__ __launch_bounds__(256) void gather_mean_bwd_kernel(
-    const int32_t *__restrict__ hdr, const int32_t *__restrict__ indptr,
+// `bid` of `nblk` workgroups (a multiple of eight) share the rows.
+template <typename T, int LPR, int NCHUNK, bool GCN>
+__device__ __forceinline__ void gather_mean_bwd_body(
+    uint32_t bid, uint32_t nblk, const int32_t *__restrict__ hdr, const int32_t *__restrict__ indptr,
     const int32_t *__restrict__ t_indptr, const int32_t *__restrict__ t_indices,
     const T *__restrict__ d_agg, const T *__restrict__ d_self, int64_t ld_in, int F,
     const void *__restrict__ relu_out, int relu_is_bf16, int64_t ld_relu, float *__restrict__ d_src,
-    uint16_t *__restrict__ d_src_bf16, int64_t ld_bf16, GcnFwd gcn = GcnFwd{nullptr, nullptr, nullptr, nullptr})
+    uint16_t *__restrict__ d_src_bf16, int64_t ld_bf16, const GcnFwd &gcn)
 {
     constexpr int VEC = Vec16<T>::N;
     constexpr int U = NCHUNK == 1 ? 8 : (NCHUNK <= 3 ? 4 : 2);
@@ -312,10 +314,10 @@ __global__ __launch_bounds__(256) void gather_mean_bwd_kernel(
     const int n_dst = hdr[CR_HDR_N_DST], n_src = hdr[CR_HDR_N_SRC];
     if (n_src <= 0) return;
     // the same walk as in the forward kernel: an eighth of the rows per XCD, swept by its workgroups together
-    const int per_xcd = (int)(gridDim.x / 8);
+    const int per_xcd = (int)(nblk / 8);
     const int xcd_rows = ((n_src + 7) / 8 + GPB - 1) / GPB * GPB;
-    const int block_first = (int)(blockIdx.x % 8) * xcd_rows + (int)(blockIdx.x / 8) * GPB;
-    const int block_end = min(n_src, (int)(blockIdx.x % 8 + 1) * xcd_rows);
+    const int block_first = (int)(bid % 8) * xcd_rows + (int)(bid / 8) * GPB;
+    const int block_end = min(n_src, (int)(bid % 8 + 1) * xcd_rows);
     const int STEP = per_xcd * GPB;
     const int gl = (int)(threadIdx.x % LPR);
     int s = block_first + (int)(threadIdx.x / LPR);
@@ -484,6 +486,51 @@ __global__ __launch_bounds__(256) void gather_mean_bwd_kernel(
         b0 = b1; e0 = e1; v0 = v1; w0 = w1;
         b1 = b2; e1 = e2;
     }
+}
+
+template <typename T, int LPR, int NCHUNK, bool GCN = false>
+__global__ __launch_bounds__(256) void gather_mean_bwd_kernel(
+    const int32_t *__restrict__ hdr, const int32_t *__restrict__ indptr,
+    const int32_t *__restrict__ t_indptr, const int32_t *__restrict__ t_indices,
+    const T *__restrict__ d_agg, const T *__restrict__ d_self, int64_t ld_in, int F,
+    const void *__restrict__ relu_out, int relu_is_bf16, int64_t ld_relu, float *__restrict__ d_src,
+    uint16_t *__restrict__ d_src_bf16, int64_t ld_bf16, GcnFwd gcn = GcnFwd{nullptr, nullptr, nullptr, nullptr})
+{
+    gather_mean_bwd_body<T, LPR, NCHUNK, GCN>(blockIdx.x, gridDim.x, hdr, indptr, t_indptr, t_indices, d_agg, d_self, ld_in, F, relu_out,
+                                              relu_is_bf16, ld_relu, d_src, d_src_bf16, ld_bf16, gcn);
+}
+
+// The aggregation's backward pass and the weight update of the same layer in one launch: neither needs anything
+// from the other (the update reads the weight-gradient partials, the aggregation the input gradients, both written
+// by the launch before), and both are short and bound by memory round trips.  The first `agg_blocks` workgroups
+// (a multiple of eight) walk the source rows, the rest reduce the partials and apply the SGD step.
+template <int LPR, int NCHUNK>
+__global__ __launch_bounds__(256) void gather_bwd_sgd_kernel(
+    uint32_t agg_blocks, SgdArgs sgd, const int32_t *__restrict__ hdr, const int32_t *__restrict__ indptr,
+    const int32_t *__restrict__ t_indptr, const int32_t *__restrict__ t_indices,
+    const uint16_t *__restrict__ d_agg, const uint16_t *__restrict__ d_self, int64_t ld_in, int F,
+    const void *__restrict__ relu_out, int relu_is_bf16, int64_t ld_relu, uint16_t *__restrict__ d_src_bf16, int64_t ld_bf16)
+{
+    __shared__ float4 red[4][64];
+    if (blockIdx.x < agg_blocks) {
+        gather_mean_bwd_body<uint16_t, LPR, NCHUNK, false>(blockIdx.x, agg_blocks, hdr, indptr, t_indptr, t_indices, d_agg, d_self, ld_in, F,
+                                                           relu_out, relu_is_bf16, ld_relu, nullptr, d_src_bf16, ld_bf16,
+                                                           GcnFwd{nullptr, nullptr, nullptr, nullptr});
+    } else {
+        sgd_reduce_body(sgd, blockIdx.x - agg_blocks, red);
+    }
+}
+
+template <int LPR, int NCHUNK>
+static void launch_bwd_sgd(const SgdArgs &sgd, unsigned sgd_blocks, int cap_src, const int32_t *hdr, const int32_t *indptr,
+                           const int32_t *t_indptr, const int32_t *t_indices, const uint16_t *d_agg, const uint16_t *d_self,
+                           int64_t ld_in, int F, const void *relu_out, int relu_is_bf16, int64_t ld_relu, uint16_t *d_src_bf16,
+                           int64_t ld_bf16, hipStream_t st)
+{
+    int64_t grid = round_up(ceil_div(cap_src, 256 / LPR), 8);
+    if (grid > 1024) grid = 1024;
+    hipLaunchKernelGGL((gather_bwd_sgd_kernel<LPR, NCHUNK>), dim3((unsigned)grid + sgd_blocks), dim3(256), 0, st, (uint32_t)grid, sgd, hdr,
+                       indptr, t_indptr, t_indices, d_agg, d_self, ld_in, F, relu_out, relu_is_bf16, ld_relu, d_src_bf16, ld_bf16);
 }
 
 template <typename T, int LPR, int NCHUNK>
@@ -704,6 +751,46 @@ extern "C" cr_status cr_gather_aggregate_bwd(const cr_block_set *blocks, int32_t
 
     run_bwd(blocks, g, d_agg, d_self, in_dtype, ld_in, F, relu_out, relu_dtype, ld_relu, d_src, d_src_bf16, ld_bf16,
             static_cast<hipStream_t>(stream), nullptr);
+    CR_LAUNCH_CHECK();
+    return CR_OK;
+}
+
+extern "C" cr_status cr_sage_layer_bwd(const cr_sage_layer *layer, const cr_block_set *blocks, int32_t g,
+                                       const uint16_t *h_self, const uint16_t *agg, int64_t ld_in, const uint16_t *dz_bf16,
+                                       float lr, float weight_decay, uint16_t *d_in_bf16, const uint16_t *relu_out_bf16,
+                                       int64_t ld_relu, uint16_t *d_src_bf16, int64_t ld_bf16, float *dW_out, float *db_out,
+                                       void *ws, size_t ws_bytes, void *stream)
+{
+    cr_status st = check_block_set(blocks, g, true);
+    if (st != CR_OK) return st;
+    CR_REQUIRE(layer != nullptr && layer->n_operands == 2, CR_ERR_INVALID_ARG, "a two-operand layer is required");
+    CR_REQUIRE(d_in_bf16 != nullptr && d_src_bf16 != nullptr, CR_ERR_INVALID_ARG, "d_in_bf16 and d_src_bf16 must be given");
+    CR_REQUIRE(aligned16(d_src_bf16) && aligned16(relu_out_bf16), CR_ERR_INVALID_ARG, "d_src_bf16 / relu_out_bf16 must be 16-byte aligned");
+    const int32_t F = layer->F_in;
+    CR_REQUIRE(F >= 1 && F <= 1024, CR_ERR_UNSUPPORTED, "F_in = %d outside 1..1024", F);
+    if (relu_out_bf16) CR_REQUIRE(ld_relu >= round_up(F, 8) && ld_relu % 8 == 0, CR_ERR_INVALID_ARG, "ld_relu must be a multiple of 8 covering F_in");
+    CR_REQUIRE(ld_bf16 % 32 == 0 && ld_bf16 >= F && ld_bf16 <= round_up(F, 64), CR_ERR_INVALID_ARG,
+               "ld_bf16 = %lld must be a multiple of 32 in [F_in, F_in rounded up to 64]", (long long)ld_bf16);
+    const int32_t *hdr = blocks->hdr + (int64_t)g * CR_HDR_WORDS;
+    SgdArgs sgd;
+    st = linear_bwd_products(layer, hdr, blocks->cap_dst, h_self, agg, ld_in, dz_bf16, lr, weight_decay, nullptr, nullptr, d_in_bf16,
+                             dW_out, db_out, ws, ws_bytes, stream, &sgd);
+    if (st != CR_OK) return st;
+    if (dry_run()) return CR_OK;
+
+    const int F_pad = (int)round_up(F, 32), N_pad = (int)round_up(layer->F_out, 64);
+    const unsigned sgd_blocks = sgd_reduce_blocks(F_pad, N_pad, 2);
+    const int32_t *indptr = blocks->indptr + (int64_t)g * (blocks->cap_dst + 1);
+    const int32_t *t_indptr = blocks->t_indptr + (int64_t)g * (blocks->cap_src + 1);
+    const int32_t *t_indices = blocks->t_indices + (int64_t)g * blocks->cap_nnz;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+#define CR_BWDS(LPR, NC) launch_bwd_sgd<LPR, NC>(sgd, sgd_blocks, blocks->cap_src, hdr, indptr, t_indptr, t_indices, d_in_bf16 + F_pad, d_in_bf16, \
+                                                 2 * (int64_t)F_pad, F, relu_out_bf16, 1, ld_relu, d_src_bf16, ld_bf16, s)
+    if (F <= 128) CR_BWDS(16, 1);
+    else if (F <= 256) CR_BWDS(32, 1);
+    else if (F <= 512) CR_BWDS(64, 1);
+    else CR_BWDS(64, 2);
+#undef CR_BWDS
     CR_LAUNCH_CHECK();
     return CR_OK;
 }

@@ -5,6 +5,7 @@
 #include <type_traits>
 
 #include "cr_common.h"
+#include "linear_bwd.h"
 
 namespace cr {
 
@@ -29,14 +30,6 @@ __device__ __forceinline__ bf16x8 lds_read8(const uint16_t *p)
 // Workgroup tile 128 (m) x 64 (n), four waves of 32 x 64; the weights are the first MFMA operand so
 // that a lane ends up with four consecutive n of one row m (vector stores along the row).
 // ------------------------------------------------------------------------------------------------
-// Rows of one split of the weight-gradient product, from the block's actual row count (read on the
-// device) and the number of partial slots the workspace holds: at most `slots` splits, at least 96 rows each.
-__host__ __device__ __forceinline__ int rows_per_split_for(int M, int slots)
-{
-    int rows = ((M + slots - 1) / slots + 95) / 96 * 96;
-    return rows < 96 ? 96 : rows;
-}
-
 struct NtArgs {
     const int32_t *hdr;
     int32_t max_rows;
@@ -457,91 +450,10 @@ __global__ __launch_bounds__(256) void gemm_tn_nt_kernel(TnArgs t, NtArgs n, uin
     }
 }
 
-// sums the partial products of the active splits in a fixed order, applies the SGD step to the float
-// master and refreshes both bf16 shadows
-struct SgdArgs {
-    const int32_t *hdr;
-    int32_t max_rows, n_splits;
-    const float *partial;
-    int32_t F_in, F_out, F_pad, N_pad, n_op;
-    float *W, *bias;
-    uint16_t *W_bf16, *Wt_bf16;
-    float lr, wd;
-    float *dW_out, *db_out;
-};
-
-// A workgroup owns 64 quadruples of consecutive n (256 outputs).  Its four waves each sum every fourth
-// split, eight loads in flight per lane; the four sums meet in LDS and wave 0 finishes in a fixed order.
 __global__ __launch_bounds__(256) void sgd_reduce_kernel(SgdArgs a)
 {
     __shared__ float4 red[4][64];
-    const int M = min(a.hdr[CR_HDR_N_DST], a.max_rows);
-    const int rows_per_split = rows_per_split_for(M, a.n_splits);
-    const int active = min(a.n_splits, (M + rows_per_split - 1) / rows_per_split);
-    const int K2 = a.n_op * a.F_pad;
-    const int nq = a.N_pad / 4;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t q = (int64_t)blockIdx.x * 64 + lane;             // quadruple index over (K2 + 1) rows of nq quadruples
-    const bool in_range = q < (int64_t)(K2 + 1) * nq;
-    const int k2 = in_range ? (int)(q / nq) : 0, n = in_range ? (int)(q % nq) * 4 : 0;
-    const bool is_bias = k2 == K2;
-    const int kin = k2 % a.F_pad, part = k2 / a.F_pad;
-    const bool live = in_range && n < a.F_out && (is_bias || kin < a.F_in);
-
-    // the master weights this lane will update are requested now (one 16-byte load when the rows allow it), so that
-    // they arrive while the partial sums are added up
-    const int64_t wi = (int64_t)(part * a.F_in + kin) * a.F_out + n;
-    const bool w_vec = (a.F_out & 3) == 0;
-    float4 wq = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (w_vec) wq = *reinterpret_cast<const float4 *>(a.W + ((live && !is_bias) ? wi : 0));      // (uniform condition)
-
-    float4 g = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (live) {
-        const float *pp = a.partial + (int64_t)k2 * a.N_pad + n;
-        const int64_t ps = (int64_t)(K2 + 1) * a.N_pad;
-        const int last = active > 0 ? active - 1 : 0;
-        for (int s = wave; s < active; s += 32) {                 // this wave's splits: wave, wave+4, wave+8, ...
-            float4 x[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) x[i] = *reinterpret_cast<const float4 *>(pp + (int64_t)min(s + 4 * i, last) * ps);
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const float keep = s + 4 * i < active ? 1.f : 0.f;
-                g.x += keep * x[i].x; g.y += keep * x[i].y; g.z += keep * x[i].z; g.w += keep * x[i].w;
-            }
-        }
-    }
-    red[wave][lane] = g;
-    __syncthreads();
-    if (wave != 0 || !live) return;
-    const float4 r0 = red[0][lane], r1 = red[1][lane], r2 = red[2][lane], r3 = red[3][lane];
-    const float gs[4] = {(r0.x + r1.x) + (r2.x + r3.x), (r0.y + r1.y) + (r2.y + r3.y),
-                         (r0.z + r1.z) + (r2.z + r3.z), (r0.w + r1.w) + (r2.w + r3.w)};
-    if (is_bias) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            if (n + i < a.F_out) {
-                if (a.db_out) a.db_out[n + i] = gs[i];
-                if (a.bias) a.bias[n + i] -= a.lr * gs[i];
-            }
-        }
-        return;
-    }
-    const float wv[4] = {wq.x, wq.y, wq.z, wq.w};
-    uint16_t wb[4] = {0, 0, 0, 0};
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        if (n + i < a.F_out) {
-            float w = w_vec ? wv[i] : a.W[wi + i];
-            if (a.dW_out) a.dW_out[wi + i] = gs[i];
-            w -= a.lr * (gs[i] + a.wd * w);
-            a.W[wi + i] = w;
-            wb[i] = f32_to_bf16(w);
-            a.Wt_bf16[(int64_t)(n + i) * K2 + k2] = wb[i];
-        }
-    }
-    *reinterpret_cast<uint2 *>(a.W_bf16 + (int64_t)k2 * a.N_pad + n) =
-        make_uint2((uint32_t)wb[0] | ((uint32_t)wb[1] << 16), (uint32_t)wb[2] | ((uint32_t)wb[3] << 16));
+    sgd_reduce_body(a, blockIdx.x, red);
 }
 
 __global__ __launch_bounds__(256) void refresh_shadows_kernel(const float *W, int F_in, int F_out, int F_pad, int N_pad, int n_op,
@@ -730,11 +642,10 @@ extern "C" cr_status cr_sage_linear_bwd_workspace_bytes(int32_t F_in, int32_t F_
     return CR_OK;
 }
 
-extern "C" cr_status cr_sage_linear_bwd(const cr_sage_layer *layer, const int32_t *hdr, int32_t max_rows,
-                                        const uint16_t *h_self, const uint16_t *agg, int64_t ld_in,
-                                        const uint16_t *dz_bf16, float lr, float weight_decay, float *d_self,
-                                        float *d_agg, uint16_t *d_in_bf16, float *dW_out, float *db_out, void *ws,
-                                        size_t ws_bytes, void *stream)
+cr_status cr::linear_bwd_products(const cr_sage_layer *layer, const int32_t *hdr, int32_t max_rows, const uint16_t *h_self,
+                                  const uint16_t *agg, int64_t ld_in, const uint16_t *dz_bf16, float lr, float weight_decay,
+                                  float *d_self, float *d_agg, uint16_t *d_in_bf16, float *dW_out, float *db_out, void *ws,
+                                  size_t ws_bytes, void *stream, SgdArgs *deferred)
 {
     int F_pad, N_pad;
     cr_status st = check_layer(layer, F_pad, N_pad);
@@ -782,9 +693,20 @@ extern "C" cr_status cr_sage_linear_bwd(const cr_sage_layer *layer, const int32_
     g.hdr = hdr; g.max_rows = max_rows; g.n_splits = splits; g.partial = partial;
     g.F_in = layer->F_in; g.F_out = layer->F_out; g.F_pad = F_pad; g.N_pad = N_pad; g.n_op = n_op; g.W = layer->W; g.bias = layer->bias;
     g.W_bf16 = layer->W_bf16; g.Wt_bf16 = layer->Wt_bf16; g.lr = lr; g.wd = weight_decay; g.dW_out = dW_out; g.db_out = db_out;
-    hipLaunchKernelGGL(sgd_reduce_kernel, dim3((unsigned)ceil_div(((int64_t)n_op * F_pad + 1) * (N_pad / 4), 64)), dim3(256), 0, s, g);
+    if (deferred) *deferred = g;
+    else hipLaunchKernelGGL(sgd_reduce_kernel, dim3(sgd_reduce_blocks(F_pad, N_pad, n_op)), dim3(256), 0, s, g);
     CR_LAUNCH_CHECK();
     return CR_OK;
+}
+
+extern "C" cr_status cr_sage_linear_bwd(const cr_sage_layer *layer, const int32_t *hdr, int32_t max_rows,
+                                        const uint16_t *h_self, const uint16_t *agg, int64_t ld_in,
+                                        const uint16_t *dz_bf16, float lr, float weight_decay, float *d_self,
+                                        float *d_agg, uint16_t *d_in_bf16, float *dW_out, float *db_out, void *ws,
+                                        size_t ws_bytes, void *stream)
+{
+    return linear_bwd_products(layer, hdr, max_rows, h_self, agg, ld_in, dz_bf16, lr, weight_decay, d_self, d_agg, d_in_bf16,
+                               dW_out, db_out, ws, ws_bytes, stream, nullptr);
 }
 
 extern "C" cr_status cr_sage_linear_bwd_input(const cr_sage_layer *layer, const int32_t *hdr, int32_t max_rows,

@@ -27,9 +27,11 @@ class Trainer:
     def __init__(self, workload: synth.Workload, group_size: int = 16, lr: float = 0.01,
                  weight_decay: float = 5e-4, seed: int = 0, device: str = "cuda", weights=None,
                  relabel_input: bool = False, edge_classes: bool = True, host_features: bool = False,
-                 cache_rows: int = 0, cache_ways: int = 16, model: str = "sage", gat_heads: int = 4, order_rows="auto"):
+                 cache_rows: int = 0, cache_ways: int = 16, model: str = "sage", gat_heads: int = 4, order_rows="auto",
+                 fused_layer_bwd: bool = True):
         import torch
         self.torch = torch
+        self.fused_layer_bwd = fused_layer_bwd
         self.w = workload
         cfg = workload.cfg
         self.cfg = cfg
@@ -403,6 +405,12 @@ class Trainer:
             else:
                 h_self, ld_in = self.out_b[l - 1], layers[l - 1].N_pad
             grads = (None if dW_out is None else dW_out[l], None if db_out is None else db_out[l])
+            if side is None and l >= 1 and self.fused_layer_bwd:
+                # the whole layer in two launches: (weight gradient | input gradient), (aggregation backward | SGD step)
+                prev = layers[l - 1]
+                B.cr_sage_layer_bwd(lay, blk, g, h_self, self.agg[l], ld_in, self.dz[l], self.lr, self.wd, self.d_in[l],
+                                    self.out_b[l - 1], prev.N_pad, self.dz[l - 1], prev.N_pad, self.ws_bwd[l], *grads)
+                continue
             if side is None:
                 B.cr_sage_linear_bwd(lay, blk.hdr_ptr(g), blk.cap_dst, h_self, self.agg[l], ld_in, self.dz[l], self.lr, self.wd,
                                      None, None, self.ws_bwd[l], *grads, d_in_bf16=self.d_in[l])

@@ -221,6 +221,29 @@ def test_linear_and_loss_validation():
     assert cnt(count=None) == B.CR_ERR_INVALID_ARG
 
 
+def test_fused_layer_backward_validation():
+    lib = B.lib()
+    layer = B.cr_sage_layer(100, 47, 2, 0, FAKE, FAKE, FAKE, FAKE)
+    need = B.cr_sage_linear_bwd_workspace_bytes(100, 47, 8)
+
+    def call(**kw):
+        blocks = kw.get("blocks", block_set())
+        return lib.cr_sage_layer_bwd(C.byref(kw.get("layer", layer)), C.byref(blocks), kw.get("g", 0), vp(kw.get("h", FAKE)), vp(),
+                                     kw.get("ld", 128), vp(kw.get("dz", FAKE)), C.c_float(0.01), C.c_float(0.0), vp(kw.get("d_in", FAKE)),
+                                     vp(kw.get("relu", FAKE)), kw.get("ld_relu", 128), vp(kw.get("d_src", FAKE)), kw.get("ld_bf16", 128),
+                                     None, None, vp(), kw.get("ws", need), None)
+    assert call() == B.CR_OK
+    assert call(relu=None) == B.CR_OK                                     # no ReLU below
+    assert call(g=1) == B.CR_ERR_INVALID_ARG
+    assert call(blocks=block_set(t=False)) == B.CR_ERR_INVALID_ARG        # needs the transposed block
+    assert call(layer=B.cr_sage_layer(128, 47, 1, 0, FAKE, FAKE, FAKE, FAKE), h=None) == B.CR_ERR_INVALID_ARG
+    assert call(d_in=None) == B.CR_ERR_INVALID_ARG and call(d_src=None) == B.CR_ERR_INVALID_ARG
+    assert call(ld_relu=100) == B.CR_ERR_INVALID_ARG and call(ld_bf16=96) == B.CR_ERR_INVALID_ARG
+    assert call(ld=96) == B.CR_ERR_INVALID_ARG and call(dz=None) == B.CR_ERR_INVALID_ARG
+    assert call(d_src=FAKE + 4) == B.CR_ERR_INVALID_ARG
+    assert call(ws=need - 1) == B.CR_ERR_CAPACITY
+
+
 def test_feature_cache_validation():
     lib = B.lib()
     def cache(**kw):

@@ -205,6 +205,32 @@ def test_input_frontier_relabelling_changes_nothing(tiny_workload):
         assert np.array_equal(a, b)
 
 
+@pytest.mark.parametrize("which", ["tiny", "arxiv"])
+def test_fused_layer_backward_changes_nothing(tiny_workload, arxiv_workload, which):
+    """cr_sage_layer_bwd (a layer's backward pass in two launches of paired work) against the four separate launches
+    of cr_sage_linear_bwd + cr_gather_aggregate_bwd: weights, exported gradients and loss are bit-identical."""
+    import torch
+    from paper_2504_18082_amd.trainer import Trainer
+    w = tiny_workload if which == "tiny" else arxiv_workload
+    steps = 5 if which == "tiny" else 2
+    out = []
+    for fused in (False, True):
+        tr = Trainer(w, group_size=4, lr=0.05, seed=0, fused_layer_bwd=fused)
+        dW = [torch.zeros_like(l.W) for l in tr.layers]
+        db = [torch.zeros(l.F_out, dtype=torch.float32, device="cuda") for l in tr.layers]
+        tr.build_batches(oracle.COMM_RAND, 2, 1)
+        tr.sample_group(0, 4, 0.9, 1)
+        for g in range(min(steps, 4)):
+            print(f"fused={fused} workload={which} batch={g}", flush=True)
+            tr.train_batch(g, dW, db)
+        torch.cuda.synchronize()
+        out.append([l.W.cpu().numpy().copy() for l in tr.layers] + [l.bias.cpu().numpy().copy() for l in tr.layers]
+                   + [x.cpu().numpy().copy() for x in dW + db] + [tr.loss.cpu().numpy().copy()]
+                   + [x.cpu().numpy().copy() for x in tr.dz[:-1]])
+    for a, b in zip(*out):
+        assert np.array_equal(a, b)
+
+
 @pytest.mark.parametrize("model", ["sage", "gcn"])
 def test_row_processing_order_changes_nothing(tiny_workload, model):
     """The layer-0 gather may walk its rows in community order (cr_block_set.row_order): every weight after some
