@@ -38,7 +38,8 @@ def hdr_for(torch, n_rows):
 
 
 @pytest.mark.parametrize("M,F_in,F_out,relu", [(300, 64, 64, True), (1000, 100, 256, True), (517, 256, 40, False),
-                                               (130, 602, 256, True), (64, 32, 10, False), (1, 64, 64, True)])
+                                               (130, 602, 256, True), (64, 32, 10, False), (1, 64, 64, True),
+                                               (33001, 64, 256, True), (66010, 100, 128, False)])     # the last two: several workgroup rounds
 def test_linear_fwd(torch_mod, M, F_in, F_out, relu):
     torch = torch_mod
     from paper_2504_18082_amd import binding as B
@@ -131,6 +132,36 @@ def test_linear_bwd_and_sgd(torch_mod, M, F_in, F_out, need_dx):
         # the bf16 copy is the float result rounded to nearest even, [d_self | d_agg] side by side
         both = np.concatenate([g_self.cpu().numpy()[:M], g_agg.cpu().numpy()[:M]], axis=1)
         np.testing.assert_array_equal(g_in_b.cpu().numpy()[:M].view(np.uint16), synth.float_to_bf16_bits(both))
+
+
+@pytest.mark.parametrize("M,F_in,F_out", [(777, 100, 40), (70000, 64, 64)])
+def test_linear_bwd_input_only(torch_mod, M, F_in, F_out):
+    """cr_sage_linear_bwd_input against the oracle, float and bf16 outputs."""
+    torch = torch_mod
+    from paper_2504_18082_amd import binding as B
+    rng = np.random.default_rng(M + 5 * F_out)
+    print(f"case bwd_input M={M} F_in={F_in} F_out={F_out}", flush=True)
+    W = (rng.standard_normal((2 * F_in, F_out)) / np.sqrt(2 * F_in)).astype(np.float32)
+    dz = (rng.standard_normal((M, F_out)) / 8).astype(np.float32)
+    zeros = np.zeros((M, F_in), dtype=np.float32)
+    _, _, d_self, d_agg = oracle.sage_linear_bwd(zeros, zeros, W, np.ones((M, F_out)), dz, False, True, need_dx=True)
+    layer = B.SageLayer(W, np.zeros(F_out, np.float32))
+    layer.refresh()
+    cap = M + 50
+    d_dz = to_bf16_dev(torch, np.pad(dz, ((0, 50), (0, 0)), constant_values=2.0), layer.N_pad)
+    g_self = torch.full((cap, layer.F_pad), np.nan, dtype=torch.float32, device="cuda")
+    g_agg = torch.full((cap, layer.F_pad), np.nan, dtype=torch.float32, device="cuda")
+    g_in_b = torch.full((cap, 2 * layer.F_pad), 0x7FC0, dtype=torch.int16, device="cuda")
+    hdr = hdr_for(torch, M)
+    B.cr_sage_linear_bwd_input(layer, C.c_void_p(hdr.data_ptr()), cap, d_dz, g_self, g_agg, d_in_bf16=g_in_b)
+    torch.cuda.synchronize()
+    gs, ga = g_self.cpu().numpy(), g_agg.cpu().numpy()
+    assert_close(gs[:M, :F_in], d_self, 1e-4, "d_self")
+    assert_close(ga[:M, :F_in], d_agg, 1e-4, "d_agg")
+    assert np.all(gs[:M, F_in:] == 0) and np.all(ga[:M, F_in:] == 0)
+    assert np.all(np.isnan(gs[M:])) and np.all(np.isnan(ga[M:]))
+    np.testing.assert_array_equal(g_in_b.cpu().numpy()[:M].view(np.uint16), synth.float_to_bf16_bits(np.concatenate([gs[:M], ga[:M]], axis=1)))
+    assert np.all(g_in_b.cpu().numpy()[M:].view(np.uint16) == 0x7FC0)
 
 
 @pytest.mark.parametrize("n,Cn", [(256, 10), (1024, 40), (1000, 172), (1, 7)])
