@@ -1,6 +1,8 @@
 // Feature-row gather with GraphSAGE-mean aggregation (forward) and its atomic-free backward over
 // the transposed block.  HBM-bound: every lane moves 16 bytes per load, a sub-wave group of LPR
 // lanes owns one output row and keeps several independent row loads in flight.
+#include <type_traits>
+
 #include "cr_common.h"
 #include "linear_bwd.h"
 
@@ -384,13 +386,16 @@ __device__ __forceinline__ void gather_mean_bwd_body(
         for (int base = b0; base < e0; base += LPR) {
             if (base > b0) load_ids(base, e0, v, w);
             const int cnt = min(LPR, e0 - base);
-            for (int t = 0; t < cnt; t += U) {
-                // branch-free: a slot past the segment's end re-reads the segment's last row with weight 0, a lane past
-                // the row's end reads column 0; so the U loads are issued back to back
-                typename Vec16<T>::Raw x[U][NCHUNK];
-                float ww[U];
+            // branch-free: a slot past the segment's end re-reads the segment's last row with weight 0, a lane past
+            // the row's end reads column 0; so the loads of one pass are issued back to back.  Most source rows of a
+            // sampled block are used by one or two destinations, so the first pass takes two slots and only longer
+            // segments go on in passes of U (a pass costs its loads whether the slots exist or not).
+            auto pass = [&](auto width, int t) {
+                constexpr int UU = decltype(width)::value;
+                typename Vec16<T>::Raw x[UU][NCHUNK];
+                float ww[UU];
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
+                for (int u = 0; u < UU; ++u) {
                     const int src = min(t + u, cnt - 1);
                     const int vv = __shfl(v, src, LPR);
                     const float wv = __shfl(w, src, LPR);
@@ -403,7 +408,7 @@ __device__ __forceinline__ void gather_mean_bwd_body(
                     }
                 }
 #pragma unroll
-                for (int u = 0; u < U; ++u)
+                for (int u = 0; u < UU; ++u)
 #pragma unroll
                     for (int c = 0; c < NCHUNK; ++c) {
                         float f[VEC];
@@ -411,7 +416,9 @@ __device__ __forceinline__ void gather_mean_bwd_body(
 #pragma unroll
                         for (int i = 0; i < VEC; ++i) acc[c][i] += f[i] * ww[u];
                     }
-            }
+            };
+            pass(std::integral_constant<int, 2>{}, 0);
+            for (int t = 2; t < cnt; t += U) pass(std::integral_constant<int, U>{}, t);
         }
 #pragma unroll
         for (int c = 0; c < NCHUNK; ++c) {
