@@ -250,6 +250,98 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
     gemm_nt_body<NTILES, CH>(a, blockIdx.y * gridDim.x + blockIdx.x, gridDim.x, As, Bs);
 }
 
+// ------------------------------------------------------------------------------------------------
+// The same product for blocks of few rows (the layers next to the roots: about a thousand rows), where the tiled
+// kernel above leaves most of the chip idle and spends its time in K steps taken one after another.  Workgroup tile
+// 32 (m) x 64 (n); the four waves split K between them (wave w takes the 16-wide steps w, w + 4, ...) and fetch
+// their MFMA operands straight from memory in the layout the matrix cores want (both operands are contiguous along
+// k: a lane's fragment is one 16-byte load), up to eight steps in flight, no staging and no barrier inside the
+// loop.  The four partial tiles meet in LDS and are added in a fixed order.
+// ------------------------------------------------------------------------------------------------
+constexpr int SMALL_DEPTH = 8;
+constexpr int SMALL_ROW = 68;     // floats per staged row: 64 + 4 of padding (272 bytes, keeps 16-byte alignment)
+
+__global__ __launch_bounds__(256) void gemm_nt_small_kernel(NtArgs a)
+{
+    __shared__ __attribute__((aligned(16))) float red[4][32][SMALL_ROW];
+    const int M = min(a.hdr[CR_HDR_N_DST], a.max_rows);
+    const int m0 = (int)blockIdx.y * 32, n0 = (int)blockIdx.x * 64;
+    if (m0 >= M) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int half = lane >> 5, lr = lane & 31;
+    const int nk = a.K / 16;
+    const int64_t arow = (int64_t)min(m0 + lr, M - 1) * a.lda + 8 * half;
+    const uint16_t *b0 = a.B + (int64_t)(n0 + lr) * a.K + 8 * half;
+    const uint16_t *b1 = b0 + (int64_t)32 * a.K;
+
+    f32x16 acc[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+
+    for (int s0 = wave; s0 < nk; s0 += 4 * SMALL_DEPTH) {
+        u32x4v xa[SMALL_DEPTH], xb0[SMALL_DEPTH], xb1[SMALL_DEPTH];
+#pragma unroll
+        for (int i = 0; i < SMALL_DEPTH; ++i) {
+            const int k0 = min(s0 + 4 * i, nk - 1) * 16;       // a step past the end re-reads the last one and is not used
+            const uint16_t *src = k0 < a.K0 ? a.A0 + k0 : a.A1 + (k0 - a.K0);
+            xa[i] = *reinterpret_cast<const u32x4v *>(src + arow);
+            xb0[i] = *reinterpret_cast<const u32x4v *>(b0 + k0);
+            xb1[i] = *reinterpret_cast<const u32x4v *>(b1 + k0);
+        }
+#pragma unroll
+        for (int i = 0; i < SMALL_DEPTH; ++i) {
+            if (s0 + 4 * i < nk) {                              // (uniform over the wave)
+                const bf16x8 act = __builtin_bit_cast(bf16x8, xa[i]);
+                acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, xb0[i]), act, acc[0], 0, 0, 0);
+                acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, xb1[i]), act, acc[1], 0, 0, 0);
+            }
+        }
+    }
+    // a lane holds, for row lr, the columns t*32 + 8*grp + 4*half .. + 4
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int grp = 0; grp < 4; ++grp)
+            *reinterpret_cast<float4 *>(&red[wave][lr][t * 32 + 8 * grp + 4 * half]) =
+                make_float4(acc[t][grp * 4 + 0], acc[t][grp * 4 + 1], acc[t][grp * 4 + 2], acc[t][grp * 4 + 3]);
+    __syncthreads();
+    const int row = tid >> 3, c8 = (tid & 7) * 8;
+    if (m0 + row >= M) return;
+    float v[8];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const float4 p0 = *reinterpret_cast<const float4 *>(&red[0][row][c8 + 4 * h]), p1 = *reinterpret_cast<const float4 *>(&red[1][row][c8 + 4 * h]);
+        const float4 p2 = *reinterpret_cast<const float4 *>(&red[2][row][c8 + 4 * h]), p3 = *reinterpret_cast<const float4 *>(&red[3][row][c8 + 4 * h]);
+        v[4 * h + 0] = (p0.x + p1.x) + (p2.x + p3.x); v[4 * h + 1] = (p0.y + p1.y) + (p2.y + p3.y);
+        v[4 * h + 2] = (p0.z + p1.z) + (p2.z + p3.z); v[4 * h + 3] = (p0.w + p1.w) + (p2.w + p3.w);
+    }
+    const int n = n0 + c8;
+    if (a.bias) {
+        const float4 q0 = *reinterpret_cast<const float4 *>(a.bias + n), q1 = *reinterpret_cast<const float4 *>(a.bias + n + 4);
+        v[0] += q0.x; v[1] += q0.y; v[2] += q0.z; v[3] += q0.w; v[4] += q1.x; v[5] += q1.y; v[6] += q1.z; v[7] += q1.w;
+    }
+    if (a.relu) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = v[i] < 0.f ? 0.f : v[i];
+    }
+    const int64_t m = m0 + row;
+    if (a.C0) {
+        float *dst = n < a.N0 ? a.C0 + m * a.ldc + n : a.C1 + m * a.ldc + (n - a.N0);    // (N0 is a multiple of 32: no piece straddles)
+        *reinterpret_cast<float4 *>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+        *reinterpret_cast<float4 *>(dst + 4) = make_float4(v[4], v[5], v[6], v[7]);
+    }
+    if (a.Cb) {
+        u32x4v x;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) x[i] = (uint32_t)f32_to_bf16(v[2 * i]) | ((uint32_t)f32_to_bf16(v[2 * i + 1]) << 16);
+        *reinterpret_cast<u32x4v *>(a.Cb + m * a.ldcb + n) = x;
+    }
+}
+
+constexpr int NT_SMALL_ROWS = 2048;    // blocks of at most this many rows (by capacity) take the kernel above
+
 // Wider tiles (NTILES = 4, 8) read the activations fewer times but measured slower on MI355X for the
 // layer widths of this path (K = 256..512, N = 256): these products are bound by memory round trips
 // and occupancy, not by the matrix cores, so the smallest tile at the highest occupancy wins.
@@ -257,6 +349,10 @@ static void launch_nt(const NtArgs &a, hipStream_t s)
 {
     // xcd_compact needs the grid rounded up to a multiple of eight blocks
     const unsigned ncol = (unsigned)(a.N / 64);
+    if (a.max_rows <= NT_SMALL_ROWS) {
+        hipLaunchKernelGGL(gemm_nt_small_kernel, dim3(ncol, (unsigned)ceil_div(a.max_rows, 32)), dim3(256), 0, s, a);
+        return;
+    }
     const dim3 grid(ncol, (unsigned)ceil_div(a.max_rows, 128) + (7 + ncol - 1) / ncol);
     hipLaunchKernelGGL((gemm_nt_kernel<2, 4>), grid, dim3(256), 0, s, a);
 }
