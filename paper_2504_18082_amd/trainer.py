@@ -184,14 +184,14 @@ class Trainer:
         self.stream_gather = torch.cuda.Stream(device=device)
         self.stream_weights = torch.cuda.Stream(device=device)
         self.weights_on_side_stream = False     # set by run_epoch(weights_on_side_stream=True)
-        self.order_now = self.order_rows        # build_batches() switches it off for the root policy it does not pay for
+        self.order_now = self.order_rows
         self.ev_weights = [None] * self.L        # event: layer l's weights are updated and its operands are free again
 
     # ------------------------------------------------------------------ step 1
     def build_batches(self, policy: int, mix_count: int, epoch: int) -> int:
-        # batches that follow the community order already have the locality the row order is for (measured: no gain,
-        # ~1 % cost); random and community-mixing batches gain from it
-        self.order_now = self.order_rows and policy != B.CR_ROOTS_NORAND
+        # every root policy gains: random and community-mixing batches from the locality of the order, batches that
+        # follow the community order already (NORAND) from gathering a whole group in one launch
+        self.order_now = self.order_rows
         return B.cr_build_batches(policy, mix_count, self.B, self.seed, epoch, self.train_ids, self.comm, self.cfg.n_comm,
                                   self.ws_batches, self.perm)
 

@@ -244,7 +244,7 @@ def test_row_processing_order_changes_nothing(tiny_workload, model):
         b0 = tr.blocks[0]
         assert tr.order_rows == order and (b0.row_order is not None or b0.group_order is not None) == order
         assert tr.group_gather == (order and model == "sage")        # GraphSAGE gathers once per sampled group
-        tr.run_epoch_serial(oracle.RAND, 1, 0.5, 1, max_batches=6)          # (the trainer skips the order for NORAND roots only)
+        tr.run_epoch_serial(oracle.RAND, 1, 0.5, 1, max_batches=6)
         torch.cuda.synchronize()
         b0 = tr.blocks[0]
         assert bool(b0.c.row_order or b0.c.group_order) == order
