@@ -444,7 +444,7 @@ __device__ __forceinline__ bool select_big_row_weighted(const SelectArgs &a, int
 // instructions: a row with deg <= fanout keeps every neighbour, otherwise the slots whose (key, slot)
 // pair ranks below the fanout inside their row survive; output keeps slot order.  Longer rows go through
 // select_big_row one at a time.
-constexpr int SEL_ROWS = 4;
+constexpr int SEL_ROWS = 8;
 
 template <int MODE>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))) void select_kernel(SelectArgs a)
