@@ -426,6 +426,22 @@ cr_status cr_softmax_xent(const int32_t *hdr, int32_t max_rows, const float *log
                           float *loss, float *row_loss, float *d_logits, uint16_t *d_logits_bf16,
                           void *stream);
 
+/* The layer next to the loss and the loss in one call: cr_sage_linear_fwd(relu = 0, out = logits, out_bf16 = NULL)
+ * followed by cr_softmax_xent(hdr, max_rows, logits, N_pad, n_classes, ..., d_logits = NULL, d_logits_bf16).  When the
+ * layer has at most 64 outputs and the block at most 2048 rows (by max_rows) this is one launch: a workgroup of the
+ * product holds whole rows of logits and finishes their loss terms in place; otherwise the separate kernels run.
+ * Logits are bit-identical to cr_sage_linear_fwd's; the loss terms may differ from cr_softmax_xent's in the last
+ * bits (sums are associated differently), never from run to run.
+ *   logits        : device float [max_rows][N_pad];  d_logits_bf16 : device bf16 [max_rows][N_pad]
+ *   scratch       : device, CR_XENT_SCRATCH_BYTES; its first word must be zero before the first call and every call
+ *                   leaves it zero again; calls that share a scratch must not overlap
+ * The remaining arguments as in the two calls. */
+#define CR_XENT_SCRATCH_BYTES 512
+cr_status cr_sage_linear_fwd_xent(const cr_sage_layer *layer, const int32_t *hdr, int32_t max_rows,
+                                  const uint16_t *h_self, const uint16_t *agg, int64_t ld_in, float *logits,
+                                  int32_t n_classes, const int32_t *labels, const int32_t *root_ids, float *loss,
+                                  float *row_loss, uint16_t *d_logits_bf16, void *scratch, void *stream);
+
 /* Validation pass of the training protocol (Section 5 "Training methodology": final validation accuracy, early
  * stopping on the validation loss): adds to *count the number of root rows whose largest logit (lowest class index
  * on ties) equals the label.  Same arguments as cr_softmax_xent; count is a device int32 that the caller zeroes.

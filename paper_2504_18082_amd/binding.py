@@ -32,7 +32,7 @@ EXPORTS = [
     "cr_graph_edge_classes", "cr_block_capacities", "cr_sample_blocks_workspace_bytes", "cr_sample_blocks",
     "cr_gather_aggregate_fwd", "cr_gather_aggregate_fwd_group", "cr_gather_aggregate_bwd",
     "cr_graph_gcn_norm", "cr_gcn_block_norm", "cr_gcn_aggregate_fwd", "cr_gcn_aggregate_bwd",
-    "cr_sage_padded_dims", "cr_sage_refresh_shadows", "cr_sage_linear_fwd",
+    "cr_sage_padded_dims", "cr_sage_refresh_shadows", "cr_sage_linear_fwd", "cr_sage_linear_fwd_xent",
     "cr_sage_linear_bwd_workspace_bytes", "cr_sage_linear_bwd", "cr_sage_linear_bwd_input", "cr_sage_layer_bwd", "cr_softmax_xent",
     "cr_count_correct",
     "cr_gather_rows_bf16", "cr_gat_attention_fwd", "cr_gat_attention_bwd_workspace_bytes", "cr_gat_attention_bwd",
@@ -128,6 +128,7 @@ def lib():
         L.cr_sage_padded_dims.argtypes = [i32, i32, C.POINTER(i32), C.POINTER(i32)]
         L.cr_sage_refresh_shadows.argtypes = [C.POINTER(cr_sage_layer), vp]
         L.cr_sage_linear_fwd.argtypes = [C.POINTER(cr_sage_layer), vp, i32, vp, vp, i64, C.c_int, vp, vp, vp]
+        L.cr_sage_linear_fwd_xent.argtypes = [C.POINTER(cr_sage_layer), vp, i32, vp, vp, i64, vp, i32, vp, vp, vp, vp, vp, vp, vp]
         L.cr_sage_linear_bwd_workspace_bytes.argtypes = [i32, i32, i32, C.POINTER(C.c_size_t)]
         L.cr_sage_linear_bwd.argtypes = [C.POINTER(cr_sage_layer), vp, i32, vp, vp, i64, vp, C.c_float,
                                          C.c_float, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
@@ -412,6 +413,16 @@ def cr_sage_linear_bwd_workspace_bytes(F_in, F_out, max_rows) -> int:
     n = C.c_size_t(0)
     _check(lib().cr_sage_linear_bwd_workspace_bytes(F_in, F_out, max_rows, C.byref(n)))
     return n.value
+
+
+CR_XENT_SCRATCH_BYTES = 512
+
+
+def cr_sage_linear_fwd_xent(layer: SageLayer, hdr_ptr, max_rows, h_self, agg, ld_in, logits, n_classes, labels, root_ids_ptr, loss,
+                            row_loss, d_logits_bf16, scratch, stream=None):
+    _check(lib().cr_sage_linear_fwd_xent(C.byref(layer.c), hdr_ptr, max_rows, _ptr(h_self), _ptr(agg), ld_in, _ptr(logits), n_classes,
+                                         _ptr(labels), root_ids_ptr, _ptr(loss), _ptr(row_loss), _ptr(d_logits_bf16), _ptr(scratch),
+                                         _stream(stream)))
 
 
 def cr_sage_linear_bwd(layer: SageLayer, hdr_ptr, max_rows, h_self, agg, ld_in, dz_bf16, lr, weight_decay,

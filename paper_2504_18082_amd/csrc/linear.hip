@@ -261,11 +261,31 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
 constexpr int SMALL_DEPTH = 8;
 constexpr int SMALL_ROW = 68;     // floats per staged row: 64 + 4 of padding (272 bytes, keeps 16-byte alignment)
 
-__global__ __launch_bounds__(256) void gemm_nt_small_kernel(NtArgs a)
+// loss part of the fused top-layer launch (XENT == true): the product's rows are the roots, its columns the classes
+struct XentArgs {
+    int32_t n_classes;
+    const int32_t *labels, *root_ids;
+    float *loss, *row_loss;
+    uint16_t *d_logits_bf16;      // [max_rows][64]
+    float *part;                  // [ceil(max_rows / 32)] per-workgroup sums of row losses
+    int32_t *ticket;              // counts finished workgroups; zero between calls
+};
+
+// XENT == true (one column tile: at most 64 classes; no ReLU, no bf16 copy): a workgroup holds whole rows of
+// logits after the reduction, so the softmax cross-entropy of its rows, their gradient and its share of the mean
+// loss are taken right there; the workgroup that finishes last adds the shares up in index order.
+template <bool XENT>
+__global__ __launch_bounds__(256) void gemm_nt_small_kernel(NtArgs a, XentArgs x)
 {
     __shared__ __attribute__((aligned(16))) float red[4][32][SMALL_ROW];
+    __shared__ float wg_loss[32];
+    __shared__ int last_flag;
     const int M = min(a.hdr[CR_HDR_N_DST], a.max_rows);
     const int m0 = (int)blockIdx.y * 32, n0 = (int)blockIdx.x * 64;
+    if (XENT && M <= 0) {
+        if (blockIdx.y == 0 && threadIdx.x == 0) x.loss[0] = 0.f;
+        return;
+    }
     if (m0 >= M) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, lr = lane & 31;
@@ -308,7 +328,8 @@ __global__ __launch_bounds__(256) void gemm_nt_small_kernel(NtArgs a)
                 make_float4(acc[t][grp * 4 + 0], acc[t][grp * 4 + 1], acc[t][grp * 4 + 2], acc[t][grp * 4 + 3]);
     __syncthreads();
     const int row = tid >> 3, c8 = (tid & 7) * 8;
-    if (m0 + row >= M) return;
+    if (!XENT && m0 + row >= M) return;
+    const bool row_ok = m0 + row < M;
     float v[8];
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
@@ -326,17 +347,79 @@ __global__ __launch_bounds__(256) void gemm_nt_small_kernel(NtArgs a)
 #pragma unroll
         for (int i = 0; i < 8; ++i) v[i] = v[i] < 0.f ? 0.f : v[i];
     }
-    const int64_t m = m0 + row;
-    if (a.C0) {
+    const int64_t m = min(m0 + row, M - 1);
+    if (a.C0 && row_ok) {
         float *dst = n < a.N0 ? a.C0 + m * a.ldc + n : a.C1 + m * a.ldc + (n - a.N0);    // (N0 is a multiple of 32: no piece straddles)
         *reinterpret_cast<float4 *>(dst) = make_float4(v[0], v[1], v[2], v[3]);
         *reinterpret_cast<float4 *>(dst + 4) = make_float4(v[4], v[5], v[6], v[7]);
     }
-    if (a.Cb) {
-        u32x4v x;
+    if (a.Cb && row_ok) {
+        u32x4v xb;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) x[i] = (uint32_t)f32_to_bf16(v[2 * i]) | ((uint32_t)f32_to_bf16(v[2 * i + 1]) << 16);
-        *reinterpret_cast<u32x4v *>(a.Cb + m * a.ldcb + n) = x;
+        for (int i = 0; i < 4; ++i) xb[i] = (uint32_t)f32_to_bf16(v[2 * i]) | ((uint32_t)f32_to_bf16(v[2 * i + 1]) << 16);
+        *reinterpret_cast<u32x4v *>(a.Cb + m * a.ldcb + n) = xb;
+    }
+    if constexpr (XENT) {
+        // the eight threads of a row sit in eight neighbouring lanes; rows past the last one compute on row M - 1 and store nothing
+        const int C = x.n_classes;
+        float mx = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) mx = fmaxf(mx, n + i < C ? v[i] : -INFINITY);
+#pragma unroll
+        for (int off = 1; off < 8; off <<= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+        float e[8], den = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            e[i] = n + i < C ? expf(v[i] - mx) : 0.f;
+            den += e[i];
+        }
+#pragma unroll
+        for (int off = 1; off < 8; off <<= 1) den += __shfl_xor(den, off);
+        const int label = x.labels[x.root_ids[m]];
+        const float inv_n = 1.0f / (float)M;
+        u32x4v dq;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float d0 = 0.f, d1 = 0.f;
+            if (n + 2 * i < C) d0 = (e[2 * i] / den - (n + 2 * i == label ? 1.f : 0.f)) * inv_n;
+            if (n + 2 * i + 1 < C) d1 = (e[2 * i + 1] / den - (n + 2 * i + 1 == label ? 1.f : 0.f)) * inv_n;
+            dq[i] = (uint32_t)f32_to_bf16(d0) | ((uint32_t)f32_to_bf16(d1) << 16);
+        }
+        if (row_ok) *reinterpret_cast<u32x4v *>(x.d_logits_bf16 + m * 64 + n) = dq;
+        if ((tid & 7) == 0) wg_loss[row] = 0.f;
+        __syncthreads();
+        if (label >= n && label < n + 8) {          // the thread that holds the label's logit
+            float zl = v[0];
+#pragma unroll
+            for (int i = 1; i < 8; ++i) zl = label == n + i ? v[i] : zl;
+            const float rl = -(zl - mx - logf(den));
+            if (row_ok) { x.row_loss[m] = rl; wg_loss[row] = rl; }
+        }
+        __syncthreads();
+        if (tid < 64) {
+            float t = tid < 32 ? wg_loss[tid] : 0.f;
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) t += __shfl_xor(t, off);
+            if (tid == 0) {
+                // the share is published before the ticket is taken; the last workgroup reads every share past its L1
+                __hip_atomic_store(&x.part[blockIdx.y], t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+                const int done = __hip_atomic_fetch_add(x.ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                last_flag = done == (M + 31) / 32 - 1;
+            }
+        }
+        __syncthreads();
+        if (last_flag && tid < 64) {
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+            const int nb = (M + 31) / 32;           // at most 64: this kernel takes blocks of at most 2048 rows
+            float t = tid < nb ? __hip_atomic_load(&x.part[tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.f;
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) t += __shfl_xor(t, off);
+            if (tid == 0) {
+                x.loss[0] = t / (float)M;
+                __hip_atomic_store(x.ticket, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
     }
 }
 
@@ -350,7 +433,7 @@ static void launch_nt(const NtArgs &a, hipStream_t s)
     // xcd_compact needs the grid rounded up to a multiple of eight blocks
     const unsigned ncol = (unsigned)(a.N / 64);
     if (a.max_rows <= NT_SMALL_ROWS) {
-        hipLaunchKernelGGL(gemm_nt_small_kernel, dim3(ncol, (unsigned)ceil_div(a.max_rows, 32)), dim3(256), 0, s, a);
+        hipLaunchKernelGGL(gemm_nt_small_kernel<false>, dim3(ncol, (unsigned)ceil_div(a.max_rows, 32)), dim3(256), 0, s, a, XentArgs{});
         return;
     }
     const dim3 grid(ncol, (unsigned)ceil_div(a.max_rows, 128) + (7 + ncol - 1) / ncol);
@@ -719,6 +802,45 @@ extern "C" cr_status cr_sage_linear_fwd(const cr_sage_layer *layer, const int32_
     a.B = layer->Wt_bf16; a.N = N_pad; a.bias = layer->bias; a.relu = relu ? 1 : 0;
     a.C0 = out; a.C1 = nullptr; a.ldc = N_pad; a.N0 = N_pad; a.Cb = out_bf16; a.ldcb = N_pad;
     launch_nt(a, static_cast<hipStream_t>(stream));
+    CR_LAUNCH_CHECK();
+    return CR_OK;
+}
+
+extern "C" cr_status cr_sage_linear_fwd_xent(const cr_sage_layer *layer, const int32_t *hdr, int32_t max_rows,
+                                             const uint16_t *h_self, const uint16_t *agg, int64_t ld_in, float *logits,
+                                             int32_t n_classes, const int32_t *labels, const int32_t *root_ids, float *loss,
+                                             float *row_loss, uint16_t *d_logits_bf16, void *scratch, void *stream)
+{
+    int F_pad, N_pad;
+    cr_status st = check_layer(layer, F_pad, N_pad);
+    if (st != CR_OK) return st;
+    CR_REQUIRE(hdr != nullptr && max_rows >= 1, CR_ERR_INVALID_ARG, "hdr must not be NULL and max_rows must be positive");
+    const int n_op = layer->n_operands;
+    CR_REQUIRE(agg && aligned16(h_self) && aligned16(agg), CR_ERR_INVALID_ARG, "h_self / agg must be 16-byte aligned device pointers");
+    CR_REQUIRE((h_self != nullptr) == (n_op == 2), CR_ERR_INVALID_ARG, "h_self must be given for a two-operand layer and NULL for a one-operand layer");
+    CR_REQUIRE(ld_in >= F_pad && ld_in % 8 == 0, CR_ERR_INVALID_ARG, "ld_in = %lld must be a multiple of 8 and >= %d", (long long)ld_in, F_pad);
+    CR_REQUIRE(logits && d_logits_bf16 && aligned16(logits) && aligned16(d_logits_bf16), CR_ERR_INVALID_ARG,
+               "logits / d_logits_bf16 must be 16-byte aligned device pointers");
+    CR_REQUIRE(labels && root_ids && loss && row_loss, CR_ERR_INVALID_ARG, "labels / root_ids / loss / row_loss must not be NULL");
+    CR_REQUIRE(n_classes >= 1 && n_classes <= layer->F_out, CR_ERR_INVALID_ARG, "need 1 <= n_classes <= F_out");
+    CR_REQUIRE(scratch != nullptr && aligned16(scratch), CR_ERR_INVALID_ARG, "scratch must be a 16-byte aligned device pointer");
+    if (dry_run()) return CR_OK;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    NtArgs a;
+    a.hdr = hdr; a.max_rows = max_rows; a.A0 = n_op == 2 ? h_self : agg; a.A1 = agg; a.lda = ld_in; a.K0 = F_pad; a.K = n_op * F_pad;
+    a.B = layer->Wt_bf16; a.N = N_pad; a.bias = layer->bias; a.relu = 0;
+    a.C0 = logits; a.C1 = nullptr; a.ldc = N_pad; a.N0 = N_pad; a.Cb = nullptr; a.ldcb = N_pad;
+    if (N_pad == 64 && max_rows <= NT_SMALL_ROWS) {
+        XentArgs x;
+        x.n_classes = n_classes; x.labels = labels; x.root_ids = root_ids; x.loss = loss; x.row_loss = row_loss;
+        x.d_logits_bf16 = d_logits_bf16; x.ticket = static_cast<int32_t *>(scratch); x.part = reinterpret_cast<float *>(scratch) + 4;
+        hipLaunchKernelGGL(gemm_nt_small_kernel<true>, dim3(1, (unsigned)ceil_div(max_rows, 32)), dim3(256), 0, s, a, x);
+    } else {
+        launch_nt(a, s);
+        hipLaunchKernelGGL(xent_rows_kernel, dim3((unsigned)ceil_div(max_rows, 4)), dim3(256), 0, s, hdr, max_rows, logits, (int64_t)N_pad,
+                           n_classes, labels, root_ids, row_loss, (float *)nullptr, d_logits_bf16);
+        hipLaunchKernelGGL(xent_mean_kernel, dim3(1), dim3(1024), 0, s, hdr, max_rows, row_loss, loss);
+    }
     CR_LAUNCH_CHECK();
     return CR_OK;
 }

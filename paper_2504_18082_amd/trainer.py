@@ -28,7 +28,7 @@ class Trainer:
                  weight_decay: float = 5e-4, seed: int = 0, device: str = "cuda", weights=None,
                  relabel_input: bool = False, edge_classes: bool = True, host_features: bool = False,
                  cache_rows: int = 0, cache_ways: int = 16, model: str = "sage", gat_heads: int = 4, order_rows="auto",
-                 fused_layer_bwd: bool = True):
+                 fused_layer_bwd: bool = True, fused_top_loss: bool = True):
         import torch
         self.torch = torch
         self.fused_layer_bwd = fused_layer_bwd
@@ -168,6 +168,8 @@ class Trainer:
                                    dtype=torch.uint8, device=device) for l in range(self.L)]
         self.loss = torch.zeros(1, dtype=torch.float32, device=device)
         self.row_loss = torch.zeros(self.B, dtype=torch.float32, device=device)
+        self.xent_scratch = torch.zeros(B.CR_XENT_SCRATCH_BYTES, dtype=torch.uint8, device=device)
+        self.fused_top_loss = fused_top_loss and model == "sage"
         self.agg[0] = self.agg0_bufs[0]
         self.gather0_events = []          # (start, stop) pairs around the layer-0 gather when timing is on
         self.time_gather0 = False
@@ -272,8 +274,9 @@ class Trainer:
             ev1.record()
             self.gather0_events.append((ev0, ev1))
 
-    def forward_batch(self, g: int, slot: Optional[int] = None, buf: int = 0, gather0: bool = True):
-        """Forward pass of mini-batch g of a sampled group (current stream); leaves the logits in self.out[L-1]."""
+    def forward_batch(self, g: int, slot: Optional[int] = None, buf: int = 0, gather0: bool = True, with_loss: bool = False):
+        """Forward pass of mini-batch g of a sampled group (current stream); leaves the logits in self.out[L-1].
+        with_loss: also the loss on the roots and its gradient (self.loss, self.dz[L-1]); returns whether they were taken."""
         if slot is not None:
             self.blocks = self.block_slots[slot]
         else:
@@ -301,8 +304,14 @@ class Trainer:
                 B.cr_gather_aggregate_fwd(blk, g, self.out_b[l - 1], B.CR_BF16, prev.N_pad, prev.F_out, False,
                                           None, self.agg[l], None, prev.N_pad)
                 h_self, ld_in = self.out_b[l - 1], prev.N_pad
+            if with_loss and l == L - 1 and self.fused_top_loss:
+                # the layer next to the loss and the loss itself in one launch
+                B.cr_sage_linear_fwd_xent(lay, blk.hdr_ptr(g), blk.cap_dst, h_self, self.agg[l], ld_in, self.out[l], self.cfg.n_classes,
+                                          self.labels, blk.src_ids_ptr(g), self.loss, self.row_loss, self.dz[l], self.xent_scratch)
+                return True
             B.cr_sage_linear_fwd(lay, blk.hdr_ptr(g), blk.cap_dst, h_self, self.agg[l], ld_in, l < L - 1,
                                  self.out[l], self.out_b[l])
+        return False
 
     def _forward_batch_gcn(self, g: int):
         """GCN layers: normalised aggregation over the block (the destination's own row included), one-operand layer."""
@@ -386,12 +395,13 @@ class Trainer:
     def train_batch(self, g: int, dW_out=None, db_out=None, slot: Optional[int] = None, buf: int = 0, gather0: bool = True,
                     d_attn_out=None):
         """Forward, loss, backward and SGD for mini-batch g of a sampled group (current stream)."""
-        self.forward_batch(g, slot, buf, gather0)
+        have_loss = self.forward_batch(g, slot, buf, gather0, with_loss=True)
         L, blocks, layers = self.L, self.blocks, self.layers
         # loss on the roots
         top = blocks[L - 1]
-        B.cr_softmax_xent(top.hdr_ptr(g), top.cap_dst, self.out[L - 1], layers[L - 1].N_pad, self.cfg.n_classes,
-                          self.labels, top.src_ids_ptr(g), self.loss, self.row_loss, None, self.dz[L - 1])
+        if not have_loss:
+            B.cr_softmax_xent(top.hdr_ptr(g), top.cap_dst, self.out[L - 1], layers[L - 1].N_pad, self.cfg.n_classes,
+                              self.labels, top.src_ids_ptr(g), self.loss, self.row_loss, None, self.dz[L - 1])
         # backward + SGD
         if self.model == "gcn":
             return self._backward_batch_gcn(g, dW_out, db_out)

@@ -244,6 +244,24 @@ def test_fused_layer_backward_validation():
     assert call(ws=need - 1) == B.CR_ERR_CAPACITY
 
 
+def test_forward_with_loss_validation():
+    lib = B.lib()
+    layer = B.cr_sage_layer(100, 47, 2, 0, FAKE, FAKE, FAKE, FAKE)
+
+    def call(**kw):
+        return lib.cr_sage_linear_fwd_xent(C.byref(kw.get("layer", layer)), vp(kw.get("hdr", FAKE)), kw.get("rows", 1024), vp(kw.get("h", FAKE)), vp(),
+                                           kw.get("ld", 128), vp(kw.get("logits", FAKE)), kw.get("C", 47), vp(kw.get("labels", FAKE)), vp(),
+                                           vp(kw.get("loss", FAKE)), vp(), vp(kw.get("d", FAKE)), vp(kw.get("scratch", FAKE)), None)
+    assert call() == B.CR_OK
+    assert call(rows=100000) == B.CR_OK                                   # large blocks take the separate kernels
+    assert call(hdr=None) == B.CR_ERR_INVALID_ARG and call(rows=0) == B.CR_ERR_INVALID_ARG
+    assert call(ld=96) == B.CR_ERR_INVALID_ARG and call(h=None) == B.CR_ERR_INVALID_ARG
+    assert call(logits=None) == B.CR_ERR_INVALID_ARG and call(d=None) == B.CR_ERR_INVALID_ARG and call(d=FAKE + 2) == B.CR_ERR_INVALID_ARG
+    assert call(C=48) == B.CR_ERR_INVALID_ARG and call(C=0) == B.CR_ERR_INVALID_ARG
+    assert call(labels=None) == B.CR_ERR_INVALID_ARG and call(loss=None) == B.CR_ERR_INVALID_ARG
+    assert call(scratch=None) == B.CR_ERR_INVALID_ARG
+
+
 def test_feature_cache_validation():
     lib = B.lib()
     def cache(**kw):

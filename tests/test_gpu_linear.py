@@ -194,6 +194,54 @@ def test_softmax_xent(torch_mod, n, Cn):
     assert_close(bf16_tensor_to_float(db)[:n], want_d, 2.0 ** -8, "d_logits bf16")
 
 
+@pytest.mark.parametrize("M,F_in,Cn,cap_extra", [(1000, 256, 40, 24), (1024, 100, 47, 0), (33, 64, 64, 7), (1, 32, 3, 0),
+                                                 (300, 64, 172, 5), (2500, 64, 10, 12)])     # the last two: separate kernels inside
+def test_linear_fwd_with_loss(torch_mod, M, F_in, Cn, cap_extra):
+    """cr_sage_linear_fwd_xent: logits bit-identical to cr_sage_linear_fwd, loss and gradient against the oracle's
+    softmax cross-entropy of those logits; two calls in a row on the same scratch, the second on fewer rows."""
+    torch = torch_mod
+    from paper_2504_18082_amd import binding as B
+    rng = np.random.default_rng(M + 3 * Cn)
+    hs = rng.standard_normal((M, F_in)).astype(np.float32)
+    ag = rng.standard_normal((M, F_in)).astype(np.float32) * 0.5
+    W = (rng.standard_normal((2 * F_in, Cn)) * 3 / np.sqrt(2 * F_in)).astype(np.float32)
+    b = rng.standard_normal(Cn).astype(np.float32) * 0.1
+    layer = B.SageLayer(W, b)
+    layer.refresh()
+    cap = M + cap_extra
+    ld_in, Np = layer.F_pad, layer.N_pad
+    d_hs = to_bf16_dev(torch, np.pad(hs, ((0, cap_extra), (0, 0))), ld_in)
+    d_ag = to_bf16_dev(torch, np.pad(ag, ((0, cap_extra), (0, 0))), ld_in)
+    n_nodes = 6000
+    labels_all = rng.integers(0, Cn, size=n_nodes).astype(np.int32)
+    roots = rng.choice(n_nodes, size=cap, replace=False).astype(np.int32)
+    up = lambda a: torch.from_numpy(a).cuda()
+    d_labels, d_roots = up(labels_all), up(roots)
+    scratch = torch.zeros(B.CR_XENT_SCRATCH_BYTES, dtype=torch.uint8, device="cuda")
+    for rows in (M, max(1, M // 3)):
+        print(f"case fwd+loss M={rows} F_in={F_in} classes={Cn} cap={cap}", flush=True)
+        hdr = hdr_for(torch, rows)
+        ref = torch.full((cap, Np), np.nan, dtype=torch.float32, device="cuda")
+        B.cr_sage_linear_fwd(layer, C.c_void_p(hdr.data_ptr()), cap, d_hs, d_ag, ld_in, False, ref, None)
+        logits = torch.full((cap, Np), np.nan, dtype=torch.float32, device="cuda")
+        loss = torch.full((1,), np.nan, dtype=torch.float32, device="cuda")
+        row_loss = torch.zeros(cap, dtype=torch.float32, device="cuda")
+        db = torch.full((cap, Np), 0x7FC0, dtype=torch.int16, device="cuda")
+        B.cr_sage_linear_fwd_xent(layer, C.c_void_p(hdr.data_ptr()), cap, d_hs, d_ag, ld_in, logits, Cn, d_labels,
+                                  C.c_void_p(d_roots.data_ptr()), loss, row_loss, db, scratch)
+        torch.cuda.synchronize()
+        got = logits.cpu().numpy()
+        np.testing.assert_array_equal(got[:rows], ref.cpu().numpy()[:rows])
+        assert np.all(np.isnan(got[rows:]))
+        want_loss, want_d = oracle.softmax_xent(got[:rows].astype(np.float64), labels_all[roots[:rows]], n_classes=Cn)
+        assert abs(float(loss.cpu()[0]) - want_loss) <= RTOL_F32 * max(1.0, abs(want_loss))
+        gd = bf16_tensor_to_float(db)
+        assert_close(gd[:rows, :Cn], want_d[:, :Cn], 2.0 ** -8, "d_logits bf16")
+        assert np.all(gd[:rows, Cn:] == 0)
+        assert np.all(db.cpu().numpy()[rows:].view(np.uint16) == 0x7FC0)
+        assert np.all(scratch.cpu().numpy()[:4] == 0)            # the ticket is back at zero
+
+
 @pytest.mark.parametrize("n,Cn", [(256, 10), (1024, 40), (1000, 172), (1, 7), (3, 1)])
 def test_count_correct(torch_mod, n, Cn):
     """Integer result: the same float32 logits go to both sides, so the counts must agree exactly

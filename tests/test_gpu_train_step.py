@@ -231,6 +231,33 @@ def test_fused_layer_backward_changes_nothing(tiny_workload, arxiv_workload, whi
         assert np.array_equal(a, b)
 
 
+def test_fused_top_layer_loss_changes_only_rounding(tiny_workload):
+    """cr_sage_linear_fwd_xent (the layer next to the loss and the loss in one launch) against the separate calls: the first
+    step's logits are bit-identical, its loss agrees to float rounding, and the weights after some steps stay within
+    the noise of a bf16 gradient rounded differently here and there."""
+    import torch
+    from paper_2504_18082_amd.trainer import Trainer
+    w = tiny_workload
+    out = []
+    for fused in (False, True):
+        tr = Trainer(w, group_size=4, lr=0.05, seed=0, fused_top_loss=fused)
+        assert tr.fused_top_loss == fused
+        tr.build_batches(oracle.COMM_RAND, 2, 1)
+        tr.sample_group(0, 4, 0.9, 1)
+        tr.train_batch(0)
+        torch.cuda.synchronize()
+        first = [tr.out[tr.L - 1].cpu().numpy().copy(), float(tr.loss.cpu()[0])]
+        for g in range(1, 4):
+            tr.train_batch(g)
+        torch.cuda.synchronize()
+        out.append(first + [l.W.cpu().numpy().copy() for l in tr.layers])
+    n_roots = w.cfg.batch_size
+    assert np.array_equal(out[0][0][:n_roots], out[1][0][:n_roots])
+    assert abs(out[0][1] - out[1][1]) <= 1e-6 * abs(out[0][1])
+    for a, b in zip(out[0][2:], out[1][2:]):
+        assert_close(b, a, 1e-3, "weights with and without the fused loss")
+
+
 @pytest.mark.parametrize("model", ["sage", "gcn"])
 def test_row_processing_order_changes_nothing(tiny_workload, model):
     """The layer-0 gather may walk its rows in community order (cr_block_set.row_order): every weight after some
