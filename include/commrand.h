@@ -433,8 +433,10 @@ cr_status cr_softmax_xent(const int32_t *hdr, int32_t max_rows, const float *log
  * Logits are bit-identical to cr_sage_linear_fwd's; the loss terms may differ from cr_softmax_xent's in the last
  * bits (sums are associated differently), never from run to run.
  *   logits        : device float [max_rows][N_pad];  d_logits_bf16 : device bf16 [max_rows][N_pad]
- *   scratch       : device, CR_XENT_SCRATCH_BYTES; its first word must be zero before the first call and every call
- *                   leaves it zero again; calls that share a scratch must not overlap
+ *   scratch       : device, CR_XENT_SCRATCH_BYTES; zero before the first call, and every call leaves it zero again;
+ *                   calls that share a scratch must not overlap.  In the one-launch form the mean loss is the sum of
+ *                   per-workgroup shares rounded to 2^-20 (a device-side integer accumulator: reproducible whatever the
+ *                   order of arrival), NaN if a share is not finite
  * The remaining arguments as in the two calls. */
 #define CR_XENT_SCRATCH_BYTES 512
 cr_status cr_sage_linear_fwd_xent(const cr_sage_layer *layer, const int32_t *hdr, int32_t max_rows,

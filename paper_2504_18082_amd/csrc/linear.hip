@@ -267,19 +267,17 @@ struct XentArgs {
     const int32_t *labels, *root_ids;
     float *loss, *row_loss;
     uint16_t *d_logits_bf16;      // [max_rows][64]
-    float *part;                  // [ceil(max_rows / 32)] per-workgroup sums of row losses
-    int32_t *ticket;              // counts finished workgroups; zero between calls
+    unsigned long long *acc;      // tickets and the fixed-point sum of the workgroups' loss shares; zero between calls
 };
 
 // XENT == true (one column tile: at most 64 classes; no ReLU, no bf16 copy): a workgroup holds whole rows of
 // logits after the reduction, so the softmax cross-entropy of its rows, their gradient and its share of the mean
-// loss are taken right there; the workgroup that finishes last adds the shares up in index order.
+// loss are taken right there; the shares meet in one device-side accumulator.
 template <bool XENT>
 __global__ __launch_bounds__(256) void gemm_nt_small_kernel(NtArgs a, XentArgs x)
 {
     __shared__ __attribute__((aligned(16))) float red[4][32][SMALL_ROW];
     __shared__ float wg_loss[32];
-    __shared__ int last_flag;
     const int M = min(a.hdr[CR_HDR_N_DST], a.max_rows);
     const int m0 = (int)blockIdx.y * 32, n0 = (int)blockIdx.x * 64;
     if (XENT && M <= 0) {
@@ -290,6 +288,9 @@ __global__ __launch_bounds__(256) void gemm_nt_small_kernel(NtArgs a, XentArgs x
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, lr = lane & 31;
     const int nk = a.K / 16;
+    // the label of the row this thread will finish: requested now (two dependent loads), used after the product
+    int label = 0;
+    if constexpr (XENT) label = x.labels[x.root_ids[min(m0 + (tid >> 3), M - 1)]];
     const int64_t arow = (int64_t)min(m0 + lr, M - 1) * a.lda + 8 * half;
     const uint16_t *b0 = a.B + (int64_t)(n0 + lr) * a.K + 8 * half;
     const uint16_t *b1 = b0 + (int64_t)32 * a.K;
@@ -375,7 +376,6 @@ __global__ __launch_bounds__(256) void gemm_nt_small_kernel(NtArgs a, XentArgs x
         }
 #pragma unroll
         for (int off = 1; off < 8; off <<= 1) den += __shfl_xor(den, off);
-        const int label = x.labels[x.root_ids[m]];
         const float inv_n = 1.0f / (float)M;
         u32x4v dq;
 #pragma unroll
@@ -401,23 +401,20 @@ __global__ __launch_bounds__(256) void gemm_nt_small_kernel(NtArgs a, XentArgs x
 #pragma unroll
             for (int off = 32; off >= 1; off >>= 1) t += __shfl_xor(t, off);
             if (tid == 0) {
-                // the share is published before the ticket is taken; the last workgroup reads every share past its L1
-                __hip_atomic_store(&x.part[blockIdx.y], t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-                const int done = __hip_atomic_fetch_add(x.ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                last_flag = done == (M + 31) / 32 - 1;
-            }
-        }
-        __syncthreads();
-        if (last_flag && tid < 64) {
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-            const int nb = (M + 31) / 32;           // at most 64: this kernel takes blocks of at most 2048 rows
-            float t = tid < nb ? __hip_atomic_load(&x.part[tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.f;
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) t += __shfl_xor(t, off);
-            if (tid == 0) {
-                x.loss[0] = t / (float)M;
-                __hip_atomic_store(x.ticket, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                // One 64-bit atomic per workgroup carries its share of the loss (fixed point, 2^-20, bits 0..39: integer
+                // sums do not depend on the order of arrival, so the mean is reproducible), a ticket (bits 40..55) and a
+                // mark for a share that is not finite (bits 56..62).  The workgroup whose ticket is the last one has the
+                // whole sum in hand.  No fence, no access to another workgroup's data: the atomic is performed at the
+                // memory side.
+                const bool finite = t == t && fabsf(t) <= 8192.0f;       // 32 rows of at most ~100 each
+                const unsigned long long share = finite ? (unsigned long long)(fmaxf(t, 0.f) * 1048576.0f + 0.5f) : 0ull;
+                const unsigned long long add = share | (1ull << 40) | (finite ? 0ull : 1ull << 56);
+                const unsigned long long after = __hip_atomic_fetch_add(x.acc, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + add;
+                if ((int)((after >> 40) & 0xFFFFull) == (M + 31) / 32) {
+                    const float mean = (float)((double)(after & ((1ull << 40) - 1ull)) * (1.0 / 1048576.0) / (double)M);
+                    x.loss[0] = (after >> 56) ? __builtin_nanf("") : mean;
+                    __hip_atomic_store(x.acc, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
             }
         }
     }
@@ -833,7 +830,7 @@ extern "C" cr_status cr_sage_linear_fwd_xent(const cr_sage_layer *layer, const i
     if (N_pad == 64 && max_rows <= NT_SMALL_ROWS) {
         XentArgs x;
         x.n_classes = n_classes; x.labels = labels; x.root_ids = root_ids; x.loss = loss; x.row_loss = row_loss;
-        x.d_logits_bf16 = d_logits_bf16; x.ticket = static_cast<int32_t *>(scratch); x.part = reinterpret_cast<float *>(scratch) + 4;
+        x.d_logits_bf16 = d_logits_bf16; x.acc = static_cast<unsigned long long *>(scratch);
         hipLaunchKernelGGL(gemm_nt_small_kernel<true>, dim3(1, (unsigned)ceil_div(max_rows, 32)), dim3(256), 0, s, a, x);
     } else {
         launch_nt(a, s);

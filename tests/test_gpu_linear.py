@@ -239,7 +239,7 @@ def test_linear_fwd_with_loss(torch_mod, M, F_in, Cn, cap_extra):
         assert_close(gd[:rows, :Cn], want_d[:, :Cn], 2.0 ** -8, "d_logits bf16")
         assert np.all(gd[:rows, Cn:] == 0)
         assert np.all(db.cpu().numpy()[rows:].view(np.uint16) == 0x7FC0)
-        assert np.all(scratch.cpu().numpy()[:4] == 0)            # the ticket is back at zero
+        assert np.all(scratch.cpu().numpy()[:8] == 0)            # the accumulator is back at zero
 
 
 @pytest.mark.parametrize("n,Cn", [(256, 10), (1024, 40), (1000, 172), (1, 7), (3, 1)])
