@@ -169,7 +169,7 @@ class Trainer:
         self.loss = torch.zeros(1, dtype=torch.float32, device=device)
         self.row_loss = torch.zeros(self.B, dtype=torch.float32, device=device)
         self.xent_scratch = torch.zeros(B.CR_XENT_SCRATCH_BYTES, dtype=torch.uint8, device=device)
-        self.fused_top_loss = fused_top_loss and model == "sage"
+        self.fused_top_loss = fused_top_loss and model in ("sage", "gcn")
         self.agg[0] = self.agg0_bufs[0]
         self.gather0_events = []          # (start, stop) pairs around the layer-0 gather when timing is on
         self.time_gather0 = False
@@ -287,7 +287,7 @@ class Trainer:
             self.self0, self.agg[0] = self.self0_bufs[buf], self.agg0_bufs[buf]
         L, blocks, layers = self.L, self.blocks, self.layers
         if self.model == "gcn":
-            return self._forward_batch_gcn(g)
+            return self._forward_batch_gcn(g, with_loss)
         if self.model == "gat":
             return self._forward_batch_gat(g)
         for l in range(L):
@@ -313,7 +313,7 @@ class Trainer:
                                  self.out[l], self.out_b[l])
         return False
 
-    def _forward_batch_gcn(self, g: int):
+    def _forward_batch_gcn(self, g: int, with_loss: bool = False):
         """GCN layers: normalised aggregation over the block (the destination's own row included), one-operand layer."""
         L, blocks, layers = self.L, self.blocks, self.layers
         self.wait_weights()
@@ -335,7 +335,12 @@ class Trainer:
                 B.cr_gcn_aggregate_fwd(blk, g, self.gcn_norm, self.blk_norm[l], self.out_b[l - 1], B.CR_BF16, prev.N_pad, prev.F_out,
                                        False, None, self.agg[l], prev.N_pad)
                 ld_in = prev.N_pad
+            if with_loss and l == L - 1 and self.fused_top_loss:
+                B.cr_sage_linear_fwd_xent(lay, blk.hdr_ptr(g), blk.cap_dst, None, self.agg[l], ld_in, self.out[l], self.cfg.n_classes,
+                                          self.labels, blk.src_ids_ptr(g), self.loss, self.row_loss, self.dz[l], self.xent_scratch)
+                return True
             B.cr_sage_linear_fwd(lay, blk.hdr_ptr(g), blk.cap_dst, None, self.agg[l], ld_in, l < L - 1, self.out[l], self.out_b[l])
+        return False
 
     def _backward_batch_gcn(self, g: int, dW_out, db_out):
         L, blocks, layers = self.L, self.blocks, self.layers
