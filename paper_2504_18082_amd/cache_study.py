@@ -52,7 +52,7 @@ def main(argv=None):
     ap.add_argument("--modes", nargs="+", default=["host", "host+cache"], choices=["hbm", "host", "host+cache"])
     ap.add_argument("--steps", type=int, default=60)
     ap.add_argument("--warmup", type=int, default=60, help="untimed steps that also warm the cache")
-    ap.add_argument("--group", type=int, default=16)
+    ap.add_argument("--group", type=int, default=32)
     ap.add_argument("--seed", type=int, default=0)
     args = ap.parse_args(argv)
 

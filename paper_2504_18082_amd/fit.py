@@ -36,7 +36,7 @@ def main(argv=None):
     ap.add_argument("--lr-patience", type=int, default=3)
     ap.add_argument("--lr", type=float, default=0.1)
     ap.add_argument("--weight-decay", type=float, default=5e-4)
-    ap.add_argument("--group", type=int, default=16)
+    ap.add_argument("--group", type=int, default=32)
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--model", default="sage", choices=["sage", "gcn", "gat"])
     args = ap.parse_args(argv)

@@ -6,7 +6,7 @@ grows or shrinks: the same graph recipe at several node counts and feature width
 
     python -m paper_2504_18082_amd.sensitivity --workload arxiv --scales 0.25 1 4 16 --widths 128
 
-Prints one JSON line per (scale, width): table size, ms per step and per layer-0 gather for the fully random
+Prints one JSON line per (scale, width): table size, ms per step and layer-0 gather time per mini-batch for the fully random
 baseline and for two COMM-RAND settings, and the speed-ups over the baseline."""
 from __future__ import annotations
 
@@ -37,7 +37,8 @@ def time_setting(tr, policy, mix, p, steps, warmup, epoch0):
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     tr.time_gather0 = False
-    gather_ms = sum(a.elapsed_time(b) for a, b in tr.gather0_events) / max(1, len(tr.gather0_events))
+    # per mini-batch: a launch covers one batch or, for the grouped layer-0 gather, a whole sampled group
+    gather_ms = sum(a.elapsed_time(b) for a, b in tr.gather0_events) / max(1, steps)
     # input nodes per batch (the rows of X a batch touches), over the first groups of one more epoch
     n_in, _ = tr.input_node_stats(policy, mix, p, epoch0 + 2000)
     return dt * 1e3 / steps, gather_ms, n_in
@@ -50,7 +51,7 @@ def main(argv=None):
     ap.add_argument("--widths", type=int, nargs="+", default=[0], help="feature widths (0 = the workload's own)")
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=40)
-    ap.add_argument("--group", type=int, default=16)
+    ap.add_argument("--group", type=int, default=32)
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--model", default="sage", choices=["sage", "gcn", "gat"])
     ap.add_argument("--settings", nargs="+", default=DEFAULT_SETTINGS)
