@@ -231,6 +231,31 @@ def test_fused_layer_backward_changes_nothing(tiny_workload, arxiv_workload, whi
         assert np.array_equal(a, b)
 
 
+@pytest.mark.parametrize("hidden", [32, 320, 600])
+def test_fused_layer_backward_other_widths(tiny_workload, hidden):
+    """The same comparison at hidden widths that take the other instantiations of the backward gather (16, 64 and
+    2 x 64 lanes per row), three layers deep."""
+    import copy
+    import torch
+    from paper_2504_18082_amd.trainer import Trainer
+    w = copy.copy(tiny_workload)
+    w.cfg = copy.deepcopy(tiny_workload.cfg)
+    w.cfg.hidden, w.cfg.fanouts = hidden, [10, 5, 5]
+    out = []
+    for fused in (False, True):
+        tr = Trainer(w, group_size=2, lr=0.05, seed=0, fused_layer_bwd=fused)
+        assert tr.L == 3
+        tr.build_batches(oracle.RAND, 1, 1)
+        tr.sample_group(0, 2, 0.5, 1)
+        for g in range(2):
+            print(f"fused={fused} hidden={hidden} batch={g}", flush=True)
+            tr.train_batch(g)
+        torch.cuda.synchronize()
+        out.append([l.W.cpu().numpy().copy() for l in tr.layers] + [x.cpu().numpy().copy() for x in tr.dz[:-1]])
+    for a, b in zip(*out):
+        assert np.array_equal(a, b)
+
+
 def test_fused_top_layer_loss_changes_only_rounding(tiny_workload):
     """cr_sage_linear_fwd_xent (the layer next to the loss and the loss in one launch) against the separate calls: the first
     step's logits are bit-identical, its loss agrees to float rounding, and the weights after some steps stay within
