@@ -311,7 +311,7 @@ __device__ __forceinline__ void gather_mean_bwd_body(
     uint16_t *__restrict__ d_src_bf16, int64_t ld_bf16, const GcnFwd &gcn)
 {
     constexpr int VEC = Vec16<T>::N;
-    constexpr int U = NCHUNK == 1 ? 8 : (NCHUNK <= 3 ? 4 : 2);
+    constexpr int U = NCHUNK == 1 ? 4 : 2;       // slots per pass after the first (few rows get that far)
     constexpr int GPB = 256 / LPR;
     const int n_dst = hdr[CR_HDR_N_DST], n_src = hdr[CR_HDR_N_SRC];
     if (n_src <= 0) return;
@@ -528,6 +528,10 @@ __global__ __launch_bounds__(256) void gather_bwd_sgd_kernel(
     }
 }
 
+// six workgroups per compute unit: what the backward kernels' registers allow (the rows in flight are what hides
+// the chain of dependent loads behind a source row)
+constexpr int64_t BWD_MAX_BLOCKS = 1536;
+
 template <int LPR, int NCHUNK>
 static void launch_bwd_sgd(const SgdArgs &sgd, unsigned sgd_blocks, int cap_src, const int32_t *hdr, const int32_t *indptr,
                            const int32_t *t_indptr, const int32_t *t_indices, const uint16_t *d_agg, const uint16_t *d_self,
@@ -535,7 +539,7 @@ static void launch_bwd_sgd(const SgdArgs &sgd, unsigned sgd_blocks, int cap_src,
                            int64_t ld_bf16, hipStream_t st)
 {
     int64_t grid = round_up(ceil_div(cap_src, 256 / LPR), 8);
-    if (grid > 1024) grid = 1024;
+    if (grid > BWD_MAX_BLOCKS) grid = BWD_MAX_BLOCKS;
     hipLaunchKernelGGL((gather_bwd_sgd_kernel<LPR, NCHUNK>), dim3((unsigned)grid + sgd_blocks), dim3(256), 0, st, (uint32_t)grid, sgd, hdr,
                        indptr, t_indptr, t_indices, d_agg, d_self, ld_in, F, relu_out, relu_is_bf16, ld_relu, d_src_bf16, ld_bf16);
 }
@@ -547,7 +551,7 @@ static void launch_bwd(int cap_src, const int32_t *hdr, const int32_t *indptr, c
                        int64_t ld_bf16, hipStream_t st, const GcnFwd *gcn = nullptr)
 {
     int64_t grid = round_up(ceil_div(cap_src, 256 / LPR), 8);
-    if (grid > 1024) grid = 1024;
+    if (grid > BWD_MAX_BLOCKS) grid = BWD_MAX_BLOCKS;
     if (gcn)
         hipLaunchKernelGGL((gather_mean_bwd_kernel<T, LPR, NCHUNK, true>), dim3((unsigned)grid), dim3(256), 0, st, hdr, indptr, t_indptr,
                            t_indices, static_cast<const T *>(d_agg), static_cast<const T *>(d_self), ld_in, F, relu_out, relu_is_bf16,
