@@ -164,6 +164,50 @@ def test_gather_bwd(torch_mod, tiny_workload, F):
     assert_close(d_src.cpu().numpy(), oracle.gather_mean_bwd(blk, d_agg[:, :F]), RTOL, "d_src no self")
 
 
+@pytest.mark.parametrize("F,in_bf16", [(64, False), (256, True), (600, True)])
+def test_gather_bwd_hub_sources(torch_mod, F, in_bf16):
+    """A hand-made block in which a few source rows are used by very many destinations (segments of the transposed
+    block far longer than a pass, and longer than the lanes of a row group) beside sources used once or not at all."""
+    torch = torch_mod
+    from paper_2504_18082_amd import binding as B
+    rng = np.random.default_rng(F)
+    n_dst, n_src, fanout = 500, 3000, 6
+    hubs = np.array([0, 1, 777], dtype=np.int32)           # two hubs are destinations themselves, one is not
+    rows = []
+    for v in range(n_dst):
+        nb = set(rng.choice(np.arange(2, n_src - 1), size=int(rng.integers(0, fanout - 2)), replace=False).tolist())
+        if v % 2 == 0: nb.add(0)
+        if v % 3 == 0: nb.add(1)
+        if v % 5 != 0: nb.add(777)
+        rows.append(np.array(sorted(nb), dtype=np.int32))
+    indptr = np.zeros(n_dst + 1, dtype=np.int32)
+    indptr[1:] = np.cumsum([len(r) for r in rows])
+    indices = np.concatenate(rows).astype(np.int32)
+    blk = oracle.transpose_block(oracle.Block(n_dst, np.arange(n_src, dtype=np.int32), indptr, indices, np.zeros_like(indices)))
+    uses = np.diff(blk.t_indptr)
+    assert uses[0] == 250 and uses[777] == 400 and uses[n_src - 1] == 0
+    print(f"case bwd hubs F={F} bf16={in_bf16} nnz={blk.nnz}", flush=True)
+    ld_in = (F + 31) // 32 * 32
+    both = np.zeros((n_dst, 2 * ld_in), dtype=np.float32)
+    both[:, :F] = rng.standard_normal((n_dst, F), dtype=np.float32)
+    both[:, ld_in:ld_in + F] = rng.standard_normal((n_dst, F), dtype=np.float32)
+    if in_bf16:
+        both = synth.bf16_bits_to_float(synth.float_to_bf16_bits(both))
+    want = oracle.gather_mean_bwd(blk, both[:, ld_in:ld_in + F], both[:, :F])
+    bs = B.BlockSet.from_host(blk, fanout)
+    d_src = torch.full((bs.cap_src, F), np.nan, dtype=torch.float32, device="cuda")
+    if in_bf16:
+        dev = torch.from_numpy(synth.float_to_bf16_bits(both).view(np.int16)).cuda()
+        B.cr_gather_aggregate_bwd(bs, 0, C.c_void_p(dev.data_ptr() + 2 * ld_in), dev, 2 * ld_in, F, d_src=d_src, in_dtype=B.CR_BF16)
+    else:
+        dev = torch.from_numpy(both).cuda()
+        B.cr_gather_aggregate_bwd(bs, 0, C.c_void_p(dev.data_ptr() + 4 * ld_in), dev, 2 * ld_in, F, d_src=d_src)
+    torch.cuda.synchronize()
+    got = d_src.cpu().numpy()
+    assert_close(got[:n_src], want, RTOL, "d_src with hub sources")
+    assert np.all(got[n_src - 1] == 0)                      # a source nobody uses and that is no destination
+
+
 @pytest.mark.parametrize("F,dtype,gcn", [(128, "f32", False), (602, "f32", False), (256, "bf16", False), (100, "f32", True)])
 def test_gather_fwd_with_a_processing_order(torch_mod, tiny_workload, F, dtype, gcn):
     """A block set that carries a row order (any permutation of the destination rows) gives bit-identical outputs:
