@@ -88,6 +88,7 @@ struct GcnFwd {
 struct GroupInfo {
     int32_t n_batches, cap_dst, cap_src, cap_nnz;
     int64_t out_stride;       // output rows per batch
+    int32_t out_cols;         // bf16 output columns this launch writes (payload + zero padding); 0 = the whole row stride
 };
 
 template <typename T, int LPR, int NCHUNK, bool GCN = false, bool GROUPED = false>
@@ -97,7 +98,7 @@ __global__ __launch_bounds__(256) void gather_mean_fwd_kernel(
     const int32_t *__restrict__ self_map, const T *__restrict__ table, int64_t ld, int F,
     float *__restrict__ agg, uint16_t *__restrict__ agg_bf16, uint16_t *__restrict__ self_bf16, int64_t ld_bf16,
     GcnFwd gcn = GcnFwd{nullptr, nullptr, nullptr, nullptr}, const int32_t *__restrict__ order = nullptr,
-    GroupInfo grp = GroupInfo{0, 0, 0, 0, 0})
+    GroupInfo grp = GroupInfo{0, 0, 0, 0, 0, 0})
 {
     constexpr int VEC = Vec16<T>::N;
     constexpr int U = NCHUNK == 1 ? 8 : (NCHUNK <= 3 ? 4 : 2);   // independent row loads in flight per lane
@@ -215,6 +216,7 @@ __global__ __launch_bounds__(256) void gather_mean_fwd_kernel(
 
         const int deg = e0 - s0;
         const float fdeg = (float)(deg > 0 ? deg : 1);
+        const int64_t wcols = (GROUPED && grp.out_cols) ? (int64_t)grp.out_cols : ld_bf16;     // a column panel writes its own columns only
 #pragma unroll
         for (int c = 0; c < NCHUNK; ++c) {
             const int col = (c * LPR + gl) * VEC;
@@ -241,7 +243,7 @@ __global__ __launch_bounds__(256) void gather_mean_fwd_kernel(
                         if (col + i < F) o[i] = acc[c][i];
                 }
             }
-            if (agg_bf16 && col < ld_bf16) store_bf16_row<VEC>(agg_bf16 + (int64_t)out0 * ld_bf16 + col, acc[c], col, F);
+            if (agg_bf16 && col < wcols) store_bf16_row<VEC>(agg_bf16 + (int64_t)out0 * ld_bf16 + col, acc[c], col, F);
         }
 
         if (self_bf16) {
@@ -249,7 +251,7 @@ __global__ __launch_bounds__(256) void gather_mean_fwd_kernel(
 #pragma unroll
             for (int c = 0; c < NCHUNK; ++c) {
                 const int col = (c * LPR + gl) * VEC;
-                if (col < ld_bf16) {
+                if (col < wcols) {
                     float v[VEC];
 #pragma unroll
                     for (int i = 0; i < VEC; ++i) v[i] = 0.f;
@@ -282,14 +284,17 @@ static void launch_fwd(int cap_dst, const int32_t *hdr, const int32_t *indptr, c
                            GcnFwd{nullptr, nullptr, nullptr, nullptr}, order);
 }
 
+constexpr int GROUP_PANEL_BYTES = 512;             // column panel of the grouped gather
+constexpr int GROUP_PANEL_MIN_ROW_BYTES = 1024;    // rows wider than this are gathered in panels
+
 template <typename T, int LPR, int NCHUNK>
 static void launch_fwd_group(const cr_block_set *b, const void *table, int64_t ld, int F, uint16_t *agg_bf16, uint16_t *self_bf16,
-                             int64_t out_stride, int64_t ld_bf16, hipStream_t st)
+                             int64_t out_stride, int64_t ld_bf16, hipStream_t st, int out_cols = 0)
 {
     constexpr int GPB = 256 / LPR;
     int64_t grid = round_up(ceil_div((int64_t)b->n_batches * b->cap_dst, GPB), 8);
     if (grid > 1024) grid = 1024;
-    const GroupInfo gi{b->n_batches, b->cap_dst, b->cap_src, b->cap_nnz, out_stride};
+    const GroupInfo gi{b->n_batches, b->cap_dst, b->cap_src, b->cap_nnz, out_stride, out_cols};
     hipLaunchKernelGGL((gather_mean_fwd_kernel<T, LPR, NCHUNK, false, true>), dim3((unsigned)grid), dim3(256), 0, st, b->hdr, b->indptr,
                        b->gather_ids, (const int32_t *)nullptr, b->src_ids, static_cast<const T *>(table), ld, F, (float *)nullptr, agg_bf16,
                        self_bf16, ld_bf16, GcnFwd{nullptr, nullptr, nullptr, nullptr}, b->group_order, gi);
@@ -716,6 +721,24 @@ extern "C" cr_status cr_gather_aggregate_fwd_group(const cr_block_set *blocks, c
     CR_REQUIRE(batch_stride_rows * blocks->n_batches < 0x7FFFFFFF, CR_ERR_UNSUPPORTED, "output rows do not fit 31 bits");
     if (dry_run()) return CR_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    // Rows wider than 1 KB go in column panels of 512 bytes, one sweep over the group's rows per panel: with the rows in
+    // community order a sweep then keeps one community's panel (nodes x 512 B) in an XCD's L2 where whole rows of a
+    // large community do not fit (233 K-node reddit-like graph: 4660 nodes x 2408 B = 11 MB per community, 2.4 MB per
+    // panel).  The row pointers and ids are read once per panel, a small price beside the rows themselves.
+    const int elem = dtype == CR_F32 ? 4 : 2;
+    if ((int64_t)F * elem > GROUP_PANEL_MIN_ROW_BYTES) {
+        const int pw = GROUP_PANEL_BYTES / elem;                  // panel width in elements
+        for (int c0 = 0; c0 < F; c0 += pw) {
+            const int Fk = F - c0 < pw ? F - c0 : pw;
+            const bool last = c0 + pw >= F;
+            const int out_cols = last ? (int)(ld_bf16 - c0) : pw;
+            const void *tab = static_cast<const char *>(H_src) + (int64_t)c0 * elem;
+            if (dtype == CR_F32) launch_fwd_group<float, 32, 1>(blocks, tab, ld_src, Fk, agg_bf16 + c0, self_bf16 + c0, batch_stride_rows, ld_bf16, s, out_cols);
+            else launch_fwd_group<uint16_t, 32, 1>(blocks, tab, ld_src, Fk, agg_bf16 + c0, self_bf16 + c0, batch_stride_rows, ld_bf16, s, out_cols);
+        }
+        CR_LAUNCH_CHECK();
+        return CR_OK;
+    }
 #define CR_FWDG(T, LPR, NC) launch_fwd_group<T, LPR, NC>(blocks, H_src, ld_src, F, agg_bf16, self_bf16, batch_stride_rows, ld_bf16, s)
     if (dtype == CR_F32) {
         if (F <= 64) CR_FWDG(float, 16, 1);

@@ -256,6 +256,38 @@ def test_fused_layer_backward_other_widths(tiny_workload, hidden):
         assert np.array_equal(a, b)
 
 
+@pytest.mark.parametrize("n_feat,dtype", [(602, "f32"), (300, "f32"), (776, "bf16")])
+def test_grouped_gather_of_wide_rows(n_feat, dtype):
+    """Feature rows wider than 1 KB are gathered in column panels (one sweep over the group per panel): same bits as the
+    per-batch gather, padding columns zero, nothing written past a batch's rows."""
+    import copy
+    import torch
+    from paper_2504_18082_amd import binding as B
+    from paper_2504_18082_amd.trainer import Trainer
+    cfg = copy.deepcopy(synth.CONFIGS["tiny"])
+    cfg.n_feat, cfg.feat_dtype, cfg.n_nodes, cfg.n_edges_undirected = n_feat, dtype, 4000, 20000
+    w = synth.make_workload(cfg, seed=1)
+    tr = Trainer(w, group_size=3, seed=0, order_rows=True)
+    assert tr.group_gather
+    tr.build_batches(oracle.RAND, 1, 2)
+    tr.agg0_all[0].fill_(0x7FC0)
+    tr.self0_all[0].fill_(0x7FC0)
+    tr.sample_group(0, 3, 0.5, 2)
+    torch.cuda.synchronize()
+    blk, lay = tr.blocks[0], tr.layers[0]
+    hdr = tr.headers()[0]
+    agg = torch.zeros((blk.cap_dst, lay.F_pad), dtype=torch.int16, device="cuda")
+    slf = torch.zeros_like(agg)
+    for g in range(3):
+        n = int(hdr[g][0])
+        print(f"wide rows n_feat={n_feat} {dtype} batch={g} n_dst={n}", flush=True)
+        B.cr_gather_aggregate_fwd(blk, g, tr.table_ptr, tr.feat_dtype, tr.ld_table, n_feat, True, None, agg, slf, lay.F_pad)
+        torch.cuda.synchronize()
+        assert torch.equal(tr.agg0_all[0][g, :n], agg[:n]) and torch.equal(tr.self0_all[0][g, :n], slf[:n])
+        assert bool((tr.agg0_all[0][g, :n, n_feat:] == 0).all()) and bool((tr.self0_all[0][g, :n, n_feat:] == 0).all())
+        assert bool((tr.agg0_all[0][g, n:] == 0x7FC0).all()) and bool((tr.self0_all[0][g, n:] == 0x7FC0).all())
+
+
 def test_fused_top_layer_loss_changes_only_rounding(tiny_workload):
     """cr_sage_linear_fwd_xent (the layer next to the loss and the loss in one launch) against the separate calls: the first
     step's logits are bit-identical, its loss agrees to float rounding, and the weights after some steps stay within
