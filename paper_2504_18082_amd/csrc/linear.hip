@@ -147,25 +147,11 @@ __device__ __forceinline__ void gemm_nt_body(const NtArgs &a, uint32_t bid, uint
     NtState st{a.A0, a.A1, a.K0, a.K, ga0, ga1, gb, kc, a_row0, a_row1, tid >> 2, wave * 32 + lr, lr, half};
     int s0 = 0;
     for (; s0 + CH <= nsteps; s0 += CH) {
-        const NtFetch<NB> f0 = nt_fetch<NB>(st, s0 + 0), f1 = nt_fetch<NB>(st, s0 + 1), f2 = nt_fetch<NB>(st, s0 + 2),
-                          f3 = nt_fetch<NB>(st, s0 + 3);
-        if constexpr (CH == 8) {
-            const NtFetch<NB> f4 = nt_fetch<NB>(st, s0 + 4), f5 = nt_fetch<NB>(st, s0 + 5), f6 = nt_fetch<NB>(st, s0 + 6),
-                              f7 = nt_fetch<NB>(st, s0 + 7);
-            nt_step<NTILES>(st, f0, buf, As, Bs, acc);
-            nt_step<NTILES>(st, f1, buf, As, Bs, acc);
-            nt_step<NTILES>(st, f2, buf, As, Bs, acc);
-            nt_step<NTILES>(st, f3, buf, As, Bs, acc);
-            nt_step<NTILES>(st, f4, buf, As, Bs, acc);
-            nt_step<NTILES>(st, f5, buf, As, Bs, acc);
-            nt_step<NTILES>(st, f6, buf, As, Bs, acc);
-            nt_step<NTILES>(st, f7, buf, As, Bs, acc);
-        } else {
-            nt_step<NTILES>(st, f0, buf, As, Bs, acc);
-            nt_step<NTILES>(st, f1, buf, As, Bs, acc);
-            nt_step<NTILES>(st, f2, buf, As, Bs, acc);
-            nt_step<NTILES>(st, f3, buf, As, Bs, acc);
-        }
+        NtFetch<NB> f[CH];
+#pragma unroll
+        for (int i = 0; i < CH; ++i) f[i] = nt_fetch<NB>(st, s0 + i);
+#pragma unroll
+        for (int i = 0; i < CH; ++i) nt_step<NTILES>(st, f[i], buf, As, Bs, acc);
     }
     while (s0 < nsteps) {         // the remaining steps (K not a multiple of 32 * CH), again fetched together: up to three at a time
         const int rem = nsteps - s0;
@@ -241,9 +227,11 @@ __device__ __forceinline__ void gemm_nt_body(const NtArgs &a, uint32_t bid, uint
 }
 
 // Register budget: up to four waves per SIMD.  Four K steps of prefetch at this occupancy measured faster
-// than eight steps at two waves per SIMD.
+// than eight steps at two waves per SIMD on the products that fill the chip; a product with few workgroups and a
+// long K loop (the reddit-like input layer: 88 row tiles, K = 1216) gains nothing from occupancy and takes the
+// eight-step instantiation, which halves the round trips of its K loop.
 template <int NTILES, int CH>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) void gemm_nt_kernel(NtArgs a)
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(CH == 4 ? 3 : 1, CH == 4 ? 4 : 2))) void gemm_nt_kernel(NtArgs a)
 {
     __shared__ __attribute__((aligned(16))) uint16_t As[2][128][LDS_ROW];
     __shared__ __attribute__((aligned(16))) uint16_t Bs[2][NTILES * 32][LDS_ROW];
@@ -425,6 +413,9 @@ constexpr int NT_SMALL_ROWS = 2048;    // blocks of at most this many rows (by c
 // Wider tiles (NTILES = 4, 8) read the activations fewer times but measured slower on MI355X for the
 // layer widths of this path (K = 256..512, N = 256): these products are bound by memory round trips
 // and occupancy, not by the matrix cores, so the smallest tile at the highest occupancy wins.
+constexpr int64_t NT_DEEP_MAX_BLOCKS = 512;   // at most two workgroups per compute unit and ...
+constexpr int NT_DEEP_MIN_K = 768;            // ... a K loop of at least 24 steps: eight steps of prefetch
+
 static void launch_nt(const NtArgs &a, hipStream_t s)
 {
     // xcd_compact needs the grid rounded up to a multiple of eight blocks
@@ -434,7 +425,8 @@ static void launch_nt(const NtArgs &a, hipStream_t s)
         return;
     }
     const dim3 grid(ncol, (unsigned)ceil_div(a.max_rows, 128) + (7 + ncol - 1) / ncol);
-    hipLaunchKernelGGL((gemm_nt_kernel<2, 4>), grid, dim3(256), 0, s, a);
+    if ((int64_t)grid.x * grid.y <= NT_DEEP_MAX_BLOCKS && a.K >= NT_DEEP_MIN_K) hipLaunchKernelGGL((gemm_nt_kernel<2, 8>), grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((gemm_nt_kernel<2, 4>), grid, dim3(256), 0, s, a);
 }
 
 // ------------------------------------------------------------------------------------------------

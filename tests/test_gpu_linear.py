@@ -39,7 +39,8 @@ def hdr_for(torch, n_rows):
 
 @pytest.mark.parametrize("M,F_in,F_out,relu", [(300, 64, 64, True), (1000, 100, 256, True), (517, 256, 40, False),
                                                (130, 602, 256, True), (64, 32, 10, False), (1, 64, 64, True),
-                                               (33001, 64, 256, True), (66010, 100, 128, False)])     # the last two: several workgroup rounds
+                                               (33001, 64, 256, True), (66010, 100, 128, False),     # several workgroup rounds
+                                               (5000, 400, 256, True)])                             # few workgroups, long K loop
 def test_linear_fwd(torch_mod, M, F_in, F_out, relu):
     torch = torch_mod
     from paper_2504_18082_amd import binding as B
