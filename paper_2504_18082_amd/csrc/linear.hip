@@ -722,7 +722,7 @@ __global__ __launch_bounds__(256) void count_correct_kernel(const int32_t *hdr, 
 static void split_plan(int F_pad, int N_pad, int n_op, int max_rows, int &rows_per_split, int &n_splits)
 {
     const int tiles = (int)(n_op * ceil_div(F_pad, 128) * ceil_div(N_pad, 128));
-    int target = 768 / tiles;
+    int target = 512 / tiles;        // two workgroups of this kernel are resident per compute unit: one round of workgroups
     if (target < 1) target = 1;
     if (target > 128) target = 128;
     int rows = (int)round_up(ceil_div(max_rows, target), 96);
