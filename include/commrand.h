@@ -282,6 +282,15 @@ cr_status cr_gcn_aggregate_fwd(const cr_block_set *blocks, int32_t g, const floa
                                const void *H_src, int32_t dtype, int64_t ld_src, int32_t F, int32_t indirect,
                                float *agg, uint16_t *agg_bf16, int64_t ld_bf16, void *stream);
 
+/* cr_gcn_aggregate_fwd for every batch of the group in one launch (input-side block, indirect addressing through
+ * blocks->gather_ids, bf16 output only), walking blocks->group_order like cr_gather_aggregate_fwd_group; rows wider than
+ * 1 KB go in column panels there as here.  The destination scales and self weights are taken from `norm` directly, so
+ * no cr_gcn_block_norm is needed for this block.  Same bits as the per-batch call.
+ *   agg_bf16 : device bf16 [n_batches][batch_stride_rows][ld_bf16] */
+cr_status cr_gcn_aggregate_fwd_group(const cr_block_set *blocks, const float *norm, const void *H_src, int32_t dtype,
+                                     int64_t ld_src, int32_t F, uint16_t *agg_bf16, int64_t batch_stride_rows,
+                                     int64_t ld_bf16, void *stream);
+
 /* Transpose of cr_gcn_aggregate_fwd (dense addressing): gradient with respect to the source rows, atomic-free over the
  * transposed block.  d_out: device float or bf16 (in_dtype) [cap_dst][ld_in]; other arguments as
  * cr_gather_aggregate_bwd. */

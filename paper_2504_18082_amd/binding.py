@@ -31,7 +31,7 @@ EXPORTS = [
     "cr_build_batches_workspace_bytes", "cr_build_batches",
     "cr_graph_edge_classes", "cr_block_capacities", "cr_sample_blocks_workspace_bytes", "cr_sample_blocks",
     "cr_gather_aggregate_fwd", "cr_gather_aggregate_fwd_group", "cr_gather_aggregate_bwd",
-    "cr_graph_gcn_norm", "cr_gcn_block_norm", "cr_gcn_aggregate_fwd", "cr_gcn_aggregate_bwd",
+    "cr_graph_gcn_norm", "cr_gcn_block_norm", "cr_gcn_aggregate_fwd", "cr_gcn_aggregate_fwd_group", "cr_gcn_aggregate_bwd",
     "cr_sage_padded_dims", "cr_sage_refresh_shadows", "cr_sage_linear_fwd", "cr_sage_linear_fwd_xent",
     "cr_sage_linear_bwd_workspace_bytes", "cr_sage_linear_bwd", "cr_sage_linear_bwd_input", "cr_sage_layer_bwd", "cr_softmax_xent",
     "cr_count_correct",
@@ -125,6 +125,7 @@ def lib():
         L.cr_gcn_block_norm.argtypes = [C.POINTER(cr_block_set), i32, vp, vp, vp]
         L.cr_gcn_aggregate_fwd.argtypes = [C.POINTER(cr_block_set), i32, vp, vp, vp, i32, i64, i32, i32, vp, vp, i64, vp]
         L.cr_gcn_aggregate_bwd.argtypes = [C.POINTER(cr_block_set), i32, vp, vp, i32, i64, i32, vp, i32, i64, vp, vp, i64, vp]
+        L.cr_gcn_aggregate_fwd_group.argtypes = [C.POINTER(cr_block_set), vp, vp, i32, i64, i32, vp, i64, i64, vp]
         L.cr_sage_padded_dims.argtypes = [i32, i32, C.POINTER(i32), C.POINTER(i32)]
         L.cr_sage_refresh_shadows.argtypes = [C.POINTER(cr_sage_layer), vp]
         L.cr_sage_linear_fwd.argtypes = [C.POINTER(cr_sage_layer), vp, i32, vp, vp, i64, C.c_int, vp, vp, vp]
@@ -344,6 +345,13 @@ def cr_gather_aggregate_bwd(blocks: BlockSet, g, d_agg, d_self, ld_in, F, relu_o
     _check(lib().cr_gather_aggregate_bwd(C.byref(blocks.c), g, as_ptr(d_agg), as_ptr(d_self), in_dtype, ld_in, F,
                                          _ptr(relu_out), relu_dtype, ld_relu, _ptr(d_src), _ptr(d_src_bf16), ld_bf16,
                                          _stream(stream)))
+
+
+def cr_gcn_aggregate_fwd_group(blocks, norm, H_src, dtype, ld_src, F, agg_bf16, batch_stride_rows, ld_bf16, stream=None):
+    """blocks: a BlockSet or a view of its first batches (anything with a cr_block_set in .c)."""
+    as_ptr = lambda t: t if isinstance(t, C.c_void_p) else _ptr(t)
+    _check(lib().cr_gcn_aggregate_fwd_group(C.byref(blocks.c), _ptr(norm), as_ptr(H_src), dtype, ld_src, F, _ptr(agg_bf16), batch_stride_rows,
+                                            ld_bf16, _stream(stream)))
 
 
 def cr_graph_gcn_norm(graph: cr_graph, stream=None):

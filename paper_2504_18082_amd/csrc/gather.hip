@@ -134,6 +134,14 @@ __global__ __launch_bounds__(256) void gather_mean_fwd_kernel(
             const int32_t *ip = indptr + (int64_t)g * (grp.cap_dst + 1);
             const int a = ip[rr] + g * grp.cap_nnz, b = ip[rr + 1] + g * grp.cap_nnz;
             self_row = self_map[(int64_t)g * grp.cap_src + rr];
+            if constexpr (GCN) {
+                // the destination's scale and self weight, as cr_gcn_block_norm computes them, from the per-node
+                // normalisation of the graph (self_row is the destination's node id here)
+                const float isd = gcn.node_norm[2 * (int64_t)self_row], dg = gcn.node_norm[2 * (int64_t)self_row + 1];
+                const int n_s = b - a;
+                sc = n_s > 0 ? dg / (float)n_s * isd : 0.0f;
+                sf = 1.0f / (dg + 1.0f);
+            }
             rc = (int)(g * grp.out_stride + rr);
             s = r < block_end ? a : 0;
             e = r < block_end ? b : 0;
@@ -206,7 +214,7 @@ __global__ __launch_bounds__(256) void gather_mean_fwd_kernel(
                             Vec16<T>::unpack(v[u][c], f);
 #pragma unroll
                             for (int i = 0; i < VEC; ++i) {
-                                if constexpr (GCN) acc[c][i] += wu[u] * f[i];
+                                if constexpr (GCN) acc[c][i] = __builtin_fmaf(wu[u], f[i], acc[c][i]);
                                 else acc[c][i] += f[i];
                             }
                         }
@@ -226,7 +234,11 @@ __global__ __launch_bounds__(256) void gather_mean_fwd_kernel(
                 for (int i = 0; i < VEC; ++i) sv[i] = 0.f;
                 if (col < F) Vec16<T>::load(table + (int64_t)self0 * ld + col, sv);
 #pragma unroll
-                for (int i = 0; i < VEC; ++i) acc[c][i] = acc[c][i] * sc0 + sv[i] * sf0;
+                for (int i = 0; i < VEC; ++i) {
+                    // (spelled out so that every instantiation rounds the same way: the self term first, then one fused step)
+                    const float self_term = sv[i] * sf0;
+                    acc[c][i] = __builtin_fmaf(acc[c][i], sc0, self_term);
+                }
             } else {
 #pragma unroll
                 for (int i = 0; i < VEC; ++i) acc[c][i] = acc[c][i] / fdeg;
@@ -287,17 +299,17 @@ static void launch_fwd(int cap_dst, const int32_t *hdr, const int32_t *indptr, c
 constexpr int GROUP_PANEL_BYTES = 512;             // column panel of the grouped gather
 constexpr int GROUP_PANEL_MIN_ROW_BYTES = 1024;    // rows wider than this are gathered in panels
 
-template <typename T, int LPR, int NCHUNK>
+template <typename T, int LPR, int NCHUNK, bool GCN = false>
 static void launch_fwd_group(const cr_block_set *b, const void *table, int64_t ld, int F, uint16_t *agg_bf16, uint16_t *self_bf16,
-                             int64_t out_stride, int64_t ld_bf16, hipStream_t st, int out_cols = 0)
+                             int64_t out_stride, int64_t ld_bf16, hipStream_t st, int out_cols = 0, const float *node_norm = nullptr)
 {
     constexpr int GPB = 256 / LPR;
     int64_t grid = round_up(ceil_div((int64_t)b->n_batches * b->cap_dst, GPB), 8);
     if (grid > 1024) grid = 1024;
     const GroupInfo gi{b->n_batches, b->cap_dst, b->cap_src, b->cap_nnz, out_stride, out_cols};
-    hipLaunchKernelGGL((gather_mean_fwd_kernel<T, LPR, NCHUNK, false, true>), dim3((unsigned)grid), dim3(256), 0, st, b->hdr, b->indptr,
+    hipLaunchKernelGGL((gather_mean_fwd_kernel<T, LPR, NCHUNK, GCN, true>), dim3((unsigned)grid), dim3(256), 0, st, b->hdr, b->indptr,
                        b->gather_ids, (const int32_t *)nullptr, b->src_ids, static_cast<const T *>(table), ld, F, (float *)nullptr, agg_bf16,
-                       self_bf16, ld_bf16, GcnFwd{nullptr, nullptr, nullptr, nullptr}, b->group_order, gi);
+                       self_bf16, ld_bf16, GcnFwd{nullptr, node_norm, nullptr, nullptr}, b->group_order, gi);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -695,9 +707,10 @@ static void run_bwd(const cr_block_set *blocks, int32_t g, const void *d_agg, co
 #undef CR_BWD
 }
 
-extern "C" cr_status cr_gather_aggregate_fwd_group(const cr_block_set *blocks, const void *H_src, int32_t dtype, int64_t ld_src,
-                                                   int32_t F, uint16_t *agg_bf16, uint16_t *self_bf16, int64_t batch_stride_rows,
-                                                   int64_t ld_bf16, void *stream)
+// the grouped gather of GraphSAGE (GCN == false: aggregate and self rows) and of GCN (GCN == true: the normalised sum, node_norm given)
+template <bool GCN>
+static cr_status gather_group(const cr_block_set *blocks, const void *H_src, int32_t dtype, int64_t ld_src, int32_t F, uint16_t *agg_bf16,
+                              uint16_t *self_bf16, int64_t batch_stride_rows, int64_t ld_bf16, void *stream, const float *node_norm)
 {
     CR_REQUIRE(blocks != nullptr, CR_ERR_INVALID_ARG, "blocks is NULL");
     CR_REQUIRE(blocks->n_batches >= 1 && blocks->cap_dst >= 1 && blocks->cap_src >= blocks->cap_dst && blocks->cap_nnz >= 1,
@@ -712,8 +725,9 @@ extern "C" cr_status cr_gather_aggregate_fwd_group(const cr_block_set *blocks, c
     CR_REQUIRE(F >= 1 && F <= 1024, CR_ERR_INVALID_ARG, "F = %d outside 1..1024", F);
     CR_REQUIRE(ld_src >= round_up(F, vec) && ld_src % vec == 0, CR_ERR_INVALID_ARG,
                "ld_src = %lld must be a multiple of %d and >= F rounded up to it", (long long)ld_src, vec);
-    CR_REQUIRE(agg_bf16 && self_bf16 && aligned16(agg_bf16) && aligned16(self_bf16), CR_ERR_INVALID_ARG,
+    CR_REQUIRE(agg_bf16 && aligned16(agg_bf16) && aligned16(self_bf16) && (GCN || self_bf16), CR_ERR_INVALID_ARG,
                "agg_bf16 / self_bf16 must be 16-byte aligned device pointers");
+    CR_REQUIRE(!GCN || node_norm, CR_ERR_INVALID_ARG, "norm must not be NULL");
     CR_REQUIRE(ld_bf16 % 32 == 0 && ld_bf16 >= F && ld_bf16 <= round_up(F, 64), CR_ERR_INVALID_ARG,
                "ld_bf16 = %lld must be a multiple of 32 in [F, F rounded up to 64]", (long long)ld_bf16);
     CR_REQUIRE(batch_stride_rows >= blocks->cap_dst, CR_ERR_INVALID_ARG, "batch_stride_rows = %lld below cap_dst = %d",
@@ -733,13 +747,14 @@ extern "C" cr_status cr_gather_aggregate_fwd_group(const cr_block_set *blocks, c
             const bool last = c0 + pw >= F;
             const int out_cols = last ? (int)(ld_bf16 - c0) : pw;
             const void *tab = static_cast<const char *>(H_src) + (int64_t)c0 * elem;
-            if (dtype == CR_F32) launch_fwd_group<float, 32, 1>(blocks, tab, ld_src, Fk, agg_bf16 + c0, self_bf16 + c0, batch_stride_rows, ld_bf16, s, out_cols);
-            else launch_fwd_group<uint16_t, 32, 1>(blocks, tab, ld_src, Fk, agg_bf16 + c0, self_bf16 + c0, batch_stride_rows, ld_bf16, s, out_cols);
+            uint16_t *self_k = self_bf16 ? self_bf16 + c0 : nullptr;
+            if (dtype == CR_F32) launch_fwd_group<float, 32, 1, GCN>(blocks, tab, ld_src, Fk, agg_bf16 + c0, self_k, batch_stride_rows, ld_bf16, s, out_cols, node_norm);
+            else launch_fwd_group<uint16_t, 32, 1, GCN>(blocks, tab, ld_src, Fk, agg_bf16 + c0, self_k, batch_stride_rows, ld_bf16, s, out_cols, node_norm);
         }
         CR_LAUNCH_CHECK();
         return CR_OK;
     }
-#define CR_FWDG(T, LPR, NC) launch_fwd_group<T, LPR, NC>(blocks, H_src, ld_src, F, agg_bf16, self_bf16, batch_stride_rows, ld_bf16, s)
+#define CR_FWDG(T, LPR, NC) launch_fwd_group<T, LPR, NC, GCN>(blocks, H_src, ld_src, F, agg_bf16, self_bf16, batch_stride_rows, ld_bf16, s, 0, node_norm)
     if (dtype == CR_F32) {
         if (F <= 64) CR_FWDG(float, 16, 1);
         else if (F <= 128) CR_FWDG(float, 32, 1);
@@ -756,6 +771,20 @@ extern "C" cr_status cr_gather_aggregate_fwd_group(const cr_block_set *blocks, c
 #undef CR_FWDG
     CR_LAUNCH_CHECK();
     return CR_OK;
+}
+
+extern "C" cr_status cr_gather_aggregate_fwd_group(const cr_block_set *blocks, const void *H_src, int32_t dtype, int64_t ld_src,
+                                                   int32_t F, uint16_t *agg_bf16, uint16_t *self_bf16, int64_t batch_stride_rows,
+                                                   int64_t ld_bf16, void *stream)
+{
+    return gather_group<false>(blocks, H_src, dtype, ld_src, F, agg_bf16, self_bf16, batch_stride_rows, ld_bf16, stream, nullptr);
+}
+
+extern "C" cr_status cr_gcn_aggregate_fwd_group(const cr_block_set *blocks, const float *norm, const void *H_src, int32_t dtype,
+                                                int64_t ld_src, int32_t F, uint16_t *agg_bf16, int64_t batch_stride_rows,
+                                                int64_t ld_bf16, void *stream)
+{
+    return gather_group<true>(blocks, H_src, dtype, ld_src, F, agg_bf16, nullptr, batch_stride_rows, ld_bf16, stream, norm);
 }
 
 extern "C" cr_status cr_gather_aggregate_bwd(const cr_block_set *blocks, int32_t g, const void *d_agg,

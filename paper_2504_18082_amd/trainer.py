@@ -108,14 +108,14 @@ class Trainer:
         # (measured: -13 % gather time on the arxiv-like graph, -11 % on the reddit-like one, nothing on the
         # products-like one with its 5000 communities), so "auto" asks for it from 32 rows per community on.
         cap_dst0 = B.cr_block_capacities(scfg, self.n_nodes, self.B)[0][0]
-        group_possible = model == "sage" and not (host_features or cache_rows > 0)
+        group_possible = model in ("sage", "gcn") and not (host_features or cache_rows > 0)
         if order_rows == "auto":
             # per batch the order needs enough rows per community to pay; over a whole group (below) it always did
             order_rows = group_possible or (model != "gat" and cap_dst0 >= 32 * cfg.n_comm)
         self.order_rows = bool(order_rows) and model != "gat"
         if self.order_rows:
             self.sample_flags |= B.CR_SAMPLE_ROW_ORDER
-        # GraphSAGE on a resident table goes one step further: the layer-0 aggregation needs neither weights nor
+        # GraphSAGE and GCN on a resident table go one step further: the layer-0 aggregation needs neither weights nor
         # gradients, so it runs once per sampled group, over the rows of all its batches in community order
         # (cr_gather_aggregate_fwd_group): a feature row is then fetched once for the group, not once per batch
         # (measured per batch: arxiv-like 31.8 -> 18.2 us, products-like 77.5 -> 55.6 us, papers-like 46.8 -> 30.4 us).
@@ -137,7 +137,8 @@ class Trainer:
         self.self0_all = self.agg0_all = None
         if self.group_gather:     # [slot][batch][row][column]: layer-0 operands of a whole group
             b16g = lambda: torch.zeros((self.G, self.blocks[0].cap_dst, self.layers[0].F_pad), dtype=torch.int16, device=device)
-            self.self0_all, self.agg0_all = [b16g(), b16g()], [b16g(), b16g()]
+            self.agg0_all = [b16g(), b16g()]
+            self.self0_all = [b16g(), b16g()] if model == "sage" else [None, None]      # (GCN's sum includes the destination's own row)
         self.group_gathered = [False, False]     # per block slot: the current group's layer-0 operands are in *_all
         self.agg = [b16(self.blocks[l].cap_dst, self.layers[l].F_pad if l == 0 else self.layers[l - 1].N_pad) for l in range(self.L)]
         # hidden activations are kept in bf16 only (next layer's self operand, aggregation input and
@@ -238,8 +239,12 @@ class Trainer:
         if self.time_gather0:
             ev0, ev1 = self.torch.cuda.Event(enable_timing=True), self.torch.cuda.Event(enable_timing=True)
             ev0.record()
-        B.cr_gather_aggregate_fwd_group(blk0, self.table_ptr, self.feat_dtype, self.ld_table, self.cfg.n_feat, self.agg0_all[slot],
-                                        self.self0_all[slot], self.block_slots[slot][0].cap_dst, self.layers[0].F_pad)
+        if self.model == "gcn":
+            B.cr_gcn_aggregate_fwd_group(blk0, self.gcn_norm, self.table_ptr, self.feat_dtype, self.ld_table, self.cfg.n_feat,
+                                         self.agg0_all[slot], self.block_slots[slot][0].cap_dst, self.layers[0].F_pad)
+        else:
+            B.cr_gather_aggregate_fwd_group(blk0, self.table_ptr, self.feat_dtype, self.ld_table, self.cfg.n_feat, self.agg0_all[slot],
+                                            self.self0_all[slot], self.block_slots[slot][0].cap_dst, self.layers[0].F_pad)
         if self.time_gather0:
             ev1.record()
             self.gather0_events.append((ev0, ev1))
@@ -282,12 +287,14 @@ class Trainer:
         else:
             slot = self.block_slots.index(self.blocks)
         if self.group_gathered[slot]:
-            self.self0, self.agg[0] = self.self0_all[slot][g], self.agg0_all[slot][g]
+            self.agg[0] = self.agg0_all[slot][g]
+            if self.self0_all[slot] is not None:
+                self.self0 = self.self0_all[slot][g]
         else:
             self.self0, self.agg[0] = self.self0_bufs[buf], self.agg0_bufs[buf]
         L, blocks, layers = self.L, self.blocks, self.layers
         if self.model == "gcn":
-            return self._forward_batch_gcn(g, with_loss)
+            return self._forward_batch_gcn(g, with_loss, self.group_gathered[slot])
         if self.model == "gat":
             return self._forward_batch_gat(g)
         for l in range(L):
@@ -313,12 +320,15 @@ class Trainer:
                                  self.out[l], self.out_b[l])
         return False
 
-    def _forward_batch_gcn(self, g: int, with_loss: bool = False):
+    def _forward_batch_gcn(self, g: int, with_loss: bool = False, gathered0: bool = False):
         """GCN layers: normalised aggregation over the block (the destination's own row included), one-operand layer."""
         L, blocks, layers = self.L, self.blocks, self.layers
         self.wait_weights()
         for l in range(L):
             blk, lay = blocks[l], layers[l]
+            if l == 0 and gathered0:          # aggregated for the whole group right after sampling (self.agg[0])
+                B.cr_sage_linear_fwd(lay, blk.hdr_ptr(g), blk.cap_dst, None, self.agg[0], lay.F_pad, l < L - 1, self.out[l], self.out_b[l])
+                continue
             B.cr_gcn_block_norm(blk, g, self.gcn_norm, self.blk_norm[l])
             if l == 0:
                 if self.time_gather0:

@@ -370,3 +370,11 @@ def test_grouped_gather_validation():
     assert call(blocks(), ld_src=126) == B.CR_ERR_INVALID_ARG
     assert call(blocks(), dtype=3) == B.CR_ERR_INVALID_ARG
     assert call(blocks(), H=None) == B.CR_ERR_INVALID_ARG
+    assert call(blocks(), self_=None) == B.CR_ERR_INVALID_ARG           # GraphSAGE needs the self rows too
+    gcn = lambda b, **kw: lib.cr_gcn_aggregate_fwd_group(C.byref(b), vp(kw.get("norm", FAKE)), vp(kw.get("H", FAKE)), kw.get("dtype", 0),
+                                                         kw.get("ld_src", 128), kw.get("F", 128), vp(kw.get("agg", FAKE)), kw.get("stride", 48),
+                                                         kw.get("ld", 128), None)
+    assert gcn(blocks()) == B.CR_OK
+    assert gcn(blocks(), norm=None) == B.CR_ERR_INVALID_ARG
+    assert gcn(blocks(group_order=None)) == B.CR_ERR_INVALID_ARG and gcn(blocks(), agg=None) == B.CR_ERR_INVALID_ARG
+    assert gcn(blocks(), stride=47) == B.CR_ERR_INVALID_ARG and gcn(blocks(), ld=100) == B.CR_ERR_INVALID_ARG

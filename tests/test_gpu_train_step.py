@@ -288,6 +288,26 @@ def test_grouped_gather_of_wide_rows(n_feat, dtype):
         assert bool((tr.agg0_all[0][g, n:] == 0x7FC0).all()) and bool((tr.self0_all[0][g, n:] == 0x7FC0).all())
 
 
+def test_grouped_gcn_gather_of_wide_rows():
+    """GCN on 2408-byte feature rows: the grouped layer-0 aggregation (column panels) gives the weights of the per-batch
+    path bit for bit."""
+    import copy
+    import torch
+    from paper_2504_18082_amd.trainer import Trainer
+    cfg = copy.deepcopy(synth.CONFIGS["tiny"])
+    cfg.n_feat, cfg.n_nodes, cfg.n_edges_undirected = 602, 4000, 20000
+    w = synth.make_workload(cfg, seed=2)
+    out = []
+    for order in (False, True):
+        tr = Trainer(w, group_size=3, lr=0.05, seed=0, model="gcn", order_rows=order)
+        assert tr.group_gather == order
+        tr.run_epoch_serial(oracle.COMM_RAND, 3, 0.9, 1, max_batches=3)
+        torch.cuda.synchronize()
+        out.append([l.W.cpu().numpy().copy() for l in tr.layers] + [tr.loss.cpu().numpy().copy()])
+    for a, b in zip(*out):
+        assert np.array_equal(a, b)
+
+
 def test_fused_top_layer_loss_changes_only_rounding(tiny_workload):
     """cr_sage_linear_fwd_xent (the layer next to the loss and the loss in one launch) against the separate calls: the first
     step's logits are bit-identical, its loss agrees to float rounding, and the weights after some steps stay within
@@ -327,7 +347,7 @@ def test_row_processing_order_changes_nothing(tiny_workload, model):
         tr = Trainer(w, group_size=4, lr=0.05, seed=0, model=model, order_rows=order)
         b0 = tr.blocks[0]
         assert tr.order_rows == order and (b0.row_order is not None or b0.group_order is not None) == order
-        assert tr.group_gather == (order and model == "sage")        # GraphSAGE gathers once per sampled group
+        assert tr.group_gather == order                      # both models aggregate layer 0 once per sampled group
         tr.run_epoch_serial(oracle.RAND, 1, 0.5, 1, max_batches=6)
         torch.cuda.synchronize()
         b0 = tr.blocks[0]
