@@ -880,10 +880,17 @@ cr_status cr::linear_bwd_products(const cr_sage_layer *layer, const int32_t *hdr
     if (dry_run()) return CR_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
 
+    const unsigned tn_tiles = (unsigned)(n_op * ceil_div(F_pad, 128) * ceil_div(N_pad, 128));
+    if (d_agg || d_in_bf16) {
+        // the input-gradient product shares the launch and the 512 resident workgroup slots: fewer, longer splits so
+        // that both parts fit one round (its tiles counted at ~0.7 of the capacity, the usual fill of a sampled block)
+        const int64_t nt_share = (int64_t)(n_op * F_pad / 64) * ceil_div(max_rows, 128) * 7 / 10;
+        const int64_t room = (512 - nt_share) / tn_tiles;
+        if (room >= 8 && room < splits) splits = (int)room;
+    }
     TnArgs t;
     t.hdr = hdr; t.max_rows = max_rows; t.A0 = n_op == 2 ? h_self : agg; t.A1 = agg; t.lda = ld_in; t.K0 = F_pad; t.K2 = n_op * F_pad;
     t.Z = dz_bf16; t.N = N_pad; t.slots = splits; t.partial = partial;
-    const unsigned tn_tiles = (unsigned)(n_op * ceil_div(F_pad, 128) * ceil_div(N_pad, 128));
     if (d_agg || d_in_bf16) {   // also the gradient w.r.t. the layer's inputs (weights from before the step), in the same launch
         NtArgs a;
         a.hdr = hdr; a.max_rows = max_rows; a.A0 = dz_bf16; a.A1 = nullptr; a.lda = N_pad; a.K0 = N_pad; a.K = N_pad;
