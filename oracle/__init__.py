@@ -16,23 +16,44 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "oracle.c")
 _LIB = os.path.join(_HERE, "liboracle.so")
+_LIB_OMP = os.path.join(_HERE, "liboracle_omp.so")
 _lib = None
+_libs = {}
 
 
 def build(force: bool = False) -> str:
-    """Compile oracle.c with gcc (no fused multiply-add contraction)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        subprocess.check_call(
-            ["gcc", "-O2", "-std=c99", "-ffp-contract=off", "-fPIC", "-shared", "-Wall",
-             "-o", _LIB, _SRC, "-lm"])
+    """Compile oracle.c with gcc (no fused multiply-add contraction): the single-threaded library that everything
+    uses, and the same source with OpenMP enabled for the benchmark's all-cores CPU baseline."""
+    for out, extra in ((_LIB, ["-Wno-unknown-pragmas"]), (_LIB_OMP, ["-fopenmp"])):
+        if force or not os.path.exists(out) or os.path.getmtime(out) < os.path.getmtime(_SRC):
+            subprocess.check_call(
+                ["gcc", "-O2", "-std=c99", "-ffp-contract=off", "-fPIC", "-shared", "-Wall"] + extra +
+                ["-o", out, _SRC, "-lm"])
     return _LIB
 
 
-def lib():
+def use_all_cores(on: bool) -> int:
+    """Switches every later call between the single-threaded library (the oracle proper; the default) and the OpenMP
+    build of the same source (row loops spread over the host's cores).  Returns the number of threads in use."""
     global _lib
-    if _lib is None:
+    _lib = None
+    lib(_LIB_OMP if on else _LIB)
+    if on:
+        omp = C.CDLL("libgomp.so.1")
+        omp.omp_get_max_threads.restype = C.c_int
+        return int(omp.omp_get_max_threads())
+    return 1
+
+
+def lib(path: str = None):
+    global _lib
+    if _lib is None or path is not None:
         build()
-        L = C.CDLL(_LIB)
+        path = path or _LIB
+        if path in _libs:
+            _lib = _libs[path]
+            return _lib
+        L = C.CDLL(path)
         L.orc_shuffle_key.restype = C.c_uint64
         L.orc_shuffle_key.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32]
         L.orc_slot_word.restype = C.c_uint32
@@ -75,6 +96,7 @@ def lib():
         L.orc_cache_fetch.restype = C.c_int32
         L.orc_cache_fetch.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
         L.orc_count_correct.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p]
+        _libs[path] = L
         _lib = L
     return _lib
 
@@ -205,14 +227,14 @@ def round_bf16(x):
 
 
 def gather_mean(blk: Block, table, indirect: bool, F=None, want_self=False):
-    """table: float32 [rows, ld] or uint16 (raw bf16) [rows, ld]."""
-    assert table.dtype in (np.float32, np.uint16) and table.flags.c_contiguous
+    """table: float32 [rows, ld], uint16 (raw bf16) [rows, ld] or float64 [rows, ld]."""
+    assert table.dtype in (np.float32, np.uint16, np.float64) and table.flags.c_contiguous
     F = table.shape[1] if F is None else F
     agg = np.empty((blk.n_dst, F), dtype=np.float64)
     self_rows = np.empty((blk.n_dst, F), dtype=np.float64) if want_self else None
     lib().orc_gather_mean(blk.n_dst, _p(blk.indptr), _p(blk.indices),
                           _p(blk.src_ids) if indirect else None, _p(table),
-                          0 if table.dtype == np.float32 else 1, table.shape[1], F,
+                          {np.dtype(np.float32): 0, np.dtype(np.uint16): 1, np.dtype(np.float64): 2}[table.dtype], table.shape[1], F,
                           _p(agg), _p(self_rows))
     return (agg, self_rows) if want_self else agg
 

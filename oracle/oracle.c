@@ -26,6 +26,12 @@
  * rounding here (round-to-nearest-even on the fp32 bit pattern); accumulation
  * stays in double.
  *
+ * Threads: the library the tests load is built without OpenMP and runs on one
+ * thread.  The "#pragma omp parallel for" lines sit on loops over destination /
+ * output rows whose iterations are independent (every output element is still
+ * one thread's sum, in the same order); they take effect only in the second
+ * build (-fopenmp) that the benchmark times as its all-cores CPU baseline.
+ *
  * Parity pins: every function below is pinned by tests/test_oracle_*.py
  * (known-answer vectors, closed forms, brute force, dense-matrix identities,
  * finite differences).  Nothing here is "parity unpinned".
@@ -351,12 +357,13 @@ void orc_round_bf16(const double *in, int64_t n, double *out)
     for (int64_t i = 0; i < n; ++i) out[i] = (double)bf16_round((float)in[i]);
 }
 
-/* table_dtype: 0 = float32, 1 = bfloat16 (raw uint16).  row_map (may be NULL)
+/* table_dtype: 0 = float32, 1 = bfloat16 (raw uint16), 2 = float64.  row_map (may be NULL)
  * sends a block-local source position to a table row (layer 0: the frontier's
  * global node ids). */
 static double table_at(const void *table, int table_dtype, int64_t ld, int64_t row, int32_t col)
 {
     if (table_dtype == 0) return (double)((const float *)table)[row * ld + col];
+    if (table_dtype == 2) return ((const double *)table)[row * ld + col];
     return bf16_to_double(((const uint16_t *)table)[row * ld + col]);
 }
 
@@ -364,6 +371,7 @@ void orc_gather_mean(int32_t n_dst, const int32_t *indptr, const int32_t *indice
                      const int32_t *row_map, const void *table, int table_dtype, int64_t ld,
                      int32_t F, double *agg /*[n_dst*F]*/, double *self_rows /*[n_dst*F] or NULL*/)
 {
+#pragma omp parallel for schedule(static)
     for (int32_t v = 0; v < n_dst; ++v) {
         int32_t deg = indptr[v + 1] - indptr[v];
         for (int32_t c = 0; c < F; ++c) {
@@ -408,6 +416,7 @@ void orc_sage_linear_fwd(int32_t M, int32_t F_in, int32_t F_out, const double *h
                          const double *agg, const double *W, const double *bias, int relu,
                          int round_operands, double *out /*[M*F_out]*/)
 {
+#pragma omp parallel for schedule(static)
     for (int32_t m = 0; m < M; ++m)
         for (int32_t n = 0; n < F_out; ++n) {
             double s = 0.0;
@@ -438,6 +447,7 @@ void orc_sage_linear_bwd(int32_t M, int32_t F_in, int32_t F_out, const double *h
         for (int32_t m = 0; m < M; ++m) s += dz[(int64_t)m * F_out + n];
         db[n] = s;
     }
+#pragma omp parallel for schedule(static)
     for (int32_t k = 0; k < 2 * F_in; ++k)
         for (int32_t n = 0; n < F_out; ++n) {
             double s = 0.0;
@@ -450,6 +460,7 @@ void orc_sage_linear_bwd(int32_t M, int32_t F_in, int32_t F_out, const double *h
     for (int part = 0; part < 2; ++part) {
         double *dx = part == 0 ? d_self : d_agg;
         if (!dx) continue;
+#pragma omp parallel for schedule(static)
         for (int32_t m = 0; m < M; ++m)
             for (int32_t k = 0; k < F_in; ++k) {
                 double s = 0.0;

@@ -137,29 +137,40 @@ def make_graph(cfg: WorkloadConfig, seed: int = 0, verbose: bool = False):
     cum_hi = cum[comm_ptr[1:] - 1]
     total = cum[-1]
 
-    keys = []
-    n_intra_kept = 0
-    n_kept = 0
-    chunk = 8_000_000
-    for start in range(0, E, chunk):
-        m = min(chunk, E - start)
+    def draw(m):
+        """m undirected edges as directed (row * N + column) keys, both directions."""
         a = np.minimum(np.searchsorted(cum, rng.random(m) * total, side="right"), N - 1)
         want_intra = rng.random(m) < cfg.intra_fraction
         ca = comm[a]
+        lo, width = cum_lo[ca], cum_hi[ca] - cum_lo[ca]
         r = rng.random(m)
-        target = np.where(want_intra, cum_lo[ca] + r * (cum_hi[ca] - cum_lo[ca]), r * total)
+        # second endpoint by propensity: inside a's community, or among all nodes outside it (the community's
+        # stretch of the cumulative mass is skipped, so no draw is wasted)
+        t_out = r * (total - width)
+        target = np.where(want_intra, lo + r * width, np.where(t_out < lo, t_out, t_out + width))
         b = np.minimum(np.searchsorted(cum, target, side="right"), N - 1)
-        same = comm[b] == ca
-        keep = (a != b) & (same == want_intra)          # drop self loops and inter draws that fell inside
+        keep = (a != b) & ((comm[b] == ca) == want_intra)      # self loops; rounding at a community's edge
         a, b = a[keep].astype(np.int64), b[keep].astype(np.int64)
-        n_kept += a.shape[0]
-        n_intra_kept += int(same[keep].sum())
-        keys.append(a * N + b)
-        keys.append(b * N + a)
-        say(f"edges drawn {start + m} / {E}")
-    key = np.unique(np.concatenate(keys))
+        return [a * N + b, b * N + a]
+
+    # Drawing with replacement loses the repeated pairs when the adjacency is de-duplicated: draw, de-duplicate, and
+    # top up what is missing until the graph has (within half a percent) the number of edges asked for.
+    key = np.zeros(0, dtype=np.int64)
+    want = E
+    for _ in range(8):
+        keys = [key]
+        chunk = 8_000_000
+        for start in range(0, want, chunk):
+            keys += draw(min(chunk, want - start))
+            say(f"edges drawn {min(want, start + chunk)} / {want}")
+        before = key.size
+        key = np.unique(np.concatenate(keys))
+        del keys
+        if key.size >= 0.995 * 2 * E:
+            break
+        yield_ = max(0.2, (key.size - before) / (2.0 * want))
+        want = int((2 * E - key.size) / 2 / yield_ * 1.02) + 1
     say(f"{key.size} directed entries after symmetrising and de-duplicating")
-    del keys
     rows = key // N
     indices = (key - rows * N).astype(np.int32)
     indptr = np.zeros(N + 1, dtype=np.int64)

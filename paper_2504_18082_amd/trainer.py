@@ -54,24 +54,34 @@ class Trainer:
         self.sample_flags = 0 if relabel_input else B.CR_SAMPLE_INPUT_GLOBAL_IDS
         if model == "gat":
             self.sample_flags |= B.CR_SAMPLE_TRANSPOSE_INPUT
-        up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(device)
-        self.indptr = up(workload.indptr.astype(np.int64))
-        self.indices = up(workload.indices.astype(np.int32))
-        self.comm = up(workload.comm.astype(np.int32))
-        self.labels = up(workload.labels.astype(np.int32))
-        self.train_ids = up(workload.train_ids.astype(np.int32))
+        # the workload's arrays are numpy (synth.Workload: uploaded here) or already device tensors (synth_gpu.DeviceWorkload)
+        def up(a, dtype):
+            if isinstance(a, torch.Tensor):
+                return a.to(device=device, dtype=dtype).contiguous()
+            return torch.from_numpy(np.ascontiguousarray(a)).to(device=device, dtype=dtype)
+        self.indptr = up(workload.indptr, torch.int64)
+        self.indices = up(workload.indices, torch.int32)
+        self.comm = up(workload.comm, torch.int32)
+        self.labels = up(workload.labels, torch.int32)
+        self.train_ids = up(workload.train_ids, torch.int32)
         feats = workload.features
-        self.feat_dtype = B.CR_BF16 if feats.dtype == np.uint16 else B.CR_F32
-        self.ld_table = feats.shape[1]
-        self.row_bytes = feats.shape[1] * feats.dtype.itemsize
+        on_device = isinstance(feats, torch.Tensor)
+        is_bf16 = feats.dtype == (torch.int16 if on_device else np.uint16)
+        self.feat_dtype = B.CR_BF16 if is_bf16 else B.CR_F32
+        self.ld_table = int(feats.shape[1])
+        self.row_bytes = self.ld_table * (2 if is_bf16 else 4)
         self.host_store = None
         if host_features:      # the table stays in pinned host memory; kernels read it over the host link
+            assert not on_device, "a host-resident store takes a numpy workload"
             self.host_store = B.HostBuffer(feats.shape, feats.dtype)
             self.host_store.array[:] = feats
             self.table = None
             self.table_ptr = self.host_store.device_ptr
         else:
-            self.table = up(feats.view(np.int16) if feats.dtype == np.uint16 else feats)
+            if on_device:
+                self.table = feats.to(device).contiguous()
+            else:
+                self.table = torch.from_numpy(np.ascontiguousarray(feats.view(np.int16) if is_bf16 else feats)).to(device)
             self.table_ptr = C.c_void_p(self.table.data_ptr())
         self.graph = B.make_graph(self.indptr, self.indices, self.comm, cfg.n_comm)
         if edge_classes:     # static per graph: one bit per adjacency entry, read by the biased selection

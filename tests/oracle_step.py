@@ -1,48 +1,89 @@
 """One training step of the L-layer GraphSAGE-mean model written with the oracle's pieces only
-(test infrastructure; mirrors the precision points of the GPU path: bf16 operands into every
-contraction, hidden activations stored in bf16)."""
+(test infrastructure).
+
+Two compositions of the same pieces:
+  mirror=False  the precision model of the plain definition: the operands of every dense product are rounded to
+                bf16 (the matrix cores take bf16), everything between the products -- hidden activations,
+                aggregates, gradients -- stays in float64;
+  mirror=True   additionally rounds what the GPU path STORES in bf16 between its kernels: hidden activations
+                (self operand, aggregation input, ReLU mask), the input gradients d_self / d_agg, and the bias
+                gradient summed from the rounded dZ.
+The GPU path is compared with both: with the mirror at the tight tolerance (only the accumulation order
+differs), with the plain composition at the bf16 tolerance (which bounds what the bf16 storage costs).
+"""
+import time
+
 import numpy as np
 
 import oracle
 
 
-def oracle_forward(graph, table, n_feat, roots, fanouts, p, seed, epoch, batch, params, pos_map=None, strict=False):
+class StageTimers(dict):
+    """Seconds per stage of the path, accumulated over calls (used by the benchmark's cpu_baseline leg)."""
+
+    def add(self, stage, t0):
+        self[stage] = self.get(stage, 0.0) + (time.perf_counter() - t0)
+
+
+def oracle_forward(graph, table, n_feat, roots, fanouts, p, seed, epoch, batch, params, pos_map=None, strict=False,
+                   mirror=True, timers=None):
     """Sampling and forward pass only; returns (blocks, h_self, aggs, outs)."""
     L = len(fanouts)
+    tm = timers if timers is not None else StageTimers()
+    t0 = time.perf_counter()
     blocks = oracle.sample_blocks(graph, roots, fanouts, p, strict, seed, epoch, batch, pos_map)
+    tm.add("sample_blocks", t0)
     h_self, aggs, outs = [None] * L, [None] * L, [None] * L
     for l in range(L):
         blk = blocks[l]
         W, b = params[l]
+        t0 = time.perf_counter()
         if l == 0:
             aggs[0], h_self[0] = oracle.gather_mean(blk, table, indirect=True, F=n_feat, want_self=True)
+            tm.add("gather_aggregate_fwd_layer0", t0)
         else:
-            prev = np.ascontiguousarray(oracle.round_bf16(outs[l - 1]).astype(np.float32))   # hidden activations live in bf16
-            aggs[l] = oracle.gather_mean(blk, prev, indirect=False)
+            if mirror:      # hidden activations live in bf16 on the GPU
+                prev = np.ascontiguousarray(oracle.round_bf16(outs[l - 1]).astype(np.float32))
+                aggs[l] = oracle.gather_mean(blk, prev, indirect=False)
+            else:
+                aggs[l] = oracle.gather_mean(blk, np.ascontiguousarray(outs[l - 1]), indirect=False)
             h_self[l] = outs[l - 1][:blk.n_dst]
+            tm.add("gather_aggregate_fwd_hidden", t0)
+        t0 = time.perf_counter()
         outs[l] = oracle.sage_linear_fwd(h_self[l], aggs[l], W, b, l < L - 1, True)
+        tm.add("sage_linear_fwd", t0)
     return blocks, h_self, aggs, outs
 
 
 def oracle_train_step(graph, table, n_feat, labels, roots, fanouts, p, seed, epoch, batch, params, lr, wd,
-                      pos_map=None, strict=False):
+                      pos_map=None, strict=False, mirror=True, timers=None):
     """params: list of (W float64 [2F_in, F_out], b float64 [F_out]); returns dict with loss, logits,
     grads and the updated params (inputs are not modified)."""
     L = len(fanouts)
-    blocks, h_self, aggs, outs = oracle_forward(graph, table, n_feat, roots, fanouts, p, seed, epoch, batch, params, pos_map, strict)
+    tm = timers if timers is not None else StageTimers()
+    blocks, h_self, aggs, outs = oracle_forward(graph, table, n_feat, roots, fanouts, p, seed, epoch, batch, params, pos_map, strict,
+                                                mirror, tm)
+    t0 = time.perf_counter()
     loss, dz = oracle.softmax_xent(outs[L - 1], labels[np.asarray(roots)])
+    tm.add("softmax_xent", t0)
     grads, new_params = [None] * L, [None] * L
     for l in range(L - 1, -1, -1):
         W, b = params[l]
+        t0 = time.perf_counter()
         dW, db, d_self, d_agg = oracle.sage_linear_bwd(h_self[l], aggs[l], W, outs[l], dz, False, True, need_dx=l > 0)
-        db = oracle.round_bf16(dz).sum(axis=0)          # the GPU sums the operand it feeds the matrix cores
+        if mirror:
+            db = oracle.round_bf16(dz).sum(axis=0)          # the GPU sums the operand it feeds the matrix cores
         grads[l] = (dW, db)
         new_params[l] = oracle.sgd_step(W, dW, b, db, lr, wd)
+        tm.add("sage_linear_bwd_sgd", t0)
         if l > 0:
-            d_agg, d_self = oracle.round_bf16(d_agg), oracle.round_bf16(d_self)     # the GPU path stores them in bf16
+            t0 = time.perf_counter()
+            if mirror:
+                d_agg, d_self = oracle.round_bf16(d_agg), oracle.round_bf16(d_self)     # the GPU path stores them in bf16
             d_src = oracle.gather_mean_bwd(blocks[l], d_agg, d_self)
-            dz = d_src * (oracle.round_bf16(outs[l - 1]) > 0)
-    return dict(blocks=blocks, loss=loss, logits=outs[L - 1], outs=outs, grads=grads, params=new_params)
+            dz = d_src * ((oracle.round_bf16(outs[l - 1]) if mirror else outs[l - 1]) > 0)
+            tm.add("gather_aggregate_bwd", t0)
+    return dict(blocks=blocks, loss=loss, logits=outs[L - 1], outs=outs, grads=grads, params=new_params, timers=tm)
 
 
 def oracle_train_step_gcn(graph, table, n_feat, labels, roots, fanouts, p, seed, epoch, batch, params, lr, wd, pos_map=None):
