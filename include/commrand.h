@@ -100,6 +100,23 @@ cr_status cr_build_batches(const cr_batch_cfg *cfg, const int32_t *train_ids, in
                            const int32_t *comm, int32_t n_comm, void *ws, size_t ws_bytes,
                            int32_t *out_perm, int64_t *out_n_batches, void *stream);
 
+/* cr_build_batches for callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): the same result, bit for bit, with the sort buffers, digit histograms and
+ * community tables in a fixed 8 MiB device array that belongs to the library instead of a caller workspace.  The call
+ * allocates and frees nothing, on the host or on the device.
+ *   limits : n_train <= CR_STATIC_MAX_TRAIN and n_comm <= CR_STATIC_MAX_COMM, otherwise CR_ERR_CAPACITY (use
+ *            cr_build_batches with a workspace)
+ *   sharing: every call on a GPU uses that GPU's one array (each GPU the library runs on holds its own copy until the
+ *            process ends).  Nothing in it needs to start at zero from outside: the call clears what it accumulates
+ *            into with a kernel of its own.  Two calls that overlap on one GPU (different streams or threads) race;
+ *            calls on one stream, or ordered by events, are safe.
+ * All other arguments as in cr_build_batches. */
+#define CR_STATIC_MAX_TRAIN 262144
+#define CR_STATIC_MAX_COMM 65536
+cr_status cr_build_batches_static(const cr_batch_cfg *cfg, const int32_t *train_ids, int64_t n_train,
+                                  const int32_t *comm, int32_t n_comm, int32_t *out_perm,
+                                  int64_t *out_n_batches, void *stream);
+
 /* ------------------------------------------------------------------------- */
 /* Step-2: sub-graph construction (Algorithm 1 Step-2; Section 4.2).          */
 /* ------------------------------------------------------------------------- */

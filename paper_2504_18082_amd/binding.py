@@ -28,7 +28,7 @@ CR_SAMPLE_ROW_ORDER = 16
 
 EXPORTS = [
     "cr_last_error", "cr_version", "cr_set_dry_run", "cr_mix_count_from_percent",
-    "cr_build_batches_workspace_bytes", "cr_build_batches",
+    "cr_build_batches_workspace_bytes", "cr_build_batches", "cr_build_batches_static",
     "cr_graph_edge_classes", "cr_block_capacities", "cr_sample_blocks_workspace_bytes", "cr_sample_blocks",
     "cr_gather_aggregate_fwd", "cr_gather_aggregate_fwd_group", "cr_gather_aggregate_bwd",
     "cr_graph_gcn_norm", "cr_gcn_block_norm", "cr_gcn_aggregate_fwd", "cr_gcn_aggregate_fwd_group", "cr_gcn_aggregate_bwd",
@@ -109,6 +109,7 @@ def lib():
         L.cr_build_batches_workspace_bytes.argtypes = [i64, i32, C.POINTER(C.c_size_t)]
         L.cr_build_batches.argtypes = [C.POINTER(cr_batch_cfg), vp, i64, vp, i32, vp, C.c_size_t, vp,
                                        C.POINTER(i64), vp]
+        L.cr_build_batches_static.argtypes = [C.POINTER(cr_batch_cfg), vp, i64, vp, i32, vp, C.POINTER(i64), vp]
         L.cr_block_capacities.argtypes = [C.POINTER(cr_sample_cfg), i64, i32, C.POINTER(i32),
                                           C.POINTER(i32), C.POINTER(i32)]
         L.cr_sample_blocks_workspace_bytes.argtypes = [C.POINTER(cr_sample_cfg), i64, i32, i32,
@@ -292,6 +293,18 @@ def cr_build_batches(policy, mix_count, batch_size, seed, epoch, train_ids, comm
     _check(lib().cr_build_batches(C.byref(cfg), _ptr(train_ids), train_ids.numel(), _ptr(comm), n_comm,
                                   _ptr(ws), ws.numel() * ws.element_size(), _ptr(out_perm), C.byref(nb),
                                   _stream(stream)))
+    return nb.value
+
+
+CR_STATIC_MAX_TRAIN, CR_STATIC_MAX_COMM = 262144, 65536
+
+
+def cr_build_batches_static(policy, mix_count, batch_size, seed, epoch, train_ids, comm, n_comm, out_perm, stream=None) -> int:
+    """cr_build_batches without a workspace argument (the library's fixed scratch array; allocates nothing)."""
+    cfg = cr_batch_cfg(policy, mix_count, batch_size, epoch, seed)
+    nb = C.c_int64(0)
+    _check(lib().cr_build_batches_static(C.byref(cfg), _ptr(train_ids), train_ids.numel(), _ptr(comm), n_comm,
+                                         _ptr(out_perm), C.byref(nb), _stream(stream)))
     return nb.value
 
 

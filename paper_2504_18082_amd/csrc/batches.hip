@@ -2,6 +2,8 @@
 // training set under NORAND-ROOTS, COMM-RAND-MIX and RAND-ROOTS.  Every shuffle is a stable
 // least-significant-digit radix sort by a Philox key, started from ascending ids, so equal keys
 // keep the smaller id first and the result does not depend on scheduling.
+#include <mutex>
+
 #include "cr_common.h"
 
 namespace cr {
@@ -189,19 +191,10 @@ extern "C" cr_status cr_build_batches_workspace_bytes(int64_t n_train, int32_t n
     return CR_OK;
 }
 
-extern "C" cr_status cr_build_batches(const cr_batch_cfg *cfg, const int32_t *train_ids, int64_t n_train,
-                                      const int32_t *comm, int32_t n_comm, void *ws, size_t ws_bytes,
-                                      int32_t *out_perm, int64_t *out_n_batches, void *stream)
+static cr_status build_batches_impl(const cr_batch_cfg *cfg, const int32_t *train_ids, int64_t n_train,
+                                    const int32_t *comm, int32_t n_comm, void *ws, size_t ws_bytes,
+                                    int32_t *out_perm, int64_t *out_n_batches, void *stream)
 {
-    CR_REQUIRE(cfg != nullptr, CR_ERR_INVALID_ARG, "cfg is NULL");
-    CR_REQUIRE(cfg->policy >= CR_ROOTS_NORAND && cfg->policy <= CR_ROOTS_RAND, CR_ERR_INVALID_ARG, "unknown root policy %d", cfg->policy);
-    CR_REQUIRE(cfg->policy != CR_ROOTS_COMM_RAND || cfg->mix_count >= 1, CR_ERR_INVALID_ARG, "mix_count must be >= 1");
-    CR_REQUIRE(cfg->batch_size >= 1, CR_ERR_INVALID_ARG, "batch_size must be positive");
-    CR_REQUIRE(cfg->epoch < (1u << 24), CR_ERR_INVALID_ARG, "epoch must be below 2^24");
-    CR_REQUIRE(n_train >= 0 && n_train < 0x7FFFFFFF, CR_ERR_INVALID_ARG, "n_train must be in 0..2^31-2");
-    CR_REQUIRE(n_comm >= 1, CR_ERR_INVALID_ARG, "n_comm must be positive");
-    CR_REQUIRE(n_train == 0 || (train_ids && out_perm), CR_ERR_INVALID_ARG, "train_ids / out_perm must not be NULL");
-    CR_REQUIRE(comm != nullptr, CR_ERR_INVALID_ARG, "comm is NULL");
     BatchPlan p;
     plan_batches(n_train, n_comm, ws, p);
     CR_REQUIRE(ws != nullptr && aligned16(ws), CR_ERR_INVALID_ARG, "workspace must be a 16-byte aligned device pointer");
@@ -246,4 +239,78 @@ extern "C" cr_status cr_build_batches(const cr_batch_cfg *cfg, const int32_t *tr
     hipLaunchKernelGGL(copy_i32_kernel, grid_n, blk, 0, s, reinterpret_cast<const int32_t *>(b.vals[b.cur]), n, out_perm);
     CR_LAUNCH_CHECK();
     return CR_OK;
+}
+
+static cr_status check_batch_args(const cr_batch_cfg *cfg, const int32_t *train_ids, int64_t n_train, const int32_t *comm,
+                                  int32_t n_comm, const int32_t *out_perm)
+{
+    CR_REQUIRE(cfg != nullptr, CR_ERR_INVALID_ARG, "cfg is NULL");
+    CR_REQUIRE(cfg->policy >= CR_ROOTS_NORAND && cfg->policy <= CR_ROOTS_RAND, CR_ERR_INVALID_ARG, "unknown root policy %d", cfg->policy);
+    CR_REQUIRE(cfg->policy != CR_ROOTS_COMM_RAND || cfg->mix_count >= 1, CR_ERR_INVALID_ARG, "mix_count must be >= 1");
+    CR_REQUIRE(cfg->batch_size >= 1, CR_ERR_INVALID_ARG, "batch_size must be positive");
+    CR_REQUIRE(cfg->epoch < (1u << 24), CR_ERR_INVALID_ARG, "epoch must be below 2^24");
+    CR_REQUIRE(n_train >= 0 && n_train < 0x7FFFFFFF, CR_ERR_INVALID_ARG, "n_train must be in 0..2^31-2");
+    CR_REQUIRE(n_comm >= 1, CR_ERR_INVALID_ARG, "n_comm must be positive");
+    CR_REQUIRE(n_train == 0 || (train_ids && out_perm), CR_ERR_INVALID_ARG, "train_ids / out_perm must not be NULL");
+    CR_REQUIRE(comm != nullptr, CR_ERR_INVALID_ARG, "comm is NULL");
+    return CR_OK;
+}
+
+extern "C" cr_status cr_build_batches(const cr_batch_cfg *cfg, const int32_t *train_ids, int64_t n_train,
+                                      const int32_t *comm, int32_t n_comm, void *ws, size_t ws_bytes,
+                                      int32_t *out_perm, int64_t *out_n_batches, void *stream)
+{
+    cr_status st = check_batch_args(cfg, train_ids, n_train, comm, n_comm, out_perm);
+    if (st != CR_OK) return st;
+    return build_batches_impl(cfg, train_ids, n_train, comm, n_comm, ws, ws_bytes, out_perm, out_n_batches, stream);
+}
+
+// ---------------------------------------------------------------------------------------------
+// The same without a caller workspace: sort buffers, histograms and community tables live in a fixed device array of
+// this library.  Host code never uses the array's name as an address: the array's device address is looked up once
+// per device and kept.
+// ---------------------------------------------------------------------------------------------
+constexpr size_t STATIC_SCRATCH_BYTES = 8u << 20;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex scratch_mutex;
+void *scratch_ptr[MAX_DEVICES] = {};
+}  // namespace
+
+extern "C" cr_status cr_build_batches_static(const cr_batch_cfg *cfg, const int32_t *train_ids, int64_t n_train,
+                                             const int32_t *comm, int32_t n_comm, int32_t *out_perm,
+                                             int64_t *out_n_batches, void *stream)
+{
+    cr_status st = check_batch_args(cfg, train_ids, n_train, comm, n_comm, out_perm);
+    if (st != CR_OK) return st;
+    CR_REQUIRE(n_train <= CR_STATIC_MAX_TRAIN, CR_ERR_CAPACITY,
+               "n_train = %lld exceeds what the library's fixed scratch array holds (%d training nodes); use cr_build_batches with a workspace",
+               (long long)n_train, CR_STATIC_MAX_TRAIN);
+    CR_REQUIRE(n_comm <= CR_STATIC_MAX_COMM, CR_ERR_CAPACITY,
+               "n_comm = %d exceeds what the library's fixed scratch array holds (%d communities); use cr_build_batches with a workspace",
+               n_comm, CR_STATIC_MAX_COMM);
+    BatchPlan p;
+    plan_batches(n_train, n_comm, nullptr, p);
+    CR_REQUIRE(p.bytes <= STATIC_SCRATCH_BYTES, CR_ERR_CAPACITY, "scratch of %zu bytes, %zu needed", STATIC_SCRATCH_BYTES, p.bytes);
+    if (dry_run()) {
+        if (out_n_batches) *out_n_batches = ceil_div(n_train, cfg->batch_size);
+        return CR_OK;
+    }
+    int dev = 0;
+    CR_HIP_CHECK(hipGetDevice(&dev));
+    CR_REQUIRE(dev >= 0 && dev < MAX_DEVICES, CR_ERR_UNSUPPORTED, "device index %d outside 0..%d", dev, MAX_DEVICES - 1);
+    void *ws = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(scratch_mutex);
+        if (!scratch_ptr[dev]) {
+            void *ptr = nullptr;
+            CR_HIP_CHECK(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+            CR_REQUIRE(ptr != nullptr, CR_ERR_HIP, "the scratch array has no device address");
+            scratch_ptr[dev] = ptr;
+        }
+        ws = scratch_ptr[dev];
+    }
+    return build_batches_impl(cfg, train_ids, n_train, comm, n_comm, ws, STATIC_SCRATCH_BYTES, out_perm, out_n_batches, stream);
 }

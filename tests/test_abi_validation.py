@@ -64,6 +64,24 @@ def test_build_batches_validation():
     assert b"workspace" in B.lib().cr_last_error()
 
 
+def test_build_batches_static_validation():
+    lib = B.lib()
+
+    def call(n_train=1000, n_comm=10, policy=1, mix=1, train=FAKE, out=FAKE):
+        cfg = B.cr_batch_cfg(policy, mix, 256, 0, 0)
+        nb = C.c_int64(-1)
+        return lib.cr_build_batches_static(C.byref(cfg), vp(train), n_train, vp(), n_comm, vp(out), C.byref(nb), None), nb.value
+
+    assert call() == (B.CR_OK, 4)
+    assert call(n_train=B.CR_STATIC_MAX_TRAIN, n_comm=B.CR_STATIC_MAX_COMM)[0] == B.CR_OK       # the stated maximum fits the array
+    assert call(n_train=B.CR_STATIC_MAX_TRAIN + 1)[0] == B.CR_ERR_CAPACITY
+    assert b"fixed scratch array" in lib.cr_last_error()
+    assert call(n_comm=B.CR_STATIC_MAX_COMM + 1)[0] == B.CR_ERR_CAPACITY
+    assert call(policy=3)[0] == B.CR_ERR_INVALID_ARG
+    assert call(policy=1, mix=0)[0] == B.CR_ERR_INVALID_ARG
+    assert call(train=None)[0] == B.CR_ERR_INVALID_ARG
+
+
 def sample(fanouts=(10, 5), p=0.9, epoch=0, n_nodes=10000, batch=8, n_batches=1, n_roots=8, flags=0, layers=None,
            ws_bytes=None, graph_null=None):
     lib = B.lib()
