@@ -22,7 +22,7 @@
  *  - All work is enqueued on the given hipStream_t (passed as void*, NULL = the
  *    default stream) and the call returns without synchronising, except where
  *    stated.  Arguments are validated on the host before anything is launched;
- *    with cr_set_dry_run(1) calls stop after validation (no GPU needed).
+ *    under a context created with CR_CTX_DRY_RUN calls stop after validation (no GPU needed).
  *  - Device pointers must be 16-byte aligned.  Row strides (ld*) are in
  *    elements and must make every row 16-byte aligned.
  *  - Sizes that depend on the sampled data (rows, edges, frontier length of a
@@ -46,7 +46,8 @@ enum {
     CR_ERR_INVALID_ARG = 1, /* null / misaligned pointer, knob out of range, shape mismatch */
     CR_ERR_CAPACITY = 2,    /* a caller-provided buffer or workspace is too small */
     CR_ERR_UNSUPPORTED = 3, /* valid request outside what the kernels were built for */
-    CR_ERR_HIP = 4          /* the HIP runtime reported an error */
+    CR_ERR_HIP = 4,         /* the HIP runtime reported an error */
+    CR_ERR_ASYNC_OVERFLOW = 5 /* cr_ctx_poll_error only: a kernel found a data-dependent size beyond the caller's capacity */
 };
 
 #define CR_MAX_LAYERS 8
@@ -56,12 +57,41 @@ enum {
 #define CR_HDR_N_DST 0
 #define CR_HDR_N_SRC 1
 #define CR_HDR_NNZ 2
-#define CR_HDR_STATUS 3 /* 0 = valid; non-zero = the block overflowed its hash table (never with bound-sized capacities) */
+#define CR_HDR_STATUS 3 /* 0 = valid; otherwise CR_ASYNC_* bits: the block did not fit its arrays and must not be used
+                           (never with the capacities of cr_block_capacities) */
 
 const char *cr_last_error(void);
 const char *cr_version(void);
-/* on != 0: every later call on any thread validates its arguments, then returns without touching the GPU. */
-void cr_set_dry_run(int on);
+
+/* ------------------------------------------------------------------------- */
+/* Contexts.  Algorithm 1's loop runs one mini-batch after the other without   */
+/* the host looking at any sampled size, so a size that exceeds a caller's     */
+/* capacity can only be reported after the fact: kernels record it in device   */
+/* status words, and the caller polls them when it chooses (once per epoch,    */
+/* say).  A context carries those words and the dry-run flag.  It is a small   */
+/* host object; the entry points below take no context argument: they follow   */
+/* the context that is CURRENT on the calling thread (none by default).        */
+/* ------------------------------------------------------------------------- */
+typedef struct cr_ctx cr_ctx;
+#define CR_CTX_DRY_RUN 1u       /* calls made under this context validate their arguments on the host and return
+                                   without touching the GPU (error paths can be exercised without a device) */
+#define CR_CTX_STATUS_WORDS 2   /* status[0]: OR of CR_ASYNC_* bits, sticky; status[1]: the largest size that was needed */
+#define CR_ASYNC_TABLE_FULL 1        /* a frontier de-duplication table ran full */
+#define CR_ASYNC_FRONTIER_OVERFLOW 2 /* a block's frontier needed more than cap_src entries (CR_SAMPLE_SMALL_FRONTIER) */
+
+/*   device : the device the context's work runs on (informational; the caller selects devices)
+ *   flags  : 0 or CR_CTX_DRY_RUN
+ *   status : device int64[CR_CTX_STATUS_WORDS], caller-owned, zeroed by the caller, 8-byte aligned; NULL = kernels
+ *            record overflows in the block headers only
+ * Allocates host memory only. */
+cr_status cr_ctx_create(cr_ctx **ctx, int32_t device, uint32_t flags, int64_t *status);
+cr_status cr_ctx_destroy(cr_ctx *ctx);       /* frees host memory only; NULL is allowed */
+/* Makes ctx (or none, with NULL) the calling thread's current context.  Other threads are not affected. */
+cr_status cr_ctx_make_current(cr_ctx *ctx);
+/* Reads the status words (one small copy on `stream`, then waits for that stream): CR_OK if nothing overflowed since
+ * the words were last cleared, else CR_ERR_ASYNC_OVERFLOW with *required (may be NULL) = the largest frontier length
+ * that was needed.  clear != 0 zeroes the words again (by a kernel on `stream`). */
+cr_status cr_ctx_poll_error(cr_ctx *ctx, int64_t *required, int32_t clear, void *stream);
 
 /* ------------------------------------------------------------------------- */
 /* Step-1: root node partitioning (Algorithm 1 Step-1; Section 4.1; Table 1). */
@@ -193,6 +223,15 @@ typedef struct {
 #define CR_SAMPLE_TRANSPOSE_INPUT 8u /* layers[0] may carry t_indptr / t_indices too (a model whose first layer needs a
                                      gradient per source row: graph attention projects the source rows before it
                                      aggregates).  Not together with CR_SAMPLE_INPUT_GLOBAL_IDS. */
+
+#define CR_SAMPLE_SMALL_FRONTIER 32u /* the block sets may be smaller than the bounds of cr_block_capacities (which assume that
+                                  no two sampled neighbours of a batch coincide): per layer cap_src >= cap_dst, cap_nnz >=
+                                  cap_dst * fanout, cap_dst of the root layer >= batch_size and cap_dst of layer l-1 >=
+                                  min(cap_src of layer l, its bound).  A frontier that needs more than cap_src entries is
+                                  cut at cap_src, its block (and what is sampled below it) gets a non-zero CR_HDR_STATUS, and
+                                  the current context's status words record CR_ASYNC_FRONTIER_OVERFLOW with the length that
+                                  was needed; every access stays inside the arrays.  The workspace is sized as without the
+                                  flag. */
 
 #define CR_SAMPLE_ROW_ORDER 16u /* fill the row_order array of every layer whose block set carries one (the workspace is
                                   then larger: set the flag for cr_sample_blocks_workspace_bytes too) */
@@ -477,6 +516,13 @@ cr_status cr_sage_linear_fwd_xent(const cr_sage_layer *layer, const int32_t *hdr
 cr_status cr_count_correct(const int32_t *hdr, int32_t max_rows, const float *logits, int64_t ld,
                            int32_t n_classes, const int32_t *labels, const int32_t *root_ids,
                            int32_t *count, void *stream);
+
+/* Mean of a per-batch mean over batches of different sizes (the validation loss of the training protocol is the mean
+ * over all validation nodes, and the last batch is short): with n = min(hdr[CR_HDR_N_DST], max_rows),
+ *   acc[0] += value[0] * n,  acc[1] += n,  acc[2] = acc[0] / acc[1].
+ *   value : device float[1] (the loss cr_softmax_xent left for this batch)
+ *   acc   : device double[3], zeroed by the caller before the first batch; calls must be ordered (one stream) */
+cr_status cr_mean_accumulate(const int32_t *hdr, int32_t max_rows, const float *value, double *acc, void *stream);
 
 /* ------------------------------------------------------------------------- */
 /* Software-managed feature cache (Section 6.5, impact of software-managed     */

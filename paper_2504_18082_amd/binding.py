@@ -17,7 +17,10 @@ CR_MAX_LAYERS = 8
 CR_MAX_FANOUT = 64
 CR_HDR_WORDS = 8
 CR_HDR_N_DST, CR_HDR_N_SRC, CR_HDR_NNZ, CR_HDR_STATUS = 0, 1, 2, 3
-CR_OK, CR_ERR_INVALID_ARG, CR_ERR_CAPACITY, CR_ERR_UNSUPPORTED, CR_ERR_HIP = range(5)
+CR_OK, CR_ERR_INVALID_ARG, CR_ERR_CAPACITY, CR_ERR_UNSUPPORTED, CR_ERR_HIP, CR_ERR_ASYNC_OVERFLOW = range(6)
+CR_CTX_DRY_RUN = 1
+CR_CTX_STATUS_WORDS = 2
+CR_ASYNC_TABLE_FULL, CR_ASYNC_FRONTIER_OVERFLOW = 1, 2
 CR_ROOTS_NORAND, CR_ROOTS_COMM_RAND, CR_ROOTS_RAND = 0, 1, 2
 CR_F32, CR_BF16 = 0, 1
 CR_SAMPLE_STRICT_INTRA = 1
@@ -25,16 +28,18 @@ CR_SAMPLE_HASH_DEDUP = 2
 CR_SAMPLE_INPUT_GLOBAL_IDS = 4
 CR_SAMPLE_TRANSPOSE_INPUT = 8
 CR_SAMPLE_ROW_ORDER = 16
+CR_SAMPLE_SMALL_FRONTIER = 32
 
 EXPORTS = [
-    "cr_last_error", "cr_version", "cr_set_dry_run", "cr_mix_count_from_percent",
+    "cr_last_error", "cr_version", "cr_mix_count_from_percent",
+    "cr_ctx_create", "cr_ctx_destroy", "cr_ctx_make_current", "cr_ctx_poll_error",
     "cr_build_batches_workspace_bytes", "cr_build_batches", "cr_build_batches_static",
     "cr_graph_edge_classes", "cr_block_capacities", "cr_sample_blocks_workspace_bytes", "cr_sample_blocks",
     "cr_gather_aggregate_fwd", "cr_gather_aggregate_fwd_group", "cr_gather_aggregate_bwd",
     "cr_graph_gcn_norm", "cr_gcn_block_norm", "cr_gcn_aggregate_fwd", "cr_gcn_aggregate_fwd_group", "cr_gcn_aggregate_bwd",
     "cr_sage_padded_dims", "cr_sage_refresh_shadows", "cr_sage_linear_fwd", "cr_sage_linear_fwd_xent",
     "cr_sage_linear_bwd_workspace_bytes", "cr_sage_linear_bwd", "cr_sage_linear_bwd_input", "cr_sage_layer_bwd", "cr_softmax_xent",
-    "cr_count_correct",
+    "cr_count_correct", "cr_mean_accumulate",
     "cr_gather_rows_bf16", "cr_gat_attention_fwd", "cr_gat_attention_bwd_workspace_bytes", "cr_gat_attention_bwd",
     "cr_cache_reset", "cr_cache_fetch", "cr_stage_rows", "cr_host_alloc", "cr_host_free",
 ]
@@ -102,8 +107,10 @@ def lib():
         vp, i32, i64, u64 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64
         L.cr_last_error.restype = C.c_char_p
         L.cr_version.restype = C.c_char_p
-        L.cr_set_dry_run.argtypes = [C.c_int]
-        L.cr_set_dry_run.restype = None
+        L.cr_ctx_create.argtypes = [C.POINTER(vp), i32, C.c_uint32, vp]
+        L.cr_ctx_destroy.argtypes = [vp]
+        L.cr_ctx_make_current.argtypes = [vp]
+        L.cr_ctx_poll_error.argtypes = [vp, C.POINTER(i64), i32, vp]
         L.cr_mix_count_from_percent.argtypes = [C.c_double, i32]
         L.cr_mix_count_from_percent.restype = i32
         L.cr_build_batches_workspace_bytes.argtypes = [i64, i32, C.POINTER(C.c_size_t)]
@@ -139,6 +146,7 @@ def lib():
                                         vp, vp, i64, vp, i64, vp, vp, vp, C.c_size_t, vp]
         L.cr_softmax_xent.argtypes = [vp, i32, vp, i64, i32, vp, vp, vp, vp, vp, vp, vp]
         L.cr_count_correct.argtypes = [vp, i32, vp, i64, i32, vp, vp, vp, vp]
+        L.cr_mean_accumulate.argtypes = [vp, i32, vp, vp, vp]
         L.cr_gather_rows_bf16.argtypes = [vp, i32, i64, i32, vp, vp, i32, i32, vp, i64, vp]
         L.cr_gat_attention_fwd.argtypes = [C.POINTER(cr_block_set), i32, C.POINTER(cr_gat_params), vp, i64, i32, vp, vp, vp, vp, vp, vp]
         L.cr_gat_attention_bwd_workspace_bytes.argtypes = [i32, i64, i32, C.POINTER(C.c_size_t)]
@@ -151,7 +159,7 @@ def lib():
         L.cr_host_free.argtypes = [vp]
         for name in EXPORTS:
             fn = getattr(L, name)
-            if name not in ("cr_last_error", "cr_version", "cr_set_dry_run", "cr_mix_count_from_percent"):
+            if name not in ("cr_last_error", "cr_version", "cr_mix_count_from_percent"):
                 fn.restype = i32
         _lib = L
     return _lib
@@ -188,8 +196,57 @@ def cr_version() -> str:
     return lib().cr_version().decode()
 
 
+class Context:
+    """A cr_ctx: the dry-run flag and (optionally) the device status words that kernels record overflows in.
+    The entry points follow the context that is current on the calling thread."""
+
+    def __init__(self, device: int = 0, dry_run: bool = False, status=None):
+        """status: a zeroed device int64[CR_CTX_STATUS_WORDS] tensor (kept alive here), or None."""
+        self.status = status
+        h = C.c_void_p()
+        _check(lib().cr_ctx_create(C.byref(h), device, CR_CTX_DRY_RUN if dry_run else 0, _ptr(status)))
+        self.handle = h
+
+    def make_current(self):
+        _check(lib().cr_ctx_make_current(self.handle))
+
+    @staticmethod
+    def make_none_current():
+        _check(lib().cr_ctx_make_current(None))
+
+    def poll_error(self, clear: bool = True, stream=None):
+        """(status code, required): (CR_OK, 0) or (CR_ERR_ASYNC_OVERFLOW, the frontier length that was needed)."""
+        req = C.c_int64(0)
+        st = lib().cr_ctx_poll_error(self.handle, C.byref(req), int(clear), _stream(stream))
+        if st not in (CR_OK, CR_ERR_ASYNC_OVERFLOW):
+            _check(st)
+        return st, req.value
+
+    def destroy(self):
+        if self.handle is not None and self.handle.value:
+            lib().cr_ctx_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+_dry_ctx = None
+
+
 def cr_set_dry_run(on: bool):
-    lib().cr_set_dry_run(int(on))
+    """Puts the calling thread under a dry-run context (calls validate, then return without touching the GPU), or
+    back under no context."""
+    global _dry_ctx
+    if on:
+        if _dry_ctx is None:
+            _dry_ctx = Context(dry_run=True)
+        _dry_ctx.make_current()
+    else:
+        Context.make_none_current()
 
 
 def cr_mix_count_from_percent(k_percent: float, n_comm_in_train: int) -> int:
@@ -475,6 +532,10 @@ def cr_softmax_xent(hdr_ptr, max_rows, logits, ld, n_classes, labels, root_ids_p
 def cr_count_correct(hdr_ptr, max_rows, logits, ld, n_classes, labels, root_ids_ptr, count, stream=None):
     _check(lib().cr_count_correct(hdr_ptr, max_rows, _ptr(logits), ld, n_classes, _ptr(labels), root_ids_ptr, _ptr(count),
                                   _stream(stream)))
+
+
+def cr_mean_accumulate(hdr_ptr, max_rows, value, acc, stream=None):
+    _check(lib().cr_mean_accumulate(hdr_ptr, max_rows, _ptr(value), _ptr(acc), _stream(stream)))
 
 
 class GatParams:

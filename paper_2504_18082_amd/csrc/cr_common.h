@@ -6,11 +6,19 @@
 
 #include "../../include/commrand.h"
 
+// host-side handle behind the C ABI's cr_ctx
+struct cr_ctx {
+    int32_t device;
+    uint32_t flags;
+    int64_t *status;        // device int64[CR_CTX_STATUS_WORDS], caller-owned, or NULL
+};
+
 namespace cr {
 
 // ---- host side: error text, dry-run flag, argument checks ------------------------------------
 void set_error(const char *fmt, ...);
-bool dry_run();
+bool dry_run();             // the calling thread's current context asks for validation only
+int64_t *async_status();    // device status words of the calling thread's current context, or NULL
 
 #define CR_REQUIRE(cond, code, ...)                  \
     do {                                             \

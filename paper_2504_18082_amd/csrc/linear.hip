@@ -964,6 +964,31 @@ extern "C" cr_status cr_softmax_xent(const int32_t *hdr, int32_t max_rows, const
     return CR_OK;
 }
 
+namespace cr {
+// acc[0] += value * rows, acc[1] += rows, acc[2] = their ratio (one thread: the calls of a pass are ordered on their stream)
+__global__ void mean_accumulate_kernel(const int32_t *hdr, int max_rows, const float *value, double *acc)
+{
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    const int n = min(hdr[CR_HDR_N_DST], max_rows);
+    if (n <= 0) return;
+    const double sum = acc[0] + (double)value[0] * (double)n, rows = acc[1] + (double)n;
+    acc[0] = sum;
+    acc[1] = rows;
+    acc[2] = sum / rows;
+}
+}  // namespace cr
+
+extern "C" cr_status cr_mean_accumulate(const int32_t *hdr, int32_t max_rows, const float *value, double *acc, void *stream)
+{
+    CR_REQUIRE(hdr != nullptr && max_rows >= 1, CR_ERR_INVALID_ARG, "hdr must not be NULL and max_rows must be positive");
+    CR_REQUIRE(value != nullptr && acc != nullptr, CR_ERR_INVALID_ARG, "value / acc must not be NULL");
+    CR_REQUIRE((reinterpret_cast<uintptr_t>(acc) & 7u) == 0, CR_ERR_INVALID_ARG, "acc must be 8-byte aligned");
+    if (dry_run()) return CR_OK;
+    hipLaunchKernelGGL(mean_accumulate_kernel, dim3(1), dim3(64), 0, static_cast<hipStream_t>(stream), hdr, max_rows, value, acc);
+    CR_LAUNCH_CHECK();
+    return CR_OK;
+}
+
 extern "C" cr_status cr_count_correct(const int32_t *hdr, int32_t max_rows, const float *logits, int64_t ld,
                                       int32_t n_classes, const int32_t *labels, const int32_t *root_ids,
                                       int32_t *count, void *stream)

@@ -569,6 +569,8 @@ struct ScanArgs {
     int32_t *hdr;
     int32_t n_fixed;
     const int32_t *tile_before;   // optional (one batch only): sum of everything in front of each tile, computed beforehand
+    int32_t cap_src;              // mode 1: entries the frontier array holds
+    int64_t *async_status;        // mode 1: status words of the caller's context, or NULL
 };
 
 // out[0..n] = exclusive prefix sums of in[0..n) per batch (blockIdx.y).  A workgroup owns one tile of 256 x 16
@@ -630,10 +632,21 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_kernel(ScanArgs a)
         if (a.mode == 0) {
             hdr[CR_HDR_N_DST] = n_dst;
             hdr[CR_HDR_NNZ] = total;
-            hdr[CR_HDR_STATUS] = 0;
+            // a block sampled below a frontier that was cut short is as invalid as that frontier
+            hdr[CR_HDR_STATUS] = a.prev_hdr ? a.prev_hdr[(int64_t)g * CR_HDR_WORDS + CR_HDR_STATUS] : 0;
             hdr[4] = hdr[5] = hdr[6] = hdr[7] = 0;
         } else if (a.mode == 1) {
-            hdr[CR_HDR_N_SRC] = n_dst + total;
+            const int need = n_dst + total;
+            if (need > a.cap_src) {        // only possible with capacities below the bound: cut the frontier, mark the block
+                hdr[CR_HDR_N_SRC] = a.cap_src;
+                atomicOr(&hdr[CR_HDR_STATUS], CR_ASYNC_FRONTIER_OVERFLOW);
+                if (a.async_status) {
+                    atomicOr(reinterpret_cast<unsigned long long *>(a.async_status), (unsigned long long)CR_ASYNC_FRONTIER_OVERFLOW);
+                    atomicMax(reinterpret_cast<long long *>(a.async_status + 1), (long long)need);
+                }
+            } else {
+                hdr[CR_HDR_N_SRC] = need;
+            }
         }
     }
 }
@@ -820,6 +833,8 @@ struct DedupArgs {
     int32_t *hdr;
     int32_t *src_ids;
     int64_t src_stride;
+    int32_t cap_src;          // entries the frontier array holds per batch
+    int64_t *async_status;    // status words of the caller's context, or NULL
     int32_t *indptr;
     int64_t indptr_stride;
     int32_t *indices;
@@ -874,7 +889,10 @@ __global__ __launch_bounds__(256) void insert_kernel(DedupArgs a)
         if (a.direct) atomicMin(&dtab[u], (int32_t)(n_dst + ell));
         else ok = table_insert(table, a.table_bits, (uint32_t)u, (uint32_t)(n_dst + ell)) && ok;
     }
-    if (!ok) atomicOr(&hdr[CR_HDR_STATUS], 1);
+    if (!ok) {
+        atomicOr(&hdr[CR_HDR_STATUS], CR_ASYNC_TABLE_FULL);
+        if (a.async_status) atomicOr(reinterpret_cast<unsigned long long *>(a.async_status), (unsigned long long)CR_ASYNC_TABLE_FULL);
+    }
 }
 
 // which chosen neighbours are seen here for the first time (and are not destination nodes)
@@ -916,7 +934,7 @@ __global__ __launch_bounds__(256) void assign_kernel(DedupArgs a)
     if (!((rowmask >> j) & 1ull)) return;
     const int32_t u = a.sel[(int64_t)g * a.sel_stride + ell];
     const int local = n_dst + a.newoff[(int64_t)g * a.off_stride + row] + __popcll(rowmask & ((1ull << j) - 1ull));
-    a.src_ids[(int64_t)g * a.src_stride + local] = u;
+    if (local < a.cap_src) a.src_ids[(int64_t)g * a.src_stride + local] = u;      // (a frontier cut short: the block is marked invalid)
     if (a.direct) {
         reinterpret_cast<int32_t *>(table)[u] = local;
     } else {
@@ -934,6 +952,7 @@ __global__ __launch_bounds__(256) void relabel_kernel(DedupArgs a)
     uint32_t local;
     if (a.direct) local = (uint32_t)reinterpret_cast<const int32_t *>(table)[u];
     else table_find(table, a.table_bits, (uint32_t)u, local);
+    if (local >= (uint32_t)a.cap_src) local = 0;       // only in a block that is marked invalid: keeps every later access in range
     a.indices[(int64_t)g * a.indices_stride + rstart + j] = (int32_t)local;
     if (a.gather_ids) a.gather_ids[(int64_t)g * a.indices_stride + rstart + j] = u;
     if (a.tcount) atomicAdd(&a.tcount[(int64_t)g * a.t_stride + local], 1);
@@ -1160,9 +1179,18 @@ extern "C" cr_status cr_sample_blocks(const cr_graph *graph, const cr_sample_cfg
         const cr_block_set &b = layers[l];
         CR_REQUIRE(b.n_batches == n_batches && b.fanout == cfg->fanout[l], CR_ERR_INVALID_ARG,
                    "layers[%d]: n_batches / fanout do not match the request", l);
-        CR_REQUIRE(b.cap_dst >= p.cap_dst[l] && b.cap_src >= p.cap_src[l] && b.cap_nnz >= p.cap_nnz[l], CR_ERR_CAPACITY,
-                   "layers[%d]: capacities (%d, %d, %d) below the bound (%d, %d, %d)", l, b.cap_dst, b.cap_src, b.cap_nnz,
-                   p.cap_dst[l], p.cap_src[l], p.cap_nnz[l]);
+        if (!(cfg->flags & CR_SAMPLE_SMALL_FRONTIER)) {
+            CR_REQUIRE(b.cap_dst >= p.cap_dst[l] && b.cap_src >= p.cap_src[l] && b.cap_nnz >= p.cap_nnz[l], CR_ERR_CAPACITY,
+                       "layers[%d]: capacities (%d, %d, %d) below the bound (%d, %d, %d)", l, b.cap_dst, b.cap_src, b.cap_nnz,
+                       p.cap_dst[l], p.cap_src[l], p.cap_nnz[l]);
+        } else {
+            // the rows of layer l are the frontier of layer l+1, which is cut at that layer's cap_src
+            const int64_t rows = l == p.L - 1 ? (int64_t)batch_size
+                                              : (layers[l + 1].cap_src < p.cap_dst[l] ? layers[l + 1].cap_src : p.cap_dst[l]);
+            CR_REQUIRE(b.cap_dst >= rows && b.cap_src >= b.cap_dst && (int64_t)b.cap_nnz >= rows * cfg->fanout[l], CR_ERR_CAPACITY,
+                       "layers[%d]: capacities (%d, %d, %d) cannot hold %lld rows of fanout %d and their own ids", l, b.cap_dst,
+                       b.cap_src, b.cap_nnz, (long long)rows, cfg->fanout[l]);
+        }
         CR_REQUIRE(b.hdr && b.src_ids && b.indptr && b.indices, CR_ERR_INVALID_ARG, "layers[%d] has a NULL array", l);
         CR_REQUIRE((b.t_indptr == nullptr) == (b.t_indices == nullptr), CR_ERR_INVALID_ARG,
                    "layers[%d]: t_indptr and t_indices must be given together", l);
@@ -1228,7 +1256,7 @@ extern "C" cr_status cr_sample_blocks(const cr_graph *graph, const cr_sample_cfg
             so.prev_hdr = prev_hdr; so.n_roots_total = n_roots_total; so.batch_size = batch_size;
             so.mode = 3; so.n_fixed = n_cells; so.in = p.order_hist; so.in_stride = n_cells + 1; so.out = p.order_cursor;
             so.out_stride = n_cells + 1; so.out_copy = nullptr; so.copy_stride = 0; so.hdr = b.hdr;
-            so.tile_before = nullptr;
+            so.tile_before = nullptr; so.cap_src = 0; so.async_status = nullptr;
             const int scan_tiles = (int)ceil_div(n_cells, SCAN_TILE);
             if (grouped && scan_tiles > 8 && scan_tiles <= 16384) {
                 hipLaunchKernelGGL(scan_tile_sums_kernel, dim3((unsigned)scan_tiles), dim3(SCAN_THREADS), 0, s, p.order_hist, n_cells, p.order_tiles);
@@ -1244,6 +1272,7 @@ extern "C" cr_status cr_sample_blocks(const cr_graph *graph, const cr_sample_cfg
         sc.prev_hdr = prev_hdr; sc.n_roots_total = n_roots_total; sc.batch_size = batch_size;
         sc.mode = 0; sc.in = p.cnt; sc.in_stride = p.max_dst; sc.out = b.indptr; sc.out_stride = b.cap_dst + 1;
         sc.out_copy = nullptr; sc.copy_stride = 0; sc.hdr = b.hdr;
+        sc.cap_src = b.cap_src; sc.async_status = async_status();
         const dim3 scan_grid((unsigned)ceil_div(cap_dst, SCAN_TILE), n_batches);
         hipLaunchKernelGGL(scan_kernel, scan_grid, dim3(SCAN_THREADS), 0, s, sc);
 
@@ -1253,7 +1282,7 @@ extern "C" cr_status cr_sample_blocks(const cr_graph *graph, const cr_sample_cfg
         da.dst_ids = dst_ids; da.dst_stride = dst_stride; da.sel = p.sel; da.sel_stride = p.max_nnz;
         da.direct = p.direct ? 1 : 0;
         da.table = p.table; da.table_stride = p.table_stride; da.table_bits = p.table_bits[l];
-        da.hdr = b.hdr; da.src_ids = b.src_ids; da.src_stride = b.cap_src;
+        da.hdr = b.hdr; da.src_ids = b.src_ids; da.src_stride = b.cap_src; da.cap_src = b.cap_src; da.async_status = async_status();
         da.indptr = b.indptr; da.indptr_stride = b.cap_dst + 1; da.indices = b.indices; da.indices_stride = b.cap_nnz; da.gather_ids = b.gather_ids;
         da.newcnt = p.cnt; da.newoff = p.newoff; da.newmask = p.newmask; da.row_stride = p.max_dst; da.off_stride = p.max_dst + 1;
         const dim3 grid((unsigned)ceil_div((int64_t)cap_dst * da.gw, 256), n_batches);

@@ -22,7 +22,7 @@ def parse_setting(text: str, n_comm_train: int):
     if pol == "norand":
         return B.CR_ROOTS_NORAND, 1, p
     if pol.startswith("mix"):
-        return B.CR_ROOTS_COMM_RAND, synth.mix_count_from_percent(float(pol[3:]), n_comm_train), p
+        return B.CR_ROOTS_COMM_RAND, B.cr_mix_count_from_percent(float(pol[3:]), n_comm_train), p
     raise ValueError(f"unknown root policy '{pol}'")
 
 

@@ -258,12 +258,6 @@ def init_gat_weights(cfg: WorkloadConfig, seed: int = 0, heads: int = 4):
     return out
 
 
-def mix_count_from_percent(k_percent: float, n_comm_in_train: int) -> int:
-    """Number of communities per super-block for COMM-RAND-MIX-k% (k% of the
-    communities present in the training set, at least one)."""
-    return max(1, int(np.floor(k_percent * n_comm_in_train / 100.0 + 0.5)))
-
-
 def star_graph(n_leaves_intra: int, n_leaves_inter: int):
     """Node 0 joined to n_leaves_intra leaves of its own community and
     n_leaves_inter leaves of another one (tiny closed-form test graph)."""

@@ -84,6 +84,9 @@ class Trainer:
                 self.table = torch.from_numpy(np.ascontiguousarray(feats.view(np.int16) if is_bf16 else feats)).to(device)
             self.table_ptr = C.c_void_p(self.table.data_ptr())
         self.graph = B.make_graph(self.indptr, self.indices, self.comm, cfg.n_comm)
+        # context of this trainer's calls: kernels record data-dependent overflows in its device status words
+        self.ctx = B.Context(device=torch.device(device).index or 0, status=torch.zeros(B.CR_CTX_STATUS_WORDS, dtype=torch.int64, device=device))
+        self.ctx.make_current()
         if edge_classes:     # static per graph: one bit per adjacency entry, read by the biased selection
             self.edge_bits = B.cr_graph_edge_classes(self.graph)
             self.graph.edge_intra = self.edge_bits.data_ptr()
@@ -213,6 +216,7 @@ class Trainer:
         """Samples mini-batches first_batch .. first_batch+n_batches-1 of the current permutation into
         block storage `slot` (on the current stream)."""
         assert 1 <= n_batches <= self.G
+        self.ctx.make_current()
         self.blocks = self.block_slots[slot]
         flags = self.sample_flags if flags is None else flags
         flags = self._apply_row_order(self.blocks[0], flags)
@@ -578,7 +582,8 @@ class Trainer:
         if n == 0:
             return float("nan"), float("nan")
         nb = -(-n // self.B)
-        losses = torch.zeros(nb, dtype=torch.float32, device=node_ids.device)
+        batch_loss = torch.zeros(1, dtype=torch.float32, device=node_ids.device)
+        mean_loss = torch.zeros(3, dtype=torch.float64, device=node_ids.device)     # sum of loss x rows, rows, mean over all rows
         correct = torch.zeros(1, dtype=torch.int32, device=node_ids.device)
         top_l = self.L - 1
         for first in range(0, nb, self.G):
@@ -596,13 +601,11 @@ class Trainer:
                 self.forward_batch(g, slot=0, buf=0)
                 top = self.block_slots[0][top_l]
                 B.cr_softmax_xent(top.hdr_ptr(g), top.cap_dst, self.out[top_l], self.layers[top_l].N_pad, self.cfg.n_classes,
-                                  self.labels, top.src_ids_ptr(g), losses[first + g:first + g + 1], self.row_loss)
+                                  self.labels, top.src_ids_ptr(g), batch_loss, self.row_loss)
+                B.cr_mean_accumulate(top.hdr_ptr(g), top.cap_dst, batch_loss, mean_loss)
                 B.cr_count_correct(top.hdr_ptr(g), top.cap_dst, self.out[top_l], self.layers[top_l].N_pad, self.cfg.n_classes,
                                    self.labels, top.src_ids_ptr(g), correct)
-        per_batch = losses.cpu().numpy().astype(np.float64)
-        sizes = np.full(nb, self.B, dtype=np.float64)
-        sizes[-1] = n - (nb - 1) * self.B
-        return float((per_batch * sizes).sum() / n), float(int(correct.cpu()[0]) / n)
+        return float(mean_loss.cpu()[2]), float(int(correct.cpu()[0]) / n)
 
     def fit(self, policy: int, mix_count: int, p_intra: float, val_ids, max_epochs: int = 100, patience: int = 6,
             lr_patience: int = 3, lr_factor: float = 0.1, first_epoch: int = 0):
@@ -624,11 +627,21 @@ class Trainer:
             hist.val_loss.append(vl)
             hist.val_acc.append(va)
             hist.lr.append(self.lr)
+            self.check_async_status()
             self.lr = sched.step(vl)
             if stop.step(vl, e):
                 hist.stopped_early = True
                 break
         return hist
+
+    def check_async_status(self):
+        """Polls what the kernels recorded since the last poll (one small read-back; once per epoch in fit): raises if a
+        sampled block did not fit its arrays or the feature cache dropped a request."""
+        st, required = self.ctx.poll_error()
+        if st != B.CR_OK:
+            raise B.CrError(st, f"{B.lib().cr_last_error().decode()} (required: {required})")
+        if self.cache is not None and self.cache.stats()[3] != 0:
+            raise B.CrError(B.CR_ERR_CAPACITY, "the feature cache's per-set miss lists overflowed")
 
     def input_node_stats(self, policy: int, mix_count: int, p_intra: float, epoch: int, max_groups: int = 4):
         """Distinct input nodes and gathered rows per batch over the first groups of an epoch (sampled once more

@@ -27,7 +27,8 @@ def test_library_exports_every_declared_function():
 
 def test_mix_count_from_percent():
     from paper_2504_18082_amd import binding as B
-    from paper_2504_18082_amd import synth
+    import math
+    # k percent of the communities present in the training set, rounded to nearest, at least one (Section 5, evaluated schemes)
     for k, c in ((0, 50), (12.5, 50), (25, 50), (50, 50), (100, 50), (12.5, 3), (50, 1), (12.5, 497)):
-        assert B.cr_mix_count_from_percent(k, c) == min(c, synth.mix_count_from_percent(k, c))
+        assert B.cr_mix_count_from_percent(k, c) == min(c, max(1, math.floor(k * c / 100.0 + 0.5)))
     assert B.cr_mix_count_from_percent(12.5, 50) == 6
