@@ -103,6 +103,9 @@ def lib():
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2504_18082_amd.build`")
+        # torch first: the library must bind to the HIP runtime that torch brings into the process (a second copy of the
+        # runtime, loaded from the system before torch's, sees no device)
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         vp, i32, i64, u64 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64
         L.cr_last_error.restype = C.c_char_p

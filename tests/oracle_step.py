@@ -8,8 +8,9 @@ Two compositions of the same pieces:
   mirror=True   additionally rounds what the GPU path STORES in bf16 between its kernels: hidden activations
                 (self operand, aggregation input, ReLU mask), the input gradients d_self / d_agg, and the bias
                 gradient summed from the rounded dZ.
-The GPU path is compared with both: with the mirror at the tight tolerance (only the accumulation order
-differs), with the plain composition at the bf16 tolerance (which bounds what the bf16 storage costs).
+The GPU path is compared with both: with the mirror at a tight tolerance (only the accumulation order differs, and
+bf16 values that sat on a rounding boundary), with the plain composition at the bf16 tolerance; a third composition in
+exact float64 (round_operands=False) measures how far each bf16 model is from the unrounded result.
 """
 import time
 
@@ -26,7 +27,7 @@ class StageTimers(dict):
 
 
 def oracle_forward(graph, table, n_feat, roots, fanouts, p, seed, epoch, batch, params, pos_map=None, strict=False,
-                   mirror=True, timers=None):
+                   mirror=True, timers=None, round_operands=True):
     """Sampling and forward pass only; returns (blocks, h_self, aggs, outs)."""
     L = len(fanouts)
     tm = timers if timers is not None else StageTimers()
@@ -50,19 +51,20 @@ def oracle_forward(graph, table, n_feat, roots, fanouts, p, seed, epoch, batch, 
             h_self[l] = outs[l - 1][:blk.n_dst]
             tm.add("gather_aggregate_fwd_hidden", t0)
         t0 = time.perf_counter()
-        outs[l] = oracle.sage_linear_fwd(h_self[l], aggs[l], W, b, l < L - 1, True)
+        outs[l] = oracle.sage_linear_fwd(h_self[l], aggs[l], W, b, l < L - 1, round_operands)
         tm.add("sage_linear_fwd", t0)
     return blocks, h_self, aggs, outs
 
 
 def oracle_train_step(graph, table, n_feat, labels, roots, fanouts, p, seed, epoch, batch, params, lr, wd,
-                      pos_map=None, strict=False, mirror=True, timers=None):
+                      pos_map=None, strict=False, mirror=True, timers=None, round_operands=True):
     """params: list of (W float64 [2F_in, F_out], b float64 [F_out]); returns dict with loss, logits,
-    grads and the updated params (inputs are not modified)."""
+    grads and the updated params (inputs are not modified).  round_operands=False (with mirror=False) is the step in
+    exact float64 arithmetic, nothing rounded anywhere: the yardstick for what each bf16 model costs in accuracy."""
     L = len(fanouts)
     tm = timers if timers is not None else StageTimers()
     blocks, h_self, aggs, outs = oracle_forward(graph, table, n_feat, roots, fanouts, p, seed, epoch, batch, params, pos_map, strict,
-                                                mirror, tm)
+                                                mirror, tm, round_operands)
     t0 = time.perf_counter()
     loss, dz = oracle.softmax_xent(outs[L - 1], labels[np.asarray(roots)])
     tm.add("softmax_xent", t0)
@@ -70,7 +72,7 @@ def oracle_train_step(graph, table, n_feat, labels, roots, fanouts, p, seed, epo
     for l in range(L - 1, -1, -1):
         W, b = params[l]
         t0 = time.perf_counter()
-        dW, db, d_self, d_agg = oracle.sage_linear_bwd(h_self[l], aggs[l], W, outs[l], dz, False, True, need_dx=l > 0)
+        dW, db, d_self, d_agg = oracle.sage_linear_bwd(h_self[l], aggs[l], W, outs[l], dz, False, round_operands, need_dx=l > 0)
         if mirror:
             db = oracle.round_bf16(dz).sum(axis=0)          # the GPU sums the operand it feeds the matrix cores
         grads[l] = (dW, db)

@@ -7,7 +7,7 @@ import pytest
 
 import oracle
 from paper_2504_18082_amd import synth
-from gpu_util import assert_close, bf16_tensor_to_float
+from gpu_util import assert_close, assert_weight_step, bf16_tensor_to_float
 
 pytestmark = pytest.mark.gpu
 RTOL = 1e-4
@@ -194,6 +194,8 @@ def test_gat_train_steps_match_oracle(tiny_workload):
         for g in range(n):
             b = done + g
             print(f"gat step batch={b}", flush=True)
+            W_before = [l.W.cpu().numpy() for l in tr.layers]
+            attn_before = [tr.gat[l].attn.cpu().numpy() for l in range(tr.L)]
             tr.train_batch(g, dW_out, None, d_attn_out=d_attn)
             torch.cuda.synchronize()
             roots = perm[b * cfg.batch_size:(b + 1) * cfg.batch_size]
@@ -212,10 +214,11 @@ def test_gat_train_steps_match_oracle(tiny_workload):
                 assert_close(ga[0, :HD], d_al, 2e-2, f"d a_l layer {l} batch {b}")
                 assert_close(ga[1, :HD], d_ar, 2e-2, f"d a_r layer {l} batch {b}")
                 assert_close(ga[2, :HD], d_b, 2e-2, f"d bias layer {l} batch {b}")
-                assert_close(tr.layers[l].W.cpu().numpy(), ref["params"][l][0], 2e-2, f"W layer {l} batch {b}")
+                assert_weight_step(tr.layers[l].W.cpu().numpy(), W_before[l], ref["params"][l][0], params[l][0], 2e-2, f"W change layer {l} batch {b}")
                 new = tr.gat[l].attn.cpu().numpy()
                 for k in range(3):
-                    assert_close(new[k, :HD], ref["params"][l][1 + k], 2e-2, f"attn[{k}] layer {l} batch {b}")
+                    assert_weight_step(new[k, :HD], attn_before[l][k, :HD], ref["params"][l][1 + k], params[l][1 + k], 2e-2,
+                                       f"attn[{k}] change layer {l} batch {b}")
             params = [(tr.layers[l].W.cpu().numpy().astype(np.float64),) +
                       tuple(tr.gat[l].attn.cpu().numpy()[k, :tr.layers[l].F_out].astype(np.float64) for k in range(3))
                       for l in range(tr.L)]

@@ -4,9 +4,10 @@ import pytest
 
 import oracle
 from paper_2504_18082_amd import synth
-from gpu_util import assert_close, bf16_tensor_to_float
+from gpu_util import assert_close, assert_weight_step, bf16_tensor_to_float
 
 pytestmark = pytest.mark.gpu
+RTOL_STEP = 4e-3
 RTOL = 1e-5
 RTOL_BF16 = 2.0 ** -8
 
@@ -133,16 +134,20 @@ def test_gcn_train_steps_match_oracle(tiny_workload):
         for g in range(n):
             b = done + g
             print(f"gcn step batch={b}", flush=True)
+            W_before = [l.W.cpu().numpy() for l in tr.layers]
             tr.train_batch(g, dW_out, db_out)
             torch.cuda.synchronize()
             roots = perm[b * cfg.batch_size:(b + 1) * cfg.batch_size]
             ref = oracle_train_step_gcn(w.graph, w.features, cfg.n_feat, w.labels, roots, cfg.fanouts, p, seed, epoch, b, params, lr, wd, pos)
             assert abs(float(tr.loss.cpu()[0]) - ref["loss"]) <= 1e-3 * abs(ref["loss"])
-            assert_close(tr.out[tr.L - 1].cpu().numpy()[:len(roots), :cfg.n_classes], ref["logits"], 2e-2, f"logits batch {b}")
+            # the oracle step rounds what the GPU path stores in bf16, so what is left is accumulation order and bf16 values
+            # that sat on a rounding boundary: far inside the bf16 tolerance of 2e-2
+            assert_close(tr.out[tr.L - 1].cpu().numpy()[:len(roots), :cfg.n_classes], ref["logits"], RTOL_STEP, f"logits batch {b}")
             for l in range(tr.L):
-                assert_close(dW_out[l].cpu().numpy(), ref["grads"][l][0], 2e-2, f"dW layer {l} batch {b}")
-                assert_close(db_out[l].cpu().numpy(), ref["grads"][l][1], 2e-2, f"db layer {l} batch {b}")
-                assert_close(tr.layers[l].W.cpu().numpy(), ref["params"][l][0], 2e-2, f"W layer {l} batch {b}")
+                assert_close(dW_out[l].cpu().numpy(), ref["grads"][l][0], RTOL_STEP, f"dW layer {l} batch {b}")
+                assert_close(db_out[l].cpu().numpy(), ref["grads"][l][1], RTOL_STEP, f"db layer {l} batch {b}")
+                assert_weight_step(tr.layers[l].W.cpu().numpy(), W_before[l], ref["params"][l][0], params[l][0], RTOL_STEP,
+                                   f"W change layer {l} batch {b}")
             params = [(l.W.cpu().numpy().astype(np.float64), l.bias.cpu().numpy()[:l.F_out].astype(np.float64)) for l in tr.layers]
         done += n
 

@@ -5,16 +5,30 @@ import pytest
 
 import oracle
 from paper_2504_18082_amd import synth
-from gpu_util import assert_close
+from gpu_util import assert_close, assert_weight_step
 from oracle_step import oracle_train_step
 
 pytestmark = pytest.mark.gpu
-RTOL_BF16 = 2e-2
+RTOL_BF16 = 2e-2        # against the plain composition: bf16 operands into the products, float64 everywhere between them
+RTOL_MIRROR = 4e-3      # against the composition that also rounds what the GPU path stores in bf16 between its kernels: what
+                        # is left is float accumulation order, and bf16 values that sat on a rounding boundary (one bf16
+                        # step, 2^-8 relative, on a few activations, carried through the layers above)
+WORST = {}              # worst observed error per tensor kind and composition, printed by the tests
 
 
-def run_case(w, policy, mix, p, n_steps, group, lr=0.05, wd=5e-4, seed=0, epoch=3, relabel_input=False):
+def _note(kind, mirror, err):
+    key = (kind, "mirror" if mirror else "plain")
+    WORST[key] = max(WORST.get(key, 0.0), err)
+
+
+def run_case(w, policy, mix, p, n_steps, group, lr=0.05, wd=5e-4, seed=0, epoch=3, relabel_input=False, deep=False):
+    """deep=True (the three-layer, 256-wide model): the weight gradients of the lower layers are sums of ~60 K heavily
+    cancelling terms, and two bf16 roundings of the same terms differ, element by element, by more than 2e-2 of such a
+    sum; there the comparison with the plain composition is taken in the root-mean-square sense, and both are measured
+    against the step in exact float64 arithmetic: the GPU path must be no further from it than the plain composition."""
     import torch
     from paper_2504_18082_amd.trainer import Trainer
+    from gpu_util import frac_outside, rms_rel_err, worst_rel_err
     cfg = w.cfg
     weights = synth.init_weights(cfg, seed)
     tr = Trainer(w, group_size=group, lr=lr, weight_decay=wd, seed=seed, weights=weights, relabel_input=relabel_input)
@@ -33,27 +47,56 @@ def run_case(w, policy, mix, p, n_steps, group, lr=0.05, wd=5e-4, seed=0, epoch=
         for g in range(n):
             b = done + g
             print(f"step batch={b} policy={policy} p={p}", flush=True)
+            W_before = [l.W.cpu().numpy().astype(np.float64) for l in tr.layers]
             tr.train_batch(g, dW_out, db_out)
             torch.cuda.synchronize()
             roots = want_perm[b * cfg.batch_size:(b + 1) * cfg.batch_size]
-            ref = oracle_train_step(w.graph, w.features, cfg.n_feat, w.labels, roots, cfg.fanouts, p, seed, epoch, b,
-                                    params, lr, wd, pos)
-            hdrs = tr.headers()
-            for l in range(tr.L):
-                n_src = -1 if l == 0 and not relabel_input else ref["blocks"][l].n_src     # input frontier not counted by default
-                assert hdrs[l][g].tolist() == [ref["blocks"][l].n_dst, n_src, ref["blocks"][l].nnz, 0]
-            assert abs(float(tr.loss.cpu()[0]) - ref["loss"]) <= RTOL_BF16 * abs(ref["loss"])
-            assert abs(float(tr.loss.cpu()[0]) - ref["loss"]) <= 1e-3 * abs(ref["loss"])       # in practice far tighter
             n_roots = len(roots)
+            loss = float(tr.loss.cpu()[0])
             logits = tr.out[tr.L - 1].cpu().numpy()[:n_roots, :cfg.n_classes]
-            assert_close(logits, ref["logits"], RTOL_BF16, f"logits batch {b}")
-            for l in range(tr.L):
-                assert_close(dW_out[l].cpu().numpy(), ref["grads"][l][0], RTOL_BF16, f"dW layer {l} batch {b}")
-                assert_close(db_out[l].cpu().numpy(), ref["grads"][l][1], RTOL_BF16, f"db layer {l} batch {b}")
-                assert_close(tr.layers[l].W.cpu().numpy(), ref["params"][l][0], RTOL_BF16, f"W layer {l} batch {b}")
+            hdrs = tr.headers()
+            exact = None
+            if deep:
+                exact = oracle_train_step(w.graph, w.features, cfg.n_feat, w.labels, roots, cfg.fanouts, p, seed, epoch, b,
+                                          params, lr, wd, pos, mirror=False, round_operands=False)
+            for mirror, rtol in ((True, RTOL_MIRROR), (False, RTOL_BF16)):
+                ref = oracle_train_step(w.graph, w.features, cfg.n_feat, w.labels, roots, cfg.fanouts, p, seed, epoch, b,
+                                        params, lr, wd, pos, mirror=mirror)
+                elementwise = mirror or not deep
+                for l in range(tr.L):
+                    n_src = -1 if l == 0 and not relabel_input else ref["blocks"][l].n_src     # input frontier not counted by default
+                    assert hdrs[l][g].tolist() == [ref["blocks"][l].n_dst, n_src, ref["blocks"][l].nnz, 0]
+                assert abs(loss - ref["loss"]) <= (1e-3 if mirror else RTOL_BF16) * abs(ref["loss"])
+                _note("loss", mirror, abs(loss - ref["loss"]) / abs(ref["loss"]))
+                assert_close(logits, ref["logits"], rtol, f"logits batch {b} mirror={mirror}")
+                _note("logits", mirror, worst_rel_err(logits, ref["logits"]))
+                for l in range(tr.L):
+                    dW, db = dW_out[l].cpu().numpy(), db_out[l].cpu().numpy()
+                    _note("dW", mirror, worst_rel_err(dW, ref["grads"][l][0]))
+                    _note("db", mirror, worst_rel_err(db, ref["grads"][l][1]))
+                    if not elementwise:
+                        # two bf16 models of one cancelling sum: close in the root-mean-square sense, and the GPU path is as
+                        # close to the exact float64 step as the plain composition is
+                        for name, got, k in (("dW", dW, 0), ("db", db, 1)):
+                            e_plain = rms_rel_err(got, ref["grads"][l][k])
+                            e_gpu_exact = rms_rel_err(got, exact["grads"][l][k])
+                            e_plain_exact = rms_rel_err(ref["grads"][l][k], exact["grads"][l][k])
+                            print(f"{name} layer {l}: rms |gpu - plain| / rms = {e_plain:.4f}, outside 2e-2 element-wise: "
+                                  f"{frac_outside(got, ref['grads'][l][k], rtol):.4f}; against exact float64: gpu {e_gpu_exact:.4f}, "
+                                  f"plain composition {e_plain_exact:.4f}", flush=True)
+                            assert e_plain <= rtol, (name, l, e_plain)
+                            assert e_gpu_exact <= 1.1 * e_plain_exact + 1e-4, (name, l, e_gpu_exact, e_plain_exact)
+                        continue
+                    assert_close(dW, ref["grads"][l][0], rtol, f"dW layer {l} batch {b} mirror={mirror}")
+                    assert_close(db, ref["grads"][l][1], rtol, f"db layer {l} batch {b} mirror={mirror}")
+                    # the SGD step itself: the CHANGE of the master weights against the oracle's change (the weights
+                    # themselves would pass for any gradient: lr * dW is far below the tolerance times |W|)
+                    assert_weight_step(tr.layers[l].W.cpu().numpy(), W_before[l], ref["params"][l][0], params[l][0], rtol,
+                                       f"W change layer {l} batch {b} mirror={mirror}")
             # keep the two trajectories on the same weights: continue the oracle from the GPU's master copy
             params = [(l.W.cpu().numpy().astype(np.float64), l.bias.cpu().numpy()[:l.F_out].astype(np.float64)) for l in tr.layers]
         done += n
+    print("worst |a-b| / (|b| + rms b) so far:", {f"{k[0]}/{k[1]}": float(f"{v:.3g}") for k, v in sorted(WORST.items())}, flush=True)
     return tr
 
 
@@ -88,14 +131,14 @@ def test_last_short_batch(tiny_workload):
     assert tr.headers()[tr.L - 1][1][0] == n_last
     assert abs(float(tr.loss.cpu()[0]) - ref["loss"]) <= 1e-3 * abs(ref["loss"])
     for l in range(tr.L):
-        assert_close(tr.layers[l].W.cpu().numpy(), ref["params"][l][0], RTOL_BF16, f"W layer {l}")
+        assert_weight_step(tr.layers[l].W.cpu().numpy(), params[l][0], ref["params"][l][0], params[l][0], RTOL_MIRROR, f"W change layer {l}")
 
 
 def test_arxiv_one_step_three_layers(arxiv_workload):
     # 3 layers, hidden 256, batch 1024: ~60K rows at layer 0 (oracle: a few seconds)
     import copy
     w = copy.copy(arxiv_workload)
-    tr = run_case(w, oracle.COMM_RAND, 62, 1.0, n_steps=1, group=2, lr=0.01)
+    tr = run_case(w, oracle.COMM_RAND, 62, 1.0, n_steps=1, group=2, lr=0.01, deep=True)
     assert tr.L == 3
 
 
