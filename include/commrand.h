@@ -256,6 +256,13 @@ cr_status cr_block_capacities(const cr_sample_cfg *cfg, int64_t n_nodes, int32_t
 cr_status cr_sample_blocks_workspace_bytes(const cr_sample_cfg *cfg, int64_t n_nodes, int32_t batch_size,
                                            int32_t n_batches, size_t *bytes /*host*/);
 
+/* Which frontier de-duplication table cr_sample_blocks will use for this request (same results either way): one int32
+ * per node and batch, addressed by node id (CR_DEDUP_DIRECT: graphs up to four times the largest table), or an
+ * open-addressing table of twice the largest frontier (CR_DEDUP_HASH: larger graphs, or CR_SAMPLE_HASH_DEDUP). */
+#define CR_DEDUP_DIRECT 0
+#define CR_DEDUP_HASH 1
+cr_status cr_sample_blocks_dedup_table(const cr_sample_cfg *cfg, int64_t n_nodes, int32_t batch_size, int32_t *kind /*host*/);
+
 /* Samples the blocks of n_batches consecutive mini-batches in one set of launches.
  *   roots : device int32[n_roots_total]: the slice of the epoch's permutation that starts at
  *           mini-batch cfg->first_batch; batch g of the group is roots[g*batch_size ..

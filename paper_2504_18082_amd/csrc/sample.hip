@@ -1144,6 +1144,16 @@ extern "C" cr_status cr_sample_blocks_workspace_bytes(const cr_sample_cfg *cfg, 
     return CR_OK;
 }
 
+extern "C" cr_status cr_sample_blocks_dedup_table(const cr_sample_cfg *cfg, int64_t n_nodes, int32_t batch_size, int32_t *kind)
+{
+    SamplePlan p;
+    cr_status st = make_plan(cfg, n_nodes, batch_size, 1, nullptr, p);
+    if (st != CR_OK) return st;
+    CR_REQUIRE(kind != nullptr, CR_ERR_INVALID_ARG, "kind is NULL");
+    *kind = p.direct ? CR_DEDUP_DIRECT : CR_DEDUP_HASH;
+    return CR_OK;
+}
+
 extern "C" cr_status cr_graph_edge_classes(const cr_graph *graph, uint32_t *edge_intra, void *stream)
 {
     CR_REQUIRE(graph != nullptr, CR_ERR_INVALID_ARG, "graph is NULL");

@@ -27,8 +27,9 @@ class StageTimers(dict):
 
 
 def oracle_forward(graph, table, n_feat, roots, fanouts, p, seed, epoch, batch, params, pos_map=None, strict=False,
-                   mirror=True, timers=None, round_operands=True):
-    """Sampling and forward pass only; returns (blocks, h_self, aggs, outs)."""
+                   mirror=True, timers=None, round_operands=True, table_is_frontier=False):
+    """Sampling and forward pass only; returns (blocks, h_self, aggs, outs).  table_is_frontier: `table` holds the
+    feature rows of this batch's input frontier only, in frontier order (for graphs whose whole table is not on the host)."""
     L = len(fanouts)
     tm = timers if timers is not None else StageTimers()
     t0 = time.perf_counter()
@@ -40,7 +41,7 @@ def oracle_forward(graph, table, n_feat, roots, fanouts, p, seed, epoch, batch, 
         W, b = params[l]
         t0 = time.perf_counter()
         if l == 0:
-            aggs[0], h_self[0] = oracle.gather_mean(blk, table, indirect=True, F=n_feat, want_self=True)
+            aggs[0], h_self[0] = oracle.gather_mean(blk, table, indirect=not table_is_frontier, F=n_feat, want_self=True)
             tm.add("gather_aggregate_fwd_layer0", t0)
         else:
             if mirror:      # hidden activations live in bf16 on the GPU
@@ -57,20 +58,21 @@ def oracle_forward(graph, table, n_feat, roots, fanouts, p, seed, epoch, batch, 
 
 
 def oracle_train_step(graph, table, n_feat, labels, roots, fanouts, p, seed, epoch, batch, params, lr, wd,
-                      pos_map=None, strict=False, mirror=True, timers=None, round_operands=True):
+                      pos_map=None, strict=False, mirror=True, timers=None, round_operands=True, table_is_frontier=False):
     """params: list of (W float64 [2F_in, F_out], b float64 [F_out]); returns dict with loss, logits,
     grads and the updated params (inputs are not modified).  round_operands=False (with mirror=False) is the step in
     exact float64 arithmetic, nothing rounded anywhere: the yardstick for what each bf16 model costs in accuracy."""
     L = len(fanouts)
     tm = timers if timers is not None else StageTimers()
     blocks, h_self, aggs, outs = oracle_forward(graph, table, n_feat, roots, fanouts, p, seed, epoch, batch, params, pos_map, strict,
-                                                mirror, tm, round_operands)
+                                                mirror, tm, round_operands, table_is_frontier)
     t0 = time.perf_counter()
     loss, dz = oracle.softmax_xent(outs[L - 1], labels[np.asarray(roots)])
     tm.add("softmax_xent", t0)
-    grads, new_params = [None] * L, [None] * L
+    grads, new_params, dzs = [None] * L, [None] * L, [None] * L
     for l in range(L - 1, -1, -1):
         W, b = params[l]
+        dzs[l] = dz
         t0 = time.perf_counter()
         dW, db, d_self, d_agg = oracle.sage_linear_bwd(h_self[l], aggs[l], W, outs[l], dz, False, round_operands, need_dx=l > 0)
         if mirror:
@@ -85,7 +87,8 @@ def oracle_train_step(graph, table, n_feat, labels, roots, fanouts, p, seed, epo
             d_src = oracle.gather_mean_bwd(blocks[l], d_agg, d_self)
             dz = d_src * ((oracle.round_bf16(outs[l - 1]) if mirror else outs[l - 1]) > 0)
             tm.add("gather_aggregate_bwd", t0)
-    return dict(blocks=blocks, loss=loss, logits=outs[L - 1], outs=outs, grads=grads, params=new_params, timers=tm)
+    return dict(blocks=blocks, loss=loss, logits=outs[L - 1], outs=outs, grads=grads, params=new_params, timers=tm, dzs=dzs,
+                h_self=h_self, aggs=aggs)
 
 
 def oracle_train_step_gcn(graph, table, n_feat, labels, roots, fanouts, p, seed, epoch, batch, params, lr, wd, pos_map=None):

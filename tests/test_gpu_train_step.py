@@ -10,9 +10,10 @@ from oracle_step import oracle_train_step
 
 pytestmark = pytest.mark.gpu
 RTOL_BF16 = 2e-2        # against the plain composition: bf16 operands into the products, float64 everywhere between them
-RTOL_MIRROR = 4e-3      # against the composition that also rounds what the GPU path stores in bf16 between its kernels: what
+RTOL_MIRROR = 1e-2      # against the composition that also rounds what the GPU path stores in bf16 between its kernels: what
                         # is left is float accumulation order, and bf16 values that sat on a rounding boundary (one bf16
-                        # step, 2^-8 relative, on a few activations, carried through the layers above)
+                        # step, 2^-8 relative, on a few per cent of the stored values, carried through the layers above)
+RMS_MIRROR = 3e-3       # the same comparison in the root-mean-square sense (difference over the tensor's rms)
 WORST = {}              # worst observed error per tensor kind and composition, printed by the tests
 
 
@@ -70,6 +71,13 @@ def run_case(w, policy, mix, p, n_steps, group, lr=0.05, wd=5e-4, seed=0, epoch=
                 _note("loss", mirror, abs(loss - ref["loss"]) / abs(ref["loss"]))
                 assert_close(logits, ref["logits"], rtol, f"logits batch {b} mirror={mirror}")
                 _note("logits", mirror, worst_rel_err(logits, ref["logits"]))
+                if mirror:
+                    rms = {"logits": rms_rel_err(logits, ref["logits"])}
+                    for l in range(tr.L):
+                        rms[f"dW{l}"] = rms_rel_err(dW_out[l].cpu().numpy(), ref["grads"][l][0])
+                        rms[f"db{l}"] = rms_rel_err(db_out[l].cpu().numpy(), ref["grads"][l][1])
+                    _note("rms", mirror, max(rms.values()))
+                    assert max(rms.values()) <= RMS_MIRROR, rms
                 for l in range(tr.L):
                     dW, db = dW_out[l].cpu().numpy(), db_out[l].cpu().numpy()
                     _note("dW", mirror, worst_rel_err(dW, ref["grads"][l][0]))
