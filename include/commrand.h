@@ -545,7 +545,7 @@ cr_status cr_mean_accumulate(const int32_t *hdr, int32_t max_rows, const float *
  * After a fetch, rows[slot_out[i]] holds the feature row of ids[i] for every i, so the feature gather can read the
  * cache's row array through slot_out in place of the store through the node ids.  All arrays are the caller's. */
 #define CR_CACHE_MAX_WAYS 64
-#define CR_CACHE_LIST_CAP 32 /* misses one set can take in one batch; more raise counters[3] (use more sets) */
+#define CR_CACHE_LIST_CAP 64 /* entries of a set's scratch list (the earliest CR_CACHE_MAX_WAYS misses of the batch) */
 
 typedef struct {
     int32_t n_sets;     /* >= 1 */
@@ -556,10 +556,10 @@ typedef struct {
     int32_t *stamps;    /* device int32[n_sets*ways]: stamp of the last batch that used the row, or -1 */
     void *rows;         /* device [(n_sets*ways + n_overflow)][row_bytes], 16-byte aligned */
     int32_t *set_count; /* device int32[n_sets]: scratch, zero between calls */
-    int32_t *set_list;  /* device int32[n_sets][CR_CACHE_LIST_CAP]: scratch */
+    int32_t *set_list;  /* device int32[n_sets][CR_CACHE_LIST_CAP]: scratch, kept by cr_cache_reset / cr_cache_fetch */
     int32_t *counters;  /* device int32[8], cumulative since cr_cache_reset: [0] look-ups, [1] misses, [2] misses that
-                           went to the overflow area, [3] nonzero = a set took more than CR_CACHE_LIST_CAP misses in
-                           one batch (results invalid); [4..7] unused */
+                           went to the overflow area (any number of misses per set and batch is handled); [3..7]
+                           unused, zero */
 } cr_feature_cache;
 
 /* Empties the cache and zeroes its scratch and counters. */

@@ -68,7 +68,7 @@ class cr_feature_cache(C.Structure):
                 ("set_list", C.c_void_p), ("counters", C.c_void_p)]
 
 
-CR_CACHE_LIST_CAP = 32
+CR_CACHE_LIST_CAP = 64
 
 
 class cr_block_set(C.Structure):

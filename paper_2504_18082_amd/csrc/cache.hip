@@ -6,7 +6,7 @@
 
 namespace cr {
 
-constexpr int CNT_QUERIES = 0, CNT_MISSES = 1, CNT_UNCACHED = 2, CNT_STATUS = 3;
+constexpr int CNT_QUERIES = 0, CNT_MISSES = 1, CNT_UNCACHED = 2;
 
 struct CacheArgs {
     cr_feature_cache c;
@@ -19,8 +19,25 @@ struct CacheArgs {
     int32_t *slot_out;
 };
 
-// GW lanes (a power of two >= ways) look one node up: lane w compares way w.  A miss is appended to its set's
-// list (one atomic per miss, on the set's own counter).
+constexpr int32_t NO_POS = 0x7FFFFFFF;       // an empty entry of a set's list
+
+// copies one feature row from the store into row `slot` of the cache's row array, by the GW lanes of a group
+template <int GW>
+__device__ __forceinline__ void copy_row(const CacheArgs &a, int32_t id, int32_t slot, int w)
+{
+    const int chunks = a.c.row_bytes / 16;
+    for (int c = w; c < chunks; c += GW) {
+        const uint4 v = *reinterpret_cast<const uint4 *>(a.store + (int64_t)id * a.store_ld + (int64_t)c * 16);
+        *reinterpret_cast<uint4 *>(static_cast<char *>(a.c.rows) + (int64_t)slot * a.c.row_bytes + (int64_t)c * 16) = v;
+    }
+}
+
+// GW lanes (a power of two >= ways) look one node up: lane w compares way w.  A set can give at most `ways` rows to the
+// misses of one batch, and by the replacement rule they go to the misses that come FIRST in the batch, so a set's list
+// keeps the `ways` smallest batch positions among its misses, whatever order the waves run in: a miss replaces the
+// list's largest entry if it is smaller (compare-and-swap on that entry; entries only ever decrease, so the entry that
+// was the largest when it was read still is when the swap succeeds).  A miss that cannot enter the list, or is pushed out
+// of it, is served from the overflow area: the group that finds this out writes its slot and copies its row right away.
 template <int GW>
 __global__ __launch_bounds__(256) void cache_lookup_kernel(CacheArgs a)
 {
@@ -40,16 +57,37 @@ __global__ __launch_bounds__(256) void cache_lookup_kernel(CacheArgs a)
             a.c.stamps[s0 + w] = a.stamp;
             a.slot_out[i] = (int32_t)(s0 + w);
         }
-    } else if (w == 0) {
-        const int r = atomicAdd(&a.c.set_count[set], 1);
-        if (r < CR_CACHE_LIST_CAP) a.c.set_list[(int64_t)set * CR_CACHE_LIST_CAP + r] = i;
-        else atomicOr(&a.c.counters[CNT_STATUS], 1);
+        return;
+    }
+    // a miss (the whole group takes this path together)
+    if (w == 0) atomicAdd(&a.c.set_count[set], 1);
+    int32_t *list = a.c.set_list + (int64_t)set * CR_CACHE_LIST_CAP;
+    int32_t out_pos = -1;                                   // batch position that goes to the overflow area, if any
+    for (;;) {
+        int32_t vmax = w < a.c.ways ? __hip_atomic_load(&list[w], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : -1;
+        int smax = w;
+#pragma unroll
+        for (int off = GW / 2; off; off >>= 1) {
+            const int32_t ov = __shfl_xor(vmax, off, GW);
+            const int os = __shfl_xor(smax, off, GW);
+            if (ov > vmax || (ov == vmax && os < smax)) { vmax = ov; smax = os; }
+        }
+        if (i > vmax) { out_pos = i; break; }               // `ways` earlier misses are listed already
+        int ok = 0;
+        if (w == 0) ok = atomicCAS(&list[smax], vmax, (int32_t)i) == vmax ? 1 : 0;
+        ok = __shfl(ok, 0, GW);
+        if (ok) { out_pos = vmax == NO_POS ? -1 : vmax; break; }
+    }
+    if (out_pos >= 0) {
+        const int32_t slot = a.c.n_sets * a.c.ways + out_pos;
+        if (w == 0) a.slot_out[out_pos] = slot;
+        copy_row<GW>(a, a.ids[out_pos], slot, w);
     }
 }
 
 // Replacement and row copies.  A fixed grid of waves walks the sets, 64 set counters per load; for a set that took
-// misses, the misses in batch order take the set's rows in (stamp, way) order, except rows used in this batch; what
-// is left over goes to the overflow area at the node's position in the batch.  The wave then copies its sets'
+// misses, the listed misses (the earliest `ways` of the batch) in batch order take the set's rows in (stamp, way) order,
+// except rows used in this batch; what is left over goes to the overflow area at the node's position in the batch.  The wave then copies its sets'
 // missing rows from the store, 16 bytes per lane.  Counters are accumulated per wave and added once.
 __global__ __launch_bounds__(256) void cache_resolve_kernel(CacheArgs a)
 {
@@ -68,10 +106,10 @@ __global__ __launch_bounds__(256) void cache_resolve_kernel(CacheArgs a)
             dirty &= dirty - 1;
             const int set = base + j;
             const int m_all = __builtin_amdgcn_readlane(my_cnt, j);
-            const int m = min(m_all, (int)CR_CACHE_LIST_CAP);
+            const int m = min(m_all, a.c.ways);              // the list holds the set's earliest misses, in its first m entries
             const int64_t s0 = (int64_t)set * a.c.ways;
 
-            const int pos = lane < m ? a.c.set_list[(int64_t)set * CR_CACHE_LIST_CAP + lane] : 0x7FFFFFFF;
+            const int pos = lane < m ? a.c.set_list[(int64_t)set * CR_CACHE_LIST_CAP + lane] : NO_POS;
             int miss_rank = 0;
             for (int t = 0; t < m; ++t) miss_rank += __builtin_amdgcn_readlane(pos, t) < pos ? 1 : 0;
 
@@ -100,8 +138,9 @@ __global__ __launch_bounds__(256) void cache_resolve_kernel(CacheArgs a)
             }
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // way_of_rank is reused for the next set
             if (lane == 0) a.c.set_count[set] = 0;
+            if (lane < m) a.c.set_list[(int64_t)set * CR_CACHE_LIST_CAP + lane] = NO_POS;
             misses += m_all;
-            uncached += m - min(m, n_avail);
+            uncached += m_all - min(m, n_avail);
 
             // copy the m rows: 64 / chunks rows per step when a row is at most 64 lanes wide
             if (chunks <= WAVE) {
@@ -150,6 +189,7 @@ __global__ __launch_bounds__(256) void cache_reset_kernel(cr_feature_cache c)
     const int64_t slots = (int64_t)c.n_sets * c.ways;
     if (i < slots) { c.keys[i] = -1; c.stamps[i] = -1; }
     if (i < c.n_sets) c.set_count[i] = 0;
+    if (i < (int64_t)c.n_sets * CR_CACHE_LIST_CAP) c.set_list[i] = NO_POS;
     if (i < 8) c.counters[i] = 0;
 }
 
@@ -175,7 +215,7 @@ extern "C" cr_status cr_cache_reset(const cr_feature_cache *cache, void *stream)
     cr_status st = check_cache(cache);
     if (st != CR_OK) return st;
     if (dry_run()) return CR_OK;
-    int64_t n = (int64_t)cache->n_sets * cache->ways;
+    int64_t n = (int64_t)cache->n_sets * CR_CACHE_LIST_CAP;       // >= n_sets * ways, the list array is the longest
     if (n < 8) n = 8;
     hipLaunchKernelGGL(cache_reset_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, static_cast<hipStream_t>(stream), *cache);
     CR_LAUNCH_CHECK();

@@ -636,12 +636,10 @@ class Trainer:
 
     def check_async_status(self):
         """Polls what the kernels recorded since the last poll (one small read-back; once per epoch in fit): raises if a
-        sampled block did not fit its arrays or the feature cache dropped a request."""
+        sampled block did not fit its arrays."""
         st, required = self.ctx.poll_error()
         if st != B.CR_OK:
             raise B.CrError(st, f"{B.lib().cr_last_error().decode()} (required: {required})")
-        if self.cache is not None and self.cache.stats()[3] != 0:
-            raise B.CrError(B.CR_ERR_CAPACITY, "the feature cache's per-set miss lists overflowed")
 
     def input_node_stats(self, policy: int, mix_count: int, p_intra: float, epoch: int, max_groups: int = 4):
         """Distinct input nodes and gathered rows per batch over the first groups of an epoch (sampled once more

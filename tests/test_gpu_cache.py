@@ -40,13 +40,17 @@ def run_trace(torch, B, batches, n_sets, ways, store, max_n, host_store=None):
         rows = cache.rows.cpu().numpy()
         assert np.array_equal(rows[got_slots], store[ids])                              # every node's row is where slot_out says
         assert not cache.set_count.cpu().numpy().any()                                  # scratch is clean again
+        assert np.all(cache.set_list.cpu().numpy() == 0x7FFFFFFF)
         q, m, u, status = cache.stats()
         assert (q, m, status) == (model.queries, model.misses, 0)
     return cache, model
 
 
+# the last three: far more misses per set and batch than a set has rows (4 sets x 4 ways taking 300 nodes: ~75 misses per set;
+# one set of 64 ways taking 1500; one way per set): only the earliest misses of the batch get rows, the rest are served from
+# the overflow area, and the cache's state still equals the model's bit for bit
 @pytest.mark.parametrize("n_sets,ways,universe,batch", [(64, 16, 3000, 300), (1, 64, 200, 20), (37, 1, 500, 40), (256, 32, 20000, 2000),
-                                                        (8, 4, 400, 60)])
+                                                        (8, 4, 400, 60), (4, 4, 5000, 300), (1, 64, 8000, 1500), (3, 1, 2000, 500)])
 def test_cache_matches_model(n_sets, ways, universe, batch):
     import torch
     from paper_2504_18082_amd import binding as B
