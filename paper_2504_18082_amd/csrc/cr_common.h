@@ -100,14 +100,16 @@ __device__ __forceinline__ uint64_t shuffle_key(uint64_t seed, uint32_t epoch, u
 
 __device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & (WAVE - 1)); }
 
-// bf16 <-> float on raw bit patterns, round to nearest even
-__device__ __forceinline__ uint16_t f32_to_bf16(float f)
+// float -> bf16 on raw bit patterns, round to nearest even, two values per instruction (gfx950 converts in hardware:
+// v_cvt_pk_bf16_f32; infinities stay, NaNs stay NaNs)
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
 {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7F800000u) == 0x7F800000u) return (uint16_t)(u >> 16);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    const f32x2_t x = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2_t));
 }
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) { return (uint16_t)(pack_bf16x2(f, 0.f) & 0xFFFFu); }
 __device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
 
 // Block ids are dealt round-robin to the 8 XCDs, each with its own L2.  Give every XCD one

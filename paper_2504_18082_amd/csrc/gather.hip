@@ -50,9 +50,8 @@ __device__ __forceinline__ void store_bf16_row(uint16_t *dst, const float (&v)[N
     uint32_t packed[N / 2];
 #pragma unroll
     for (int i = 0; i < N; i += 2) {
-        const uint16_t lo = (col + i < F) ? f32_to_bf16(v[i]) : (uint16_t)0;
-        const uint16_t hi = (col + i + 1 < F) ? f32_to_bf16(v[i + 1]) : (uint16_t)0;
-        packed[i / 2] = (uint32_t)lo | ((uint32_t)hi << 16);
+        const uint32_t both = pack_bf16x2(v[i], v[i + 1]);
+        packed[i / 2] = (col + i + 1 < F) ? both : ((col + i < F) ? (both & 0xFFFFu) : 0u);
     }
     if constexpr (N == 4) {
         *reinterpret_cast<uint2 *>(dst) = make_uint2(packed[0], packed[1]);

@@ -190,8 +190,8 @@ __device__ __forceinline__ void gemm_nt_body(const NtArgs &a, uint32_t bid, uint
         for (int t = 0; t < 2; ++t)
 #pragma unroll
             for (int grp = 0; grp < 4; ++grp) {
-                const uint32_t lo = (uint32_t)f32_to_bf16(v[t][grp][0]) | ((uint32_t)f32_to_bf16(v[t][grp][1]) << 16);
-                const uint32_t hi = (uint32_t)f32_to_bf16(v[t][grp][2]) | ((uint32_t)f32_to_bf16(v[t][grp][3]) << 16);
+                const uint32_t lo = pack_bf16x2(v[t][grp][0], v[t][grp][1]);
+                const uint32_t hi = pack_bf16x2(v[t][grp][2], v[t][grp][3]);
                 *reinterpret_cast<uint2 *>(&ob[lr][t * 32 + 8 * grp + 4 * half]) = make_uint2(lo, hi);
             }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -345,7 +345,7 @@ __global__ __launch_bounds__(256) void gemm_nt_small_kernel(NtArgs a, XentArgs x
     if (a.Cb && row_ok) {
         u32x4v xb;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) xb[i] = (uint32_t)f32_to_bf16(v[2 * i]) | ((uint32_t)f32_to_bf16(v[2 * i + 1]) << 16);
+        for (int i = 0; i < 4; ++i) xb[i] = pack_bf16x2(v[2 * i], v[2 * i + 1]);
         *reinterpret_cast<u32x4v *>(a.Cb + m * a.ldcb + n) = xb;
     }
     if constexpr (XENT) {
@@ -371,7 +371,7 @@ __global__ __launch_bounds__(256) void gemm_nt_small_kernel(NtArgs a, XentArgs x
             float d0 = 0.f, d1 = 0.f;
             if (n + 2 * i < C) d0 = (e[2 * i] / den - (n + 2 * i == label ? 1.f : 0.f)) * inv_n;
             if (n + 2 * i + 1 < C) d1 = (e[2 * i + 1] / den - (n + 2 * i + 1 == label ? 1.f : 0.f)) * inv_n;
-            dq[i] = (uint32_t)f32_to_bf16(d0) | ((uint32_t)f32_to_bf16(d1) << 16);
+            dq[i] = pack_bf16x2(d0, d1);
         }
         if (row_ok) *reinterpret_cast<u32x4v *>(x.d_logits_bf16 + m * 64 + n) = dq;
         if ((tid & 7) == 0) wg_loss[row] = 0.f;
@@ -408,6 +408,148 @@ __global__ __launch_bounds__(256) void gemm_nt_small_kernel(NtArgs a, XentArgs x
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// The same product for the input layer of the large workloads: tens of thousands of rows, K = 2 x 128 (self | aggregate,
+// 128 features each after padding), N = 256.  The tiled kernel above reads every activation row four times (once per
+// 64-column tile) and spends most of its time moving operands; here one workgroup per compute unit takes 256 rows and
+// ALL columns, so activations and weights pass through a compute unit once:
+//   - K is taken in its two natural halves (the self array against W_self, the aggregate array against W_neigh).  A
+//     half is 256 rows x 256 bytes of activations, one contiguous 64 KB block of the operand array, and 256 x 256 bytes
+//     of weights: both are fetched with fully coalesced 16-byte loads (16 per thread each) and laid out in LDS with rows
+//     padded by 16 bytes, so that the MFMA fragments are conflict-free 16-byte LDS reads;
+//   - the second half's loads are issued inside the first half's K loop, four per step, and travel under its MFMAs
+//     (issued in one go they hold the wave, the only one on its SIMD, for as long as the memory pipeline takes them);
+//   - a wave owns 64 rows x 256 columns (256 accumulator registers, one wave per SIMD): per 16-wide K step 10 fragment
+//     reads feed 16 MFMAs; the fragments of step s + 1 are requested before the MFMAs of step s are issued, because no
+//     other wave is there to hide the LDS latency;
+//   - the accumulators start from the bias; ReLU and the bf16 conversion happen on the way through LDS again, from
+//     where whole 512-byte rows leave.
+// ------------------------------------------------------------------------------------------------
+constexpr int WIDE_ROWS = 256;          // rows per workgroup
+constexpr int WIDE_KH = 128;            // K of one half
+constexpr int WIDE_N = 256;
+constexpr int WIDE_LROW = WIDE_KH + 8;  // staged row: 128 bf16 + 8 of padding (272 bytes)
+constexpr int WIDE_OROW = WIDE_N + 8;   // staged output row
+constexpr size_t WIDE_LDS_BYTES = (size_t)2 * 256 * WIDE_LROW * sizeof(uint16_t) + WIDE_N * sizeof(float);
+
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void gemm_nt_wide_kernel(NtArgs a)
+{
+    constexpr int KSTEPS = WIDE_KH / 16, NTILES = WIDE_N / 32, K = 2 * WIDE_KH;
+    extern __shared__ __attribute__((aligned(16))) uint16_t wide_lds[];
+    uint16_t *Ws = wide_lds;                                   // [256 n][WIDE_LROW]
+    uint16_t *As = wide_lds + 256 * WIDE_LROW;                 // [256 m][WIDE_LROW]
+    float *bias_s = reinterpret_cast<float *>(wide_lds + 2 * 256 * WIDE_LROW);
+    static_assert((size_t)4 * 64 * WIDE_OROW * sizeof(uint16_t) <= (size_t)2 * 256 * WIDE_LROW * sizeof(uint16_t), "output staging must fit");
+    const int M = min(a.hdr[CR_HDR_N_DST], a.max_rows);
+    const int m0 = (int)blockIdx.x * WIDE_ROWS;
+    if (m0 >= M) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int half = lane >> 5, lr = lane & 31;
+
+    // staging assignment: chunk c = i * 256 + tid of a half = (row c / 16, 16-byte piece c % 16)
+    const int srow = tid >> 4, spiece = tid & 15;
+    u32x4v wreg[16], areg[16];
+    auto fetch = [&](int h, int i) {     // pieces i of the half's 16 activation and 16 weight pieces of this thread
+        const uint16_t *A = h == 0 ? a.A0 : a.A1;
+        const int row = i * 16 + srow;
+        areg[i] = *reinterpret_cast<const u32x4v *>(A + (int64_t)min(m0 + row, M - 1) * a.lda + spiece * 8);
+        wreg[i] = *reinterpret_cast<const u32x4v *>(a.B + (int64_t)row * K + h * WIDE_KH + spiece * 8);
+    };
+    auto stage = [&]() {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int row = i * 16 + srow;
+            *reinterpret_cast<u32x4v *>(&As[row * WIDE_LROW + spiece * 8]) = areg[i];
+            *reinterpret_cast<u32x4v *>(&Ws[row * WIDE_LROW + spiece * 8]) = wreg[i];
+        }
+    };
+#pragma unroll
+    for (int i = 0; i < 16; ++i) fetch(0, i);
+    if (tid < WIDE_N / 4)
+        *reinterpret_cast<float4 *>(&bias_s[tid * 4]) = a.bias ? *reinterpret_cast<const float4 *>(a.bias + tid * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+    stage();
+    __syncthreads();
+
+    // the accumulators start from the bias (a lane's 4-column pieces: columns t*32 + 8*grp + 4*half .. + 4)
+    f32x16 acc[2][NTILES];
+#pragma unroll
+    for (int t = 0; t < NTILES; ++t)
+#pragma unroll
+        for (int grp = 0; grp < 4; ++grp) {
+            const float4 bq = *reinterpret_cast<const float4 *>(&bias_s[t * 32 + 8 * grp + 4 * half]);
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb) {
+                acc[rb][t][grp * 4 + 0] = bq.x; acc[rb][t][grp * 4 + 1] = bq.y; acc[rb][t][grp * 4 + 2] = bq.z; acc[rb][t][grp * 4 + 3] = bq.w;
+            }
+        }
+    const uint16_t *arow0 = As + (wave * 64 + lr) * WIDE_LROW + 8 * half, *arow1 = arow0 + 32 * WIDE_LROW;
+    const uint16_t *wrow = Ws + lr * WIDE_LROW + 8 * half;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        bf16x8 wnext[NTILES], anext[2];
+        anext[0] = lds_read8(arow0);
+        anext[1] = lds_read8(arow1);
+#pragma unroll
+        for (int t = 0; t < NTILES; ++t) wnext[t] = lds_read8(wrow + t * 32 * WIDE_LROW);
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks) {
+            bf16x8 wcur[NTILES];
+            const bf16x8 a0 = anext[0], a1 = anext[1];
+#pragma unroll
+            for (int t = 0; t < NTILES; ++t) wcur[t] = wnext[t];
+            if (ks + 1 < KSTEPS) {
+                anext[0] = lds_read8(arow0 + (ks + 1) * 16);
+                anext[1] = lds_read8(arow1 + (ks + 1) * 16);
+#pragma unroll
+                for (int t = 0; t < NTILES; ++t) wnext[t] = lds_read8(wrow + t * 32 * WIDE_LROW + (ks + 1) * 16);
+            }
+            if (h == 0) {                 // the second half's loads, two of each per step: they travel under the MFMAs
+                fetch(1, 2 * ks);
+                fetch(1, 2 * ks + 1);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int t = 0; t < NTILES; ++t) {
+                acc[0][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wcur[t], a0, acc[0][t], 0, 0, 0);
+                acc[1][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wcur[t], a1, acc[1][t], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        __syncthreads();                  // every wave is done reading this half
+        if (h == 0) {
+            stage();
+            __syncthreads();
+        }
+    }
+
+    // epilogue: ReLU, bf16; a lane holds, for row lr of each block, the columns t*32 + 8*grp + 4*half .. + 4
+    const float floor_v = a.relu ? 0.f : -INFINITY;
+    uint16_t *ob = wide_lds + wave * 64 * WIDE_OROW;
+#pragma unroll
+    for (int t = 0; t < NTILES; ++t)
+#pragma unroll
+        for (int grp = 0; grp < 4; ++grp) {
+            const int n = t * 32 + 8 * grp + 4 * half;
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb) {
+                const float v0 = fmaxf(acc[rb][t][grp * 4 + 0], floor_v), v1 = fmaxf(acc[rb][t][grp * 4 + 1], floor_v);
+                const float v2 = fmaxf(acc[rb][t][grp * 4 + 2], floor_v), v3 = fmaxf(acc[rb][t][grp * 4 + 3], floor_v);
+                *reinterpret_cast<uint2 *>(&ob[(rb * 32 + lr) * WIDE_OROW + n]) = make_uint2(pack_bf16x2(v0, v1), pack_bf16x2(v2, v3));
+            }
+        }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    constexpr int CPR = WIDE_N / 8;       // 16-byte chunks per output row
+    const int mw = m0 + wave * 64;
+#pragma unroll 8
+    for (int it = 0; it < CPR; ++it) {
+        const int c = it * 64 + lane, row = c / CPR, c8 = (c % CPR) * 8;
+        const u32x4v x = *reinterpret_cast<const u32x4v *>(&ob[row * WIDE_OROW + c8]);
+        if (mw + row < M) *reinterpret_cast<u32x4v *>(a.Cb + (int64_t)(mw + row) * a.ldcb + c8) = x;
+    }
+}
+
+constexpr int NT_WIDE_MIN_ROWS = 16384;   // below this the 256-row workgroups leave most compute units idle
+
 constexpr int NT_SMALL_ROWS = 2048;    // blocks of at most this many rows (by capacity) take the kernel above
 
 // Wider tiles (NTILES = 4, 8) read the activations fewer times but measured slower on MI355X for the
@@ -418,6 +560,18 @@ constexpr int NT_DEEP_MIN_K = 768;            // ... a K loop of at least 24 ste
 
 static void launch_nt(const NtArgs &a, hipStream_t s)
 {
+    // many rows against weights that fit one compute unit's LDS, bf16 output only: the weight-stationary kernel
+    if (a.max_rows >= NT_WIDE_MIN_ROWS && a.N == WIDE_N && a.K == 2 * WIDE_KH && a.K0 == WIDE_KH && a.A1 != nullptr && a.Cb != nullptr &&
+        a.C0 == nullptr && a.ldcb == a.N) {
+        static const bool ready = [] {
+            return hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_nt_wide_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)WIDE_LDS_BYTES) == hipSuccess;
+        }();
+        if (ready) {
+            hipLaunchKernelGGL(gemm_nt_wide_kernel, dim3((unsigned)ceil_div(a.max_rows, WIDE_ROWS)), dim3(256), WIDE_LDS_BYTES, s, a);
+            return;
+        }
+    }
     // xcd_compact needs the grid rounded up to a multiple of eight blocks
     const unsigned ncol = (unsigned)(a.N / 64);
     if (a.max_rows <= NT_SMALL_ROWS) {

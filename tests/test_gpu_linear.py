@@ -72,6 +72,39 @@ def test_linear_fwd(torch_mod, M, F_in, F_out, relu):
     assert_close(gb[:M, :F_out], want, RTOL_BF16, "out_bf16")
 
 
+@pytest.mark.parametrize("M,F_in,F_out,relu", [(20001, 128, 256, True), (61221, 100, 256, True), (16384, 128, 200, False)])
+def test_linear_fwd_many_rows_bf16_output(torch_mod, M, F_in, F_out, relu):
+    """The input layer of the large workloads: tens of thousands of rows, K = N = 256 after padding, bf16 output only
+    (the weight-stationary kernel: whole weight matrix in LDS, 256 rows per workgroup)."""
+    torch = torch_mod
+    from paper_2504_18082_amd import binding as B
+    rng = np.random.default_rng(M + F_in)
+    print(f"case fwd wide M={M} F_in={F_in} F_out={F_out}", flush=True)
+    hs = rng.standard_normal((M, F_in)).astype(np.float32)
+    ag = rng.standard_normal((M, F_in)).astype(np.float32) * 0.5
+    W = (rng.standard_normal((2 * F_in, F_out)) / np.sqrt(2 * F_in)).astype(np.float32)
+    b = rng.standard_normal(F_out).astype(np.float32) * 0.1
+    oracle.use_all_cores(True)
+    try:
+        want = oracle.sage_linear_fwd(hs, ag, W, b, relu, True)
+    finally:
+        oracle.use_all_cores(False)
+    layer = B.SageLayer(W, b)
+    layer.refresh()
+    cap = M + 300                                    # capacity above the live row count: whole workgroups without rows
+    ld_in = layer.F_pad
+    d_hs, d_ag = to_bf16_dev(torch, np.pad(hs, ((0, 300), (0, 0))), ld_in), to_bf16_dev(torch, np.pad(ag, ((0, 300), (0, 0))), ld_in)
+    out_b = torch.full((cap, layer.N_pad), 0x7FC0, dtype=torch.int16, device="cuda")
+    hdr = hdr_for(torch, M)
+    B.cr_sage_linear_fwd(layer, C.c_void_p(hdr.data_ptr()), cap, d_hs, d_ag, ld_in, relu, None, out_b)
+    torch.cuda.synchronize()
+    gb = bf16_tensor_to_float(out_b)
+    # one rounding to bf16 (2^-9 relative) on top of the float accumulation
+    assert_close(gb[:M, :F_out], want, 2.0 ** -8, "out_bf16")
+    assert np.all(gb[:M, F_out:] == 0)
+    assert np.all(out_b[M:].cpu().numpy() == 0x7FC0)          # rows past the header's count untouched
+
+
 @pytest.mark.parametrize("M,F_in,F_out,need_dx", [(300, 64, 64, True), (2500, 100, 256, False), (777, 256, 40, True),
                                                   (200, 602, 256, False), (33, 32, 10, True)])
 def test_linear_bwd_and_sgd(torch_mod, M, F_in, F_out, need_dx):
