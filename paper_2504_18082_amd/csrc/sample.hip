@@ -48,7 +48,25 @@ struct SelectArgs {
     int32_t *cnt;             // [G][cap_dst]
     int64_t cnt_stride;
     uint32_t cand_target;     // long rows, uniform sampling: expected number of slots below the pre-filter threshold
+    // Direct output (input-side block left in global ids, every row keeps min(fanout, degree) neighbours): the row
+    // pointers are known before anything is selected, so the chosen ids go straight to their place in the block's
+    // per-edge id array and the intermediate [row][fanout] array is not written at all.
+    const int32_t *out_indptr;   // [G][out_indptr_stride] or NULL
+    int64_t out_indptr_stride;
+    int32_t *out_ids;            // [G][out_stride]
+    int64_t out_stride;
 };
+
+// where the chosen neighbours of a row go, and (when they go to the intermediate array) the row's count
+__device__ __forceinline__ int32_t *sel_row_ptr(const SelectArgs &a, int g, int row)
+{
+    if (a.out_indptr) return a.out_ids + (int64_t)g * a.out_stride + a.out_indptr[(int64_t)g * a.out_indptr_stride + row];
+    return a.sel + (int64_t)g * a.sel_stride + (int64_t)row * a.fanout;
+}
+__device__ __forceinline__ void set_row_count(const SelectArgs &a, int g, int row, int n)
+{
+    if (!a.out_indptr) a.cnt[(int64_t)g * a.cnt_stride + row] = n;
+}
 
 __device__ __forceinline__ int group_n_dst(const int32_t *prev_hdr, int g, int64_t n_roots_total, int batch_size)
 {
@@ -100,7 +118,7 @@ __device__ __forceinline__ void select_big_row(const SelectArgs &a, int g, int r
 {
     constexpr bool WIDE = MODE != 0;
     const int f = a.fanout;
-    int32_t *sel_row = a.sel + (int64_t)g * a.sel_stride + (int64_t)row * f;
+    int32_t *sel_row = sel_row_ptr(a, g, row);
     const int k = f;
     const uint32_t batch = a.first_batch + (uint32_t)g;
     auto less = [&](uint64_t ka, uint32_t sa, uint64_t kb, uint32_t sb) -> bool {
@@ -216,7 +234,7 @@ __device__ __forceinline__ void select_big_row(const SelectArgs &a, int g, int r
     }
     const uint64_t vmask = __ballot(valid);
     if (valid) sel_row[rank] = cu;
-    if (lane == 0) a.cnt[(int64_t)g * a.cnt_stride + row] = __popcll(vmask);
+    if (lane == 0) set_row_count(a, g, row, __popcll(vmask));
 }
 
 // Uniform sampling of a row with more than 64 neighbours, the common way: slots whose random word falls
@@ -255,7 +273,9 @@ __device__ __forceinline__ bool select_big_row_filtered(const SelectArgs &a, int
         pool = n_in;
     }
     const int64_t w_max = (a.n_entries - 1) >> 5;
-    uint64_t thr = ((uint64_t)a.cand_target << 32) / (uint64_t)pool;     // > 2^32 - 1 keeps every slot of the pool
+    // (float arithmetic: the threshold only steers how many candidates there are, any value gives the same result)
+    const float thr_f = (float)a.cand_target * 4294967296.0f / (float)pool;
+    const uint64_t thr = thr_f >= 4294967296.0f ? 0x100000000ull : (uint64_t)thr_f;     // 2^32 keeps every slot of the pool
     int n = 0;
     for (int j0 = 0; j0 < deg; j0 += 4 * WAVE) {
         const int jb = j0 + 4 * lane;
@@ -272,8 +292,10 @@ __device__ __forceinline__ bool select_big_row_filtered(const SelectArgs &a, int
         uint64_t b[4];
         int before = n, total = 0;
 #pragma unroll
+        for (int i = 0; i < 4; ++i) c[i] = jb + i < deg && (uint64_t)wr[i] < thr && ((nib >> i) & 1u);
+        if (__ballot(c[0] || c[1] || c[2] || c[3]) == 0) continue;      // (most iterations of a long row)
+#pragma unroll
         for (int i = 0; i < 4; ++i) {
-            c[i] = jb + i < deg && (uint64_t)wr[i] < thr && ((nib >> i) & 1u);
             b[i] = __ballot(c[i]);
             before += __popcll(b[i] & lt_mask);
             total += __popcll(b[i]);
@@ -307,10 +329,10 @@ __device__ __forceinline__ bool select_big_row_filtered(const SelectArgs &a, int
     }
     const bool s0 = have0 && r0 < k, s1 = have1 && r1 < k;
     const uint64_t m0 = __ballot(s0), m1 = __ballot(s1);
-    int32_t *sel_row = a.sel + (int64_t)g * a.sel_stride + (int64_t)row * k;
+    int32_t *sel_row = sel_row_ptr(a, g, row);
     if (s0) sel_row[__popcll(m0 & lt_mask)] = a.g_indices[base + c0.y];
     if (s1) sel_row[__popcll(m0) + __popcll(m1 & lt_mask)] = a.g_indices[base + c1.y];
-    if (lane == 0) a.cnt[(int64_t)g * a.cnt_stride + row] = k;
+    if (lane == 0) set_row_count(a, g, row, k);
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");      // the buffer is reused by this wave's next long row
     return true;
 }
@@ -431,10 +453,10 @@ __device__ __forceinline__ bool select_big_row_weighted(const SelectArgs &a, int
 
     const bool s0 = have0 && r0 < k, s1 = have1 && r1 < k;
     const uint64_t m0 = __ballot(s0), m1 = __ballot(s1);
-    int32_t *sel_row = a.sel + (int64_t)g * a.sel_stride + (int64_t)row * k;
+    int32_t *sel_row = sel_row_ptr(a, g, row);
     if (s0) sel_row[__popcll(m0 & lt_mask)] = a.g_indices[base + (c0.y & 0x7FFFFFFFu)];
     if (s1) sel_row[__popcll(m0) + __popcll(m1 & lt_mask)] = a.g_indices[base + (c1.y & 0x7FFFFFFFu)];
-    if (lane == 0) a.cnt[(int64_t)g * a.cnt_stride + row] = k;
+    if (lane == 0) set_row_count(a, g, row, k);
     return true;
 }
 
@@ -470,7 +492,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
         const int64_t d = a.g_indptr[mv + 1] - mbase;
         mdeg = (int)(d > 0x7FFFFFFF ? 0x7FFFFFFF : d);
         if (WIDE) mcv = a.comm[mv];
-        if (mdeg == 0) a.cnt[(int64_t)g * a.cnt_stride + row0 + lane] = 0;
+        if (mdeg == 0) set_row_count(a, g, row0 + lane, 0);
     }
     int32_t v[SEL_ROWS], cv[SEL_ROWS];
     int deg[SEL_ROWS], start[SEL_ROWS], pass[SEL_ROWS];
@@ -537,8 +559,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
         const uint64_t smask = __ballot(survivor) & seg;
         if (active) {
             const int row = row0 + ri;
-            if (survivor) a.sel[(int64_t)g * a.sel_stride + (int64_t)row * f + __popcll(smask & ((1ull << lane) - 1ull))] = u;
-            if (j == 0) a.cnt[(int64_t)g * a.cnt_stride + row] = __popcll(smask);
+            if (survivor) sel_row_ptr(a, g, row)[__popcll(smask & ((1ull << lane) - 1ull))] = u;
+            if (j == 0) set_row_count(a, g, row, __popcll(smask));
         }
     }
 
@@ -552,6 +574,20 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
                 select_big_row_weighted(a, g, row0 + i, v[i], base[i], deg[i], lane, buf, ckey[threadIdx.x / WAVE])) continue;
             select_big_row<MODE>(a, g, row0 + i, v[i], base[i], deg[i], cv[i], lane);
         }
+}
+
+// rows of a block that keep min(fanout, degree) neighbours each (no strict mode): the counts need no selection
+__global__ __launch_bounds__(256) void row_counts_kernel(const int64_t *__restrict__ g_indptr, const int32_t *__restrict__ dst_ids,
+                                                         int64_t dst_stride, const int32_t *__restrict__ prev_hdr, int64_t n_roots_total,
+                                                         int32_t batch_size, int32_t fanout, int32_t *__restrict__ cnt, int64_t cnt_stride)
+{
+    const int g = blockIdx.y;
+    const int n_dst = group_n_dst(prev_hdr, g, n_roots_total, batch_size);
+    const int row = (int)(blockIdx.x * 256 + threadIdx.x);
+    if (row >= n_dst) return;
+    const int32_t v = dst_ids[(int64_t)g * dst_stride + row];
+    const int64_t d = g_indptr[v + 1] - g_indptr[v];
+    cnt[(int64_t)g * cnt_stride + row] = (int32_t)(d < fanout ? d : fanout);
 }
 
 struct ScanArgs {
@@ -965,7 +1001,7 @@ __global__ __launch_bounds__(256) void compact_ids_kernel(DedupArgs a)
     CR_ROW_LANE();
     if (blockIdx.x == 0 && threadIdx.x == 0) hdr[CR_HDR_N_SRC] = -1;
     if (in_row && j == 0) a.src_ids[(int64_t)g * a.src_stride + row] = a.dst_ids[(int64_t)g * a.dst_stride + row];
-    if (!active) return;
+    if (!active || a.sel == nullptr) return;       // (a.sel == NULL: the selection wrote the ids in place)
     a.gather_ids[(int64_t)g * a.indices_stride + rstart + j] = a.sel[(int64_t)g * a.sel_stride + ell];
 }
 
@@ -1245,6 +1281,23 @@ extern "C" cr_status cr_sample_blocks(const cr_graph *graph, const cr_sample_cfg
             sa.cand_target = (uint32_t)(target > 96 ? 96 : target);
         }
         const dim3 sel_grid((unsigned)ceil_div(cap_dst, 4 * SEL_ROWS), n_batches);
+        // Input-side block in global ids, every row keeps min(fanout, degree) neighbours: counts and row pointers first
+        // (they need no selection), then the selection writes the chosen ids straight into the block.
+        const bool direct_out = l == 0 && (cfg->flags & CR_SAMPLE_INPUT_GLOBAL_IDS) && !sa.strict_p1;
+        ScanArgs sc;
+        sc.tile_before = nullptr;
+        sc.prev_hdr = prev_hdr; sc.n_roots_total = n_roots_total; sc.batch_size = batch_size;
+        sc.mode = 0; sc.in = p.cnt; sc.in_stride = p.max_dst; sc.out = b.indptr; sc.out_stride = b.cap_dst + 1;
+        sc.out_copy = nullptr; sc.copy_stride = 0; sc.hdr = b.hdr;
+        sc.cap_src = b.cap_src; sc.async_status = async_status();
+        const dim3 scan_grid((unsigned)ceil_div(cap_dst, SCAN_TILE), n_batches);
+        sa.out_indptr = nullptr; sa.out_indptr_stride = 0; sa.out_ids = nullptr; sa.out_stride = 0;
+        if (direct_out) {
+            hipLaunchKernelGGL(row_counts_kernel, dim3((unsigned)ceil_div(cap_dst, 256), n_batches), blk, 0, s, graph->indptr, dst_ids, dst_stride,
+                               prev_hdr, n_roots_total, batch_size, f, p.cnt, (int64_t)p.max_dst);
+            hipLaunchKernelGGL(scan_kernel, scan_grid, dim3(SCAN_THREADS), 0, s, sc);
+            sa.out_indptr = b.indptr; sa.out_indptr_stride = b.cap_dst + 1; sa.out_ids = b.gather_ids; sa.out_stride = b.cap_nnz;
+        }
         if (q_in == q_out) hipLaunchKernelGGL(select_kernel<0>, sel_grid, blk, 0, s, sa);
         else if (q_out == 0) hipLaunchKernelGGL(select_kernel<1>, sel_grid, blk, 0, s, sa);
         else hipLaunchKernelGGL(select_kernel<2>, sel_grid, blk, 0, s, sa);
@@ -1277,14 +1330,7 @@ extern "C" cr_status cr_sample_blocks(const cr_graph *graph, const cr_sample_cfg
             hipLaunchKernelGGL(order_pass_kernel<true>, og, blk, 0, s, oa);
         }
 
-        ScanArgs sc;
-        sc.tile_before = nullptr;
-        sc.prev_hdr = prev_hdr; sc.n_roots_total = n_roots_total; sc.batch_size = batch_size;
-        sc.mode = 0; sc.in = p.cnt; sc.in_stride = p.max_dst; sc.out = b.indptr; sc.out_stride = b.cap_dst + 1;
-        sc.out_copy = nullptr; sc.copy_stride = 0; sc.hdr = b.hdr;
-        sc.cap_src = b.cap_src; sc.async_status = async_status();
-        const dim3 scan_grid((unsigned)ceil_div(cap_dst, SCAN_TILE), n_batches);
-        hipLaunchKernelGGL(scan_kernel, scan_grid, dim3(SCAN_THREADS), 0, s, sc);
+        if (!direct_out) hipLaunchKernelGGL(scan_kernel, scan_grid, dim3(SCAN_THREADS), 0, s, sc);
 
         DedupArgs da;
         da.prev_hdr = prev_hdr; da.n_roots_total = n_roots_total; da.batch_size = batch_size; da.fanout = f;
@@ -1299,6 +1345,7 @@ extern "C" cr_status cr_sample_blocks(const cr_graph *graph, const cr_sample_cfg
         if (l == 0 && (cfg->flags & CR_SAMPLE_INPUT_GLOBAL_IDS)) {
             da.tcount = nullptr; da.tfill = nullptr; da.t_stride = 0; da.t_indptr = nullptr; da.t_indptr_stride = 0;
             da.t_indices = nullptr; da.t_tmp = nullptr; da.t_pos = nullptr; da.tt_stride = 0;
+            if (direct_out) da.sel = nullptr;      // nothing left to copy but the destination nodes
             hipLaunchKernelGGL(compact_ids_kernel, grid, blk, 0, s, da);
             continue;
         }
