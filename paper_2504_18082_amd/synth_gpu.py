@@ -26,7 +26,7 @@ from . import synth
 # How many undirected edges are drawn per edge asked for: drawing with replacement loses the repeated pairs
 # when the adjacency is de-duplicated.  Measured once per shape (the loss is a property of the recipe); a
 # top-up round below closes whatever gap is left, so these only save that round.
-DRAW_FACTOR = {"reddit": 1.22, "products": 1.17, "papers": 1.02}
+DRAW_FACTOR = {"reddit": 1.21, "products": 1.145, "papers": 1.02}
 
 
 @dataclass
