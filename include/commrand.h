@@ -233,6 +233,10 @@ typedef struct {
                                   was needed; every access stays inside the arrays.  The workspace is sized as without the
                                   flag. */
 
+#define CR_SAMPLE_EXACT_RANKING 64u /* verification aid: neighbour selection without its pre-filter thresholds, every row ranked on
+                                  full (key, slot) pairs -- the path that otherwise only serves the rare rows whose threshold
+                                  let too few slots through or whose boundary keys are equal.  Same results, slower. */
+
 #define CR_SAMPLE_ROW_ORDER 16u /* fill the row_order array of every layer whose block set carries one (the workspace is
                                   then larger: set the flag for cr_sample_blocks_workspace_bytes too) */
 

@@ -29,6 +29,7 @@ CR_SAMPLE_INPUT_GLOBAL_IDS = 4
 CR_SAMPLE_TRANSPOSE_INPUT = 8
 CR_SAMPLE_ROW_ORDER = 16
 CR_SAMPLE_SMALL_FRONTIER = 32
+CR_SAMPLE_EXACT_RANKING = 64
 
 EXPORTS = [
     "cr_last_error", "cr_version", "cr_mix_count_from_percent",

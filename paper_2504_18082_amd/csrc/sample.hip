@@ -55,6 +55,7 @@ struct SelectArgs {
     int64_t out_indptr_stride;
     int32_t *out_ids;            // [G][out_stride]
     int64_t out_stride;
+    uint32_t exact_select;       // verification aid: no pre-filter thresholds, every ranking on full (key, slot) pairs
 };
 
 // where the chosen neighbours of a row go, and (when they go to the intermediate array) the row's count
@@ -568,12 +569,229 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
     for (int i = 0; i < SEL_ROWS; ++i)
         if (deg[i] > WAVE) {
             uint2 *buf = cand[threadIdx.x / WAVE];
-            if (MODE == 0 && select_big_row_filtered<false>(a, g, row0 + i, v[i], base[i], deg[i], lane, buf)) continue;
-            if (MODE == 1 && a.edge_intra && select_big_row_filtered<true>(a, g, row0 + i, v[i], base[i], deg[i], lane, buf)) continue;
-            if (MODE == 2 && a.edge_intra &&
+            if (MODE == 0 && !a.exact_select && select_big_row_filtered<false>(a, g, row0 + i, v[i], base[i], deg[i], lane, buf)) continue;
+            if (MODE == 1 && !a.exact_select && a.edge_intra && select_big_row_filtered<true>(a, g, row0 + i, v[i], base[i], deg[i], lane, buf)) continue;
+            if (MODE == 2 && !a.exact_select && a.edge_intra &&
                 select_big_row_weighted(a, g, row0 + i, v[i], base[i], deg[i], lane, buf, ckey[threadIdx.x / WAVE])) continue;
             select_big_row<MODE>(a, g, row0 + i, v[i], base[i], deg[i], cv[i], lane);
         }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Selection with four neighbour slots per lane: uniform sampling, and p = 1 on a graph that carries its edge-class bits
+// ---------------------------------------------------------------------------------------------
+// One Philox block yields the random words of four consecutive slots, so a lane owns a "quad" of slots and a pass of the
+// wave covers 256 slots of consecutive destination rows laid side by side (a row of up to 256 slots never straddles two
+// passes).  Both settings reduce to "keep the m smallest words of a pool of P slots, and all of the rest that is kept":
+//   uniform        pool = the row, m = min(fanout, degree);
+//   p = 1          with n_in >= fanout intra-community slots the pool is those and m = fanout; with fewer, all of them are
+//                  kept and the pool is the inter-community slots with m = fanout - n_in (0 in strict mode).
+// Slots whose word lies below a threshold of about (m + 3 sqrt(m) + 3) / P become candidates, are compacted in slot order
+// into the row's stretch of an LDS list, and every lane ranks its four slots against that list (one broadcast read serves
+// four comparisons per lane).  The ranking compares words only; a row whose kept count then differs from the count it must
+// have (a threshold that let fewer than m slots through, or equal words at the boundary) is redone without threshold and
+// with (word, slot) pairs compared in full, so the result is exact in every case.
+constexpr int QUAD_ROWS = 16;            // destination rows per wave
+constexpr int QUAD_MAX_DEG = 4 * WAVE;   // longest row a pass holds
+
+struct alignas(16) QuadRow {
+    int32_t v, deg, startq, nq;          // node, degree, first quad in the wave's quad sequence, number of quads
+    int64_t base;                        // first adjacency entry
+    int32_t *out;                        // where the row's chosen ids go
+};
+
+__device__ __forceinline__ int lanes_below(uint64_t mask, int acc)      // acc + number of set bits below this lane
+{
+    return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, (uint32_t)acc));
+}
+
+// One pass; returns the rows (bit r = row r of the wave) that have to be redone exactly.  rowmask: rows to process.
+template <int MODE, bool EXACT>
+__device__ __forceinline__ uint32_t quad_pass(const SelectArgs &a, int g, int row0, int p, uint32_t rowmask, const QuadRow *rows,
+                                              const int *startq, uint32_t *klist, int lane)
+{
+    const int f = a.fanout;
+    const uint32_t batch = a.first_batch + (uint32_t)g;
+    const int gq = p * WAVE + lane;
+    // the row of this lane's quad: the last one that starts at or before it (startq is non-decreasing, startq[0] = 0)
+    int r = startq[8] <= gq ? 8 : 0;
+    r += startq[r + 4] <= gq ? 4 : 0;
+    r += startq[r + 2] <= gq ? 2 : 0;
+    r += startq[r + 1] <= gq ? 1 : 0;
+    const QuadRow R = rows[r];
+    const int qi = gq - R.startq;
+    const bool active = qi < R.nq && ((rowmask >> r) & 1u);
+    if (__ballot(active) == 0) return 0u;
+    const int first = R.startq - p * WAVE, last = first + R.nq - 1;       // the row's lanes in this pass
+    const int jb = 4 * qi;
+    const int left = active ? R.deg - jb : 0;
+    const uint32_t vmask = left >= 4 ? 0xFu : ((1u << left) - 1u);        // the quad's slots that exist
+    const u32x4 w = philox4x32_10((uint32_t)qi, (uint32_t)R.v, batch, a.ctr3, a.seed_lo, a.seed_hi);
+    const uint32_t wr[4] = {w.x, w.y, w.z, w.w};
+
+    // number of set flags of this row in the lanes before this one, and in the whole row (flags of lanes outside any
+    // row are zero)
+    auto seg = [&](uint32_t m4, int &excl, int &total) {
+        int e = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) e = lanes_below(__ballot((m4 >> i) & 1u), e);
+        const int before_row = (int)pull32((uint32_t)e, first);
+        const int upto_last = (int)pull32((uint32_t)(e + __popc(m4)), last);
+        excl = e - before_row;
+        total = upto_last - before_row;
+    };
+
+    uint32_t pool = vmask, take = 0u;
+    int m = min(f, R.deg), P = R.deg, expect = m;
+    if (MODE == 1) {
+        uint32_t nib = 0u;
+        if (active) {
+            const int64_t e = R.base + jb, wi = e >> 5, w_max = (a.n_entries - 1) >> 5;
+            const uint64_t win = (uint64_t)a.edge_intra[wi] | ((uint64_t)a.edge_intra[min(wi + 1, w_max)] << 32);
+            nib = (uint32_t)(win >> (e & 31)) & 0xFu;
+        }
+        const uint32_t in4 = nib & vmask;
+        int unused, n_in;
+        seg(in4, unused, n_in);
+        if (n_in >= f) {
+            pool = in4; m = f; P = n_in; expect = f;
+        } else {
+            take = in4; pool = vmask & ~nib; P = R.deg - n_in;
+            m = a.strict_p1 ? 0 : min(f - n_in, P);
+            expect = n_in + m;
+        }
+    }
+    const bool ranked = active && m > 0 && m < P;
+    if (!ranked) {
+        if (m >= P) take |= pool;           // the whole pool is kept
+        pool = 0u;
+    }
+    uint32_t cm = pool;                      // candidates among this lane's slots
+    if (!EXACT && ranked) {
+        // (float arithmetic: the threshold only steers how many candidates there are)
+        const float mf = (float)m;
+        const float tf = (mf + 3.0f * __builtin_amdgcn_sqrtf(mf) + 3.0f) * 4294967296.0f * __builtin_amdgcn_rcpf((float)P);
+        if (tf < 4294967040.0f) {
+            const uint32_t T = (uint32_t)tf;
+            uint32_t below = 0u;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) below |= (wr[i] < T ? 1u : 0u) << i;
+            cm &= below;
+        }
+    }
+    int cpos, n_c;
+    seg(cm, cpos, n_c);
+    // the row's list: candidates' words in slot order, padded with the largest word to a multiple of four
+    uint32_t *kl = klist + 4 * first;
+    if (active) *reinterpret_cast<uint4 *>(klist + 4 * lane) = make_uint4(~0u, ~0u, ~0u, ~0u);
+    if (ranked) {
+        int k = cpos;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if ((cm >> i) & 1u) kl[k++] = wr[i];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    int rk[4] = {0, 0, 0, 0};
+    const int nc_mine = ranked ? n_c : 0;
+    for (int t0 = 0; __ballot(t0 < nc_mine) != 0; t0 += 4) {
+        if (t0 < nc_mine) {
+            const uint4 kt = *reinterpret_cast<const uint4 *>(kl + t0);
+            const uint32_t ks[4] = {kt.x, kt.y, kt.z, kt.w};
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    if (!EXACT) rk[i] += ks[q] < wr[i] ? 1 : 0;
+                    else rk[i] += (ks[q] < wr[i] || (ks[q] == wr[i] && t0 + q < cpos + (int)__popc(cm & ((1u << i) - 1u)))) ? 1 : 0;
+                }
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");      // the list is reused by the next pass
+    uint32_t emit = take;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) emit |= (((cm >> i) & 1u) && rk[i] < m) ? 1u << i : 0u;
+    int epos, total;
+    seg(emit, epos, total);
+    const bool ok = total == expect;      // (always true in the exact pass)
+    if (active && ok) {
+        int k = epos;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if ((emit >> i) & 1u) R.out[k++] = a.g_indices[R.base + jb + i];
+        if (qi == 0) set_row_count(a, g, row0 + r, total);
+    }
+    uint64_t bad = __ballot(active && qi == 0 && !ok);
+    uint32_t redo = 0u;
+    while (bad) {
+        redo |= 1u << rl32((uint32_t)r, __ffsll((long long)bad) - 1);
+        bad &= bad - 1;
+    }
+    return redo;
+}
+
+template <int MODE>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))) void select_quad_kernel(SelectArgs a)
+{
+    __shared__ QuadRow rows_s[4][QUAD_ROWS];
+    __shared__ int startq_s[4][QUAD_ROWS];
+    __shared__ __align__(16) uint32_t klist_s[4][4 * WAVE];
+    __shared__ uint2 cand[4][CAND_CAP];
+    const int wv = (int)threadIdx.x / WAVE;
+    const int g = blockIdx.y;
+    const int n_dst = group_n_dst(a.prev_hdr, g, a.n_roots_total, a.batch_size);
+    const int row0 = (int)(blockIdx.x * 4 + wv) * QUAD_ROWS;
+    if (row0 >= n_dst) return;
+    const int lane = lane_id();
+
+    // lanes 0..QUAD_ROWS-1 fetch one row's node id, adjacency range and output place each
+    int32_t mv = 0;
+    int64_t mbase = 0;
+    int mdeg = 0;
+    int32_t *mout = nullptr;
+    if (lane < QUAD_ROWS && row0 + lane < n_dst) {
+        mv = a.dst_ids[(int64_t)g * a.dst_stride + row0 + lane];
+        mbase = a.g_indptr[mv];
+        const int64_t d = a.g_indptr[mv + 1] - mbase;
+        mdeg = (int)(d > 0x7FFFFFFF ? 0x7FFFFFFF : d);
+        mout = sel_row_ptr(a, g, row0 + lane);
+        if (mdeg == 0) set_row_count(a, g, row0 + lane, 0);
+    }
+    const int mq = (mdeg > 0 && mdeg <= QUAD_MAX_DEG) ? (mdeg + 3) >> 2 : 0;
+    // greedy packing of the rows' quads into passes of 64
+    int off = 0, my_start = 0;
+#pragma unroll
+    for (int i = 0; i < QUAD_ROWS; ++i) {
+        const int q = (int)rl32((uint32_t)mq, i);
+        if ((off & (WAVE - 1)) + q > WAVE) off = (off + WAVE - 1) & ~(WAVE - 1);
+        if (lane == i) my_start = off;
+        off += q;
+    }
+    const int n_pass = (off + WAVE - 1) / WAVE;
+    if (lane < QUAD_ROWS) {
+        QuadRow R;
+        R.v = mv; R.deg = mdeg; R.startq = my_start; R.nq = mq; R.base = mbase; R.out = mout;
+        rows_s[wv][lane] = R;
+        startq_s[wv][lane] = my_start;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+
+    uint32_t exact_rows = a.exact_select ? 0xFFFFu : 0u;
+    if (!a.exact_select)
+        for (int p = 0; p < n_pass; ++p)
+            exact_rows |= quad_pass<MODE, false>(a, g, row0, p, 0xFFFFu, rows_s[wv], startq_s[wv], klist_s[wv], lane);
+    if (exact_rows)
+        for (int p = 0; p < n_pass; ++p) quad_pass<MODE, true>(a, g, row0, p, exact_rows, rows_s[wv], startq_s[wv], klist_s[wv], lane);
+
+    // longer rows, one at a time
+#pragma unroll 1
+    for (int i = 0; i < QUAD_ROWS; ++i) {
+        const int deg = (int)rl32((uint32_t)mdeg, i);
+        if (deg <= QUAD_MAX_DEG) continue;
+        const int32_t v = (int32_t)rl32((uint32_t)mv, i);
+        const int64_t base = (int64_t)rl64((uint64_t)mbase, i);
+        if (!a.exact_select && select_big_row_filtered<MODE == 1>(a, g, row0 + i, v, base, deg, lane, cand[wv])) continue;
+        select_big_row<MODE>(a, g, row0 + i, v, base, deg, MODE == 1 ? a.comm[v] : 0, lane);
+    }
 }
 
 // rows of a block that keep min(fanout, degree) neighbours each (no strict mode): the counts need no selection
@@ -1280,7 +1498,9 @@ extern "C" cr_status cr_sample_blocks(const cr_graph *graph, const cr_sample_cfg
             int target = f + (int)(4.0 * sqrt((double)f)) + 4;
             sa.cand_target = (uint32_t)(target > 96 ? 96 : target);
         }
+        sa.exact_select = (cfg->flags & CR_SAMPLE_EXACT_RANKING) ? 1u : 0u;
         const dim3 sel_grid((unsigned)ceil_div(cap_dst, 4 * SEL_ROWS), n_batches);
+        const dim3 quad_grid((unsigned)ceil_div(cap_dst, 4 * QUAD_ROWS), n_batches);
         // Input-side block in global ids, every row keeps min(fanout, degree) neighbours: counts and row pointers first
         // (they need no selection), then the selection writes the chosen ids straight into the block.
         const bool direct_out = l == 0 && (cfg->flags & CR_SAMPLE_INPUT_GLOBAL_IDS) && !sa.strict_p1;
@@ -1298,7 +1518,8 @@ extern "C" cr_status cr_sample_blocks(const cr_graph *graph, const cr_sample_cfg
             hipLaunchKernelGGL(scan_kernel, scan_grid, dim3(SCAN_THREADS), 0, s, sc);
             sa.out_indptr = b.indptr; sa.out_indptr_stride = b.cap_dst + 1; sa.out_ids = b.gather_ids; sa.out_stride = b.cap_nnz;
         }
-        if (q_in == q_out) hipLaunchKernelGGL(select_kernel<0>, sel_grid, blk, 0, s, sa);
+        if (q_in == q_out) hipLaunchKernelGGL(select_quad_kernel<0>, quad_grid, blk, 0, s, sa);
+        else if (q_out == 0 && graph->edge_intra) hipLaunchKernelGGL(select_quad_kernel<1>, quad_grid, blk, 0, s, sa);
         else if (q_out == 0) hipLaunchKernelGGL(select_kernel<1>, sel_grid, blk, 0, s, sa);
         else hipLaunchKernelGGL(select_kernel<2>, sel_grid, blk, 0, s, sa);
 

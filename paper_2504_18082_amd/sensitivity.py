@@ -55,11 +55,13 @@ def main(argv=None):
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--model", default="sage", choices=["sage", "gcn", "gat"])
     ap.add_argument("--settings", nargs="+", default=DEFAULT_SETTINGS)
+    ap.add_argument("--row-order", default="auto", choices=["auto", "on", "off"],
+                    help="process the input-side block's rows in community order (the sorted-frontier ablation: off)")
     args = ap.parse_args(argv)
 
     import numpy as np
     import torch
-    from . import synth
+    from . import synth, synth_gpu
     from .fit import parse_setting
     from .trainer import Trainer
     if not torch.cuda.is_available():
@@ -69,11 +71,18 @@ def main(argv=None):
             cfg = synth.scaled(synth.CONFIGS[args.workload], scale) if scale != 1.0 else copy.deepcopy(synth.CONFIGS[args.workload])
             if width:
                 cfg.n_feat = width
-            w = synth.make_workload(cfg, args.seed)
-            n_comm_train = int(np.unique(w.comm[w.train_ids]).size)
-            tr = Trainer(w, group_size=args.group, seed=args.seed, model=args.model)
-            out = dict(workload=cfg.name, model=args.model, n_nodes=cfg.n_nodes, n_feat=cfg.n_feat,
-                       table_MB=round(w.features.nbytes / 1e6, 1), steps=args.steps, settings={})
+            if cfg.n_edges_undirected > 5_000_000:        # large graphs are drawn on the GPU and stay there
+                w = synth_gpu.make_workload_gpu(cfg, args.seed)
+                n_comm_train = w.n_comm_in_train
+                table_bytes = w.features.numel() * w.features.element_size()
+            else:
+                w = synth.make_workload(cfg, args.seed)
+                n_comm_train = int(np.unique(w.comm[w.train_ids]).size)
+                table_bytes = w.features.nbytes
+            tr = Trainer(w, group_size=args.group, seed=args.seed, model=args.model,
+                         order_rows={"auto": "auto", "on": True, "off": False}[args.row_order])
+            out = dict(workload=cfg.name, model=args.model, n_nodes=cfg.n_nodes, n_feat=cfg.n_feat, scale=scale,
+                       row_order=args.row_order, table_MB=round(table_bytes / 1e6, 1), steps=args.steps, settings={})
             for i, name in enumerate(args.settings):
                 policy, mix, p = parse_setting(name, n_comm_train)
                 ms, gather_ms, n_in = time_setting(tr, policy, mix, p, args.steps, args.warmup, 10 * i)

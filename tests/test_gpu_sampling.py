@@ -29,11 +29,13 @@ class DeviceGraph:
             self.c.edge_intra = self.bits.data_ptr()
 
 
-def run_gpu(torch, dg, roots, fanouts, p, strict, seed, epoch, first_batch, batch_size, hash_dedup=False, input_global=False):
+def run_gpu(torch, dg, roots, fanouts, p, strict, seed, epoch, first_batch, batch_size, hash_dedup=False, input_global=False,
+            exact_ranking=False):
     from paper_2504_18082_amd import binding as B
     n_batches = -(-len(roots) // batch_size)
     flags = (B.CR_SAMPLE_STRICT_INTRA if strict else 0) | (B.CR_SAMPLE_HASH_DEDUP if hash_dedup else 0)
     flags |= B.CR_SAMPLE_INPUT_GLOBAL_IDS if input_global else 0
+    flags |= B.CR_SAMPLE_EXACT_RANKING if exact_ranking else 0
     cfg = B.make_sample_cfg(fanouts, p, seed, epoch, first_batch, flags)
     layers = B.alloc_block_sets(cfg, dg.n_nodes, batch_size, n_batches)
     ws = torch.empty(B.cr_sample_blocks_workspace_bytes(cfg, dg.n_nodes, batch_size, n_batches), dtype=torch.uint8, device="cuda")
@@ -205,6 +207,28 @@ def test_long_rows_all_paths(torch_mod, edge_classes):
             compare(layers, nb, graph, roots, fan, p, False, 5, 1, 0, 16, f"long rows p={p} {fan}")
     layers, nb = run_gpu(torch_mod, dg, roots, [15], 1.0, True, 5, 1, 0, 16)
     compare(layers, nb, graph, roots, [15], 1.0, True, 5, 1, 0, 16, "long rows strict")
+
+
+@pytest.mark.parametrize("edge_classes", [True, False])
+def test_exact_ranking_path(torch_mod, arxiv_workload, edge_classes):
+    """CR_SAMPLE_EXACT_RANKING sends every row through the path that otherwise only redoes the rare rows whose pre-filter
+    threshold let too few slots through or whose boundary words are equal: same blocks, for short and long rows."""
+    w = arxiv_workload
+    dg = DeviceGraph(torch_mod, w.graph, w.cfg.n_comm, edge_classes=edge_classes)
+    perm = oracle.build_batches(oracle.RAND, 1, 0, 2, w.train_ids, w.comm, w.cfg.n_comm)
+    roots = perm[:1024 + 300]
+    for p, strict in ((0.5, False), (1.0, False), (1.0, True), (0.9, False)):
+        print(f"case exact ranking arxiv p={p} strict={strict} bits={edge_classes}", flush=True)
+        layers, nb = run_gpu(torch_mod, dg, roots, w.cfg.fanouts, p, strict, 2, 2, 1, 1024, input_global=not strict, exact_ranking=True)
+        compare(layers, nb, w.graph, roots, w.cfg.fanouts, p, strict, 2, 2, 1, 1024, f"exact ranking p={p}", input_global=not strict)
+    graph, n_hubs = many_hubs_graph(seed=3)
+    dg = DeviceGraph(torch_mod, graph, 4, edge_classes=edge_classes)
+    roots = np.arange(n_hubs, dtype=np.int32)
+    for p in (0.5, 1.0):
+        for fan in ([15], [64]):
+            print(f"case exact ranking long rows p={p} fanout={fan} bits={edge_classes}", flush=True)
+            layers, nb = run_gpu(torch_mod, dg, roots, fan, p, False, 5, 1, 0, 16, exact_ranking=True)
+            compare(layers, nb, graph, roots, fan, p, False, 5, 1, 0, 16, f"exact ranking long rows p={p} {fan}")
 
 
 @pytest.mark.parametrize("n_comm,input_global", [(50, True), (50, False), (9000, True)])
