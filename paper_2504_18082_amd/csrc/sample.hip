@@ -247,13 +247,47 @@ __device__ __forceinline__ void select_big_row(const SelectArgs &a, int g, int r
 // general path, which needs no threshold).
 constexpr int CAND_CAP = 128;
 
+// rk[i] += (k < w[i]) for four words at once.  Written out by hand so that the four comparisons land in four different
+// scalar register pairs and the four add-with-carry instructions follow them: the compiler routes every comparison
+// through VCC and has to wait two cycles between each comparison and its add (three instructions lie between a
+// comparison and the add that reads its result here, more than the two wait states the hardware asks for).
+__device__ __forceinline__ void rank4(uint32_t k, const uint32_t (&w)[4], int (&rk)[4])
+{
+    uint64_t s0, s1, s2, s3;
+    asm("v_cmp_lt_u32_e64 %4, %8, %9\n\t"
+        "v_cmp_lt_u32_e64 %5, %8, %10\n\t"
+        "v_cmp_lt_u32_e64 %6, %8, %11\n\t"
+        "v_cmp_lt_u32_e64 %7, %8, %12\n\t"
+        "v_addc_co_u32_e64 %0, %4, 0, %0, %4\n\t"
+        "v_addc_co_u32_e64 %1, %5, 0, %1, %5\n\t"
+        "v_addc_co_u32_e64 %2, %6, 0, %2, %6\n\t"
+        "v_addc_co_u32_e64 %3, %7, 0, %3, %7"
+        : "+v"(rk[0]), "+v"(rk[1]), "+v"(rk[2]), "+v"(rk[3]), "=&s"(s0), "=&s"(s1), "=&s"(s2), "=&s"(s3)
+        : "v"(k), "v"(w[0]), "v"(w[1]), "v"(w[2]), "v"(w[3]));
+}
+// the same with the comparison turned round: rk[i] += (w[i] < k)
+__device__ __forceinline__ void rank4_below(uint32_t k, const uint32_t (&w)[4], int (&rk)[4])
+{
+    uint64_t s0, s1, s2, s3;
+    asm("v_cmp_gt_u32_e64 %4, %8, %9\n\t"
+        "v_cmp_gt_u32_e64 %5, %8, %10\n\t"
+        "v_cmp_gt_u32_e64 %6, %8, %11\n\t"
+        "v_cmp_gt_u32_e64 %7, %8, %12\n\t"
+        "v_addc_co_u32_e64 %0, %4, 0, %0, %4\n\t"
+        "v_addc_co_u32_e64 %1, %5, 0, %1, %5\n\t"
+        "v_addc_co_u32_e64 %2, %6, 0, %2, %6\n\t"
+        "v_addc_co_u32_e64 %3, %7, 0, %3, %7"
+        : "+v"(rk[0]), "+v"(rk[1]), "+v"(rk[2]), "+v"(rk[3]), "=&s"(s0), "=&s"(s1), "=&s"(s2), "=&s"(s3)
+        : "v"(k), "v"(w[0]), "v"(w[1]), "v"(w[2]), "v"(w[3]));
+}
+
 //
 // INTRA_ONLY is the same for p = 1 when the graph carries its edge-class bits: the pool is the row's
 // intra-community slots (counted from the bits first); with fewer of them than the fanout the caller's general
 // path fills up with inter-community ones.
 template <bool INTRA_ONLY>
 __device__ __forceinline__ bool select_big_row_filtered(const SelectArgs &a, int g, int row, int32_t v, int64_t base, int deg,
-                                                        int lane, uint2 *cand)
+                                                        int lane, uint32_t *ckey /*[CAND_CAP + 4]*/, uint32_t *cslot /*[CAND_CAP]*/)
 {
     const int k = a.fanout;
     const uint32_t batch = a.first_batch + (uint32_t)g;
@@ -276,7 +310,8 @@ __device__ __forceinline__ bool select_big_row_filtered(const SelectArgs &a, int
     const int64_t w_max = (a.n_entries - 1) >> 5;
     // (float arithmetic: the threshold only steers how many candidates there are, any value gives the same result)
     const float thr_f = (float)a.cand_target * 4294967296.0f / (float)pool;
-    const uint64_t thr = thr_f >= 4294967296.0f ? 0x100000000ull : (uint64_t)thr_f;     // 2^32 keeps every slot of the pool
+    const bool keep_all = thr_f >= 4294967040.0f;                  // every slot of the pool is a candidate
+    const uint32_t thr = keep_all ? 0xFFFFFFFFu : (uint32_t)thr_f;
     int n = 0;
     for (int j0 = 0; j0 < deg; j0 += 4 * WAVE) {
         const int jb = j0 + 4 * lane;
@@ -293,7 +328,7 @@ __device__ __forceinline__ bool select_big_row_filtered(const SelectArgs &a, int
         uint64_t b[4];
         int before = n, total = 0;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) c[i] = jb + i < deg && (uint64_t)wr[i] < thr && ((nib >> i) & 1u);
+        for (int i = 0; i < 4; ++i) c[i] = jb + i < deg && (keep_all || wr[i] < thr) && ((nib >> i) & 1u);
         if (__ballot(c[0] || c[1] || c[2] || c[3]) == 0) continue;      // (most iterations of a long row)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -304,38 +339,46 @@ __device__ __forceinline__ bool select_big_row_filtered(const SelectArgs &a, int
         if (n + total > CAND_CAP) return false;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            if (c[i]) cand[before] = make_uint2(wr[i], (uint32_t)(jb + i));
+            if (c[i]) { ckey[before] = wr[i]; cslot[before] = (uint32_t)(jb + i); }
             before += c[i] ? 1 : 0;
         }
         n += total;
     }
     if (n < k) return false;
+    if (lane < 4) ckey[n + lane] = ~0u;            // pad the words to a multiple of four with the largest one
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
 
-    // candidate t sits at index t in slot order; a lane owns candidates lane and lane + 64
-    const uint2 c0 = cand[min(lane, n - 1)], c1 = cand[min(lane + WAVE, n - 1)];
+    // candidate t sits at index t in slot order; a lane owns candidates lane and lane + 64.  Words only are compared: with
+    // equal words at the boundary the kept count is off and the caller's general path takes the row.
     const bool have0 = lane < n, have1 = lane + WAVE < n;
-    int r0 = 0, r1 = 0;
+    const uint32_t w0 = ckey[min(lane, n - 1)], w1 = ckey[min(lane + WAVE, n - 1)];
+    int ra[4] = {0, 0, 0, 0}, rb[4] = {0, 0, 0, 0};
     if (n <= WAVE) {
-        for (int t = 0; t < n; ++t) {
-            const uint32_t wt = cand[t].x;
-            r0 += (wt < c0.x || (wt == c0.x && t < lane)) ? 1 : 0;
+        for (int t0 = 0; t0 < n; t0 += 4) {
+            const uint4 kt = *reinterpret_cast<const uint4 *>(ckey + t0);
+            const uint32_t ks[4] = {kt.x, kt.y, kt.z, kt.w};
+            rank4_below(w0, ks, ra);
         }
     } else {
-        for (int t = 0; t < n; ++t) {
-            const uint32_t wt = cand[t].x;
-            r0 += (wt < c0.x || (wt == c0.x && t < lane)) ? 1 : 0;
-            r1 += (wt < c1.x || (wt == c1.x && t < lane + WAVE)) ? 1 : 0;
+        for (int t0 = 0; t0 < n; t0 += 4) {
+            const uint4 kt = *reinterpret_cast<const uint4 *>(ckey + t0);
+            const uint32_t ks[4] = {kt.x, kt.y, kt.z, kt.w};
+            rank4_below(w0, ks, ra);
+            rank4_below(w1, ks, rb);
         }
     }
+    const int r0 = ra[0] + ra[1] + ra[2] + ra[3], r1 = rb[0] + rb[1] + rb[2] + rb[3];
     const bool s0 = have0 && r0 < k, s1 = have1 && r1 < k;
     const uint64_t m0 = __ballot(s0), m1 = __ballot(s1);
-    int32_t *sel_row = sel_row_ptr(a, g, row);
-    if (s0) sel_row[__popcll(m0 & lt_mask)] = a.g_indices[base + c0.y];
-    if (s1) sel_row[__popcll(m0) + __popcll(m1 & lt_mask)] = a.g_indices[base + c1.y];
-    if (lane == 0) set_row_count(a, g, row, k);
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");      // the buffer is reused by this wave's next long row
-    return true;
+    const bool exact = __popcll(m0) + __popcll(m1) == k;
+    if (exact) {
+        int32_t *sel_row = sel_row_ptr(a, g, row);
+        if (s0) sel_row[__popcll(m0 & lt_mask)] = a.g_indices[base + cslot[lane]];
+        if (s1) sel_row[__popcll(m0) + __popcll(m1 & lt_mask)] = a.g_indices[base + cslot[lane + WAVE]];
+        if (lane == 0) set_row_count(a, g, row, k);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");      // the buffers are reused by this wave's next long row
+    return exact;
 }
 
 // Long rows for 0.5 < p < 1, with the graph's edge-class bits.  A slot's key is E(r) * m with m = 1-p for an
@@ -569,8 +612,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
     for (int i = 0; i < SEL_ROWS; ++i)
         if (deg[i] > WAVE) {
             uint2 *buf = cand[threadIdx.x / WAVE];
-            if (MODE == 0 && !a.exact_select && select_big_row_filtered<false>(a, g, row0 + i, v[i], base[i], deg[i], lane, buf)) continue;
-            if (MODE == 1 && !a.exact_select && a.edge_intra && select_big_row_filtered<true>(a, g, row0 + i, v[i], base[i], deg[i], lane, buf)) continue;
             if (MODE == 2 && !a.exact_select && a.edge_intra &&
                 select_big_row_weighted(a, g, row0 + i, v[i], base[i], deg[i], lane, buf, ckey[threadIdx.x / WAVE])) continue;
             select_big_row<MODE>(a, g, row0 + i, v[i], base[i], deg[i], cv[i], lane);
@@ -698,12 +739,15 @@ __device__ __forceinline__ uint32_t quad_pass(const SelectArgs &a, int g, int ro
             const uint4 kt = *reinterpret_cast<const uint4 *>(kl + t0);
             const uint32_t ks[4] = {kt.x, kt.y, kt.z, kt.w};
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
+            for (int q = 0; q < 4; ++q) {
+                if (!EXACT) {
+                    rank4(ks[q], wr, rk);
+                } else {
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    if (!EXACT) rk[i] += ks[q] < wr[i] ? 1 : 0;
-                    else rk[i] += (ks[q] < wr[i] || (ks[q] == wr[i] && t0 + q < cpos + (int)__popc(cm & ((1u << i) - 1u)))) ? 1 : 0;
+                    for (int i = 0; i < 4; ++i)
+                        rk[i] += (ks[q] < wr[i] || (ks[q] == wr[i] && t0 + q < cpos + (int)__popc(cm & ((1u << i) - 1u)))) ? 1 : 0;
                 }
+            }
         }
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");      // the list is reused by the next pass
@@ -735,7 +779,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
     __shared__ QuadRow rows_s[4][QUAD_ROWS];
     __shared__ int startq_s[4][QUAD_ROWS];
     __shared__ __align__(16) uint32_t klist_s[4][4 * WAVE];
-    __shared__ uint2 cand[4][CAND_CAP];
+    __shared__ uint32_t cslot_s[4][CAND_CAP];
     const int wv = (int)threadIdx.x / WAVE;
     const int g = blockIdx.y;
     const int n_dst = group_n_dst(a.prev_hdr, g, a.n_roots_total, a.batch_size);
@@ -789,7 +833,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
         if (deg <= QUAD_MAX_DEG) continue;
         const int32_t v = (int32_t)rl32((uint32_t)mv, i);
         const int64_t base = (int64_t)rl64((uint64_t)mbase, i);
-        if (!a.exact_select && select_big_row_filtered<MODE == 1>(a, g, row0 + i, v, base, deg, lane, cand[wv])) continue;
+        if (!a.exact_select && select_big_row_filtered<MODE == 1>(a, g, row0 + i, v, base, deg, lane, klist_s[wv], cslot_s[wv])) continue;
         select_big_row<MODE>(a, g, row0 + i, v, base, deg, MODE == 1 ? a.comm[v] : 0, lane);
     }
 }
