@@ -635,8 +635,13 @@ __device__ __forceinline__ void gemm_tn_body(const TnArgs &a, uint32_t bid, uint
     // three steps stay in flight together.
     const int op = tid >> 7;                       // 0: A, 1: Z (uniform per wave)
     const int st = tid & 127, mg = st >> 4, sc = (st & 15) * 8;
-    const uint16_t *base = op == 0 ? (part == 0 ? a.A0 : a.A1) : a.Z;
-    const uint32_t ld_bytes = (uint32_t)((op == 0 ? a.lda : (int64_t)a.N) * 2);
+    // (op is the same for a whole wave; the descriptor is built from values the compiler can see are wave-uniform --
+    // with a descriptor it takes for lane-dependent it wraps every load in a loop over the distinct descriptors and then
+    // waits for nearly all earlier loads before each new one, which undoes the ring)
+    const uint64_t base_v = reinterpret_cast<uint64_t>(op == 0 ? (part == 0 ? a.A0 : a.A1) : a.Z);
+    const uint16_t *base = reinterpret_cast<const uint16_t *>(
+        ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(base_v >> 32)) << 32) | (uint32_t)__builtin_amdgcn_readfirstlane((int)base_v));
+    const uint32_t ld_bytes = (uint32_t)__builtin_amdgcn_readfirstlane((int)((op == 0 ? a.lda : (int64_t)a.N) * 2));
     const bool col_ok = op == 0 ? sc < k_valid : n0 + sc < a.N;
     const uint32_t col_bytes = (uint32_t)((op == 0 ? kp0 + sc : n0 + sc) * 2);
     const __amdgpu_buffer_rsrc_t rsrc =
@@ -712,14 +717,20 @@ __device__ __forceinline__ void gemm_tn_body(const TnArgs &a, uint32_t bid, uint
 #pragma unroll
                 for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x[i], z[j], acc[i][j], 0, 0, 0);
         }
-        if (t + 1 < nsteps) stage(slot_next_stage, buf ^ 1);
+        // (unconditional, also after the last step, where it stores the zeros that loads past the end return: with a
+        // branch here the compiler sees a path on which a ring slot's loads are never waited for, and drains every
+        // outstanding load at the head of the loop)
+        stage(slot_next_stage, buf ^ 1);
         __syncthreads();
     };
-    for (int t = 0; t < nsteps; t += 3) {
+    int t = 0;
+    for (; t + 3 <= nsteps; t += 3) {
         body(t, ring[0], ring[1]);
-        if (t + 1 < nsteps) body(t + 1, ring[1], ring[2]);
-        if (t + 2 < nsteps) body(t + 2, ring[2], ring[0]);
+        body(t + 1, ring[1], ring[2]);
+        body(t + 2, ring[2], ring[0]);
     }
+    if (t < nsteps) body(t, ring[0], ring[1]);
+    if (t + 1 < nsteps) body(t + 1, ring[1], ring[2]);
 
     float *P = a.partial + (int64_t)split * (a.K2 + 1) * a.N;
 #pragma unroll
@@ -877,6 +888,7 @@ static void split_plan(int F_pad, int N_pad, int n_op, int max_rows, int &rows_p
 {
     const int tiles = (int)(n_op * ceil_div(F_pad, 128) * ceil_div(N_pad, 128));
     int target = 512 / tiles;        // two workgroups of this kernel are resident per compute unit: one round of workgroups
+    if (const char *e = getenv("CR_TN_WGS")) target = atoi(e) / tiles;     // EXPERIMENT
     if (target < 1) target = 1;
     if (target > 128) target = 128;
     int rows = (int)round_up(ceil_div(max_rows, target), 96);
