@@ -14,6 +14,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4v __attribute__((ext_vector_type(4)));
 typedef short v4s16 __attribute__((ext_vector_type(4)));
 
+constexpr int TN_BM = 32;     // rows of the operands staged per step of the TN product (a multiple of 16; 96-row splits hold two)
 constexpr int TN_ROW = 144;   // staged row of the TN product: 128 columns + 16 of padding (288 bytes)
 
 constexpr int LDS_ROW = 40;   // 32 bf16 of payload + 8 of padding per staged row (80 bytes)
@@ -586,8 +587,9 @@ static void launch_nt(const NtArgs &a, hipStream_t s)
 // ------------------------------------------------------------------------------------------------
 // P[s][k][n] = sum_{m in split s} A[m][k] * Z[m][n]      (both operands strided along m).  Also the
 // column sums of Z per split (bias gradient).
-// Workgroup tile 128 (k) x 128 (n), four waves of 64 x 64; 32 rows of m per step.  Half of the
-// threads stage A, half stage Z: a thread fetches one 8-column chunk of four consecutive rows and
+// Workgroup tile 128 (k) x 128 (n), four waves of 64 x 64; TN_BM rows of m per step (one barrier per step: taller
+// steps spread its cost and the LDS round trip over more MFMAs).  Half of the
+// threads stage A, half stage Z: a thread fetches one 8-column chunk of TN_BM / 8 consecutive rows and
 // writes it transposed as eight 64-bit LDS stores (four m of one column each), so the MFMA operands
 // are again 16-byte reads along m.  Global loads run three steps ahead in a register ring.
 // ------------------------------------------------------------------------------------------------
@@ -607,7 +609,7 @@ struct TnArgs {
 // the transposition the MFMA operands need (eight consecutive m of one column per lane) is done by the LDS
 // transpose read of gfx950.  Row stride 288 bytes: the four 32-byte row pieces a 16-lane group reads
 // fall into disjoint banks.  `bid` is the workgroup's number among the `ntile` x (splits) workgroups of the product.
-__device__ __forceinline__ void gemm_tn_body(const TnArgs &a, uint32_t bid, uint32_t ntile, uint16_t (&T)[2][2][32][TN_ROW])
+__device__ __forceinline__ void gemm_tn_body(const TnArgs &a, uint32_t bid, uint32_t ntile, uint16_t (&T)[2][2][TN_BM][TN_ROW])
 {
     const int M = min(a.hdr[CR_HDR_N_DST], a.max_rows);
     // the tiles of one split run next to each other on one XCD (they share the split's rows of A and Z);
@@ -647,25 +649,26 @@ __device__ __forceinline__ void gemm_tn_body(const TnArgs &a, uint32_t bid, uint
     const __amdgpu_buffer_rsrc_t rsrc =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(base), 0, (int)((uint32_t)m_end * ld_bytes), 0x00020000);
 
-    uint4 ring[3][4];
-    auto fetch = [&](uint4 (&r)[4], int step) {
-        const uint32_t mrow = (uint32_t)(m_begin + step * 32 + mg * 4);
+    constexpr int RPT = TN_BM / 8;                 // rows per thread and step: row group mg takes rows mg * RPT .. + RPT
+    uint4 ring[3][RPT];
+    auto fetch = [&](uint4 (&r)[RPT], int step) {
+        const uint32_t mrow = (uint32_t)(m_begin + step * TN_BM + mg * RPT);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < RPT; ++i) {
             const uint32_t off = col_ok ? (mrow + i) * ld_bytes + col_bytes : 0xFFFFFFF0u;
             const u32x4v v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)off, 0, 0);
             r[i] = make_uint4(v[0], v[1], v[2], v[3]);
         }
     };
-    // a thread holds an 8-column chunk of four consecutive rows: four plain 16-byte stores
+    // a thread holds an 8-column chunk of RPT consecutive rows: plain 16-byte stores
     float cacc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};      // column sums of Z over this thread's rows (kt == 0 only)
     const bool do_colsum = kt == 0 && op == 1;
-    auto stage = [&](const uint4 (&r)[4], int buf) {
+    auto stage = [&](const uint4 (&r)[RPT], int buf) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) *reinterpret_cast<uint4 *>(&T[buf][op][mg * 4 + i][sc]) = r[i];
+        for (int i = 0; i < RPT; ++i) *reinterpret_cast<uint4 *>(&T[buf][op][mg * RPT + i][sc]) = r[i];
         if (do_colsum) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
+            for (int i = 0; i < RPT; ++i) {
                 cacc[0] += __uint_as_float(r[i].x << 16); cacc[1] += __uint_as_float(r[i].x & 0xFFFF0000u);
                 cacc[2] += __uint_as_float(r[i].y << 16); cacc[3] += __uint_as_float(r[i].y & 0xFFFF0000u);
                 cacc[4] += __uint_as_float(r[i].z << 16); cacc[5] += __uint_as_float(r[i].z & 0xFFFF0000u);
@@ -694,18 +697,18 @@ __device__ __forceinline__ void gemm_tn_body(const TnArgs &a, uint32_t bid, uint
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    const int nsteps = (m_end - m_begin + 31) / 32;
+    const int nsteps = (m_end - m_begin + TN_BM - 1) / TN_BM;
     fetch(ring[0], 0);
     fetch(ring[1], 1);
     fetch(ring[2], 2);
     stage(ring[0], 0);
     __syncthreads();
 
-    auto body = [&](int t, uint4 (&slot_next_fetch)[4], const uint4 (&slot_next_stage)[4]) {
+    auto body = [&](int t, uint4 (&slot_next_fetch)[RPT], const uint4 (&slot_next_stage)[RPT]) {
         const int buf = t & 1;
         fetch(slot_next_fetch, t + 3);             // the slot that held step t (already staged)
 #pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
+        for (int kk = 0; kk < TN_BM / 16; ++kk) {
             bf16x8 x[2], z[2];
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
@@ -763,7 +766,7 @@ __device__ __forceinline__ void gemm_tn_body(const TnArgs &a, uint32_t bid, uint
 
 __global__ __launch_bounds__(256) void gemm_tn_kernel(TnArgs a)
 {
-    __shared__ __attribute__((aligned(16))) uint16_t T[2][2][32][TN_ROW];
+    __shared__ __attribute__((aligned(16))) uint16_t T[2][2][TN_BM][TN_ROW];
     gemm_tn_body(a, blockIdx.y * gridDim.x + blockIdx.x, gridDim.x, T);
 }
 
@@ -773,10 +776,10 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(TnArgs a)
 // XCD mapping) run the weight-gradient product, the rest the input-gradient product.
 __global__ __launch_bounds__(256) void gemm_tn_nt_kernel(TnArgs t, NtArgs n, uint32_t tn_blocks, uint32_t tn_tiles, uint32_t nt_cols)
 {
-    __shared__ __attribute__((aligned(16))) uint16_t lds[2 * 2 * 32 * TN_ROW];
+    __shared__ __attribute__((aligned(16))) uint16_t lds[2 * 2 * TN_BM * TN_ROW];
     static_assert(sizeof(lds) >= sizeof(uint16_t) * (2 * 128 * LDS_ROW + 2 * 64 * LDS_ROW), "the staging tiles of either product fit");
     if (blockIdx.x < tn_blocks) {
-        gemm_tn_body(t, blockIdx.x, tn_tiles, *reinterpret_cast<uint16_t (*)[2][2][32][TN_ROW]>(lds));
+        gemm_tn_body(t, blockIdx.x, tn_tiles, *reinterpret_cast<uint16_t (*)[2][2][TN_BM][TN_ROW]>(lds));
     } else {
         gemm_nt_body<2, 4>(n, blockIdx.x - tn_blocks, nt_cols, *reinterpret_cast<uint16_t (*)[2][128][LDS_ROW]>(lds),
                            *reinterpret_cast<uint16_t (*)[2][64][LDS_ROW]>(lds + 2 * 128 * LDS_ROW));
@@ -887,8 +890,9 @@ __global__ __launch_bounds__(256) void count_correct_kernel(const int32_t *hdr, 
 static void split_plan(int F_pad, int N_pad, int n_op, int max_rows, int &rows_per_split, int &n_splits)
 {
     const int tiles = (int)(n_op * ceil_div(F_pad, 128) * ceil_div(N_pad, 128));
-    int target = 512 / tiles;        // two workgroups of this kernel are resident per compute unit: one round of workgroups
-    if (const char *e = getenv("CR_TN_WGS")) target = atoi(e) / tiles;     // EXPERIMENT
+    // one workgroup per compute unit: with two (the kernel's residency) the product itself is no faster, and the partial
+    // sums -- written once and read once by the reduction -- double
+    int target = 256 / tiles;
     if (target < 1) target = 1;
     if (target > 128) target = 128;
     int rows = (int)round_up(ceil_div(max_rows, target), 96);
