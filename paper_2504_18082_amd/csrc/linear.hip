@@ -410,15 +410,15 @@ __global__ __launch_bounds__(256) void gemm_nt_small_kernel(NtArgs a, XentArgs x
 }
 
 // ------------------------------------------------------------------------------------------------
-// The same product for the input layer of the large workloads: tens of thousands of rows, K = 2 x 128 (self | aggregate,
-// 128 features each after padding), N = 256.  The tiled kernel above reads every activation row four times (once per
-// 64-column tile) and spends most of its time moving operands; here one workgroup per compute unit takes 256 rows and
-// ALL columns, so activations and weights pass through a compute unit once:
-//   - K is taken in its two natural halves (the self array against W_self, the aggregate array against W_neigh).  A
-//     half is 256 rows x 256 bytes of activations, one contiguous 64 KB block of the operand array, and 256 x 256 bytes
-//     of weights: both are fetched with fully coalesced 16-byte loads (16 per thread each) and laid out in LDS with rows
-//     padded by 16 bytes, so that the MFMA fragments are conflict-free 16-byte LDS reads;
-//   - the second half's loads are issued inside the first half's K loop, four per step, and travel under its MFMAs
+// The same product for the input layer of the large workloads: tens of thousands of rows, N = 256, any K (GraphSAGE:
+// self | aggregate, 2 x 128 features after padding; one-operand layers: all of K from one array).  The tiled kernel
+// above reads every activation row four times (once per 64-column tile) and spends most of its time moving operands;
+// here one workgroup per compute unit takes 256 rows and ALL columns, so activations pass through a compute unit once:
+//   - K is taken in chunks of 128 columns.  A chunk is 256 rows x 256 bytes of activations and 256 x 256 bytes of
+//     weights: both are fetched with coalesced 16-byte loads (16 per thread each) and laid out in LDS with rows
+//     padded by 16 bytes, so that the MFMA fragments are conflict-free 16-byte LDS reads; a last chunk that reaches
+//     past K is staged with zeros there;
+//   - the next chunk's loads are issued inside the current chunk's K loop, four per step, and travel under its MFMAs
 //     (issued in one go they hold the wave, the only one on its SIMD, for as long as the memory pipeline takes them);
 //   - a wave owns 64 rows x 256 columns (256 accumulator registers, one wave per SIMD): per 16-wide K step 10 fragment
 //     reads feed 16 MFMAs; the fragments of step s + 1 are requested before the MFMAs of step s are issued, because no
@@ -427,7 +427,7 @@ __global__ __launch_bounds__(256) void gemm_nt_small_kernel(NtArgs a, XentArgs x
 //     where whole 512-byte rows leave.
 // ------------------------------------------------------------------------------------------------
 constexpr int WIDE_ROWS = 256;          // rows per workgroup
-constexpr int WIDE_KH = 128;            // K of one half
+constexpr int WIDE_KH = 128;            // K of one chunk
 constexpr int WIDE_N = 256;
 constexpr int WIDE_LROW = WIDE_KH + 8;  // staged row: 128 bf16 + 8 of padding (272 bytes)
 constexpr int WIDE_OROW = WIDE_N + 8;   // staged output row
@@ -435,40 +435,56 @@ constexpr size_t WIDE_LDS_BYTES = (size_t)2 * 256 * WIDE_LROW * sizeof(uint16_t)
 
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void gemm_nt_wide_kernel(NtArgs a)
 {
-    constexpr int KSTEPS = WIDE_KH / 16, NTILES = WIDE_N / 32, K = 2 * WIDE_KH;
+    constexpr int KSTEPS = WIDE_KH / 16, NTILES = WIDE_N / 32;
     extern __shared__ __attribute__((aligned(16))) uint16_t wide_lds[];
     uint16_t *Ws = wide_lds;                                   // [256 n][WIDE_LROW]
     uint16_t *As = wide_lds + 256 * WIDE_LROW;                 // [256 m][WIDE_LROW]
     float *bias_s = reinterpret_cast<float *>(wide_lds + 2 * 256 * WIDE_LROW);
     static_assert((size_t)4 * 64 * WIDE_OROW * sizeof(uint16_t) <= (size_t)2 * 256 * WIDE_LROW * sizeof(uint16_t), "output staging must fit");
     const int M = min(a.hdr[CR_HDR_N_DST], a.max_rows);
-    const int m0 = (int)blockIdx.x * WIDE_ROWS;
-    if (m0 >= M) return;
+    if ((int)blockIdx.x * WIDE_ROWS >= M) return;
+    // the last tile is moved back so that it ends at the last row: it recomputes a few rows of its neighbour (same
+    // values, written twice) and no load has to be clamped to the row count.  With fewer than 256 rows the one tile
+    // reads rows past the last one: they exist (the arrays hold max_rows >= 16384 rows), rows are independent, and
+    // results past the last row are not stored.
+    const int m0 = max(0, min((int)blockIdx.x * WIDE_ROWS, M - WIDE_ROWS));
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, lr = lane & 31;
+    const int K = a.K, K0 = a.K0;
+    const int nchunk = (K + WIDE_KH - 1) / WIDE_KH;
 
-    // staging assignment: chunk c = i * 256 + tid of a half = (row c / 16, 16-byte piece c % 16)
+    // staging assignment: piece p = i * 256 + tid of a chunk = (row p / 16, 16-byte piece p % 16).  Column k of the
+    // product sits in the first operand array for k < K0 and in the second from there on; a chunk lies in one of the two
+    // (K0 is a multiple of 128, or there is one operand only).  An address is a base that is the same for the whole
+    // workgroup (chunk, 16-row group i) plus one per-thread offset that serves all 16 pieces: no address registers are
+    // held across the K loop.  Pieces past K (last chunk of a K that is no multiple of 128) are loaded from the chunk's
+    // first piece and staged as zeros.
     const int srow = tid >> 4, spiece = tid & 15;
     u32x4v wreg[16], areg[16];
-    auto fetch = [&](int h, int i) {     // pieces i of the half's 16 activation and 16 weight pieces of this thread
-        const uint16_t *A = h == 0 ? a.A0 : a.A1;
-        const int row = i * 16 + srow;
-        areg[i] = *reinterpret_cast<const u32x4v *>(A + (int64_t)min(m0 + row, M - 1) * a.lda + spiece * 8);
-        wreg[i] = *reinterpret_cast<const u32x4v *>(a.B + (int64_t)row * K + h * WIDE_KH + spiece * 8);
+    auto fetch = [&](int c, int i) {     // pieces i of the chunk's 16 activation and 16 weight pieces of this thread
+        const int kbase = c * WIDE_KH;
+        const int sp = kbase + spiece * 8 < K ? spiece * 8 : 0;
+        const uint16_t *Ai = (kbase < K0 ? a.A0 + kbase : a.A1 + (kbase - K0)) + (int64_t)(m0 + i * 16) * a.lda;
+        const uint16_t *Wi = a.B + kbase + (int64_t)(i * 16) * K;
+        areg[i] = *reinterpret_cast<const u32x4v *>(Ai + (uint32_t)(srow * (int)a.lda + sp));
+        wreg[i] = *reinterpret_cast<const u32x4v *>(Wi + (uint32_t)(srow * K + sp));
     };
-    auto stage = [&]() {
+    auto stage = [&](int c) {
+        const bool full = (c + 1) * WIDE_KH <= K;              // (uniform)
+        const bool mine = c * WIDE_KH + spiece * 8 < K;
+        const u32x4v zero = {0u, 0u, 0u, 0u};
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             const int row = i * 16 + srow;
-            *reinterpret_cast<u32x4v *>(&As[row * WIDE_LROW + spiece * 8]) = areg[i];
-            *reinterpret_cast<u32x4v *>(&Ws[row * WIDE_LROW + spiece * 8]) = wreg[i];
+            *reinterpret_cast<u32x4v *>(&As[row * WIDE_LROW + spiece * 8]) = (full || mine) ? areg[i] : zero;
+            *reinterpret_cast<u32x4v *>(&Ws[row * WIDE_LROW + spiece * 8]) = (full || mine) ? wreg[i] : zero;
         }
     };
 #pragma unroll
     for (int i = 0; i < 16; ++i) fetch(0, i);
     if (tid < WIDE_N / 4)
         *reinterpret_cast<float4 *>(&bias_s[tid * 4]) = a.bias ? *reinterpret_cast<const float4 *>(a.bias + tid * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
-    stage();
+    stage(0);
     __syncthreads();
 
     // the accumulators start from the bias (a lane's 4-column pieces: columns t*32 + 8*grp + 4*half .. + 4)
@@ -485,8 +501,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         }
     const uint16_t *arow0 = As + (wave * 64 + lr) * WIDE_LROW + 8 * half, *arow1 = arow0 + 32 * WIDE_LROW;
     const uint16_t *wrow = Ws + lr * WIDE_LROW + 8 * half;
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
+    // one chunk's K loop; PREFETCH: the next chunk's loads, two of each per step, travel under the MFMAs
+    auto chunk_loop = [&](auto prefetch, int c) {
+        constexpr bool PREFETCH = decltype(prefetch)::value;
         bf16x8 wnext[NTILES], anext[2];
         anext[0] = lds_read8(arow0);
         anext[1] = lds_read8(arow1);
@@ -504,9 +521,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #pragma unroll
                 for (int t = 0; t < NTILES; ++t) wnext[t] = lds_read8(wrow + t * 32 * WIDE_LROW + (ks + 1) * 16);
             }
-            if (h == 0) {                 // the second half's loads, two of each per step: they travel under the MFMAs
-                fetch(1, 2 * ks);
-                fetch(1, 2 * ks + 1);
+            if constexpr (PREFETCH) {
+                fetch(c + 1, 2 * ks);
+                fetch(c + 1, 2 * ks + 1);
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -516,12 +533,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
             }
             __builtin_amdgcn_sched_barrier(0);
         }
-        __syncthreads();                  // every wave is done reading this half
-        if (h == 0) {
-            stage();
-            __syncthreads();
-        }
+    };
+    // (the last chunk is peeled off: with the prefetch and the staging under a condition inside one loop the compiler
+    // keeps the 128 staging registers alive across the whole loop and spills)
+    for (int c = 0; c + 1 < nchunk; ++c) {
+        chunk_loop(std::true_type{}, c);
+        __syncthreads();                  // every wave is done reading this chunk
+        stage(c + 1);
+        __syncthreads();
     }
+    chunk_loop(std::false_type{}, nchunk - 1);
+    __syncthreads();
 
     // epilogue: ReLU, bf16; a lane holds, for row lr of each block, the columns t*32 + 8*grp + 4*half .. + 4
     const float floor_v = a.relu ? 0.f : -INFINITY;
@@ -562,8 +584,8 @@ constexpr int NT_DEEP_MIN_K = 768;            // ... a K loop of at least 24 ste
 static void launch_nt(const NtArgs &a, hipStream_t s)
 {
     // many rows against weights that fit one compute unit's LDS, bf16 output only: the weight-stationary kernel
-    if (a.max_rows >= NT_WIDE_MIN_ROWS && a.N == WIDE_N && a.K == 2 * WIDE_KH && a.K0 == WIDE_KH && a.A1 != nullptr && a.Cb != nullptr &&
-        a.C0 == nullptr && a.ldcb == a.N) {
+    if (a.max_rows >= NT_WIDE_MIN_ROWS && a.N == WIDE_N && (a.K0 == a.K || a.K0 % WIDE_KH == 0) && a.A1 != nullptr && a.Cb != nullptr &&
+        a.C0 == nullptr && a.ldcb == a.N && a.lda < (1 << 20)) {
         static const bool ready = [] {
             return hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_nt_wide_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)WIDE_LDS_BYTES) == hipSuccess;

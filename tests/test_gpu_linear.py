@@ -72,31 +72,43 @@ def test_linear_fwd(torch_mod, M, F_in, F_out, relu):
     assert_close(gb[:M, :F_out], want, RTOL_BF16, "out_bf16")
 
 
-@pytest.mark.parametrize("M,F_in,F_out,relu", [(20001, 128, 256, True), (61221, 100, 256, True), (16384, 128, 200, False)])
-def test_linear_fwd_many_rows_bf16_output(torch_mod, M, F_in, F_out, relu):
-    """The input layer of the large workloads: tens of thousands of rows, K = N = 256 after padding, bf16 output only
-    (the weight-stationary kernel: whole weight matrix in LDS, 256 rows per workgroup)."""
+@pytest.mark.parametrize("M,F_in,F_out,relu,cap,n_op", [
+    (20001, 128, 256, True, None, 2), (61221, 100, 256, True, None, 2), (16384, 128, 200, False, None, 2),
+    (17003, 256, 256, True, None, 2),          # K = 512: four chunks of 128
+    (100, 128, 256, True, 16500, 2),           # fewer rows than one tile holds, capacity still large
+    (16640, 128, 256, False, 16700, 2),        # last tile moved back onto its neighbour
+    (18000, 602, 256, False, None, 1),         # one operand, K = 608: five chunks, the last one a partial one
+    (16500, 32, 256, True, None, 1)])          # one operand, K = 32: a single partial chunk
+def test_linear_fwd_many_rows_bf16_output(torch_mod, M, F_in, F_out, relu, cap, n_op):
+    """The input layer of the large workloads: tens of thousands of rows, N = 256 after padding, bf16 output only
+    (the weight-stationary kernel: 256 rows x all columns per workgroup, K in chunks of 128)."""
     torch = torch_mod
     from paper_2504_18082_amd import binding as B
     rng = np.random.default_rng(M + F_in)
-    print(f"case fwd wide M={M} F_in={F_in} F_out={F_out}", flush=True)
+    print(f"case fwd wide M={M} F_in={F_in} F_out={F_out} cap={cap} operands={n_op}", flush=True)
     hs = rng.standard_normal((M, F_in)).astype(np.float32)
     ag = rng.standard_normal((M, F_in)).astype(np.float32) * 0.5
-    W = (rng.standard_normal((2 * F_in, F_out)) / np.sqrt(2 * F_in)).astype(np.float32)
+    W = (rng.standard_normal((n_op * F_in, F_out)) / np.sqrt(n_op * F_in)).astype(np.float32)
     b = rng.standard_normal(F_out).astype(np.float32) * 0.1
     oracle.use_all_cores(True)
     try:
-        want = oracle.sage_linear_fwd(hs, ag, W, b, relu, True)
+        if n_op == 2:
+            want = oracle.sage_linear_fwd(hs, ag, W, b, relu, True)
+        else:                                        # (zero self operand against zero weights adds exact zeros)
+            want = oracle.sage_linear_fwd(np.zeros_like(ag), ag, np.vstack([np.zeros_like(W), W]), b, relu, True)
     finally:
         oracle.use_all_cores(False)
-    layer = B.SageLayer(W, b)
+    layer = B.SageLayer(W, b, n_operands=n_op)
     layer.refresh()
-    cap = M + 300                                    # capacity above the live row count: whole workgroups without rows
+    cap = cap or M + 300                             # capacity above the live row count: whole workgroups without rows
     ld_in = layer.F_pad
-    d_hs, d_ag = to_bf16_dev(torch, np.pad(hs, ((0, 300), (0, 0))), ld_in), to_bf16_dev(torch, np.pad(ag, ((0, 300), (0, 0))), ld_in)
+    pad = ((0, cap - M), (0, 0))
+    # rows past the live ones hold NaNs: they may be read but must not reach any stored result
+    d_hs = to_bf16_dev(torch, np.pad(hs, pad, constant_values=np.nan), ld_in)
+    d_ag = to_bf16_dev(torch, np.pad(ag, pad, constant_values=np.nan), ld_in)
     out_b = torch.full((cap, layer.N_pad), 0x7FC0, dtype=torch.int16, device="cuda")
     hdr = hdr_for(torch, M)
-    B.cr_sage_linear_fwd(layer, C.c_void_p(hdr.data_ptr()), cap, d_hs, d_ag, ld_in, relu, None, out_b)
+    B.cr_sage_linear_fwd(layer, C.c_void_p(hdr.data_ptr()), cap, d_hs if n_op == 2 else None, d_ag, ld_in, relu, None, out_b)
     torch.cuda.synchronize()
     gb = bf16_tensor_to_float(out_b)
     # one rounding to bf16 (2^-9 relative) on top of the float accumulation
