@@ -265,6 +265,15 @@ cr_status cr_sample_blocks_workspace_bytes(const cr_sample_cfg *cfg, int64_t n_n
  * open-addressing table of twice the largest frontier (CR_DEDUP_HASH: larger graphs, or CR_SAMPLE_HASH_DEDUP). */
 #define CR_DEDUP_DIRECT 0
 #define CR_DEDUP_HASH 1
+/* Self-test of the weighted neighbour selection (Section 4.2 with 0.5 < p < 1; exponential-clock keys): the selection
+ * ranks single-precision keys first and accepts a row only if its result provably equals the one of the exact integer
+ * keys, which rests on a bound on the error of the single-precision clock.  This call measures that error over all 2^32
+ * random words on the device.  result: device float[4] (16-byte aligned), written asynchronously on `stream`:
+ * [0] largest |error| in units of 2^-24 over the words of the upper half (clocks below 1), [1] largest relative error
+ * over the lower half, [2] largest error as a fraction of the bound the library assumes (must be <= 1; the library keeps
+ * a factor of two in hand), [3] zero.  ~30 ms.  Errors: CR_ERR_INVALID_ARG. */
+cr_status cr_selftest_clock_approximation(float *result /*device*/, void *stream);
+
 cr_status cr_sample_blocks_dedup_table(const cr_sample_cfg *cfg, int64_t n_nodes, int32_t batch_size, int32_t *kind /*host*/);
 
 /* Samples the blocks of n_batches consecutive mini-batches in one set of launches.

@@ -35,7 +35,7 @@ EXPORTS = [
     "cr_last_error", "cr_version", "cr_mix_count_from_percent",
     "cr_ctx_create", "cr_ctx_destroy", "cr_ctx_make_current", "cr_ctx_poll_error",
     "cr_build_batches_workspace_bytes", "cr_build_batches", "cr_build_batches_static",
-    "cr_graph_edge_classes", "cr_block_capacities", "cr_sample_blocks_workspace_bytes", "cr_sample_blocks_dedup_table", "cr_sample_blocks",
+    "cr_graph_edge_classes", "cr_block_capacities", "cr_sample_blocks_workspace_bytes", "cr_sample_blocks_dedup_table", "cr_sample_blocks", "cr_selftest_clock_approximation",
     "cr_gather_aggregate_fwd", "cr_gather_aggregate_fwd_group", "cr_gather_aggregate_bwd",
     "cr_graph_gcn_norm", "cr_gcn_block_norm", "cr_gcn_aggregate_fwd", "cr_gcn_aggregate_fwd_group", "cr_gcn_aggregate_bwd",
     "cr_sage_padded_dims", "cr_sage_refresh_shadows", "cr_sage_linear_fwd", "cr_sage_linear_fwd_xent",
@@ -126,6 +126,7 @@ def lib():
         L.cr_sample_blocks_workspace_bytes.argtypes = [C.POINTER(cr_sample_cfg), i64, i32, i32,
                                                        C.POINTER(C.c_size_t)]
         L.cr_sample_blocks_dedup_table.argtypes = [C.POINTER(cr_sample_cfg), i64, i32, C.POINTER(i32)]
+        L.cr_selftest_clock_approximation.argtypes = [vp, vp]
         L.cr_graph_edge_classes.argtypes = [C.POINTER(cr_graph), vp, vp]
         L.cr_sample_blocks.argtypes = [C.POINTER(cr_graph), C.POINTER(cr_sample_cfg), vp, i64, i32, i32,
                                        vp, C.c_size_t, C.POINTER(cr_block_set), vp]
@@ -392,6 +393,10 @@ def cr_sample_blocks_workspace_bytes(cfg, n_nodes, batch_size, n_batches) -> int
 
 
 CR_DEDUP_DIRECT, CR_DEDUP_HASH = 0, 1
+
+
+def cr_selftest_clock_approximation(result, stream=None):
+    _check(lib().cr_selftest_clock_approximation(_ptr(result), _stream(stream)))
 
 
 def cr_sample_blocks_dedup_table(cfg, n_nodes, batch_size) -> int:

@@ -12,13 +12,17 @@ constexpr uint64_t EMPTY = ~0ull;
 // ---------------------------------------------------------------------------------------------
 // integer exponential clock: E(r) = -log2((2r+1)/2^33) in Q24, one result bit per squaring
 // ---------------------------------------------------------------------------------------------
+// COMPACT: the squarings as a loop (for the rarely taken exact paths of kernels whose common path should keep its
+// registers: unrolled, four of these chains side by side cost the weighted kernel half its occupancy)
+template <bool COMPACT = false>
 __device__ __forceinline__ uint32_t exp_clock_q24(uint32_t r)
 {
     const uint64_t x = 2ull * r + 1ull;
     const int t = 63 - __clzll((long long)x);
     uint32_t y = (uint32_t)((x << (63 - t)) >> 32);
     uint32_t frac = 0;
-#pragma unroll
+    constexpr int UNROLL = COMPACT ? 1 : 24;
+#pragma unroll UNROLL
     for (int i = 0; i < 24; ++i) {
         const uint32_t hi = __umulhi(y, y), lo = y * y;
         const bool top = (hi >> 31) != 0;
@@ -93,12 +97,12 @@ __device__ __forceinline__ uint32_t pull32(uint32_t v, int src_lane) { return (u
 
 // ordering key of slot j of node v given its random word: narrow mode (p = 0.5) uses the word itself
 // MODE: 0 uniform (p = 0.5), 1 p = 1 (classes only, no clock), 2 weighted (0.5 < p < 1)
-template <int MODE>
+template <int MODE, bool COMPACT = false>
 __device__ __forceinline__ uint64_t slot_key(const SelectArgs &a, uint32_t r, bool intra)
 {
     if (MODE == 0) return r;
     if (MODE == 1) return (intra ? 0ull : (1ull << 62)) + (uint64_t)r;
-    return (uint64_t)exp_clock_q24(r) * (uint64_t)(intra ? a.q_out : a.q_in);
+    return (uint64_t)exp_clock_q24<COMPACT>(r) * (uint64_t)(intra ? a.q_out : a.q_in);
 }
 
 __device__ __forceinline__ uint32_t slot_word(const SelectArgs &a, int j, int32_t v, uint32_t batch)
@@ -113,7 +117,7 @@ __device__ __forceinline__ uint32_t slot_word(const SelectArgs &a, int j, int32_
 // Lanes 0..k-1 hold the k smallest pairs seen so far in ascending order: the first 64 slots are ranked
 // by counting and permuted into place, later chunks of 64 slots are tested against the k-th pair and
 // inserted by shifting.  Every pair is distinct, so the surviving set is unique.
-template <int MODE>
+template <int MODE, bool COMPACT = false>
 __device__ __forceinline__ void select_big_row(const SelectArgs &a, int g, int row, int32_t v, int64_t base, int deg, int32_t cv,
                                             int lane)
 {
@@ -131,7 +135,7 @@ __device__ __forceinline__ void select_big_row(const SelectArgs &a, int g, int r
             ck = ((uint64_t)r << 32) | (uint32_t)j;
             cs = 0;
         } else {
-            ck = slot_key<MODE>(a, r, intra);
+            ck = slot_key<MODE, COMPACT>(a, r, intra);
             cs = (uint32_t)j;
         }
     };
@@ -388,6 +392,7 @@ __device__ __forceinline__ bool select_big_row_filtered(const SelectArgs &a, int
 // slots pass; only those get the 24-squaring clock.  The result is exact iff the fanout-th smallest candidate key
 // is below the smallest key any left-out slot can have, E(threshold - 1) * m per class in integer arithmetic: that is
 // checked, and otherwise (or with too few / too many candidates) the caller takes the general path.
+template <bool COMPACT = false>
 __device__ __forceinline__ bool select_big_row_weighted(const SelectArgs &a, int g, int row, int32_t v, int64_t base, int deg,
                                                         int lane, uint2 *cand, unsigned long long *ckey)
 {
@@ -430,7 +435,7 @@ __device__ __forceinline__ bool select_big_row_weighted(const SelectArgs &a, int
         const uint64_t t = lane == 0 ? t_in : t_out;
         const uint32_t m = lane == 0 ? a.q_out : a.q_in;
         const int pool = lane == 0 ? n_in : n_out;
-        const uint64_t e = (uint64_t)exp_clock_q24((uint32_t)(t > 0 ? t - 1 : 0)) * m;
+        const uint64_t e = (uint64_t)exp_clock_q24<COMPACT>((uint32_t)(t > 0 ? t - 1 : 0)) * m;
         const uint64_t mine = (t == 0 || pool == 0) ? KEY_MAX : e;
         const uint64_t b0 = rl64(mine, 0), b1 = rl64(mine, 1);
         bound = b0 < b1 ? b0 : b1;
@@ -470,9 +475,9 @@ __device__ __forceinline__ bool select_big_row_weighted(const SelectArgs &a, int
     // keys of the candidates only; candidate t sits at index t in slot order, a lane owns candidates lane and lane + 64
     const uint2 c0 = cand[min(lane, n - 1)], c1 = cand[min(lane + WAVE, n - 1)];
     const bool have0 = lane < n, have1 = lane + WAVE < n;
-    const uint64_t key0 = (uint64_t)exp_clock_q24(c0.x) * ((c0.y >> 31) ? a.q_out : a.q_in);
+    const uint64_t key0 = (uint64_t)exp_clock_q24<COMPACT>(c0.x) * ((c0.y >> 31) ? a.q_out : a.q_in);
     uint64_t key1 = KEY_MAX;
-    if (n > WAVE) key1 = (uint64_t)exp_clock_q24(c1.x) * ((c1.y >> 31) ? a.q_out : a.q_in);
+    if (n > WAVE) key1 = (uint64_t)exp_clock_q24<COMPACT>(c1.x) * ((c1.y >> 31) ? a.q_out : a.q_in);
     if (have0) ckey[lane] = key0;
     if (have1) ckey[lane + WAVE] = key1;
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -632,6 +637,40 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
 // four comparisons per lane).  The ranking compares words only; a row whose kept count then differs from the count it must
 // have (a threshold that let fewer than m slots through, or equal words at the boundary) is redone without threshold and
 // with (word, slot) pairs compared in full, so the result is exact in every case.
+//
+// Weighted sampling (0.5 < p < 1) takes the same passes with single-precision keys: approx_clock(r) * m_class, compared
+// through their bit patterns (all positive).  They decide only WHICH slots are kept (the output is in slot order), so the
+// result is exact whenever the largest kept key and the smallest key left out are further apart than the keys' error
+// bounds; that is checked per row, and a row that fails (or whose threshold let too few slots through) is redone with
+// the exact integer keys.  The bound |approx_clock(r) * 2^24 - E(r)| <= CLOCK_ERR_ABS + CLOCK_ERR_REL * E(r) (E in its
+// Q24 units) holds with a factor of two to spare for every one of the 2^32 words: cr_selftest_clock_approximation
+// measures it on the device.
+constexpr float CLOCK_ERR_ABS = 8.0f;             // Q24 units
+constexpr float CLOCK_ERR_REL = 0x1p-17f;       // (measured: 3 units / 2^-19)
+
+__device__ __forceinline__ float approx_clock(uint32_t r)
+{
+    // (2r+1) / 2^33 below one half: 33 - log2(2r+1), the argument rounded to 24 bits.  Above: the distance from one,
+    // d = 2^33 - (2r+1), is converted instead, so that the small clocks -- the ones that get picked -- keep their
+    // relative precision.
+    // (one logarithm: the argument is chosen first; the instruction runs at a quarter of the rate of ordinary ones)
+    const bool far = r < 0x80000000u;
+    const float arg = far ? (float)(2u * r + 1u) : 1.0f - (float)(2u * ~r + 1u) * 0x1p-33f;
+    const float lg = __builtin_amdgcn_logf(arg);
+    return far ? 33.0f - lg : __builtin_fabsf(lg);
+}
+
+// Is every key of the kept side provably below every key of the left-out side?  hi = the largest approximate key kept
+// (class weight m_hi), lo = the smallest approximate key left out (class weight m_lo; +infinity: nothing there).  A key's
+// error: its clock's (CLOCK_ERR_ABS + CLOCK_ERR_REL * E, times the class weight) plus the rounding of the product; the
+// last term covers the rounding of this comparison itself.
+__device__ __forceinline__ bool keys_apart(float hi, float m_hi, float lo, float m_lo)
+{
+    if (!(lo < INFINITY)) return true;
+    const float slack = (hi + lo) * (CLOCK_ERR_REL + 0x1p-21f) + CLOCK_ERR_ABS * 0x1p-24f * (m_hi + m_lo);
+    return lo - hi > slack;
+}
+
 constexpr int QUAD_ROWS = 16;            // destination rows per wave
 constexpr int QUAD_MAX_DEG = 4 * WAVE;   // longest row a pass holds
 
@@ -649,7 +688,7 @@ __device__ __forceinline__ int lanes_below(uint64_t mask, int acc)      // acc +
 // One pass; returns the rows (bit r = row r of the wave) that have to be redone exactly.  rowmask: rows to process.
 template <int MODE, bool EXACT>
 __device__ __forceinline__ uint32_t quad_pass(const SelectArgs &a, int g, int row0, int p, uint32_t rowmask, const QuadRow *rows,
-                                              const int *startq, uint32_t *klist, int lane)
+                                              const int *startq, uint32_t *klist, unsigned long long *k64, uint32_t *rowstat, int lane)
 {
     const int f = a.fanout;
     const uint32_t batch = a.first_batch + (uint32_t)g;
@@ -684,16 +723,19 @@ __device__ __forceinline__ uint32_t quad_pass(const SelectArgs &a, int g, int ro
 
     uint32_t pool = vmask, take = 0u;
     int m = min(f, R.deg), P = R.deg, expect = m;
-    if (MODE == 1) {
-        uint32_t nib = 0u;
+    uint32_t nib = 0u;
+    int n_in = 0;
+    if (MODE >= 1) {
         if (active) {
             const int64_t e = R.base + jb, wi = e >> 5, w_max = (a.n_entries - 1) >> 5;
             const uint64_t win = (uint64_t)a.edge_intra[wi] | ((uint64_t)a.edge_intra[min(wi + 1, w_max)] << 32);
             nib = (uint32_t)(win >> (e & 31)) & 0xFu;
         }
+        int unused;
+        seg(nib & vmask, unused, n_in);
+    }
+    if (MODE == 1) {
         const uint32_t in4 = nib & vmask;
-        int unused, n_in;
-        seg(in4, unused, n_in);
         if (n_in >= f) {
             pool = in4; m = f; P = n_in; expect = f;
         } else {
@@ -702,50 +744,102 @@ __device__ __forceinline__ uint32_t quad_pass(const SelectArgs &a, int g, int ro
             expect = n_in + m;
         }
     }
+    // the ordering words of the lane's four slots: the random words themselves, or (weighted) the bit patterns of the
+    // single-precision keys
+    uint32_t kw[4] = {wr[0], wr[1], wr[2], wr[3]};
+    if (MODE == 2 && !EXACT) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) kw[i] = __float_as_uint(approx_clock(wr[i]) * (float)(((nib >> i) & 1u) ? a.q_out : a.q_in));
+    }
     const bool ranked = active && m > 0 && m < P;
     if (!ranked) {
         if (m >= P) take |= pool;           // the whole pool is kept
         pool = 0u;
     }
     uint32_t cm = pool;                      // candidates among this lane's slots
+    float kappa = INFINITY;                  // weighted: every slot that is no candidate has a key of at least this
     if (!EXACT && ranked) {
         // (float arithmetic: the threshold only steers how many candidates there are)
         const float mf = (float)m;
-        const float tf = (mf + 3.0f * __builtin_amdgcn_sqrtf(mf) + 3.0f) * 4294967296.0f * __builtin_amdgcn_rcpf((float)P);
-        if (tf < 4294967040.0f) {
-            const uint32_t T = (uint32_t)tf;
+        const float target = mf + 3.0f * __builtin_amdgcn_sqrtf(mf) + 3.0f;
+        uint32_t T = 0xFFFFFFFFu;
+        bool all = true;
+        if (MODE == 2) {
+            // expected number of keys below kappa: n_in (1 - 2^(-kappa / q_out)) + n_out (1 - 2^(-kappa / q_in)); three
+            // Newton steps from the tangent at zero (never past the root)
+            if (target < (float)P) {
+                const float ln2 = 0.69314718f, fi = (float)n_in, fo = (float)(P - n_in);
+                const float s_in = __builtin_amdgcn_rcpf((float)a.q_out), s_out = __builtin_amdgcn_rcpf((float)a.q_in);
+                float kp = target / (ln2 * (fi * s_in + fo * s_out));
+#pragma unroll
+                for (int it = 0; it < 3; ++it) {
+                    const float ei = __builtin_amdgcn_exp2f(-kp * s_in), eo = __builtin_amdgcn_exp2f(-kp * s_out);
+                    const float gv = fi * (1.0f - ei) + fo * (1.0f - eo) - target;
+                    const float gd = ln2 * (fi * s_in * ei + fo * s_out * eo);
+                    if (gd > 0.0f) kp -= gv / gd;
+                }
+                if (kp > 0.0f && kp < 3.0e38f) { kappa = kp; T = __float_as_uint(kp); all = false; }
+            }
+        } else {
+            const float tf = target * 4294967296.0f * __builtin_amdgcn_rcpf((float)P);
+            if (tf < 4294967040.0f) { T = (uint32_t)tf; all = false; }
+        }
+        if (!all) {
             uint32_t below = 0u;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) below |= (wr[i] < T ? 1u : 0u) << i;
+            for (int i = 0; i < 4; ++i) below |= (kw[i] < T ? 1u : 0u) << i;
             cm &= below;
         }
     }
     int cpos, n_c;
     seg(cm, cpos, n_c);
-    // the row's list: candidates' words in slot order, padded with the largest word to a multiple of four
-    uint32_t *kl = klist + 4 * first;
-    if (active) *reinterpret_cast<uint4 *>(klist + 4 * lane) = make_uint4(~0u, ~0u, ~0u, ~0u);
-    if (ranked) {
-        int k = cpos;
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            if ((cm >> i) & 1u) kl[k++] = wr[i];
-    }
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     int rk[4] = {0, 0, 0, 0};
     const int nc_mine = ranked ? n_c : 0;
-    for (int t0 = 0; __ballot(t0 < nc_mine) != 0; t0 += 4) {
-        if (t0 < nc_mine) {
-            const uint4 kt = *reinterpret_cast<const uint4 *>(kl + t0);
-            const uint32_t ks[4] = {kt.x, kt.y, kt.z, kt.w};
+    if constexpr (MODE == 2 && EXACT) {
+        // the exact integer keys, 64 bits each: every slot of the row is a candidate, (key, slot) pairs compared in full
+        unsigned long long ek[4];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                if (!EXACT) {
-                    rank4(ks[q], wr, rk);
-                } else {
+        for (int i = 0; i < 4; ++i) ek[i] = (uint64_t)exp_clock_q24<true>(wr[i]) * (uint64_t)(((nib >> i) & 1u) ? a.q_out : a.q_in);
+        unsigned long long *kl = k64 + 4 * first;
+        if (ranked) {
+            int k = cpos;
 #pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        rk[i] += (ks[q] < wr[i] || (ks[q] == wr[i] && t0 + q < cpos + (int)__popc(cm & ((1u << i) - 1u)))) ? 1 : 0;
+            for (int i = 0; i < 4; ++i)
+                if ((cm >> i) & 1u) kl[k++] = ek[i];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        for (int t = 0; __ballot(t < nc_mine) != 0; ++t) {
+            if (t < nc_mine) {
+                const unsigned long long kt = kl[t];
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    rk[i] += (kt < ek[i] || (kt == ek[i] && t < cpos + (int)__popc(cm & ((1u << i) - 1u)))) ? 1 : 0;
+            }
+        }
+    } else {
+        // the row's list: candidates' words in slot order, padded with the largest word to a multiple of four
+        uint32_t *kl = klist + 4 * first;
+        if (active) *reinterpret_cast<uint4 *>(klist + 4 * lane) = make_uint4(~0u, ~0u, ~0u, ~0u);
+        if (ranked) {
+            int k = cpos;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if ((cm >> i) & 1u) kl[k++] = kw[i];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        for (int t0 = 0; __ballot(t0 < nc_mine) != 0; t0 += 4) {
+            if (t0 < nc_mine) {
+                const uint4 kt = *reinterpret_cast<const uint4 *>(kl + t0);
+                const uint32_t ks[4] = {kt.x, kt.y, kt.z, kt.w};
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    if (!EXACT) {
+                        rank4(ks[q], kw, rk);
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            rk[i] += (ks[q] < kw[i] || (ks[q] == kw[i] && t0 + q < cpos + (int)__popc(cm & ((1u << i) - 1u)))) ? 1 : 0;
+                    }
                 }
             }
         }
@@ -756,7 +850,35 @@ __device__ __forceinline__ uint32_t quad_pass(const SelectArgs &a, int g, int ro
     for (int i = 0; i < 4; ++i) emit |= (((cm >> i) & 1u) && rk[i] < m) ? 1u << i : 0u;
     int epos, total;
     seg(emit, epos, total);
-    const bool ok = total == expect;      // (always true in the exact pass)
+    bool ok = total == expect;            // (always true in the exact pass)
+    if constexpr (MODE == 2 && !EXACT) {
+        // largest kept key and smallest key left out, per row and class (LDS atomics on the bit patterns):
+        // rowstat[4 r + ..] = max kept intra, max kept inter, min left-out intra, min left-out inter
+        rowstat[lane] = (lane & 2) ? 0x7F800000u : 0u;
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        if (ranked) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if ((cm >> i) & 1u) {
+                    const int cls = ((nib >> i) & 1u) ? 0 : 1;
+                    if (rk[i] < m) atomicMax(&rowstat[4 * r + cls], kw[i]);
+                    else atomicMin(&rowstat[4 * r + 2 + cls], kw[i]);
+                }
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        if (ranked) {
+            const uint4 st = *reinterpret_cast<const uint4 *>(&rowstat[4 * r]);
+            const float m_in = (float)a.q_out, m_out = (float)a.q_in;      // an intra-community slot's clock is scaled by 1 - p
+            const float hi_in = __uint_as_float(st.x), hi_out = __uint_as_float(st.y);
+            const float lo_in = __uint_as_float(st.z), lo_out = __uint_as_float(st.w);
+            // (a slot that is no candidate has an approximate key of at least kappa, whatever its class)
+            ok = ok && keys_apart(hi_in, m_in, lo_in, m_in) && keys_apart(hi_in, m_in, lo_out, m_out) &&
+                 keys_apart(hi_out, m_out, lo_in, m_in) && keys_apart(hi_out, m_out, lo_out, m_out) &&
+                 keys_apart(hi_in, m_in, kappa, m_out) && keys_apart(hi_out, m_out, kappa, m_out);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    }
     if (active && ok) {
         int k = epos;
 #pragma unroll
@@ -773,6 +895,127 @@ __device__ __forceinline__ uint32_t quad_pass(const SelectArgs &a, int g, int ro
     return redo;
 }
 
+// Long rows, weighted, with single-precision keys: the row's slots are filtered by per-class thresholds on the random word
+// (chosen so that about cand_target keys lie below a common kappa), the candidates' keys approx_clock(r) * m_class are
+// ranked through their bit patterns, and the result is accepted if the largest kept key and the smallest key left out
+// (among the candidates, and the smallest a filtered-out slot can have) are further apart than the keys' error bounds.
+// Returns false otherwise (too few or too many candidates, check failed): the caller goes on to the exact paths.
+__device__ __forceinline__ bool select_big_row_weighted_f32(const SelectArgs &a, int g, int row, int32_t v, int64_t base, int deg,
+                                                            int lane, uint32_t *ckey /*[CAND_CAP + 4]*/, uint32_t *cslot /*[CAND_CAP]*/)
+{
+    const int k = a.fanout;
+    const uint32_t batch = a.first_batch + (uint32_t)g;
+    const uint64_t lt_mask = (1ull << lane) - 1ull;
+    const int64_t w_first = base >> 5, e_last = base + deg, w_last = (e_last - 1) >> 5;
+    int n_in = 0;
+    for (int64_t w = w_first + lane; w <= w_last; w += WAVE) {
+        uint32_t bits = a.edge_intra[w];
+        if (w == w_first) bits &= ~0u << (base & 31);
+        if (w == w_last && (e_last & 31)) bits &= (1u << (e_last & 31)) - 1u;
+        n_in += __popc(bits);
+    }
+#pragma unroll
+    for (int o = 32; o; o >>= 1) n_in += __shfl_xor(n_in, o);
+    const int n_out = deg - n_in;
+    const float m_in = (float)a.q_out, m_out = (float)a.q_in;       // an intra-community slot's clock is scaled by 1 - p
+
+    // candidate iff r >= t_class; lo_non: the smallest key a slot below its class's threshold can have
+    uint32_t t_in = 0u, t_out = 0u;
+    float non_in = INFINITY, non_out = INFINITY;
+    if ((int)a.cand_target < deg) {
+        const float ln2 = 0.69314718f, target = (float)a.cand_target, fi = (float)n_in, fo = (float)n_out;
+        const float s_in = __builtin_amdgcn_rcpf(m_in), s_out = __builtin_amdgcn_rcpf(m_out);
+        float kp = target / (ln2 * (fi * s_in + fo * s_out));
+#pragma unroll
+        for (int it = 0; it < 3; ++it) {
+            const float ei = __builtin_amdgcn_exp2f(-kp * s_in), eo = __builtin_amdgcn_exp2f(-kp * s_out);
+            const float gv = fi * (1.0f - ei) + fo * (1.0f - eo) - target;
+            const float gd = ln2 * (fi * s_in * ei + fo * s_out * eo);
+            if (gd > 0.0f) kp -= gv / gd;
+        }
+        const float pi = __builtin_amdgcn_exp2f(-kp * s_in) * 4294967296.0f, po = __builtin_amdgcn_exp2f(-kp * s_out) * 4294967296.0f;
+        t_in = pi >= 4294967040.0f ? 0xFFFFFFFFu : (uint32_t)(pi > 0.0f ? pi : 0.0f);
+        t_out = po >= 4294967040.0f ? 0xFFFFFFFFu : (uint32_t)(po > 0.0f ? po : 0.0f);
+        if (t_in > 0u && n_in > 0) non_in = approx_clock(t_in - 1u) * m_in;
+        if (t_out > 0u && n_out > 0) non_out = approx_clock(t_out - 1u) * m_out;
+    }
+
+    const int64_t w_max = (a.n_entries - 1) >> 5;
+    int n = 0;
+    for (int j0 = 0; j0 < deg; j0 += 4 * WAVE) {
+        const int jb = j0 + 4 * lane;
+        const u32x4 w = philox4x32_10((uint32_t)jb >> 2, (uint32_t)v, batch, a.ctr3, a.seed_lo, a.seed_hi);
+        const uint32_t wr[4] = {w.x, w.y, w.z, w.w};
+        const int64_t e = base + min(jb, deg - 1);
+        const int64_t wi = e >> 5;
+        const uint64_t win = (uint64_t)a.edge_intra[wi] | ((uint64_t)a.edge_intra[min(wi + 1, w_max)] << 32);
+        const uint32_t nib = (uint32_t)(win >> (e & 31)) & 0xFu;
+        bool c[4];
+        uint64_t b[4];
+        int before = n, total = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) c[i] = jb + i < deg && wr[i] >= (((nib >> i) & 1u) ? t_in : t_out);
+        if (__ballot(c[0] || c[1] || c[2] || c[3]) == 0) continue;      // (most iterations of a long row)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            b[i] = __ballot(c[i]);
+            before += __popcll(b[i] & lt_mask);
+            total += __popcll(b[i]);
+        }
+        if (n + total > CAND_CAP) return false;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (c[i]) {
+                ckey[before] = __float_as_uint(approx_clock(wr[i]) * (((nib >> i) & 1u) ? m_in : m_out));
+                cslot[before] = (uint32_t)(jb + i) | (((nib >> i) & 1u) << 31);
+            }
+            before += c[i] ? 1 : 0;
+        }
+        n += total;
+    }
+    if (n < k) return false;
+    if (lane < 4) ckey[n + lane] = ~0u;            // pad the keys to a multiple of four with the largest pattern
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+
+    const bool have0 = lane < n, have1 = lane + WAVE < n;
+    const uint32_t w0 = ckey[min(lane, n - 1)], w1 = ckey[min(lane + WAVE, n - 1)];
+    int ra[4] = {0, 0, 0, 0}, rb[4] = {0, 0, 0, 0};
+    for (int t0 = 0; t0 < n; t0 += 4) {
+        const uint4 kt = *reinterpret_cast<const uint4 *>(ckey + t0);
+        const uint32_t ks[4] = {kt.x, kt.y, kt.z, kt.w};
+        rank4_below(w0, ks, ra);
+        if (n > WAVE) rank4_below(w1, ks, rb);
+    }
+    const int r0 = ra[0] + ra[1] + ra[2] + ra[3], r1 = rb[0] + rb[1] + rb[2] + rb[3];
+    const bool s0 = have0 && r0 < k, s1 = have1 && r1 < k;
+    const uint64_t m0 = __ballot(s0), m1 = __ballot(s1);
+    // largest kept key and smallest candidate key left out, per class (x: intra, y: inter)
+    const uint32_t q0 = cslot[min(lane, n - 1)], q1 = cslot[min(lane + WAVE, n - 1)];
+    const bool in0 = q0 >> 31, in1 = q1 >> 31;
+    uint32_t hi_x = max((s0 && in0) ? w0 : 0u, (s1 && in1) ? w1 : 0u), hi_y = max((s0 && !in0) ? w0 : 0u, (s1 && !in1) ? w1 : 0u);
+    uint32_t lo_x = min((have0 && !s0 && in0) ? w0 : 0x7F800000u, (have1 && !s1 && in1) ? w1 : 0x7F800000u);
+    uint32_t lo_y = min((have0 && !s0 && !in0) ? w0 : 0x7F800000u, (have1 && !s1 && !in1) ? w1 : 0x7F800000u);
+#pragma unroll
+    for (int o = 32; o; o >>= 1) {
+        hi_x = max(hi_x, (uint32_t)__shfl_xor((int)hi_x, o));
+        hi_y = max(hi_y, (uint32_t)__shfl_xor((int)hi_y, o));
+        lo_x = min(lo_x, (uint32_t)__shfl_xor((int)lo_x, o));
+        lo_y = min(lo_y, (uint32_t)__shfl_xor((int)lo_y, o));
+    }
+    const float hx = __uint_as_float(hi_x), hy = __uint_as_float(hi_y);
+    const float lx = fminf(__uint_as_float(lo_x), non_in), ly = fminf(__uint_as_float(lo_y), non_out);
+    const bool exact = __popcll(m0) + __popcll(m1) == k && keys_apart(hx, m_in, lx, m_in) && keys_apart(hx, m_in, ly, m_out) &&
+                       keys_apart(hy, m_out, lx, m_in) && keys_apart(hy, m_out, ly, m_out);
+    if (exact) {
+        int32_t *sel_row = sel_row_ptr(a, g, row);
+        if (s0) sel_row[__popcll(m0 & lt_mask)] = a.g_indices[base + (q0 & 0x7FFFFFFFu)];
+        if (s1) sel_row[__popcll(m0) + __popcll(m1 & lt_mask)] = a.g_indices[base + (q1 & 0x7FFFFFFFu)];
+        if (lane == 0) set_row_count(a, g, row, k);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");      // the buffers are reused by this wave's next long row
+    return exact;
+}
+
 template <int MODE>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))) void select_quad_kernel(SelectArgs a)
 {
@@ -780,7 +1023,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
     __shared__ int startq_s[4][QUAD_ROWS];
     __shared__ __align__(16) uint32_t klist_s[4][4 * WAVE];
     __shared__ uint32_t cslot_s[4][CAND_CAP];
+    __shared__ unsigned long long k64_s[MODE == 2 ? 4 : 1][MODE == 2 ? 4 * WAVE : 1];     // weighted: exact 64-bit keys
+    __shared__ __align__(16) uint32_t rowstat_s[MODE == 2 ? 4 : 1][4 * QUAD_ROWS];
     const int wv = (int)threadIdx.x / WAVE;
+    unsigned long long *k64 = k64_s[MODE == 2 ? wv : 0];
+    uint32_t *rowstat = rowstat_s[MODE == 2 ? wv : 0];
     const int g = blockIdx.y;
     const int n_dst = group_n_dst(a.prev_hdr, g, a.n_roots_total, a.batch_size);
     const int row0 = (int)(blockIdx.x * 4 + wv) * QUAD_ROWS;
@@ -822,9 +1069,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
     uint32_t exact_rows = a.exact_select ? 0xFFFFu : 0u;
     if (!a.exact_select)
         for (int p = 0; p < n_pass; ++p)
-            exact_rows |= quad_pass<MODE, false>(a, g, row0, p, 0xFFFFu, rows_s[wv], startq_s[wv], klist_s[wv], lane);
+            exact_rows |= quad_pass<MODE, false>(a, g, row0, p, 0xFFFFu, rows_s[wv], startq_s[wv], klist_s[wv], k64, rowstat, lane);
     if (exact_rows)
-        for (int p = 0; p < n_pass; ++p) quad_pass<MODE, true>(a, g, row0, p, exact_rows, rows_s[wv], startq_s[wv], klist_s[wv], lane);
+        for (int p = 0; p < n_pass; ++p)
+            quad_pass<MODE, true>(a, g, row0, p, exact_rows, rows_s[wv], startq_s[wv], klist_s[wv], k64, rowstat, lane);
 
     // longer rows, one at a time
 #pragma unroll 1
@@ -833,8 +1081,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
         if (deg <= QUAD_MAX_DEG) continue;
         const int32_t v = (int32_t)rl32((uint32_t)mv, i);
         const int64_t base = (int64_t)rl64((uint64_t)mbase, i);
-        if (!a.exact_select && select_big_row_filtered<MODE == 1>(a, g, row0 + i, v, base, deg, lane, klist_s[wv], cslot_s[wv])) continue;
-        select_big_row<MODE>(a, g, row0 + i, v, base, deg, MODE == 1 ? a.comm[v] : 0, lane);
+        if constexpr (MODE == 2) {
+            if (!a.exact_select && select_big_row_weighted_f32(a, g, row0 + i, v, base, deg, lane, klist_s[wv], cslot_s[wv])) continue;
+            if (!a.exact_select &&
+                select_big_row_weighted<true>(a, g, row0 + i, v, base, deg, lane, reinterpret_cast<uint2 *>(klist_s[wv]), k64)) continue;
+        } else {
+            if (!a.exact_select && select_big_row_filtered<MODE == 1>(a, g, row0 + i, v, base, deg, lane, klist_s[wv], cslot_s[wv])) continue;
+        }
+        select_big_row<MODE, true>(a, g, row0 + i, v, base, deg, MODE >= 1 ? a.comm[v] : 0, lane);
     }
 }
 
@@ -850,6 +1104,30 @@ __global__ __launch_bounds__(256) void row_counts_kernel(const int64_t *__restri
     const int32_t v = dst_ids[(int64_t)g * dst_stride + row];
     const int64_t d = g_indptr[v + 1] - g_indptr[v];
     cnt[(int64_t)g * cnt_stride + row] = (int32_t)(d < fanout ? d : fanout);
+}
+
+// Error of approx_clock against the integer clock over every 32-bit word: out[0] = largest |error| (Q24 units) among the
+// words of the upper half (small clocks), out[1] = largest |error| / E over the lower half, out[2] = largest
+// |error| / (CLOCK_ERR_ABS + CLOCK_ERR_REL * E) over all words (the selection relies on this being at most 1).
+__global__ __launch_bounds__(256) void clock_selftest_kernel(float *out)
+{
+    float worst_abs = 0.f, worst_rel = 0.f, worst_ratio = 0.f;
+    const uint32_t stride = gridDim.x * 256u;
+    uint32_t r = blockIdx.x * 256u + threadIdx.x;
+    for (uint64_t n = r; n < 0x100000000ull; n += stride, r += stride) {
+        const uint32_t exact = exp_clock_q24(r);
+        // (the single-precision value times 2^24 and the 30-bit integer are both exact in double precision)
+        const float err = (float)fabs((double)approx_clock(r) * 16777216.0 - (double)exact);
+        const float ef = (float)exact;
+        const bool small_clock = r >= 0x80000000u;
+        worst_abs = fmaxf(worst_abs, small_clock ? err : 0.f);
+        worst_rel = fmaxf(worst_rel, small_clock ? 0.f : err / ef);
+        worst_ratio = fmaxf(worst_ratio, err / (CLOCK_ERR_ABS + CLOCK_ERR_REL * ef));
+    }
+    // (non-negative floats order like their bit patterns)
+    atomicMax(reinterpret_cast<unsigned int *>(out + 0), __float_as_uint(worst_abs));
+    atomicMax(reinterpret_cast<unsigned int *>(out + 1), __float_as_uint(worst_rel));
+    atomicMax(reinterpret_cast<unsigned int *>(out + 2), __float_as_uint(worst_ratio));
 }
 
 struct ScanArgs {
@@ -1442,6 +1720,17 @@ extern "C" cr_status cr_sample_blocks_workspace_bytes(const cr_sample_cfg *cfg, 
     return CR_OK;
 }
 
+extern "C" cr_status cr_selftest_clock_approximation(float *result, void *stream)
+{
+    CR_REQUIRE(result != nullptr, CR_ERR_INVALID_ARG, "result must not be NULL");
+    if (dry_run()) return CR_OK;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipLaunchKernelGGL(fill_u64_kernel, dim3(1), dim3(256), 0, s, reinterpret_cast<unsigned long long *>(result), (int64_t)0, (int64_t)2, 0ull);
+    hipLaunchKernelGGL(clock_selftest_kernel, dim3(4096), dim3(256), 0, s, result);
+    CR_LAUNCH_CHECK();
+    return CR_OK;
+}
+
 extern "C" cr_status cr_sample_blocks_dedup_table(const cr_sample_cfg *cfg, int64_t n_nodes, int32_t batch_size, int32_t *kind)
 {
     SamplePlan p;
@@ -1564,6 +1853,7 @@ extern "C" cr_status cr_sample_blocks(const cr_graph *graph, const cr_sample_cfg
         }
         if (q_in == q_out) hipLaunchKernelGGL(select_quad_kernel<0>, quad_grid, blk, 0, s, sa);
         else if (q_out == 0 && graph->edge_intra) hipLaunchKernelGGL(select_quad_kernel<1>, quad_grid, blk, 0, s, sa);
+        else if (graph->edge_intra) hipLaunchKernelGGL(select_quad_kernel<2>, quad_grid, blk, 0, s, sa);
         else if (q_out == 0) hipLaunchKernelGGL(select_kernel<1>, sel_grid, blk, 0, s, sa);
         else hipLaunchKernelGGL(select_kernel<2>, sel_grid, blk, 0, s, sa);
 

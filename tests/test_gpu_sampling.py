@@ -209,6 +209,20 @@ def test_long_rows_all_paths(torch_mod, edge_classes):
     compare(layers, nb, graph, roots, [15], 1.0, True, 5, 1, 0, 16, "long rows strict")
 
 
+def test_clock_approximation_bound(torch_mod):
+    """The weighted selection ranks single-precision keys and accepts a row only if the integer keys provably give the same
+    result; that rests on a bound on the error of the single-precision clock, measured here over all 2^32 words."""
+    from paper_2504_18082_amd import binding as B
+    res = torch_mod.full((4,), -1.0, dtype=torch_mod.float32, device="cuda")
+    B.cr_selftest_clock_approximation(res)
+    torch_mod.cuda.synchronize()
+    worst_abs, worst_rel, worst_ratio, zero = res.cpu().numpy().tolist()
+    print(f"clock approximation: |error| <= {worst_abs:.3f} units of 2^-24 (small clocks), relative <= {worst_rel:.3e} (large clocks), "
+          f"fraction of the assumed bound {worst_ratio:.3f}", flush=True)
+    assert zero == 0.0
+    assert 0.0 < worst_ratio <= 0.5           # a factor of two in hand
+
+
 @pytest.mark.parametrize("edge_classes", [True, False])
 def test_exact_ranking_path(torch_mod, arxiv_workload, edge_classes):
     """CR_SAMPLE_EXACT_RANKING sends every row through the path that otherwise only redoes the rare rows whose pre-filter
