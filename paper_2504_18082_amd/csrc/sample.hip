@@ -966,7 +966,7 @@ __device__ __forceinline__ bool select_big_row_weighted_f32(const SelectArgs &a,
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             if (c[i]) {
-                ckey[before] = __float_as_uint(approx_clock(wr[i]) * (((nib >> i) & 1u) ? m_in : m_out));
+                ckey[before] = wr[i];               // (the key is computed once per candidate, after the loop)
                 cslot[before] = (uint32_t)(jb + i) | (((nib >> i) & 1u) << 31);
             }
             before += c[i] ? 1 : 0;
@@ -974,11 +974,21 @@ __device__ __forceinline__ bool select_big_row_weighted_f32(const SelectArgs &a,
         n += total;
     }
     if (n < k) return false;
-    if (lane < 4) ckey[n + lane] = ~0u;            // pad the keys to a multiple of four with the largest pattern
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
 
+    // candidate t sits at index t in slot order; a lane owns candidates lane and lane + 64 and turns their random words
+    // into keys
     const bool have0 = lane < n, have1 = lane + WAVE < n;
-    const uint32_t w0 = ckey[min(lane, n - 1)], w1 = ckey[min(lane + WAVE, n - 1)];
+    const uint32_t q0 = cslot[min(lane, n - 1)], q1 = cslot[min(lane + WAVE, n - 1)];
+    const bool in0 = q0 >> 31, in1 = q1 >> 31;
+    const uint32_t w0 = __float_as_uint(approx_clock(ckey[min(lane, n - 1)]) * (in0 ? m_in : m_out));
+    uint32_t w1 = 0x7F800000u;
+    if (n > WAVE) w1 = __float_as_uint(approx_clock(ckey[min(lane + WAVE, n - 1)]) * (in1 ? m_in : m_out));
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");      // every lane has read its words
+    if (have0) ckey[lane] = w0;
+    if (have1) ckey[lane + WAVE] = w1;
+    if (lane < 4) ckey[n + lane] = ~0u;            // pad the keys to a multiple of four with the largest pattern
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     int ra[4] = {0, 0, 0, 0}, rb[4] = {0, 0, 0, 0};
     for (int t0 = 0; t0 < n; t0 += 4) {
         const uint4 kt = *reinterpret_cast<const uint4 *>(ckey + t0);
@@ -990,8 +1000,6 @@ __device__ __forceinline__ bool select_big_row_weighted_f32(const SelectArgs &a,
     const bool s0 = have0 && r0 < k, s1 = have1 && r1 < k;
     const uint64_t m0 = __ballot(s0), m1 = __ballot(s1);
     // largest kept key and smallest candidate key left out, per class (x: intra, y: inter)
-    const uint32_t q0 = cslot[min(lane, n - 1)], q1 = cslot[min(lane + WAVE, n - 1)];
-    const bool in0 = q0 >> 31, in1 = q1 >> 31;
     uint32_t hi_x = max((s0 && in0) ? w0 : 0u, (s1 && in1) ? w1 : 0u), hi_y = max((s0 && !in0) ? w0 : 0u, (s1 && !in1) ? w1 : 0u);
     uint32_t lo_x = min((have0 && !s0 && in0) ? w0 : 0x7F800000u, (have1 && !s1 && in1) ? w1 : 0x7F800000u);
     uint32_t lo_y = min((have0 && !s0 && !in0) ? w0 : 0x7F800000u, (have1 && !s1 && !in1) ? w1 : 0x7F800000u);
