@@ -90,7 +90,7 @@ def test_bench_configuration(large):
 
     # ---- one group of 32 batches, as the benchmark samples it (RAND roots are current)
     first = GROUP                                      # second group of the epoch
-    for p, full_batches in ((0.5, (0, 31)), (1.0, (17,))):
+    for p, full_batches in ((0.5, (0, 31)), (1.0, (17,)), (0.9, (5,))):
         print(f"{cfg.name}: sampling a group of {GROUP} at p={p}", flush=True)
         tr.sample_group(first, GROUP, p, epoch)
         torch.cuda.synchronize()
