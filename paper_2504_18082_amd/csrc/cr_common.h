@@ -82,6 +82,9 @@ __device__ __forceinline__ void mul_hi_lo(uint32_t m, uint32_t c, uint32_t &hi, 
     lo = (uint32_t)p;
 }
 
+// a ^ b ^ c in one instruction (gfx950's three-input bit operation; truth table 0x96 is the parity of the three bits)
+__device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c) { return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96); }
+
 __device__ __forceinline__ u32x4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
                                                uint32_t k0, uint32_t k1)
 {
@@ -90,9 +93,10 @@ __device__ __forceinline__ u32x4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_
         uint32_t hi0, lo0, hi1, lo1;
         mul_hi_lo(0xD2511F53u, c0, hi0, lo0);
         mul_hi_lo(0xCD9E8D57u, c2, hi1, lo1);
-        c0 = hi1 ^ c1 ^ k0;
+        // (first round: counter and key words are often the same for the whole wave, and their xor is then scalar work)
+        c0 = i == 0 ? hi1 ^ (c1 ^ k0) : xor3(hi1, c1, k0);
         c1 = lo1;
-        c2 = hi0 ^ c3 ^ k1;
+        c2 = i == 0 ? hi0 ^ (c3 ^ k1) : xor3(hi0, c3, k1);
         c3 = lo0;
         k0 += 0x9E3779B9u;
         k1 += 0xBB67AE85u;

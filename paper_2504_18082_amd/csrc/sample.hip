@@ -3,6 +3,7 @@
 // CSR blocks with local column ids and their transposes.  Integer arithmetic only; a whole group of
 // mini-batches is sampled by one set of launches (blockIdx.y = batch within the group).
 #include "cr_common.h"
+#include <type_traits>
 
 namespace cr {
 
@@ -94,6 +95,10 @@ __device__ __forceinline__ uint64_t push64(uint64_t v, int dst_lane)
 __device__ __forceinline__ bool edge_is_intra(const SelectArgs &a, int64_t e) { return (a.edge_intra[e >> 5] >> (e & 31)) & 1u; }
 
 __device__ __forceinline__ uint32_t pull32(uint32_t v, int src_lane) { return (uint32_t)__builtin_amdgcn_ds_bpermute(src_lane << 2, (int)v); }
+__device__ __forceinline__ int lanes_below(uint64_t mask, int acc)      // acc + number of set bits below this lane
+{
+    return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, (uint32_t)acc));
+}
 
 // ordering key of slot j of node v given its random word: narrow mode (p = 0.5) uses the word itself
 // MODE: 0 uniform (p = 0.5), 1 p = 1 (classes only, no clock), 2 weighted (0.5 < p < 1)
@@ -314,32 +319,40 @@ __device__ __forceinline__ bool select_big_row_filtered(const SelectArgs &a, int
     const int64_t w_max = (a.n_entries - 1) >> 5;
     // (float arithmetic: the threshold only steers how many candidates there are, any value gives the same result)
     const float thr_f = (float)a.cand_target * 4294967296.0f / (float)pool;
-    const bool keep_all = thr_f >= 4294967040.0f;                  // every slot of the pool is a candidate
+    const bool keep_all = thr_f >= 4294967040.0f;                  // every slot of the pool is to be a candidate
     const uint32_t thr = keep_all ? 0xFFFFFFFFu : (uint32_t)thr_f;
     int n = 0;
-    for (int j0 = 0; j0 < deg; j0 += 4 * WAVE) {
+    // 256 slots from j0 on; a slot is a candidate iff its word is below thr and it belongs to the pool (of the right class,
+    // and, in the row's last stretch, not beyond its end).  false: more candidates than the list holds.
+    auto stretch = [&](int j0, auto is_last) -> bool {
+        constexpr bool LAST = decltype(is_last)::value;
         const int jb = j0 + 4 * lane;
         const u32x4 w = philox4x32_10((uint32_t)jb >> 2, (uint32_t)v, batch, a.ctr3, a.seed_lo, a.seed_hi);
         const uint32_t wr[4] = {w.x, w.y, w.z, w.w};
-        uint32_t nib = 0xFu;          // class bits of the lane's four slots
+        uint32_t nib = 0xFu;          // which of the lane's four slots belong to the pool
         if (INTRA_ONLY) {
             const int64_t e = base + min(jb, deg - 1);
             const int64_t wi = e >> 5;
             const uint64_t win = (uint64_t)a.edge_intra[wi] | ((uint64_t)a.edge_intra[min(wi + 1, w_max)] << 32);
             nib = (uint32_t)(win >> (e & 31)) & 0xFu;
         }
+        if (LAST) {
+            const int left = deg - jb;
+            nib &= left >= 4 ? 0xFu : (left > 0 ? (1u << left) - 1u : 0u);
+        }
         bool c[4];
         uint64_t b[4];
-        int before = n, total = 0;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) c[i] = jb + i < deg && (keep_all || wr[i] < thr) && ((nib >> i) & 1u);
-        if (__ballot(c[0] || c[1] || c[2] || c[3]) == 0) continue;      // (most iterations of a long row)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
+            const uint32_t t = (INTRA_ONLY || LAST) ? (((nib >> i) & 1u) ? thr : 0u) : thr;
+            c[i] = wr[i] < t;
             b[i] = __ballot(c[i]);
-            before += __popcll(b[i] & lt_mask);
-            total += __popcll(b[i]);
         }
+        if ((b[0] | b[1] | b[2] | b[3]) == 0) return true;             // (most stretches of a very long row)
+        int before = n;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) before = lanes_below(b[i], before);
+        const int total = __popcll(b[0]) + __popcll(b[1]) + __popcll(b[2]) + __popcll(b[3]);
         if (n + total > CAND_CAP) return false;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -347,7 +360,14 @@ __device__ __forceinline__ bool select_big_row_filtered(const SelectArgs &a, int
             before += c[i] ? 1 : 0;
         }
         n += total;
-    }
+        return true;
+    };
+    int j0 = 0;
+    for (; j0 + 4 * WAVE <= deg; j0 += 4 * WAVE)
+        if (!stretch(j0, std::false_type{})) return false;
+    if (j0 < deg && !stretch(j0, std::true_type{})) return false;
+    // (a word of all ones is never below the threshold: with every slot wanted, leave such a row to the general path)
+    if (keep_all && n != pool) return false;
     if (n < k) return false;
     if (lane < 4) ckey[n + lane] = ~0u;            // pad the words to a multiple of four with the largest one
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -680,15 +700,11 @@ struct alignas(16) QuadRow {
     int32_t *out;                        // where the row's chosen ids go
 };
 
-__device__ __forceinline__ int lanes_below(uint64_t mask, int acc)      // acc + number of set bits below this lane
-{
-    return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, (uint32_t)acc));
-}
-
 // One pass; returns the rows (bit r = row r of the wave) that have to be redone exactly.  rowmask: rows to process.
 template <int MODE, bool EXACT>
 __device__ __forceinline__ uint32_t quad_pass(const SelectArgs &a, int g, int row0, int p, uint32_t rowmask, const QuadRow *rows,
-                                              const int *startq, uint32_t *klist, unsigned long long *k64, uint32_t *rowstat, int lane)
+                                              const int *startq, uint32_t *klist, uint32_t *clist, uint32_t *rowinfo,
+                                              unsigned long long *k64, uint32_t *rowstat, int lane)
 {
     const int f = a.fanout;
     const uint32_t batch = a.first_batch + (uint32_t)g;
@@ -711,7 +727,8 @@ __device__ __forceinline__ uint32_t quad_pass(const SelectArgs &a, int g, int ro
 
     // number of set flags of this row in the lanes before this one, and in the whole row (flags of lanes outside any
     // row are zero)
-    auto seg = [&](uint32_t m4, int &excl, int &total) {
+    // (in_pass: the same count over all the lanes before this one, whatever their row)
+    auto seg = [&](uint32_t m4, int &excl, int &total, int &in_pass) {
         int e = 0;
 #pragma unroll
         for (int i = 0; i < 4; ++i) e = lanes_below(__ballot((m4 >> i) & 1u), e);
@@ -719,6 +736,7 @@ __device__ __forceinline__ uint32_t quad_pass(const SelectArgs &a, int g, int ro
         const int upto_last = (int)pull32((uint32_t)(e + __popc(m4)), last);
         excl = e - before_row;
         total = upto_last - before_row;
+        in_pass = e;
     };
 
     uint32_t pool = vmask, take = 0u;
@@ -731,8 +749,8 @@ __device__ __forceinline__ uint32_t quad_pass(const SelectArgs &a, int g, int ro
             const uint64_t win = (uint64_t)a.edge_intra[wi] | ((uint64_t)a.edge_intra[min(wi + 1, w_max)] << 32);
             nib = (uint32_t)(win >> (e & 31)) & 0xFu;
         }
-        int unused;
-        seg(nib & vmask, unused, n_in);
+        int unused, unused2;
+        seg(nib & vmask, unused, n_in, unused2);
     }
     if (MODE == 1) {
         const uint32_t in4 = nib & vmask;
@@ -791,9 +809,10 @@ __device__ __forceinline__ uint32_t quad_pass(const SelectArgs &a, int g, int ro
             cm &= below;
         }
     }
-    int cpos, n_c;
-    seg(cm, cpos, n_c);
+    int cpos, n_c, cglob;
+    seg(cm, cpos, n_c, cglob);
     int rk[4] = {0, 0, 0, 0};
+    uint32_t below_m = 0u;                   // candidates among this lane's slots with fewer than m candidates in front
     const int nc_mine = ranked ? n_c : 0;
     if constexpr (MODE == 2 && EXACT) {
         // the exact integer keys, 64 bits each: every slot of the row is a candidate, (key, slot) pairs compared in full
@@ -816,40 +835,79 @@ __device__ __forceinline__ uint32_t quad_pass(const SelectArgs &a, int g, int ro
                     rk[i] += (kt < ek[i] || (kt == ek[i] && t < cpos + (int)__popc(cm & ((1u << i) - 1u)))) ? 1 : 0;
             }
         }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) below_m |= rk[i] < m ? 1u << i : 0u;
     } else {
         // the row's list: candidates' words in slot order, padded with the largest word to a multiple of four
         uint32_t *kl = klist + 4 * first;
         if (active) *reinterpret_cast<uint4 *>(klist + 4 * lane) = make_uint4(~0u, ~0u, ~0u, ~0u);
+        // With at most 64 candidates in the whole pass a lane ranks ONE candidate (the lane-th of the pass, in slot order)
+        // against its row's list, two instructions per list entry, instead of its own four slots against it, eight per
+        // entry: in rows much longer than their list most slots are no candidates.  clist[c]: where candidate c sits in the
+        // lists (bits 0..7) and its row (bits 8..11); rowinfo[r]: start of the row's list, its length << 8, m << 20.
+        const int n_pass_cand = (int)rl32((uint32_t)(cglob + (int)__popc(cm)), WAVE - 1);
+        const bool by_candidate = !EXACT && n_pass_cand <= WAVE;
         if (ranked) {
-            int k = cpos;
+            int k = cpos, c = cglob;
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                if ((cm >> i) & 1u) kl[k++] = kw[i];
+                if ((cm >> i) & 1u) {
+                    kl[k] = kw[i];
+                    if (by_candidate) clist[c++] = (uint32_t)(4 * first + k) | ((uint32_t)r << 8);
+                    ++k;
+                }
+            if (by_candidate && qi == 0) rowinfo[r] = (uint32_t)(4 * first) | ((uint32_t)n_c << 8) | ((uint32_t)m << 20);
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        for (int t0 = 0; __ballot(t0 < nc_mine) != 0; t0 += 4) {
-            if (t0 < nc_mine) {
-                const uint4 kt = *reinterpret_cast<const uint4 *>(kl + t0);
-                const uint32_t ks[4] = {kt.x, kt.y, kt.z, kt.w};
+        if (by_candidate) {
+            const bool have = lane < n_pass_cand;
+            const uint32_t ce = clist[lane];                       // (stale beyond the pass's candidates: masked below)
+            const uint32_t ri = rowinfo[(ce >> 8) & (QUAD_ROWS - 1)];
+            const uint32_t mine = klist[ce & 0xFFu];
+            const uint32_t *rl = klist + (ri & 0xFCu);
+            const int nc = have ? (int)((ri >> 8) & 0xFFFu) : 0;
+            int ra[4] = {0, 0, 0, 0};
+            for (int t0 = 0; __ballot(t0 < nc) != 0; t0 += 4) {
+                if (t0 < nc) {
+                    const uint4 kt = *reinterpret_cast<const uint4 *>(rl + t0);
+                    const uint32_t ks[4] = {kt.x, kt.y, kt.z, kt.w};
+                    rank4_below(mine, ks, ra);
+                }
+            }
+            const uint64_t low = __ballot(have && ra[0] + ra[1] + ra[2] + ra[3] < (int)(ri >> 20));
+            // this lane's candidates are numbers cglob, cglob + 1, .. of the pass: hand their bits back to its slots
+            uint32_t b = (uint32_t)(low >> (cglob & (WAVE - 1)));
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    if (!EXACT) {
-                        rank4(ks[q], kw, rk);
-                    } else {
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t is_c = (cm >> i) & 1u;
+                below_m |= (b & is_c) << i;
+                b >>= is_c;
+            }
+        } else {
+            for (int t0 = 0; __ballot(t0 < nc_mine) != 0; t0 += 4) {
+                if (t0 < nc_mine) {
+                    const uint4 kt = *reinterpret_cast<const uint4 *>(kl + t0);
+                    const uint32_t ks[4] = {kt.x, kt.y, kt.z, kt.w};
 #pragma unroll
-                        for (int i = 0; i < 4; ++i)
-                            rk[i] += (ks[q] < kw[i] || (ks[q] == kw[i] && t0 + q < cpos + (int)__popc(cm & ((1u << i) - 1u)))) ? 1 : 0;
+                    for (int q = 0; q < 4; ++q) {
+                        if (!EXACT) {
+                            rank4(ks[q], kw, rk);
+                        } else {
+#pragma unroll
+                            for (int i = 0; i < 4; ++i)
+                                rk[i] += (ks[q] < kw[i] || (ks[q] == kw[i] && t0 + q < cpos + (int)__popc(cm & ((1u << i) - 1u)))) ? 1 : 0;
+                        }
                     }
                 }
             }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) below_m |= rk[i] < m ? 1u << i : 0u;
         }
     }
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");      // the list is reused by the next pass
-    uint32_t emit = take;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) emit |= (((cm >> i) & 1u) && rk[i] < m) ? 1u << i : 0u;
-    int epos, total;
-    seg(emit, epos, total);
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");      // the lists are reused by the next pass
+    const uint32_t emit = take | (cm & below_m);
+    int epos, total, unused3;
+    seg(emit, epos, total, unused3);
     bool ok = total == expect;            // (always true in the exact pass)
     if constexpr (MODE == 2 && !EXACT) {
         // largest kept key and smallest key left out, per row and class (LDS atomics on the bit patterns):
@@ -861,7 +919,7 @@ __device__ __forceinline__ uint32_t quad_pass(const SelectArgs &a, int g, int ro
             for (int i = 0; i < 4; ++i) {
                 if ((cm >> i) & 1u) {
                     const int cls = ((nib >> i) & 1u) ? 0 : 1;
-                    if (rk[i] < m) atomicMax(&rowstat[4 * r + cls], kw[i]);
+                    if ((below_m >> i) & 1u) atomicMax(&rowstat[4 * r + cls], kw[i]);
                     else atomicMin(&rowstat[4 * r + 2 + cls], kw[i]);
                 }
             }
@@ -1030,7 +1088,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
     __shared__ QuadRow rows_s[4][QUAD_ROWS];
     __shared__ int startq_s[4][QUAD_ROWS];
     __shared__ __align__(16) uint32_t klist_s[4][4 * WAVE];
-    __shared__ uint32_t cslot_s[4][CAND_CAP];
+    __shared__ uint32_t cslot_s[4][CAND_CAP];              // (long rows: candidates' slots; passes: the pass's candidates)
+    __shared__ uint32_t rowinfo_s[4][QUAD_ROWS];
     __shared__ unsigned long long k64_s[MODE == 2 ? 4 : 1][MODE == 2 ? 4 * WAVE : 1];     // weighted: exact 64-bit keys
     __shared__ __align__(16) uint32_t rowstat_s[MODE == 2 ? 4 : 1][4 * QUAD_ROWS];
     const int wv = (int)threadIdx.x / WAVE;
@@ -1077,10 +1136,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
     uint32_t exact_rows = a.exact_select ? 0xFFFFu : 0u;
     if (!a.exact_select)
         for (int p = 0; p < n_pass; ++p)
-            exact_rows |= quad_pass<MODE, false>(a, g, row0, p, 0xFFFFu, rows_s[wv], startq_s[wv], klist_s[wv], k64, rowstat, lane);
+            exact_rows |= quad_pass<MODE, false>(a, g, row0, p, 0xFFFFu, rows_s[wv], startq_s[wv], klist_s[wv], cslot_s[wv], rowinfo_s[wv], k64, rowstat, lane);
     if (exact_rows)
         for (int p = 0; p < n_pass; ++p)
-            quad_pass<MODE, true>(a, g, row0, p, exact_rows, rows_s[wv], startq_s[wv], klist_s[wv], k64, rowstat, lane);
+            quad_pass<MODE, true>(a, g, row0, p, exact_rows, rows_s[wv], startq_s[wv], klist_s[wv], cslot_s[wv], rowinfo_s[wv], k64, rowstat, lane);
 
     // longer rows, one at a time
 #pragma unroll 1
