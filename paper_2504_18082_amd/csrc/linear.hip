@@ -410,8 +410,9 @@ __global__ __launch_bounds__(256) void gemm_nt_small_kernel(NtArgs a, XentArgs x
 }
 
 // ------------------------------------------------------------------------------------------------
-// The same product for the input layer of the large workloads: tens of thousands of rows, N = 256, any K (GraphSAGE:
-// self | aggregate, 2 x 128 features after padding; one-operand layers: all of K from one array).  The tiled kernel
+// The same product for the input layer of the large workloads: tens of thousands of rows, N = 256, any K (K <= 256 takes
+// the streaming kernel further down; this one serves wider inputs, e.g. 602 features.  GraphSAGE: self | aggregate;
+// one-operand layers: all of K from one array).  The tiled kernel
 // above reads every activation row four times (once per 64-column tile) and spends most of its time moving operands;
 // here one workgroup per compute unit takes 256 rows and ALL columns, so activations pass through a compute unit once:
 //   - K is taken in chunks of 128 columns.  A chunk is 256 rows x 256 bytes of activations and 256 x 256 bytes of
@@ -571,6 +572,240 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// The same product again for K <= 256 (the input layer of the papers-like workload: 2 x 128 features): the weights
+// of a wave's 64 output columns fit its registers (64 x 256 bf16 = 128 registers per lane), so they are fetched once
+// per workgroup and only activations pass through LDS.  One persistent workgroup per compute unit walks over tiles
+// of 64 rows (tile t, t + gridDim.x, ..):
+//   - a tile's activations (64 rows x K) travel global -> registers -> LDS; the loads of tiles t+1 and t+2 are in
+//     flight while tile t is multiplied (two register sets, two LDS buffers, one barrier per tile), so a compute unit
+//     keeps two tiles (64 KB) on the way and the chip about 16 MB: enough to cover the memory latency at full rate;
+//   - a wave multiplies all 64 rows by its own 64 columns: per 16-wide K step two fragment reads feed four MFMAs
+//     (the activation fragments are the only LDS reads of the K loop);
+//   - bias, ReLU and the bf16 conversion happen in the wave's own LDS patch, from where 128-byte row pieces leave;
+//     the stores of tile t overlap the loads of the tiles behind it.
+// With K = N = 256 the product moves 1 KB per row against 131 K multiply-adds: even at the full memory rate the matrix
+// cores can be busy for about 30 % of the time at most.
+// ------------------------------------------------------------------------------------------------
+constexpr int STREAM_ROWS = 64;
+constexpr int STREAM_KMAX = 256;
+constexpr int STREAM_LROW = STREAM_KMAX + 8;    // staged activation row: 256 bf16 + 8 of padding (528 bytes)
+constexpr int STREAM_OROW = 64 + 8;             // staged output row of one wave
+constexpr size_t STREAM_LDS_BYTES = ((size_t)2 * STREAM_ROWS * STREAM_LROW + (size_t)4 * STREAM_ROWS * STREAM_OROW) * sizeof(uint16_t) +
+                                    WIDE_N * sizeof(float);
+
+// KS: 16-wide K steps held in registers (8: K <= 128, 16: K <= 256; columns from K on count as zeros).  FULL: at least
+// 64 rows, so that every tile is a whole one and nothing in the tile loop is conditional: every wait on the counter of
+// outstanding memory operations then leaves exactly the newer loads and stores in flight.
+// UNIFORM: each wave's sixteen pieces of a row lie in one operand array (K0 = K or a multiple of 128): a load address is
+// then a base that is the same for the whole wave (array, tile, row group) plus one 32-bit offset per thread that never
+// changes, so no address registers are computed per tile (the compiler puts such temporaries into the registers the
+// previous tile's loads went to, and then waits for loads that have long been consumed).
+template <int KS, bool FULL, bool UNIFORM>
+__device__ __forceinline__ void nt_stream_body(const NtArgs &a, const int M, uint16_t *stream_lds, const bf16x8 (&wf)[2][KS])
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int half = lane >> 5, lr = lane & 31;
+    uint16_t *As0 = stream_lds, *As1 = stream_lds + STREAM_ROWS * STREAM_LROW;
+    uint16_t *ob = stream_lds + 2 * STREAM_ROWS * STREAM_LROW + wave * STREAM_ROWS * STREAM_OROW;
+    float *bias_s = reinterpret_cast<float *>(stream_lds + 2 * STREAM_ROWS * STREAM_LROW + 4 * STREAM_ROWS * STREAM_OROW);
+    const int ntiles = (M + STREAM_ROWS - 1) / STREAM_ROWS;
+    const int K = a.K, K0 = a.K0;
+
+    // staging: a thread moves the same 16-byte piece (columns 8 kp ..) of eight rows (srow, srow + 8, ..) of every tile;
+    // a wave covers 16 pieces (256 bytes) of four rows per load.
+    // The last tile is moved back so that it ends at the last row (it recomputes rows of its neighbour: same values,
+    // written twice); with fewer than 64 rows the one tile reads rows past the last one: they exist (the arrays hold
+    // max_rows >= 16384 rows), rows are independent, and results past the last row are not stored.  A fetch for a tile
+    // past the last one, or of a piece past K, still issues its eight loads (all of the first operand's first bytes).
+    const int uwave = __builtin_amdgcn_readfirstlane(wave);
+    const int kp = (lane & 15) + 16 * (uwave & 1), srow = (lane >> 4) + 4 * (uwave >> 1);
+    const bool mine = kp * 8 < K;
+    const uint16_t *col_src = !mine ? a.A0 : (kp * 8 < K0 ? a.A0 + kp * 8 : a.A1 + (kp * 8 - K0));
+    // (UNIFORM: the wave's array, the second one addressed from K0 columns in front of it; the host has checked that
+    // the arrays are shorter than 2^31 bytes)
+    const bool second = 128 * (uwave & 1) >= K0;
+    const uint64_t base_v = reinterpret_cast<uint64_t>(second ? a.A1 - K0 : a.A0);
+    const uint16_t *wave_src = reinterpret_cast<const uint16_t *>(
+        ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(base_v >> 32)) << 32) | (uint32_t)__builtin_amdgcn_readfirstlane((int)base_v));
+    const uint32_t ld_bytes = (uint32_t)__builtin_amdgcn_readfirstlane((int)(a.lda * 2));
+    const uint32_t records = (uint32_t)__builtin_amdgcn_readfirstlane((int)((uint32_t)a.max_rows * ld_bytes + (second ? 2u * (uint32_t)K0 : 0u)));
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(wave_src), 0, (int)records, 0x00020000);
+    // (a thread without a piece of its own -- columns from K on -- reads its array's first bytes: with the second array
+    // that is K0 columns past the shifted base, not the base itself, which lies in front of the array)
+    const uint32_t lane_off = mine ? (uint32_t)srow * ld_bytes + 16u * (uint32_t)kp : (second ? 2u * (uint32_t)K0 : 0u);
+    auto tile_m0 = [&](int t) { return max(0, min(t * STREAM_ROWS, M - STREAM_ROWS)); };
+    auto fetch = [&](u32x4v (&r)[8], int t) {
+        if constexpr (UNIFORM) {
+            // buffer loads: descriptor and row offset in scalar registers, the thread's offset in one register that
+            // never changes (a tile past the last one: the first tile's rows again, they exist)
+            const uint32_t row0 = t < ntiles ? (uint32_t)tile_m0(t) : 0u;
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                r[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)lane_off, (int)((row0 + 8u * i) * ld_bytes), 0);
+        } else {
+            const bool real = mine && t < ntiles;
+            const int64_t ld = real ? a.lda : 0;
+            const uint16_t *src = real ? col_src + (int64_t)(tile_m0(t) + srow) * ld : a.A0;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) r[i] = *reinterpret_cast<const u32x4v *>(src + (int64_t)(8 * i) * ld);
+        }
+    };
+    auto stage = [&](uint16_t *As, const u32x4v (&r)[8]) {
+        if (!mine) return;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4v *>(&As[(8 * i + srow) * STREAM_LROW + kp * 8]) = r[i];
+    };
+    const float floor_v = a.relu ? 0.f : -INFINITY;
+    // Two sets of accumulators: while the MFMAs of a tile fill one, the other -- the tile before -- is converted and
+    // written to the wave's LDS patch, a sixteenth (K <= 128: an eighth) per K step, in the shadow of that step's MFMAs;
+    // this wave is alone on its SIMD, so nothing else would fill the vector pipe while the matrix pipe runs, nor the
+    // matrix pipe during a separate epilogue.
+    // piece 0..15 of a tile's results: a lane holds, for row lr of each 32-row block rb, the columns
+    // 32 cb + 8 grp + 4 half .. + 4 of the wave's 64
+    auto convert_piece = [&](const f32x16 (&acc)[2][2], int piece) {
+        const int cb = piece >> 3, grp = (piece >> 1) & 3, rb = piece & 1;
+        const int n = 32 * cb + 8 * grp + 4 * half;
+        const float v0 = fmaxf(acc[rb][cb][grp * 4 + 0], floor_v), v1 = fmaxf(acc[rb][cb][grp * 4 + 1], floor_v);
+        const float v2 = fmaxf(acc[rb][cb][grp * 4 + 2], floor_v), v3 = fmaxf(acc[rb][cb][grp * 4 + 3], floor_v);
+        *reinterpret_cast<uint2 *>(&ob[(rb * 32 + lr) * STREAM_OROW + n]) = make_uint2(pack_bf16x2(v0, v1), pack_bf16x2(v2, v3));
+    };
+    // the patch leaves as 128-byte row pieces
+    auto flush = [&](int t) {
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        const int m0 = tile_m0(t);
+#pragma unroll
+        for (int it = 0; it < 8; ++it) {
+            const int c = it * 64 + lane, row = c >> 3, c8 = (c & 7) * 8;
+            const u32x4v x = *reinterpret_cast<const u32x4v *>(&ob[row * STREAM_OROW + c8]);
+            if (FULL || m0 + row < M) *reinterpret_cast<u32x4v *>(a.Cb + (int64_t)(m0 + row) * a.ldcb + 64 * wave + c8) = x;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");      // the patch is rewritten for the next tile
+    };
+    auto multiply = [&](const uint16_t *As, f32x16 (&acc)[2][2], const f32x16 (&prev)[2][2], auto with_prev) {
+        constexpr bool PREV = decltype(with_prev)::value;
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+            for (int grp = 0; grp < 4; ++grp) {
+                const float4 bq = *reinterpret_cast<const float4 *>(&bias_s[64 * wave + 32 * cb + 8 * grp + 4 * half]);
+#pragma unroll
+                for (int rb = 0; rb < 2; ++rb) {
+                    acc[rb][cb][grp * 4 + 0] = bq.x; acc[rb][cb][grp * 4 + 1] = bq.y; acc[rb][cb][grp * 4 + 2] = bq.z; acc[rb][cb][grp * 4 + 3] = bq.w;
+                }
+            }
+        const uint16_t *ar0 = As + lr * STREAM_LROW + 8 * half, *ar1 = ar0 + 32 * STREAM_LROW;
+        // (fragments are requested two K steps ahead: four MFMAs do not cover an LDS round trip)
+        bf16x8 f0[3], f1[3];
+        f0[0] = lds_read8(ar0); f1[0] = lds_read8(ar1);
+        f0[1] = lds_read8(ar0 + 16); f1[1] = lds_read8(ar1 + 16);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            if (ks + 2 < KS) {
+                f0[(ks + 2) % 3] = lds_read8(ar0 + (ks + 2) * 16);
+                f1[(ks + 2) % 3] = lds_read8(ar1 + (ks + 2) * 16);
+            }
+            const bf16x8 a0 = f0[ks % 3], a1 = f1[ks % 3];
+            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[0][ks], a0, acc[0][0], 0, 0, 0);
+            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[0][ks], a1, acc[1][0], 0, 0, 0);
+            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[1][ks], a0, acc[0][1], 0, 0, 0);
+            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[1][ks], a1, acc[1][1], 0, 0, 0);
+            if constexpr (PREV) {
+#pragma unroll
+                for (int q = 0; q < 16 / KS; ++q) convert_piece(prev, ks * (16 / KS) + q);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    auto convert_all = [&](const f32x16 (&acc)[2][2]) {
+#pragma unroll
+        for (int piece = 0; piece < 16; ++piece) convert_piece(acc, piece);
+    };
+
+    const int step = (int)gridDim.x;
+    int t = (int)blockIdx.x;
+    u32x4v ra[8], rb[8];
+    fetch(ra, t);
+    fetch(rb, t + step);
+    if (tid < WIDE_N / 4)
+        *reinterpret_cast<float4 *>(&bias_s[tid * 4]) = a.bias ? *reinterpret_cast<const float4 *>(a.bias + tid * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+    if (!mine) {                 // columns from K on stay zero in both buffers
+        const u32x4v zero = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            *reinterpret_cast<u32x4v *>(&As0[(8 * i + srow) * STREAM_LROW + kp * 8]) = zero;
+            *reinterpret_cast<u32x4v *>(&As1[(8 * i + srow) * STREAM_LROW + kp * 8]) = zero;
+        }
+    }
+    stage(As0, ra);
+    __syncthreads();
+    f32x16 acc_a[2][2], acc_b[2][2];
+    // tile t sits in the first buffer, tile t + step is on its way into rb
+    fetch(ra, t + 2 * step);
+    multiply(As0, acc_a, acc_b, std::false_type{});
+    for (;;) {
+        // acc_a holds tile t; tile t + step (if there is one) is on its way into rb
+        if (t + step >= ntiles) {
+            convert_all(acc_a);
+            flush(t);
+            break;
+        }
+        stage(As1, rb);
+        __syncthreads();
+        fetch(rb, t + 3 * step);
+        multiply(As1, acc_b, acc_a, std::true_type{});
+        flush(t);
+        t += step;
+        // acc_b holds tile t; tile t + step is on its way into ra
+        if (t + step >= ntiles) {
+            convert_all(acc_b);
+            flush(t);
+            break;
+        }
+        stage(As0, ra);
+        __syncthreads();
+        fetch(ra, t + 3 * step);
+        multiply(As0, acc_a, acc_b, std::true_type{});
+        flush(t);
+        t += step;
+    }
+}
+
+// The wave's weights are requested before the row count is read (they do not depend on it): the two round trips to
+// memory overlap.  Columns 64 wave + 32 cb + lr, eight k from 16 ks + 8 half on (K is a multiple of 8).
+template <int KS>
+__device__ __forceinline__ void nt_stream_run(const NtArgs &a, uint16_t *stream_lds)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int half = lane >> 5, lr = lane & 31;
+    const int K = a.K;
+    bf16x8 wf[2][KS];
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const int k = ks * 16 + 8 * half;
+            const uint16_t *src = a.B + (int64_t)(64 * wave + 32 * cb + lr) * K + (k < K ? k : 0);
+            const u32x4v x = *reinterpret_cast<const u32x4v *>(src);
+            const u32x4v zero = {0u, 0u, 0u, 0u};
+            wf[cb][ks] = __builtin_bit_cast(bf16x8, k < K ? x : zero);
+        }
+    asm volatile("" ::: "memory");      // (keeps the loads above from being moved below the branch on the row count)
+    const int M = min(a.hdr[CR_HDR_N_DST], a.max_rows);
+    if ((int)blockIdx.x * STREAM_ROWS >= M) return;
+    const bool uniform = a.K0 == a.K || a.K0 % 128 == 0;
+    if (M < STREAM_ROWS) nt_stream_body<KS, false, false>(a, M, stream_lds, wf);
+    else if (uniform) nt_stream_body<KS, true, true>(a, M, stream_lds, wf);
+    else nt_stream_body<KS, true, false>(a, M, stream_lds, wf);
+}
+
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void gemm_nt_stream_kernel(NtArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) uint16_t stream_lds[];
+    if (a.K <= 128) nt_stream_run<8>(a, stream_lds);
+    else nt_stream_run<16>(a, stream_lds);
+}
+
 constexpr int NT_WIDE_MIN_ROWS = 16384;   // below this the 256-row workgroups leave most compute units idle
 
 constexpr int NT_SMALL_ROWS = 2048;    // blocks of at most this many rows (by capacity) take the kernel above
@@ -583,6 +818,19 @@ constexpr int NT_DEEP_MIN_K = 768;            // ... a K loop of at least 24 ste
 
 static void launch_nt(const NtArgs &a, hipStream_t s)
 {
+    // many rows, bf16 output only, K small enough for the weights to stay in registers: the streaming kernel
+    if (a.max_rows >= NT_WIDE_MIN_ROWS && a.N == WIDE_N && a.K <= STREAM_KMAX && a.K % 8 == 0 && a.K0 % 8 == 0 && a.A1 != nullptr &&
+        a.Cb != nullptr && a.C0 == nullptr && a.ldcb == a.N && (int64_t)a.max_rows * a.lda < (1ll << 29)) {
+        static const bool ready = [] {
+            return hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_nt_stream_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)STREAM_LDS_BYTES) == hipSuccess;
+        }();
+        if (ready) {
+            const int64_t tiles = ceil_div(a.max_rows, STREAM_ROWS);
+            hipLaunchKernelGGL(gemm_nt_stream_kernel, dim3((unsigned)(tiles < 256 ? tiles : 256)), dim3(256), STREAM_LDS_BYTES, s, a);
+            return;
+        }
+    }
     // many rows against weights that fit one compute unit's LDS, bf16 output only: the weight-stationary kernel
     if (a.max_rows >= NT_WIDE_MIN_ROWS && a.N == WIDE_N && (a.K0 == a.K || a.K0 % WIDE_KH == 0) && a.A1 != nullptr && a.Cb != nullptr &&
         a.C0 == nullptr && a.ldcb == a.N && a.lda < (1 << 20)) {

@@ -78,10 +78,15 @@ def test_linear_fwd(torch_mod, M, F_in, F_out, relu):
     (100, 128, 256, True, 16500, 2),           # fewer rows than one tile holds, capacity still large
     (16640, 128, 256, False, 16700, 2),        # last tile moved back onto its neighbour
     (18000, 602, 256, False, None, 1),         # one operand, K = 608: five chunks, the last one a partial one
-    (16500, 32, 256, True, None, 1)])          # one operand, K = 32: a single partial chunk
+    (16500, 32, 256, True, None, 1),           # one operand, K = 32: a single partial chunk
+    (40, 128, 256, True, 16500, 2),            # fewer rows than the streaming kernel's 64-row tile
+    (19201, 64, 256, False, None, 2),          # K = 128: the streaming kernel with half the weight registers; a moved-back tile
+    (70003, 128, 256, True, None, 2),          # several tiles per workgroup of the persistent streaming kernel
+    (16500, 128, 256, True, None, 1)])         # one operand, K = 128: half of the streaming kernel's waves have no piece to load
 def test_linear_fwd_many_rows_bf16_output(torch_mod, M, F_in, F_out, relu, cap, n_op):
     """The input layer of the large workloads: tens of thousands of rows, N = 256 after padding, bf16 output only
-    (the weight-stationary kernel: 256 rows x all columns per workgroup, K in chunks of 128)."""
+    (K <= 256: the streaming kernel, weights in registers, 64-row tiles; larger K: the weight-stationary kernel, 256 rows
+    x all columns per workgroup, K in chunks of 128)."""
     torch = torch_mod
     from paper_2504_18082_amd import binding as B
     rng = np.random.default_rng(M + F_in)
