@@ -415,10 +415,10 @@ __global__ __launch_bounds__(256) void gemm_nt_small_kernel(NtArgs a, XentArgs x
 // one-operand layers: all of K from one array).  The tiled kernel
 // above reads every activation row four times (once per 64-column tile) and spends most of its time moving operands;
 // here one workgroup per compute unit takes 256 rows and ALL columns, so activations pass through a compute unit once:
-//   - K is taken in chunks of 128 columns.  A chunk is 256 rows x 256 bytes of activations and 256 x 256 bytes of
-//     weights: both are fetched with coalesced 16-byte loads (16 per thread each) and laid out in LDS with rows
-//     padded by 16 bytes, so that the MFMA fragments are conflict-free 16-byte LDS reads; a last chunk that reaches
-//     past K is staged with zeros there;
+//   - K is taken in chunks of 128 columns, each operand array's columns in chunks of their own.  A chunk is 256 rows x
+//     256 bytes of activations and 256 x 256 bytes of weights: both are fetched with coalesced 16-byte loads (16 per
+//     thread each) and laid out in LDS with rows padded by 16 bytes, so that the MFMA fragments are conflict-free
+//     16-byte LDS reads; an array's last chunk that reaches past its columns is staged with zeros there;
 //   - the next chunk's loads are issued inside the current chunk's K loop, four per step, and travel under its MFMAs
 //     (issued in one go they hold the wave, the only one on its SIMD, for as long as the memory pipeline takes them);
 //   - a wave owns 64 rows x 256 columns (256 accumulator registers, one wave per SIMD): per 16-wide K step 10 fragment
@@ -452,27 +452,32 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, lr = lane & 31;
     const int K = a.K, K0 = a.K0;
-    const int nchunk = (K + WIDE_KH - 1) / WIDE_KH;
+    // Column k of the product sits in the first operand array for k < K0 and in the second from there on.  Each array's
+    // columns are taken in chunks of 128 of their own (the first array's chunks, then the second's), so a chunk lies in
+    // one array whatever K0 is; the last chunk of an array whose width is no multiple of 128 is a partial one.
+    const int nchunk0 = (K0 + WIDE_KH - 1) / WIDE_KH;
+    const int nchunk = nchunk0 + (K - K0 + WIDE_KH - 1) / WIDE_KH;
+    // chunk c: its first column within its array, and the columns it has there (128, fewer in a partial chunk)
+    auto chunk_off = [&](int c) { return (c < nchunk0 ? c : c - nchunk0) * WIDE_KH; };
+    auto chunk_cols = [&](int c) { return min(WIDE_KH, (c < nchunk0 ? K0 : K - K0) - chunk_off(c)); };
 
-    // staging assignment: piece p = i * 256 + tid of a chunk = (row p / 16, 16-byte piece p % 16).  Column k of the
-    // product sits in the first operand array for k < K0 and in the second from there on; a chunk lies in one of the two
-    // (K0 is a multiple of 128, or there is one operand only).  An address is a base that is the same for the whole
-    // workgroup (chunk, 16-row group i) plus one per-thread offset that serves all 16 pieces: no address registers are
-    // held across the K loop.  Pieces past K (last chunk of a K that is no multiple of 128) are loaded from the chunk's
-    // first piece and staged as zeros.
+    // staging assignment: piece p = i * 256 + tid of a chunk = (row p / 16, 16-byte piece p % 16).  An address is a base
+    // that is the same for the whole workgroup (chunk, 16-row group i) plus one per-thread offset that serves all 16
+    // pieces: no address registers are held across the K loop.  Pieces past a partial chunk's columns are loaded from the
+    // chunk's first piece and staged as zeros.
     const int srow = tid >> 4, spiece = tid & 15;
     u32x4v wreg[16], areg[16];
     auto fetch = [&](int c, int i) {     // pieces i of the chunk's 16 activation and 16 weight pieces of this thread
-        const int kbase = c * WIDE_KH;
-        const int sp = kbase + spiece * 8 < K ? spiece * 8 : 0;
-        const uint16_t *Ai = (kbase < K0 ? a.A0 + kbase : a.A1 + (kbase - K0)) + (int64_t)(m0 + i * 16) * a.lda;
-        const uint16_t *Wi = a.B + kbase + (int64_t)(i * 16) * K;
+        const int koff = chunk_off(c);
+        const int sp = spiece * 8 < chunk_cols(c) ? spiece * 8 : 0;
+        const uint16_t *Ai = (c < nchunk0 ? a.A0 : a.A1) + koff + (int64_t)(m0 + i * 16) * a.lda;
+        const uint16_t *Wi = a.B + (c < nchunk0 ? 0 : K0) + koff + (int64_t)(i * 16) * K;
         areg[i] = *reinterpret_cast<const u32x4v *>(Ai + (uint32_t)(srow * (int)a.lda + sp));
         wreg[i] = *reinterpret_cast<const u32x4v *>(Wi + (uint32_t)(srow * K + sp));
     };
     auto stage = [&](int c) {
-        const bool full = (c + 1) * WIDE_KH <= K;              // (uniform)
-        const bool mine = c * WIDE_KH + spiece * 8 < K;
+        const bool full = chunk_cols(c) == WIDE_KH;            // (uniform)
+        const bool mine = spiece * 8 < chunk_cols(c);
         const u32x4v zero = {0u, 0u, 0u, 0u};
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
@@ -832,7 +837,7 @@ static void launch_nt(const NtArgs &a, hipStream_t s)
         }
     }
     // many rows against weights that fit one compute unit's LDS, bf16 output only: the weight-stationary kernel
-    if (a.max_rows >= NT_WIDE_MIN_ROWS && a.N == WIDE_N && (a.K0 == a.K || a.K0 % WIDE_KH == 0) && a.A1 != nullptr && a.Cb != nullptr &&
+    if (a.max_rows >= NT_WIDE_MIN_ROWS && a.N == WIDE_N && a.K0 % 8 == 0 && a.K % 8 == 0 && a.A1 != nullptr && a.Cb != nullptr &&
         a.C0 == nullptr && a.ldcb == a.N && a.lda < (1 << 20)) {
         static const bool ready = [] {
             return hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_nt_wide_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
