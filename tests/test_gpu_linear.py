@@ -247,7 +247,8 @@ def test_softmax_xent(torch_mod, n, Cn):
 
 
 @pytest.mark.parametrize("M,F_in,Cn,cap_extra", [(1000, 256, 40, 24), (1024, 100, 47, 0), (33, 64, 64, 7), (1, 32, 3, 0),
-                                                 (300, 64, 172, 5), (2500, 64, 10, 12)])     # the last two: separate kernels inside
+                                                 (300, 64, 172, 5), (2500, 64, 10, 12),      # these and the next: separate kernels inside
+                                                 (9000, 32, 172, 100)])
 def test_linear_fwd_with_loss(torch_mod, M, F_in, Cn, cap_extra):
     """cr_sage_linear_fwd_xent: logits bit-identical to cr_sage_linear_fwd, loss and gradient against the oracle's
     softmax cross-entropy of those logits; two calls in a row on the same scratch, the second on fewer rows."""
@@ -264,7 +265,7 @@ def test_linear_fwd_with_loss(torch_mod, M, F_in, Cn, cap_extra):
     ld_in, Np = layer.F_pad, layer.N_pad
     d_hs = to_bf16_dev(torch, np.pad(hs, ((0, cap_extra), (0, 0))), ld_in)
     d_ag = to_bf16_dev(torch, np.pad(ag, ((0, cap_extra), (0, 0))), ld_in)
-    n_nodes = 6000
+    n_nodes = 12000
     labels_all = rng.integers(0, Cn, size=n_nodes).astype(np.int32)
     roots = rng.choice(n_nodes, size=cap, replace=False).astype(np.int32)
     up = lambda a: torch.from_numpy(a).cuda()
