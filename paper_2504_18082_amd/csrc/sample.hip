@@ -1608,8 +1608,19 @@ __global__ __launch_bounds__(256) void compact_ids_kernel(DedupArgs a)
     CR_ROW_LANE();
     if (blockIdx.x == 0 && threadIdx.x == 0) hdr[CR_HDR_N_SRC] = -1;
     if (in_row && j == 0) a.src_ids[(int64_t)g * a.src_stride + row] = a.dst_ids[(int64_t)g * a.dst_stride + row];
-    if (!active || a.sel == nullptr) return;       // (a.sel == NULL: the selection wrote the ids in place)
+    if (!active) return;
     a.gather_ids[(int64_t)g * a.indices_stride + rstart + j] = a.sel[(int64_t)g * a.sel_stride + ell];
+}
+
+// the same when the selection has already written the ids in place: only the destination nodes are left to copy, one
+// thread per row
+__global__ __launch_bounds__(256) void frontier_head_kernel(DedupArgs a)
+{
+    const int g = blockIdx.y;
+    const int n_dst = group_n_dst(a.prev_hdr, g, a.n_roots_total, a.batch_size);
+    const int row = (int)(blockIdx.x * 256 + threadIdx.x);
+    if (blockIdx.x == 0 && threadIdx.x == 0) a.hdr[(int64_t)g * CR_HDR_WORDS + CR_HDR_N_SRC] = -1;
+    if (row < n_dst) a.src_ids[(int64_t)g * a.src_stride + row] = a.dst_ids[(int64_t)g * a.dst_stride + row];
 }
 
 // direct-address table: put the entries this hop touched back to "absent"
@@ -1967,8 +1978,8 @@ extern "C" cr_status cr_sample_blocks(const cr_graph *graph, const cr_sample_cfg
         if (l == 0 && (cfg->flags & CR_SAMPLE_INPUT_GLOBAL_IDS)) {
             da.tcount = nullptr; da.tfill = nullptr; da.t_stride = 0; da.t_indptr = nullptr; da.t_indptr_stride = 0;
             da.t_indices = nullptr; da.t_tmp = nullptr; da.t_pos = nullptr; da.tt_stride = 0;
-            if (direct_out) da.sel = nullptr;      // nothing left to copy but the destination nodes
-            hipLaunchKernelGGL(compact_ids_kernel, grid, blk, 0, s, da);
+            if (direct_out) hipLaunchKernelGGL(frontier_head_kernel, dim3((unsigned)ceil_div(cap_dst, 256), n_batches), blk, 0, s, da);
+            else hipLaunchKernelGGL(compact_ids_kernel, grid, blk, 0, s, da);
             continue;
         }
 
