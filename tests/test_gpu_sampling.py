@@ -170,7 +170,7 @@ def test_edge_class_bits(torch_mod, tiny_workload, arxiv_workload):
         compare(layers, nb, w.graph, roots, w.cfg.fanouts, p, strict, 0, 1, 3, 1024, f"edge bits p={p}")
 
 
-def many_hubs_graph(seed=0, n_hubs=48, n_leaves=6000, n_comm=4):
+def many_hubs_graph(seed=0, n_hubs=48, n_leaves=6000, n_comm=4, degrees=(65, 66, 100, 128, 129, 255, 257, 700, 3000)):
     """Hubs of degree 65..3000 whose neighbours are 0 %, a few, half, most or all in the hub's own community
     (symmetrised); exercises every long-row path of the selection kernels."""
     rng = np.random.default_rng(seed)
@@ -180,7 +180,7 @@ def many_hubs_graph(seed=0, n_hubs=48, n_leaves=6000, n_comm=4):
     others_of = [n_hubs + np.nonzero(comm[n_hubs:] != c)[0] for c in range(n_comm)]
     rows, cols = [], []
     for h in range(n_hubs):
-        deg = int(rng.choice([65, 66, 100, 128, 129, 255, 257, 700, 3000]))
+        deg = int(rng.choice(list(degrees)))
         frac = float(rng.choice([0.0, 0.02, 0.1, 0.5, 0.9, 1.0]))
         n_in = min(int(round(deg * frac)), len(leaves_of[comm[h]]))
         n_out = min(deg - n_in, len(others_of[comm[h]]))
@@ -207,6 +207,21 @@ def test_long_rows_all_paths(torch_mod, edge_classes):
             compare(layers, nb, graph, roots, fan, p, False, 5, 1, 0, 16, f"long rows p={p} {fan}")
     layers, nb = run_gpu(torch_mod, dg, roots, [15], 1.0, True, 5, 1, 0, 16)
     compare(layers, nb, graph, roots, [15], 1.0, True, 5, 1, 0, 16, "long rows strict")
+
+
+@pytest.mark.parametrize("degrees", [(17, 24, 40, 64), (65, 100, 128, 200, 255, 256), (5, 17, 40, 100, 200, 256)])
+def test_medium_rows_both_rankings(torch_mod, degrees):
+    """Rows of 5..256 neighbours, 160 of them side by side (ten waves of sixteen rows): passes of many short rows, where
+    every lane ranks its own four slots, passes of one or two long rows with few candidates, where a lane ranks one
+    candidate, and mixtures of both."""
+    graph, n_hubs = many_hubs_graph(seed=3, n_hubs=160, n_leaves=4000, n_comm=4, degrees=degrees)
+    dg = DeviceGraph(torch_mod, graph, 4, edge_classes=True)
+    roots = np.arange(n_hubs, dtype=np.int32)
+    for p in (0.5, 0.9, 1.0):
+        for fan in ([5], [15], [30]):
+            print(f"case medium rows degrees={degrees} p={p} fanout={fan}", flush=True)
+            layers, nb = run_gpu(torch_mod, dg, roots, fan, p, False, 11, 2, 0, 160, input_global=(fan[0] == 15))
+            compare(layers, nb, graph, roots, fan, p, False, 11, 2, 0, 160, f"medium rows p={p} {fan}", input_global=(fan[0] == 15))
 
 
 def test_clock_approximation_bound(torch_mod):
