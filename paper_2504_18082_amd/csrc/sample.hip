@@ -691,16 +691,18 @@ __device__ __forceinline__ bool keys_apart(float hi, float m_hi, float lo, float
     return lo - hi > slack;
 }
 
-constexpr int QUAD_ROWS = 16;            // destination rows per wave
+constexpr int QUAD_ROWS = 32;            // destination rows per wave
 constexpr int QUAD_MAX_DEG = 4 * WAVE;   // longest row a pass holds
 
 struct alignas(16) QuadRow {
-    int32_t v, deg, startq, nq;          // node, degree, first quad in the wave's quad sequence, number of quads
+    int32_t v, deg, startq, nq_row;      // node, degree, first quad in the wave's quad sequence, number of quads | which of
+                                         // the wave's destination rows it is << 8
     int64_t base;                        // first adjacency entry
     int32_t *out;                        // where the row's chosen ids go
 };
 
-// One pass; returns the rows (bit r = row r of the wave) that have to be redone exactly.  rowmask: rows to process.
+// One pass; returns the rows that have to be redone exactly (bit r = the r-th row of the wave's quad sequence: the rows
+// are laid out in the order the packing placed them, not in the order of the block).  rowmask: rows to process.
 template <int MODE, bool EXACT>
 __device__ __forceinline__ uint32_t quad_pass(const SelectArgs &a, int g, int row0, int p, uint32_t rowmask, const QuadRow *rows,
                                               const int *startq, uint32_t *klist, uint32_t *clist, uint32_t *rowinfo,
@@ -710,15 +712,18 @@ __device__ __forceinline__ uint32_t quad_pass(const SelectArgs &a, int g, int ro
     const uint32_t batch = a.first_batch + (uint32_t)g;
     const int gq = p * WAVE + lane;
     // the row of this lane's quad: the last one that starts at or before it (startq is non-decreasing, startq[0] = 0)
-    int r = startq[8] <= gq ? 8 : 0;
+    static_assert(QUAD_ROWS == 32, "the bisection below takes five steps");
+    int r = startq[16] <= gq ? 16 : 0;
+    r += startq[r + 8] <= gq ? 8 : 0;
     r += startq[r + 4] <= gq ? 4 : 0;
     r += startq[r + 2] <= gq ? 2 : 0;
     r += startq[r + 1] <= gq ? 1 : 0;
     const QuadRow R = rows[r];
     const int qi = gq - R.startq;
-    const bool active = qi < R.nq && ((rowmask >> r) & 1u);
+    const int nq = R.nq_row & 0xFF;
+    const bool active = qi < nq && ((rowmask >> r) & 1u);
     if (__ballot(active) == 0) return 0u;
-    const int first = R.startq - p * WAVE, last = first + R.nq - 1;       // the row's lanes in this pass
+    const int first = R.startq - p * WAVE, last = first + nq - 1;         // the row's lanes in this pass
     const int jb = 4 * qi;
     const int left = active ? R.deg - jb : 0;
     const uint32_t vmask = left >= 4 ? 0xFu : ((1u << left) - 1u);        // the quad's slots that exist
@@ -912,7 +917,7 @@ __device__ __forceinline__ uint32_t quad_pass(const SelectArgs &a, int g, int ro
     if constexpr (MODE == 2 && !EXACT) {
         // largest kept key and smallest key left out, per row and class (LDS atomics on the bit patterns):
         // rowstat[4 r + ..] = max kept intra, max kept inter, min left-out intra, min left-out inter
-        rowstat[lane] = (lane & 2) ? 0x7F800000u : 0u;
+        rowstat[lane] = rowstat[lane + WAVE] = (lane & 2) ? 0x7F800000u : 0u;
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         if (ranked) {
 #pragma unroll
@@ -942,7 +947,7 @@ __device__ __forceinline__ uint32_t quad_pass(const SelectArgs &a, int g, int ro
 #pragma unroll
         for (int i = 0; i < 4; ++i)
             if ((emit >> i) & 1u) R.out[k++] = a.g_indices[R.base + jb + i];
-        if (qi == 0) set_row_count(a, g, row0 + r, total);
+        if (qi == 0) set_row_count(a, g, row0 + (R.nq_row >> 8), total);
     }
     uint64_t bad = __ballot(active && qi == 0 && !ok);
     uint32_t redo = 0u;
@@ -1115,28 +1120,42 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
         if (mdeg == 0) set_row_count(a, g, row0 + lane, 0);
     }
     const int mq = (mdeg > 0 && mdeg <= QUAD_MAX_DEG) ? (mdeg + 3) >> 2 : 0;
-    // greedy packing of the rows' quads into passes of 64
-    int off = 0, my_start = 0;
-#pragma unroll
-    for (int i = 0; i < QUAD_ROWS; ++i) {
-        const int q = (int)rl32((uint32_t)mq, i);
-        if ((off & (WAVE - 1)) + q > WAVE) off = (off + WAVE - 1) & ~(WAVE - 1);
-        if (lane == i) my_start = off;
-        off += q;
+    // Packing of the rows' quads into passes of 64 (a row never straddles two passes): a pass takes, again and again, the
+    // first row not yet placed that still fits (first fit over the rows; filling the passes with the rows in their own
+    // order leaves them three quarters full on the degree mixes of sampled frontiers, this gets them to ~85 %).  The rows
+    // are stored in the order they were placed, so that their first quads ascend and a lane finds its row by bisection;
+    // rows without quads (empty, or longer than a pass) come last with a start no lane reaches.
+    uint32_t waiting = (uint32_t)__ballot(mq > 0);       // (lanes from QUAD_ROWS on hold no row: mq = 0)
+    int my_start = 0x3FFFFFFF, my_place = 0, placed = 0, n_pass = 0;
+    while (waiting) {
+        int room = WAVE;
+        for (;;) {
+            const uint32_t fits = (uint32_t)__ballot(mq <= room) & waiting;
+            if (!fits) break;
+            const int i = __builtin_ctz(fits);
+            if (lane == i) { my_start = n_pass * WAVE + (WAVE - room); my_place = placed; }
+            room -= (int)rl32((uint32_t)mq, i);
+            waiting &= ~(1u << i);
+            ++placed;
+        }
+        ++n_pass;
     }
-    const int n_pass = (off + WAVE - 1) / WAVE;
+    {
+        const uint32_t rest = (uint32_t)__ballot(lane < QUAD_ROWS && mq == 0);
+        if (lane < QUAD_ROWS && mq == 0) my_place = placed + (int)__popc(rest & ((1u << lane) - 1u));
+    }
     if (lane < QUAD_ROWS) {
         QuadRow R;
-        R.v = mv; R.deg = mdeg; R.startq = my_start; R.nq = mq; R.base = mbase; R.out = mout;
-        rows_s[wv][lane] = R;
-        startq_s[wv][lane] = my_start;
+        R.v = mv; R.deg = mdeg; R.startq = my_start; R.nq_row = mq | (lane << 8); R.base = mbase; R.out = mout;
+        rows_s[wv][my_place] = R;
+        startq_s[wv][my_place] = my_start;
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
 
-    uint32_t exact_rows = a.exact_select ? 0xFFFFu : 0u;
+    uint32_t exact_rows = a.exact_select ? ~0u : 0u;
     if (!a.exact_select)
         for (int p = 0; p < n_pass; ++p)
-            exact_rows |= quad_pass<MODE, false>(a, g, row0, p, 0xFFFFu, rows_s[wv], startq_s[wv], klist_s[wv], cslot_s[wv], rowinfo_s[wv], k64, rowstat, lane);
+            exact_rows |= quad_pass<MODE, false>(a, g, row0, p, ~0u, rows_s[wv], startq_s[wv], klist_s[wv], cslot_s[wv], rowinfo_s[wv], k64, rowstat, lane);
     if (exact_rows)
         for (int p = 0; p < n_pass; ++p)
             quad_pass<MODE, true>(a, g, row0, p, exact_rows, rows_s[wv], startq_s[wv], klist_s[wv], cslot_s[wv], rowinfo_s[wv], k64, rowstat, lane);
