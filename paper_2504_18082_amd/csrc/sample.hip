@@ -1261,7 +1261,20 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_kernel(ScanArgs a)
         before = a.tile_before[blockIdx.x];
     } else if (first > 0) {
         int part = 0;
-        for (int i0 = (int)threadIdx.x; i0 < first; i0 += SCAN_TILE) {      // first is a multiple of the tile size
+        int i0 = (int)threadIdx.x;                               // (first is a multiple of the tile size)
+        // four tiles' loads in flight at a time: the loop is a chain of round trips to the L2, not of additions
+        for (; i0 + 3 * SCAN_TILE < first; i0 += 4 * SCAN_TILE) {
+            int x[4][SCAN_ITEMS];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int k = 0; k < SCAN_ITEMS; ++k) x[u][k] = in[i0 + u * SCAN_TILE + k * SCAN_THREADS];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int k = 0; k < SCAN_ITEMS; ++k) part += x[u][k];
+        }
+        for (; i0 < first; i0 += SCAN_TILE) {
             int x[SCAN_ITEMS];
 #pragma unroll
             for (int k = 0; k < SCAN_ITEMS; ++k) x[k] = in[i0 + k * SCAN_THREADS];
@@ -1271,10 +1284,21 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_kernel(ScanArgs a)
         block_exclusive_scan<SCAN_THREADS / WAVE>(part, lds, before);
         __syncthreads();                                     // lds is reused below
     }
-    const int start = first + (int)threadIdx.x * SCAN_ITEMS;
+    // A thread scans sixteen consecutive elements, but the tile travels between memory and the threads through LDS, so
+    // that a wave's loads and stores touch consecutive words (a thread reading its own sixteen words straight from memory
+    // makes every load instruction touch 64 different cache lines).  Sixteen words are followed by one of padding: the
+    // threads' stretches start 17 words apart, on different banks.
+    __shared__ int tile[SCAN_TILE + SCAN_TILE / SCAN_ITEMS];
+#pragma unroll
+    for (int k = 0; k < SCAN_ITEMS; ++k) {
+        const int j = k * SCAN_THREADS + (int)threadIdx.x;
+        tile[j + j / SCAN_ITEMS] = first + j < n ? in[first + j] : 0;
+    }
+    __syncthreads();
+    int *mine = tile + (int)threadIdx.x * (SCAN_ITEMS + 1);
     int x[SCAN_ITEMS];
 #pragma unroll
-    for (int i = 0; i < SCAN_ITEMS; ++i) x[i] = start + i < n ? in[start + i] : 0;
+    for (int i = 0; i < SCAN_ITEMS; ++i) x[i] = mine[i];
     int sum = 0;
 #pragma unroll
     for (int i = 0; i < SCAN_ITEMS; ++i) sum += x[i];
@@ -1282,11 +1306,18 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_kernel(ScanArgs a)
     int run = before + block_exclusive_scan<SCAN_THREADS / WAVE>(sum, lds, tile_total);
 #pragma unroll
     for (int i = 0; i < SCAN_ITEMS; ++i) {
-        if (start + i < n) {
-            out[start + i] = run;
-            if (out_copy) out_copy[start + i] = run;
-        }
+        mine[i] = run;
         run += x[i];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < SCAN_ITEMS; ++k) {
+        const int j = k * SCAN_THREADS + (int)threadIdx.x;
+        if (first + j < n) {
+            const int v = tile[j + j / SCAN_ITEMS];
+            out[first + j] = v;
+            if (out_copy) out_copy[first + j] = v;
+        }
     }
     if (threadIdx.x == 0 && n <= first + SCAN_TILE) {        // the last tile
         const int total = before + tile_total;
