@@ -1410,6 +1410,8 @@ struct OrderArgs {
     int64_t order_stride;
     int32_t grouped;          // 1: one order over all batches of the group, entries batch * cap_dst + row, count at the end
     int32_t cap_dst;
+    uint16_t *bucket;         // [n_batches][bucket_stride]: a row's bucket, kept from the counting pass for the scatter pass
+    int64_t bucket_stride;
 };
 
 __device__ __forceinline__ int order_bucket(const OrderArgs &a, int node)
@@ -1434,17 +1436,35 @@ __global__ __launch_bounds__(256) void order_pass_kernel(OrderArgs a)
         a.order[(int64_t)gridDim.y * a.cap_dst] = a.offsets[(int64_t)a.n_buckets * cols];      // number of entries
     __syncthreads();
     constexpr int PER = ORDER_TILE / 256;
-    int node[PER];
+    // the counting pass looks the rows' communities up (one scattered read per row) and leaves their buckets behind; the
+    // scatter pass reads those in row order
+    uint16_t *kept = a.bucket + (int64_t)g * a.bucket_stride;
+    int bkt[PER];
+    if (SCATTER) {
 #pragma unroll
-    for (int i = 0; i < PER; ++i) {
-        const int r = tile * ORDER_TILE + i * 256 + (int)threadIdx.x;
-        node[i] = a.dst_ids[(int64_t)g * a.dst_stride + min(r, max(n_dst - 1, 0))];
+        for (int i = 0; i < PER; ++i) {
+            const int r = tile * ORDER_TILE + i * 256 + (int)threadIdx.x;
+            bkt[i] = kept[min(r, max(n_dst - 1, 0))];
+        }
+    } else {
+        int node[PER];
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int r = tile * ORDER_TILE + i * 256 + (int)threadIdx.x;
+            node[i] = a.dst_ids[(int64_t)g * a.dst_stride + min(r, max(n_dst - 1, 0))];
+        }
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int r = tile * ORDER_TILE + i * 256 + (int)threadIdx.x;
+            bkt[i] = order_bucket(a, node[i]);
+            if (r < n_dst) kept[r] = (uint16_t)bkt[i];
+        }
     }
 #pragma unroll
     for (int i = 0; i < PER; ++i) {
         const int r = tile * ORDER_TILE + i * 256 + (int)threadIdx.x;
         if (r < n_dst) {
-            const int pos = atomicAdd(&lds[order_bucket(a, node[i])], 1);
+            const int pos = atomicAdd(&lds[bkt[i]], 1);
             if (SCATTER) {
                 if (a.grouped) a.order[pos] = g * a.cap_dst + r;
                 else a.order[(int64_t)g * a.order_stride + pos] = r;
@@ -1750,6 +1770,7 @@ struct SamplePlan {
     int64_t table_stride = 0; // per batch, in 8-byte units
     // workspace slices
     int32_t *sel, *cnt, *newoff, *tcount, *tfill, *t_tmp, *t_pos, *order_hist, *order_cursor, *order_tiles;
+    uint16_t *order_bucket;
     unsigned long long *newmask, *table;
     size_t bytes;
 };
@@ -1811,8 +1832,10 @@ static cr_status make_plan(const cr_sample_cfg *cfg, int64_t n_nodes, int32_t ba
         p.order_hist = c.take<int32_t>(G * cells);
         p.order_cursor = c.take<int32_t>(G * cells);
         p.order_tiles = c.take<int32_t>(16384);
+        p.order_bucket = c.take<uint16_t>(G * p.max_dst);
     } else {
         p.order_hist = p.order_cursor = p.order_tiles = nullptr;
+        p.order_bucket = nullptr;
     }
     p.bytes = c.bytes();
     return CR_OK;
@@ -1995,6 +2018,7 @@ extern "C" cr_status cr_sample_blocks(const cr_graph *graph, const cr_sample_cfg
             oa.n_tiles = (int32_t)ceil_div(cap_dst, ORDER_TILE);
             oa.cells = p.order_hist; oa.offsets = p.order_cursor; oa.order = order; oa.order_stride = b.cap_dst;
             oa.grouped = grouped; oa.cap_dst = b.cap_dst;
+            oa.bucket = p.order_bucket; oa.bucket_stride = p.max_dst;
             const int n_cells = oa.n_buckets * oa.n_tiles * (grouped ? n_batches : 1);
             const dim3 og((unsigned)oa.n_tiles, n_batches);
             hipLaunchKernelGGL(order_pass_kernel<false>, og, blk, 0, s, oa);
