@@ -1005,7 +1005,10 @@ __device__ __forceinline__ bool select_big_row_weighted_f32(const SelectArgs &a,
 
     const int64_t w_max = (a.n_entries - 1) >> 5;
     int n = 0;
-    for (int j0 = 0; j0 < deg; j0 += 4 * WAVE) {
+    // 256 slots from j0 on; a slot is a candidate iff its word is at or above its class's threshold (in the row's last
+    // stretch: and it is not beyond the row's end).  false: more candidates than the list holds.
+    auto stretch = [&](int j0, auto is_last) -> bool {
+        constexpr bool LAST = decltype(is_last)::value;
         const int jb = j0 + 4 * lane;
         const u32x4 w = philox4x32_10((uint32_t)jb >> 2, (uint32_t)v, batch, a.ctr3, a.seed_lo, a.seed_hi);
         const uint32_t wr[4] = {w.x, w.y, w.z, w.w};
@@ -1015,16 +1018,17 @@ __device__ __forceinline__ bool select_big_row_weighted_f32(const SelectArgs &a,
         const uint32_t nib = (uint32_t)(win >> (e & 31)) & 0xFu;
         bool c[4];
         uint64_t b[4];
-        int before = n, total = 0;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) c[i] = jb + i < deg && wr[i] >= (((nib >> i) & 1u) ? t_in : t_out);
-        if (__ballot(c[0] || c[1] || c[2] || c[3]) == 0) continue;      // (most iterations of a long row)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
+            c[i] = wr[i] >= (((nib >> i) & 1u) ? t_in : t_out);
+            if (LAST) c[i] = c[i] && jb + i < deg;
             b[i] = __ballot(c[i]);
-            before += __popcll(b[i] & lt_mask);
-            total += __popcll(b[i]);
         }
+        if ((b[0] | b[1] | b[2] | b[3]) == 0) return true;             // (most stretches of a very long row)
+        int before = n;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) before = lanes_below(b[i], before);
+        const int total = __popcll(b[0]) + __popcll(b[1]) + __popcll(b[2]) + __popcll(b[3]);
         if (n + total > CAND_CAP) return false;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -1035,7 +1039,12 @@ __device__ __forceinline__ bool select_big_row_weighted_f32(const SelectArgs &a,
             before += c[i] ? 1 : 0;
         }
         n += total;
-    }
+        return true;
+    };
+    int j0 = 0;
+    for (; j0 + 4 * WAVE <= deg; j0 += 4 * WAVE)
+        if (!stretch(j0, std::false_type{})) return false;
+    if (j0 < deg && !stretch(j0, std::true_type{})) return false;
     if (n < k) return false;
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
 
