@@ -1096,11 +1096,11 @@ __device__ __forceinline__ bool select_big_row_weighted_f32(const SelectArgs &a,
     return exact;
 }
 
-// (at least six waves per SIMD: the weighted instantiation takes 85 registers when left alone, which leaves five waves and
-// measures 5 % slower on a sampled group than 80 registers with two words spilled; its LDS allows six workgroups per
-// compute unit anyway)
+// (occupancy targets: the weighted instantiation takes 85 registers when left alone, which leaves five waves per SIMD and
+// measures 5 % slower on a sampled group than 80 registers -- six waves, as many workgroups as its LDS allows -- with two
+// words spilled; the other two fit 64 registers, eight waves: 3 % on a group at p = 1)
 template <int MODE>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(6, 8))) void select_quad_kernel(SelectArgs a)
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 2 ? 6 : 8, 8))) void select_quad_kernel(SelectArgs a)
 {
     __shared__ QuadRow rows_s[4][QUAD_ROWS];
     __shared__ int startq_s[4][QUAD_ROWS];
