@@ -2,6 +2,8 @@
 mini-batches of 1024 roots, three layers, input-side block in global ids, layer-0 gather once per group over the
 group-wide community order):
 
+  reddit-like   : 233 K nodes, ~114 M adjacency entries (mean degree 490: most destination rows take the long-row
+                  paths of the selection), 2408-byte float rows gathered in five 512-byte column panels, 41 classes
   products-like : 2.45 M nodes, ~124 M adjacency entries, 400-byte float rows (not 128-byte aligned), 5000 communities
   papers-like   : the FULL shape, 111 M nodes, ~3.2 G adjacency entries (offsets beyond 2^31), 256-byte bf16 rows,
                   100,000 communities, 172 classes; the graph is too large for the direct-address de-duplication
@@ -53,7 +55,7 @@ class Large:
         return rows.view(np.uint16) if rows.dtype == np.int16 else rows
 
 
-@pytest.fixture(scope="module", params=["products", "papers"])
+@pytest.fixture(scope="module", params=["reddit", "products", "papers"])
 def large(request):
     import torch
     lw = Large(request.param)
