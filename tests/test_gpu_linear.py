@@ -87,7 +87,8 @@ def test_linear_fwd(torch_mod, M, F_in, F_out, relu):
     (16400, 96, 256, True, None, 2),           # K = 192 with the operands meeting inside a wave's sixteen pieces (per-thread addresses)
     (16400, 256, 256, False, None, 1),         # one operand, K = 256: every wave loads from the same array
     (5000, 602, 256, True, None, 2),           # a few thousand rows against K = 1216: the tiled kernel with the deep prefetch
-    (4200, 800, 256, False, None, 1)])         # the same, one operand of 800 columns
+    (4200, 800, 256, False, None, 1),          # the same, one operand of 800 columns
+    (0, 128, 256, True, 16500, 2)])            # no live row at all: nothing may be written
 def test_linear_fwd_many_rows_bf16_output(torch_mod, M, F_in, F_out, relu, cap, n_op):
     """The input layer of the large workloads: tens of thousands of rows, N = 256 after padding, bf16 output only
     (K <= 256: the streaming kernel, weights in registers, 64-row tiles; larger K: the weight-stationary kernel, 256 rows
